@@ -1,0 +1,375 @@
+/*
+ * kvq_oracle.c -- plain, slow, single-purpose CPU oracle for the mixed-precision KV cache
+ * ("Quantize What Counts: More for Keys, Less for Values", arXiv 2502.15075).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It exists to check the GPU library; nothing on the product
+ * path may call it.  It shares no code, header, table or helper with the GPU sources.
+ *
+ * What it computes, and which passage each part follows:
+ *
+ *   - the b-bit uniform scalar quantizer "scale, round, clip, reconstruct" of App. B
+ *     "Preliminaries" (scale factor, Q = round(A/alpha) clipped to the code range,
+ *     A^ = alpha Q), applied per group of G consecutive head_dim elements of one token row
+ *     (token-wise grouping, Sec. 4 "Downstream Task Accuracy"; group sizes Sec. 4
+ *     "Integration with Rotation-Based Methods"), in its asymmetric min-max form with
+ *     2^b - 1 steps over the group range (the reading that reproduces the 3-bit/4-bit error
+ *     ratio of Table 1), codes unsigned 0 .. 2^b - 1, scale and zero stored as binary16;
+ *   - independent bit widths b_K and b_V for keys and values (Sec. 1, Theorem 2);
+ *   - the reconstruction A^ = code * scale + zero (App. B "Dequantization");
+ *   - decode attention of one query row over the reconstructed cache,
+ *     A = softmax(q K^T * softmax_scale), out = A V  (App. A notation table and the
+ *     "attention outputs" equation), summed in binary64;
+ *   - the reconstruction MSE of App. B "Frobenius Norm (MSE) Perspective".
+ *
+ * Arithmetic of the quantizer is IEEE binary32, round-to-nearest-even, one rounding per
+ * written operation (build with -ffp-contract=off, no fast-math).  The decisions that
+ * produce integers (codes) are therefore taken in binary32, the precision the GPU kernel
+ * uses; everything that is not an integer decision (attention) is binary64.
+ *
+ * Storage format (the paper is silent on layout; this is the library's own format, stated
+ * here in full because bytes are compared one by one):
+ *
+ *   capacity   T_cap = max_seq rounded up to a multiple of 64 tokens.
+ *   k_codes    [B][H][T_cap][D*b_K/8] bytes; element d of a token row occupies bits
+ *              [d*b_K, (d+1)*b_K) of the row read as a little-endian bit string.
+ *   *_meta     [B][H][T_cap/16][D/G][16] entries of 4 bytes: little-endian uint16 scale
+ *              then little-endian uint16 zero (both binary16 bit patterns); entry
+ *              (t/16, g, t%16) belongs to token t, group g.
+ *   v_codes    [B][H][T_cap/64][1024*b_V] bytes: blocks of 64 tokens.  Inside a block the
+ *              code of (token t, channel d) lives in a little-endian 32-bit word found as
+ *                tt = t%64; o = tt/32; u = tt%32; x4 = u/16; j = (u%16)/4; r = u%4;
+ *                i = 4*x4 + r; x = i%2; v = i/2; pv = 4*o + v; P = 16/b_V;
+ *                n = pv/P; p = pv%P; dt = d/16; e = dt*(b_V/2) + n;
+ *                word byte offset = (e/4)*(8*D) + (16*j + d%16)*16 + 4*(e%4);
+ *                bit offset inside the word = 16*x + b_V*p.
+ *              (For D = 128 the stride 8*D is 1024 bytes: one 16-byte piece per wavefront
+ *              lane.  The order is the one in which a 16x16x32 matrix instruction wants a
+ *              "tokens x channels" operand, so a decode kernel needs no transpose.)
+ *   bits == 16 the planes hold the 16-bit input patterns unchanged in the same positions
+ *              (b = 16 in the formulas above); the meta planes are unused.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { REF_F16 = 0, REF_BF16 = 1, REF_F32 = 2 };
+
+typedef struct {
+  int32_t batch, kv_heads, max_seq, head_dim;
+  int32_t bits_k, bits_v;   /* 2, 4, 8, or 16 = keep the 16-bit input unquantized */
+  int32_t group_k, group_v; /* G: consecutive head_dim elements sharing one scale/zero */
+  int32_t raw_dtype;        /* REF_F16 or REF_BF16: meaning of the planes when bits == 16 */
+} ref_layout;
+
+/* ------------------------------------------------------------------ number formats */
+
+/* binary16 bit pattern -> binary32 value (exact). */
+float ref_f16_to_f32(uint16_t h) {
+  int sign = h >> 15, e = (h >> 10) & 31, m = h & 1023;
+  float v;
+  if (e == 0) v = ldexpf((float)m, -24);                 /* zero and subnormals */
+  else if (e == 31) v = m ? NAN : INFINITY;
+  else v = ldexpf((float)(1024 + m), e - 25);
+  return sign ? -v : v;
+}
+
+/* binary32 value -> nearest binary16 bit pattern, ties to even, subnormals kept,
+ * overflow to infinity.  Works on the real number, not on bit tricks: find the spacing of
+ * binary16 numbers around |f| and round the quotient with rint (ties-to-even). */
+uint16_t ref_f32_to_f16(float f) {
+  uint16_t sign = signbit(f) ? 0x8000u : 0u;
+  if (isnan(f)) return (uint16_t)(sign | 0x7E00u);
+  double a = fabs((double)f);
+  if (isinf(f) || a >= 65520.0) return (uint16_t)(sign | 0x7C00u); /* 65520 = halfway to 2^16 */
+  if (a == 0.0) return sign;
+  int ex;
+  (void)frexp(a, &ex);            /* a = frac * 2^ex, frac in [0.5,1)  =>  2^(ex-1) <= a */
+  int e = ex - 1;                 /* unbiased exponent of a */
+  if (e < -14) e = -14;           /* subnormal range shares the spacing of 2^-14 */
+  double ulp = ldexp(1.0, e - 10);
+  double q = rint(a / ulp);       /* exact quotient (power-of-two divisor), RNE */
+  /* q is in [0, 2048]; 2048 means the rounding carried into the next binade */
+  uint32_t bits;
+  if (e == -14 && q < 1024.0) bits = (uint32_t)q;                       /* subnormal */
+  else {
+    if (q >= 2048.0) { q = 1024.0; e += 1; }
+    bits = ((uint32_t)(e + 15) << 10) | ((uint32_t)q - 1024u);
+  }
+  return (uint16_t)(sign | bits);
+}
+
+float ref_bf16_to_f32(uint16_t h) {
+  uint32_t u = (uint32_t)h << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+static float load_elem(const void* base, int dtype, int64_t idx) {
+  if (dtype == REF_F16) return ref_f16_to_f32(((const uint16_t*)base)[idx]);
+  if (dtype == REF_BF16) return ref_bf16_to_f32(((const uint16_t*)base)[idx]);
+  return ((const float*)base)[idx];
+}
+
+/* ------------------------------------------------------------------ sizes */
+
+static int64_t cap_tokens(const ref_layout* L) { return ((int64_t)L->max_seq + 63) / 64 * 64; }
+
+/* bytes of k_codes, k_meta, v_codes, v_meta */
+int ref_plane_bytes(const ref_layout* L, uint64_t out[4]) {
+  int64_t rows = (int64_t)L->batch * L->kv_heads * cap_tokens(L);
+  int D = L->head_dim;
+  out[0] = (uint64_t)(rows * (D * L->bits_k / 8));
+  out[1] = L->bits_k == 16 ? 0 : (uint64_t)(rows * (D / L->group_k) * 4);
+  out[2] = (uint64_t)(rows * (D * L->bits_v / 8));
+  out[3] = L->bits_v == 16 ? 0 : (uint64_t)(rows * (D / L->group_v) * 4);
+  return 0;
+}
+
+/* ------------------------------------------------------------------ where things live */
+
+/* byte offset of meta entry (token t, group g) inside one (b,h) stream of a meta plane */
+static int64_t meta_offset(int64_t t, int g, int ngroups) {
+  return (((t / 16) * ngroups + g) * 16 + (t % 16)) * 4;
+}
+
+/* K codes: bit offset of (t, d) inside one (b,h) stream */
+static int64_t k_bit_offset(int64_t t, int d, int D, int b) { return (t * D + d) * b; }
+
+/* V codes: byte offset of the 32-bit word and bit offset inside it, one (b,h) stream */
+static void v_position(int64_t t, int d, int D, int b, int64_t* word_byte, int* bit) {
+  int64_t blk = t / 64;
+  int tt = (int)(t % 64);
+  int o = tt / 32, u = tt % 32;
+  int x4 = u / 16, j = (u % 16) / 4, r = u % 4;
+  int i = 4 * x4 + r;
+  int x = i % 2, v = i / 2;
+  int pv = 4 * o + v;
+  int P = 16 / b;
+  int n = pv / P, p = pv % P;
+  int dt = d / 16;
+  int e = dt * (b / 2) + n;
+  *word_byte = blk * (64 * (int64_t)D * b / 8) + (int64_t)(e / 4) * (8 * D) + (16 * j + d % 16) * 16 + 4 * (e % 4);
+  *bit = 16 * x + b * p;
+}
+
+static void put_bits_le(uint8_t* base, int64_t bit_offset, int nbits, uint32_t value) {
+  for (int k = 0; k < nbits; ++k) {
+    int64_t pos = bit_offset + k;
+    uint8_t mask = (uint8_t)(1u << (pos % 8));
+    if ((value >> k) & 1u) base[pos / 8] |= mask; else base[pos / 8] &= (uint8_t)~mask;
+  }
+}
+static uint32_t get_bits_le(const uint8_t* base, int64_t bit_offset, int nbits) {
+  uint32_t v = 0;
+  for (int k = 0; k < nbits; ++k) {
+    int64_t pos = bit_offset + k;
+    v |= (uint32_t)((base[pos / 8] >> (pos % 8)) & 1u) << k;
+  }
+  return v;
+}
+
+/* ------------------------------------------------------------------ the quantizer */
+
+/* Quantize one group of n binary32 values to `bits`-bit codes (1 <= bits <= 8).
+ * Returns the binary16 patterns of scale and zero through *S, *Z.
+ *   range  = max - min, scale = range / (2^b - 1)            (App. B scale factor, min-max form)
+ *   code   = clip(round((x - zero) / scale), 0, 2^b - 1)      (App. B "Quantization")
+ * with the stored (binary16) scale and zero used for the codes, so that reconstruction
+ * with the stored numbers is the inverse map, and the division done as multiplication by
+ * the once-rounded reciprocal of the scale. */
+void ref_quantize_group(const float* x, int n, int bits, uint8_t* codes, uint16_t* S, uint16_t* Z) {
+  float mn = x[0], mx = x[0];
+  for (int d = 1; d < n; ++d) {
+    if (x[d] < mn) mn = x[d];
+    if (x[d] > mx) mx = x[d];
+  }
+  if (mn == 0.0f) mn = 0.0f;                      /* -0 -> +0 : one canonical zero */
+  float levels = (float)((1 << bits) - 1);
+  float s32 = (mx - mn) / levels;
+  uint16_t sb = ref_f32_to_f16(s32);
+  if ((sb & 0x7FFFu) == 0) sb = 0;                /* no negative zero scale */
+  uint16_t zb = ref_f32_to_f16(mn);
+  float s = ref_f16_to_f32(sb), z = ref_f16_to_f32(zb);
+  *S = sb;
+  *Z = zb;
+  if (s == 0.0f) {                                /* constant group (or range below binary16) */
+    for (int d = 0; d < n; ++d) codes[d] = 0;
+    return;
+  }
+  float rcp = 1.0f / s;
+  for (int d = 0; d < n; ++d) {
+    float t = (x[d] - z) * rcp;                   /* two roundings: subtract, multiply */
+    float q = rintf(t);                           /* ties to even */
+    if (q < 0.0f) q = 0.0f;
+    if (q > levels) q = levels;
+    codes[d] = (uint8_t)q;
+  }
+}
+
+/* reconstruction of one element: code * scale + zero, one rounding (the product is exact) */
+float ref_reconstruct(uint32_t code, uint16_t S, uint16_t Z) {
+  return (float)code * ref_f16_to_f32(S) + ref_f16_to_f32(Z);
+}
+
+/* Quantize tokens [pos, pos+n_new) of every (b,h) stream and write them into the planes.
+ * k_new / v_new: [B][H][n_new][D] with the given element strides (D contiguous).
+ * Returns 0, or a negative number for an argument the format cannot take. */
+int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, uint8_t* v_codes,
+                        uint8_t* v_meta, const void* k_new, const void* v_new, int in_dtype,
+                        int64_t stride_b, int64_t stride_h, int64_t stride_t, int32_t pos, int32_t n_new) {
+  int D = L->head_dim;
+  if (pos < 0 || n_new < 0 || (int64_t)pos + n_new > L->max_seq) return -3;
+  if (D % 64 || D > 1024) return -1;
+  uint64_t pb[4];
+  ref_plane_bytes(L, pb);
+  int64_t streams = (int64_t)L->batch * L->kv_heads;
+  float* row = (float*)malloc(sizeof(float) * (size_t)D);
+  uint8_t* codes = (uint8_t*)malloc((size_t)D);
+  for (int which = 0; which < 2; ++which) {                 /* 0 = keys, 1 = values */
+    int b = which ? L->bits_v : L->bits_k;
+    int G = which ? L->group_v : L->group_k;
+    const void* src = which ? v_new : k_new;
+    uint8_t* cplane = which ? v_codes : k_codes;
+    uint8_t* mplane = which ? v_meta : k_meta;
+    int64_t cstream = (int64_t)(pb[which ? 2 : 0] / (uint64_t)streams);
+    int64_t mstream = (int64_t)(pb[which ? 3 : 1] / (uint64_t)streams);
+    if (b != 16 && (D % G || (b != 2 && b != 4 && b != 8))) { free(row); free(codes); return -1; }
+    for (int64_t bh = 0; bh < streams; ++bh) {
+      int64_t bi = bh / L->kv_heads, hi = bh % L->kv_heads;
+      uint8_t* cs = cplane + bh * cstream;
+      uint8_t* ms = mplane ? mplane + bh * mstream : NULL;
+      for (int64_t tn = 0; tn < n_new; ++tn) {
+        int64_t t = pos + tn;
+        int64_t base = bi * stride_b + hi * stride_h + tn * stride_t;
+        if (b == 16) {                                      /* unquantized: copy the 16-bit patterns */
+          for (int d = 0; d < D; ++d) {
+            uint32_t bits16 = ((const uint16_t*)src)[base + d];
+            if (!which) put_bits_le(cs, k_bit_offset(t, d, D, 16), 16, bits16);
+            else { int64_t wb; int bit; v_position(t, d, D, 16, &wb, &bit); put_bits_le(cs + wb, bit, 16, bits16); }
+          }
+          continue;
+        }
+        for (int d = 0; d < D; ++d) row[d] = load_elem(src, in_dtype, base + d);
+        for (int g = 0; g < D / G; ++g) {
+          uint16_t S, Z;
+          ref_quantize_group(row + g * G, G, b, codes + g * G, &S, &Z);
+          uint8_t* m = ms + meta_offset(t, g, D / G);
+          m[0] = (uint8_t)(S & 0xFF); m[1] = (uint8_t)(S >> 8);
+          m[2] = (uint8_t)(Z & 0xFF); m[3] = (uint8_t)(Z >> 8);
+        }
+        for (int d = 0; d < D; ++d) {
+          if (!which) put_bits_le(cs, k_bit_offset(t, d, D, b), b, codes[d]);
+          else { int64_t wb; int bit; v_position(t, d, D, b, &wb, &bit); put_bits_le(cs + wb, bit, b, codes[d]); }
+        }
+      }
+    }
+  }
+  free(row); free(codes);
+  return 0;
+}
+
+/* Reconstruct tokens [t0,t1) of both tensors as binary32: k_out, v_out are [B][H][t1-t0][D]. */
+int ref_dequantize(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
+                   const uint8_t* v_meta, int32_t t0, int32_t t1, float* k_out, float* v_out) {
+  int D = L->head_dim;
+  if (t0 < 0 || t1 < t0 || t1 > L->max_seq) return -3;
+  uint64_t pb[4];
+  ref_plane_bytes(L, pb);
+  int64_t streams = (int64_t)L->batch * L->kv_heads;
+  int64_t nt = t1 - t0;
+  for (int which = 0; which < 2; ++which) {
+    int b = which ? L->bits_v : L->bits_k;
+    int G = which ? L->group_v : L->group_k;
+    const uint8_t* cplane = which ? v_codes : k_codes;
+    const uint8_t* mplane = which ? v_meta : k_meta;
+    float* out = which ? v_out : k_out;
+    if (!out) continue;
+    int64_t cstream = (int64_t)(pb[which ? 2 : 0] / (uint64_t)streams);
+    int64_t mstream = (int64_t)(pb[which ? 3 : 1] / (uint64_t)streams);
+    for (int64_t bh = 0; bh < streams; ++bh) {
+      const uint8_t* cs = cplane + bh * cstream;
+      const uint8_t* ms = mplane ? mplane + bh * mstream : NULL;
+      for (int64_t t = t0; t < t1; ++t)
+        for (int d = 0; d < D; ++d) {
+          uint32_t code;
+          if (!which) code = get_bits_le(cs, k_bit_offset(t, d, D, b), b);
+          else { int64_t wb; int bit; v_position(t, d, D, b, &wb, &bit); code = get_bits_le(cs + wb, bit, b); }
+          float val;
+          if (b == 16) val = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32((uint16_t)code) : ref_f16_to_f32((uint16_t)code);
+          else {
+            const uint8_t* m = ms + meta_offset(t, d / G, D / G);
+            uint16_t S = (uint16_t)(m[0] | (m[1] << 8)), Z = (uint16_t)(m[2] | (m[3] << 8));
+            val = ref_reconstruct(code, S, Z);
+          }
+          out[((bh * nt) + (t - t0)) * D + d] = val;
+        }
+    }
+  }
+  return 0;
+}
+
+/* ------------------------------------------------------------------ attention */
+
+/* Exact softmax attention of one query row per (b, h_q) over dense binary32 K, V:
+ *   logit_t = softmax_scale * sum_d q_d K[t][d];  A = softmax(logit);  out = A V.
+ * K, V: [B][H_kv][T][D] (T = seq_len rows used); q: [B][H_q][D] of dtype q_dtype;
+ * query head h_q reads KV head h_q / (H_q/H_kv).  Two passes, binary64 sums. */
+int ref_attention_dense(const float* K, const float* V, int32_t batch, int32_t kv_heads, int32_t q_heads,
+                        int32_t seq_len, int32_t D, const void* q, int q_dtype, float softmax_scale, float* out) {
+  if (seq_len <= 0 || q_heads % kv_heads) return -1;
+  int R = q_heads / kv_heads;
+  double* logit = (double*)malloc(sizeof(double) * (size_t)seq_len);
+  double* acc = (double*)malloc(sizeof(double) * (size_t)D);
+  for (int b = 0; b < batch; ++b)
+    for (int hq = 0; hq < q_heads; ++hq) {
+      int hk = hq / R;
+      const float* Kh = K + ((int64_t)b * kv_heads + hk) * seq_len * D;
+      const float* Vh = V + ((int64_t)b * kv_heads + hk) * seq_len * D;
+      int64_t qbase = ((int64_t)b * q_heads + hq) * D;
+      double mx = -INFINITY;
+      for (int t = 0; t < seq_len; ++t) {
+        double s = 0.0;
+        for (int d = 0; d < D; ++d) s += (double)load_elem(q, q_dtype, qbase + d) * (double)Kh[(int64_t)t * D + d];
+        logit[t] = (double)softmax_scale * s;
+        if (logit[t] > mx) mx = logit[t];
+      }
+      double denom = 0.0;
+      for (int d = 0; d < D; ++d) acc[d] = 0.0;
+      for (int t = 0; t < seq_len; ++t) {
+        double p = exp(logit[t] - mx);
+        denom += p;
+        for (int d = 0; d < D; ++d) acc[d] += p * (double)Vh[(int64_t)t * D + d];
+      }
+      for (int d = 0; d < D; ++d) out[qbase + d] = (float)(acc[d] / denom);
+    }
+  free(logit); free(acc);
+  return 0;
+}
+
+/* Decode attention over the packed cache = reconstruct tokens [0, seq_len), then the dense
+ * definition above.  out: [B][H_q][D] binary32. */
+int ref_decode_attention(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
+                         const uint8_t* v_meta, const void* q, int q_dtype, int32_t q_heads, int32_t seq_len,
+                         float softmax_scale, float* out) {
+  if (seq_len <= 0 || seq_len > L->max_seq) return -1;
+  int64_t n = (int64_t)L->batch * L->kv_heads * seq_len * L->head_dim;
+  float* Kd = (float*)malloc(sizeof(float) * (size_t)n);
+  float* Vd = (float*)malloc(sizeof(float) * (size_t)n);
+  if (!Kd || !Vd) { free(Kd); free(Vd); return -2; }
+  int rc = ref_dequantize(L, k_codes, k_meta, v_codes, v_meta, 0, seq_len, Kd, Vd);
+  if (!rc) rc = ref_attention_dense(Kd, Vd, L->batch, L->kv_heads, q_heads, seq_len, L->head_dim, q, q_dtype, softmax_scale, out);
+  free(Kd); free(Vd);
+  return rc;
+}
+
+/* ------------------------------------------------------------------ error metric */
+
+/* MSE(A, A^) = ||A - A^||_F^2 / (number of entries)   (App. B, Frobenius / MSE perspective) */
+double ref_mse(const float* a, const float* ahat, int64_t n) {
+  double s = 0.0;
+  for (int64_t i = 0; i < n; ++i) { double e = (double)a[i] - (double)ahat[i]; s += e * e; }
+  return s / (double)n;
+}

@@ -1,0 +1,181 @@
+"""ctypes view of the C oracle in ``kvq_oracle.c`` (test infrastructure only).
+
+The arithmetic lives in the C file; this module only builds it, marshals numpy arrays and
+hands back numpy arrays.  It imports nothing from the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kvq_oracle.c")
+_LIB = os.path.join(_HERE, "libkvq_oracle.so")
+
+F16, BF16, F32 = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (strict IEEE: no contraction, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Layout(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("batch", "kv_heads", "max_seq", "head_dim", "bits_k", "bits_v",
+                                          "group_k", "group_v", "raw_dtype")]
+
+
+@dataclass(frozen=True)
+class Layout:
+    batch: int
+    kv_heads: int
+    max_seq: int
+    head_dim: int = 128
+    bits_k: int = 4
+    bits_v: int = 2
+    group_k: int = 64
+    group_v: int = 64
+    raw_dtype: int = F16
+
+    def c(self) -> _Layout:
+        return _Layout(self.batch, self.kv_heads, self.max_seq, self.head_dim, self.bits_k, self.bits_v,
+                       self.group_k, self.group_v, self.raw_dtype)
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.ref_f16_to_f32.restype = C.c_float
+        _lib.ref_f16_to_f32.argtypes = [C.c_uint16]
+        _lib.ref_f32_to_f16.restype = C.c_uint16
+        _lib.ref_f32_to_f16.argtypes = [C.c_float]
+        _lib.ref_bf16_to_f32.restype = C.c_float
+        _lib.ref_bf16_to_f32.argtypes = [C.c_uint16]
+        _lib.ref_reconstruct.restype = C.c_float
+        _lib.ref_reconstruct.argtypes = [C.c_uint32, C.c_uint16, C.c_uint16]
+        _lib.ref_mse.restype = C.c_double
+        _lib.ref_mse.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+        _lib.ref_quantize_group.restype = None
+        _lib.ref_quantize_group.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def dtype_code(a: np.ndarray, bf16: bool = False) -> int:
+    """numpy has no bfloat16: bf16 data travels as uint16 bit patterns with bf16=True."""
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.float16:
+        return F16
+    if a.dtype == np.uint16:
+        return BF16 if bf16 else F16
+    raise TypeError(a.dtype)
+
+
+def f32_to_f16_bits(x) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float32).ravel()
+    f = lib().ref_f32_to_f16
+    return np.array([f(float(v)) for v in x], dtype=np.uint16)
+
+
+def f16_bits_to_f32(h) -> np.ndarray:
+    h = np.ascontiguousarray(h, dtype=np.uint16).ravel()
+    f = lib().ref_f16_to_f32
+    return np.array([f(int(v)) for v in h], dtype=np.float32)
+
+
+def plane_bytes(L: Layout):
+    out = (C.c_uint64 * 4)()
+    cl = L.c()
+    lib().ref_plane_bytes(C.byref(cl), out)
+    return [int(v) for v in out]
+
+
+def new_planes(L: Layout, fill: int = 0):
+    """Four uint8 planes (k_codes, k_meta, v_codes, v_meta) of the sizes the format needs."""
+    return [np.full(n, fill, dtype=np.uint8) for n in plane_bytes(L)]
+
+
+def quantize_group(x: np.ndarray, bits: int):
+    """One group -> (codes uint8[n], scale_bits, zero_bits)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    codes = np.zeros(x.size, dtype=np.uint8)
+    S = C.c_uint16()
+    Z = C.c_uint16()
+    lib().ref_quantize_group(_ptr(x), x.size, bits, _ptr(codes), C.byref(S), C.byref(Z))
+    return codes, int(S.value), int(Z.value)
+
+
+def quantize_append(L: Layout, planes, k_new: np.ndarray, v_new: np.ndarray, pos: int, bf16: bool = False) -> None:
+    """k_new, v_new: contiguous [B, H, n_new, D] arrays (float16, float32, or uint16 bit patterns)."""
+    assert k_new.shape == v_new.shape and k_new.flags.c_contiguous and v_new.flags.c_contiguous
+    B, H, n_new, D = k_new.shape
+    assert (B, H, D) == (L.batch, L.kv_heads, L.head_dim)
+    cl = L.c()
+    rc = lib().ref_quantize_append(C.byref(cl), _ptr(planes[0]), _ptr(planes[1]), _ptr(planes[2]), _ptr(planes[3]),
+                                   _ptr(k_new), _ptr(v_new), C.c_int(dtype_code(k_new, bf16)),
+                                   C.c_int64(H * n_new * D), C.c_int64(n_new * D), C.c_int64(D),
+                                   C.c_int32(pos), C.c_int32(n_new))
+    if rc:
+        raise ValueError(f"ref_quantize_append rc={rc}")
+
+
+def dequantize(L: Layout, planes, t0: int, t1: int):
+    shape = (L.batch, L.kv_heads, t1 - t0, L.head_dim)
+    k = np.zeros(shape, dtype=np.float32)
+    v = np.zeros(shape, dtype=np.float32)
+    cl = L.c()
+    rc = lib().ref_dequantize(C.byref(cl), _ptr(planes[0]), _ptr(planes[1]), _ptr(planes[2]), _ptr(planes[3]),
+                              C.c_int32(t0), C.c_int32(t1), _ptr(k), _ptr(v))
+    if rc:
+        raise ValueError(f"ref_dequantize rc={rc}")
+    return k, v
+
+
+def attention_dense(K: np.ndarray, V: np.ndarray, q: np.ndarray, softmax_scale: float, bf16: bool = False) -> np.ndarray:
+    """K, V: float32 [B, H_kv, T, D]; q: [B, H_q, D]; returns float32 [B, H_q, D]."""
+    K = np.ascontiguousarray(K, dtype=np.float32)
+    V = np.ascontiguousarray(V, dtype=np.float32)
+    q = np.ascontiguousarray(q)
+    B, Hk, T, D = K.shape
+    Hq = q.shape[1]
+    out = np.zeros((B, Hq, D), dtype=np.float32)
+    rc = lib().ref_attention_dense(_ptr(K), _ptr(V), C.c_int32(B), C.c_int32(Hk), C.c_int32(Hq), C.c_int32(T),
+                                   C.c_int32(D), _ptr(q), C.c_int(dtype_code(q, bf16)), C.c_float(softmax_scale), _ptr(out))
+    if rc:
+        raise ValueError(f"ref_attention_dense rc={rc}")
+    return out
+
+
+def decode_attention(L: Layout, planes, q: np.ndarray, seq_len: int, softmax_scale: float, bf16: bool = False) -> np.ndarray:
+    q = np.ascontiguousarray(q)
+    Hq = q.shape[1]
+    out = np.zeros((L.batch, Hq, L.head_dim), dtype=np.float32)
+    cl = L.c()
+    rc = lib().ref_decode_attention(C.byref(cl), _ptr(planes[0]), _ptr(planes[1]), _ptr(planes[2]), _ptr(planes[3]),
+                                    _ptr(q), C.c_int(dtype_code(q, bf16)), C.c_int32(Hq), C.c_int32(seq_len),
+                                    C.c_float(softmax_scale), _ptr(out))
+    if rc:
+        raise ValueError(f"ref_decode_attention rc={rc}")
+    return out
+
+
+def mse(a: np.ndarray, ahat: np.ndarray) -> float:
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    ahat = np.ascontiguousarray(ahat, dtype=np.float32)
+    return float(lib().ref_mse(_ptr(a), _ptr(ahat), C.c_int64(a.size)))

@@ -1,0 +1,321 @@
+"""Pins for the CPU oracle's quantizer and storage format.
+
+Each test ties the oracle to something other than itself: IEEE conversions done by numpy,
+bytes worked out by hand, closed forms and bounds from App. B of the paper, numbers the
+paper prints in Table 1, and an array-transpose statement of the storage order.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_15075_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# --------------------------------------------------------------------------- number formats
+
+def test_f16_to_f32_all_patterns_match_numpy(oracle):
+    bits = np.arange(65536, dtype=np.uint16)
+    want = bits.view(np.float16).astype(np.float32)
+    got = oracle.f16_bits_to_f32(bits)
+    finite = np.isfinite(want)
+    assert np.array_equal(got[finite].view(np.uint32), want[finite].view(np.uint32))
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.array_equal(np.isinf(got), np.isinf(want))
+
+
+def test_f32_to_f16_matches_numpy_rne(oracle):
+    rng = np.random.default_rng(0)
+    xs = [rng.standard_normal(20000).astype(np.float32) * s for s in (1e-7, 1e-5, 1e-3, 1.0, 300.0, 4e4)]
+    # exact halfway points between neighbouring binary16 numbers (ties), both parities
+    h = rng.integers(0, 0x7BFF, 20000).astype(np.uint16)
+    lo = h.view(np.float16).astype(np.float64)
+    hi = (h + 1).astype(np.uint16).view(np.float16).astype(np.float64)
+    xs.append(((lo + hi) / 2).astype(np.float32))
+    xs.append(np.array([0.0, -0.0, 65504.0, 65519.9, 65520.0, 7e4, -7e4, 2.0**-24, 2.0**-25, 2.0**-25 * 1.0001,
+                        2.0**-14, 2.0**-14 - 2.0**-25, 5.96e-8, 1e-10], dtype=np.float32))
+    x = np.concatenate(xs)
+    x = np.concatenate([x, -x])
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).view(np.uint16)
+    got = oracle.f32_to_f16_bits(x)
+    assert np.array_equal(got, want)
+
+
+def test_bf16_widening_matches_torch(oracle):
+    bits = np.arange(0, 65536, 7, dtype=np.uint16)
+    want = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).float().numpy()
+    got = np.array([oracle.lib().ref_bf16_to_f32(int(b)) for b in bits], dtype=np.float32)
+    ok = ~np.isnan(want)
+    assert np.array_equal(got[ok].view(np.uint32), want[ok].view(np.uint32))
+
+
+# --------------------------------------------------------------------------- hand-worked groups
+
+def test_hand_worked_groups(oracle):
+    # b=2: range 3 over 3 steps -> scale 1.0 (0x3C00), zero 0; 0.5, 1.5, 2.5 are exact ties -> even codes
+    x = np.array([0, 3, 0.5, 1.5, 2.5, 0.49, 2.51, 1.0] * 4, dtype=np.float32)
+    codes, S, Z = oracle.quantize_group(x, 2)
+    assert (S, Z) == (0x3C00, 0x0000)
+    assert codes[:8].tolist() == [0, 3, 0, 2, 2, 0, 3, 1]
+    # b=4: x = -1 + 0.5 c  -> scale 0.5 (0x3800), zero -1 (0xBC00), codes = c
+    c = np.arange(32) % 16
+    codes, S, Z = oracle.quantize_group((-1 + 0.5 * c).astype(np.float32), 4)
+    assert (S, Z) == (0x3800, 0xBC00) and codes.tolist() == c.tolist()
+    # b=8: x = 2 + c/4 -> scale 0.25 (0x3400), zero 2 (0x4000)
+    c = np.arange(256)
+    codes, S, Z = oracle.quantize_group((2 + c / 4).astype(np.float32), 8)
+    assert (S, Z) == (0x3400, 0x4000) and codes.tolist() == c.tolist()
+    # a scale that binary16 must round: range 1 over 3 steps = 0.33333334 -> 0x3555 (0.33325195)
+    codes, S, Z = oracle.quantize_group(np.array([0, 1, 1 / 3, 2 / 3], dtype=np.float32), 2)
+    assert (S, Z) == (0x3555, 0) and codes.tolist() == [0, 3, 1, 2]
+    # constant group: scale 0, codes 0, zero = the constant; -0 everywhere gives +0 zero and +0 scale
+    codes, S, Z = oracle.quantize_group(np.full(32, -2.5, dtype=np.float32), 4)
+    assert (S, Z) == (0, 0xC100) and not codes.any()
+    codes, S, Z = oracle.quantize_group(np.array([-0.0] * 32, dtype=np.float32), 4)
+    assert (S, Z) == (0, 0) and not codes.any()
+    # min is -0, max is +0 would give a -0 range: scale must still be +0
+    codes, S, Z = oracle.quantize_group(np.array([0.0, -0.0] * 16, dtype=np.float32), 2)
+    assert (S, Z) == (0, 0)
+
+
+def test_reconstruct_is_code_times_scale_plus_zero(oracle):
+    f = oracle.lib().ref_reconstruct
+    assert f(5, 0x3800, 0xBC00) == 1.5          # 5*0.5 - 1
+    assert f(0, 0x3800, 0xBC00) == -1.0
+    assert f(255, 0x3400, 0x4000) == 65.75      # 255/4 + 2
+    assert f(3, 0x3555, 0x0000) == np.float32(3) * np.float16(0.33325195).astype(np.float32)
+
+
+# --------------------------------------------------------------------------- grid-aligned inputs are exact
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("G", [32, 64, 128])
+def test_grid_aligned_inputs_round_trip_exactly(oracle, bits, G):
+    rng = np.random.default_rng(bits * 100 + G)
+    B, H, T, D = 1, 2, 70, 128
+    nlev = 2 ** bits
+    codes = rng.integers(0, nlev, size=(B, H, T, D))
+    # every group holds code 0 and code 2^b-1 so that min/max recover scale and zero
+    codes = codes.reshape(B, H, T, D // G, G)
+    codes[..., 0] = 0
+    codes[..., 1] = nlev - 1
+    # scale = {1,3,5} * 2^e and zero = integer * scale with |integer + code| * 5 < 2048: every x fits 11 bits
+    scale = (rng.choice([1, 3, 5], size=(B, H, T, D // G, 1)) * 2.0 ** rng.integers(-6, 3, size=(B, H, T, D // G, 1)))
+    zero = rng.integers(-100, 100, size=(B, H, T, D // G, 1)) * scale
+    x = (zero + codes * scale).reshape(B, H, T, D).astype(np.float32)
+    assert np.array_equal(x.astype(np.float16).astype(np.float32), x)   # inputs are binary16-exact
+    L = oracle.Layout(B, H, T, D, bits, bits, G, G)
+    planes = oracle.new_planes(L)
+    oracle.quantize_append(L, planes, x.astype(np.float16), x.astype(np.float16), 0)
+    kd, vd = oracle.dequantize(L, planes, 0, T)
+    assert np.array_equal(kd, x) and np.array_equal(vd, x)
+    # stored scale/zero are exactly the construction's
+    meta = planes[1].view(np.uint16).reshape(B, H, -1, D // G, 16, 2)
+    t = np.arange(T)
+    S = meta[:, :, t // 16, :, t % 16, 0]          # -> [T, B, H, groups]
+    Zb = meta[:, :, t // 16, :, t % 16, 1]
+    assert np.array_equal(S.view(np.float16).astype(np.float64), np.moveaxis(scale[..., 0], 2, 0))
+    assert np.array_equal(Zb.view(np.float16).astype(np.float64), np.moveaxis(zero[..., 0], 2, 0))
+
+
+# --------------------------------------------------------------------------- App. B entry-wise and Frobenius bounds
+
+def _cfg_tensor(seed, dtype, T=96):
+    K, V, _ = synth.make_kvq(seed, 1, 2, 2, T, 128, dtype=dtype)
+    return K, V
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("bits,G", [(2, 32), (2, 64), (4, 32), (4, 64), (4, 128), (8, 64)])
+def test_entrywise_error_at_most_half_a_step(oracle, dtype, bits, G):
+    """|A_ij - A^_ij| <= alpha/2 (proof of the spectral-norm bound, App. B) and
+    ||A - A^||_F <= sqrt(mn) alpha/2 (Frobenius bound), with alpha the stored group scale."""
+    K, V = _cfg_tensor(3, dtype)
+    T = K.shape[2]
+    L = oracle.Layout(1, 2, T, 128, bits, bits, G, G)
+    planes = oracle.new_planes(L)
+    kn, vn = synth.to_numpy_bits(K), synth.to_numpy_bits(V)
+    oracle.quantize_append(L, planes, kn, vn, 0, bf16=dtype == torch.bfloat16)
+    kd, vd = oracle.dequantize(L, planes, 0, T)
+    for x, xd, mplane in ((K, kd, planes[1]), (V, vd, planes[3])):
+        x = x.float().numpy().astype(np.float64)
+        meta = mplane.view(np.uint16).reshape(1, 2, -1, 128 // G, 16, 2)
+        t = np.arange(T)
+        s = meta[:, :, t // 16, :, t % 16, 0].view(np.float16).astype(np.float64)   # [T,1,2,groups]
+        s = np.repeat(np.moveaxis(s, 0, 2), G, axis=-1)                              # [1,2,T,D]
+        err = np.abs(x - xd.astype(np.float64))
+        # binary32 evaluation of (x-z)*(1/s) can sit a few ulp past an exact tie
+        assert np.all(err <= s / 2 * (1 + 2.0 ** -11) + 2.0 ** -23 * np.abs(x))
+        assert np.sqrt((err ** 2).sum()) <= np.sqrt(x.size) * s.max() / 2 * (1 + 1e-3)
+        assert err.max() > 0.2 * s.max() / 2          # and the bound is not vacuous
+
+
+# --------------------------------------------------------------------------- error scaling with bit width
+
+def _group_mse(oracle, x, bits, G=128):
+    errs = []
+    for row in x.reshape(-1, G):
+        codes, S, Z = oracle.quantize_group(row, bits)
+        s, z = np.uint16(S).view(np.float16).astype(np.float64), np.uint16(Z).view(np.float16).astype(np.float64)
+        errs.append(((row - (codes * s + z)) ** 2).mean())
+    return float(np.mean(errs))
+
+
+def test_uniform_data_mse_is_step_squared_over_twelve(oracle):
+    rng = np.random.default_rng(5)
+    x = rng.uniform(-1, 1, size=(400, 128)).astype(np.float16).astype(np.float32)
+    for bits in (2, 3, 4, 6):
+        step = 2.0 / (2 ** bits - 1)
+        m = _group_mse(oracle, x, bits)
+        assert m == pytest.approx(step ** 2 / 12, rel=0.08)
+
+
+def test_three_to_four_bit_ratio_matches_table_1(oracle):
+    """Table 1 prints K_3 and K_4 reconstruction MSE for 7 models x 3 datasets; their ratio is
+    4.5-4.7 everywhere, which is ((2^4-1)/(2^3-1))^2 = 4.59: a quantizer with 2^b-1 steps over
+    the range.  (2^(b-1)-1 steps, the symmetric form, would give (7/3)^2 = 5.44.)"""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "table1_k3_k4_mse.txt")) if l.strip() and not l.startswith("#")]
+    ratios = np.array([float(r[2]) / float(r[3]) for r in rows])
+    assert len(ratios) == 21
+    assert abs(np.median(ratios) - (15 / 7) ** 2) < 0.05
+    assert ratios.min() > 4.4 and ratios.max() < 4.75
+    K, _, _ = synth.make_kvq(11, 1, 4, 4, 200, 128, dtype=torch.bfloat16, outlier_scale=1.0)
+    x = K.float().numpy()
+    r = _group_mse(oracle, x, 3) / _group_mse(oracle, x, 4)
+    assert ratios.min() - 0.1 < r < ratios.max() + 0.1
+    # and every extra bit follows the same law:  MSE(b)/MSE(b+1) = ((2^(b+1)-1)/(2^b-1))^2
+    for b in (2, 4, 5):
+        r = _group_mse(oracle, x, b) / _group_mse(oracle, x, b + 1)
+        assert r == pytest.approx(((2 ** (b + 1) - 1) / (2 ** b - 1)) ** 2, rel=0.06)
+
+
+def test_key_error_exceeds_value_error_at_equal_bits(oracle):
+    """Table 1's headline: at the same bit width K reconstructs worse than V because its norm is larger
+    (MSE ~ ||M||_F^2 2^-2b, Sec. 3 "Quantization Error and Norm Magnitude")."""
+    K, V, _ = synth.make_kvq(12, 1, 2, 2, 128, 128, dtype=torch.bfloat16)
+    for bits in (2, 4):
+        L = oracle.Layout(1, 2, 128, 128, bits, bits, 64, 64)
+        planes = oracle.new_planes(L)
+        oracle.quantize_append(L, planes, synth.to_numpy_bits(K), synth.to_numpy_bits(V), 0, bf16=True)
+        kd, vd = oracle.dequantize(L, planes, 0, 128)
+        mk, mv = oracle.mse(K.float().numpy(), kd), oracle.mse(V.float().numpy(), vd)
+        assert mk > 4 * mv
+        ek = ((K.float().numpy().astype(np.float64) - kd) ** 2).mean()
+        assert mk == pytest.approx(ek, rel=1e-9)        # ref_mse is ||A-A^||_F^2 / entries
+
+
+# --------------------------------------------------------------------------- storage order
+
+def _pack_fields_le(fields, b):
+    """Library statement of 'b-bit fields, first field in the lowest bits': numpy bit packing."""
+    f = np.asarray(fields, dtype=np.uint16).reshape(-1, 1)
+    bits = (f >> np.arange(b, dtype=np.uint16)) & 1
+    return np.packbits(bits.astype(np.uint8).ravel(), bitorder="little")
+
+
+def _expected_planes(codes, S, Z, b, G):
+    """Build one (b,h) stream of the three layouts with array reshapes/transposes instead of
+    per-element index arithmetic.  codes: [T, D] with T % 64 == 0, S/Z: uint16 [T, D/G]."""
+    T, D = codes.shape
+    k_plane = _pack_fields_le(codes.ravel(), b)                       # token rows, channels in order
+    m = np.stack([S, Z], axis=-1).reshape(T // 16, 16, D // G, 2)       # [blk16, t%16, g, 2]
+    meta = np.ascontiguousarray(m.transpose(0, 2, 1, 3)).view(np.uint8).ravel()
+    P = 16 // b
+    # token t = blk*64 + o*32 + x4*16 + j*4 + rh*2 + x ; channel d = dt*16 + dl
+    A = codes.reshape(T // 64, 2, 2, 4, 2, 2, D // 16, 16)
+    #        axes:       blk  o  x4 j  rh x  dt      dl
+    W = A.transpose(0, 6, 1, 2, 4, 3, 7, 5)                             # blk dt o x4 rh j dl x
+    W = W.reshape(T // 64, D // 16, b // 2, P, 4, 16, 2)                # blk dt n p j dl x   ((o,x4,rh) -> (n,p))
+    W = W.transpose(0, 1, 2, 4, 5, 6, 3)                                # blk dt n j dl x p
+    W = W.reshape(T // 64, (D // 16) * (b // 2) // 4, 4, 4, 16, 2, P)   # blk q m j dl x p   ((dt,n) -> (q,m))
+    W = W.transpose(0, 1, 3, 4, 2, 5, 6)                                # blk q j dl m x p
+    v_plane = _pack_fields_le(W.ravel(), b)
+    return k_plane, meta, v_plane
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("G", [32, 128])
+def test_plane_layouts_against_array_transposes(oracle, bits, G):
+    rng = np.random.default_rng(bits + G)
+    B, H, T, D = 2, 2, 128, 128
+    x = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    L = oracle.Layout(B, H, T, D, bits, bits, G, G)
+    planes = oracle.new_planes(L)
+    oracle.quantize_append(L, planes, x, x, 0)
+    streams = [p.reshape(B * H, -1) for p in planes]
+    for bh in range(B * H):
+        rows = x.reshape(B * H, T, D)[bh].astype(np.float32)
+        codes = np.zeros((T, D), dtype=np.uint8)
+        S = np.zeros((T, D // G), dtype=np.uint16)
+        Z = np.zeros((T, D // G), dtype=np.uint16)
+        for t in range(T):
+            for g in range(D // G):
+                codes[t, g * G:(g + 1) * G], S[t, g], Z[t, g] = oracle.quantize_group(rows[t, g * G:(g + 1) * G], bits)
+        k_plane, meta, v_plane = _expected_planes(codes, S, Z, bits, G)
+        assert np.array_equal(streams[0][bh], k_plane)
+        assert np.array_equal(streams[1][bh], meta)
+        assert np.array_equal(streams[2][bh], v_plane)
+        assert np.array_equal(streams[3][bh], meta)
+
+
+def test_unquantized_planes_hold_the_input_bits(oracle):
+    rng = np.random.default_rng(9)
+    B, H, T, D = 1, 2, 64, 128
+    x = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    y = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    L = oracle.Layout(B, H, T, D, 16, 16, 64, 64)
+    planes = oracle.new_planes(L)
+    assert planes[1].size == 0 and planes[3].size == 0
+    oracle.quantize_append(L, planes, x, y, 0)
+    assert np.array_equal(planes[0].view(np.float16).reshape(B, H, T, D), x)
+    for bh in range(B * H):
+        _, _, v_plane = _expected_planes(y.reshape(B * H, T, D)[bh].view(np.uint16), np.zeros((T, 1), np.uint16),
+                                         np.zeros((T, 1), np.uint16), 16, 128)
+        assert np.array_equal(planes[2].reshape(B * H, -1)[bh], v_plane)
+    kd, vd = oracle.dequantize(L, planes, 0, T)
+    assert np.array_equal(kd, x.astype(np.float32)) and np.array_equal(vd, y.astype(np.float32))
+
+
+def test_append_touches_only_its_own_tokens_and_chunks_compose(oracle):
+    rng = np.random.default_rng(21)
+    B, H, T, D = 2, 2, 150, 128
+    x = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    y = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    L = oracle.Layout(B, H, T, D, 4, 2, 32, 64)
+    whole = oracle.new_planes(L, fill=0xA5)
+    oracle.quantize_append(L, whole, x, y, 0)
+    parts = oracle.new_planes(L, fill=0xA5)
+    for a, b in ((0, 1), (1, 17), (17, 100), (100, 150)):          # ragged chunks, single-token step included
+        oracle.quantize_append(L, parts, np.ascontiguousarray(x[:, :, a:b]), np.ascontiguousarray(y[:, :, a:b]), a)
+    for p, w in zip(parts, whole):
+        assert np.array_equal(p, w)
+    # capacity is 192 tokens; the tail [150,192) and nothing else keeps the fill pattern
+    fresh = oracle.new_planes(L, fill=0xA5)
+    kd_f, vd_f = oracle.dequantize(L, fresh, 0, T)
+    oracle.quantize_append(L, fresh, np.ascontiguousarray(x[:, :, 40:41]), np.ascontiguousarray(y[:, :, 40:41]), 40)
+    kd, vd = oracle.dequantize(L, fresh, 0, T)
+    kw, vw = oracle.dequantize(L, whole, 0, T)
+    changed_k = np.zeros(T, bool); changed_k[40] = True
+    assert np.array_equal(kd[:, :, 40], kw[:, :, 40]) and np.array_equal(vd[:, :, 40], vw[:, :, 40])
+    assert np.array_equal(kd[:, :, ~changed_k], kd_f[:, :, ~changed_k])
+    assert np.array_equal(vd[:, :, ~changed_k], vd_f[:, :, ~changed_k])
+    n_changed = sum(int((f != 0xA5).sum()) for f in fresh)
+    # K row 64 bytes; a value token owns 2 bits in each of D different bytes; 4 + 2 meta entries of 4 bytes
+    assert n_changed <= B * H * (D * 4 // 8 + D + 4 * 4 + 4 * 2)
+
+
+def test_code_bytes_k4v2_are_three_quarters_of_k4v4(oracle):
+    """Sec. 1: K4V2 cuts KV-cache memory by 25 % against K4V4 (code bits (4+2)/(4+4))."""
+    a = oracle.plane_bytes(oracle.Layout(8, 8, 8192, 128, 4, 2, 64, 64))
+    b = oracle.plane_bytes(oracle.Layout(8, 8, 8192, 128, 4, 4, 64, 64))
+    assert (a[0] + a[2]) / (b[0] + b[2]) == 0.75
+    rows = 8 * 8 * 8192
+    assert sum(a) == rows * 112 and sum(b) == rows * 144          # with binary16 scale/zero per 64 channels
+    c = oracle.plane_bytes(oracle.Layout(1, 8, 1024, 128, 4, 2, 32, 32))
+    assert sum(c) == 8 * 1024 * 128
+    d = oracle.plane_bytes(oracle.Layout(1, 1, 65, 128, 8, 8, 64, 64))
+    assert sum(d) == 128 * 272                                     # capacity rounds 65 tokens up to 128
