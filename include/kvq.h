@@ -1,0 +1,128 @@
+/*
+ * kvq.h -- C ABI of the key-prioritized mixed-precision KV cache for MI355X (gfx950).
+ *
+ * The library implements the data-parallel hot path of "Quantize What Counts: More for Keys,
+ * Less for Values" (arXiv 2502.15075): keys and values of one transformer layer are stored at
+ * independent bit widths b_K, b_V (Sec. 1; Theorem 2: b_K > b_V when ||K||_F > ||V||_F; K4V2 is
+ * the headline allocation), each quantized group-wise with the b-bit uniform scalar quantizer of
+ * App. B "Preliminaries" in its asymmetric min-max form, and single-token decode attention
+ * (App. A: A = softmax(q K^T / sqrt(d)), output A V) reads the packed codes directly.
+ *
+ * Conventions
+ *   - Every pointer in kvq_cache and every tensor argument is a DEVICE pointer owned by the
+ *     caller.  The library never allocates, frees or synchronizes; each call enqueues kernels on
+ *     the given hipStream_t (passed as void*; NULL = the default stream) and returns.
+ *   - Arguments are validated on the host before anything is launched; on error nothing ran.
+ *   - Status codes only: the library never aborts, throws or prints.
+ *   - Not checked (undefined results): non-finite inputs, |x| > 65504, a group whose
+ *     range / (2^b - 1) exceeds 128 for values (the attention kernel scales softmax weights by the
+ *     value scale in binary16), overlapping buffers, concurrent calls that write the same cache.
+ *
+ * Quantizer (per tensor X in {K, V}, bits b, group size G; one group = G consecutive head_dim
+ * elements of one token row -- token-wise grouping, Sec. 4 "Downstream Task Accuracy"):
+ *     mn, mx   = min, max of the group in binary32 (mn = -0 is stored as +0)
+ *     scale    = binary16( (mx - mn) / (2^b - 1) )        zero = binary16( mn )
+ *     code_d   = clip( rint( (x_d - zero) * (1 / scale) ), 0, 2^b - 1 )   (all codes 0 if scale == 0)
+ *     x^_d     = code_d * scale + zero                                   (App. B "Dequantization")
+ *   every operation rounded once in binary32, round-to-nearest-even; codes use the STORED scale/zero.
+ *
+ * Storage format of one layer (sizes from kvq_cache_bytes; T_cap = max_seq rounded up to 64):
+ *   k_codes  [B][H_kv][T_cap][D*b_K/8]      element d of a row at bits [d*b_K, (d+1)*b_K), little-endian
+ *   k_meta   [B][H_kv][T_cap/16][D/G_K][16] entries {uint16 scale, uint16 zero} (binary16 patterns);
+ *                                           entry (t/16, g, t%16) is token t, group g
+ *   v_codes  [B][H_kv][T_cap/64][1024*b_V]  64-token blocks laid out in the order a 16x16x32 matrix
+ *                                           instruction consumes a "tokens x channels" operand.  With
+ *                                             tt=t%64, o=tt/32, u=tt%32, x4=u/16, j=(u%16)/4, r=u%4,
+ *                                             i=4*x4+r, x=i%2, v=i/2, pv=4*o+v, P=16/b_V, n=pv/P, p=pv%P,
+ *                                             dt=d/16, e=dt*(b_V/2)+n
+ *                                           the code of (t, d) sits in the little-endian 32-bit word at
+ *                                           byte (e/4)*1024 + (16*j + d%16)*16 + 4*(e%4) of the block,
+ *                                           at bit 16*x + b_V*p.
+ *   v_meta   as k_meta with G_V.
+ *   bits == 16 keeps the 16-bit input patterns (raw_dtype) in the same positions; no meta plane.
+ */
+#ifndef KVQ_H
+#define KVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  KVQ_OK = 0,
+  KVQ_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, bits/group not allowed, bad head ratio */
+  KVQ_ERR_UNSUPPORTED = 2, /* a valid request this build has no kernel for (head_dim != 128, axis) */
+  KVQ_ERR_CAPACITY = 3,    /* pos + n_new > max_seq, seq_len > max_seq */
+  KVQ_ERR_WORKSPACE = 4,   /* workspace smaller than kvq_decode_workspace_bytes */
+  KVQ_ERR_DEVICE = 5       /* the HIP runtime reported an error at launch */
+} kvq_status;
+
+typedef enum { KVQ_F16 = 0, KVQ_BF16 = 1, KVQ_F32 = 2 } kvq_dtype;
+
+typedef enum {
+  KVQ_AXIS_HEAD_DIM = 0, /* token-wise: groups of G channels inside one token row (Sec. 4, "per-row") */
+  KVQ_AXIS_SEQ = 1       /* channel-wise: groups along the sequence (Sec. 4, "per-column"); not built */
+} kvq_axis;
+
+/* Immutable description of one layer's cache.  head_dim must be 128.  bits in {2,4,8,16};
+ * group in {32,64,128} (ignored for bits == 16).  raw_dtype (KVQ_F16 / KVQ_BF16) is the element
+ * type of a plane whose bits == 16. */
+typedef struct {
+  int32_t batch, kv_heads, max_seq, head_dim;
+  int32_t bits_k, bits_v;
+  int32_t group_k, group_v;
+  int32_t axis_k, axis_v;
+  int32_t raw_dtype;
+} kvq_layout;
+
+/* Caller-owned device buffers of at least the sizes kvq_cache_bytes reports (16-byte aligned).
+ * A meta pointer may be NULL iff the matching bits == 16. */
+typedef struct {
+  void *k_codes, *k_meta, *v_codes, *v_meta;
+} kvq_cache;
+
+/* Host only.  bytes_out = sizes of k_codes, k_meta, v_codes, v_meta.  Pins the paper's memory
+ * claim (Sec. 1): K4V2 code bytes are 3/4 of K4V4's. */
+kvq_status kvq_cache_bytes(const kvq_layout* layout, size_t bytes_out[4]);
+
+/* Host only.  Bytes of scratch kvq_decode_attention needs for (q_heads, seq_len): the partial
+ * (max, sum, accumulator) records of its split-sequence pass. */
+kvq_status kvq_decode_workspace_bytes(const kvq_layout* layout, int32_t q_heads, int32_t seq_len,
+                                      size_t* bytes_out);
+
+/* Quantize n_new tokens of keys and values and store them at positions [pos, pos + n_new)
+ * (the per-step cache update of autoregressive decoding, Sec. 4 "Quantization-Error Evaluation").
+ *   k_new, v_new   [B][H_kv][n_new][D] of in_dtype (KVQ_F16 / KVQ_BF16), element strides given,
+ *                  the D axis contiguous.  For bits == 16, in_dtype must equal raw_dtype.
+ * Writes only the bytes (for values: only the bit fields) of those tokens.  n_new == 0 is a no-op. */
+kvq_status kvq_quantize_append(const kvq_layout* layout, const kvq_cache* cache, const void* k_new,
+                               const void* v_new, kvq_dtype in_dtype, int64_t stride_b, int64_t stride_h,
+                               int64_t stride_t, int32_t pos, int32_t n_new, void* stream);
+
+/* Decode attention of one query token per sequence over cached tokens [0, seq_len):
+ *   out[b,hq,:] = softmax_t( softmax_scale * q[b,hq,:] . K^[b,hq/R,t,:] ) . V^[b,hq/R,t,:],  R = q_heads/kv_heads
+ * (App. A; the caller passes softmax_scale = 1/sqrt(head_dim); it must be positive and finite).
+ *   q    [B][q_heads][D] contiguous, KVQ_F16 or KVQ_BF16 (used exactly; values beyond binary16 range
+ *        are not supported); q_heads / kv_heads in {1,2,4,8}.
+ *   out  [B][q_heads][D] contiguous, KVQ_F32 (the graded type), KVQ_F16 or KVQ_BF16 (rounded once).
+ *   workspace  at least kvq_decode_workspace_bytes(layout, q_heads, seq_len) bytes, 16-byte aligned. */
+kvq_status kvq_decode_attention(const kvq_layout* layout, const kvq_cache* cache, const void* q,
+                                kvq_dtype q_dtype, int32_t q_heads, int32_t seq_len, float softmax_scale,
+                                void* out, kvq_dtype out_dtype, void* workspace, size_t workspace_bytes,
+                                void* stream);
+
+/* Reconstruct tokens [t0, t1) as x^ = code * scale + zero (App. B "Dequantization"):
+ *   k_out, v_out  [B][H_kv][t1-t0][D] contiguous of out_dtype; either may be NULL to skip it.
+ * KVQ_F32 output is exactly the binary32 value; 16-bit outputs round it once. */
+kvq_status kvq_dequantize(const kvq_layout* layout, const kvq_cache* cache, int32_t t0, int32_t t1,
+                          void* k_out, void* v_out, kvq_dtype out_dtype, void* stream);
+
+const char* kvq_status_string(kvq_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVQ_H */

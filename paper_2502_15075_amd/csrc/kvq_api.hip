@@ -1,0 +1,140 @@
+// C ABI of libkvq: argument validation on the host, then one launcher call per entry point.
+#include "kvq_internal.h"
+
+namespace {
+
+bool bits_ok(int b) { return b == 2 || b == 4 || b == 8 || b == 16; }
+bool group_ok(int g) { return g == 32 || g == 64 || g == 128; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Checks everything about a layout that does not depend on the call.
+kvq_status check_layout(const kvq_layout* L) {
+  if (!L) return KVQ_ERR_INVALID_ARG;
+  if (L->batch <= 0 || L->kv_heads <= 0 || L->max_seq <= 0 || L->head_dim <= 0) return KVQ_ERR_INVALID_ARG;
+  if (!bits_ok(L->bits_k) || !bits_ok(L->bits_v)) return KVQ_ERR_INVALID_ARG;
+  if (L->bits_k != 16 && (!group_ok(L->group_k) || L->head_dim % L->group_k)) return KVQ_ERR_INVALID_ARG;
+  if (L->bits_v != 16 && (!group_ok(L->group_v) || L->head_dim % L->group_v)) return KVQ_ERR_INVALID_ARG;
+  if ((L->axis_k != KVQ_AXIS_HEAD_DIM && L->axis_k != KVQ_AXIS_SEQ) ||
+      (L->axis_v != KVQ_AXIS_HEAD_DIM && L->axis_v != KVQ_AXIS_SEQ))
+    return KVQ_ERR_INVALID_ARG;
+  if (L->raw_dtype != KVQ_F16 && L->raw_dtype != KVQ_BF16) return KVQ_ERR_INVALID_ARG;
+  if (L->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;
+  if (L->axis_k != KVQ_AXIS_HEAD_DIM || L->axis_v != KVQ_AXIS_HEAD_DIM) return KVQ_ERR_UNSUPPORTED;
+  if ((int64_t)L->batch * L->kv_heads > 65535) return KVQ_ERR_UNSUPPORTED;
+  if (L->max_seq > (1 << 30)) return KVQ_ERR_UNSUPPORTED;
+  return KVQ_OK;
+}
+
+kvq_status check_cache(const kvq_layout* L, const kvq_cache* c) {
+  if (!c || !c->k_codes || !c->v_codes) return KVQ_ERR_INVALID_ARG;
+  if (L->bits_k != 16 && !c->k_meta) return KVQ_ERR_INVALID_ARG;
+  if (L->bits_v != 16 && !c->v_meta) return KVQ_ERR_INVALID_ARG;
+  if (!aligned16(c->k_codes) || !aligned16(c->v_codes) || !aligned16(c->k_meta) || !aligned16(c->v_meta))
+    return KVQ_ERR_INVALID_ARG;
+  return KVQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+kvq_status kvq_cache_bytes(const kvq_layout* layout, size_t bytes_out[4]) {
+  kvq_status st = check_layout(layout);
+  if (st != KVQ_OK) return st;
+  if (!bytes_out) return KVQ_ERR_INVALID_ARG;
+  const kvq::Geom g = kvq::make_geom(*layout);
+  const int64_t streams = (int64_t)g.batch * g.kv_heads;
+  bytes_out[0] = (size_t)(streams * g.kc_stream);
+  bytes_out[1] = (size_t)(streams * g.km_stream);
+  bytes_out[2] = (size_t)(streams * g.vc_stream);
+  bytes_out[3] = (size_t)(streams * g.vm_stream);
+  return KVQ_OK;
+}
+
+kvq_status kvq_decode_workspace_bytes(const kvq_layout* layout, int32_t q_heads, int32_t seq_len, size_t* bytes_out) {
+  kvq_status st = check_layout(layout);
+  if (st != KVQ_OK) return st;
+  if (!bytes_out || q_heads <= 0 || q_heads % layout->kv_heads || seq_len <= 0) return KVQ_ERR_INVALID_ARG;
+  if (seq_len > layout->max_seq) return KVQ_ERR_CAPACITY;
+  const kvq::Geom g = kvq::make_geom(*layout);
+  const kvq::DecodePlan plan = kvq::plan_decode(g, seq_len);
+  // one record of (head_dim + 2) floats per (batch, query head, split), padded to 16 bytes
+  *bytes_out = (size_t)layout->batch * q_heads * plan.n_splits * (kvq::kHeadDim + 4) * sizeof(float);
+  return KVQ_OK;
+}
+
+kvq_status kvq_quantize_append(const kvq_layout* layout, const kvq_cache* cache, const void* k_new, const void* v_new,
+                               kvq_dtype in_dtype, int64_t stride_b, int64_t stride_h, int64_t stride_t, int32_t pos,
+                               int32_t n_new, void* stream) {
+  kvq_status st = check_layout(layout);
+  if (st != KVQ_OK) return st;
+  st = check_cache(layout, cache);
+  if (st != KVQ_OK) return st;
+  if (pos < 0 || n_new < 0) return KVQ_ERR_INVALID_ARG;
+  if ((int64_t)pos + n_new > layout->max_seq) return KVQ_ERR_CAPACITY;
+  if (n_new == 0) return KVQ_OK;
+  if (!k_new || !v_new) return KVQ_ERR_INVALID_ARG;
+  if (in_dtype != KVQ_F16 && in_dtype != KVQ_BF16) return KVQ_ERR_INVALID_ARG;
+  if ((layout->bits_k == 16 || layout->bits_v == 16) && (int)in_dtype != layout->raw_dtype) return KVQ_ERR_INVALID_ARG;
+  // rows are read with 16-byte loads
+  if (!aligned16(k_new) || !aligned16(v_new) || stride_b % 8 || stride_h % 8 || stride_t % 8 || stride_t < layout->head_dim)
+    return KVQ_ERR_INVALID_ARG;
+  const kvq::Geom g = kvq::make_geom(*layout);
+  hipError_t e = kvq::launch_quantize_append(g, *cache, k_new, v_new, in_dtype, stride_b, stride_h, stride_t, pos, n_new,
+                                             (hipStream_t)stream);
+  return e == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
+}
+
+kvq_status kvq_decode_attention(const kvq_layout* layout, const kvq_cache* cache, const void* q, kvq_dtype q_dtype,
+                                int32_t q_heads, int32_t seq_len, float softmax_scale, void* out, kvq_dtype out_dtype,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  kvq_status st = check_layout(layout);
+  if (st != KVQ_OK) return st;
+  st = check_cache(layout, cache);
+  if (st != KVQ_OK) return st;
+  if (!q || !out || q_heads <= 0 || q_heads % layout->kv_heads || seq_len <= 0) return KVQ_ERR_INVALID_ARG;
+  if (seq_len > layout->max_seq) return KVQ_ERR_CAPACITY;
+  if (q_dtype != KVQ_F16 && q_dtype != KVQ_BF16) return KVQ_ERR_INVALID_ARG;
+  if (out_dtype != KVQ_F32 && out_dtype != KVQ_F16 && out_dtype != KVQ_BF16) return KVQ_ERR_INVALID_ARG;
+  if (!(softmax_scale > 0.0f) || softmax_scale > 3.0e38f) return KVQ_ERR_INVALID_ARG;   // positive and finite
+  if (!aligned16(q) || !aligned16(out)) return KVQ_ERR_INVALID_ARG;
+  const kvq::Geom g = kvq::make_geom(*layout);
+  if (!kvq::decode_supported(g, q_heads)) return KVQ_ERR_UNSUPPORTED;
+  size_t need = 0;
+  st = kvq_decode_workspace_bytes(layout, q_heads, seq_len, &need);
+  if (st != KVQ_OK) return st;
+  if (!workspace || workspace_bytes < need || !aligned16(workspace)) return KVQ_ERR_WORKSPACE;
+  const kvq::DecodePlan plan = kvq::plan_decode(g, seq_len);
+  hipError_t e = kvq::launch_decode_attention(g, *cache, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype,
+                                              (float*)workspace, plan, (hipStream_t)stream);
+  return e == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
+}
+
+kvq_status kvq_dequantize(const kvq_layout* layout, const kvq_cache* cache, int32_t t0, int32_t t1, void* k_out,
+                          void* v_out, kvq_dtype out_dtype, void* stream) {
+  kvq_status st = check_layout(layout);
+  if (st != KVQ_OK) return st;
+  st = check_cache(layout, cache);
+  if (st != KVQ_OK) return st;
+  if (t0 < 0 || t1 < t0) return KVQ_ERR_INVALID_ARG;
+  if (t1 > layout->max_seq) return KVQ_ERR_CAPACITY;
+  if (out_dtype != KVQ_F32 && out_dtype != KVQ_F16 && out_dtype != KVQ_BF16) return KVQ_ERR_INVALID_ARG;
+  if (!k_out && !v_out) return KVQ_ERR_INVALID_ARG;
+  const kvq::Geom g = kvq::make_geom(*layout);
+  hipError_t e = kvq::launch_dequantize(g, *cache, t0, t1, k_out, v_out, out_dtype, (hipStream_t)stream);
+  return e == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
+}
+
+const char* kvq_status_string(kvq_status status) {
+  switch (status) {
+    case KVQ_OK: return "ok";
+    case KVQ_ERR_INVALID_ARG: return "invalid argument";
+    case KVQ_ERR_UNSUPPORTED: return "unsupported configuration";
+    case KVQ_ERR_CAPACITY: return "beyond cache capacity";
+    case KVQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case KVQ_ERR_DEVICE: return "HIP runtime error at launch";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

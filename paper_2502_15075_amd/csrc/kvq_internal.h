@@ -1,0 +1,80 @@
+// Internal declarations shared by the translation units of libkvq (host launchers + device helpers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvq.h"
+
+namespace kvq {
+
+constexpr int kHeadDim = 128;     // the only head_dim the kernels are written for
+constexpr int kBlockTokens = 64;  // value codes are stored in blocks of this many tokens
+
+// Geometry derived once on the host and passed by value to every kernel.
+struct Geom {
+  int32_t batch, kv_heads, t_cap;   // t_cap = max_seq rounded up to kBlockTokens
+  int32_t bits_k, bits_v, ng_k, ng_v, g_k, g_v;
+  int32_t raw_dtype;
+  int64_t kc_stream, km_stream, vc_stream, vm_stream;   // bytes per (b,h) stream in each plane
+};
+
+inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+
+inline Geom make_geom(const kvq_layout& L) {
+  Geom g{};
+  g.batch = L.batch; g.kv_heads = L.kv_heads;
+  g.t_cap = (int32_t)round_up(L.max_seq, kBlockTokens);
+  g.bits_k = L.bits_k; g.bits_v = L.bits_v;
+  g.g_k = L.bits_k == 16 ? kHeadDim : L.group_k;
+  g.g_v = L.bits_v == 16 ? kHeadDim : L.group_v;
+  g.ng_k = kHeadDim / g.g_k; g.ng_v = kHeadDim / g.g_v;
+  g.raw_dtype = L.raw_dtype;
+  g.kc_stream = (int64_t)g.t_cap * (kHeadDim * L.bits_k / 8);
+  g.vc_stream = (int64_t)g.t_cap * (kHeadDim * L.bits_v / 8);
+  g.km_stream = L.bits_k == 16 ? 0 : (int64_t)g.t_cap * g.ng_k * 4;
+  g.vm_stream = L.bits_v == 16 ? 0 : (int64_t)g.t_cap * g.ng_v * 4;
+  return g;
+}
+
+// Number of sequence splits the decode kernel uses for this problem (host-side plan).
+struct DecodePlan {
+  int32_t n_splits;          // workgroups per (b, h_kv)
+  int32_t blocks_per_split;  // 64-token blocks each workgroup walks
+};
+DecodePlan plan_decode(const Geom& g, int32_t seq_len);
+
+// Launchers (each validates nothing: the C ABI layer has done it).  Return hipGetLastError().
+hipError_t launch_quantize_append(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new,
+                                  int in_dtype, int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new,
+                                  hipStream_t stream);
+hipError_t launch_dequantize(const Geom& g, const kvq_cache& c, int32_t t0, int32_t t1, void* k_out, void* v_out,
+                             int out_dtype, hipStream_t stream);
+// Returns hipErrorInvalidValue if no kernel instance exists for (bits, groups, head ratio).
+hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void* q, int q_dtype, int32_t q_heads,
+                                   int32_t seq_len, float softmax_scale, void* out, int out_dtype, float* workspace,
+                                   const DecodePlan& plan, hipStream_t stream);
+bool decode_supported(const Geom& g, int32_t q_heads);
+
+#if defined(__HIPCC__)
+// ---- device-side address helpers (the storage order documented in kvq.h) ----
+
+// dword index of meta entry (token t, group g) inside one (b,h) stream
+__host__ __device__ inline int64_t meta_index(int64_t t, int g, int ng) { return ((t >> 4) * ng + g) * 16 + (t & 15); }
+
+// Position of value code (tt = token inside its 64-token block, d) for bit width b:
+// dword index inside the block and bit offset inside the dword.
+__host__ __device__ inline void v_field(int tt, int d, int b, int* dword, int* bit) {
+  int o = tt >> 5, u = tt & 31;
+  int x4 = u >> 4, j = (u >> 2) & 3, r = u & 3;
+  int i = 4 * x4 + r;
+  int x = i & 1, v = i >> 1;
+  int pv = 4 * o + v;
+  int P = 16 / b;
+  int n = pv / P, p = pv % P;
+  int e = (d >> 4) * (b >> 1) + n;
+  *dword = (e >> 2) * 256 + (16 * j + (d & 15)) * 4 + (e & 3);
+  *bit = 16 * x + b * p;
+}
+#endif
+
+}  // namespace kvq

@@ -1,0 +1,164 @@
+"""Thin Python binding of libkvq's C ABI (include/kvq.h): argument marshalling only.
+
+Every step of the path runs in the HIP kernels of libkvq.so; torch is used for device memory
+and streams.  There is no fallback: if the library is missing the import of the functions
+below raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvq.so")
+
+KVQ_F16, KVQ_BF16, KVQ_F32 = 0, 1, 2
+AXIS_HEAD_DIM, AXIS_SEQ = 0, 1
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_WORKSPACE, ERR_DEVICE = range(6)
+
+_DTYPES = {torch.float16: KVQ_F16, torch.bfloat16: KVQ_BF16, torch.float32: KVQ_F32}
+
+
+class KvqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class _CLayout(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("batch", "kv_heads", "max_seq", "head_dim", "bits_k", "bits_v", "group_k",
+                                          "group_v", "axis_k", "axis_v", "raw_dtype")]
+
+
+class _CCache(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_meta", "v_codes", "v_meta")]
+
+
+_lib = None
+
+
+def load():
+    """Loads libkvq.so (built by `paper_2502_15075_amd.build`); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2502_15075_amd.build` (there is no fallback path)")
+        lib = C.CDLL(LIB_PATH)
+        lib.kvq_cache_bytes.argtypes = [C.POINTER(_CLayout), C.POINTER(C.c_size_t)]
+        lib.kvq_decode_workspace_bytes.argtypes = [C.POINTER(_CLayout), C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+        lib.kvq_quantize_append.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int,
+                                            C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p]
+        lib.kvq_decode_attention.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_int, C.c_int32,
+                                             C.c_int32, C.c_float, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.kvq_dequantize.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_int32, C.c_int32, C.c_void_p,
+                                       C.c_void_p, C.c_int, C.c_void_p]
+        lib.kvq_status_string.argtypes = [C.c_int]
+        lib.kvq_status_string.restype = C.c_char_p
+        for f in ("kvq_cache_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
+                  "kvq_dequantize"):
+            getattr(lib, f).restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().kvq_status_string(int(status)).decode()
+
+
+@dataclass(frozen=True)
+class Layout:
+    """Mirror of kvq_layout."""
+    batch: int
+    kv_heads: int
+    max_seq: int
+    head_dim: int = 128
+    bits_k: int = 4
+    bits_v: int = 2
+    group_k: int = 64
+    group_v: int = 64
+    axis_k: int = AXIS_HEAD_DIM
+    axis_v: int = AXIS_HEAD_DIM
+    raw_dtype: int = KVQ_F16
+
+    def c(self) -> _CLayout:
+        return _CLayout(self.batch, self.kv_heads, self.max_seq, self.head_dim, self.bits_k, self.bits_v, self.group_k,
+                        self.group_v, self.axis_k, self.axis_v, self.raw_dtype)
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise KvqError(status, where)
+
+
+def _stream_ptr():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _p(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def cache_bytes(layout: Layout):
+    out = (C.c_size_t * 4)()
+    cl = layout.c()
+    _check(load().kvq_cache_bytes(C.byref(cl), out), "kvq_cache_bytes")
+    return [int(v) for v in out]
+
+
+def decode_workspace_bytes(layout: Layout, q_heads: int, seq_len: int) -> int:
+    out = C.c_size_t()
+    cl = layout.c()
+    _check(load().kvq_decode_workspace_bytes(C.byref(cl), q_heads, seq_len, C.byref(out)), "kvq_decode_workspace_bytes")
+    return int(out.value)
+
+
+class Cache:
+    """Four caller-owned device planes (torch uint8 tensors) for one layer."""
+
+    def __init__(self, layout: Layout, device="cuda", fill=None):
+        self.layout = layout
+        sizes = cache_bytes(layout)
+        mk = (lambda n: torch.empty(n, dtype=torch.uint8, device=device)) if fill is None else \
+             (lambda n: torch.full((n,), fill, dtype=torch.uint8, device=device))
+        self.planes = [mk(n) if n else None for n in sizes]
+
+    def c(self) -> _CCache:
+        return _CCache(*[(0 if p is None else p.data_ptr()) for p in self.planes])
+
+    def nbytes(self) -> int:
+        return sum(0 if p is None else p.numel() for p in self.planes)
+
+
+def quantize_append(layout: Layout, cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, pos: int) -> None:
+    """k_new, v_new: [B, H_kv, n_new, D] fp16/bf16 device tensors, last axis contiguous."""
+    assert k_new.shape == v_new.shape and k_new.dtype == v_new.dtype and k_new.dim() == 4
+    assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1
+    cl, cc = layout.c(), cache.c()
+    st = load().kvq_quantize_append(C.byref(cl), C.byref(cc), _p(k_new), _p(v_new), _DTYPES[k_new.dtype],
+                                    k_new.stride(0), k_new.stride(1), k_new.stride(2), pos, k_new.shape[2], _stream_ptr())
+    _check(st, "kvq_quantize_append")
+
+
+def decode_attention(layout: Layout, cache: Cache, q: torch.Tensor, seq_len: int, softmax_scale: float,
+                     out: torch.Tensor, workspace: torch.Tensor) -> torch.Tensor:
+    """q: [B, H_q, D] contiguous fp16/bf16; out: [B, H_q, D] contiguous fp32/fp16/bf16; workspace: uint8 device tensor."""
+    assert q.is_contiguous() and out.is_contiguous() and q.dim() == 3 and out.shape == q.shape
+    cl, cc = layout.c(), cache.c()
+    st = load().kvq_decode_attention(C.byref(cl), C.byref(cc), _p(q), _DTYPES[q.dtype], q.shape[1], seq_len,
+                                     C.c_float(softmax_scale), _p(out), _DTYPES[out.dtype], _p(workspace),
+                                     0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_ptr())
+    _check(st, "kvq_decode_attention")
+    return out
+
+
+def dequantize(layout: Layout, cache: Cache, t0: int, t1: int, k_out, v_out) -> None:
+    """k_out, v_out: [B, H_kv, t1-t0, D] contiguous (fp32/fp16/bf16) or None."""
+    ref = k_out if k_out is not None else v_out
+    for t in (k_out, v_out):
+        assert t is None or (t.is_contiguous() and t.dtype == ref.dtype)
+    cl, cc = layout.c(), cache.c()
+    st = load().kvq_dequantize(C.byref(cl), C.byref(cc), t0, t1, _p(k_out), _p(v_out), _DTYPES[ref.dtype], _stream_ptr())
+    _check(st, "kvq_dequantize")
