@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the K4V2 decode hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--workload llama70b|llama8b]
+
+One step = one pass of the whole hot path over one layer's batch: quantize-and-append the new
+token's K/V (B x H_kv rows) into the packed cache, then single-token decode attention over the
+whole context reading the packed codes.  The default workload is the Llama-3-70B-shaped layer
+(64 query heads, 8 KV heads, head_dim 128, batch 32, context 32768, bf16 inputs, K4V2 with
+64-channel groups); `--layers` independently seeded layers (K scale drawn from U[2,6]) are
+resident in HBM and taken in turn, so every step streams a different 896 MiB cache.
+
+Prints ONE JSON line: effective packed-KV GB/s over the whole step, the HBM roofline of the
+decode kernel (HIP events around it on its own stream), and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import re
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+WORKLOADS = {
+    # name: (batch, q_heads, kv_heads, context, description)
+    "llama70b": (32, 64, 8, 32768, "configs[3]: Llama-3-70B layer, B=32, H_q=64, H_kv=8, D=128, T=32768, bf16, K4V2 G=64"),
+    "llama8b": (8, 32, 8, 8192, "configs[1]: Llama-3-8B layer, B=8, H_q=32, H_kv=8, D=128, T=8192, bf16, K4V2 G=64"),
+}
+
+
+def _traffic_from_profile(name: str):
+    """HBM bytes per decode launch from the committed counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+    return float(m.group(1)) if m else None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--layers", type=int, default=40, help="resident layer caches taken in turn")
+    ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path is a single-GPU kernel library (no collectives); run with --gpus 1", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+
+    from paper_2502_15075_amd import kvq, synth
+    kvq.load()                                   # fails loudly if libkvq.so is missing
+    dev = "cuda"
+    B, Hq, Hkv, T, desc = WORKLOADS[args.workload]
+    D, G = 128, 64
+    L = kvq.Layout(B, Hkv, T, D, 4, 2, G, G)
+    scale = 1.0 / math.sqrt(D)
+    row_bytes = 16 * 4 + 16 * 2 + 2 * (D // G) * 4          # K4 codes + V2 codes + scale/zero pairs = 112
+    kv_bytes = B * Hkv * T * row_bytes
+
+    # ---- resident layers: generate, quantize (timed: bulk quantize tok/s), keep the last token + query
+    g = torch.Generator().manual_seed(3)
+    ratios = (torch.rand(args.layers, generator=g) * 4 + 2).tolist()
+    layers = []
+    fill_ms, fill_tokens = 0.0, 0
+    chunk = 2048
+    for li in range(args.layers):
+        K, V, q = synth.make_kvq(1000 + li, B, Hkv, Hq, T, D, dtype=torch.bfloat16, sigma_k=ratios[li], device=dev)
+        cache = kvq.Cache(L, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for a in range(0, T, chunk):
+            kvq.quantize_append(L, cache, K[:, :, a:a + chunk], V[:, :, a:a + chunk], a)
+        e1.record()
+        torch.cuda.synchronize()
+        fill_ms += e0.elapsed_time(e1)
+        fill_tokens += B * T
+        layers.append((cache, K[:, :, T - 1:T].clone(), V[:, :, T - 1:T].clone(), q))
+        if li == 0:
+            sample = (K[:4].cpu(), V[:4].cpu(), q[:4].cpu())
+        del K, V
+    ws = torch.empty(kvq.decode_workspace_bytes(L, Hq, T), dtype=torch.uint8, device=dev)
+    out = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
+
+    def step(i, ev=None):
+        cache, k1, v1, q = layers[i % len(layers)]
+        kvq.quantize_append(L, cache, k1, v1, T - 1)
+        if ev is not None:
+            ev[0].record()
+        kvq.decode_attention(L, cache, q, T, scale, out, ws)
+        if ev is not None:
+            ev[1].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    decode_ms = sum(a.elapsed_time(b) for a, b in events) / args.steps
+    value = kv_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved = kv_bytes / (decode_ms * 1e-3) / 1e9
+
+    # ---- parity of the sampled outputs and the CPU oracle timed on the same sample
+    cpu_baseline, parity = None, None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import ref
+        Ks, Vs, qs = sample
+        nb = Ks.shape[0]
+        Lo = ref.Layout(nb, Hkv, T, D, 4, 2, G, G)
+        planes = ref.new_planes(Lo)
+        c0 = time.perf_counter()
+        ref.quantize_append(Lo, planes, synth.to_numpy_bits(Ks), synth.to_numpy_bits(Vs), 0, bf16=True)
+        c1 = time.perf_counter()
+        want = ref.decode_attention(Lo, planes, synth.to_numpy_bits(qs), T, scale, bf16=True)
+        c2 = time.perf_counter()
+        cache0, _, _, q0 = layers[0]
+        kvq.decode_attention(L, cache0, q0, T, scale, out, ws)
+        torch.cuda.synchronize()
+        got = out[:nb].cpu().numpy().astype(np.float64)
+        parity = float((np.abs(got - want).max(axis=-1) / np.abs(want).max(axis=-1)).max())
+        gpu_planes = [p.view(B, -1)[:nb].reshape(-1).cpu().numpy() for p in cache0.planes]
+        bytes_equal = all(bool((gp == op).all()) for gp, op in zip(gpu_planes, planes))
+        cpu_baseline = {
+            "value": round(nb * Hkv * T * row_bytes / (c2 - c1) / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"decode attention for batch elements 0..{nb - 1} of layer 0 at full context ({nb * Hkv * T} of {B * Hkv * T} rows), "
+                      f"{c2 - c1:.1f} s; oracle quantize of the same rows {nb * T / (c1 - c0):.0f} tok/s",
+            "parity_max_rel_err_vs_oracle": parity, "planes_byte_identical": bytes_equal,
+        }
+
+    line = {
+        "metric": "effective packed-KV HBM GB/s, K4V2 decode step (append + attention)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": desc, "layers_resident": args.layers, "kv_bytes_per_step": kv_bytes,
+                   "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
+                   "decode_tok_s": round(B / (ms_per_step * 1e-3), 1),
+                   "quantize_tok_s_bulk_fill": round(fill_tokens / (fill_ms * 1e-3), 1)},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": _traffic_from_profile(f"decode_k4v2_{args.workload}_pmc.txt"),
+                     "kernel": "kvq decode_kernel<4,2,R> (+ merge_kernel), mean of HIP-event pairs around each launch",
+                     "kernel_ms": round(decode_ms, 5)},
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
