@@ -55,6 +55,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=40, help="resident layer caches taken in turn")
     ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run 5 plain device copies of this size (reference for hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path is a single-GPU kernel library (no collectives); run with --gpus 1", file=sys.stderr)
@@ -106,6 +108,13 @@ def main() -> int:
         if ev is not None:
             ev[1].record()
 
+    if args.copy_calibration_mib:
+        src = torch.ones(args.copy_calibration_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()

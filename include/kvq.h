@@ -15,7 +15,7 @@
  *   - Arguments are validated on the host before anything is launched; on error nothing ran.
  *   - Status codes only: the library never aborts, throws or prints.
  *   - Not checked (undefined results): non-finite inputs, |x| > 65504, a group whose
- *     range / (2^b - 1) exceeds 128 for values (the attention kernel scales softmax weights by the
+ *     range / (2^b - 1) exceeds 32 for values (the attention kernel scales softmax weights by the
  *     value scale in binary16), overlapping buffers, concurrent calls that write the same cache.
  *
  * Quantizer (per tensor X in {K, V}, bits b, group size G; one group = G consecutive head_dim

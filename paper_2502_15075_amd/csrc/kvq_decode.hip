@@ -26,7 +26,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kCodeUnit = 5.9604644775390625e-08f;  // 2^-24: value of a code's lowest mantissa bit
 constexpr float kInvCodeUnit = 16777216.0f;
-constexpr float kPShift = 8.0f;                       // softmax weights are carried times 2^8 (binary16 headroom)
+constexpr float kPShift = 10.0f;                      // softmax weights are carried times 2^10 (binary16 headroom)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;
 
@@ -77,14 +77,20 @@ template <int BK> __device__ __forceinline__ half8 unpack_k(const uint32_t* w, i
 }
 
 // ---- value codes: one lane holds, per 64-token block, 4*BV dwords (index = 4*piece + dword) --
+// Register v (0..3) of a step's operand holds slots 2v, 2v+1 and is left at bit offset v_slot_shift(v) of
+// its 16-bit lane, i.e. it reads as code * 2^shift * 2^-24; the softmax weight of those slots is
+// divided by 2^shift instead (an exponent offset, free).
+template <int BV> __device__ __forceinline__ constexpr int v_slot_shift(int v) {
+  return BV == 2 ? 2 * v : (BV == 4 ? 4 * (v & 1) : 0);
+}
 template <int BV> __device__ __forceinline__ half8 unpack_v(const uint32_t* w, int dt, int o) {
   u32x4 a;
   if (BV == 2) {
     const uint32_t ws = w[dt] >> (8 * o);
-    a = u32x4{ws & 0x00030003u, (ws >> 2) & 0x00030003u, (ws >> 4) & 0x00030003u, (ws >> 6) & 0x00030003u};
+    a = u32x4{ws & 0x00030003u, ws & 0x000C000Cu, ws & 0x00300030u, ws & 0x00C000C0u};
   } else if (BV == 4) {
-    const uint32_t ws = w[2 * dt + o];
-    a = u32x4{ws & 0x000F000Fu, (ws >> 4) & 0x000F000Fu, (ws >> 8) & 0x000F000Fu, (ws >> 12) & 0x000F000Fu};
+    const uint32_t lo = w[2 * dt + o], hi = lo >> 8;
+    a = u32x4{lo & 0x000F000Fu, lo & 0x00F000F0u, hi & 0x000F000Fu, hi & 0x00F000F0u};
   } else {
     const uint32_t w0 = w[4 * dt + 2 * o], w1 = w[4 * dt + 2 * o + 1];
     a = u32x4{w0 & 0x00FF00FFu, (w0 >> 8) & 0x00FF00FFu, w1 & 0x00FF00FFu, (w1 >> 8) & 0x00FF00FFu};
@@ -139,9 +145,19 @@ __device__ __forceinline__ float meta_zero(uint32_t m) { return (float)__builtin
 struct WaveState {
   float4v acc[8];   // out^T tile dt: rows d = 16*dt + 4*j + r, column c
   float m;          // running max of this lane's head, in log2 units
-  float l;          // this lane's share of sum_t p * 2^kPShift
-  float zacc;       // this lane's share of sum_t p * 2^kPShift * zV[t, gv]
+  float noff[4];    // kPShift - m - v_slot_shift(v): exponent offset of the slots in operand register v
+  float l[4];       // per register class v: this lane's share of sum_t p * 2^(kPShift - shift(v))
+  float zacc[4];    // same, weighted by zV[t, gv]
 };
+
+// binary16 product of a binary32 weight and the binary16 held in the low half of `meta`, written to the
+// low / high half of `dst` (one rounding).
+__device__ __forceinline__ void mix_lo(uint32_t& dst, float p, uint32_t meta) {
+  asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "=v"(dst) : "v"(p), "v"(meta));
+}
+__device__ __forceinline__ void mix_hi(uint32_t& dst, float p, uint32_t meta) {
+  asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "+v"(dst) : "v"(p), "v"(meta));
+}
 
 // One 64-token block.  MASKED: tokens at or beyond seq_len get weight 0 (garbage may sit there).
 template <int BK, int BV, int R, bool MASKED>
@@ -150,25 +166,27 @@ __device__ __forceinline__ void compute_block(const BlockRegs<BK, BV>& r, const 
 #pragma unroll
   for (int o = 0; o < 2; ++o) {                 // two steps of 32 tokens
     float s[8];                                  // slot i: token 16*(i/4) + 4*j + i%4 of this step
+    {
+      float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int x4 = 0; x4 < 2; ++x4) {
-      const int tile = 2 * o + x4;
-      float4v d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int m = 0; m < 4; ++m) d = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_k<BK>(r.kc[tile], m), qb[m], d, 0, 0, 0);
-      const uint32_t meta[4] = {r.km[tile].x, r.km[tile].y, r.km[tile].z, r.km[tile].w};
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        float part = fmaf(d[rr], meta_scale(meta[rr]), meta_zero(meta[rr]) * qsum_u);
-        s[4 * x4 + rr] = sum_over_groups<R>(part);
+      for (int m = 0; m < 4; ++m) {              // two independent accumulation chains
+        d0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_k<BK>(r.kc[2 * o], m), qb[m], d0, 0, 0, 0);
+        d1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_k<BK>(r.kc[2 * o + 1], m), qb[m], d1, 0, 0, 0);
       }
-    }
-    if (MASKED) {
+      const uint32_t meta[8] = {r.km[2 * o].x, r.km[2 * o].y, r.km[2 * o].z, r.km[2 * o].w,
+                                r.km[2 * o + 1].x, r.km[2 * o + 1].y, r.km[2 * o + 1].z, r.km[2 * o + 1].w};
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const int t = blk * 64 + 32 * o + 16 * (i >> 2) + 4 * L.j + (i & 3);
-        if (t >= seq_len) s[i] = kNegBig;
+        const float d = i < 4 ? d0[i & 3] : d1[i & 3];
+        const float part = fmaf(d, meta_scale(meta[i]), meta_zero(meta[i]) * qsum_u);
+        s[i] = sum_over_groups<R>(part);
       }
+    }
+    bool valid[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      valid[i] = !MASKED || (blk * 64 + 32 * o + 16 * (i >> 2) + 4 * L.j + (i & 3) < seq_len);
+      if (MASKED && !valid[i]) s[i] = kNegBig;
     }
     // running max: only when some lane sees a larger logit than its current max
     float lmax = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
@@ -177,31 +195,30 @@ __device__ __forceinline__ void compute_block(const BlockRegs<BK, BV>& r, const 
       lx = fmaxf(lx, __shfl_xor(lx, 16));
       lx = fmaxf(lx, __shfl_xor(lx, 32));
       const float m_new = fmaxf(st.m, lx);
-      const float f = exp2f(st.m - m_new);
+      const float f = __builtin_amdgcn_exp2f(st.m - m_new);
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt) st.acc[dt] *= f;
-      st.l *= f; st.zacc *= f; st.m = m_new;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        st.l[v] *= f; st.zacc[v] *= f;
+        st.noff[v] = kPShift - (float)v_slot_shift<BV>(v) - m_new;
+      }
+      st.m = m_new;
     }
-    const float moff = st.m - kPShift;
     const uint32_t vmeta[8] = {r.vm[2 * o].x, r.vm[2 * o].y, r.vm[2 * o].z, r.vm[2 * o].w,
                                r.vm[2 * o + 1].x, r.vm[2 * o + 1].y, r.vm[2 * o + 1].z, r.vm[2 * o + 1].w};
-    half8 pb;
+    uint32_t pw[4];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      float p = exp2f(fmaf(s[i], kappa, -moff));
-      if (MASKED) {
-        const int t = blk * 64 + 32 * o + 16 * (i >> 2) + 4 * L.j + (i & 3);
-        if (t >= seq_len) p = 0.f;
-      }
-      st.l += p;
-      float sv = meta_scale(vmeta[i]), zv = meta_zero(vmeta[i]);
-      if (MASKED) {
-        const int t = blk * 64 + 32 * o + 16 * (i >> 2) + 4 * L.j + (i & 3);
-        if (t >= seq_len) { sv = 0.f; zv = 0.f; }
-      }
-      st.zacc = fmaf(p, zv, st.zacc);
-      pb[i] = (_Float16)(p * sv);
+      const int v = i >> 1;
+      float p = __builtin_amdgcn_exp2f(fmaf(s[i], kappa, st.noff[v]));
+      uint32_t vm = vmeta[i];
+      if (MASKED && !valid[i]) { p = 0.f; vm = 0u; }
+      st.l[v] += p;
+      st.zacc[v] = fmaf(p, meta_zero(vm), st.zacc[v]);
+      if (i & 1) mix_hi(pw[v], p, vm); else mix_lo(pw[v], p, vm);
     }
+    const half8 pb = as_half8(u32x4{pw[0], pw[1], pw[2], pw[3]});
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
       st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v<BV>(r.vc, dt, o), pb, st.acc[dt], 0, 0, 0);
@@ -258,26 +275,42 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(Geom g, kvq_cache cache,
   WaveState st;
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) st.acc[dt] = float4v{0.f, 0.f, 0.f, 0.f};
-  st.m = kNegBig; st.l = 0.f; st.zacc = 0.f;
+  st.m = kNegBig;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) { st.l[v] = 0.f; st.zacc[v] = 0.f; st.noff[v] = kPShift - (float)v_slot_shift<BV>(v) - kNegBig; }
 
-  // ---- walk this wavefront's blocks
+  // ---- walk this wavefront's blocks: complete blocks in a two-deep register pipeline, then the ragged one
   const int n_blocks = (seq_len + 63) >> 6;
   const int blk_begin = split * blocks_per_split;
   const int blk_end = min(blk_begin + blocks_per_split, n_blocks);
   const int full_end = min(blk_end, seq_len >> 6);             // blocks below this index are complete
-  BlockRegs<BK, BV> cur, nxt;
-  int blk = blk_begin + wave;
-  if (blk < blk_end) load_block<BK, BV>(cur, L, blk);
-  for (; blk < blk_end; blk += 4) {
-    const bool more = blk + 4 < blk_end;
-    if (more) load_block<BK, BV>(nxt, L, blk + 4);
-    if (blk < full_end) compute_block<BK, BV, R, false>(cur, qb, qsum_u, kappa, st, L, blk, seq_len);
-    else compute_block<BK, BV, R, true>(cur, qb, qsum_u, kappa, st, L, blk, seq_len);
-    if (more) cur = nxt;
+  {
+    BlockRegs<BK, BV> ra, rb;
+    int blk = blk_begin + wave;
+    if (blk < full_end) load_block<BK, BV>(ra, L, blk);
+    while (blk < full_end) {
+      if (blk + 4 < full_end) load_block<BK, BV>(rb, L, blk + 4);
+      compute_block<BK, BV, R, false>(ra, qb, qsum_u, kappa, st, L, blk, seq_len);
+      blk += 4;
+      if (blk >= full_end) break;
+      if (blk + 4 < full_end) load_block<BK, BV>(ra, L, blk + 4);
+      compute_block<BK, BV, R, false>(rb, qb, qsum_u, kappa, st, L, blk, seq_len);
+      blk += 4;
+    }
+    // blk is now the first block of this wavefront's stride at or beyond full_end
+    if (blk < blk_end) {
+      load_block<BK, BV>(ra, L, blk);
+      compute_block<BK, BV, R, true>(ra, qb, qsum_u, kappa, st, L, blk, seq_len);
+    }
   }
 
-  // ---- wavefront totals: l and zacc over the 4 lane groups j; then out rows of this lane's value group
-  float l = st.l, z = st.zacc;
+  // ---- wavefront totals: l and zacc over register classes and the 4 lane groups j
+  float l = 0.f, z = 0.f;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const float w = (float)(1 << v_slot_shift<BV>(v));
+    l = fmaf(st.l[v], w, l); z = fmaf(st.zacc[v], w, z);
+  }
   l += __shfl_xor(l, 16); l += __shfl_xor(l, 32);
   z += __shfl_xor(z, 16); z += __shfl_xor(z, 32);
   if (act_v) {
