@@ -26,15 +26,14 @@
  *     x^_d     = code_d * scale + zero                                   (App. B "Dequantization")
  *   every operation rounded once in binary32, round-to-nearest-even; codes use the STORED scale/zero.
  *
- * Storage format of one layer (sizes from kvq_cache_bytes; T_cap = max_seq rounded up to 64):
+ * Storage format of one layer (sizes from kvq_cache_bytes; T_cap = max_seq rounded up to 32):
  *   k_codes  [B][H_kv][T_cap][D*b_K/8]      element d of a row at bits [d*b_K, (d+1)*b_K), little-endian
  *   k_meta   [B][H_kv][T_cap/16][D/G_K][16] entries {uint16 scale, uint16 zero} (binary16 patterns);
  *                                           entry (t/16, g, t%16) is token t, group g
- *   v_codes  [B][H_kv][T_cap/64][1024*b_V]  64-token blocks laid out in the order a 16x16x32 matrix
+ *   v_codes  [B][H_kv][T_cap/32][512*b_V]   32-token blocks laid out in the order a 16x16x32 matrix
  *                                           instruction consumes a "tokens x channels" operand.  With
- *                                             tt=t%64, o=tt/32, u=tt%32, x4=u/16, j=(u%16)/4, r=u%4,
- *                                             i=4*x4+r, x=i%2, v=i/2, pv=4*o+v, P=16/b_V, n=pv/P, p=pv%P,
- *                                             dt=d/16, e=dt*(b_V/2)+n
+ *                                             u=t%32, x4=u/16, j=(u%16)/4, r=u%4, i=4*x4+r, x=i%2, v=i/2,
+ *                                             q=4*(d/16)+v, P=16/b_V, e=q/P, p=q%P
  *                                           the code of (t, d) sits in the little-endian 32-bit word at
  *                                           byte (e/4)*1024 + (16*j + d%16)*16 + 4*(e%4) of the block,
  *                                           at bit 16*x + b_V*p.

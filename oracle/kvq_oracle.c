@@ -29,17 +29,16 @@
  * Storage format (the paper is silent on layout; this is the library's own format, stated
  * here in full because bytes are compared one by one):
  *
- *   capacity   T_cap = max_seq rounded up to a multiple of 64 tokens.
+ *   capacity   T_cap = max_seq rounded up to a multiple of 32 tokens.
  *   k_codes    [B][H][T_cap][D*b_K/8] bytes; element d of a token row occupies bits
  *              [d*b_K, (d+1)*b_K) of the row read as a little-endian bit string.
  *   *_meta     [B][H][T_cap/16][D/G][16] entries of 4 bytes: little-endian uint16 scale
  *              then little-endian uint16 zero (both binary16 bit patterns); entry
  *              (t/16, g, t%16) belongs to token t, group g.
- *   v_codes    [B][H][T_cap/64][1024*b_V] bytes: blocks of 64 tokens.  Inside a block the
+ *   v_codes    [B][H][T_cap/32][512*b_V] bytes: blocks of 32 tokens.  Inside a block the
  *              code of (token t, channel d) lives in a little-endian 32-bit word found as
- *                tt = t%64; o = tt/32; u = tt%32; x4 = u/16; j = (u%16)/4; r = u%4;
- *                i = 4*x4 + r; x = i%2; v = i/2; pv = 4*o + v; P = 16/b_V;
- *                n = pv/P; p = pv%P; dt = d/16; e = dt*(b_V/2) + n;
+ *                u = t%32; x4 = u/16; j = (u%16)/4; r = u%4; i = 4*x4 + r; x = i%2; v = i/2;
+ *                q = 4*(d/16) + v; P = 16/b_V; e = q/P; p = q%P;
  *                word byte offset = (e/4)*(8*D) + (16*j + d%16)*16 + 4*(e%4);
  *                bit offset inside the word = 16*x + b_V*p.
  *              (For D = 128 the stride 8*D is 1024 bytes: one 16-byte piece per wavefront
@@ -115,7 +114,7 @@ static float load_elem(const void* base, int dtype, int64_t idx) {
 
 /* ------------------------------------------------------------------ sizes */
 
-static int64_t cap_tokens(const ref_layout* L) { return ((int64_t)L->max_seq + 63) / 64 * 64; }
+static int64_t cap_tokens(const ref_layout* L) { return ((int64_t)L->max_seq + 31) / 32 * 32; }
 
 /* bytes of k_codes, k_meta, v_codes, v_meta */
 int ref_plane_bytes(const ref_layout* L, uint64_t out[4]) {
@@ -140,18 +139,15 @@ static int64_t k_bit_offset(int64_t t, int d, int D, int b) { return (t * D + d)
 
 /* V codes: byte offset of the 32-bit word and bit offset inside it, one (b,h) stream */
 static void v_position(int64_t t, int d, int D, int b, int64_t* word_byte, int* bit) {
-  int64_t blk = t / 64;
-  int tt = (int)(t % 64);
-  int o = tt / 32, u = tt % 32;
+  int64_t blk = t / 32;
+  int u = (int)(t % 32);
   int x4 = u / 16, j = (u % 16) / 4, r = u % 4;
   int i = 4 * x4 + r;
   int x = i % 2, v = i / 2;
-  int pv = 4 * o + v;
+  int q = 4 * (d / 16) + v;
   int P = 16 / b;
-  int n = pv / P, p = pv % P;
-  int dt = d / 16;
-  int e = dt * (b / 2) + n;
-  *word_byte = blk * (64 * (int64_t)D * b / 8) + (int64_t)(e / 4) * (8 * D) + (16 * j + d % 16) * 16 + 4 * (e % 4);
+  int e = q / P, p = q % P;
+  *word_byte = blk * (32 * (int64_t)D * b / 8) + (int64_t)(e / 4) * (8 * D) + (16 * j + d % 16) * 16 + 4 * (e % 4);
   *bit = 16 * x + b * p;
 }
 

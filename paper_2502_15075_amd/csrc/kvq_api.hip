@@ -21,7 +21,7 @@ kvq_status check_layout(const kvq_layout* L) {
   if (L->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;
   if (L->axis_k != KVQ_AXIS_HEAD_DIM || L->axis_v != KVQ_AXIS_HEAD_DIM) return KVQ_ERR_UNSUPPORTED;
   if ((int64_t)L->batch * L->kv_heads > 65535) return KVQ_ERR_UNSUPPORTED;
-  if (L->max_seq > (1 << 30)) return KVQ_ERR_UNSUPPORTED;
+  if (L->max_seq > (1 << 24)) return KVQ_ERR_UNSUPPORTED;   // a (b,h) stream of any plane stays below 4 GiB
   return KVQ_OK;
 }
 

@@ -10,11 +10,14 @@
 // k), which the matrix unit multiplies exactly, so "unpacking" is one AND per two codes; the
 // power-of-two position factors are divided out of the query operand once per wavefront.
 //
-// Work split: one workgroup (4 wavefronts) walks a contiguous range of 64-token blocks of one
-// (batch, kv head); each wavefront takes every 4th block and carries all R query heads of that kv
+// Work split: one workgroup (4 wavefronts) walks a contiguous range of 32-token steps of one
+// (batch, kv head); each wavefront takes every 4th step and carries all R query heads of that kv
 // head as matrix columns (column c = g*R + h: key group g, head h), so every cache byte is read
-// once.  Wavefronts merge through LDS, workgroups through a workspace of (max, sum, acc) records
-// and a small second kernel.
+// once.  Each wavefront keeps a ring of KVQ_STAGES steps in registers: after a step is computed its
+// registers are refilled with the step KVQ_STAGES ahead, so several steps of streaming loads are
+// always in flight per wavefront (the kernel is bound by bytes in flight, not by arithmetic).
+// Wavefronts merge through LDS, workgroups through a workspace of (max, sum, acc) records and a
+// small second kernel.
 #include "kvq_internal.h"
 
 namespace kvq {
@@ -76,66 +79,86 @@ template <int BK> __device__ __forceinline__ half8 unpack_k(const uint32_t* w, i
   return as_half8(a);
 }
 
-// ---- value codes: one lane holds, per 64-token block, 4*BV dwords (index = 4*piece + dword) --
-// Register v (0..3) of a step's operand holds slots 2v, 2v+1 and is left at bit offset v_slot_shift(v) of
-// its 16-bit lane, i.e. it reads as code * 2^shift * 2^-24; the softmax weight of those slots is
+// ---- value codes: one lane holds, per 32-token step, 2*BV dwords (index = 4*piece + dword) ----
+// Register v (0..3) of d-tile dt's operand holds slots 2v, 2v+1 and is left at bit offset v_slot_shift(v)
+// of its 16-bit lane, i.e. it reads as code * 2^shift * 2^-24; the softmax weight of those slots is
 // divided by 2^shift instead (an exponent offset, free).
 template <int BV> __device__ __forceinline__ constexpr int v_slot_shift(int v) {
   return BV == 2 ? 2 * v : (BV == 4 ? 4 * (v & 1) : 0);
 }
-template <int BV> __device__ __forceinline__ half8 unpack_v(const uint32_t* w, int dt, int o) {
+template <int BV> __device__ __forceinline__ half8 unpack_v(const uint32_t* w, int dt) {
   u32x4 a;
   if (BV == 2) {
-    const uint32_t ws = w[dt] >> (8 * o);
+    const uint32_t ws = w[dt >> 1] >> (8 * (dt & 1));
     a = u32x4{ws & 0x00030003u, ws & 0x000C000Cu, ws & 0x00300030u, ws & 0x00C000C0u};
   } else if (BV == 4) {
-    const uint32_t lo = w[2 * dt + o], hi = lo >> 8;
+    const uint32_t lo = w[dt], hi = lo >> 8;
     a = u32x4{lo & 0x000F000Fu, lo & 0x00F000F0u, hi & 0x000F000Fu, hi & 0x00F000F0u};
   } else {
-    const uint32_t w0 = w[4 * dt + 2 * o], w1 = w[4 * dt + 2 * o + 1];
+    const uint32_t w0 = w[2 * dt], w1 = w[2 * dt + 1];
     a = u32x4{w0 & 0x00FF00FFu, (w0 >> 8) & 0x00FF00FFu, w1 & 0x00FF00FFu, (w1 >> 8) & 0x00FF00FFu};
   }
   return as_half8(a);
 }
 
+#ifndef KVQ_STAGES
+#define KVQ_STAGES 4           // 32-token steps resident or in flight per wavefront (register ring)
+#endif
+#ifndef KVQ_WAVES_PER_SIMD
+#define KVQ_WAVES_PER_SIMD 2   // occupancy the register allocation is held to
+#endif
+
+// Everything one lane loads for one 32-token step (two 16-token tiles).
 template <int BK, int BV>
-struct BlockRegs {                 // everything one lane loads for one 64-token block
-  uint32_t kc[4][BK];              // 4 tiles of 16 tokens
-  u32x4 km[4];                     // key scale/zero of this lane's 4 tokens per tile (its own group)
-  uint32_t vc[4 * BV];
-  u32x4 vm[4];
+struct StepRegs {
+  uint32_t kc[2][BK];            // tile x4: row 16*x4 + c, this lane's 32 channels
+  uint32_t vc[2 * BV];           // value codes: piece k, dword m at [4k + m]
+  u32x4 meta;                    // 16 bytes of the step's scale/zero bytes, in plane order (lanes < 8 (ng_k + ng_v));
+                                 // redistributed through LDS when the step is computed
 };
 
 struct LaneCtx {
-  const uint8_t* kc; const uint32_t* km; const uint8_t* vc; const uint32_t* vm;   // (b,h) stream bases
+  const uint8_t* kc; const uint8_t* vc;   // (b,h) stream bases of the code planes (wave-uniform)
+  const uint8_t* meta_base;               // this lane's scale/zero plane: key plane for lanes < 8 ng_k, else value plane
+  uint32_t meta_mul, meta_off;            // bytes of that plane per 32-token step; this lane's offset inside them
+  bool meta_lane;                         // lane < 8 (ng_k + ng_v)
+  uint32_t kc_off, vc_off;                // this lane's byte offsets inside one step of the code planes
+  uint32_t km_rd, vm_rd;                  // byte offsets of this lane's key / value scale-zero entries (tile 0) in the
+                                          // wavefront's LDS copy of a step's scale/zero bytes
+  uint8_t* meta_lds;                      // that LDS copy (1 KB per wavefront)
   int lane, c, j, gk, gv, ngk, ngv;
 };
 
+// Cache bytes are read exactly once per decode step: streaming (non-temporal) loads.
+__device__ __forceinline__ u32x4 ld16(const uint8_t* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
 template <int BK, int BV>
-__device__ __forceinline__ void load_block(BlockRegs<BK, BV>& r, const LaneCtx& L, int blk) {
+__device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L, int step) {
+  // uniform 64-bit stream base + 32-bit offset (a (b,h) stream of any plane is below 4 GiB)
+  const uint32_t ko = (uint32_t)step * (512 * BK) + L.kc_off;
 #pragma unroll
-  for (int tile = 0; tile < 4; ++tile) {
-    const int64_t t16 = (int64_t)blk * 4 + tile;
-    const uint8_t* p = L.kc + ((t16 * 16 + L.c) * (16 * BK) + L.j * (4 * BK));
-    if (BK == 4) {
-      u32x4 v = *reinterpret_cast<const u32x4*>(p);
-      r.kc[tile][0] = v.x; r.kc[tile][1] = v.y; r.kc[tile][2] = v.z; r.kc[tile][3] = v.w;
-    } else if (BK == 8) {
-      u32x4 v0 = *reinterpret_cast<const u32x4*>(p), v1 = *reinterpret_cast<const u32x4*>(p + 16);
-      r.kc[tile][0] = v0.x; r.kc[tile][1] = v0.y; r.kc[tile][2] = v0.z; r.kc[tile][3] = v0.w;
-      r.kc[tile][4] = v1.x; r.kc[tile][5] = v1.y; r.kc[tile][6] = v1.z; r.kc[tile][7] = v1.w;
+  for (int x4 = 0; x4 < 2; ++x4) {
+    const uint8_t* p = L.kc + (ko + x4 * (256 * BK));
+    if (BK == 2) {
+      typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+      const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+      r.kc[x4][0] = v.x; r.kc[x4][1] = v.y;
     } else {
-      uint2 v = *reinterpret_cast<const uint2*>(p);
-      r.kc[tile][0] = v.x; r.kc[tile][1] = v.y;
-    }
-    r.km[tile] = *reinterpret_cast<const u32x4*>(L.km + ((t16 * L.ngk + L.gk) * 16 + 4 * L.j));
-    r.vm[tile] = *reinterpret_cast<const u32x4*>(L.vm + ((t16 * L.ngv + L.gv) * 16 + 4 * L.j));
-  }
-  const uint8_t* vb = L.vc + (int64_t)blk * (1024 * BV) + L.lane * 16;
 #pragma unroll
-  for (int piece = 0; piece < BV; ++piece) {
-    u32x4 v = *reinterpret_cast<const u32x4*>(vb + piece * 1024);
-    r.vc[4 * piece + 0] = v.x; r.vc[4 * piece + 1] = v.y; r.vc[4 * piece + 2] = v.z; r.vc[4 * piece + 3] = v.w;
+      for (int k = 0; k < BK / 4; ++k) {
+        const u32x4 v = ld16(p + 16 * k);
+        r.kc[x4][4 * k + 0] = v.x; r.kc[x4][4 * k + 1] = v.y; r.kc[x4][4 * k + 2] = v.z; r.kc[x4][4 * k + 3] = v.w;
+      }
+    }
+  }
+  if (L.meta_lane) r.meta = ld16(L.meta_base + ((uint32_t)step * L.meta_mul + L.meta_off));
+  const uint32_t vo = (uint32_t)step * (512 * BV) + L.vc_off;
+#pragma unroll
+  for (int k = 0; k < BV / 2; ++k) {
+    const u32x4 v = ld16(L.vc + (vo + k * 1024));
+    r.vc[4 * k + 0] = v.x; r.vc[4 * k + 1] = v.y; r.vc[4 * k + 2] = v.z; r.vc[4 * k + 3] = v.w;
   }
 }
 
@@ -159,84 +182,93 @@ __device__ __forceinline__ void mix_hi(uint32_t& dst, float p, uint32_t meta) {
   asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "+v"(dst) : "v"(p), "v"(meta));
 }
 
-// One 64-token block.  MASKED: tokens at or beyond seq_len get weight 0 (garbage may sit there).
+// One 32-token step.  MASKED: tokens at or beyond seq_len get weight 0 (garbage may sit there).
 template <int BK, int BV, int R, bool MASKED>
-__device__ __forceinline__ void compute_block(const BlockRegs<BK, BV>& r, const half8 (&qb)[4], float qsum_u, float kappa,
-                                              WaveState& st, const LaneCtx& L, int blk, int seq_len) {
+__device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const half8 (&qb)[4], float qsum_u, float kappa,
+                                             WaveState& st, const LaneCtx& L, int step, int seq_len) {
+  // scale/zero bytes: plane order -> LDS -> the entries this lane needs (tokens 4j..4j+3 of both tiles, own group)
+  if (L.meta_lane) *reinterpret_cast<u32x4*>(L.meta_lds + L.lane * 16) = r.meta;
+  uint32_t kmeta[8], vmeta[8];
 #pragma unroll
-  for (int o = 0; o < 2; ++o) {                 // two steps of 32 tokens
-    float s[8];                                  // slot i: token 16*(i/4) + 4*j + i%4 of this step
-    {
-      float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int m = 0; m < 4; ++m) {              // two independent accumulation chains
-        d0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_k<BK>(r.kc[2 * o], m), qb[m], d0, 0, 0, 0);
-        d1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_k<BK>(r.kc[2 * o + 1], m), qb[m], d1, 0, 0, 0);
-      }
-      const uint32_t meta[8] = {r.km[2 * o].x, r.km[2 * o].y, r.km[2 * o].z, r.km[2 * o].w,
-                                r.km[2 * o + 1].x, r.km[2 * o + 1].y, r.km[2 * o + 1].z, r.km[2 * o + 1].w};
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float d = i < 4 ? d0[i & 3] : d1[i & 3];
-        const float part = fmaf(d, meta_scale(meta[i]), meta_zero(meta[i]) * qsum_u);
-        s[i] = sum_over_groups<R>(part);
-      }
-    }
-    bool valid[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      valid[i] = !MASKED || (blk * 64 + 32 * o + 16 * (i >> 2) + 4 * L.j + (i & 3) < seq_len);
-      if (MASKED && !valid[i]) s[i] = kNegBig;
-    }
-    // running max: only when some lane sees a larger logit than its current max
-    float lmax = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-    float lx = lmax * kappa;
-    if (__any(lx > st.m)) {
-      lx = fmaxf(lx, __shfl_xor(lx, 16));
-      lx = fmaxf(lx, __shfl_xor(lx, 32));
-      const float m_new = fmaxf(st.m, lx);
-      const float f = __builtin_amdgcn_exp2f(st.m - m_new);
-#pragma unroll
-      for (int dt = 0; dt < 8; ++dt) st.acc[dt] *= f;
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        st.l[v] *= f; st.zacc[v] *= f;
-        st.noff[v] = kPShift - (float)v_slot_shift<BV>(v) - m_new;
-      }
-      st.m = m_new;
-    }
-    const uint32_t vmeta[8] = {r.vm[2 * o].x, r.vm[2 * o].y, r.vm[2 * o].z, r.vm[2 * o].w,
-                               r.vm[2 * o + 1].x, r.vm[2 * o + 1].y, r.vm[2 * o + 1].z, r.vm[2 * o + 1].w};
-    uint32_t pw[4];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int v = i >> 1;
-      float p = __builtin_amdgcn_exp2f(fmaf(s[i], kappa, st.noff[v]));
-      uint32_t vm = vmeta[i];
-      if (MASKED && !valid[i]) { p = 0.f; vm = 0u; }
-      st.l[v] += p;
-      st.zacc[v] = fmaf(p, meta_zero(vm), st.zacc[v]);
-      if (i & 1) mix_hi(pw[v], p, vm); else mix_lo(pw[v], p, vm);
-    }
-    const half8 pb = as_half8(u32x4{pw[0], pw[1], pw[2], pw[3]});
-#pragma unroll
-    for (int dt = 0; dt < 8; ++dt)
-      st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v<BV>(r.vc, dt, o), pb, st.acc[dt], 0, 0, 0);
+  for (int x4 = 0; x4 < 2; ++x4) {
+    const u32x4 a = *reinterpret_cast<const u32x4*>(L.meta_lds + L.km_rd + x4 * (64 * L.ngk));
+    const u32x4 b = *reinterpret_cast<const u32x4*>(L.meta_lds + L.vm_rd + x4 * (64 * L.ngv));
+    kmeta[4 * x4 + 0] = a.x; kmeta[4 * x4 + 1] = a.y; kmeta[4 * x4 + 2] = a.z; kmeta[4 * x4 + 3] = a.w;
+    vmeta[4 * x4 + 0] = b.x; vmeta[4 * x4 + 1] = b.y; vmeta[4 * x4 + 2] = b.z; vmeta[4 * x4 + 3] = b.w;
   }
+
+  // ---- scores: slot i = token 16*(i/4) + 4*j + i%4 of this step
+  float s[8];
+  {
+    float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {                // two independent accumulation chains
+      d0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_k<BK>(r.kc[0], m), qb[m], d0, 0, 0, 0);
+      d1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_k<BK>(r.kc[1], m), qb[m], d1, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float d = i < 4 ? d0[i & 3] : d1[i & 3];
+      const float part = fmaf(d, meta_scale(kmeta[i]), meta_zero(kmeta[i]) * qsum_u);
+      s[i] = sum_over_groups<R>(part);
+    }
+  }
+  bool valid[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    valid[i] = !MASKED || (step * 32 + 16 * (i >> 2) + 4 * L.j + (i & 3) < seq_len);
+    if (MASKED && !valid[i]) s[i] = kNegBig;
+  }
+  // ---- running max: only when some lane sees a larger logit than its current max
+  float lmax = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+  float lx = lmax * kappa;
+  if (__any(lx > st.m)) {
+    lx = fmaxf(lx, __shfl_xor(lx, 16));
+    lx = fmaxf(lx, __shfl_xor(lx, 32));
+    const float m_new = fmaxf(st.m, lx);
+    const float f = __builtin_amdgcn_exp2f(st.m - m_new);
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) st.acc[dt] *= f;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      st.l[v] *= f; st.zacc[v] *= f;
+      st.noff[v] = kPShift - (float)v_slot_shift<BV>(v) - m_new;
+    }
+    st.m = m_new;
+  }
+  // ---- softmax weights, their binary16 products with the value scale, and the value-zero term
+  uint32_t pw[4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int v = i >> 1;
+    float p = __builtin_amdgcn_exp2f(fmaf(s[i], kappa, st.noff[v]));
+    uint32_t vm = vmeta[i];
+    if (MASKED && !valid[i]) { p = 0.f; vm = 0u; }
+    st.l[v] += p;
+    st.zacc[v] = fmaf(p, meta_zero(vm), st.zacc[v]);
+    if (i & 1) mix_hi(pw[v], p, vm); else mix_lo(pw[v], p, vm);
+  }
+  const half8 pb = as_half8(u32x4{pw[0], pw[1], pw[2], pw[3]});
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt)
+    st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v<BV>(r.vc, dt), pb, st.acc[dt], 0, 0, 0);
 }
 
 // Record layout in the workspace: [b][hq][split] x (kHeadDim + 4) floats = acc[128], m, l, 0, 0.
 constexpr int kRec = kHeadDim + 4;
 
 template <int BK, int BV, int R>
-__global__ __launch_bounds__(256, 2) void decode_kernel(Geom g, kvq_cache cache, const uint16_t* __restrict__ q, int q_bf16,
-                                                        int32_t q_heads, int32_t seq_len, float softmax_scale,
-                                                        float* __restrict__ ws, void* __restrict__ out, int out_dtype,
-                                                        int32_t n_splits, int32_t blocks_per_split) {
+__global__ __launch_bounds__(256, KVQ_WAVES_PER_SIMD) void decode_kernel(
+    Geom g, kvq_cache cache, const uint16_t* __restrict__ q, int q_bf16, int32_t q_heads, int32_t seq_len,
+    float softmax_scale, float* __restrict__ ws, void* __restrict__ out, int out_dtype, int32_t n_splits,
+    int32_t steps_per_split) {
   __shared__ float sm_o[4][R][kHeadDim];
   __shared__ float sm_m[4][R], sm_l[4][R];
+  __shared__ __attribute__((aligned(16))) uint16_t sm_q[R][kHeadDim];
+  __shared__ __attribute__((aligned(16))) uint8_t sm_meta[4][1024];
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int split = blockIdx.x, bh = blockIdx.y;
   const int b = bh / g.kv_heads, hk = bh % g.kv_heads;
 
@@ -247,28 +279,75 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(Geom g, kvq_cache cache,
   const bool act_k = grp < g.ng_k, act_v = grp < g.ng_v;
   L.gk = act_k ? grp : 0; L.gv = act_v ? grp : 0;
   L.kc = (const uint8_t*)cache.k_codes + (int64_t)bh * g.kc_stream;
-  L.km = (const uint32_t*)((const uint8_t*)cache.k_meta + (int64_t)bh * g.km_stream);
   L.vc = (const uint8_t*)cache.v_codes + (int64_t)bh * g.vc_stream;
-  L.vm = (const uint32_t*)((const uint8_t*)cache.v_meta + (int64_t)bh * g.vm_stream);
+  L.kc_off = L.c * (16 * BK) + L.j * (4 * BK);
+  L.vc_off = lane * 16;
+  {
+    const int nk = 8 * g.ng_k, nv = 8 * g.ng_v;
+    const bool is_k = lane < nk;
+    L.meta_lane = lane < nk + nv;
+    L.meta_base = is_k ? (const uint8_t*)cache.k_meta + (int64_t)bh * g.km_stream
+                       : (const uint8_t*)cache.v_meta + (int64_t)bh * g.vm_stream;
+    L.meta_mul = 128 * (is_k ? g.ng_k : g.ng_v);
+    L.meta_off = 16 * (is_k ? lane : lane - nk);
+    L.km_rd = (L.gk * 16 + 4 * L.j) * 4;                       // key bytes come first in the LDS copy
+    L.vm_rd = 128 * g.ng_k + (L.gv * 16 + 4 * L.j) * 4;
+    L.meta_lds = &sm_meta[wave][0];
+  }
 
-  // ---- query operand: column c carries head h restricted to key group gk (zero elsewhere)
-  const uint16_t* qrow = q + ((int64_t)b * q_heads + hk * R + h) * kHeadDim;
-  auto qval = [&](int d) -> float {
-    const uint16_t bits = qrow[d];
+  // ---- this wavefront's steps: step_begin + wave, +4, ...; start filling the ring right away
+  const int n_steps = (seq_len + 31) >> 5;
+  const int step_begin = split * steps_per_split;
+  const int step_end = min(step_begin + steps_per_split, n_steps);
+  const int first = step_begin + wave;
+  auto step_of = [&](int i) { return first + 4 * i; };
+  const int n_my = first < step_end ? (step_end - first + 3) >> 2 : 0;
+  const bool ragged = (seq_len & 31) != 0;
+  const bool own_tail = ragged && n_my > 0 && step_of(n_my - 1) == n_steps - 1;
+  const int n_full = own_tail ? n_my - 1 : n_my;   // complete steps of this wavefront
+  // register ring of KVQ_STAGES steps: start the first loads before anything else
+  StepRegs<BK, BV> buf[KVQ_STAGES];
+#pragma unroll
+  for (int k = 0; k < KVQ_STAGES; ++k)
+    if (k < n_full) load_step<BK, BV>(buf[k], L, step_of(k));
+
+  // ---- query rows of this kv head -> LDS (one coalesced 16-byte load per thread), then per-lane operands
+  if (tid < R * 16)
+    reinterpret_cast<u32x4*>(&sm_q[0][0])[tid] =
+        *reinterpret_cast<const u32x4*>(q + ((int64_t)b * q_heads + hk * R) * kHeadDim + tid * 8);
+  __syncthreads();
+  auto widen = [&](uint16_t bits) -> float {
     return q_bf16 ? __uint_as_float((uint32_t)bits << 16) : (float)__builtin_bit_cast(_Float16, bits);
   };
+  // column c carries head h restricted to key group gk (zero elsewhere); this lane's 32 channels are 32j..32j+31
   half8 qb[4];
-  const bool mine = act_k && ((32 * L.j) / g.g_k == L.gk);   // this lane's 32 channels lie in one group
-#pragma unroll
-  for (int m = 0; m < 4; ++m)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float v = mine ? qval(32 * L.j + k_slot_elem<BK>(m, i)) / k_slot_scale<BK>(i) : 0.f;
-      qb[m][i] = (_Float16)v;
-    }
   float qsum = 0.f;
-  if (act_k)
-    for (int d = L.gk * g.g_k; d < (L.gk + 1) * g.g_k; ++d) qsum += qval(d);
+  {
+    const bool mine = act_k && ((32 * L.j) / g.g_k == L.gk);   // the 32 channels lie in one group
+    uint16_t mych[32];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const u32x4 v = reinterpret_cast<const u32x4*>(&sm_q[h][32 * L.j])[k];
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) mych[8 * k + e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+    }
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        qb[m][i] = (_Float16)(mine ? widen(mych[k_slot_elem<BK>(m, i)]) / k_slot_scale<BK>(i) : 0.f);
+    if (act_k) {
+#pragma unroll
+      for (int c8 = 0; c8 < 16; ++c8) {
+        if ((8 * c8) / g.g_k != L.gk) continue;
+        const u32x4 v = reinterpret_cast<const u32x4*>(&sm_q[h][0])[c8];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qsum += widen((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+      }
+    }
+  }
   const float qsum_u = qsum * kCodeUnit;
   const float kappa = softmax_scale * kLog2e * kInvCodeUnit;
 
@@ -277,31 +356,24 @@ __global__ __launch_bounds__(256, 2) void decode_kernel(Geom g, kvq_cache cache,
   for (int dt = 0; dt < 8; ++dt) st.acc[dt] = float4v{0.f, 0.f, 0.f, 0.f};
   st.m = kNegBig;
 #pragma unroll
-  for (int v = 0; v < 4; ++v) { st.l[v] = 0.f; st.zacc[v] = 0.f; st.noff[v] = kPShift - (float)v_slot_shift<BV>(v) - kNegBig; }
+  for (int v = 0; v < 4; ++v) { st.l[v] = 0.f; st.zacc[v] = 0.f; st.noff[v] = 0.f; }
 
-  // ---- walk this wavefront's blocks: complete blocks in a two-deep register pipeline, then the ragged one
-  const int n_blocks = (seq_len + 63) >> 6;
-  const int blk_begin = split * blocks_per_split;
-  const int blk_end = min(blk_begin + blocks_per_split, n_blocks);
-  const int full_end = min(blk_end, seq_len >> 6);             // blocks below this index are complete
-  {
-    BlockRegs<BK, BV> ra, rb;
-    int blk = blk_begin + wave;
-    if (blk < full_end) load_block<BK, BV>(ra, L, blk);
-    while (blk < full_end) {
-      if (blk + 4 < full_end) load_block<BK, BV>(rb, L, blk + 4);
-      compute_block<BK, BV, R, false>(ra, qb, qsum_u, kappa, st, L, blk, seq_len);
-      blk += 4;
-      if (blk >= full_end) break;
-      if (blk + 4 < full_end) load_block<BK, BV>(ra, L, blk + 4);
-      compute_block<BK, BV, R, false>(rb, qb, qsum_u, kappa, st, L, blk, seq_len);
-      blk += 4;
+  // ---- main loop, unrolled over the ring: compute a step, then refill its registers with the step KVQ_STAGES
+  // ahead, so that KVQ_STAGES-1 steps of loads are always in flight behind the one being computed.
+  int it = 0;
+  for (; it + KVQ_STAGES <= n_full; it += KVQ_STAGES) {
+#pragma unroll
+    for (int k = 0; k < KVQ_STAGES; ++k) {
+      compute_step<BK, BV, R, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(it + k), seq_len);
+      if (it + k + KVQ_STAGES < n_full) load_step<BK, BV>(buf[k], L, step_of(it + k + KVQ_STAGES));
     }
-    // blk is now the first block of this wavefront's stride at or beyond full_end
-    if (blk < blk_end) {
-      load_block<BK, BV>(ra, L, blk);
-      compute_block<BK, BV, R, true>(ra, qb, qsum_u, kappa, st, L, blk, seq_len);
-    }
+  }
+#pragma unroll
+  for (int k = 0; k < KVQ_STAGES - 1; ++k)         // the last few complete steps are already in the ring
+    if (it + k < n_full) compute_step<BK, BV, R, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(it + k), seq_len);
+  if (own_tail) {                                 // ragged last step of the sequence: masked
+    load_step<BK, BV>(buf[0], L, n_steps - 1);
+    compute_step<BK, BV, R, true>(buf[0], qb, qsum_u, kappa, st, L, n_steps - 1, seq_len);
   }
 
   // ---- wavefront totals: l and zacc over register classes and the 4 lane groups j
@@ -384,7 +456,7 @@ hipError_t launch_one(const Geom& g, const kvq_cache& c, const void* q, int q_dt
   dim3 grid(plan.n_splits, g.batch * g.kv_heads);
   hipLaunchKernelGGL((decode_kernel<BK, BV, R>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)q,
                      q_dtype == KVQ_BF16 ? 1 : 0, q_heads, seq_len, softmax_scale, ws, out, out_dtype, plan.n_splits,
-                     plan.blocks_per_split);
+                     plan.steps_per_split);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || plan.n_splits == 1) return e;
   hipLaunchKernelGGL(merge_kernel, dim3(g.batch * q_heads), dim3(128), 0, stream, ws, out, out_dtype, plan.n_splits);
@@ -414,17 +486,18 @@ bool decode_supported(const Geom& g, int32_t q_heads) {
 }
 
 DecodePlan plan_decode(const Geom& g, int32_t seq_len) {
-  const int n_blocks = (seq_len + 63) / 64;
+  const int n_steps = (seq_len + 31) / 32;
   const int streams = g.batch * g.kv_heads;
-  const int target_wgs = 256 * 2;                              // CUs x resident workgroups per CU
+  const int target_wgs = 256 * KVQ_WAVES_PER_SIMD;             // CUs x resident workgroups (4 wavefronts each) per CU:
+                                                               // one full round of workgroups, no tail
   int splits = (target_wgs + streams - 1) / streams;
-  const int max_splits = (n_blocks + 3) / 4;                   // at least one block per wavefront
+  const int max_splits = (n_steps + 7) / 8;                    // at least two steps per wavefront
   if (splits > max_splits) splits = max_splits;
   if (splits < 1) splits = 1;
-  int bps = (n_blocks + splits - 1) / splits;
-  bps = (bps + 3) / 4 * 4;
-  splits = (n_blocks + bps - 1) / bps;
-  return DecodePlan{splits, bps};
+  int sps = (n_steps + splits - 1) / splits;
+  sps = (sps + 3) / 4 * 4;
+  splits = (n_steps + sps - 1) / sps;
+  return DecodePlan{splits, sps};
 }
 
 hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void* q, int q_dtype, int32_t q_heads,

@@ -8,7 +8,7 @@
 namespace kvq {
 
 constexpr int kHeadDim = 128;     // the only head_dim the kernels are written for
-constexpr int kBlockTokens = 64;  // value codes are stored in blocks of this many tokens
+constexpr int kBlockTokens = 32;  // value codes are stored in blocks of this many tokens
 
 // Geometry derived once on the host and passed by value to every kernel.
 struct Geom {
@@ -38,8 +38,8 @@ inline Geom make_geom(const kvq_layout& L) {
 
 // Number of sequence splits the decode kernel uses for this problem (host-side plan).
 struct DecodePlan {
-  int32_t n_splits;          // workgroups per (b, h_kv)
-  int32_t blocks_per_split;  // 64-token blocks each workgroup walks
+  int32_t n_splits;         // workgroups per (b, h_kv)
+  int32_t steps_per_split;  // 32-token steps each workgroup walks (a multiple of 4: one per wavefront)
 };
 DecodePlan plan_decode(const Geom& g, int32_t seq_len);
 
@@ -61,17 +61,15 @@ bool decode_supported(const Geom& g, int32_t q_heads);
 // dword index of meta entry (token t, group g) inside one (b,h) stream
 __host__ __device__ inline int64_t meta_index(int64_t t, int g, int ng) { return ((t >> 4) * ng + g) * 16 + (t & 15); }
 
-// Position of value code (tt = token inside its 64-token block, d) for bit width b:
+// Position of value code (u = token inside its 32-token block, d) for bit width b:
 // dword index inside the block and bit offset inside the dword.
-__host__ __device__ inline void v_field(int tt, int d, int b, int* dword, int* bit) {
-  int o = tt >> 5, u = tt & 31;
+__host__ __device__ inline void v_field(int u, int d, int b, int* dword, int* bit) {
   int x4 = u >> 4, j = (u >> 2) & 3, r = u & 3;
   int i = 4 * x4 + r;
   int x = i & 1, v = i >> 1;
-  int pv = 4 * o + v;
+  int q = 4 * (d >> 4) + v;
   int P = 16 / b;
-  int n = pv / P, p = pv % P;
-  int e = (d >> 4) * (b >> 1) + n;
+  int e = q / P, p = q % P;
   *dword = (e >> 2) * 256 + (16 * j + (d & 15)) * 4 + (e & 3);
   *bit = 16 * x + b * p;
 }

@@ -62,19 +62,20 @@ __device__ __forceinline__ void quantize8(const float x[8], int bits, int lanes_
 }
 
 constexpr int kLdsPitch = kHeadDim + 2;  // uint16 elements per staged value row (odd dword pitch)
+constexpr int kSpan = 64;                // tokens one workgroup covers (two 32-token value blocks)
 
-// One workgroup = one 64-token block of one (b,h) stream, restricted to the new tokens in it.
+// One workgroup = one 64-token span of one (b,h) stream, restricted to the new tokens in it.
 __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_new,
                                                               const uint16_t* __restrict__ v_new, int in_bf16,
                                                               int64_t sb, int64_t sh, int64_t st, int32_t pos,
                                                               int32_t n_new) {
-  __shared__ uint16_t vstage[kBlockTokens * kLdsPitch];
+  __shared__ uint16_t vstage[kSpan * kLdsPitch];
   const int tid = threadIdx.x;
   const int bh = blockIdx.y;
   const int b = bh / g.kv_heads, h = bh % g.kv_heads;
-  const int blk = pos / kBlockTokens + blockIdx.x;
-  const int lo = max(pos, blk * kBlockTokens) - blk * kBlockTokens;
-  const int hi = min(pos + n_new, (blk + 1) * kBlockTokens) - blk * kBlockTokens;
+  const int blk = pos / kSpan + blockIdx.x;
+  const int lo = max(pos, blk * kSpan) - blk * kSpan;
+  const int hi = min(pos + n_new, (blk + 1) * kSpan) - blk * kSpan;
   const int lane16 = tid & 15;
   const int d0 = lane16 * 8;
 
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
   uint32_t* vc = (uint32_t*)((uint8_t*)c.v_codes + (int64_t)bh * g.vc_stream) + (int64_t)blk * (256 * g.bits_v);
 
   for (int row = lo + (tid >> 4); row < hi; row += 16) {
-    const int64_t t = (int64_t)blk * kBlockTokens + row;
+    const int64_t t = (int64_t)blk * kSpan + row;
     const int64_t src = (int64_t)b * sb + (int64_t)h * sh + (t - pos) * st + d0;
     // ---- keys: row-major codes
     {
@@ -143,28 +144,27 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
   }
   __syncthreads();
 
-  // ---- values: assemble the block's dwords in storage order; keep the fields of other tokens
+  // ---- values: assemble the span's dwords (two 32-token blocks) in storage order; keep the fields of other tokens
   const int bv = g.bits_v;
   const int P = 16 / bv;
   const uint32_t fmask = bv == 16 ? 0xFFFFu : ((1u << bv) - 1u);
-  const int n_dwords = 256 * bv;
-  for (int w = tid; w < n_dwords; w += 256) {
-    const int q = w >> 8, rem = w & 255;
+  const int blk_dwords = 128 * bv;
+  for (int w = tid; w < 2 * blk_dwords; w += 256) {
+    const int sub = w / blk_dwords, wi = w % blk_dwords;
+    const int piece = wi >> 8, rem = wi & 255;
     const int L = rem >> 2, m = rem & 3;
-    const int e = 4 * q + m;
+    const int e = 4 * piece + m;
     const int j = L >> 4, dl = L & 15;
-    const int dt = e / (bv >> 1), n = e % (bv >> 1);
-    const int d = dt * 16 + dl;
     uint32_t bits = 0, mask = 0;
     for (int x = 0; x < 2; ++x)
       for (int p = 0; p < P; ++p) {
-        const int pv = n * P + p;
-        const int o = pv >> 2, v = pv & 3;
+        const int q = e * P + p;
+        const int dt = q >> 2, v = q & 3;
         const int i = 2 * v + x;
-        const int tt = 32 * o + 16 * (i >> 2) + 4 * j + (i & 3);
+        const int tt = 32 * sub + 16 * (i >> 2) + 4 * j + (i & 3);
         if (tt >= lo && tt < hi) {
           const int sh_ = 16 * x + bv * p;
-          bits |= ((uint32_t)vstage[tt * kLdsPitch + d] & fmask) << sh_;
+          bits |= ((uint32_t)vstage[tt * kLdsPitch + dt * 16 + dl] & fmask) << sh_;
           mask |= fmask << sh_;
         }
       }
@@ -213,8 +213,8 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Geom g, kvq_cache c, in
         code = (wd >> (bit & 31)) & (b == 16 ? 0xFFFFu : ((1u << b) - 1u));
       } else {
         int dw, bit;
-        v_field((int)(t & 63), d, b, &dw, &bit);
-        const uint32_t wd = reinterpret_cast<const uint32_t*>(cs + (t >> 6) * (int64_t)(1024 * b))[dw];
+        v_field((int)(t & 31), d, b, &dw, &bit);
+        const uint32_t wd = reinterpret_cast<const uint32_t*>(cs + (t >> 5) * (int64_t)(512 * b))[dw];
         code = (wd >> bit) & (b == 16 ? 0xFFFFu : ((1u << b) - 1u));
       }
       val[e] = b == 16 ? widen16((uint16_t)code, raw_bf16) : (float)code * s + z;
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Geom g, kvq_cache c, in
 hipError_t launch_quantize_append(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype,
                                   int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
   if (n_new == 0) return hipSuccess;
-  const int first = pos / kBlockTokens, last = (pos + n_new - 1) / kBlockTokens;
+  const int first = pos / kSpan, last = (pos + n_new - 1) / kSpan;
   dim3 grid(last - first + 1, g.batch * g.kv_heads);
   hipLaunchKernelGGL(quantize_append_kernel, grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
                      (const uint16_t*)v_new, in_dtype == KVQ_BF16 ? 1 : 0, sb, sh, st, pos, n_new);

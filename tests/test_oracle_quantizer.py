@@ -219,20 +219,20 @@ def _pack_fields_le(fields, b):
 
 def _expected_planes(codes, S, Z, b, G):
     """Build one (b,h) stream of the three layouts with array reshapes/transposes instead of
-    per-element index arithmetic.  codes: [T, D] with T % 64 == 0, S/Z: uint16 [T, D/G]."""
+    per-element index arithmetic.  codes: [T, D] with T % 32 == 0, S/Z: uint16 [T, D/G]."""
     T, D = codes.shape
     k_plane = _pack_fields_le(codes.ravel(), b)                       # token rows, channels in order
     m = np.stack([S, Z], axis=-1).reshape(T // 16, 16, D // G, 2)       # [blk16, t%16, g, 2]
     meta = np.ascontiguousarray(m.transpose(0, 2, 1, 3)).view(np.uint8).ravel()
     P = 16 // b
-    # token t = blk*64 + o*32 + x4*16 + j*4 + rh*2 + x ; channel d = dt*16 + dl
-    A = codes.reshape(T // 64, 2, 2, 4, 2, 2, D // 16, 16)
-    #        axes:       blk  o  x4 j  rh x  dt      dl
-    W = A.transpose(0, 6, 1, 2, 4, 3, 7, 5)                             # blk dt o x4 rh j dl x
-    W = W.reshape(T // 64, D // 16, b // 2, P, 4, 16, 2)                # blk dt n p j dl x   ((o,x4,rh) -> (n,p))
-    W = W.transpose(0, 1, 2, 4, 5, 6, 3)                                # blk dt n j dl x p
-    W = W.reshape(T // 64, (D // 16) * (b // 2) // 4, 4, 4, 16, 2, P)   # blk q m j dl x p   ((dt,n) -> (q,m))
-    W = W.transpose(0, 1, 3, 4, 2, 5, 6)                                # blk q j dl m x p
+    # token t = blk*32 + x4*16 + j*4 + rh*2 + x ; channel d = dt*16 + dl
+    A = codes.reshape(T // 32, 2, 4, 2, 2, D // 16, 16)
+    #        axes:       blk   x4 j  rh x  dt      dl
+    W = A.transpose(0, 5, 1, 3, 2, 6, 4)                                # blk dt x4 rh j dl x
+    W = W.reshape(T // 32, (D // 16) * 4 // P, P, 4, 16, 2)             # blk e p j dl x      ((dt,x4,rh) -> (e,p))
+    W = W.transpose(0, 1, 3, 4, 5, 2)                                   # blk e j dl x p
+    W = W.reshape(T // 32, (D // 16) * 4 // P // 4, 4, 4, 16, 2, P)     # blk piece m j dl x p
+    W = W.transpose(0, 1, 3, 4, 2, 5, 6)                                # blk piece j dl m x p
     v_plane = _pack_fields_le(W.ravel(), b)
     return k_plane, meta, v_plane
 
@@ -293,7 +293,7 @@ def test_append_touches_only_its_own_tokens_and_chunks_compose(oracle):
         oracle.quantize_append(L, parts, np.ascontiguousarray(x[:, :, a:b]), np.ascontiguousarray(y[:, :, a:b]), a)
     for p, w in zip(parts, whole):
         assert np.array_equal(p, w)
-    # capacity is 192 tokens; the tail [150,192) and nothing else keeps the fill pattern
+    # capacity is 160 tokens; the tail [150,160) and nothing else keeps the fill pattern
     fresh = oracle.new_planes(L, fill=0xA5)
     kd_f, vd_f = oracle.dequantize(L, fresh, 0, T)
     oracle.quantize_append(L, fresh, np.ascontiguousarray(x[:, :, 40:41]), np.ascontiguousarray(y[:, :, 40:41]), 40)
@@ -318,4 +318,4 @@ def test_code_bytes_k4v2_are_three_quarters_of_k4v4(oracle):
     c = oracle.plane_bytes(oracle.Layout(1, 8, 1024, 128, 4, 2, 32, 32))
     assert sum(c) == 8 * 1024 * 128
     d = oracle.plane_bytes(oracle.Layout(1, 1, 65, 128, 8, 8, 64, 64))
-    assert sum(d) == 128 * 272                                     # capacity rounds 65 tokens up to 128
+    assert sum(d) == 96 * 272                                      # capacity rounds 65 tokens up to 96
