@@ -96,15 +96,15 @@ def main() -> int:
         if li == 0:
             sample = (K[:4].cpu(), V[:4].cpu(), q[:4].cpu())
         del K, V
-    ws = torch.empty(kvq.decode_workspace_bytes(L, Hq, T), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, Hq, T)), dtype=torch.uint8, device=dev)
     out = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
 
     def step(i, ev=None):
+        # one launch: the new token's K/V rows are quantized into position T-1 by the decode kernel itself
         cache, k1, v1, q = layers[i % len(layers)]
-        kvq.quantize_append(L, cache, k1, v1, T - 1)
         if ev is not None:
             ev[0].record()
-        kvq.decode_attention(L, cache, q, T, scale, out, ws)
+        kvq.decode_step(L, cache, k1, v1, T - 1, q, scale, out, ws)
         if ev is not None:
             ev[1].record()
 
@@ -159,7 +159,7 @@ def main() -> int:
         }
 
     line = {
-        "metric": "effective packed-KV HBM GB/s, K4V2 decode step (append + attention)",
+        "metric": "effective packed-KV HBM GB/s, K4V2 decode step (quantize-append of the new token + attention)",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
@@ -170,7 +170,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": _traffic_from_profile(f"decode_k4v2_{args.workload}_pmc.txt"),
-                     "kernel": "kvq decode_kernel<4,2,R> (+ merge_kernel), mean of HIP-event pairs around each launch",
+                     "kernel": "kvq decode_kernel<4,2,R,NW> (fused step; + merge_kernel when the sequence is split), mean of HIP-event pairs around each launch",
                      "kernel_ms": round(decode_ms, 5)},
         "cpu_baseline": cpu_baseline,
     }

@@ -88,7 +88,8 @@ typedef struct {
 kvq_status kvq_cache_bytes(const kvq_layout* layout, size_t bytes_out[4]);
 
 /* Host only.  Bytes of scratch kvq_decode_attention needs for (q_heads, seq_len): the partial
- * (max, sum, accumulator) records of its split-sequence pass. */
+ * (max, sum, accumulator) records of its split-sequence pass.  May be 0 (enough (b, h_kv) streams to fill
+ * the chip without splitting the sequence); then the workspace pointer may be NULL. */
 kvq_status kvq_decode_workspace_bytes(const kvq_layout* layout, int32_t q_heads, int32_t seq_len,
                                       size_t* bytes_out);
 
@@ -112,6 +113,16 @@ kvq_status kvq_decode_attention(const kvq_layout* layout, const kvq_cache* cache
                                 kvq_dtype q_dtype, int32_t q_heads, int32_t seq_len, float softmax_scale,
                                 void* out, kvq_dtype out_dtype, void* workspace, size_t workspace_bytes,
                                 void* stream);
+
+/* One autoregressive decode step in a single launch (Sec. 4: the cache grows by one quantized token per generated
+ * token): quantize the new token's K/V row of every (b, h_kv) into position pos -- same bytes as
+ * kvq_quantize_append with n_new = 1 -- then attend over tokens [0, pos].
+ *   k_new, v_new   [B][H_kv][D] of in_dtype (KVQ_F16 / KVQ_BF16), element strides given, D contiguous.
+ *   everything else as in kvq_decode_attention with seq_len = pos + 1. */
+kvq_status kvq_decode_step(const kvq_layout* layout, const kvq_cache* cache, const void* k_new, const void* v_new,
+                           kvq_dtype in_dtype, int64_t stride_b, int64_t stride_h, int32_t pos, const void* q,
+                           kvq_dtype q_dtype, int32_t q_heads, float softmax_scale, void* out, kvq_dtype out_dtype,
+                           void* workspace, size_t workspace_bytes, void* stream);
 
 /* Reconstruct tokens [t0, t1) as x^ = code * scale + zero (App. B "Dequantization"):
  *   k_out, v_out  [B][H_kv][t1-t0][D] contiguous of out_dtype; either may be NULL to skip it.

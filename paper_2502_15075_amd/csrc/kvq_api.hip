@@ -59,7 +59,7 @@ kvq_status kvq_decode_workspace_bytes(const kvq_layout* layout, int32_t q_heads,
   const kvq::Geom g = kvq::make_geom(*layout);
   const kvq::DecodePlan plan = kvq::plan_decode(g, seq_len);
   // one record of (head_dim + 2) floats per (batch, query head, split), padded to 16 bytes
-  *bytes_out = (size_t)layout->batch * q_heads * plan.n_splits * (kvq::kHeadDim + 4) * sizeof(float);
+  *bytes_out = plan.n_splits == 1 ? 0 : (size_t)layout->batch * q_heads * plan.n_splits * (kvq::kHeadDim + 4) * sizeof(float);
   return KVQ_OK;
 }
 
@@ -85,9 +85,10 @@ kvq_status kvq_quantize_append(const kvq_layout* layout, const kvq_cache* cache,
   return e == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
 }
 
-kvq_status kvq_decode_attention(const kvq_layout* layout, const kvq_cache* cache, const void* q, kvq_dtype q_dtype,
-                                int32_t q_heads, int32_t seq_len, float softmax_scale, void* out, kvq_dtype out_dtype,
-                                void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+kvq_status decode_common(const kvq_layout* layout, const kvq_cache* cache, const void* q, kvq_dtype q_dtype, int32_t q_heads,
+                         int32_t seq_len, float softmax_scale, void* out, kvq_dtype out_dtype, void* workspace,
+                         size_t workspace_bytes, const kvq::AppendOne* app, void* stream) {
   kvq_status st = check_layout(layout);
   if (st != KVQ_OK) return st;
   st = check_cache(layout, cache);
@@ -103,11 +104,33 @@ kvq_status kvq_decode_attention(const kvq_layout* layout, const kvq_cache* cache
   size_t need = 0;
   st = kvq_decode_workspace_bytes(layout, q_heads, seq_len, &need);
   if (st != KVQ_OK) return st;
-  if (!workspace || workspace_bytes < need || !aligned16(workspace)) return KVQ_ERR_WORKSPACE;
+  if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return KVQ_ERR_WORKSPACE;
   const kvq::DecodePlan plan = kvq::plan_decode(g, seq_len);
   hipError_t e = kvq::launch_decode_attention(g, *cache, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype,
-                                              (float*)workspace, plan, (hipStream_t)stream);
+                                              (float*)workspace, plan, app, (hipStream_t)stream);
   return e == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
+}
+}  // namespace
+
+kvq_status kvq_decode_attention(const kvq_layout* layout, const kvq_cache* cache, const void* q, kvq_dtype q_dtype,
+                                int32_t q_heads, int32_t seq_len, float softmax_scale, void* out, kvq_dtype out_dtype,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_common(layout, cache, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype, workspace,
+                       workspace_bytes, nullptr, stream);
+}
+
+kvq_status kvq_decode_step(const kvq_layout* layout, const kvq_cache* cache, const void* k_new, const void* v_new,
+                           kvq_dtype in_dtype, int64_t stride_b, int64_t stride_h, int32_t pos, const void* q,
+                           kvq_dtype q_dtype, int32_t q_heads, float softmax_scale, void* out, kvq_dtype out_dtype,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  if (!layout) return KVQ_ERR_INVALID_ARG;
+  if (pos < 0) return KVQ_ERR_INVALID_ARG;
+  if (pos >= layout->max_seq) return KVQ_ERR_CAPACITY;
+  if (!k_new || !v_new || (in_dtype != KVQ_F16 && in_dtype != KVQ_BF16)) return KVQ_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || stride_b % 8 || stride_h % 8) return KVQ_ERR_INVALID_ARG;
+  const kvq::AppendOne app{k_new, v_new, (int)in_dtype, stride_b, stride_h};
+  return decode_common(layout, cache, q, q_dtype, q_heads, pos + 1, softmax_scale, out, out_dtype, workspace,
+                       workspace_bytes, &app, stream);
 }
 
 kvq_status kvq_dequantize(const kvq_layout* layout, const kvq_cache* cache, int32_t t0, int32_t t1, void* k_out,

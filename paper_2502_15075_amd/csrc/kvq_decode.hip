@@ -19,6 +19,7 @@
 // Wavefronts merge through LDS, workgroups through a workspace of (max, sum, acc) records and a
 // small second kernel.
 #include "kvq_internal.h"
+#include "kvq_quantizer.h"
 
 namespace kvq {
 namespace {
@@ -257,15 +258,96 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const ha
 // Record layout in the workspace: [b][hq][split] x (kHeadDim + 4) floats = acc[128], m, l, 0, 0.
 constexpr int kRec = kHeadDim + 4;
 
-template <int BK, int BV, int R>
-__global__ __launch_bounds__(256, KVQ_WAVES_PER_SIMD) void decode_kernel(
-    Geom g, kvq_cache cache, const uint16_t* __restrict__ q, int q_bf16, int32_t q_heads, int32_t seq_len,
-    float softmax_scale, float* __restrict__ ws, void* __restrict__ out, int out_dtype, int32_t n_splits,
-    int32_t steps_per_split) {
-  __shared__ float sm_o[4][R][kHeadDim];
-  __shared__ float sm_m[4][R], sm_l[4][R];
+struct DecodeArgs {
+  Geom g;
+  kvq_cache cache;
+  const uint16_t* q; int q_bf16; int32_t q_heads;
+  int32_t seq_len; float softmax_scale;
+  float* ws; void* out; int out_dtype;
+  int32_t n_splits, steps_per_split;
+  // fused decode step: the token at position seq_len-1 is quantized from k_new/v_new ([B][H_kv][D], element strides
+  // nsb, nsh) by the workgroup that owns the last step, before it is read.  k_new == nullptr: plain attention.
+  const uint16_t* k_new; const uint16_t* v_new; int in_bf16; int64_t nsb, nsh;
+};
+
+// Quantize the one new token of this (b,h) and store it at position pos = seq_len-1: the first 16 lanes take the key
+// row, the next 16 the value row (8 channels per lane).  Same arithmetic and bytes as the bulk quantize-append kernel.
+// Value codes go to `vstage` (128 bytes of LDS); after a barrier append_one_values() puts them into the block.
+template <int BK, int BV>
+__device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, int hk, int tid, uint8_t* vstage) {
+  const Geom& g = a.g;
+  if (tid >= 32) return;
+  const bool is_v = tid >= 16;
+  const int lane16 = tid & 15, d0 = lane16 * 8;
+  const int64_t t = a.seq_len - 1;
+  const uint16_t* src = (is_v ? a.v_new : a.k_new) + (int64_t)b * a.nsb + (int64_t)hk * a.nsh + d0;
+  const u32x4 raw = *reinterpret_cast<const u32x4*>(src);
+  const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+  float x[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), a.in_bf16);
+  uint32_t codes[8];
+  uint16_t S, Z;
+  const int bits = is_v ? BV : BK;
+  const int G = is_v ? g.g_v : g.g_k, ng = is_v ? g.ng_v : g.ng_k;
+  const int lpg = G >> 3;
+  quantize8(x, bits, lpg, codes, &S, &Z);
+  uint32_t* meta = (uint32_t*)((uint8_t*)(is_v ? a.cache.v_meta : a.cache.k_meta) + (int64_t)bh * (is_v ? g.vm_stream : g.km_stream));
+  if ((lane16 & (lpg - 1)) == 0) meta[meta_index(t, lane16 / lpg, ng)] = (uint32_t)S | ((uint32_t)Z << 16);
+  if (!is_v) {
+    uint8_t* rowp = (uint8_t*)a.cache.k_codes + (int64_t)bh * g.kc_stream + t * (16 * BK);
+    uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (BK == 8) { if (e < 4) w0 |= codes[e] << (8 * e); else w1 |= codes[e] << (8 * (e - 4)); }
+      else w0 |= codes[e] << (BK * e);
+    }
+    if (BK == 4) reinterpret_cast<uint32_t*>(rowp)[lane16] = w0;
+    else if (BK == 2) reinterpret_cast<uint16_t*>(rowp)[lane16] = (uint16_t)w0;
+    else reinterpret_cast<uint2*>(rowp)[lane16] = make_uint2(w0, w1);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vstage[d0 + e] = (uint8_t)codes[e];
+  }
+}
+
+// Second half of the fused append: thread d < 128 inserts channel d's code of token seq_len-1 into its 32-bit word
+// (read-modify-write; the other fields of the word belong to other tokens of the same 32-token block).  With 2-bit
+// codes channels d and d+16 share a word, so the thread of the even 16-channel tile writes both.
+template <int BV>
+__device__ __forceinline__ void append_one_values(const DecodeArgs& a, int bh, int tid, const uint8_t* vstage) {
+  if (tid >= kHeadDim) return;
+  if (BV == 2 && ((tid >> 4) & 1)) return;
+  const Geom& g = a.g;
+  const int64_t t = a.seq_len - 1;
+  uint32_t* blk = (uint32_t*)((uint8_t*)a.cache.v_codes + (int64_t)bh * g.vc_stream) + (t >> 5) * (int64_t)(128 * BV);
+  const uint32_t fmask = (1u << BV) - 1u;
+  int dw, bit;
+  v_field((int)(t & 31), tid, BV, &dw, &bit);
+  uint32_t w = (blk[dw] & ~(fmask << bit)) | ((uint32_t)vstage[tid] << bit);
+  if (BV == 2) {
+    int dw2, bit2;
+    v_field((int)(t & 31), tid + 16, BV, &dw2, &bit2);    // same word, the neighbouring tile's field
+    w = (w & ~(fmask << bit2)) | ((uint32_t)vstage[tid + 16] << bit2);
+  }
+  blk[dw] = w;
+}
+
+template <int BK, int BV, int R, int NW>
+__global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(const DecodeArgs a) {
+  __shared__ float sm_o[NW][R][kHeadDim];
+  __shared__ float sm_m[NW][R], sm_l[NW][R];
   __shared__ __attribute__((aligned(16))) uint16_t sm_q[R][kHeadDim];
-  __shared__ __attribute__((aligned(16))) uint8_t sm_meta[4][1024];
+  __shared__ __attribute__((aligned(16))) uint8_t sm_meta[NW][1024];
+  __shared__ uint8_t sm_vnew[kHeadDim];
+  const Geom& g = a.g;
+  const kvq_cache& cache = a.cache;
+  const uint16_t* __restrict__ q = a.q;
+  const int q_bf16 = a.q_bf16, q_heads = a.q_heads, seq_len = a.seq_len, out_dtype = a.out_dtype;
+  const int n_splits = a.n_splits, steps_per_split = a.steps_per_split;
+  const float softmax_scale = a.softmax_scale;
+  float* __restrict__ ws = a.ws;
+  void* __restrict__ out = a.out;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -300,22 +382,40 @@ __global__ __launch_bounds__(256, KVQ_WAVES_PER_SIMD) void decode_kernel(
   const int step_begin = split * steps_per_split;
   const int step_end = min(step_begin + steps_per_split, n_steps);
   const int first = step_begin + wave;
-  auto step_of = [&](int i) { return first + 4 * i; };
-  const int n_my = first < step_end ? (step_end - first + 3) >> 2 : 0;
+  auto step_of = [&](int i) { return first + NW * i; };
+  const int n_my = first < step_end ? (step_end - first + NW - 1) / NW : 0;
   const bool ragged = (seq_len & 31) != 0;
   const bool own_tail = ragged && n_my > 0 && step_of(n_my - 1) == n_steps - 1;
   const int n_full = own_tail ? n_my - 1 : n_my;   // complete steps of this wavefront
-  // register ring of KVQ_STAGES steps: start the first loads before anything else
+  // fused decode step: the owner of the last step writes the new token first.  When the ring's first loads cannot
+  // reach that step they are started before the (short) quantization, otherwise after it.
+  const bool do_append = a.k_new != nullptr && split == n_splits - 1;
+  const bool early = !do_append || n_my > KVQ_STAGES;
+  // register ring of KVQ_STAGES steps
   StepRegs<BK, BV> buf[KVQ_STAGES];
+  if (early) {
 #pragma unroll
-  for (int k = 0; k < KVQ_STAGES; ++k)
-    if (k < n_full) load_step<BK, BV>(buf[k], L, step_of(k));
+    for (int k = 0; k < KVQ_STAGES; ++k)
+      if (k < n_full) load_step<BK, BV>(buf[k], L, step_of(k));
+  }
+  if (do_append) {                                 // uniform over the workgroup
+    append_one<BK, BV>(a, bh, b, hk, tid, sm_vnew);
+    __syncthreads();
+    append_one_values<BV>(a, bh, tid, sm_vnew);
+    __threadfence_block();                         // writer and readers share this workgroup: a workgroup-scope
+                                                   // release is enough (no L2 write-back/invalidate across XCDs)
+  }
 
   // ---- query rows of this kv head -> LDS (one coalesced 16-byte load per thread), then per-lane operands
   if (tid < R * 16)
     reinterpret_cast<u32x4*>(&sm_q[0][0])[tid] =
         *reinterpret_cast<const u32x4*>(q + ((int64_t)b * q_heads + hk * R) * kHeadDim + tid * 8);
   __syncthreads();
+  if (!early) {
+#pragma unroll
+    for (int k = 0; k < KVQ_STAGES; ++k)
+      if (k < n_full) load_step<BK, BV>(buf[k], L, step_of(k));
+  }
   auto widen = [&](uint16_t bits) -> float {
     return q_bf16 ? __uint_as_float((uint32_t)bits << 16) : (float)__builtin_bit_cast(_Float16, bits);
   };
@@ -399,13 +499,15 @@ __global__ __launch_bounds__(256, KVQ_WAVES_PER_SIMD) void decode_kernel(
   }
   __syncthreads();
 
-  // ---- merge the 4 wavefronts; write a partial record, or the result when there is one split
-  for (int idx = tid; idx < R * kHeadDim; idx += 256) {
+  // ---- merge the wavefronts; write a partial record, or the result when there is one split
+  for (int idx = tid; idx < R * kHeadDim; idx += 64 * NW) {
     const int hh = idx / kHeadDim, d = idx % kHeadDim;
-    float M = fmaxf(fmaxf(sm_m[0][hh], sm_m[1][hh]), fmaxf(sm_m[2][hh], sm_m[3][hh]));
+    float M = sm_m[0][hh];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, sm_m[w][hh]);
     float o = 0.f, ll = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NW; ++w) {
       const float f = exp2f(sm_m[w][hh] - M);
       o = fmaf(f, sm_o[w][hh][d], o);
       ll = fmaf(f, sm_l[w][hh], ll);
@@ -451,26 +553,23 @@ __global__ __launch_bounds__(128) void merge_kernel(const float* __restrict__ ws
 }
 
 template <int BK, int BV, int R>
-hipError_t launch_one(const Geom& g, const kvq_cache& c, const void* q, int q_dtype, int32_t q_heads, int32_t seq_len,
-                      float softmax_scale, void* out, int out_dtype, float* ws, const DecodePlan& plan, hipStream_t stream) {
-  dim3 grid(plan.n_splits, g.batch * g.kv_heads);
-  hipLaunchKernelGGL((decode_kernel<BK, BV, R>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)q,
-                     q_dtype == KVQ_BF16 ? 1 : 0, q_heads, seq_len, softmax_scale, ws, out, out_dtype, plan.n_splits,
-                     plan.steps_per_split);
+hipError_t launch_one(const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream) {
+  dim3 grid(plan.n_splits, a.g.batch * a.g.kv_heads);
+  if (plan.waves_per_wg == 8) hipLaunchKernelGGL((decode_kernel<BK, BV, R, 8>), grid, dim3(512), 0, stream, a);
+  else hipLaunchKernelGGL((decode_kernel<BK, BV, R, 4>), grid, dim3(256), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || plan.n_splits == 1) return e;
-  hipLaunchKernelGGL(merge_kernel, dim3(g.batch * q_heads), dim3(128), 0, stream, ws, out, out_dtype, plan.n_splits);
+  hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128), 0, stream, a.ws, a.out, a.out_dtype, plan.n_splits);
   return hipGetLastError();
 }
 
 template <int BK, int BV>
-hipError_t launch_r(int R, const Geom& g, const kvq_cache& c, const void* q, int q_dtype, int32_t q_heads, int32_t seq_len,
-                    float softmax_scale, void* out, int out_dtype, float* ws, const DecodePlan& plan, hipStream_t stream) {
+hipError_t launch_r(int R, const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream) {
   switch (R) {
-    case 1: return launch_one<BK, BV, 1>(g, c, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype, ws, plan, stream);
-    case 2: return launch_one<BK, BV, 2>(g, c, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype, ws, plan, stream);
-    case 4: return launch_one<BK, BV, 4>(g, c, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype, ws, plan, stream);
-    case 8: return launch_one<BK, BV, 8>(g, c, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype, ws, plan, stream);
+    case 1: return launch_one<BK, BV, 1>(a, plan, stream);
+    case 2: return launch_one<BK, BV, 2>(a, plan, stream);
+    case 4: return launch_one<BK, BV, 4>(a, plan, stream);
+    case 8: return launch_one<BK, BV, 8>(a, plan, stream);
   }
   return hipErrorInvalidValue;
 }
@@ -486,27 +585,41 @@ bool decode_supported(const Geom& g, int32_t q_heads) {
 }
 
 DecodePlan plan_decode(const Geom& g, int32_t seq_len) {
+  // Fill the chip exactly once: 256 CUs x 4 SIMDs x KVQ_WAVES_PER_SIMD wavefronts, spread over the (b,h) streams.
+  // Workgroups of 8 wavefronts halve the number of sequence splits (none at all from 256 streams up, where the
+  // merge kernel and the workspace traffic disappear); each wavefront should still own a few steps.
   const int n_steps = (seq_len + 31) / 32;
   const int streams = g.batch * g.kv_heads;
-  const int target_wgs = 256 * KVQ_WAVES_PER_SIMD;             // CUs x resident workgroups (4 wavefronts each) per CU:
-                                                               // one full round of workgroups, no tail
-  int splits = (target_wgs + streams - 1) / streams;
-  const int max_splits = (n_steps + 7) / 8;                    // at least two steps per wavefront
-  if (splits > max_splits) splits = max_splits;
+  const int total_waves = 256 * 4 * KVQ_WAVES_PER_SIMD;
+  int waves_per_stream = (total_waves + streams - 1) / streams;
+  const int max_waves = (n_steps + 1) / 2;                     // at least two steps per wavefront
+  if (waves_per_stream > max_waves) waves_per_stream = max_waves;
+  if (waves_per_stream < 4) waves_per_stream = 4;
+  const int nw = waves_per_stream >= 8 ? 8 : 4;
+  int splits = waves_per_stream / nw;
   if (splits < 1) splits = 1;
   int sps = (n_steps + splits - 1) / splits;
-  sps = (sps + 3) / 4 * 4;
+  sps = (sps + nw - 1) / nw * nw;
   splits = (n_steps + sps - 1) / sps;
-  return DecodePlan{splits, sps};
+  return DecodePlan{splits, sps, nw};
 }
 
 hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void* q, int q_dtype, int32_t q_heads,
                                    int32_t seq_len, float softmax_scale, void* out, int out_dtype, float* workspace,
-                                   const DecodePlan& plan, hipStream_t stream) {
+                                   const DecodePlan& plan, const AppendOne* app, hipStream_t stream) {
   const int R = q_heads / g.kv_heads;
-#define KVQ_CASE(BK_, BV_)                                                                                          \
-  if (g.bits_k == BK_ && g.bits_v == BV_)                                                                           \
-    return launch_r<BK_, BV_>(R, g, c, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype, workspace, plan, stream);
+  DecodeArgs a{};
+  a.g = g; a.cache = c;
+  a.q = (const uint16_t*)q; a.q_bf16 = q_dtype == KVQ_BF16 ? 1 : 0; a.q_heads = q_heads;
+  a.seq_len = seq_len; a.softmax_scale = softmax_scale;
+  a.ws = workspace; a.out = out; a.out_dtype = out_dtype;
+  a.n_splits = plan.n_splits; a.steps_per_split = plan.steps_per_split;
+  if (app) {
+    a.k_new = (const uint16_t*)app->k_new; a.v_new = (const uint16_t*)app->v_new;
+    a.in_bf16 = app->in_dtype == KVQ_BF16 ? 1 : 0; a.nsb = app->stride_b; a.nsh = app->stride_h;
+  }
+#define KVQ_CASE(BK_, BV_) \
+  if (g.bits_k == BK_ && g.bits_v == BV_) return launch_r<BK_, BV_>(R, a, plan, stream);
   KVQ_CASE(4, 2)
   KVQ_CASE(2, 4)
   KVQ_CASE(4, 4)

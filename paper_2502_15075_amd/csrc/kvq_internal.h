@@ -39,7 +39,13 @@ inline Geom make_geom(const kvq_layout& L) {
 // Number of sequence splits the decode kernel uses for this problem (host-side plan).
 struct DecodePlan {
   int32_t n_splits;         // workgroups per (b, h_kv)
-  int32_t steps_per_split;  // 32-token steps each workgroup walks (a multiple of 4: one per wavefront)
+  int32_t steps_per_split;  // 32-token steps each workgroup walks (a multiple of waves_per_wg)
+  int32_t waves_per_wg;     // 4 or 8 wavefronts per workgroup
+};
+
+// The single new token of a fused decode step: [B][H_kv][D] rows with element strides.
+struct AppendOne {
+  const void* k_new; const void* v_new; int in_dtype; int64_t stride_b, stride_h;
 };
 DecodePlan plan_decode(const Geom& g, int32_t seq_len);
 
@@ -52,7 +58,7 @@ hipError_t launch_dequantize(const Geom& g, const kvq_cache& c, int32_t t0, int3
 // Returns hipErrorInvalidValue if no kernel instance exists for (bits, groups, head ratio).
 hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void* q, int q_dtype, int32_t q_heads,
                                    int32_t seq_len, float softmax_scale, void* out, int out_dtype, float* workspace,
-                                   const DecodePlan& plan, hipStream_t stream);
+                                   const DecodePlan& plan, const AppendOne* append, hipStream_t stream);
 bool decode_supported(const Geom& g, int32_t q_heads);
 
 #if defined(__HIPCC__)

@@ -1,0 +1,66 @@
+// The quantizer arithmetic shared by the bulk quantize-append kernel and the fused decode step.
+//
+// b-bit uniform scalar quantizer of App. B ("Preliminaries": scale factor, round, clip, reconstruct) of
+// arXiv 2502.15075 in its group-wise asymmetric min-max form; the exact arithmetic is stated in kvq.h.
+// Codes and scale/zero bytes must be identical wherever this is compiled, so floating-point contraction
+// is switched off inside these functions whatever the translation unit's setting is, and every operation
+// is a single IEEE binary32 operation (hipcc's default division is correctly rounded).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kvq {
+
+__device__ __forceinline__ float widen16(uint16_t bits, bool bf16) {
+  if (bf16) return __uint_as_float((uint32_t)bits << 16);
+  return (float)__builtin_bit_cast(_Float16, bits);
+}
+
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {
+  _Float16 h = (_Float16)f;  // v_cvt_f16_f32: round-to-nearest-even, subnormals kept
+  return __builtin_bit_cast(uint16_t, h);
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
+  return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+// Quantize 8 consecutive elements held by this lane; the group spans `lanes_per_group`
+// neighbouring lanes (a power of two <= 16, aligned).  Returns the 8 codes, and the stored
+// scale/zero patterns through S, Z.
+__device__ __forceinline__ void quantize8(const float x[8], int bits, int lanes_per_group, uint32_t codes[8],
+                                          uint16_t* S, uint16_t* Z) {
+#pragma clang fp contract(off)
+  float mn = x[0], mx = x[0];
+#pragma unroll
+  for (int e = 1; e < 8; ++e) { mn = fminf(mn, x[e]); mx = fmaxf(mx, x[e]); }
+  for (int off = 1; off < lanes_per_group; off <<= 1) {
+    mn = fminf(mn, __shfl_xor(mn, off, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, off, 16));
+  }
+  if (mn == 0.0f) mn = 0.0f;  // -0 -> +0
+  const float levels = (float)((1 << bits) - 1);
+  float s32 = (mx - mn) / levels;
+  uint16_t sb = f32_to_f16_bits(s32);
+  if ((sb & 0x7FFFu) == 0) sb = 0;
+  uint16_t zb = f32_to_f16_bits(mn);
+  float s = widen16(sb, false), z = widen16(zb, false);
+  *S = sb; *Z = zb;
+  if (s == 0.0f) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) codes[e] = 0;
+    return;
+  }
+  float rcp = 1.0f / s;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float t = (x[e] - z) * rcp;
+    float q = rintf(t);
+    q = fminf(fmaxf(q, 0.0f), levels);
+    codes[e] = (uint32_t)q;
+  }
+}
+
+}  // namespace kvq

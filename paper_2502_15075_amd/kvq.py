@@ -53,12 +53,15 @@ def load():
                                             C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p]
         lib.kvq_decode_attention.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_int, C.c_int32,
                                              C.c_int32, C.c_float, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.kvq_decode_step.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int, C.c_int64,
+                                        C.c_int64, C.c_int32, C.c_void_p, C.c_int, C.c_int32, C.c_float, C.c_void_p, C.c_int,
+                                        C.c_void_p, C.c_size_t, C.c_void_p]
         lib.kvq_dequantize.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_int32, C.c_int32, C.c_void_p,
                                        C.c_void_p, C.c_int, C.c_void_p]
         lib.kvq_status_string.argtypes = [C.c_int]
         lib.kvq_status_string.restype = C.c_char_p
         for f in ("kvq_cache_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
-                  "kvq_dequantize"):
+                  "kvq_decode_step", "kvq_dequantize"):
             getattr(lib, f).restype = C.c_int
         _lib = lib
     return _lib
@@ -151,6 +154,24 @@ def decode_attention(layout: Layout, cache: Cache, q: torch.Tensor, seq_len: int
                                      C.c_float(softmax_scale), _p(out), _DTYPES[out.dtype], _p(workspace),
                                      0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_ptr())
     _check(st, "kvq_decode_attention")
+    return out
+
+
+def decode_step(layout: Layout, cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, pos: int, q: torch.Tensor,
+                softmax_scale: float, out: torch.Tensor, workspace) -> torch.Tensor:
+    """Fused step: quantize the new token (k_new, v_new: [B, H_kv, D] or [B, H_kv, 1, D]) into position pos, then attend
+    over [0, pos].  q, out, workspace as in decode_attention (workspace may be None when no bytes are needed)."""
+    if k_new.dim() == 4:
+        k_new, v_new = k_new[:, :, 0], v_new[:, :, 0]
+    assert k_new.shape == v_new.shape and k_new.dtype == v_new.dtype and k_new.dim() == 3
+    assert k_new.stride() == v_new.stride() and k_new.stride(2) == 1
+    assert q.is_contiguous() and out.is_contiguous() and q.dim() == 3 and out.shape == q.shape
+    cl, cc = layout.c(), cache.c()
+    st = load().kvq_decode_step(C.byref(cl), C.byref(cc), _p(k_new), _p(v_new), _DTYPES[k_new.dtype], k_new.stride(0),
+                                k_new.stride(1), pos, _p(q), _DTYPES[q.dtype], q.shape[1], C.c_float(softmax_scale), _p(out),
+                                _DTYPES[out.dtype], _p(workspace),
+                                0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_ptr())
+    _check(st, "kvq_decode_step")
     return out
 
 

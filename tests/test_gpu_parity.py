@@ -62,7 +62,7 @@ def _rel_err(out, ref):
 
 
 def _decode(kvq, Lg, cache, q, seq_len, out_dtype=torch.float32):
-    ws = torch.empty(kvq.decode_workspace_bytes(Lg, q.shape[1], seq_len), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, q.shape[1], seq_len)), dtype=torch.uint8, device="cuda")
     out = torch.empty(q.shape, dtype=out_dtype, device="cuda")
     kvq.decode_attention(Lg, cache, q.cuda(), seq_len, 1 / math.sqrt(128), out, ws)
     torch.cuda.synchronize()
@@ -226,6 +226,59 @@ def test_decode_step_appends_then_attends(kvq, oracle):
     assert _rel_err(out.cpu().numpy(), ref) < TOL
 
 
+@pytest.mark.parametrize("bk,bv,gk,gv,R", [(4, 2, 64, 64, 8), (4, 2, 32, 32, 4), (2, 4, 64, 128, 2), (8, 8, 64, 64, 1), (4, 4, 128, 64, 8)])
+def test_fused_decode_steps_match_append_then_attend(kvq, oracle, bk, bv, gk, gv, R):
+    """kvq_decode_step over consecutive positions (block boundaries included): planes stay byte-identical to the
+    oracle's and every step's output is the oracle's attention over the cache so far."""
+    B, H, T0, nstep = 2, 2, 60, 8                       # positions 60..67 cross the 64-token boundary
+    T = T0 + nstep
+    K, V, _ = synth.make_kvq(20 + bk, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K[:, :, :T0], V[:, :, :T0], [(0, T0)])
+    Kd, Vd = K.cuda(), V.cuda()
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    for i in range(nstep):
+        pos = T0 + i
+        _, _, q = synth.make_kvq(300 + i, B, H, H * R, 1, dtype=torch.bfloat16)
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), 1 / math.sqrt(128), out, ws)
+        torch.cuda.synchronize()
+        oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, pos:pos + 1])),
+                               np.ascontiguousarray(synth.to_numpy_bits(V[:, :, pos:pos + 1])), pos, bf16=True)
+        _assert_planes_equal(cache, planes)
+        ref = oracle.decode_attention(Lo, planes, synth.to_numpy_bits(q), pos + 1, 1 / math.sqrt(128), bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
+
+
+def test_fused_step_from_an_empty_cache_and_long_context(kvq, oracle):
+    """pos = 0 (the only token) and a context long enough for 8-wavefront workgroups and several splits."""
+    B, H, R = 1, 2, 4
+    K, V, q = synth.make_kvq(31, B, H, H * R, 1, dtype=torch.float16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, 40, 4, 2, 64, 64)
+    cache = kvq.Cache(Lg, fill=0xFF)
+    planes = oracle.new_planes(Lo, fill=0xFF)
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    kvq.decode_step(Lg, cache, K.cuda()[:, :, 0], V.cuda()[:, :, 0], 0, q.cuda(), 1 / math.sqrt(128), out, None
+                    if kvq.decode_workspace_bytes(Lg, H * R, 1) == 0 else torch.empty(1 << 16, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    oracle.quantize_append(Lo, planes, K.numpy(), V.numpy(), 0)
+    _assert_planes_equal(cache, planes)
+    ref = oracle.decode_attention(Lo, planes, q.numpy(), 1, 1 / math.sqrt(128))
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+    T = 3000
+    K, V, q = synth.make_kvq(32, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, 4, 2, 64, 64)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K[:, :, :T - 1], V[:, :, :T - 1], [(0, T - 1)])
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, T)), dtype=torch.uint8, device="cuda")
+    kvq.decode_step(Lg, cache, K.cuda()[:, :, T - 1], V.cuda()[:, :, T - 1], T - 1, q.cuda(), 1 / math.sqrt(128), out, ws)
+    torch.cuda.synchronize()
+    oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, T - 1:])),
+                           np.ascontiguousarray(synth.to_numpy_bits(V[:, :, T - 1:])), T - 1, bf16=True)
+    _assert_planes_equal(cache, planes)
+    ref = oracle.decode_attention(Lo, planes, synth.to_numpy_bits(q), T, 1 / math.sqrt(128), bf16=True)
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+
+
 def test_error_codes_on_device(kvq):
     L = kvq.Layout(1, 2, 100)
     cache = kvq.Cache(L)
@@ -236,6 +289,10 @@ def test_error_codes_on_device(kvq):
     kvq.quantize_append(L, cache, k[:, :, :0], k[:, :, :0], 100)      # empty append at the end is a no-op
     q = torch.zeros(1, 8, 128, dtype=torch.float16, device="cuda")
     out = torch.empty(1, 8, 128, dtype=torch.float32, device="cuda")
+    if kvq.decode_workspace_bytes(L, 8, 100) > 16:
+        with pytest.raises(kvq.KvqError) as e:
+            kvq.decode_attention(L, cache, q, 100, 0.1, out, torch.empty(16, dtype=torch.uint8, device="cuda"))
+        assert e.value.status == kvq.ERR_WORKSPACE
     with pytest.raises(kvq.KvqError) as e:
-        kvq.decode_attention(L, cache, q, 50, 0.1, out, torch.empty(16, dtype=torch.uint8, device="cuda"))
-    assert e.value.status == kvq.ERR_WORKSPACE
+        kvq.decode_step(L, cache, k[:, :, 0], k[:, :, 0], 100, q, 0.1, out, None)
+    assert e.value.status == kvq.ERR_CAPACITY
