@@ -1,0 +1,144 @@
+"""Host-side checks of libkvq's C ABI that need no GPU: the library loads, exports every symbol the header
+declares, sizes follow the closed forms, and every argument error is reported before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def kvq():
+    from paper_2502_15075_amd import kvq as m
+    if not os.path.exists(m.LIB_PATH):
+        from paper_2502_15075_amd import build
+        build.build_lib()
+    m.load()
+    return m
+
+
+def test_every_declared_symbol_is_exported(kvq):
+    header = open(os.path.join(ROOT, "include", "kvq.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(kvq_[a-z_]+)\s*\(", header))
+    assert {"kvq_cache_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
+            "kvq_decode_step", "kvq_dequantize", "kvq_status_string"} <= declared
+    lib = C.CDLL(kvq.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(kvq):
+    seen = {kvq.status_string(i) for i in range(6)}
+    assert len(seen) == 6 and "ok" in seen
+    assert kvq.status_string(99) == "unknown status"
+
+
+def test_cache_bytes_closed_forms(kvq):
+    """bytes per (b, h, token): 16 b_K + 16 b_V code bytes and 4 bytes per group of scale/zero (Sec. 1: K4V2 code
+    bytes are 3/4 of K4V4's)."""
+    rows = 8 * 8 * 8192
+    a = kvq.cache_bytes(kvq.Layout(8, 8, 8192, 128, 4, 2, 64, 64))
+    b = kvq.cache_bytes(kvq.Layout(8, 8, 8192, 128, 4, 4, 64, 64))
+    assert a == [rows * 64, rows * 8, rows * 32, rows * 8] and sum(a) == rows * 112
+    assert (a[0] + a[2]) / (b[0] + b[2]) == 0.75 and sum(b) == rows * 144
+    assert sum(kvq.cache_bytes(kvq.Layout(1, 8, 1024, 128, 4, 2, 32, 32))) == 8 * 1024 * 128
+    assert sum(kvq.cache_bytes(kvq.Layout(32, 8, 32768, 128, 4, 2, 64, 64))) == 896 << 20
+    assert sum(kvq.cache_bytes(kvq.Layout(1, 1, 65, 128, 8, 8, 64, 64))) == 96 * 272        # capacity rounds up to 32
+    raw = kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 16, 16, 64, 64))
+    assert raw == [2 * 2 * 64 * 256, 0, 2 * 2 * 64 * 256, 0]
+
+
+def test_sizes_agree_with_the_oracle(kvq, oracle):
+    for args in ((1, 8, 1024, 128, 4, 2, 32, 32), (3, 2, 77, 128, 2, 8, 128, 64), (2, 2, 33, 128, 16, 4, 64, 32)):
+        assert kvq.cache_bytes(kvq.Layout(*args)) == oracle.plane_bytes(oracle.Layout(*args))
+
+
+def test_workspace_plan(kvq):
+    # 256 (b,h) streams fill the chip without splitting the sequence: no workspace at all
+    assert kvq.decode_workspace_bytes(kvq.Layout(32, 8, 32768), 64, 32768) == 0
+    # few streams, long context: (splits) x (B x H_q) records of 132 floats
+    n = kvq.decode_workspace_bytes(kvq.Layout(1, 8, 131072), 32, 131072)
+    assert n > 0 and n % (32 * 132 * 4) == 0
+    assert kvq.decode_workspace_bytes(kvq.Layout(1, 8, 131072), 32, 40) <= n
+
+
+def _status(fn, *a):
+    with pytest.raises(Exception) as e:
+        fn(*a)
+    return e.value.status
+
+
+def test_layout_errors(kvq):
+    bad = [
+        (kvq.Layout(0, 8, 64), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 0), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 64, 128, 3, 2), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, 128, 4, 5), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 64, 128, 4, 2, 48, 64), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 256), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 64, 64), kvq.ERR_UNSUPPORTED), (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_k=1), kvq.ERR_UNSUPPORTED),
+        (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_v=7), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, raw_dtype=2), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 1 << 25), kvq.ERR_UNSUPPORTED),
+    ]
+    for layout, want in bad:
+        assert _status(kvq.cache_bytes, layout) == want, layout
+
+
+def test_call_errors_are_caught_before_any_launch(kvq):
+    """Fake (never dereferenced) device addresses: every one of these calls must fail on the host."""
+    lib = kvq.load()
+    L = kvq.Layout(2, 2, 100)
+    cl = L.c()
+    good = kvq._CCache(0x10000, 0x20000, 0x30000, 0x40000)
+    p = C.c_void_p
+    def qa(cache, k, v, dt, sb, sh, st, pos, n):
+        return lib.kvq_quantize_append(C.byref(cl), C.byref(cache), p(k), p(v), dt, sb, sh, st, pos, n, None)
+    assert qa(good, 0x50000, 0x60000, 0, 25600, 12800, 128, 95, 8) == kvq.ERR_CAPACITY
+    assert qa(good, 0x50000, 0x60000, 0, 25600, 12800, 128, -1, 1) == kvq.ERR_INVALID_ARG
+    assert qa(good, 0, 0x60000, 0, 25600, 12800, 128, 0, 1) == kvq.ERR_INVALID_ARG
+    assert qa(good, 0x50000, 0x60000, 2, 25600, 12800, 128, 0, 1) == kvq.ERR_INVALID_ARG          # fp32 input
+    assert qa(good, 0x50002, 0x60000, 0, 25600, 12800, 128, 0, 1) == kvq.ERR_INVALID_ARG          # misaligned rows
+    assert qa(good, 0x50000, 0x60000, 0, 25600, 12800, 100, 0, 1) == kvq.ERR_INVALID_ARG          # rows overlap
+    assert qa(kvq._CCache(0x10000, 0, 0x30000, 0x40000), 0x50000, 0x60000, 0, 25600, 12800, 128, 0, 1) == kvq.ERR_INVALID_ARG
+    assert qa(good, 0x50000, 0x60000, 0, 25600, 12800, 128, 100, 0) == kvq.OK                     # empty append: no launch
+
+    def da(q, heads, seq, scale, out, odt, ws, wsb):
+        return lib.kvq_decode_attention(C.byref(cl), C.byref(good), p(q), 1, heads, seq, C.c_float(scale), p(out), odt, p(ws), wsb, None)
+    assert da(0x50000, 8, 101, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_CAPACITY
+    assert da(0x50000, 8, 0, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_INVALID_ARG
+    assert da(0x50000, 3, 50, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_INVALID_ARG          # 3 heads over 2 kv heads
+    assert da(0x50000, 12, 50, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_UNSUPPORTED         # 6 query heads per kv head
+    assert da(0x50000, 8, 50, -1.0, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_INVALID_ARG
+    assert da(0x50000, 8, 50, float("nan"), 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_INVALID_ARG
+    assert da(0, 8, 50, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_INVALID_ARG
+    need = kvq.decode_workspace_bytes(L, 8, 100)
+    if need:
+        assert da(0x50000, 8, 100, 0.1, 0x60000, 2, 0x70000, need - 1) == kvq.ERR_WORKSPACE
+        assert da(0x50000, 8, 100, 0.1, 0x60000, 2, 0, need) == kvq.ERR_WORKSPACE
+    L32 = kvq.Layout(2, 2, 100, 128, 4, 2, 32, 32).c()                                            # 8 heads x 4 groups > 16 columns
+    assert lib.kvq_decode_attention(C.byref(L32), C.byref(good), p(0x50000), 1, 16, 50, C.c_float(0.1), p(0x60000), 2,
+                                    p(0x70000), 1 << 20, None) == kvq.ERR_UNSUPPORTED
+
+    def ds(pos, k=0x50000):
+        return lib.kvq_decode_step(C.byref(cl), C.byref(good), p(k), p(0x51000), 1, 256, 128, pos, p(0x52000), 1, 8,
+                                   C.c_float(0.1), p(0x60000), 2, p(0x70000), 1 << 20, None)
+    assert ds(100) == kvq.ERR_CAPACITY and ds(-1) == kvq.ERR_INVALID_ARG and ds(5, 0) == kvq.ERR_INVALID_ARG
+
+    def dq(t0, t1, ko, vo, dt):
+        return lib.kvq_dequantize(C.byref(cl), C.byref(good), t0, t1, p(ko), p(vo), dt, None)
+    assert dq(0, 101, 0x50000, 0x60000, 2) == kvq.ERR_CAPACITY
+    assert dq(5, 4, 0x50000, 0x60000, 2) == kvq.ERR_INVALID_ARG
+    assert dq(0, 4, 0, 0, 2) == kvq.ERR_INVALID_ARG
+    assert dq(0, 4, 0x50000, 0, 7) == kvq.ERR_INVALID_ARG
+    assert dq(4, 4, 0x50000, 0, 2) == kvq.OK                                                       # empty range: no launch
+
+
+def test_product_path_never_touches_the_oracle():
+    """The library, its binding and the benchmark's GPU leg must not import the CPU oracle."""
+    pat = re.compile(r"^\s*(from|import)\s+oracle|kvq_oracle|libkvq_oracle", re.M)
+    for rel in ("paper_2502_15075_amd/kvq.py", "paper_2502_15075_amd/synth.py", "paper_2502_15075_amd/build.py",
+                "paper_2502_15075_amd/__init__.py"):
+        assert not pat.search(open(os.path.join(ROOT, rel)).read()), rel
+    for f in os.listdir(os.path.join(ROOT, "paper_2502_15075_amd", "csrc")):
+        assert not pat.search(open(os.path.join(ROOT, "paper_2502_15075_amd", "csrc", f)).read()), f
