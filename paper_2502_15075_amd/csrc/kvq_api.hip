@@ -101,6 +101,8 @@ kvq_status decode_common(const kvq_layout* layout, const kvq_cache* cache, const
   if (!aligned16(q) || !aligned16(out)) return KVQ_ERR_INVALID_ARG;
   const kvq::Geom g = kvq::make_geom(*layout);
   if (!kvq::decode_supported(g, q_heads)) return KVQ_ERR_UNSUPPORTED;
+  if (layout->bits_k == 16 && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // matrix operands share a type
+  if (layout->bits_k == 16 && app) return KVQ_ERR_UNSUPPORTED;          // fused append exists for quantized caches only
   size_t need = 0;
   st = kvq_decode_workspace_bytes(layout, q_heads, seq_len, &need);
   if (st != KVQ_OK) return st;

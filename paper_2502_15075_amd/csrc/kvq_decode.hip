@@ -25,8 +25,16 @@ namespace kvq {
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// D += A(16x32) * B(32x16); operands travel as 4 dwords (8 x 16-bit), binary16 or bfloat16.
+template <bool BF>
+__device__ __forceinline__ float4v mma(u32x4 a, u32x4 b, float4v c) {
+  if constexpr (BF) return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  else return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
+}
 
 constexpr float kCodeUnit = 5.9604644775390625e-08f;  // 2^-24: value of a code's lowest mantissa bit
 constexpr float kInvCodeUnit = 16777216.0f;
@@ -34,7 +42,6 @@ constexpr float kPShift = 10.0f;                      // softmax weights are car
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;
 
-__device__ __forceinline__ half8 as_half8(u32x4 v) { return __builtin_bit_cast(half8, v); }
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float x) {
@@ -55,6 +62,7 @@ __device__ __forceinline__ float sum_over_groups(float x) {
 // lane's 32, stored times k_slot_scale(i).
 template <int BK> __device__ __forceinline__ int k_slot_elem(int m, int i) {
   const int v = i >> 1, x = i & 1;
+  if (BK == 16) return 8 * m + i;
   if (BK == 4) return 8 * m + v + 4 * x;
   if (BK == 8) return 8 * m + 4 * (v >> 1) + (v & 1) + 2 * x;
   return 16 * (m >> 1) + 4 * (m & 1) + v + 8 * x;  // BK == 2
@@ -62,12 +70,14 @@ template <int BK> __device__ __forceinline__ int k_slot_elem(int m, int i) {
 template <int BK> __device__ __forceinline__ float k_slot_scale(int i) {
   const int v = i >> 1;
   if (BK == 4) return (v & 1) ? 16.0f : 1.0f;
-  if (BK == 8) return 1.0f;
+  if (BK == 8 || BK == 16) return 1.0f;
   return (float)(1 << (2 * v));  // BK == 2
 }
-template <int BK> __device__ __forceinline__ half8 unpack_k(const uint32_t* w, int m) {
+template <int BK> __device__ __forceinline__ u32x4 unpack_k(const uint32_t* w, int m) {
   u32x4 a;
-  if (BK == 4) {
+  if (BK == 16) {
+    a = u32x4{w[4 * m], w[4 * m + 1], w[4 * m + 2], w[4 * m + 3]};      // unquantized: the 16-bit patterns themselves
+  } else if (BK == 4) {
     const uint32_t lo = w[m], hi = w[m] >> 8;
     a = u32x4{lo & 0x000F000Fu, lo & 0x00F000F0u, hi & 0x000F000Fu, hi & 0x00F000F0u};
   } else if (BK == 8) {
@@ -77,7 +87,7 @@ template <int BK> __device__ __forceinline__ half8 unpack_k(const uint32_t* w, i
     const uint32_t ws = w[m >> 1] >> (8 * (m & 1));
     a = u32x4{ws & 0x00030003u, ws & 0x000C000Cu, ws & 0x00300030u, ws & 0x00C000C0u};
   }
-  return as_half8(a);
+  return a;
 }
 
 // ---- value codes: one lane holds, per 32-token step, 2*BV dwords (index = 4*piece + dword) ----
@@ -87,9 +97,11 @@ template <int BK> __device__ __forceinline__ half8 unpack_k(const uint32_t* w, i
 template <int BV> __device__ __forceinline__ constexpr int v_slot_shift(int v) {
   return BV == 2 ? 2 * v : (BV == 4 ? 4 * (v & 1) : 0);
 }
-template <int BV> __device__ __forceinline__ half8 unpack_v(const uint32_t* w, int dt) {
+template <int BV> __device__ __forceinline__ u32x4 unpack_v(const uint32_t* w, int dt) {
   u32x4 a;
-  if (BV == 2) {
+  if (BV == 16) {
+    a = u32x4{w[4 * dt], w[4 * dt + 1], w[4 * dt + 2], w[4 * dt + 3]};
+  } else if (BV == 2) {
     const uint32_t ws = w[dt >> 1] >> (8 * (dt & 1));
     a = u32x4{ws & 0x00030003u, ws & 0x000C000Cu, ws & 0x00300030u, ws & 0x00C000C0u};
   } else if (BV == 4) {
@@ -99,7 +111,7 @@ template <int BV> __device__ __forceinline__ half8 unpack_v(const uint32_t* w, i
     const uint32_t w0 = w[2 * dt], w1 = w[2 * dt + 1];
     a = u32x4{w0 & 0x00FF00FFu, (w0 >> 8) & 0x00FF00FFu, w1 & 0x00FF00FFu, (w1 >> 8) & 0x00FF00FFu};
   }
-  return as_half8(a);
+  return a;
 }
 
 #ifndef KVQ_STAGES
@@ -108,6 +120,14 @@ template <int BV> __device__ __forceinline__ half8 unpack_v(const uint32_t* w, i
 #ifndef KVQ_WAVES_PER_SIMD
 #define KVQ_WAVES_PER_SIMD 2   // occupancy the register allocation is held to
 #endif
+
+// Ring depth per instantiation: a step costs 2 b_K + 2 b_V + 4 registers per lane (and the scheduler wants room to
+// start a refill before the old contents are dead); deeper rings for the narrow formats, one step for unquantized.
+template <int BK, int BV>
+constexpr int ring_stages() {
+  constexpr int regs = 2 * BK + 2 * BV + 4;
+  return regs <= 16 ? KVQ_STAGES : regs <= 20 ? 3 : regs <= 40 ? 2 : 1;
+}
 
 // Everything one lane loads for one 32-token step (two 16-token tiles).
 template <int BK, int BV>
@@ -183,19 +203,29 @@ __device__ __forceinline__ void mix_hi(uint32_t& dst, float p, uint32_t meta) {
   asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "+v"(dst) : "v"(p), "v"(meta));
 }
 
+// Round-to-nearest-even bfloat16 pattern of a finite binary32.
+__device__ __forceinline__ uint32_t bf16_rne(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
 // One 32-token step.  MASKED: tokens at or beyond seq_len get weight 0 (garbage may sit there).
-template <int BK, int BV, int R, bool MASKED>
-__device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const half8 (&qb)[4], float qsum_u, float kappa,
+// BK == BV == 16 is the unquantized cache: no scale/zero, operands are the stored patterns (BF: bfloat16).
+template <int BK, int BV, int R, bool BF, bool MASKED>
+__device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u32x4 (&qb)[4], float qsum_u, float kappa,
                                              WaveState& st, const LaneCtx& L, int step, int seq_len) {
-  // scale/zero bytes: plane order -> LDS -> the entries this lane needs (tokens 4j..4j+3 of both tiles, own group)
-  if (L.meta_lane) *reinterpret_cast<u32x4*>(L.meta_lds + L.lane * 16) = r.meta;
+  constexpr bool RAW = BK == 16;
   uint32_t kmeta[8], vmeta[8];
+  if constexpr (!RAW) {
+    // scale/zero bytes: plane order -> LDS -> the entries this lane needs (tokens 4j..4j+3 of both tiles, own group)
+    if (L.meta_lane) *reinterpret_cast<u32x4*>(L.meta_lds + L.lane * 16) = r.meta;
 #pragma unroll
-  for (int x4 = 0; x4 < 2; ++x4) {
-    const u32x4 a = *reinterpret_cast<const u32x4*>(L.meta_lds + L.km_rd + x4 * (64 * L.ngk));
-    const u32x4 b = *reinterpret_cast<const u32x4*>(L.meta_lds + L.vm_rd + x4 * (64 * L.ngv));
-    kmeta[4 * x4 + 0] = a.x; kmeta[4 * x4 + 1] = a.y; kmeta[4 * x4 + 2] = a.z; kmeta[4 * x4 + 3] = a.w;
-    vmeta[4 * x4 + 0] = b.x; vmeta[4 * x4 + 1] = b.y; vmeta[4 * x4 + 2] = b.z; vmeta[4 * x4 + 3] = b.w;
+    for (int x4 = 0; x4 < 2; ++x4) {
+      const u32x4 a = *reinterpret_cast<const u32x4*>(L.meta_lds + L.km_rd + x4 * (64 * L.ngk));
+      const u32x4 b = *reinterpret_cast<const u32x4*>(L.meta_lds + L.vm_rd + x4 * (64 * L.ngv));
+      kmeta[4 * x4 + 0] = a.x; kmeta[4 * x4 + 1] = a.y; kmeta[4 * x4 + 2] = a.z; kmeta[4 * x4 + 3] = a.w;
+      vmeta[4 * x4 + 0] = b.x; vmeta[4 * x4 + 1] = b.y; vmeta[4 * x4 + 2] = b.z; vmeta[4 * x4 + 3] = b.w;
+    }
   }
 
   // ---- scores: slot i = token 16*(i/4) + 4*j + i%4 of this step
@@ -204,13 +234,14 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const ha
     float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int m = 0; m < 4; ++m) {                // two independent accumulation chains
-      d0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_k<BK>(r.kc[0], m), qb[m], d0, 0, 0, 0);
-      d1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_k<BK>(r.kc[1], m), qb[m], d1, 0, 0, 0);
+      d0 = mma<BF>(unpack_k<BK>(r.kc[0], m), qb[m], d0);
+      d1 = mma<BF>(unpack_k<BK>(r.kc[1], m), qb[m], d1);
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float d = i < 4 ? d0[i & 3] : d1[i & 3];
-      const float part = fmaf(d, meta_scale(kmeta[i]), meta_zero(kmeta[i]) * qsum_u);
+      float part = d;
+      if constexpr (!RAW) part = fmaf(d, meta_scale(kmeta[i]), meta_zero(kmeta[i]) * qsum_u);
       s[i] = sum_over_groups<R>(part);
     }
   }
@@ -237,22 +268,40 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const ha
     }
     st.m = m_new;
   }
-  // ---- softmax weights, their binary16 products with the value scale, and the value-zero term
-  uint32_t pw[4];
+  // ---- softmax weights; quantized values: their binary16 products with the value scale, and the value-zero term
+  uint32_t pw[4], pl[4];                         // pl: low-order bfloat16 part of the weights (bfloat16 cache only)
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int v = i >> 1;
     float p = __builtin_amdgcn_exp2f(fmaf(s[i], kappa, st.noff[v]));
-    uint32_t vm = vmeta[i];
-    if (MASKED && !valid[i]) { p = 0.f; vm = 0u; }
+    if (MASKED && !valid[i]) p = 0.f;
     st.l[v] += p;
-    st.zacc[v] = fmaf(p, meta_zero(vm), st.zacc[v]);
-    if (i & 1) mix_hi(pw[v], p, vm); else mix_lo(pw[v], p, vm);
+    if constexpr (!RAW) {
+      uint32_t vm = vmeta[i];
+      if (MASKED && !valid[i]) vm = 0u;
+      st.zacc[v] = fmaf(p, meta_zero(vm), st.zacc[v]);
+      if (i & 1) mix_hi(pw[v], p, vm); else mix_lo(pw[v], p, vm);
+    } else if constexpr (!BF) {
+      if (i & 1) mix_hi(pw[v], p, 0x3C00u); else mix_lo(pw[v], p, 0x3C00u);    // times binary16 1.0
+    } else {
+      // bfloat16 keeps 8 bits: carry the weight as two bfloat16 terms (16 bits) and multiply the values by both
+      const uint32_t hi = bf16_rne(p);
+      const uint32_t lo = bf16_rne(p - __uint_as_float(hi << 16));
+      if (i & 1) { pw[v] |= hi << 16; pl[v] |= lo << 16; } else { pw[v] = hi; pl[v] = lo; }
+    }
   }
-  const half8 pb = as_half8(u32x4{pw[0], pw[1], pw[2], pw[3]});
+  const u32x4 pb = u32x4{pw[0], pw[1], pw[2], pw[3]};
 #pragma unroll
-  for (int dt = 0; dt < 8; ++dt)
-    st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack_v<BV>(r.vc, dt), pb, st.acc[dt], 0, 0, 0);
+  for (int dt = 0; dt < 8; ++dt) {
+    u32x4 a = unpack_v<BV>(r.vc, dt);
+    if constexpr (RAW && MASKED) {               // unquantized garbage may be Inf/NaN: clear the slots beyond seq_len
+      uint32_t* aw = reinterpret_cast<uint32_t*>(&a);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) aw[v] &= (valid[2 * v] ? 0x0000FFFFu : 0u) | (valid[2 * v + 1] ? 0xFFFF0000u : 0u);
+    }
+    st.acc[dt] = mma<BF>(a, pb, st.acc[dt]);
+    if constexpr (RAW && BF) st.acc[dt] = mma<BF>(a, u32x4{pl[0], pl[1], pl[2], pl[3]}, st.acc[dt]);
+  }
 }
 
 // Record layout in the workspace: [b][hq][split] x (kHeadDim + 4) floats = acc[128], m, l, 0, 0.
@@ -333,8 +382,11 @@ __device__ __forceinline__ void append_one_values(const DecodeArgs& a, int bh, i
   blk[dw] = w;
 }
 
-template <int BK, int BV, int R, int NW>
+template <int BK, int BV, int R, int NW, bool BF>
 __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(const DecodeArgs a) {
+  constexpr bool RAW = BK == 16;
+  constexpr int kStages = ring_stages<BK, BV>();
+  constexpr float kUnit = RAW ? 1.0f : kCodeUnit, kInvUnit = RAW ? 1.0f : kInvCodeUnit;
   __shared__ float sm_o[NW][R][kHeadDim];
   __shared__ float sm_m[NW][R], sm_l[NW][R];
   __shared__ __attribute__((aligned(16))) uint16_t sm_q[R][kHeadDim];
@@ -367,7 +419,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   {
     const int nk = 8 * g.ng_k, nv = 8 * g.ng_v;
     const bool is_k = lane < nk;
-    L.meta_lane = lane < nk + nv;
+    L.meta_lane = !RAW && lane < nk + nv;
     L.meta_base = is_k ? (const uint8_t*)cache.k_meta + (int64_t)bh * g.km_stream
                        : (const uint8_t*)cache.v_meta + (int64_t)bh * g.vm_stream;
     L.meta_mul = 128 * (is_k ? g.ng_k : g.ng_v);
@@ -389,19 +441,21 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   const int n_full = own_tail ? n_my - 1 : n_my;   // complete steps of this wavefront
   // fused decode step: the owner of the last step writes the new token first.  When the ring's first loads cannot
   // reach that step they are started before the (short) quantization, otherwise after it.
-  const bool do_append = a.k_new != nullptr && split == n_splits - 1;
-  const bool early = !do_append || n_my > KVQ_STAGES;
-  // register ring of KVQ_STAGES steps
-  StepRegs<BK, BV> buf[KVQ_STAGES];
+  const bool do_append = !RAW && a.k_new != nullptr && split == n_splits - 1;
+  const bool early = !do_append || n_my > kStages;
+  // register ring of kStages steps
+  StepRegs<BK, BV> buf[kStages];
   if (early) {
 #pragma unroll
-    for (int k = 0; k < KVQ_STAGES; ++k)
+    for (int k = 0; k < kStages; ++k)
       if (k < n_full) load_step<BK, BV>(buf[k], L, step_of(k));
   }
   if (do_append) {                                 // uniform over the workgroup
-    append_one<BK, BV>(a, bh, b, hk, tid, sm_vnew);
-    __syncthreads();
-    append_one_values<BV>(a, bh, tid, sm_vnew);
+    if constexpr (!RAW) {
+      append_one<BK, BV>(a, bh, b, hk, tid, sm_vnew);
+      __syncthreads();
+      append_one_values<BV>(a, bh, tid, sm_vnew);
+    }
     __threadfence_block();                         // writer and readers share this workgroup: a workgroup-scope
                                                    // release is enough (no L2 write-back/invalidate across XCDs)
   }
@@ -413,14 +467,14 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   __syncthreads();
   if (!early) {
 #pragma unroll
-    for (int k = 0; k < KVQ_STAGES; ++k)
+    for (int k = 0; k < kStages; ++k)
       if (k < n_full) load_step<BK, BV>(buf[k], L, step_of(k));
   }
   auto widen = [&](uint16_t bits) -> float {
     return q_bf16 ? __uint_as_float((uint32_t)bits << 16) : (float)__builtin_bit_cast(_Float16, bits);
   };
   // column c carries head h restricted to key group gk (zero elsewhere); this lane's 32 channels are 32j..32j+31
-  half8 qb[4];
+  u32x4 qb[4];
   float qsum = 0.f;
   {
     const bool mine = act_k && ((32 * L.j) / g.g_k == L.gk);   // the 32 channels lie in one group
@@ -433,11 +487,19 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       for (int e = 0; e < 8; ++e) mych[8 * k + e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
     }
 #pragma unroll
-    for (int m = 0; m < 4; ++m)
+    for (int m = 0; m < 4; ++m) {
+      uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
-        qb[m][i] = (_Float16)(mine ? widen(mych[k_slot_elem<BK>(m, i)]) / k_slot_scale<BK>(i) : 0.f);
-    if (act_k) {
+      for (int i = 0; i < 8; ++i) {
+        const uint16_t bits = mych[k_slot_elem<BK>(m, i)];
+        uint32_t e;                                // unquantized: the query's own 16-bit pattern (same type as the cache)
+        if constexpr (RAW) e = bits;
+        else e = __builtin_bit_cast(uint16_t, (_Float16)(widen(bits) / k_slot_scale<BK>(i)));
+        if (mine) w[i >> 1] |= e << (16 * (i & 1));
+      }
+      qb[m] = u32x4{w[0], w[1], w[2], w[3]};
+    }
+    if (act_k && !RAW) {
 #pragma unroll
       for (int c8 = 0; c8 < 16; ++c8) {
         if ((8 * c8) / g.g_k != L.gk) continue;
@@ -448,8 +510,8 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       }
     }
   }
-  const float qsum_u = qsum * kCodeUnit;
-  const float kappa = softmax_scale * kLog2e * kInvCodeUnit;
+  const float qsum_u = qsum * kUnit;
+  const float kappa = softmax_scale * kLog2e * kInvUnit;
 
   WaveState st;
 #pragma unroll
@@ -458,22 +520,22 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
 #pragma unroll
   for (int v = 0; v < 4; ++v) { st.l[v] = 0.f; st.zacc[v] = 0.f; st.noff[v] = 0.f; }
 
-  // ---- main loop, unrolled over the ring: compute a step, then refill its registers with the step KVQ_STAGES
-  // ahead, so that KVQ_STAGES-1 steps of loads are always in flight behind the one being computed.
+  // ---- main loop, unrolled over the ring: compute a step, then refill its registers with the step kStages
+  // ahead, so that kStages-1 steps of loads are always in flight behind the one being computed.
   int it = 0;
-  for (; it + KVQ_STAGES <= n_full; it += KVQ_STAGES) {
+  for (; it + kStages <= n_full; it += kStages) {
 #pragma unroll
-    for (int k = 0; k < KVQ_STAGES; ++k) {
-      compute_step<BK, BV, R, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(it + k), seq_len);
-      if (it + k + KVQ_STAGES < n_full) load_step<BK, BV>(buf[k], L, step_of(it + k + KVQ_STAGES));
+    for (int k = 0; k < kStages; ++k) {
+      compute_step<BK, BV, R, BF, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(it + k), seq_len);
+      if (it + k + kStages < n_full) load_step<BK, BV>(buf[k], L, step_of(it + k + kStages));
     }
   }
 #pragma unroll
-  for (int k = 0; k < KVQ_STAGES - 1; ++k)         // the last few complete steps are already in the ring
-    if (it + k < n_full) compute_step<BK, BV, R, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(it + k), seq_len);
+  for (int k = 0; k < kStages - 1; ++k)         // the last few complete steps are already in the ring
+    if (it + k < n_full) compute_step<BK, BV, R, BF, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(it + k), seq_len);
   if (own_tail) {                                 // ragged last step of the sequence: masked
     load_step<BK, BV>(buf[0], L, n_steps - 1);
-    compute_step<BK, BV, R, true>(buf[0], qb, qsum_u, kappa, st, L, n_steps - 1, seq_len);
+    compute_step<BK, BV, R, BF, true>(buf[0], qb, qsum_u, kappa, st, L, n_steps - 1, seq_len);
   }
 
   // ---- wavefront totals: l and zacc over register classes and the 4 lane groups j
@@ -493,7 +555,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
         float a = 0.f;
 #pragma unroll
         for (int k = 0; k < 8; ++k) if (k == dt) a = st.acc[k][rr];   // static register indexing
-        sm_o[wave][h][16 * dt + 4 * L.j + rr] = fmaf(a, kInvCodeUnit, z);
+        sm_o[wave][h][16 * dt + 4 * L.j + rr] = fmaf(a, kInvUnit, z);
       }
     if (grp == 0 && L.j == 0) { sm_m[wave][h] = st.m; sm_l[wave][h] = l; }
   }
@@ -552,24 +614,24 @@ __global__ __launch_bounds__(128) void merge_kernel(const float* __restrict__ ws
   }
 }
 
-template <int BK, int BV, int R>
+template <int BK, int BV, int R, bool BF = false>
 hipError_t launch_one(const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream) {
   dim3 grid(plan.n_splits, a.g.batch * a.g.kv_heads);
-  if (plan.waves_per_wg == 8) hipLaunchKernelGGL((decode_kernel<BK, BV, R, 8>), grid, dim3(512), 0, stream, a);
-  else hipLaunchKernelGGL((decode_kernel<BK, BV, R, 4>), grid, dim3(256), 0, stream, a);
+  if (plan.waves_per_wg == 8) hipLaunchKernelGGL((decode_kernel<BK, BV, R, 8, BF>), grid, dim3(512), 0, stream, a);
+  else hipLaunchKernelGGL((decode_kernel<BK, BV, R, 4, BF>), grid, dim3(256), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || plan.n_splits == 1) return e;
   hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128), 0, stream, a.ws, a.out, a.out_dtype, plan.n_splits);
   return hipGetLastError();
 }
 
-template <int BK, int BV>
+template <int BK, int BV, bool BF = false>
 hipError_t launch_r(int R, const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream) {
   switch (R) {
-    case 1: return launch_one<BK, BV, 1>(a, plan, stream);
-    case 2: return launch_one<BK, BV, 2>(a, plan, stream);
-    case 4: return launch_one<BK, BV, 4>(a, plan, stream);
-    case 8: return launch_one<BK, BV, 8>(a, plan, stream);
+    case 1: return launch_one<BK, BV, 1, BF>(a, plan, stream);
+    case 2: return launch_one<BK, BV, 2, BF>(a, plan, stream);
+    case 4: return launch_one<BK, BV, 4, BF>(a, plan, stream);
+    case 8: return launch_one<BK, BV, 8, BF>(a, plan, stream);
   }
   return hipErrorInvalidValue;
 }
@@ -579,7 +641,7 @@ hipError_t launch_r(int R, const DecodeArgs& a, const DecodePlan& plan, hipStrea
 bool decode_supported(const Geom& g, int32_t q_heads) {
   const int R = q_heads / g.kv_heads;
   if (R != 1 && R != 2 && R != 4 && R != 8) return false;
-  if (g.bits_k == 16 || g.bits_v == 16) return false;          // unquantized planes: no kernel yet
+  if ((g.bits_k == 16) != (g.bits_v == 16)) return false;      // one tensor unquantized, the other not: no kernel
   if (R * g.ng_k > 16 || R * g.ng_v > 16) return false;        // head x group columns must fit one 16-wide tile
   return true;
 }
@@ -630,6 +692,8 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
   KVQ_CASE(4, 8)
   KVQ_CASE(2, 8)
 #undef KVQ_CASE
+  if (g.bits_k == 16 && g.bits_v == 16)
+    return g.raw_dtype == KVQ_BF16 ? launch_r<16, 16, true>(R, a, plan, stream) : launch_r<16, 16, false>(R, a, plan, stream);
   return hipErrorInvalidValue;
 }
 

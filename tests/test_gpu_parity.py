@@ -204,6 +204,29 @@ def test_attention_ignores_garbage_beyond_seq_len(kvq, oracle):
     assert np.isfinite(out).all() and _rel_err(out, ref) < TOL
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("R", [1, 4, 8])
+def test_unquantized_cache_attention(kvq, oracle, dtype, R):
+    """bits = 16 (the full-precision baseline of the bit-allocation sweep): plain attention on the stored tensors.
+    Planes start as 0xFF bytes (NaN patterns) so that nothing beyond seq_len may leak in."""
+    B, H, T = 2, 2, 205
+    K, V, q = synth.make_kvq(40 + R, B, H, H * R, T, dtype=dtype)
+    raw = 1 if dtype == torch.bfloat16 else 0
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, 16, 16, 64, 64, raw=raw)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, 100), (100, T)], fill=0xFF)
+    _assert_planes_equal(cache, planes)
+    for seq_len in (T, 192, 33, 1):
+        out = _decode(kvq, Lg, cache, q, seq_len).cpu().numpy()
+        ref = oracle.decode_attention(Lo, planes, synth.to_numpy_bits(q), seq_len, 1 / math.sqrt(128), bf16=bool(raw))
+        assert np.isfinite(out).all()
+        assert _rel_err(out, ref) < TOL, seq_len
+    # and it is the textbook routine on the original tensors
+    want = torch.nn.functional.scaled_dot_product_attention(
+        q.double()[:, :, None, :], K.double().repeat_interleave(R, dim=1), V.double().repeat_interleave(R, dim=1),
+        scale=1 / math.sqrt(128))[:, :, 0].numpy()
+    assert _rel_err(_decode(kvq, Lg, cache, q, T).cpu().numpy(), want) < TOL
+
+
 def test_half_precision_outputs_round_once(kvq, oracle):
     B, H, R, T = 1, 2, 4, 128
     K, V, q = synth.make_kvq(9, B, H, H * R, T, dtype=torch.bfloat16)
