@@ -11,15 +11,31 @@
 namespace kvq {
 namespace {
 
-constexpr int kLdsPitch = kHeadDim + 2;  // uint16 elements per staged value row (odd dword pitch)
 constexpr int kSpan = 64;                // tokens one workgroup covers (two 32-token value blocks)
 
+// LDS staging of the value codes of one span, already in storage order: one element per code, the F = 32/b_V codes
+// of an output word adjacent (so a word is assembled from one wide LDS read), 16 bytes of padding after every 256
+// to spread the strided writes of the quantizing lanes over the banks.
+__device__ __forceinline__ int stage_phys(int a) { return a + ((a >> 8) << 4); }
+
+// Pack the codes held one per byte in w (first code in the lowest byte) into adjacent b-bit fields.
+// (Bytes of tokens that were not staged hold garbage: they are masked to b bits so that they stay inside their field.)
+template <int B> __device__ __forceinline__ uint32_t pack_bytes(uint32_t w) {
+  if (B == 2) { w &= 0x03030303u; return (w | (w >> 6) | (w >> 12) | (w >> 18)) & 0xFFu; }
+  if (B == 4) return (w & 0xFu) | ((w >> 4) & 0xF0u) | ((w >> 8) & 0xF00u) | ((w >> 12) & 0xF000u);
+  return w;
+}
+
 // One workgroup = one 64-token span of one (b,h) stream, restricted to the new tokens in it.
+template <int BK, int BV, bool BF>
 __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_new,
-                                                              const uint16_t* __restrict__ v_new, int in_bf16,
-                                                              int64_t sb, int64_t sh, int64_t st, int32_t pos,
-                                                              int32_t n_new) {
-  __shared__ uint16_t vstage[kSpan * kLdsPitch];
+                                                              const uint16_t* __restrict__ v_new, int64_t sb, int64_t sh,
+                                                              int64_t st, int32_t pos, int32_t n_new) {
+  constexpr int F = 32 / BV;                      // codes per 32-bit word of the value plane
+  constexpr int P = 16 / BV;
+  constexpr int ES = BV == 16 ? 2 : 1;            // bytes per staged element
+  constexpr int kStageBytes = kSpan * kHeadDim * ES;
+  __shared__ __attribute__((aligned(16))) uint8_t vstage[kStageBytes + (kStageBytes >> 4)];
   const int tid = threadIdx.x;
   const int bh = blockIdx.y;
   const int b = bh / g.kv_heads, h = bh % g.kv_heads;
@@ -32,95 +48,121 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
   uint8_t* kc = (uint8_t*)c.k_codes + (int64_t)bh * g.kc_stream;
   uint32_t* km = (uint32_t*)((uint8_t*)c.k_meta + (int64_t)bh * g.km_stream);
   uint32_t* vm = (uint32_t*)((uint8_t*)c.v_meta + (int64_t)bh * g.vm_stream);
-  uint32_t* vc = (uint32_t*)((uint8_t*)c.v_codes + (int64_t)bh * g.vc_stream) + (int64_t)blk * (256 * g.bits_v);
+  uint32_t* vc = (uint32_t*)((uint8_t*)c.v_codes + (int64_t)bh * g.vc_stream) + (int64_t)blk * (256 * BV);
 
-  for (int row = lo + (tid >> 4); row < hi; row += 16) {
+  // each thread owns 8 channels of rows (tid/16) + 16*it, it = 0..3: issue all eight 16-byte loads, then quantize
+  uint4 kraw[4], vraw[4];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int row = (tid >> 4) + 16 * it;
+    if (row >= lo && row < hi) {
+      const int64_t src = (int64_t)b * sb + (int64_t)h * sh + ((int64_t)blk * kSpan + row - pos) * st + d0;
+      kraw[it] = *reinterpret_cast<const uint4*>(k_new + src);
+      vraw[it] = *reinterpret_cast<const uint4*>(v_new + src);
+    }
+  }
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int row = (tid >> 4) + 16 * it;
+    if (row < lo || row >= hi) continue;           // whole 16-lane rows take the same branch
     const int64_t t = (int64_t)blk * kSpan + row;
-    const int64_t src = (int64_t)b * sb + (int64_t)h * sh + (t - pos) * st + d0;
     // ---- keys: row-major codes
     {
-      uint4 raw = *reinterpret_cast<const uint4*>(k_new + src);
+      const uint4 raw = kraw[it];
       const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
-      if (g.bits_k == 16) {
+      if (BK == 16) {
         *reinterpret_cast<uint4*>(kc + t * 256 + d0 * 2) = raw;
       } else {
         float x[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), in_bf16);
+        for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
         uint32_t codes[8];
         uint16_t S, Z;
         const int lpg = g.g_k >> 3;
-        quantize8(x, g.bits_k, lpg, codes, &S, &Z);
+        quantize8(x, BK, lpg, codes, &S, &Z);
         if ((lane16 & (lpg - 1)) == 0) km[meta_index(t, lane16 / lpg, g.ng_k)] = (uint32_t)S | ((uint32_t)Z << 16);
-        uint8_t* rowp = kc + t * (16 * g.bits_k);
-        if (g.bits_k == 4) {
-          uint32_t w = 0;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) w |= codes[e] << (4 * e);
-          reinterpret_cast<uint32_t*>(rowp)[lane16] = w;
-        } else if (g.bits_k == 2) {
-          uint32_t w = 0;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) w |= codes[e] << (2 * e);
-          reinterpret_cast<uint16_t*>(rowp)[lane16] = (uint16_t)w;
-        } else {
+        uint8_t* rowp = kc + t * (16 * BK);
+        if (BK == 8) {
           uint32_t w0 = codes[0] | (codes[1] << 8) | (codes[2] << 16) | (codes[3] << 24);
           uint32_t w1 = codes[4] | (codes[5] << 8) | (codes[6] << 16) | (codes[7] << 24);
           reinterpret_cast<uint2*>(rowp)[lane16] = make_uint2(w0, w1);
+        } else {
+          uint32_t w = 0;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) w |= codes[e] << (BK * e);
+          if (BK == 4) reinterpret_cast<uint32_t*>(rowp)[lane16] = w;
+          else reinterpret_cast<uint16_t*>(rowp)[lane16] = (uint16_t)w;
         }
       }
     }
-    // ---- values: codes staged in LDS, scale/zero straight to memory
+    // ---- values: scale/zero straight to memory, codes to their place in the staged words
     {
-      uint4 raw = *reinterpret_cast<const uint4*>(v_new + src);
+      const uint4 raw = vraw[it];
       const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
-      uint16_t* dst = vstage + row * kLdsPitch + d0;
-      if (g.bits_v == 16) {
+      uint32_t codes[8];
+      if (BV == 16) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) dst[e] = (uint16_t)(rw[e >> 1] >> (16 * (e & 1)));
+        for (int e = 0; e < 8; ++e) codes[e] = (rw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
       } else {
         float x[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), in_bf16);
-        uint32_t codes[8];
+        for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
         uint16_t S, Z;
         const int lpg = g.g_v >> 3;
-        quantize8(x, g.bits_v, lpg, codes, &S, &Z);
+        quantize8(x, BV, lpg, codes, &S, &Z);
         if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 / lpg, g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
+      }
+      // token row -> (block, word family, field): the 8 channels of this lane go to 8 words 4 apart
+      const int sub = row >> 5, u = row & 31;
+      const int j = (u >> 2) & 3, i = 4 * (u >> 4) + (u & 3);
+      const int x = i & 1, v = i >> 1;
+      const int q = 4 * (d0 >> 4) + v;
+      const int e_idx = q / P, p = q % P;
+      const int word0 = sub * (128 * BV) + (e_idx >> 2) * 256 + (16 * j + (d0 & 15)) * 4 + (e_idx & 3);
+      const int a0 = (word0 * F + x * P + p) * ES;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) dst[e] = (uint16_t)codes[e];
+      for (int e = 0; e < 8; ++e) {
+        const int a = stage_phys(a0 + e * 4 * F * ES);
+        if (BV == 16) *reinterpret_cast<uint16_t*>(vstage + a) = (uint16_t)codes[e];
+        else vstage[a] = (uint8_t)codes[e];
       }
     }
   }
   __syncthreads();
 
-  // ---- values: assemble the span's dwords (two 32-token blocks) in storage order; keep the fields of other tokens
-  const int bv = g.bits_v;
-  const int P = 16 / bv;
-  const uint32_t fmask = bv == 16 ? 0xFFFFu : ((1u << bv) - 1u);
-  const int blk_dwords = 128 * bv;
-  for (int w = tid; w < 2 * blk_dwords; w += 256) {
-    const int sub = w / blk_dwords, wi = w % blk_dwords;
+  // ---- values: one thread per 32-bit word of the span (two blocks of 128*BV words)
+  const bool full = lo == 0 && hi == kSpan;
+  for (int w = tid; w < 256 * BV; w += 256) {
+    const uint8_t* sp = vstage + stage_phys(w * F * ES);
+    uint32_t bits;
+    if (BV == 2) {
+      const uint4 r = *reinterpret_cast<const uint4*>(sp);
+      bits = pack_bytes<2>(r.x) | (pack_bytes<2>(r.y) << 8) | (pack_bytes<2>(r.z) << 16) | (pack_bytes<2>(r.w) << 24);
+    } else if (BV == 4) {
+      const uint2 r = *reinterpret_cast<const uint2*>(sp);
+      bits = pack_bytes<4>(r.x) | (pack_bytes<4>(r.y) << 16);
+    } else {
+      bits = *reinterpret_cast<const uint32_t*>(sp);            // 8-bit: four codes; 16-bit: two patterns
+    }
+    if (full) { vc[w] = bits; continue; }
+    // partially covered span: keep the fields of tokens outside [lo, hi)
+    const int sub = w / (128 * BV), wi = w % (128 * BV);
     const int piece = wi >> 8, rem = wi & 255;
     const int L = rem >> 2, m = rem & 3;
-    const int e = 4 * piece + m;
-    const int j = L >> 4, dl = L & 15;
-    uint32_t bits = 0, mask = 0;
+    const int e_idx = 4 * piece + m;
+    const int j = L >> 4;
+    const uint32_t fmask = BV == 16 ? 0xFFFFu : ((1u << BV) - 1u);
+    uint32_t mask = 0;
     for (int x = 0; x < 2; ++x)
       for (int p = 0; p < P; ++p) {
-        const int q = e * P + p;
-        const int dt = q >> 2, v = q & 3;
+        const int q = e_idx * P + p;
+        const int v = q & 3;
         const int i = 2 * v + x;
         const int tt = 32 * sub + 16 * (i >> 2) + 4 * j + (i & 3);
-        if (tt >= lo && tt < hi) {
-          const int sh_ = 16 * x + bv * p;
-          bits |= ((uint32_t)vstage[tt * kLdsPitch + dt * 16 + dl] & fmask) << sh_;
-          mask |= fmask << sh_;
-        }
+        if (tt >= lo && tt < hi) mask |= fmask << (16 * x + BV * p);
       }
     if (mask == 0) continue;
-    if (mask != 0xFFFFFFFFu) bits |= vc[w] & ~mask;
-    vc[w] = bits;
+    vc[w] = (bits & mask) | (vc[w] & ~mask);
   }
 }
 
@@ -184,14 +226,43 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Geom g, kvq_cache c, in
 
 }  // namespace
 
+namespace {
+template <int BK, int BV>
+hipError_t launch_q(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype, int64_t sb,
+                    int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
+  const int first = pos / kSpan, last = (pos + n_new - 1) / kSpan;
+  dim3 grid(last - first + 1, g.batch * g.kv_heads);
+  if (in_dtype == KVQ_BF16)
+    hipLaunchKernelGGL((quantize_append_kernel<BK, BV, true>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
+                       (const uint16_t*)v_new, sb, sh, st, pos, n_new);
+  else
+    hipLaunchKernelGGL((quantize_append_kernel<BK, BV, false>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
+                       (const uint16_t*)v_new, sb, sh, st, pos, n_new);
+  return hipGetLastError();
+}
+template <int BK>
+hipError_t launch_qk(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype, int64_t sb,
+                     int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
+  switch (g.bits_v) {
+    case 2: return launch_q<BK, 2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 4: return launch_q<BK, 4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 8: return launch_q<BK, 8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 16: return launch_q<BK, 16>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+  }
+  return hipErrorInvalidValue;
+}
+}  // namespace
+
 hipError_t launch_quantize_append(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype,
                                   int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
   if (n_new == 0) return hipSuccess;
-  const int first = pos / kSpan, last = (pos + n_new - 1) / kSpan;
-  dim3 grid(last - first + 1, g.batch * g.kv_heads);
-  hipLaunchKernelGGL(quantize_append_kernel, grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
-                     (const uint16_t*)v_new, in_dtype == KVQ_BF16 ? 1 : 0, sb, sh, st, pos, n_new);
-  return hipGetLastError();
+  switch (g.bits_k) {
+    case 2: return launch_qk<2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 4: return launch_qk<4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 8: return launch_qk<8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 16: return launch_qk<16>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+  }
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_dequantize(const Geom& g, const kvq_cache& c, int32_t t0, int32_t t1, void* k_out, void* v_out,
