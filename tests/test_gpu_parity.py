@@ -319,3 +319,53 @@ def test_error_codes_on_device(kvq):
     with pytest.raises(kvq.KvqError) as e:
         kvq.decode_step(L, cache, k[:, :, 0], k[:, :, 0], 100, q, 0.1, out, None)
     assert e.value.status == kvq.ERR_CAPACITY
+
+
+# --------------------------------------------------------------------------- full benchmark sizes, sampled streams
+
+def _check_sampled_streams(kvq, oracle, B, Hq, Hkv, T, seed, sigma_k, samples, fused=True):
+    """Fill a full-size K4V2 G=64 cache on the GPU exactly as bench.py does (chunks of 2048, last token through the
+    fused step), then compare a few (batch, kv head) streams with the oracle: plane bytes identical, output within TOL."""
+    D, G, R = 128, 64, Hq // Hkv
+    K, V, q = synth.make_kvq(seed, B, Hkv, Hq, T, D, dtype=torch.bfloat16, sigma_k=sigma_k, device="cuda")
+    Lg = kvq.Layout(B, Hkv, T, D, 4, 2, G, G)
+    cache = kvq.Cache(Lg, fill=0)                      # unwritten capacity beyond T compares equal to the oracle's zeros
+    for a in range(0, T - 1, 2048):
+        e = min(a + 2048, T - 1)
+        kvq.quantize_append(Lg, cache, K[:, :, a:e], V[:, :, a:e], a)
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, Hq, T)), dtype=torch.uint8, device="cuda")
+    out = torch.empty(B, Hq, D, dtype=torch.float32, device="cuda")
+    if fused:
+        kvq.decode_step(Lg, cache, K[:, :, T - 1], V[:, :, T - 1], T - 1, q, 1 / math.sqrt(D), out, ws)
+    else:
+        kvq.quantize_append(Lg, cache, K[:, :, T - 1:], V[:, :, T - 1:], T - 1)
+        kvq.decode_attention(Lg, cache, q, T, 1 / math.sqrt(D), out, ws)
+    torch.cuda.synchronize()
+    Lo = oracle.Layout(1, 1, T, D, 4, 2, G, G)
+    worst = 0.0
+    for b, h in samples:
+        planes = oracle.new_planes(Lo)
+        oracle.quantize_append(Lo, planes, synth.to_numpy_bits(K[b:b + 1, h:h + 1]), synth.to_numpy_bits(V[b:b + 1, h:h + 1]), 0, bf16=True)
+        for name, gp, op in zip(("k_codes", "k_meta", "v_codes", "v_meta"), cache.planes, planes):
+            got = gp.view(B * Hkv, -1)[b * Hkv + h].cpu().numpy()
+            assert np.array_equal(got, op), (name, b, h)
+        ref = oracle.decode_attention(Lo, planes, synth.to_numpy_bits(q[b:b + 1, h * R:(h + 1) * R]), T, 1 / math.sqrt(D), bf16=True)
+        worst = max(worst, _rel_err(out[b:b + 1, h * R:(h + 1) * R].cpu().numpy(), ref))
+    assert worst < TOL, worst
+
+
+def test_full_size_70b_layer_sampled_streams(kvq, oracle):
+    """BASELINE configs[3] as bench.py launches it (B=32, 64 query / 8 KV heads, context 32768): one 8-wavefront
+    workgroup per stream, no sequence split, fused append."""
+    _check_sampled_streams(kvq, oracle, 32, 64, 8, 32768, 1000, 3.3, [(0, 0), (13, 5), (31, 7)])
+
+
+def test_full_size_8b_layer_sampled_streams(kvq, oracle):
+    """BASELINE configs[1] (B=8, 32 query / 8 KV heads, context 8192): 4 sequence splits and the merge kernel."""
+    _check_sampled_streams(kvq, oracle, 8, 32, 8, 8192, 1, 4.0, [(0, 0), (3, 6), (7, 7)])
+    _check_sampled_streams(kvq, oracle, 8, 32, 8, 8192, 1, 4.0, [(5, 2)], fused=False)
+
+
+def test_long_context_batch_1_sampled_streams(kvq, oracle):
+    """BASELINE configs[4] shape (B=1, context 131072, 32 splits per stream), ragged length on purpose."""
+    _check_sampled_streams(kvq, oracle, 1, 32, 8, 131072 - 5, 4, 4.0, [(0, 3)])
