@@ -15,27 +15,38 @@ LIB = os.path.join(HERE, "libkvq.so")
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           # packed-FP32 VALU forms are kept out of the generated code
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-          "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-attributes"]
-# translation unit -> extra flags.  The quantizer must round every operation once: no contraction.
-UNITS = {
-    "kvq_api.hip": [],
-    "kvq_quant.hip": ["-ffp-contract=off"],
-    "kvq_decode.hip": [],
-}
+          "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-attributes", "-Wno-unused-function",
+          "-Wno-unneeded-internal-declaration"]
+# (b_K, b_V) pairs with decode kernels: kvq_decode.hip is compiled once per pair (-DKVQ_INST_BK/BV: the kernels of that
+# pair) and once without (plan + dispatch), so that the instances build in parallel.
+DECODE_PAIRS = [(4, 2), (2, 4), (4, 4), (8, 8), (2, 2), (8, 4), (8, 2), (4, 8), (2, 8), (16, 16)]
+# (source, object name, extra flags).  The quantizer must round every operation once: no contraction.
+UNITS = [("kvq_api.hip", "kvq_api.o", []),
+         ("kvq_quant.hip", "kvq_quant.o", ["-ffp-contract=off"]),
+         ("kvq_decode.hip", "kvq_decode.o", [])]
+UNITS += [("kvq_decode.hip", f"kvq_decode_k{bk}v{bv}.o",
+           [f"-DKVQ_INST_BK={bk}", f"-DKVQ_INST_BV={bv}", "-Rpass-analysis=kernel-resource-usage"]) for bk, bv in DECODE_PAIRS]
 
 
 def _compile(item):
-    src, extra = item
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+    src, objname, extra = item
+    obj = os.path.join(OBJ, objname)
     cmd = ["hipcc", "-c", os.path.join(CSRC, src), "-o", obj] + COMMON + extra
     r = subprocess.run(cmd, capture_output=True, text=True)
-    return src, r.returncode, (r.stdout + r.stderr), obj
+    log = r.stdout + r.stderr
+    if r.returncode == 0 and "-Rpass-analysis=kernel-resource-usage" in extra:
+        # a decode kernel that spills would wait on scratch reloads in the middle of its load pipeline: refuse it
+        spills = [l for l in log.splitlines() if "ScratchSize [bytes/lane]:" in l and not l.rstrip().endswith(": 0")]
+        if spills:
+            return objname, 1, f"{len(spills)} decode kernel(s) use scratch memory (register spills)", obj
+        log = "\n".join(l for l in log.splitlines() if "remark:" not in l)
+    return objname, r.returncode, log, obj
 
 
 def build_lib(verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
-        results = list(ex.map(_compile, UNITS.items()))
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        results = list(ex.map(_compile, UNITS))
     objs = []
     for src, rc, log, obj in results:
         if verbose and log.strip():

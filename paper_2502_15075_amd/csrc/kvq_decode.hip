@@ -123,10 +123,12 @@ template <int BV> __device__ __forceinline__ u32x4 unpack_v(const uint32_t* w, i
 
 // Ring depth per instantiation: a step costs 2 b_K + 2 b_V + 4 registers per lane (and the scheduler wants room to
 // start a refill before the old contents are dead); deeper rings for the narrow formats, one step for unquantized.
-template <int BK, int BV>
+template <int BK, int BV, int NCK = 1, int NCV = 1>
 constexpr int ring_stages() {
   constexpr int regs = 2 * BK + 2 * BV + 4;
-  return regs <= 16 ? KVQ_STAGES : regs <= 20 ? 3 : regs <= 40 ? 2 : 1;
+  constexpr int base = regs <= 16 ? KVQ_STAGES : regs <= 20 ? 3 : regs <= 40 ? 2 : 1;
+  constexpr int less = (NCK == 2 ? 2 : 0) + (NCV == 2 ? 1 : 0);   // a second column set costs registers (query operand,
+  return base - less >= 1 ? base - less : 1;                      // scale/zero entries, weights)
 }
 
 // Everything one lane loads for one 32-token step (two 16-token tiles).
@@ -186,12 +188,13 @@ __device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L,
 __device__ __forceinline__ float meta_scale(uint32_t m) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(m & 0xFFFFu)); }
 __device__ __forceinline__ float meta_zero(uint32_t m) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(m >> 16)); }
 
+template <int NCV>
 struct WaveState {
-  float4v acc[8];   // out^T tile dt: rows d = 16*dt + 4*j + r, column c
-  float m;          // running max of this lane's head, in log2 units
-  float noff[4];    // kPShift - m - v_slot_shift(v): exponent offset of the slots in operand register v
-  float l[4];       // per register class v: this lane's share of sum_t p * 2^(kPShift - shift(v))
-  float zacc[4];    // same, weighted by zV[t, gv]
+  float4v acc[8];       // out^T tile dt: rows d = 16*dt + 4*j + r, column c
+  float m;              // running max of this lane's head, in log2 units
+  float noff[4];        // kPShift - m - v_slot_shift(v): exponent offset of the slots in operand register v
+  float l[4];           // per register class v: this lane's share of sum_t p * 2^(kPShift - shift(v))
+  float zacc[NCV][4];   // same, weighted by zV[t, g] for this lane's value group of each column set
 };
 
 // binary16 product of a binary32 weight and the binary16 held in the low half of `meta`, written to the
@@ -211,39 +214,54 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
 
 // One 32-token step.  MASKED: tokens at or beyond seq_len get weight 0 (garbage may sit there).
 // BK == BV == 16 is the unquantized cache: no scale/zero, operands are the stored patterns (BF: bfloat16).
-template <int BK, int BV, int R, bool BF, bool MASKED>
-__device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u32x4 (&qb)[4], float qsum_u, float kappa,
-                                             WaveState& st, const LaneCtx& L, int step, int seq_len) {
+// NCK / NCV: column sets.  Columns are (group, head) pairs; when R * (groups) exceeds the 16 columns of a matrix tile
+// (8 heads with 32-channel groups) the groups are spread over two column sets: set cs carries group grp + cs*(16/R).
+template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool MASKED>
+__device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u32x4 (&qb)[NCK][4], const float (&qsum_u)[NCK],
+                                             float kappa, WaveState<NCV>& st, const LaneCtx& L, int step, int seq_len) {
   constexpr bool RAW = BK == 16;
-  uint32_t kmeta[8], vmeta[8];
+  constexpr int kSetStride = (16 / R) * 64;      // bytes between the scale/zero entries of a lane's groups in two sets
+  uint32_t kmeta[NCK][8], vmeta[NCV][8];
   if constexpr (!RAW) {
-    // scale/zero bytes: plane order -> LDS -> the entries this lane needs (tokens 4j..4j+3 of both tiles, own group)
+    // scale/zero bytes: plane order -> LDS -> the entries this lane needs (tokens 4j..4j+3 of both tiles, own groups)
     if (L.meta_lane) *reinterpret_cast<u32x4*>(L.meta_lds + L.lane * 16) = r.meta;
 #pragma unroll
     for (int x4 = 0; x4 < 2; ++x4) {
-      const u32x4 a = *reinterpret_cast<const u32x4*>(L.meta_lds + L.km_rd + x4 * (64 * L.ngk));
-      const u32x4 b = *reinterpret_cast<const u32x4*>(L.meta_lds + L.vm_rd + x4 * (64 * L.ngv));
-      kmeta[4 * x4 + 0] = a.x; kmeta[4 * x4 + 1] = a.y; kmeta[4 * x4 + 2] = a.z; kmeta[4 * x4 + 3] = a.w;
-      vmeta[4 * x4 + 0] = b.x; vmeta[4 * x4 + 1] = b.y; vmeta[4 * x4 + 2] = b.z; vmeta[4 * x4 + 3] = b.w;
+#pragma unroll
+      for (int cs = 0; cs < NCK; ++cs) {
+        const u32x4 a = *reinterpret_cast<const u32x4*>(L.meta_lds + L.km_rd + cs * kSetStride + x4 * (64 * L.ngk));
+        kmeta[cs][4 * x4 + 0] = a.x; kmeta[cs][4 * x4 + 1] = a.y; kmeta[cs][4 * x4 + 2] = a.z; kmeta[cs][4 * x4 + 3] = a.w;
+      }
+#pragma unroll
+      for (int cs = 0; cs < NCV; ++cs) {
+        const u32x4 b = *reinterpret_cast<const u32x4*>(L.meta_lds + L.vm_rd + cs * kSetStride + x4 * (64 * L.ngv));
+        vmeta[cs][4 * x4 + 0] = b.x; vmeta[cs][4 * x4 + 1] = b.y; vmeta[cs][4 * x4 + 2] = b.z; vmeta[cs][4 * x4 + 3] = b.w;
+      }
     }
   }
 
   // ---- scores: slot i = token 16*(i/4) + 4*j + i%4 of this step
   float s[8];
   {
-    float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+    float part[8];
 #pragma unroll
-    for (int m = 0; m < 4; ++m) {                // two independent accumulation chains
-      d0 = mma<BF>(unpack_k<BK>(r.kc[0], m), qb[m], d0);
-      d1 = mma<BF>(unpack_k<BK>(r.kc[1], m), qb[m], d1);
+    for (int cs = 0; cs < NCK; ++cs) {
+      float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {                // two independent accumulation chains
+        d0 = mma<BF>(unpack_k<BK>(r.kc[0], m), qb[cs][m], d0);
+        d1 = mma<BF>(unpack_k<BK>(r.kc[1], m), qb[cs][m], d1);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float d = i < 4 ? d0[i & 3] : d1[i & 3];
+        float pt = d;
+        if constexpr (!RAW) pt = fmaf(d, meta_scale(kmeta[cs][i]), meta_zero(kmeta[cs][i]) * qsum_u[cs]);
+        part[i] = cs == 0 ? pt : part[i] + pt;
+      }
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float d = i < 4 ? d0[i & 3] : d1[i & 3];
-      float part = d;
-      if constexpr (!RAW) part = fmaf(d, meta_scale(kmeta[i]), meta_zero(kmeta[i]) * qsum_u);
-      s[i] = sum_over_groups<R>(part);
-    }
+    for (int i = 0; i < 8; ++i) s[i] = sum_over_groups<R>(part[i]);
   }
   bool valid[8];
 #pragma unroll
@@ -263,13 +281,15 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
     for (int dt = 0; dt < 8; ++dt) st.acc[dt] *= f;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      st.l[v] *= f; st.zacc[v] *= f;
+      st.l[v] *= f;
+#pragma unroll
+      for (int cs = 0; cs < NCV; ++cs) st.zacc[cs][v] *= f;
       st.noff[v] = kPShift - (float)v_slot_shift<BV>(v) - m_new;
     }
     st.m = m_new;
   }
   // ---- softmax weights; quantized values: their binary16 products with the value scale, and the value-zero term
-  uint32_t pw[4], pl[4];                         // pl: low-order bfloat16 part of the weights (bfloat16 cache only)
+  uint32_t pw[NCV][4], pl[4];                    // pl: low-order bfloat16 part of the weights (bfloat16 cache only)
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int v = i >> 1;
@@ -277,22 +297,27 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
     if (MASKED && !valid[i]) p = 0.f;
     st.l[v] += p;
     if constexpr (!RAW) {
-      uint32_t vm = vmeta[i];
-      if (MASKED && !valid[i]) vm = 0u;
-      st.zacc[v] = fmaf(p, meta_zero(vm), st.zacc[v]);
-      if (i & 1) mix_hi(pw[v], p, vm); else mix_lo(pw[v], p, vm);
+#pragma unroll
+      for (int cs = 0; cs < NCV; ++cs) {
+        uint32_t vm = vmeta[cs][i];
+        if (MASKED && !valid[i]) vm = 0u;
+        st.zacc[cs][v] = fmaf(p, meta_zero(vm), st.zacc[cs][v]);
+        if (i & 1) mix_hi(pw[cs][v], p, vm); else mix_lo(pw[cs][v], p, vm);
+      }
     } else if constexpr (!BF) {
-      if (i & 1) mix_hi(pw[v], p, 0x3C00u); else mix_lo(pw[v], p, 0x3C00u);    // times binary16 1.0
+      if (i & 1) mix_hi(pw[0][v], p, 0x3C00u); else mix_lo(pw[0][v], p, 0x3C00u);    // times binary16 1.0
     } else {
       // bfloat16 keeps 8 bits: carry the weight as two bfloat16 terms (16 bits) and multiply the values by both
       const uint32_t hi = bf16_rne(p);
       const uint32_t lo = bf16_rne(p - __uint_as_float(hi << 16));
-      if (i & 1) { pw[v] |= hi << 16; pl[v] |= lo << 16; } else { pw[v] = hi; pl[v] = lo; }
+      if (i & 1) { pw[0][v] |= hi << 16; pl[v] |= lo << 16; } else { pw[0][v] = hi; pl[v] = lo; }
     }
   }
-  const u32x4 pb = u32x4{pw[0], pw[1], pw[2], pw[3]};
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) {
+    constexpr int kDtPerSet = 8 / NCV;           // value groups of set 0 own the first d-tiles, of set 1 the rest
+    const int cs = dt / kDtPerSet;
+    const u32x4 pb = u32x4{pw[cs][0], pw[cs][1], pw[cs][2], pw[cs][3]};
     u32x4 a = unpack_v<BV>(r.vc, dt);
     if constexpr (RAW && MASKED) {               // unquantized garbage may be Inf/NaN: clear the slots beyond seq_len
       uint32_t* aw = reinterpret_cast<uint32_t*>(&a);
@@ -306,18 +331,6 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
 
 // Record layout in the workspace: [b][hq][split] x (kHeadDim + 4) floats = acc[128], m, l, 0, 0.
 constexpr int kRec = kHeadDim + 4;
-
-struct DecodeArgs {
-  Geom g;
-  kvq_cache cache;
-  const uint16_t* q; int q_bf16; int32_t q_heads;
-  int32_t seq_len; float softmax_scale;
-  float* ws; void* out; int out_dtype;
-  int32_t n_splits, steps_per_split;
-  // fused decode step: the token at position seq_len-1 is quantized from k_new/v_new ([B][H_kv][D], element strides
-  // nsb, nsh) by the workgroup that owns the last step, before it is read.  k_new == nullptr: plain attention.
-  const uint16_t* k_new; const uint16_t* v_new; int in_bf16; int64_t nsb, nsh;
-};
 
 // Quantize the one new token of this (b,h) and store it at position pos = seq_len-1: the first 16 lanes take the key
 // row, the next 16 the value row (8 channels per lane).  Same arithmetic and bytes as the bulk quantize-append kernel.
@@ -382,10 +395,11 @@ __device__ __forceinline__ void append_one_values(const DecodeArgs& a, int bh, i
   blk[dw] = w;
 }
 
-template <int BK, int BV, int R, int NW, bool BF>
+template <int BK, int BV, int R, int NW, bool BF, int NCK, int NCV>
 __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(const DecodeArgs a) {
+  constexpr int kSetGroups = 16 / R;             // groups per column set
   constexpr bool RAW = BK == 16;
-  constexpr int kStages = ring_stages<BK, BV>();
+  constexpr int kStages = ring_stages<BK, BV, NCK, NCV>();
   constexpr float kUnit = RAW ? 1.0f : kCodeUnit, kInvUnit = RAW ? 1.0f : kInvCodeUnit;
   __shared__ float sm_o[NW][R][kHeadDim];
   __shared__ float sm_m[NW][R], sm_l[NW][R];
@@ -473,11 +487,11 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   auto widen = [&](uint16_t bits) -> float {
     return q_bf16 ? __uint_as_float((uint32_t)bits << 16) : (float)__builtin_bit_cast(_Float16, bits);
   };
-  // column c carries head h restricted to key group gk (zero elsewhere); this lane's 32 channels are 32j..32j+31
-  u32x4 qb[4];
-  float qsum = 0.f;
+  // column c of set cs carries head h restricted to key group grp + cs*kSetGroups (zero elsewhere); this lane's 32
+  // channels are 32j..32j+31 and lie in one group
+  u32x4 qb[NCK][4];
+  float qsum_u[NCK];
   {
-    const bool mine = act_k && ((32 * L.j) / g.g_k == L.gk);   // the 32 channels lie in one group
     uint16_t mych[32];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -487,38 +501,49 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       for (int e = 0; e < 8; ++e) mych[8 * k + e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
     }
 #pragma unroll
-    for (int m = 0; m < 4; ++m) {
-      uint32_t w[4] = {0u, 0u, 0u, 0u};
+    for (int cs = 0; cs < NCK; ++cs) {
+      const int gcs = grp + cs * kSetGroups;
+      const bool act = gcs < g.ng_k;
+      const bool mine = act && ((32 * L.j) / g.g_k == gcs);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint16_t bits = mych[k_slot_elem<BK>(m, i)];
-        uint32_t e;                                // unquantized: the query's own 16-bit pattern (same type as the cache)
-        if constexpr (RAW) e = bits;
-        else e = __builtin_bit_cast(uint16_t, (_Float16)(widen(bits) / k_slot_scale<BK>(i)));
-        if (mine) w[i >> 1] |= e << (16 * (i & 1));
+      for (int m = 0; m < 4; ++m) {
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const uint16_t bits = mych[k_slot_elem<BK>(m, i)];
+          uint32_t e;                              // unquantized: the query's own 16-bit pattern (same type as the cache)
+          if constexpr (RAW) e = bits;
+          else e = __builtin_bit_cast(uint16_t, (_Float16)(widen(bits) / k_slot_scale<BK>(i)));
+          if (mine) w[i >> 1] |= e << (16 * (i & 1));
+        }
+        qb[cs][m] = u32x4{w[0], w[1], w[2], w[3]};
       }
-      qb[m] = u32x4{w[0], w[1], w[2], w[3]};
-    }
-    if (act_k && !RAW) {
+      float qsum = 0.f;
+      if (act && !RAW) {
 #pragma unroll
-      for (int c8 = 0; c8 < 16; ++c8) {
-        if ((8 * c8) / g.g_k != L.gk) continue;
-        const u32x4 v = reinterpret_cast<const u32x4*>(&sm_q[h][0])[c8];
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        for (int c8 = 0; c8 < 16; ++c8) {
+          if ((8 * c8) / g.g_k != gcs) continue;
+          const u32x4 v = reinterpret_cast<const u32x4*>(&sm_q[h][0])[c8];
+          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) qsum += widen((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+          for (int e = 0; e < 8; ++e) qsum += widen((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+        }
       }
+      qsum_u[cs] = qsum * kUnit;
     }
   }
-  const float qsum_u = qsum * kUnit;
   const float kappa = softmax_scale * kLog2e * kInvUnit;
 
-  WaveState st;
+  WaveState<NCV> st;
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) st.acc[dt] = float4v{0.f, 0.f, 0.f, 0.f};
   st.m = kNegBig;
 #pragma unroll
-  for (int v = 0; v < 4; ++v) { st.l[v] = 0.f; st.zacc[v] = 0.f; st.noff[v] = 0.f; }
+  for (int v = 0; v < 4; ++v) {
+    st.l[v] = 0.f; st.noff[v] = 0.f;
+#pragma unroll
+    for (int cs = 0; cs < NCV; ++cs) st.zacc[cs][v] = 0.f;
+  }
 
   // ---- main loop, unrolled over the ring: compute a step, then refill its registers with the step kStages
   // ahead, so that kStages-1 steps of loads are always in flight behind the one being computed.
@@ -526,39 +551,43 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   for (; it + kStages <= n_full; it += kStages) {
 #pragma unroll
     for (int k = 0; k < kStages; ++k) {
-      compute_step<BK, BV, R, BF, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(it + k), seq_len);
+      compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(it + k), seq_len);
       if (it + k + kStages < n_full) load_step<BK, BV>(buf[k], L, step_of(it + k + kStages));
     }
   }
 #pragma unroll
   for (int k = 0; k < kStages - 1; ++k)         // the last few complete steps are already in the ring
-    if (it + k < n_full) compute_step<BK, BV, R, BF, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(it + k), seq_len);
+    if (it + k < n_full) compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(it + k), seq_len);
   if (own_tail) {                                 // ragged last step of the sequence: masked
     load_step<BK, BV>(buf[0], L, n_steps - 1);
-    compute_step<BK, BV, R, BF, true>(buf[0], qb, qsum_u, kappa, st, L, n_steps - 1, seq_len);
+    compute_step<BK, BV, R, BF, NCK, NCV, true>(buf[0], qb, qsum_u, kappa, st, L, n_steps - 1, seq_len);
   }
 
-  // ---- wavefront totals: l and zacc over register classes and the 4 lane groups j
-  float l = 0.f, z = 0.f;
+  // ---- wavefront totals: l and zacc over register classes and the 4 lane groups j; then this lane's output rows
+  float l = 0.f;
 #pragma unroll
-  for (int v = 0; v < 4; ++v) {
-    const float w = (float)(1 << v_slot_shift<BV>(v));
-    l = fmaf(st.l[v], w, l); z = fmaf(st.zacc[v], w, z);
-  }
+  for (int v = 0; v < 4; ++v) l = fmaf(st.l[v], (float)(1 << v_slot_shift<BV>(v)), l);
   l += __shfl_xor(l, 16); l += __shfl_xor(l, 32);
-  z += __shfl_xor(z, 16); z += __shfl_xor(z, 32);
-  if (act_v) {
-    const int dtg = 8 / g.ng_v;                                // d-tiles per value group
-    for (int dt = L.gv * dtg; dt < (L.gv + 1) * dtg; ++dt)
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        float a = 0.f;
+  for (int cs = 0; cs < NCV; ++cs) {
+    float z = 0.f;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) if (k == dt) a = st.acc[k][rr];   // static register indexing
-        sm_o[wave][h][16 * dt + 4 * L.j + rr] = fmaf(a, kInvUnit, z);
-      }
-    if (grp == 0 && L.j == 0) { sm_m[wave][h] = st.m; sm_l[wave][h] = l; }
+    for (int v = 0; v < 4; ++v) z = fmaf(st.zacc[cs][v], (float)(1 << v_slot_shift<BV>(v)), z);
+    z += __shfl_xor(z, 16); z += __shfl_xor(z, 32);
+    const int gcs = grp + cs * kSetGroups;                     // the value group this lane's column carries in set cs
+    if (gcs < g.ng_v) {
+      const int dtg = 8 / g.ng_v;                              // d-tiles per value group
+      for (int dt = gcs * dtg; dt < (gcs + 1) * dtg; ++dt)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          float av = 0.f;
+#pragma unroll
+          for (int k = 0; k < 8; ++k) if (k == dt) av = st.acc[k][rr];   // static register indexing
+          sm_o[wave][h][16 * dt + 4 * L.j + rr] = fmaf(av, kInvUnit, z);
+        }
+    }
   }
+  if (grp == 0 && L.j == 0) { sm_m[wave][h] = st.m; sm_l[wave][h] = l; }
   __syncthreads();
 
   // ---- merge the wavefronts; write a partial record, or the result when there is one split
@@ -614,11 +643,26 @@ __global__ __launch_bounds__(128) void merge_kernel(const float* __restrict__ ws
   }
 }
 
+template <int BK, int BV, int R, bool BF, int NCK, int NCV>
+void launch_nw(const DecodeArgs& a, const DecodePlan& plan, dim3 grid, hipStream_t stream) {
+  if (plan.waves_per_wg == 8) hipLaunchKernelGGL((decode_kernel<BK, BV, R, 8, BF, NCK, NCV>), grid, dim3(512), 0, stream, a);
+  else hipLaunchKernelGGL((decode_kernel<BK, BV, R, 4, BF, NCK, NCV>), grid, dim3(256), 0, stream, a);
+}
+
 template <int BK, int BV, int R, bool BF = false>
 hipError_t launch_one(const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream) {
   dim3 grid(plan.n_splits, a.g.batch * a.g.kv_heads);
-  if (plan.waves_per_wg == 8) hipLaunchKernelGGL((decode_kernel<BK, BV, R, 8, BF>), grid, dim3(512), 0, stream, a);
-  else hipLaunchKernelGGL((decode_kernel<BK, BV, R, 4, BF>), grid, dim3(256), 0, stream, a);
+  // two column sets only where 8 heads meet four groups (32 columns); quantized caches only
+  const bool k2 = R * a.g.ng_k > 16, v2 = R * a.g.ng_v > 16;
+  if constexpr (R == 8 && BK != 16) {
+    if (k2 && v2) launch_nw<BK, BV, R, BF, 2, 2>(a, plan, grid, stream);
+    else if (k2) launch_nw<BK, BV, R, BF, 2, 1>(a, plan, grid, stream);
+    else if (v2) launch_nw<BK, BV, R, BF, 1, 2>(a, plan, grid, stream);
+    else launch_nw<BK, BV, R, BF, 1, 1>(a, plan, grid, stream);
+  } else {
+    if (k2 || v2) return hipErrorInvalidValue;
+    launch_nw<BK, BV, R, BF, 1, 1>(a, plan, grid, stream);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || plan.n_splits == 1) return e;
   hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128), 0, stream, a.ws, a.out, a.out_dtype, plan.n_splits);
@@ -638,11 +682,33 @@ hipError_t launch_r(int R, const DecodeArgs& a, const DecodePlan& plan, hipStrea
 
 }  // namespace
 
+#define KVQ_CAT2(a, b, c) a##b##_##c
+#define KVQ_CAT(a, b, c) KVQ_CAT2(a, b, c)
+
+#if defined(KVQ_INST_BK)
+// ---- instance translation unit: the kernels of one (b_K, b_V) pair behind one launcher -------------------------------
+hipError_t KVQ_CAT(launch_decode_inst_, KVQ_INST_BK, KVQ_INST_BV)(int R, const DecodeArgs& a, const DecodePlan& plan,
+                                                                  hipStream_t stream) {
+#if KVQ_INST_BK == 16
+  return a.g.raw_dtype == KVQ_BF16 ? launch_r<16, 16, true>(R, a, plan, stream) : launch_r<16, 16, false>(R, a, plan, stream);
+#else
+  return launch_r<KVQ_INST_BK, KVQ_INST_BV>(R, a, plan, stream);
+#endif
+}
+
+#else
+// ---- dispatcher translation unit ----------------------------------------------------------------------------------------
+#define KVQ_FOR_EACH_PAIR(X) X(4, 2) X(2, 4) X(4, 4) X(8, 8) X(2, 2) X(8, 4) X(8, 2) X(4, 8) X(2, 8) X(16, 16)
+#define KVQ_DECL(BK_, BV_) \
+  hipError_t KVQ_CAT(launch_decode_inst_, BK_, BV_)(int R, const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream);
+KVQ_FOR_EACH_PAIR(KVQ_DECL)
+#undef KVQ_DECL
+
 bool decode_supported(const Geom& g, int32_t q_heads) {
   const int R = q_heads / g.kv_heads;
   if (R != 1 && R != 2 && R != 4 && R != 8) return false;
   if ((g.bits_k == 16) != (g.bits_v == 16)) return false;      // one tensor unquantized, the other not: no kernel
-  if (R * g.ng_k > 16 || R * g.ng_v > 16) return false;        // head x group columns must fit one 16-wide tile
+  if (R * g.ng_k > 32 || R * g.ng_v > 32) return false;        // head x group columns: at most two 16-wide tiles
   return true;
 }
 
@@ -681,20 +747,11 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
     a.in_bf16 = app->in_dtype == KVQ_BF16 ? 1 : 0; a.nsb = app->stride_b; a.nsh = app->stride_h;
   }
 #define KVQ_CASE(BK_, BV_) \
-  if (g.bits_k == BK_ && g.bits_v == BV_) return launch_r<BK_, BV_>(R, a, plan, stream);
-  KVQ_CASE(4, 2)
-  KVQ_CASE(2, 4)
-  KVQ_CASE(4, 4)
-  KVQ_CASE(8, 8)
-  KVQ_CASE(2, 2)
-  KVQ_CASE(8, 4)
-  KVQ_CASE(8, 2)
-  KVQ_CASE(4, 8)
-  KVQ_CASE(2, 8)
+  if (g.bits_k == BK_ && g.bits_v == BV_) return KVQ_CAT(launch_decode_inst_, BK_, BV_)(R, a, plan, stream);
+  KVQ_FOR_EACH_PAIR(KVQ_CASE)
 #undef KVQ_CASE
-  if (g.bits_k == 16 && g.bits_v == 16)
-    return g.raw_dtype == KVQ_BF16 ? launch_r<16, 16, true>(R, a, plan, stream) : launch_r<16, 16, false>(R, a, plan, stream);
   return hipErrorInvalidValue;
 }
+#endif
 
 }  // namespace kvq

@@ -49,6 +49,20 @@ struct AppendOne {
 };
 DecodePlan plan_decode(const Geom& g, int32_t seq_len);
 
+// Everything the decode kernels need, passed by value.
+struct DecodeArgs {
+  Geom g;
+  kvq_cache cache;
+  const uint16_t* q; int q_bf16; int32_t q_heads;
+  int32_t seq_len; float softmax_scale;
+  float* ws; void* out; int out_dtype;
+  int32_t n_splits, steps_per_split;
+  // fused decode step: the token at position seq_len-1 is quantized from k_new/v_new ([B][H_kv][D], element strides
+  // nsb, nsh) by the workgroup that owns the last step, before it is read.  k_new == nullptr: plain attention.
+  const uint16_t* k_new; const uint16_t* v_new; int in_bf16; int64_t nsb, nsh;
+};
+
+
 // Launchers (each validates nothing: the C ABI layer has done it).  Return hipGetLastError().
 hipError_t launch_quantize_append(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new,
                                   int in_dtype, int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new,

@@ -116,9 +116,10 @@ def test_call_errors_are_caught_before_any_launch(kvq):
     if need:
         assert da(0x50000, 8, 100, 0.1, 0x60000, 2, 0x70000, need - 1) == kvq.ERR_WORKSPACE
         assert da(0x50000, 8, 100, 0.1, 0x60000, 2, 0, need) == kvq.ERR_WORKSPACE
-    L32 = kvq.Layout(2, 2, 100, 128, 4, 2, 32, 32).c()                                            # 8 heads x 4 groups > 16 columns
-    assert lib.kvq_decode_attention(C.byref(L32), C.byref(good), p(0x50000), 1, 16, 50, C.c_float(0.1), p(0x60000), 2,
-                                    p(0x70000), 1 << 20, None) == kvq.ERR_UNSUPPORTED
+    assert da(0x50000, 32, 50, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_UNSUPPORTED         # 16 query heads per kv head
+    Lmix = kvq.Layout(2, 2, 100, 128, 16, 2, 64, 64).c()                                          # raw keys, quantized values
+    assert lib.kvq_decode_attention(C.byref(Lmix), C.byref(kvq._CCache(0x10000, 0, 0x30000, 0x40000)), p(0x50000), 0, 8, 50,
+                                    C.c_float(0.1), p(0x60000), 2, p(0x70000), 1 << 20, None) == kvq.ERR_UNSUPPORTED
 
     def ds(pos, k=0x50000):
         return lib.kvq_decode_step(C.byref(cl), C.byref(good), p(k), p(0x51000), 1, 256, 128, pos, p(0x52000), 1, 8,

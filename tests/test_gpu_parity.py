@@ -182,6 +182,21 @@ def test_gqa_attention_ragged_lengths(kvq, oracle, R, bk, bv, gk, gv):
         assert err < TOL, (seq_len, err)
 
 
+@pytest.mark.parametrize("gk,gv", [(32, 32), (32, 64), (64, 32), (32, 128)])
+def test_eight_heads_with_32_channel_groups(kvq, oracle, gk, gv):
+    """8 query heads per KV head with four groups per row need two sets of matrix columns (the paper finds small
+    key groups best in its group-size study)."""
+    B, H, R, T = 2, 2, 8, 300
+    K, V, q = synth.make_kvq(50 + gk + gv, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, 4, 2, gk, gv)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, T)], fill=0xFF)
+    qn = synth.to_numpy_bits(q)
+    for seq_len in (T, 129, 32):
+        out = _decode(kvq, Lg, cache, q, seq_len).cpu().numpy()
+        ref = oracle.decode_attention(Lo, planes, qn, seq_len, 1 / math.sqrt(128), bf16=True)
+        assert np.isfinite(out).all() and _rel_err(out, ref) < TOL, seq_len
+
+
 def test_small_groups_and_multi_split(kvq, oracle):
     """32-channel groups with 4 query heads per KV head, long enough for several sequence splits."""
     B, H, R, T = 1, 2, 4, 2100
