@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -36,7 +37,7 @@ def _compile(item):
     log = r.stdout + r.stderr
     if r.returncode == 0 and "-Rpass-analysis=kernel-resource-usage" in extra:
         # a decode kernel that spills would wait on scratch reloads in the middle of its load pipeline: refuse it
-        spills = [l for l in log.splitlines() if "ScratchSize [bytes/lane]:" in l and not l.rstrip().endswith(": 0")]
+        spills = [l for l in log.splitlines() if re.search(r"ScratchSize \[bytes/lane\]: [1-9]", l)]
         if spills:
             return objname, 1, f"{len(spills)} decode kernel(s) use scratch memory (register spills)", obj
         log = "\n".join(l for l in log.splitlines() if "remark:" not in l)
