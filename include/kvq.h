@@ -124,6 +124,20 @@ kvq_status kvq_decode_step(const kvq_layout* layout, const kvq_cache* cache, con
                            kvq_dtype q_dtype, int32_t q_heads, float softmax_scale, void* out, kvq_dtype out_dtype,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* Squared reconstruction error of cached tokens [t0, t1) against the full-precision rows they were made from:
+ *   sums[b][h][0] = sum over t, d of (K[b,h,t,d] - K^[b,h,t,d])^2,  sums[b][h][1] the same for V,
+ * the numerator of App. B's "Frobenius Norm (MSE) Perspective" (MSE = ||A - A^||_F^2 / number of entries; Table 1
+ * reports it for keys at 3 and 4 bits); the caller divides by (t1-t0)*D (per head) or by the whole count.
+ *   k_ref, v_ref  [B][H_kv][t1-t0][D] of ref_dtype (KVQ_F16 / KVQ_BF16): row 0 is token t0; element strides given,
+ *                 D contiguous, 16-byte aligned rows; either may be NULL (its sums are then 0).
+ *   sums          double[B][H_kv][2], overwritten.  x^ is the binary32 reconstruction of kvq_dequantize, the
+ *                 difference is taken in binary32 and squared and accumulated in binary64; the order of the
+ *                 additions is not fixed (relative spread about 2^-50).
+ * t0 == t1 writes zeros. */
+kvq_status kvq_reconstruction_error(const kvq_layout* layout, const kvq_cache* cache, const void* k_ref,
+                                    const void* v_ref, kvq_dtype ref_dtype, int64_t stride_b, int64_t stride_h,
+                                    int64_t stride_t, int32_t t0, int32_t t1, double* sums, void* stream);
+
 /* Reconstruct tokens [t0, t1) as x^ = code * scale + zero (App. B "Dequantization"):
  *   k_out, v_out  [B][H_kv][t1-t0][D] contiguous of out_dtype; either may be NULL to skip it.
  * KVQ_F32 output is exactly the binary32 value; 16-bit outputs round it once. */

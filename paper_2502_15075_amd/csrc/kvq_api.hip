@@ -150,6 +150,28 @@ kvq_status kvq_dequantize(const kvq_layout* layout, const kvq_cache* cache, int3
   return e == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
 }
 
+kvq_status kvq_reconstruction_error(const kvq_layout* layout, const kvq_cache* cache, const void* k_ref,
+                                    const void* v_ref, kvq_dtype ref_dtype, int64_t stride_b, int64_t stride_h,
+                                    int64_t stride_t, int32_t t0, int32_t t1, double* sums, void* stream) {
+  kvq_status st = check_layout(layout);
+  if (st != KVQ_OK) return st;
+  st = check_cache(layout, cache);
+  if (st != KVQ_OK) return st;
+  if (t0 < 0 || t1 < t0) return KVQ_ERR_INVALID_ARG;
+  if (t1 > layout->max_seq) return KVQ_ERR_CAPACITY;
+  if (!sums || (reinterpret_cast<uintptr_t>(sums) & 7u)) return KVQ_ERR_INVALID_ARG;
+  if (ref_dtype != KVQ_F16 && ref_dtype != KVQ_BF16) return KVQ_ERR_INVALID_ARG;
+  if (t1 > t0) {                                       // an empty range reads no reference row
+    if (!k_ref && !v_ref) return KVQ_ERR_INVALID_ARG;
+    if (!aligned16(k_ref) || !aligned16(v_ref) || stride_b % 8 || stride_h % 8 || stride_t % 8 || stride_t < layout->head_dim)
+      return KVQ_ERR_INVALID_ARG;
+  }
+  const kvq::Geom g = kvq::make_geom(*layout);
+  hipError_t e = kvq::launch_reconstruction_error(g, *cache, k_ref, v_ref, ref_dtype, stride_b, stride_h, stride_t, t0, t1,
+                                                  sums, (hipStream_t)stream);
+  return e == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
+}
+
 const char* kvq_status_string(kvq_status status) {
   switch (status) {
     case KVQ_OK: return "ok";

@@ -69,6 +69,9 @@ hipError_t launch_quantize_append(const Geom& g, const kvq_cache& c, const void*
                                   hipStream_t stream);
 hipError_t launch_dequantize(const Geom& g, const kvq_cache& c, int32_t t0, int32_t t1, void* k_out, void* v_out,
                              int out_dtype, hipStream_t stream);
+hipError_t launch_reconstruction_error(const Geom& g, const kvq_cache& c, const void* k_ref, const void* v_ref,
+                                       int ref_dtype, int64_t sb, int64_t sh, int64_t st, int32_t t0, int32_t t1,
+                                       double* sums, hipStream_t stream);
 // Returns hipErrorInvalidValue if no kernel instance exists for (bits, groups, head ratio).
 hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void* q, int q_dtype, int32_t q_heads,
                                    int32_t seq_len, float softmax_scale, void* out, int out_dtype, float* workspace,

@@ -166,7 +166,41 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
   }
 }
 
-// Reconstruction x^ = code * scale + zero.  One thread = 8 consecutive channels of one token.
+// Reconstruction x^ = code * scale + zero of 8 consecutive channels d0..d0+7 of token t of stream bh
+// (which = 0: keys, 1: values), as binary32 values; a 16-bit plane is widened exactly.
+__device__ __forceinline__ void reconstruct8(const Geom& g, const kvq_cache& c, int which, int64_t bh, int64_t t, int d0,
+                                             float val[8]) {
+  const int b = which ? g.bits_v : g.bits_k;
+  const int G = which ? g.g_v : g.g_k;
+  const int ng = which ? g.ng_v : g.ng_k;
+  const uint8_t* cs = (const uint8_t*)(which ? c.v_codes : c.k_codes) + bh * (which ? g.vc_stream : g.kc_stream);
+  const uint32_t* ms = (const uint32_t*)((const uint8_t*)(which ? c.v_meta : c.k_meta) + bh * (which ? g.vm_stream : g.km_stream));
+  const bool raw_bf16 = g.raw_dtype == KVQ_BF16;
+  float s = 0.f, z = 0.f;
+  if (b != 16) {
+    uint32_t m = ms[meta_index(t, d0 / G, ng)];
+    s = widen16((uint16_t)(m & 0xFFFF), false);
+    z = widen16((uint16_t)(m >> 16), false);
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int d = d0 + e;
+    uint32_t code;
+    if (!which) {
+      const int64_t bit = (t * kHeadDim + d) * b;
+      const uint32_t wd = *reinterpret_cast<const uint32_t*>(cs + ((bit >> 5) << 2));
+      code = (wd >> (bit & 31)) & (b == 16 ? 0xFFFFu : ((1u << b) - 1u));
+    } else {
+      int dw, bit;
+      v_field((int)(t & 31), d, b, &dw, &bit);
+      const uint32_t wd = reinterpret_cast<const uint32_t*>(cs + (t >> 5) * (int64_t)(512 * b))[dw];
+      code = (wd >> bit) & (b == 16 ? 0xFFFFu : ((1u << b) - 1u));
+    }
+    val[e] = b == 16 ? widen16((uint16_t)code, raw_bf16) : (float)code * s + z;
+  }
+}
+
+// One thread = 8 consecutive channels of one token.
 __global__ __launch_bounds__(256) void dequantize_kernel(Geom g, kvq_cache c, int32_t t0, int32_t t1, void* k_out,
                                                          void* v_out, int out_dtype) {
   const int64_t nt = t1 - t0;
@@ -178,39 +212,12 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Geom g, kvq_cache c, in
   const int64_t bh = row / nt;
   const int64_t t = t0 + row % nt;
   const int d0 = oct * 8;
-  const bool raw_bf16 = g.raw_dtype == KVQ_BF16;
 
   for (int which = 0; which < 2; ++which) {
     void* out = which ? v_out : k_out;
     if (!out) continue;
-    const int b = which ? g.bits_v : g.bits_k;
-    const int G = which ? g.g_v : g.g_k;
-    const int ng = which ? g.ng_v : g.ng_k;
-    const uint8_t* cs = (const uint8_t*)(which ? c.v_codes : c.k_codes) + bh * (which ? g.vc_stream : g.kc_stream);
-    const uint32_t* ms = (const uint32_t*)((const uint8_t*)(which ? c.v_meta : c.k_meta) + bh * (which ? g.vm_stream : g.km_stream));
     float val[8];
-    float s = 0.f, z = 0.f;
-    if (b != 16) {
-      uint32_t m = ms[meta_index(t, d0 / G, ng)];
-      s = widen16((uint16_t)(m & 0xFFFF), false);
-      z = widen16((uint16_t)(m >> 16), false);
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int d = d0 + e;
-      uint32_t code;
-      if (!which) {
-        const int64_t bit = (t * kHeadDim + d) * b;
-        const uint32_t wd = *reinterpret_cast<const uint32_t*>(cs + ((bit >> 5) << 2));
-        code = (wd >> (bit & 31)) & (b == 16 ? 0xFFFFu : ((1u << b) - 1u));
-      } else {
-        int dw, bit;
-        v_field((int)(t & 31), d, b, &dw, &bit);
-        const uint32_t wd = reinterpret_cast<const uint32_t*>(cs + (t >> 5) * (int64_t)(512 * b))[dw];
-        code = (wd >> bit) & (b == 16 ? 0xFFFFu : ((1u << b) - 1u));
-      }
-      val[e] = b == 16 ? widen16((uint16_t)code, raw_bf16) : (float)code * s + z;
-    }
+    reconstruct8(g, c, which, bh, t, d0, val);
     const int64_t o = row * kHeadDim + d0;
     if (out_dtype == KVQ_F32) {
       float* p = (float*)out + o;
@@ -222,6 +229,52 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Geom g, kvq_cache c, in
       for (int e = 0; e < 8; ++e) p[e] = out_dtype == KVQ_F16 ? f32_to_f16_bits(val[e]) : f32_to_bf16_bits(val[e]);
     }
   }
+}
+
+// Squared reconstruction error (numerator of the MSE of App. B, "Frobenius Norm (MSE) Perspective").
+// One thread = 8 consecutive channels of one token; a workgroup walks 16-token slabs of one (b,h) stream with
+// stride gridDim.x; differences in binary32, squares summed in binary64, one atomic add per wavefront and tensor.
+__global__ __launch_bounds__(256) void sq_error_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_ref,
+                                                       const uint16_t* __restrict__ v_ref, int ref_bf16, int64_t sb,
+                                                       int64_t sh, int64_t st, int32_t t0, int32_t t1,
+                                                       double* __restrict__ sums) {
+  const int tid = threadIdx.x;
+  const int64_t bh = blockIdx.y;
+  const int64_t b = bh / g.kv_heads, h = bh % g.kv_heads;
+  const int d0 = (tid & 15) * 8;
+  const int64_t nt = t1 - t0;
+  double acc[2] = {0.0, 0.0};
+  for (int64_t r = (int64_t)blockIdx.x * 16 + (tid >> 4); r < nt; r += (int64_t)gridDim.x * 16) {
+    const int64_t src = b * sb + h * sh + r * st + d0;
+    uint4 raw[2];
+    if (k_ref) raw[0] = *reinterpret_cast<const uint4*>(k_ref + src);
+    if (v_ref) raw[1] = *reinterpret_cast<const uint4*>(v_ref + src);
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+      if (!(which ? v_ref : k_ref)) continue;
+      float val[8];
+      reconstruct8(g, c, which, bh, t0 + r, d0, val);
+      const uint32_t rw[4] = {raw[which].x, raw[which].y, raw[which].z, raw[which].w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), ref_bf16 != 0);
+        const double err = (double)(x - val[e]);
+        acc[which] += err * err;
+      }
+    }
+  }
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    double v = acc[which];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+    if ((tid & 63) == 0 && v != 0.0) atomicAdd(sums + bh * 2 + which, v);
+  }
+}
+
+__global__ __launch_bounds__(256) void zero_f64_kernel(double* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0.0;
 }
 
 }  // namespace
@@ -271,6 +324,22 @@ hipError_t launch_dequantize(const Geom& g, const kvq_cache& c, int32_t t0, int3
   if (total == 0) return hipSuccess;
   const int64_t blocks = (total + 255) / 256;
   hipLaunchKernelGGL(dequantize_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, g, c, t0, t1, k_out, v_out, out_dtype);
+  return hipGetLastError();
+}
+
+hipError_t launch_reconstruction_error(const Geom& g, const kvq_cache& c, const void* k_ref, const void* v_ref,
+                                       int ref_dtype, int64_t sb, int64_t sh, int64_t st, int32_t t0, int32_t t1,
+                                       double* sums, hipStream_t stream) {
+  const int streams = g.batch * g.kv_heads;
+  const int64_t n = (int64_t)streams * 2;
+  // cleared by a kernel, not a memset, so that the call can be captured into a graph
+  hipLaunchKernelGGL(zero_f64_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, sums, n);
+  if (t1 == t0) return hipGetLastError();
+  const int64_t slabs = ((int64_t)(t1 - t0) + 15) / 16;
+  int64_t per_stream = (8192 + streams - 1) / streams;          // about 32 workgroups per compute unit in all
+  if (per_stream > slabs) per_stream = slabs;
+  hipLaunchKernelGGL(sq_error_kernel, dim3((unsigned)per_stream, streams), dim3(256), 0, stream, g, c,
+                     (const uint16_t*)k_ref, (const uint16_t*)v_ref, ref_dtype == KVQ_BF16 ? 1 : 0, sb, sh, st, t0, t1, sums);
   return hipGetLastError();
 }
 

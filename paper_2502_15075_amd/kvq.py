@@ -58,10 +58,12 @@ def load():
                                         C.c_void_p, C.c_size_t, C.c_void_p]
         lib.kvq_dequantize.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_int32, C.c_int32, C.c_void_p,
                                        C.c_void_p, C.c_int, C.c_void_p]
+        lib.kvq_reconstruction_error.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int,
+                                                 C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         lib.kvq_status_string.argtypes = [C.c_int]
         lib.kvq_status_string.restype = C.c_char_p
         for f in ("kvq_cache_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
-                  "kvq_decode_step", "kvq_dequantize"):
+                  "kvq_decode_step", "kvq_dequantize", "kvq_reconstruction_error"):
             getattr(lib, f).restype = C.c_int
         _lib = lib
     return _lib
@@ -183,3 +185,17 @@ def dequantize(layout: Layout, cache: Cache, t0: int, t1: int, k_out, v_out) -> 
     cl, cc = layout.c(), cache.c()
     st = load().kvq_dequantize(C.byref(cl), C.byref(cc), t0, t1, _p(k_out), _p(v_out), _DTYPES[ref.dtype], _stream_ptr())
     _check(st, "kvq_dequantize")
+
+
+def reconstruction_error(layout: Layout, cache: Cache, k_ref, v_ref, t0: int, sums: torch.Tensor) -> torch.Tensor:
+    """k_ref, v_ref: [B, H_kv, n, D] fp16/bf16 rows of tokens [t0, t0+n) (last axis contiguous; either may be None);
+    sums: [B, H_kv, 2] float64 device tensor, overwritten with the squared error of keys and of values per head."""
+    ref = k_ref if k_ref is not None else v_ref
+    for t in (k_ref, v_ref):
+        assert t is None or (t.dim() == 4 and t.dtype == ref.dtype and t.stride() == ref.stride() and t.stride(3) == 1)
+    assert sums.dtype == torch.float64 and sums.is_contiguous() and sums.numel() == layout.batch * layout.kv_heads * 2
+    cl, cc = layout.c(), cache.c()
+    st = load().kvq_reconstruction_error(C.byref(cl), C.byref(cc), _p(k_ref), _p(v_ref), _DTYPES[ref.dtype], ref.stride(0),
+                                         ref.stride(1), ref.stride(2), t0, t0 + ref.shape[2], _p(sums), _stream_ptr())
+    _check(st, "kvq_reconstruction_error")
+    return sums

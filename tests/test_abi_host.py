@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported(kvq):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(kvq_[a-z_]+)\s*\(", header))
     assert {"kvq_cache_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
-            "kvq_decode_step", "kvq_dequantize", "kvq_status_string"} <= declared
+            "kvq_decode_step", "kvq_dequantize", "kvq_reconstruction_error", "kvq_status_string"} <= declared
     lib = C.CDLL(kvq.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), name
@@ -133,6 +133,16 @@ def test_call_errors_are_caught_before_any_launch(kvq):
     assert dq(0, 4, 0, 0, 2) == kvq.ERR_INVALID_ARG
     assert dq(0, 4, 0x50000, 0, 7) == kvq.ERR_INVALID_ARG
     assert dq(4, 4, 0x50000, 0, 2) == kvq.OK                                                       # empty range: no launch
+
+    def re_(k, v, dt, st, t0, t1, sums):
+        return lib.kvq_reconstruction_error(C.byref(cl), C.byref(good), p(k), p(v), dt, 25600, 12800, st, t0, t1, p(sums), None)
+    assert re_(0x50000, 0x60000, 0, 128, 0, 101, 0x70000) == kvq.ERR_CAPACITY
+    assert re_(0x50000, 0x60000, 0, 128, 9, 3, 0x70000) == kvq.ERR_INVALID_ARG
+    assert re_(0, 0, 0, 128, 0, 4, 0x70000) == kvq.ERR_INVALID_ARG
+    assert re_(0x50000, 0x60000, 2, 128, 0, 4, 0x70000) == kvq.ERR_INVALID_ARG                   # fp32 reference rows
+    assert re_(0x50000, 0x60000, 0, 120, 0, 4, 0x70000) == kvq.ERR_INVALID_ARG                   # rows overlap
+    assert re_(0x50000, 0x60000, 0, 128, 0, 4, 0) == kvq.ERR_INVALID_ARG
+    assert re_(0x50000, 0x60000, 0, 128, 0, 4, 0x70004) == kvq.ERR_INVALID_ARG                   # misaligned doubles
 
 
 def test_product_path_never_touches_the_oracle():

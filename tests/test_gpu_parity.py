@@ -384,3 +384,46 @@ def test_full_size_8b_layer_sampled_streams(kvq, oracle):
 def test_long_context_batch_1_sampled_streams(kvq, oracle):
     """BASELINE configs[4] shape (B=1, context 131072, 32 splits per stream), ragged length on purpose."""
     _check_sampled_streams(kvq, oracle, 1, 32, 8, 131072 - 5, 4, 4.0, [(0, 3)])
+
+
+# --------------------------------------------------------------------------- reconstruction error (MSE numerator)
+
+@pytest.mark.parametrize("bk,bv,gk,gv", [(4, 2, 64, 64), (2, 4, 32, 128), (8, 8, 128, 32), (4, 4, 64, 32)])
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_reconstruction_error_matches_the_oracle(kvq, oracle, bk, bv, gk, gv, dtype):
+    """Per-head squared error of tokens [t0, t1) against the oracle's MSE of its own reconstruction of the same bytes
+    (App. B, Frobenius / MSE perspective).  Differences are taken in binary32 on the GPU and in binary64 by the
+    oracle: relative 2^-24 per term, so 1e-6 on a sum of squares."""
+    B, H, T = 2, 3, 333
+    K, V, _ = synth.make_kvq(90 + bk + bv, B, H, H, T, dtype=dtype)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, T)])
+    Kh, Vh = oracle.dequantize(Lo, planes, 0, T)
+    Kf, Vf = K.float().numpy(), V.float().numpy()
+    sums = torch.full((B, H, 2), -1.0, dtype=torch.float64, device="cuda")
+    for t0, t1 in ((0, T), (17, 301), (5, 6)):
+        kvq.reconstruction_error(Lg, cache, K.cuda()[:, :, t0:t1], V.cuda()[:, :, t0:t1], t0, sums)
+        got = sums.cpu().numpy()
+        n = (t1 - t0) * 128
+        for b in range(B):
+            for h in range(H):
+                want_k = oracle.mse(Kf[b, h, t0:t1], Kh[b, h, t0:t1]) * n
+                want_v = oracle.mse(Vf[b, h, t0:t1], Vh[b, h, t0:t1]) * n
+                assert got[b, h, 0] == pytest.approx(want_k, rel=1e-6), (t0, t1, b, h)
+                assert got[b, h, 1] == pytest.approx(want_v, rel=1e-6), (t0, t1, b, h)
+    # keys only, empty range, unquantized planes
+    kvq.reconstruction_error(Lg, cache, K.cuda(), None, 0, sums)
+    got = sums.cpu().numpy()
+    assert (got[..., 1] == 0).all() and got[..., 0].sum() == pytest.approx(oracle.mse(Kf, Kh) * Kf.size, rel=1e-6)
+    kvq.reconstruction_error(Lg, cache, K.cuda()[:, :, 9:9], V.cuda()[:, :, 9:9], 9, sums)
+    assert (sums.cpu().numpy() == 0).all()
+
+
+def test_reconstruction_error_of_unquantized_planes_is_zero(kvq, oracle):
+    B, H, T = 1, 2, 100
+    K, V, _ = synth.make_kvq(7, B, H, H, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, 16, 16, 64, 64, raw=1)
+    cache, _ = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, T)])
+    sums = torch.full((B, H, 2), -1.0, dtype=torch.float64, device="cuda")
+    kvq.reconstruction_error(Lg, cache, K.cuda(), V.cuda(), 0, sums)
+    assert (sums.cpu().numpy() == 0).all()
