@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the K4V2 decode hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--workload llama70b|llama8b]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--workload llama70b|llama8b|sweep|groups|stream131k]
 
 One step = one pass of the whole hot path over one layer's batch: quantize-and-append the new
 token's K/V (B x H_kv rows) into the packed cache, then single-token decode attention over the
@@ -100,6 +100,50 @@ def run_sweep(args, kvq, synth) -> int:
     return 0
 
 
+def run_groups(args, kvq, synth) -> int:
+    """Group-size study (Sec. 4, group sizes for keys and values chosen independently): K4V2 on the 8B layer shape at
+    context 32768 for (G_K, G_V) in {32, 64, 128}^2.  Per line: bytes per cached row, reconstruction MSE of keys and
+    values (kvq_reconstruction_error: App. B, MSE perspective) and that kernel's rate over the bytes it has to read
+    (512 B of reference rows + the packed row), attention-output error against exact attention on the original
+    tensors (CPU oracle, batch element 0), and effective GB/s of kvq_decode_attention over rotating cache copies."""
+    import numpy as np
+    from oracle import ref
+    B, Hq, Hkv, D, T = 8, 32, 8, 128, 32768
+    scale = 1.0 / math.sqrt(D)
+    K, V, q = synth.make_kvq(5, B, Hkv, Hq, T, D, dtype=torch.bfloat16, device="cuda")
+    want = ref.attention_dense(K[:1].float().cpu().numpy(), V[:1].float().cpu().numpy(),
+                               synth.to_numpy_bits(q[:1]), scale, bf16=True).astype(np.float64)
+    sums = torch.empty(B, Hkv, 2, dtype=torch.float64, device="cuda")
+    for gk in (32, 64, 128):
+        for gv in (32, 64, 128):
+            L = kvq.Layout(B, Hkv, T, D, 4, 2, gk, gv, raw_dtype=kvq.KVQ_BF16)
+            row_bytes = 16 * 4 + 16 * 2 + 4 * (D // gk) + 4 * (D // gv)
+            kv_bytes = B * Hkv * T * row_bytes
+            copies = 5
+            caches = []
+            for _ in range(copies):
+                c = kvq.Cache(L, device="cuda")
+                kvq.quantize_append(L, c, K, V, 0)
+                caches.append(c)
+            ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, Hq, T)), dtype=torch.uint8, device="cuda")
+            out = torch.empty(B, Hq, D, dtype=torch.float32, device="cuda")
+            ms = _time_loop(lambda i: kvq.decode_attention(L, caches[i % copies], q, T, scale, out, ws), 1000, 200)
+            ms_err = _time_loop(lambda i: kvq.reconstruction_error(L, caches[i % copies], K, V, 0, sums), 100, 10)
+            n = B * Hkv * T * D
+            tot = sums.sum(dim=(0, 1)).cpu().numpy()
+            got = out[:1].cpu().numpy().astype(np.float64)
+            rel_l2 = float((np.linalg.norm(got - want, axis=-1) / np.linalg.norm(want, axis=-1)).mean())
+            print(json.dumps({"workload": f"8B layer, B=8, T={T}, K4V2, G_K={gk}, G_V={gv}", "group_k": gk, "group_v": gv,
+                              "bytes_per_row": row_bytes, "kv_bytes": kv_bytes,
+                              "mse_k": float(tot[0] / n), "mse_v": float(tot[1] / n),
+                              "mse_kernel_us": round(ms_err * 1e3, 1),
+                              "mse_kernel_GB_s": round(B * Hkv * T * (512 + row_bytes) / ms_err / 1e6, 1),
+                              "decode_us_cold": round(ms * 1e3, 2), "decode_GB_s_cold": round(kv_bytes / ms / 1e6, 1),
+                              "err_vs_exact_attention_mean_rel_l2": round(rel_l2, 5)}), flush=True)
+            del caches
+    return 0
+
+
 def run_stream(args, kvq, synth) -> int:
     """Long-context streaming on the 8B layer shape at batch 1: fill 131072 tokens with kvq_quantize_append in chunks of
     2048, then 256 fused decode steps on the growing cache.  Quantize tok/s and decode GB/s are reported separately."""
@@ -157,7 +201,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=4000)
     ap.add_argument("--warmup", type=int, default=400)
     ap.add_argument("--layers", type=int, default=40, help="resident layer caches taken in turn")
-    ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS) + ["sweep", "stream131k"],
+    ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS) + ["sweep", "groups", "stream131k"],
                     help="llama70b (default, the headline line) / llama8b: one JSON line; sweep: bit-allocation sweep on the 8B "
                          "layer (one line per allocation and context); stream131k: chunked fill + growing-cache decode at 131072")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -176,6 +220,8 @@ def main() -> int:
     dev = "cuda"
     if args.workload == "sweep":
         return run_sweep(args, kvq, synth)
+    if args.workload == "groups":
+        return run_groups(args, kvq, synth)
     if args.workload == "stream131k":
         return run_stream(args, kvq, synth)
     B, Hq, Hkv, T, desc = WORKLOADS[args.workload]

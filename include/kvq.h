@@ -130,10 +130,10 @@ kvq_status kvq_decode_step(const kvq_layout* layout, const kvq_cache* cache, con
  * reports it for keys at 3 and 4 bits); the caller divides by (t1-t0)*D (per head) or by the whole count.
  *   k_ref, v_ref  [B][H_kv][t1-t0][D] of ref_dtype (KVQ_F16 / KVQ_BF16): row 0 is token t0; element strides given,
  *                 D contiguous, 16-byte aligned rows; either may be NULL (its sums are then 0).
- *   sums          double[B][H_kv][2], overwritten.  x^ is the binary32 reconstruction of kvq_dequantize, the
- *                 difference is taken in binary32 and squared and accumulated in binary64; the order of the
- *                 additions is not fixed (relative spread about 2^-50).
- * t0 == t1 writes zeros. */
+ *   sums          double[B][H_kv][2], overwritten.  x^ is the binary32 reconstruction of kvq_dequantize; differences
+ *                 and the squares of 8 adjacent channels are summed in binary32 (relative error below 1e-6), the
+ *                 rest in binary64; the order of those additions is not fixed (relative spread about 2^-50).
+ * t0 == t1 writes zeros and reads no reference row. */
 kvq_status kvq_reconstruction_error(const kvq_layout* layout, const kvq_cache* cache, const void* k_ref,
                                     const void* v_ref, kvq_dtype ref_dtype, int64_t stride_b, int64_t stride_h,
                                     int64_t stride_t, int32_t t0, int32_t t1, double* sums, void* stream);

@@ -166,38 +166,70 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
   }
 }
 
-// Reconstruction x^ = code * scale + zero of 8 consecutive channels d0..d0+7 of token t of stream bh
-// (which = 0: keys, 1: values), as binary32 values; a 16-bit plane is widened exactly.
+// The 8 codes of channels 8*oct .. 8*oct+7 of key row t: B consecutive bytes of the row-major bit string.
+template <int B> __device__ __forceinline__ void key_codes8(const uint8_t* cs, int64_t t, int oct, uint32_t code[8]) {
+  const uint8_t* p = cs + t * (16 * B) + oct * B;
+  if (B == 16) {
+    const uint4 w = *reinterpret_cast<const uint4*>(p);
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) code[e] = (ww[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+  } else if (B == 8) {
+    const uint2 w = *reinterpret_cast<const uint2*>(p);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) code[e] = ((e < 4 ? w.x : w.y) >> (8 * (e & 3))) & 0xFFu;
+  } else {
+    const uint32_t w = B == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) code[e] = (w >> (B * e)) & ((1u << B) - 1u);
+  }
+}
+
+// The 8 codes of channels d0 .. d0+7 (d0 a multiple of 8) of value row t: the same field of 8 words 16 bytes apart.
+template <int B> __device__ __forceinline__ void value_codes8(const uint8_t* cs, int64_t t, int d0, uint32_t code[8]) {
+  int dw, bit;
+  v_field((int)(t & 31), d0, B, &dw, &bit);
+  const uint32_t* blk = reinterpret_cast<const uint32_t*>(cs + (t >> 5) * (int64_t)(512 * B)) + dw;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) code[e] = (blk[4 * e] >> bit) & (B == 16 ? 0xFFFFu : ((1u << B) - 1u));
+}
+
+// Reconstruction x^ = code * scale + zero of 8 consecutive channels d0..d0+7 (d0 a multiple of 8) of token t of
+// stream bh (which = 0: keys, 1: values), as binary32 values; a 16-bit plane is widened exactly.
 __device__ __forceinline__ void reconstruct8(const Geom& g, const kvq_cache& c, int which, int64_t bh, int64_t t, int d0,
                                              float val[8]) {
   const int b = which ? g.bits_v : g.bits_k;
   const int G = which ? g.g_v : g.g_k;
   const int ng = which ? g.ng_v : g.ng_k;
   const uint8_t* cs = (const uint8_t*)(which ? c.v_codes : c.k_codes) + bh * (which ? g.vc_stream : g.kc_stream);
-  const uint32_t* ms = (const uint32_t*)((const uint8_t*)(which ? c.v_meta : c.k_meta) + bh * (which ? g.vm_stream : g.km_stream));
-  const bool raw_bf16 = g.raw_dtype == KVQ_BF16;
-  float s = 0.f, z = 0.f;
-  if (b != 16) {
-    uint32_t m = ms[meta_index(t, d0 / G, ng)];
-    s = widen16((uint16_t)(m & 0xFFFF), false);
-    z = widen16((uint16_t)(m >> 16), false);
-  }
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int d = d0 + e;
-    uint32_t code;
-    if (!which) {
-      const int64_t bit = (t * kHeadDim + d) * b;
-      const uint32_t wd = *reinterpret_cast<const uint32_t*>(cs + ((bit >> 5) << 2));
-      code = (wd >> (bit & 31)) & (b == 16 ? 0xFFFFu : ((1u << b) - 1u));
-    } else {
-      int dw, bit;
-      v_field((int)(t & 31), d, b, &dw, &bit);
-      const uint32_t wd = reinterpret_cast<const uint32_t*>(cs + (t >> 5) * (int64_t)(512 * b))[dw];
-      code = (wd >> bit) & (b == 16 ? 0xFFFFu : ((1u << b) - 1u));
+  uint32_t code[8];
+  if (which) {
+    switch (b) {
+      case 2: value_codes8<2>(cs, t, d0, code); break;
+      case 4: value_codes8<4>(cs, t, d0, code); break;
+      case 8: value_codes8<8>(cs, t, d0, code); break;
+      default: value_codes8<16>(cs, t, d0, code); break;
     }
-    val[e] = b == 16 ? widen16((uint16_t)code, raw_bf16) : (float)code * s + z;
+  } else {
+    switch (b) {
+      case 2: key_codes8<2>(cs, t, d0 >> 3, code); break;
+      case 4: key_codes8<4>(cs, t, d0 >> 3, code); break;
+      case 8: key_codes8<8>(cs, t, d0 >> 3, code); break;
+      default: key_codes8<16>(cs, t, d0 >> 3, code); break;
+    }
   }
+  if (b == 16) {
+    const bool raw_bf16 = g.raw_dtype == KVQ_BF16;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) val[e] = widen16((uint16_t)code[e], raw_bf16);
+    return;
+  }
+  const uint32_t* ms = (const uint32_t*)((const uint8_t*)(which ? c.v_meta : c.k_meta) + bh * (which ? g.vm_stream : g.km_stream));
+  const uint32_t m = ms[meta_index(t, d0 / G, ng)];
+  const float s = widen16((uint16_t)(m & 0xFFFF), false);
+  const float z = widen16((uint16_t)(m >> 16), false);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) val[e] = (float)code[e] * s + z;
 }
 
 // One thread = 8 consecutive channels of one token.
@@ -233,7 +265,8 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Geom g, kvq_cache c, in
 
 // Squared reconstruction error (numerator of the MSE of App. B, "Frobenius Norm (MSE) Perspective").
 // One thread = 8 consecutive channels of one token; a workgroup walks 16-token slabs of one (b,h) stream with
-// stride gridDim.x; differences in binary32, squares summed in binary64, one atomic add per wavefront and tensor.
+// stride gridDim.x; differences and the squares of a thread's 8 channels in binary32, everything above that summed
+// in binary64, one atomic add per wavefront and tensor.
 __global__ __launch_bounds__(256) void sq_error_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_ref,
                                                        const uint16_t* __restrict__ v_ref, int ref_bf16, int64_t sb,
                                                        int64_t sh, int64_t st, int32_t t0, int32_t t1,
@@ -255,12 +288,13 @@ __global__ __launch_bounds__(256) void sq_error_kernel(Geom g, kvq_cache c, cons
       float val[8];
       reconstruct8(g, c, which, bh, t0 + r, d0, val);
       const uint32_t rw[4] = {raw[which].x, raw[which].y, raw[which].z, raw[which].w};
+      float sq = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float x = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), ref_bf16 != 0);
-        const double err = (double)(x - val[e]);
-        acc[which] += err * err;
+        const float err = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), ref_bf16 != 0) - val[e];
+        sq += err * err;
       }
+      acc[which] += (double)sq;
     }
   }
 #pragma unroll
