@@ -19,7 +19,18 @@
  *   - decode attention of one query row over the reconstructed cache,
  *     A = softmax(q K^T * softmax_scale), out = A V  (App. A notation table and the
  *     "attention outputs" equation), summed in binary64;
- *   - the reconstruction MSE of App. B "Frobenius Norm (MSE) Perspective".
+ *   - the reconstruction MSE of App. B "Frobenius Norm (MSE) Perspective";
+ *   - key-only randomized Hadamard rotation before quantization (Sec. 4 "Integration with
+ *     Rotation-Based Methods", Sec. 5.3: rotating keys carries the gain, rotating values does
+ *     not): every key row k becomes R k with R = H_D diag(s) / sqrt(D), H_D the Sylvester
+ *     Hadamard matrix and s a fixed vector of signs; the query is rotated by the same R at
+ *     decode time, so the scores q.k are those of the unrotated vectors up to rounding.  The
+ *     paper leaves the arithmetic to its third-party rotation package; the reading taken here:
+ *     the transform is the in-place butterfly network over strides 1, 2, 4, ..., D/2 in that
+ *     order, each butterfly one binary32 addition and one binary32 subtraction (lower index
+ *     minus higher index), then one multiplication by binary32(1/sqrt(D)); the rotated key row
+ *     goes to the quantizer in binary32, the rotated query is rounded once to binary16 (the
+ *     16-bit query a half-precision model hands to attention).
  *
  * Arithmetic of the quantizer is IEEE binary32, round-to-nearest-even, one rounding per
  * written operation (build with -ffp-contract=off, no fast-math).  The decisions that
@@ -60,6 +71,8 @@ typedef struct {
   int32_t bits_k, bits_v;   /* 2, 4, 8, or 16 = keep the 16-bit input unquantized */
   int32_t group_k, group_v; /* G: consecutive head_dim elements sharing one scale/zero */
   int32_t raw_dtype;        /* REF_F16 or REF_BF16: meaning of the planes when bits == 16 */
+  int32_t rotate_k;         /* 1: key rows are stored as codes of R k (needs bits_k < 16) */
+  uint32_t signs_k[4];      /* bit d of the 128-bit little-endian string set: s_d = -1 (D <= 128) */
 } ref_layout;
 
 /* ------------------------------------------------------------------ number formats */
@@ -167,6 +180,39 @@ static uint32_t get_bits_le(const uint8_t* base, int64_t bit_offset, int nbits) 
   return v;
 }
 
+/* ------------------------------------------------------------------ Hadamard rotation */
+
+/* In-place butterfly network of the Walsh-Hadamard transform in Sylvester (natural) order:
+ * after the strides 1, 2, ..., n/2 the vector holds H_n y, H_n[i][j] = (-1)^popcount(i & j).
+ * Every butterfly is one binary32 addition and one binary32 subtraction. */
+static void butterflies_f32(float* y, int n) {
+  for (int h = 1; h < n; h *= 2)
+    for (int i = 0; i < n; ++i)
+      if ((i & h) == 0) {
+        float a = y[i], b = y[i + h];
+        y[i] = a + b;
+        y[i + h] = a - b;
+      }
+}
+
+static int sign_is_minus(const uint32_t* signs, int d) { return (int)((signs[d / 32] >> (d % 32)) & 1u); }
+
+/* y = R x,  R = H_n diag(s) / sqrt(n)   (Sec. 4 "Integration with Rotation-Based Methods"). */
+void ref_rotate(const float* x, int n, const uint32_t* signs, float* y) {
+  float c = (float)(1.0 / sqrt((double)n));
+  for (int d = 0; d < n; ++d) y[d] = sign_is_minus(signs, d) ? -x[d] : x[d];
+  butterflies_f32(y, n);
+  for (int d = 0; d < n; ++d) y[d] = y[d] * c;
+}
+
+/* x = R^T y = diag(s) H_n y / sqrt(n)   (H_n is symmetric and H_n H_n = n I, so R^T R = I). */
+void ref_unrotate(const float* y, int n, const uint32_t* signs, float* x) {
+  float c = (float)(1.0 / sqrt((double)n));
+  for (int d = 0; d < n; ++d) x[d] = y[d];
+  butterflies_f32(x, n);
+  for (int d = 0; d < n; ++d) { float v = x[d] * c; x[d] = sign_is_minus(signs, d) ? -v : v; }
+}
+
 /* ------------------------------------------------------------------ the quantizer */
 
 /* Quantize one group of n binary32 values to `bits`-bit codes (1 <= bits <= 8).
@@ -219,10 +265,12 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
   int D = L->head_dim;
   if (pos < 0 || n_new < 0 || (int64_t)pos + n_new > L->max_seq) return -3;
   if (D % 64 || D > 1024) return -1;
+  if (L->rotate_k && (L->bits_k == 16 || D > 128 || (D & (D - 1)))) return -1;
   uint64_t pb[4];
   ref_plane_bytes(L, pb);
   int64_t streams = (int64_t)L->batch * L->kv_heads;
   float* row = (float*)malloc(sizeof(float) * (size_t)D);
+  float* plain = (float*)malloc(sizeof(float) * (size_t)D);
   uint8_t* codes = (uint8_t*)malloc((size_t)D);
   for (int which = 0; which < 2; ++which) {                 /* 0 = keys, 1 = values */
     int b = which ? L->bits_v : L->bits_k;
@@ -232,7 +280,7 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
     uint8_t* mplane = which ? v_meta : k_meta;
     int64_t cstream = (int64_t)(pb[which ? 2 : 0] / (uint64_t)streams);
     int64_t mstream = (int64_t)(pb[which ? 3 : 1] / (uint64_t)streams);
-    if (b != 16 && (D % G || (b != 2 && b != 4 && b != 8))) { free(row); free(codes); return -1; }
+    if (b != 16 && (D % G || (b != 2 && b != 4 && b != 8))) { free(row); free(plain); free(codes); return -1; }
     for (int64_t bh = 0; bh < streams; ++bh) {
       int64_t bi = bh / L->kv_heads, hi = bh % L->kv_heads;
       uint8_t* cs = cplane + bh * cstream;
@@ -249,6 +297,10 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
           continue;
         }
         for (int d = 0; d < D; ++d) row[d] = load_elem(src, in_dtype, base + d);
+        if (!which && L->rotate_k) {                        /* keys only: quantize R k instead of k */
+          memcpy(plain, row, sizeof(float) * (size_t)D);
+          ref_rotate(plain, D, L->signs_k, row);
+        }
         for (int g = 0; g < D / G; ++g) {
           uint16_t S, Z;
           ref_quantize_group(row + g * G, G, b, codes + g * G, &S, &Z);
@@ -263,13 +315,14 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
       }
     }
   }
-  free(row); free(codes);
+  free(row); free(plain); free(codes);
   return 0;
 }
 
-/* Reconstruct tokens [t0,t1) of both tensors as binary32: k_out, v_out are [B][H][t1-t0][D]. */
-int ref_dequantize(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
-                   const uint8_t* v_meta, int32_t t0, int32_t t1, float* k_out, float* v_out) {
+/* Reconstruct tokens [t0,t1) of both tensors as binary32 exactly as stored: k_out, v_out are
+ * [B][H][t1-t0][D]; with rotate_k the key rows are reconstructions of R k (rotated basis). */
+int ref_dequantize_stored(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
+                          const uint8_t* v_meta, int32_t t0, int32_t t1, float* k_out, float* v_out) {
   int D = L->head_dim;
   if (t0 < 0 || t1 < t0 || t1 > L->max_seq) return -3;
   uint64_t pb[4];
@@ -304,6 +357,23 @@ int ref_dequantize(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k
         }
     }
   }
+  return 0;
+}
+
+/* Reconstruct tokens [t0,t1) in the basis of the inputs: as ref_dequantize_stored, and with
+ * rotate_k every reconstructed key row y is taken back to R^T y. */
+int ref_dequantize(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
+                   const uint8_t* v_meta, int32_t t0, int32_t t1, float* k_out, float* v_out) {
+  int rc = ref_dequantize_stored(L, k_codes, k_meta, v_codes, v_meta, t0, t1, k_out, v_out);
+  if (rc || !L->rotate_k || !k_out) return rc;
+  int D = L->head_dim;
+  int64_t rows = (int64_t)L->batch * L->kv_heads * (t1 - t0);
+  float* tmp = (float*)malloc(sizeof(float) * (size_t)D);
+  for (int64_t r = 0; r < rows; ++r) {
+    ref_unrotate(k_out + r * D, D, L->signs_k, tmp);
+    memcpy(k_out + r * D, tmp, sizeof(float) * (size_t)D);
+  }
+  free(tmp);
   return 0;
 }
 
@@ -345,8 +415,9 @@ int ref_attention_dense(const float* K, const float* V, int32_t batch, int32_t k
   return 0;
 }
 
-/* Decode attention over the packed cache = reconstruct tokens [0, seq_len), then the dense
- * definition above.  out: [B][H_q][D] binary32. */
+/* Decode attention over the packed cache = reconstruct tokens [0, seq_len) as stored, then the
+ * dense definition above (with rotate_k: of the rotated query against the rotated keys, which is
+ * the same bilinear form because R is orthogonal).  out: [B][H_q][D] binary32. */
 int ref_decode_attention(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
                          const uint8_t* v_meta, const void* q, int q_dtype, int32_t q_heads, int32_t seq_len,
                          float softmax_scale, float* out) {
@@ -355,8 +426,23 @@ int ref_decode_attention(const ref_layout* L, const uint8_t* k_codes, const uint
   float* Kd = (float*)malloc(sizeof(float) * (size_t)n);
   float* Vd = (float*)malloc(sizeof(float) * (size_t)n);
   if (!Kd || !Vd) { free(Kd); free(Vd); return -2; }
-  int rc = ref_dequantize(L, k_codes, k_meta, v_codes, v_meta, 0, seq_len, Kd, Vd);
-  if (!rc) rc = ref_attention_dense(Kd, Vd, L->batch, L->kv_heads, q_heads, seq_len, L->head_dim, q, q_dtype, softmax_scale, out);
+  int rc = ref_dequantize_stored(L, k_codes, k_meta, v_codes, v_meta, 0, seq_len, Kd, Vd);
+  if (!rc && L->rotate_k) {
+    /* scores against rotated keys need the rotated query: q' = binary16(R q), row by row */
+    int D = L->head_dim;
+    int64_t nq = (int64_t)L->batch * q_heads;
+    float* qr = (float*)malloc(sizeof(float) * (size_t)(nq * D));
+    float* tmp = (float*)malloc(sizeof(float) * (size_t)D);
+    for (int64_t r = 0; r < nq; ++r) {
+      for (int d = 0; d < D; ++d) tmp[d] = load_elem(q, q_dtype, r * D + d);
+      ref_rotate(tmp, D, L->signs_k, qr + r * D);
+      for (int d = 0; d < D; ++d) qr[r * D + d] = ref_f16_to_f32(ref_f32_to_f16(qr[r * D + d]));
+    }
+    rc = ref_attention_dense(Kd, Vd, L->batch, L->kv_heads, q_heads, seq_len, D, qr, REF_F32, softmax_scale, out);
+    free(qr); free(tmp);
+  } else if (!rc) {
+    rc = ref_attention_dense(Kd, Vd, L->batch, L->kv_heads, q_heads, seq_len, L->head_dim, q, q_dtype, softmax_scale, out);
+  }
   free(Kd); free(Vd);
   return rc;
 }

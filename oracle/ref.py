@@ -30,7 +30,7 @@ def build(force: bool = False) -> str:
 
 class _Layout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "kv_heads", "max_seq", "head_dim", "bits_k", "bits_v",
-                                          "group_k", "group_v", "raw_dtype")]
+                                          "group_k", "group_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4)]
 
 
 @dataclass(frozen=True)
@@ -44,10 +44,12 @@ class Layout:
     group_k: int = 64
     group_v: int = 64
     raw_dtype: int = F16
+    rotate_k: int = 0
+    signs_k: tuple = (0, 0, 0, 0)      # 128 sign bits, little-endian: bit d set means s_d = -1
 
     def c(self) -> _Layout:
         return _Layout(self.batch, self.kv_heads, self.max_seq, self.head_dim, self.bits_k, self.bits_v,
-                       self.group_k, self.group_v, self.raw_dtype)
+                       self.group_k, self.group_v, self.raw_dtype, self.rotate_k, (C.c_uint32 * 4)(*self.signs_k))
 
 
 _lib = None
@@ -135,12 +137,34 @@ def quantize_append(L: Layout, planes, k_new: np.ndarray, v_new: np.ndarray, pos
         raise ValueError(f"ref_quantize_append rc={rc}")
 
 
-def dequantize(L: Layout, planes, t0: int, t1: int):
+def _signs_array(signs):
+    return (C.c_uint32 * 4)(*signs)
+
+
+def rotate(x: np.ndarray, signs=(0, 0, 0, 0)) -> np.ndarray:
+    """R x for one vector (binary32), R = H diag(s) / sqrt(n)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    y = np.zeros_like(x)
+    lib().ref_rotate(_ptr(x), C.c_int(x.size), _signs_array(signs), _ptr(y))
+    return y
+
+
+def unrotate(y: np.ndarray, signs=(0, 0, 0, 0)) -> np.ndarray:
+    """R^T y for one vector (binary32)."""
+    y = np.ascontiguousarray(y, dtype=np.float32)
+    x = np.zeros_like(y)
+    lib().ref_unrotate(_ptr(y), C.c_int(y.size), _signs_array(signs), _ptr(x))
+    return x
+
+
+def dequantize(L: Layout, planes, t0: int, t1: int, stored: bool = False):
+    """Reconstruction of tokens [t0, t1); stored=True keeps rotated keys in the rotated basis."""
     shape = (L.batch, L.kv_heads, t1 - t0, L.head_dim)
     k = np.zeros(shape, dtype=np.float32)
     v = np.zeros(shape, dtype=np.float32)
     cl = L.c()
-    rc = lib().ref_dequantize(C.byref(cl), _ptr(planes[0]), _ptr(planes[1]), _ptr(planes[2]), _ptr(planes[3]),
+    fn = lib().ref_dequantize_stored if stored else lib().ref_dequantize
+    rc = fn(C.byref(cl), _ptr(planes[0]), _ptr(planes[1]), _ptr(planes[2]), _ptr(planes[3]),
                               C.c_int32(t0), C.c_int32(t1), _ptr(k), _ptr(v))
     if rc:
         raise ValueError(f"ref_dequantize rc={rc}")
