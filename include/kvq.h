@@ -26,6 +26,15 @@
  *     x^_d     = code_d * scale + zero                                   (App. B "Dequantization")
  *   every operation rounded once in binary32, round-to-nearest-even; codes use the STORED scale/zero.
  *
+ * Rotation (rotate_k = 1; Sec. 4 "Integration with Rotation-Based Methods", Sec. 5.3: rotating the keys, not the
+ * values, is what helps): every key row k is replaced by R k, R = H_128 diag(s) / sqrt(128) with H_128 the Sylvester
+ * Hadamard matrix and s the signs of signs_k, before it is quantized, and the query is replaced by R q inside the
+ * attention kernels, so the scores are those of the unrotated vectors up to rounding.  Arithmetic: signs first
+ * (exact), then the butterfly network over strides 1, 2, 4, ..., 64 in that order, each butterfly one binary32
+ * addition and one binary32 subtraction (lower index minus higher index), then one multiplication by
+ * binary32(1/sqrt(128)).  R k goes to the quantizer in binary32; R q is rounded once to binary16.
+ * kvq_dequantize returns keys in the input basis (R^T of the stored reconstruction: butterflies, scale, signs).
+ *
  * Storage format of one layer (sizes from kvq_cache_bytes; T_cap = max_seq rounded up to 32):
  *   k_codes  [B][H_kv][T_cap][D*b_K/8]      element d of a row at bits [d*b_K, (d+1)*b_K), little-endian
  *   k_meta   [B][H_kv][T_cap/16][D/G_K][16] entries {uint16 scale, uint16 zero} (binary16 patterns);
@@ -75,6 +84,8 @@ typedef struct {
   int32_t group_k, group_v;
   int32_t axis_k, axis_v;
   int32_t raw_dtype;
+  int32_t rotate_k;     /* 0 / 1: key-only randomized Hadamard rotation (see "Rotation" above); needs bits_k < 16 */
+  uint32_t signs_k[4];  /* the 128 signs of the rotation: bit d%32 of word d/32 set means s_d = -1 */
 } kvq_layout;
 
 /* Caller-owned device buffers of at least the sizes kvq_cache_bytes reports (16-byte aligned).

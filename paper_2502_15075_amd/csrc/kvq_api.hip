@@ -18,6 +18,8 @@ kvq_status check_layout(const kvq_layout* L) {
       (L->axis_v != KVQ_AXIS_HEAD_DIM && L->axis_v != KVQ_AXIS_SEQ))
     return KVQ_ERR_INVALID_ARG;
   if (L->raw_dtype != KVQ_F16 && L->raw_dtype != KVQ_BF16) return KVQ_ERR_INVALID_ARG;
+  if (L->rotate_k != 0 && L->rotate_k != 1) return KVQ_ERR_INVALID_ARG;
+  if (L->rotate_k && L->bits_k == 16) return KVQ_ERR_INVALID_ARG;   // the rotation exists for quantized keys only
   if (L->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;
   if (L->axis_k != KVQ_AXIS_HEAD_DIM || L->axis_v != KVQ_AXIS_HEAD_DIM) return KVQ_ERR_UNSUPPORTED;
   if ((int64_t)L->batch * L->kv_heads > 65535) return KVQ_ERR_UNSUPPORTED;

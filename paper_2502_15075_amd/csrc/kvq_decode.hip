@@ -348,6 +348,14 @@ __device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, i
   float x[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), a.in_bf16);
+  if (g.rotate_k) {                                // keys only; both 16-lane rows run the butterflies, the value row
+    float xr[8];                                   // keeps its own numbers
+#pragma unroll
+    for (int e = 0; e < 8; ++e) xr[e] = x[e];
+    rotate8(xr, lane16, rot_sign_bits(g.signs_k, lane16));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = is_v ? x[e] : xr[e];
+  }
   uint32_t codes[8];
   uint16_t S, Z;
   const int bits = is_v ? BV : BK;
@@ -475,9 +483,27 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   }
 
   // ---- query rows of this kv head -> LDS (one coalesced 16-byte load per thread), then per-lane operands
-  if (tid < R * 16)
-    reinterpret_cast<u32x4*>(&sm_q[0][0])[tid] =
-        *reinterpret_cast<const u32x4*>(q + ((int64_t)b * q_heads + hk * R) * kHeadDim + tid * 8);
+  bool q_is_bf16 = q_bf16 != 0;
+  if (tid < R * 16) {
+    u32x4 raw = *reinterpret_cast<const u32x4*>(q + ((int64_t)b * q_heads + hk * R) * kHeadDim + tid * 8);
+    if constexpr (!RAW) {
+      if (g.rotate_k) {
+        // rotated keys: the scores need R q, rounded once to binary16 (16 threads hold one query row, 8 channels each)
+        const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), q_is_bf16);
+        rotate8(x, tid & 15, rot_sign_bits(g.signs_k, tid & 15));
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          w[e] = (uint32_t)f32_to_f16_bits(x[2 * e]) | ((uint32_t)f32_to_f16_bits(x[2 * e + 1]) << 16);
+        raw = u32x4{w[0], w[1], w[2], w[3]};
+      }
+    }
+    reinterpret_cast<u32x4*>(&sm_q[0][0])[tid] = raw;
+  }
+  if constexpr (!RAW) q_is_bf16 = q_is_bf16 && !g.rotate_k;      // the staged rotated query is binary16
   __syncthreads();
   if (!early) {
 #pragma unroll
@@ -485,7 +511,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       if (k < n_full) load_step<BK, BV>(buf[k], L, step_of(k));
   }
   auto widen = [&](uint16_t bits) -> float {
-    return q_bf16 ? __uint_as_float((uint32_t)bits << 16) : (float)__builtin_bit_cast(_Float16, bits);
+    return q_is_bf16 ? __uint_as_float((uint32_t)bits << 16) : (float)__builtin_bit_cast(_Float16, bits);
   };
   // column c of set cs carries head h restricted to key group grp + cs*kSetGroups (zero elsewhere); this lane's 32
   // channels are 32j..32j+31 and lie in one group

@@ -15,6 +15,8 @@ struct Geom {
   int32_t batch, kv_heads, t_cap;   // t_cap = max_seq rounded up to kBlockTokens
   int32_t bits_k, bits_v, ng_k, ng_v, g_k, g_v;
   int32_t raw_dtype;
+  int32_t rotate_k;                 // key rows are stored as codes of R k (randomized Hadamard rotation)
+  uint32_t signs_k[4];              // bit d set: s_d = -1
   int64_t kc_stream, km_stream, vc_stream, vm_stream;   // bytes per (b,h) stream in each plane
 };
 
@@ -29,6 +31,8 @@ inline Geom make_geom(const kvq_layout& L) {
   g.g_v = L.bits_v == 16 ? kHeadDim : L.group_v;
   g.ng_k = kHeadDim / g.g_k; g.ng_v = kHeadDim / g.g_v;
   g.raw_dtype = L.raw_dtype;
+  g.rotate_k = L.rotate_k;
+  for (int i = 0; i < 4; ++i) g.signs_k[i] = L.rotate_k ? L.signs_k[i] : 0u;
   g.kc_stream = (int64_t)g.t_cap * (kHeadDim * L.bits_k / 8);
   g.vc_stream = (int64_t)g.t_cap * (kHeadDim * L.bits_v / 8);
   g.km_stream = L.bits_k == 16 ? 0 : (int64_t)g.t_cap * g.ng_k * 4;

@@ -76,6 +76,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         float x[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
+        if (g.rotate_k) rotate8(x, lane16, rot_sign_bits(g.signs_k, lane16));   // whole 16-lane rows are here together
         uint32_t codes[8];
         uint16_t S, Z;
         const int lpg = g.g_k >> 3;
@@ -250,6 +251,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Geom g, kvq_cache c, in
     if (!out) continue;
     float val[8];
     reconstruct8(g, c, which, bh, t, d0, val);
+    if (!which && g.rotate_k) unrotate8(val, oct, rot_sign_bits(g.signs_k, oct));   // 16 threads = one row, all here
     const int64_t o = row * kHeadDim + d0;
     if (out_dtype == KVQ_F32) {
       float* p = (float*)out + o;
@@ -288,10 +290,15 @@ __global__ __launch_bounds__(256) void sq_error_kernel(Geom g, kvq_cache c, cons
       float val[8];
       reconstruct8(g, c, which, bh, t0 + r, d0, val);
       const uint32_t rw[4] = {raw[which].x, raw[which].y, raw[which].z, raw[which].w};
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), ref_bf16 != 0);
+      // rotated keys are compared in the rotated basis: ||R k - y||_2 = ||k - R^T y||_2
+      if (!which && g.rotate_k) rotate8(x, tid & 15, rot_sign_bits(g.signs_k, tid & 15));
       float sq = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float err = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), ref_bf16 != 0) - val[e];
+        const float err = x[e] - val[e];
         sq += err * err;
       }
       acc[which] += (double)sq;

@@ -27,6 +27,64 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
   return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
+// ---- randomized Hadamard rotation of a 128-channel row (Sec. 4 "Integration with Rotation-Based Methods") ----
+// The row is held 8 consecutive channels per lane by 16 neighbouring lanes (lane16 = channel / 8).  R = H diag(s) /
+// sqrt(128): signs, then the butterflies over strides 1, 2, 4 (inside the lane) and 8, 16, 32, 64 (partner lane
+// lane16 ^ stride/8), each one binary32 add and one subtract (lower index minus higher index), then the scale.
+
+constexpr float kRotScale = 0.08838834764831845f;   // binary32(1/sqrt(128))
+
+// The 8 sign bits of the channels of lane16 (bit e set: channel 8*lane16 + e is negated).
+__device__ __forceinline__ uint32_t rot_sign_bits(const uint32_t signs[4], int lane16) {
+  const int w = lane16 >> 2;
+  const uint32_t word = w == 0 ? signs[0] : w == 1 ? signs[1] : w == 2 ? signs[2] : signs[3];
+  return (word >> (8 * (lane16 & 3))) & 0xFFu;
+}
+
+__device__ __forceinline__ void hadamard8x16(float x[8], int lane16) {
+#pragma clang fp contract(off)
+#pragma unroll
+  for (int h = 1; h < 8; h <<= 1) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if ((i & h) == 0) {
+        const float a = x[i], b = x[i + h];
+        x[i] = a + b;
+        x[i + h] = a - b;
+      }
+  }
+#pragma unroll
+  for (int m = 1; m < 16; m <<= 1) {
+    const bool upper = (lane16 & m) != 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float o = __shfl_xor(x[e], m, 16);
+      x[e] = upper ? o - x[e] : x[e] + o;
+    }
+  }
+}
+
+// x <- R x
+__device__ __forceinline__ void rotate8(float x[8], int lane16, uint32_t sign_bits) {
+#pragma clang fp contract(off)
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x[e] = (sign_bits >> e) & 1u ? -x[e] : x[e];
+  hadamard8x16(x, lane16);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x[e] = x[e] * kRotScale;
+}
+
+// x <- R^T x
+__device__ __forceinline__ void unrotate8(float x[8], int lane16, uint32_t sign_bits) {
+#pragma clang fp contract(off)
+  hadamard8x16(x, lane16);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float v = x[e] * kRotScale;
+    x[e] = (sign_bits >> e) & 1u ? -v : v;
+  }
+}
+
 // Quantize 8 consecutive elements held by this lane; the group spans `lanes_per_group`
 // neighbouring lanes (a power of two <= 16, aligned).  Returns the 8 codes, and the stored
 // scale/zero patterns through S, Z.

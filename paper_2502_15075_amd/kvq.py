@@ -30,7 +30,7 @@ class KvqError(RuntimeError):
 
 class _CLayout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "kv_heads", "max_seq", "head_dim", "bits_k", "bits_v", "group_k",
-                                          "group_v", "axis_k", "axis_v", "raw_dtype")]
+                                          "group_v", "axis_k", "axis_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4)]
 
 
 class _CCache(C.Structure):
@@ -87,10 +87,12 @@ class Layout:
     axis_k: int = AXIS_HEAD_DIM
     axis_v: int = AXIS_HEAD_DIM
     raw_dtype: int = KVQ_F16
+    rotate_k: int = 0
+    signs_k: tuple = (0, 0, 0, 0)
 
     def c(self) -> _CLayout:
         return _CLayout(self.batch, self.kv_heads, self.max_seq, self.head_dim, self.bits_k, self.bits_v, self.group_k,
-                        self.group_v, self.axis_k, self.axis_v, self.raw_dtype)
+                        self.group_v, self.axis_k, self.axis_v, self.raw_dtype, self.rotate_k, (C.c_uint32 * 4)(*self.signs_k))
 
 
 def _check(status: int, where: str) -> None:

@@ -25,9 +25,13 @@ def kvq():
     return m
 
 
-def _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, raw=0):
-    return (kvq.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw),
-            oracle.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw))
+SIGNS = (0x9E3779B9, 0x7F4A7C15, 0xF39CC060, 0x5CEDC834)      # the 128 signs of the key rotation used in these tests
+
+
+def _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, raw=0, rot=0):
+    signs = SIGNS if rot else (0, 0, 0, 0)
+    return (kvq.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw, rotate_k=rot, signs_k=signs),
+            oracle.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw, rotate_k=rot, signs_k=signs))
 
 
 def _fill_both(kvq, oracle, Lg, Lo, K, V, chunks, fill=0xA5):
@@ -427,3 +431,81 @@ def test_reconstruction_error_of_unquantized_planes_is_zero(kvq, oracle):
     sums = torch.full((B, H, 2), -1.0, dtype=torch.float64, device="cuda")
     kvq.reconstruction_error(Lg, cache, K.cuda(), V.cuda(), 0, sums)
     assert (sums.cpu().numpy() == 0).all()
+
+
+# --------------------------------------------------------------------------- key-only Hadamard rotation
+
+@pytest.mark.parametrize("bk,bv,gk,gv", [(4, 2, 64, 64), (2, 4, 32, 128), (8, 8, 128, 32), (2, 2, 64, 64)])
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_rotated_keys_planes_and_reconstruction_are_identical(kvq, oracle, bk, bv, gk, gv, dtype):
+    """Sec. 4 rotation case study, key-only: ragged chunked appends give the oracle's bytes, kvq_dequantize gives the
+    oracle's binary32 reconstruction in the input basis, and the squared key error (taken in the rotated basis on the
+    GPU, in the input basis by the oracle: equal up to the binary32 rounding of the rotation, about 1e-7 of |k| per
+    entry against errors of 1e-2 |k|) agrees to 2e-5."""
+    B, H, T = 2, 3, 203
+    K, V, _ = synth.make_kvq(60 + bk + bv, B, H, H, T, dtype=dtype)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, rot=1)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, 1), (1, 70), (70, 128), (128, 129), (129, 203)])
+    _assert_planes_equal(cache, planes)
+    for t0, t1 in ((0, T), (17, 93)):
+        ko = torch.empty(B, H, t1 - t0, 128, dtype=torch.float32, device="cuda")
+        vo = torch.empty_like(ko)
+        kvq.dequantize(Lg, cache, t0, t1, ko, vo)
+        kd, vd = oracle.dequantize(Lo, planes, t0, t1)
+        assert np.array_equal(ko.cpu().numpy().view(np.uint32), kd.view(np.uint32))
+        assert np.array_equal(vo.cpu().numpy().view(np.uint32), vd.view(np.uint32))
+    sums = torch.empty(B, H, 2, dtype=torch.float64, device="cuda")
+    kvq.reconstruction_error(Lg, cache, K.cuda(), V.cuda(), 0, sums)
+    got = sums.cpu().numpy()
+    Kh, Vh = oracle.dequantize(Lo, planes, 0, T)
+    for b in range(B):
+        for h in range(H):
+            assert got[b, h, 0] == pytest.approx(oracle.mse(K[b, h].float().numpy(), Kh[b, h]) * T * 128, rel=2e-5)
+            assert got[b, h, 1] == pytest.approx(oracle.mse(V[b, h].float().numpy(), Vh[b, h]) * T * 128, rel=1e-6)
+
+
+@pytest.mark.parametrize("R", [1, 2, 4, 8])
+@pytest.mark.parametrize("bk,bv,gk,gv", [(4, 2, 64, 64), (2, 4, 64, 128), (8, 8, 64, 64)])
+def test_rotated_keys_attention(kvq, oracle, R, bk, bv, gk, gv):
+    B, H, T = 2, 2, 333
+    K, V, q = synth.make_kvq(130 + R, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, rot=1)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, T)])
+    qn = synth.to_numpy_bits(q)
+    for seq_len in (333, 257, 64, 1):
+        out = _decode(kvq, Lg, cache, q, seq_len)
+        ref = oracle.decode_attention(Lo, planes, qn, seq_len, 1 / math.sqrt(128), bf16=True)
+        err = _rel_err(out.cpu().numpy(), ref)
+        assert err < TOL, (seq_len, err)
+
+
+def test_rotated_keys_small_groups_eight_heads_fp16_and_multi_split(kvq, oracle):
+    B, H, R, T = 1, 2, 8, 2100
+    K, V, q = synth.make_kvq(77, B, H, H * R, T, dtype=torch.float16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, 4, 2, 32, 64, rot=1)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, T)])
+    out = _decode(kvq, Lg, cache, q, T)
+    ref = oracle.decode_attention(Lo, planes, q.numpy(), T, 1 / math.sqrt(128))
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+
+
+@pytest.mark.parametrize("bk,bv,gk,gv,R", [(4, 2, 64, 64, 8), (4, 2, 32, 32, 4), (2, 4, 64, 128, 1)])
+def test_rotated_keys_fused_decode_steps(kvq, oracle, bk, bv, gk, gv, R):
+    B, H, T0, nstep = 2, 2, 60, 6
+    T = T0 + nstep
+    K, V, _ = synth.make_kvq(25 + bk, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, rot=1)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K[:, :, :T0], V[:, :, :T0], [(0, T0)])
+    Kd, Vd = K.cuda(), V.cuda()
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    for i in range(nstep):
+        pos = T0 + i
+        _, _, q = synth.make_kvq(400 + i, B, H, H * R, 1, dtype=torch.bfloat16)
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), 1 / math.sqrt(128), out, ws)
+        torch.cuda.synchronize()
+        oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, pos:pos + 1])),
+                               np.ascontiguousarray(synth.to_numpy_bits(V[:, :, pos:pos + 1])), pos, bf16=True)
+        _assert_planes_equal(cache, planes)
+        ref = oracle.decode_attention(Lo, planes, synth.to_numpy_bits(q), pos + 1, 1 / math.sqrt(128), bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
