@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the K4V2 decode hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--workload llama70b|llama8b|sweep|groups|stream131k]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--workload llama70b|llama8b|sweep|groups|rotation|stream131k]
 
 One step = one pass of the whole hot path over one layer's batch: quantize-and-append the new
 token's K/V (B x H_kv rows) into the packed cache, then single-token decode attention over the
@@ -144,6 +144,48 @@ def run_groups(args, kvq, synth) -> int:
     return 0
 
 
+def run_rotation(args, kvq, synth) -> int:
+    """Rotation case study (Sec. 4 "Integration with Rotation-Based Methods", Sec. 5.3) on the 8B layer shape at context
+    32768, 64-channel groups: K2V2, K2V4, K4V2, K4V4 without rotation and with key-only rotation.  Per line: key MSE
+    (kvq_reconstruction_error), attention-output error against exact attention on the original tensors (CPU oracle,
+    batch element 0), bulk quantize-append rate and fused decode-step time, so that what the rotation buys and what
+    its butterflies cost are on one line."""
+    import numpy as np
+    from oracle import ref
+    B, Hq, Hkv, D, T, G = 8, 32, 8, 128, 32768, 64
+    scale = 1.0 / math.sqrt(D)
+    signs = (0x9E3779B9, 0x7F4A7C15, 0xF39CC060, 0x5CEDC834)
+    K, V, q = synth.make_kvq(6, B, Hkv, Hq, T, D, dtype=torch.bfloat16, device="cuda")
+    want = ref.attention_dense(K[:1].float().cpu().numpy(), V[:1].float().cpu().numpy(),
+                               synth.to_numpy_bits(q[:1]), scale, bf16=True).astype(np.float64)
+    sums = torch.empty(B, Hkv, 2, dtype=torch.float64, device="cuda")
+    for bk, bv in ((2, 2), (2, 4), (4, 2), (4, 4)):
+        for rot in (0, 1):
+            L = kvq.Layout(B, Hkv, T, D, bk, bv, G, G, raw_dtype=kvq.KVQ_BF16, rotate_k=rot, signs_k=signs if rot else (0, 0, 0, 0))
+            row_bytes = 16 * bk + 16 * bv + 2 * 4 * (D // G)
+            kv_bytes = B * Hkv * T * row_bytes
+            copies = 5
+            caches = [kvq.Cache(L, device="cuda") for _ in range(copies)]
+            ms_q = _time_loop(lambda i: kvq.quantize_append(L, caches[i % copies], K, V, 0), 50, 10)
+            ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, Hq, T)), dtype=torch.uint8, device="cuda")
+            out = torch.empty(B, Hq, D, dtype=torch.float32, device="cuda")
+            kn, vn = K[:, :, T - 1].contiguous(), V[:, :, T - 1].contiguous()
+            ms = _time_loop(lambda i: kvq.decode_step(L, caches[i % copies], kn, vn, T - 1, q, scale, out, ws), 1000, 200)
+            kvq.reconstruction_error(L, caches[0], K, V, 0, sums)
+            tot = sums.sum(dim=(0, 1)).cpu().numpy()
+            n = B * Hkv * T * D
+            got = out[:1].cpu().numpy().astype(np.float64)
+            rel_l2 = float((np.linalg.norm(got - want, axis=-1) / np.linalg.norm(want, axis=-1)).mean())
+            print(json.dumps({"workload": f"8B layer, B=8, T={T}, K{bk}V{bv} G=64, key rotation {'on' if rot else 'off'}",
+                              "alloc": f"K{bk}V{bv}", "rotate_k": rot, "mse_k": float(tot[0] / n), "mse_v": float(tot[1] / n),
+                              "err_vs_exact_attention_mean_rel_l2": round(rel_l2, 5),
+                              "quantize_tok_s_bulk": round(B * T / ms_q * 1e3, 1),
+                              "quantize_GB_s": round(B * Hkv * T * (512 + row_bytes) / ms_q / 1e6, 1),
+                              "decode_step_us": round(ms * 1e3, 2), "decode_GB_s": round(kv_bytes / ms / 1e6, 1)}), flush=True)
+            del caches
+    return 0
+
+
 def run_stream(args, kvq, synth) -> int:
     """Long-context streaming on the 8B layer shape at batch 1: fill 131072 tokens with kvq_quantize_append in chunks of
     2048, then 256 fused decode steps on the growing cache.  Quantize tok/s and decode GB/s are reported separately."""
@@ -201,7 +243,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=4000)
     ap.add_argument("--warmup", type=int, default=400)
     ap.add_argument("--layers", type=int, default=40, help="resident layer caches taken in turn")
-    ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS) + ["sweep", "groups", "stream131k"],
+    ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS) + ["sweep", "groups", "rotation", "stream131k"],
                     help="llama70b (default, the headline line) / llama8b: one JSON line; sweep: bit-allocation sweep on the 8B "
                          "layer (one line per allocation and context); stream131k: chunked fill + growing-cache decode at 131072")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -222,6 +264,8 @@ def main() -> int:
         return run_sweep(args, kvq, synth)
     if args.workload == "groups":
         return run_groups(args, kvq, synth)
+    if args.workload == "rotation":
+        return run_rotation(args, kvq, synth)
     if args.workload == "stream131k":
         return run_stream(args, kvq, synth)
     B, Hq, Hkv, T, desc = WORKLOADS[args.workload]
