@@ -247,6 +247,8 @@ def main() -> int:
                     help="llama70b (default, the headline line) / llama8b: one JSON line; sweep: bit-allocation sweep on the 8B "
                          "layer (one line per allocation and context); stream131k: chunked fill + growing-cache decode at 131072")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the same steps")
+    ap.add_argument("--event-every", type=int, default=8, help="HIP-event pair around every N-th timed launch")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run 5 plain device copies of this size (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -318,17 +320,43 @@ def main() -> int:
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    # HIP-event pairs around every `event_every`-th launch of the timed region (an event pair between two launches
+    # costs about a microsecond of idle memory system: sampling keeps the timed region close to undisturbed)
+    every = max(1, args.event_every)
+    events = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for i in range(0, args.steps, every)}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i, events[i])
+        step(args.warmup + i, events.get(i))
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    decode_ms = sum(a.elapsed_time(b) for a, b in events) / args.steps
+    decode_ms = sum(a.elapsed_time(b) for a, b in events.values()) / len(events)
     value = kv_bytes / (ms_per_step * 1e-3) / 1e9
     achieved = kv_bytes / (decode_ms * 1e-3) / 1e9
+
+    # ---- the same steps replayed from a HIP graph (one graph = one pass over the resident layers): what a serving
+    # loop that captures its decode step would see; matters for the small shapes, where launches dominate
+    graph_ms = None
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=side):
+                for i in range(len(layers)):
+                    step(i)
+            reps = max(1, args.steps // len(layers))
+            for _ in range(max(1, reps // 10)):
+                gr.replay()
+            side.synchronize()
+            g0 = time.perf_counter()
+            for _ in range(reps):
+                gr.replay()
+            side.synchronize()
+            graph_ms = (time.perf_counter() - g0) * 1e3 / (reps * len(layers))
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
 
     # ---- parity of the sampled outputs and the CPU oracle timed on the same sample
     cpu_baseline, parity = None, None
@@ -366,11 +394,12 @@ def main() -> int:
         "config": {"workload": desc, "layers_resident": args.layers, "kv_bytes_per_step": kv_bytes,
                    "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
                    "decode_tok_s": round(B / (ms_per_step * 1e-3), 1),
-                   "quantize_tok_s_bulk_fill": round(fill_tokens / (fill_ms * 1e-3), 1)},
+                   "quantize_tok_s_bulk_fill": round(fill_tokens / (fill_ms * 1e-3), 1),
+                   "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 5)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": _traffic_from_profile(f"decode_k4v2_{args.workload}_pmc.txt"),
-                     "kernel": "kvq decode_kernel<4,2,R,NW> (fused step; + merge_kernel when the sequence is split), mean of HIP-event pairs around each launch",
+                     "kernel": "kvq decode_kernel<4,2,R,NW> (fused step; + merge_kernel when the sequence is split), mean of HIP-event pairs around every " + str(every) + "-th launch of the timed region",
                      "kernel_ms": round(decode_ms, 5)},
         "cpu_baseline": cpu_baseline,
     }

@@ -509,3 +509,49 @@ def test_rotated_keys_fused_decode_steps(kvq, oracle, bk, bv, gk, gv, R):
         _assert_planes_equal(cache, planes)
         ref = oracle.decode_attention(Lo, planes, synth.to_numpy_bits(q), pos + 1, 1 / math.sqrt(128), bf16=True)
         assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
+
+
+# --------------------------------------------------------------------------- HIP graph capture
+
+def test_decode_step_replayed_from_a_hip_graph(kvq, oracle):
+    """A captured kvq_decode_step (split sequence: decode + merge kernels, workspace) replayed several times, with
+    eager work and synchronizations between the replays, gives the eager result every time and stays within the
+    oracle's tolerance; the reconstruction-error call (fill kernel + reduction with atomics) is captured too."""
+    B, H, R, T = 1, 2, 4, 1500
+    K, V, q = synth.make_kvq(55, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, 4, 2, 64, 64)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K[:, :, :T - 1], V[:, :, :T - 1], [(0, T - 1)])
+    Kd, Vd, qd = K.cuda(), V.cuda(), q.cuda()
+    k1, v1 = Kd[:, :, T - 1].contiguous(), Vd[:, :, T - 1].contiguous()
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, T)), dtype=torch.uint8, device="cuda")
+    assert ws.numel() > 16                                   # the case must exercise the split + merge path
+    eager = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    kvq.decode_step(Lg, cache, k1, v1, T - 1, qd, 1 / math.sqrt(128), eager, ws)
+    sums_eager = torch.empty(B, H, 2, dtype=torch.float64, device="cuda")
+    kvq.reconstruction_error(Lg, cache, Kd, Vd, 0, sums_eager)
+    torch.cuda.synchronize()
+    out = torch.zeros_like(eager)
+    sums = torch.zeros_like(sums_eager)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            kvq.decode_step(Lg, cache, k1, v1, T - 1, qd, 1 / math.sqrt(128), out, ws)
+            kvq.reconstruction_error(Lg, cache, Kd, Vd, 0, sums)
+    torch.cuda.current_stream().wait_stream(side)
+    oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, T - 1:T])),
+                           np.ascontiguousarray(synth.to_numpy_bits(V[:, :, T - 1:T])), T - 1, bf16=True)
+    ref = oracle.decode_attention(Lo, planes, synth.to_numpy_bits(q), T, 1 / math.sqrt(128), bf16=True)
+    for rep in range(4):
+        out.fill_(float("nan")); sums.fill_(-1.0); ws.random_(0, 256)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
+        assert torch.allclose(sums, sums_eager, rtol=1e-12, atol=0), rep
+        assert _rel_err(out.cpu().numpy(), ref) < TOL
+        # eager work of the program's own between the replays
+        kvq.decode_attention(Lg, cache, qd, T - 7, 1 / math.sqrt(128), torch.empty_like(eager), ws)
+        torch.cuda.synchronize()
+    _assert_planes_equal(cache, planes)
