@@ -414,6 +414,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   __shared__ __attribute__((aligned(16))) uint16_t sm_q[R][kHeadDim];
   __shared__ __attribute__((aligned(16))) uint8_t sm_meta[NW][1024];
   __shared__ uint8_t sm_vnew[kHeadDim];
+  __shared__ float sm_qsum[R][4];
   const Geom& g = a.g;
   const kvq_cache& cache = a.cache;
   const uint16_t* __restrict__ q = a.q;
@@ -502,6 +503,17 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       }
     }
     reinterpret_cast<u32x4*>(&sm_q[0][0])[tid] = raw;
+    if constexpr (!RAW) {
+      // per-group sums of the (staged) query: the zero points of a key group enter the scores through them
+      const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+      const bool f16_now = !q_is_bf16 || g.rotate_k;
+      float part = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part += widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), !f16_now);
+      const int lpg = g.g_k >> 3;                    // lanes per key group: 4, 8 or 16
+      for (int off = 1; off < lpg; off <<= 1) part += __shfl_xor(part, off, 16);
+      if (((tid & 15) & (lpg - 1)) == 0) sm_qsum[tid >> 4][(tid & 15) / lpg] = part;
+    }
   }
   if constexpr (!RAW) q_is_bf16 = q_is_bf16 && !g.rotate_k;      // the staged rotated query is binary16
   __syncthreads();
@@ -545,16 +557,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
         qb[cs][m] = u32x4{w[0], w[1], w[2], w[3]};
       }
       float qsum = 0.f;
-      if (act && !RAW) {
-#pragma unroll
-        for (int c8 = 0; c8 < 16; ++c8) {
-          if ((8 * c8) / g.g_k != gcs) continue;
-          const u32x4 v = reinterpret_cast<const u32x4*>(&sm_q[h][0])[c8];
-          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-          for (int e = 0; e < 8; ++e) qsum += widen((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
-        }
-      }
+      if constexpr (!RAW) { if (act) qsum = sm_qsum[h][gcs]; }
       qsum_u[cs] = qsum * kUnit;
     }
   }
