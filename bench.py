@@ -248,7 +248,7 @@ def main() -> int:
                          "layer (one line per allocation and context); stream131k: chunked fill + growing-cache decode at 131072")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the same steps")
-    ap.add_argument("--event-every", type=int, default=8, help="HIP-event pair around every N-th timed launch")
+    ap.add_argument("--event-every", type=int, default=8, help="launches per HIP-event pair in the timed region")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run 5 plain device copies of this size (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -301,14 +301,10 @@ def main() -> int:
     ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, Hq, T)), dtype=torch.uint8, device=dev)
     out = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
 
-    def step(i, ev=None):
+    def step(i):
         # one launch: the new token's K/V rows are quantized into position T-1 by the decode kernel itself
         cache, k1, v1, q = layers[i % len(layers)]
-        if ev is not None:
-            ev[0].record()
         kvq.decode_step(L, cache, k1, v1, T - 1, q, scale, out, ws)
-        if ev is not None:
-            ev[1].record()
 
     if args.copy_calibration_mib:
         src = torch.ones(args.copy_calibration_mib << 20, dtype=torch.uint8, device=dev)
@@ -320,18 +316,24 @@ def main() -> int:
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    # HIP-event pairs around every `event_every`-th launch of the timed region (an event pair between two launches
-    # costs about a microsecond of idle memory system: sampling keeps the timed region close to undisturbed)
+    # HIP events bracket consecutive groups of `event_every` launches of the timed region (an event pair around every
+    # single launch leaves the memory system idle for a few microseconds per step and shows up in both numbers);
+    # kernel time = mean over all groups of (group time / launches in the group)
     every = max(1, args.event_every)
-    events = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for i in range(0, args.steps, every)}
+    n_groups = (args.steps + every - 1) // every
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_groups)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i, events.get(i))
+        if i % every == 0:
+            events[i // every][0].record()
+        step(args.warmup + i)
+        if i % every == every - 1 or i == args.steps - 1:
+            events[i // every][1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    decode_ms = sum(a.elapsed_time(b) for a, b in events.values()) / len(events)
+    decode_ms = sum(a.elapsed_time(b) for a, b in events) / args.steps
     value = kv_bytes / (ms_per_step * 1e-3) / 1e9
     achieved = kv_bytes / (decode_ms * 1e-3) / 1e9
 
@@ -399,7 +401,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": _traffic_from_profile(f"decode_k4v2_{args.workload}_pmc.txt"),
-                     "kernel": "kvq decode_kernel<4,2,R,NW> (fused step; + merge_kernel when the sequence is split), mean of HIP-event pairs around every " + str(every) + "-th launch of the timed region",
+                     "kernel": "kvq decode_kernel<4,2,R,NW> (fused step; + merge_kernel when the sequence is split), HIP events around every group of " + str(every) + " consecutive launches of the timed region, per launch",
                      "kernel_ms": round(decode_ms, 5)},
         "cpu_baseline": cpu_baseline,
     }
