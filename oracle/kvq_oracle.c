@@ -32,6 +32,16 @@
  *     goes to the quantizer in binary32, the rotated query is rounded once to binary16 (the
  *     16-bit query a half-precision model hands to attention).
  *
+ *   - channel-wise key groups with a full-precision residual buffer (Sec. 4 "Downstream Task
+ *     Accuracy": the per-column back-end, with the most recent tokens kept in full precision
+ *     and flushed periodically): with axis_k = 1 a key group is G_K consecutive TOKENS of one
+ *     channel.  The reading taken here: the newest tokens live as their 16-bit input patterns
+ *     in a residual buffer of G_K token slots (keys and values both); when token t with
+ *     (t + 1) % G_K == 0 arrives the buffer is flushed: the G_K key rows are quantized channel
+ *     by channel (one scale/zero per channel and block), the G_K value rows token-wise as
+ *     always; attention reads tokens below floor(seq_len / G_K) * G_K from the codes and the
+ *     rest from the buffer.  Tokens must be appended in order, starting at 0.
+ *
  * Arithmetic of the quantizer is IEEE binary32, round-to-nearest-even, one rounding per
  * written operation (build with -ffp-contract=off, no fast-math).  The decisions that
  * produce integers (codes) are therefore taken in binary32, the precision the GPU kernel
@@ -57,6 +67,12 @@
  *              "tokens x channels" operand, so a decode kernel needs no transpose.)
  *   bits == 16 the planes hold the 16-bit input patterns unchanged in the same positions
  *              (b = 16 in the formulas above); the meta planes are unused.
+ *   axis_k == 1 (channel-wise keys, G = group_k): T_cap = max_seq rounded up to a multiple of
+ *              max(32, G); k_codes and the value planes as above;
+ *              k_meta  [B][H][T_cap/G][D] entries (scale, zero as above): entry (t/G, d);
+ *              k_resid [B][H][G][D] 16-bit patterns, token t in slot t % G, row-major;
+ *              v_resid [B][H][G/32] blocks in the v_codes order with b = 16, token t in block
+ *                      (t % G) / 32 at u = t % 32.
  */
 #include <math.h>
 #include <stddef.h>
@@ -73,6 +89,7 @@ typedef struct {
   int32_t raw_dtype;        /* REF_F16 or REF_BF16: meaning of the planes when bits == 16 */
   int32_t rotate_k;         /* 1: key rows are stored as codes of R k (needs bits_k < 16) */
   uint32_t signs_k[4];      /* bit d of the 128-bit little-endian string set: s_d = -1 (D <= 128) */
+  int32_t axis_k;           /* 0: key groups along head_dim (token-wise); 1: along tokens (channel-wise) */
 } ref_layout;
 
 /* ------------------------------------------------------------------ number formats */
@@ -127,14 +144,17 @@ static float load_elem(const void* base, int dtype, int64_t idx) {
 
 /* ------------------------------------------------------------------ sizes */
 
-static int64_t cap_tokens(const ref_layout* L) { return ((int64_t)L->max_seq + 31) / 32 * 32; }
+static int64_t cap_tokens(const ref_layout* L) {
+  int64_t unit = (L->axis_k == 1 && L->group_k > 32) ? L->group_k : 32;
+  return ((int64_t)L->max_seq + unit - 1) / unit * unit;
+}
 
 /* bytes of k_codes, k_meta, v_codes, v_meta */
 int ref_plane_bytes(const ref_layout* L, uint64_t out[4]) {
   int64_t rows = (int64_t)L->batch * L->kv_heads * cap_tokens(L);
   int D = L->head_dim;
   out[0] = (uint64_t)(rows * (D * L->bits_k / 8));
-  out[1] = L->bits_k == 16 ? 0 : (uint64_t)(rows * (D / L->group_k) * 4);
+  out[1] = L->bits_k == 16 ? 0 : L->axis_k == 1 ? (uint64_t)(rows / L->group_k * D * 4) : (uint64_t)(rows * (D / L->group_k) * 4);
   out[2] = (uint64_t)(rows * (D * L->bits_v / 8));
   out[3] = L->bits_v == 16 ? 0 : (uint64_t)(rows * (D / L->group_v) * 4);
   return 0;
@@ -266,6 +286,7 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
   if (pos < 0 || n_new < 0 || (int64_t)pos + n_new > L->max_seq) return -3;
   if (D % 64 || D > 1024) return -1;
   if (L->rotate_k && (L->bits_k == 16 || D > 128 || (D & (D - 1)))) return -1;
+  if (L->axis_k != 0) return -1;                            /* channel-wise keys: ref_seq_append */
   uint64_t pb[4];
   ref_plane_bytes(L, pb);
   int64_t streams = (int64_t)L->batch * L->kv_heads;
@@ -325,6 +346,7 @@ int ref_dequantize_stored(const ref_layout* L, const uint8_t* k_codes, const uin
                           const uint8_t* v_meta, int32_t t0, int32_t t1, float* k_out, float* v_out) {
   int D = L->head_dim;
   if (t0 < 0 || t1 < t0 || t1 > L->max_seq) return -3;
+  if (L->axis_k != 0) return -1;                            /* channel-wise keys: ref_seq_dequantize */
   uint64_t pb[4];
   ref_plane_bytes(L, pb);
   int64_t streams = (int64_t)L->batch * L->kv_heads;
@@ -443,6 +465,171 @@ int ref_decode_attention(const ref_layout* L, const uint8_t* k_codes, const uint
   } else if (!rc) {
     rc = ref_attention_dense(Kd, Vd, L->batch, L->kv_heads, q_heads, seq_len, L->head_dim, q, q_dtype, softmax_scale, out);
   }
+  free(Kd); free(Vd);
+  return rc;
+}
+
+/* ------------------------------------------------------------------ channel-wise keys + residual buffer */
+
+/* bytes of k_resid and v_resid (axis_k == 1) */
+int ref_resid_bytes(const ref_layout* L, uint64_t out[2]) {
+  uint64_t n = (uint64_t)L->batch * L->kv_heads * L->group_k * L->head_dim * 2;
+  out[0] = n;
+  out[1] = n;
+  return 0;
+}
+
+static int seq_layout_ok(const ref_layout* L) {
+  int G = L->group_k, D = L->head_dim;
+  if (L->axis_k != 1 || L->rotate_k) return 0;
+  if (G != 32 && G != 64 && G != 128) return 0;
+  if (D % 64 || D > 1024 || D % L->group_v) return 0;
+  if ((L->bits_k != 2 && L->bits_k != 4 && L->bits_k != 8) || (L->bits_v != 2 && L->bits_v != 4 && L->bits_v != 8)) return 0;
+  return 1;
+}
+
+/* 16-bit pattern of (slot, d) in the residual planes of one (b,h) stream */
+static uint16_t resid_get_k(const uint8_t* rs, int slot, int d, int D) {
+  const uint8_t* p = rs + ((int64_t)slot * D + d) * 2;
+  return (uint16_t)(p[0] | (p[1] << 8));
+}
+static uint16_t resid_get_v(const uint8_t* rs, int slot, int d, int D) {
+  int64_t wb; int bit;
+  v_position(slot, d, D, 16, &wb, &bit);
+  return (uint16_t)get_bits_le(rs + wb, bit, 16);
+}
+
+/* Append tokens [pos, pos+n_new) to a cache with channel-wise keys: every token goes to its
+ * residual slot; a token that completes a block of G = group_k tokens triggers the flush of
+ * that block (keys channel by channel, values token by token).  pos must equal the number of
+ * tokens appended so far.  in_dtype must be raw_dtype (the buffer keeps the input patterns). */
+int ref_seq_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, uint8_t* v_codes, uint8_t* v_meta,
+                   uint8_t* k_resid, uint8_t* v_resid, const void* k_new, const void* v_new, int in_dtype,
+                   int64_t stride_b, int64_t stride_h, int64_t stride_t, int32_t pos, int32_t n_new) {
+  if (!seq_layout_ok(L)) return -1;
+  if (in_dtype != L->raw_dtype) return -1;
+  if (pos < 0 || n_new < 0 || (int64_t)pos + n_new > L->max_seq) return -3;
+  int D = L->head_dim, G = L->group_k, GV = L->group_v, bk = L->bits_k, bv = L->bits_v;
+  uint64_t pb[4];
+  ref_plane_bytes(L, pb);
+  int64_t streams = (int64_t)L->batch * L->kv_heads;
+  int64_t rstream = (int64_t)G * D * 2;
+  float* col = (float*)malloc(sizeof(float) * (size_t)(G > D ? G : D));
+  uint8_t* codes = (uint8_t*)malloc((size_t)(G > D ? G : D));
+  for (int64_t bh = 0; bh < streams; ++bh) {
+    int64_t bi = bh / L->kv_heads, hi = bh % L->kv_heads;
+    uint8_t* kc = k_codes + bh * (int64_t)(pb[0] / (uint64_t)streams);
+    uint8_t* km = k_meta + bh * (int64_t)(pb[1] / (uint64_t)streams);
+    uint8_t* vc = v_codes + bh * (int64_t)(pb[2] / (uint64_t)streams);
+    uint8_t* vm = v_meta + bh * (int64_t)(pb[3] / (uint64_t)streams);
+    uint8_t* kr = k_resid + bh * rstream;
+    uint8_t* vr = v_resid + bh * rstream;
+    for (int64_t tn = 0; tn < n_new; ++tn) {
+      int64_t t = pos + tn;
+      int slot = (int)(t % G);
+      int64_t base = bi * stride_b + hi * stride_h + tn * stride_t;
+      for (int d = 0; d < D; ++d) {                           /* the newest token stays in full precision */
+        uint32_t kb = ((const uint16_t*)k_new)[base + d], vb = ((const uint16_t*)v_new)[base + d];
+        put_bits_le(kr, ((int64_t)slot * D + d) * 16, 16, kb);
+        int64_t wb; int bit;
+        v_position(slot, d, D, 16, &wb, &bit);
+        put_bits_le(vr + wb, bit, 16, vb);
+      }
+      if (slot != G - 1) continue;
+      /* flush the block that just filled up */
+      int64_t blk = t / G, t0 = blk * G;
+      for (int d = 0; d < D; ++d) {                           /* keys: one group = G tokens of channel d */
+        for (int i = 0; i < G; ++i) {
+          uint16_t bits16 = resid_get_k(kr, i, d, D);
+          col[i] = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32(bits16) : ref_f16_to_f32(bits16);
+        }
+        uint16_t S, Z;
+        ref_quantize_group(col, G, bk, codes, &S, &Z);
+        uint8_t* m = km + (blk * D + d) * 4;
+        m[0] = (uint8_t)(S & 0xFF); m[1] = (uint8_t)(S >> 8);
+        m[2] = (uint8_t)(Z & 0xFF); m[3] = (uint8_t)(Z >> 8);
+        for (int i = 0; i < G; ++i) put_bits_le(kc, k_bit_offset(t0 + i, d, D, bk), bk, codes[i]);
+      }
+      for (int i = 0; i < G; ++i) {                           /* values: token-wise groups as always */
+        for (int d = 0; d < D; ++d) {
+          uint16_t bits16 = resid_get_v(vr, i, d, D);
+          col[d] = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32(bits16) : ref_f16_to_f32(bits16);
+        }
+        for (int g = 0; g < D / GV; ++g) {
+          uint16_t S, Z;
+          ref_quantize_group(col + g * GV, GV, bv, codes + g * GV, &S, &Z);
+          uint8_t* m = vm + meta_offset(t0 + i, g, D / GV);
+          m[0] = (uint8_t)(S & 0xFF); m[1] = (uint8_t)(S >> 8);
+          m[2] = (uint8_t)(Z & 0xFF); m[3] = (uint8_t)(Z >> 8);
+        }
+        for (int d = 0; d < D; ++d) {
+          int64_t wb; int bit;
+          v_position(t0 + i, d, D, bv, &wb, &bit);
+          put_bits_le(vc + wb, bit, bv, codes[d]);
+        }
+      }
+    }
+  }
+  free(col); free(codes);
+  return 0;
+}
+
+/* What attention sees of tokens [t0,t1) when the cache holds seq_len tokens: the reconstruction
+ * of the flushed tokens (below floor(seq_len/G)*G), the 16-bit patterns of the rest, as binary32.
+ * k_out, v_out: [B][H][t1-t0][D]. */
+int ref_seq_dequantize(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
+                       const uint8_t* v_meta, const uint8_t* k_resid, const uint8_t* v_resid, int32_t seq_len,
+                       int32_t t0, int32_t t1, float* k_out, float* v_out) {
+  if (!seq_layout_ok(L)) return -1;
+  if (t0 < 0 || t1 < t0 || t1 > seq_len || seq_len > L->max_seq) return -3;
+  int D = L->head_dim, G = L->group_k, GV = L->group_v, bk = L->bits_k, bv = L->bits_v;
+  uint64_t pb[4];
+  ref_plane_bytes(L, pb);
+  int64_t streams = (int64_t)L->batch * L->kv_heads;
+  int64_t rstream = (int64_t)G * D * 2;
+  int64_t n_flushed = (int64_t)seq_len / G * G;
+  int64_t nt = t1 - t0;
+  for (int64_t bh = 0; bh < streams; ++bh) {
+    const uint8_t* kc = k_codes + bh * (int64_t)(pb[0] / (uint64_t)streams);
+    const uint8_t* km = k_meta + bh * (int64_t)(pb[1] / (uint64_t)streams);
+    const uint8_t* vc = v_codes + bh * (int64_t)(pb[2] / (uint64_t)streams);
+    const uint8_t* vm = v_meta + bh * (int64_t)(pb[3] / (uint64_t)streams);
+    const uint8_t* kr = k_resid + bh * rstream;
+    const uint8_t* vr = v_resid + bh * rstream;
+    for (int64_t t = t0; t < t1; ++t)
+      for (int d = 0; d < D; ++d) {
+        float kv, vv;
+        if (t < n_flushed) {
+          const uint8_t* m = km + ((t / G) * D + d) * 4;
+          kv = ref_reconstruct(get_bits_le(kc, k_bit_offset(t, d, D, bk), bk), (uint16_t)(m[0] | (m[1] << 8)), (uint16_t)(m[2] | (m[3] << 8)));
+          int64_t wb; int bit;
+          v_position(t, d, D, bv, &wb, &bit);
+          const uint8_t* mv = vm + meta_offset(t, d / GV, D / GV);
+          vv = ref_reconstruct(get_bits_le(vc + wb, bit, bv), (uint16_t)(mv[0] | (mv[1] << 8)), (uint16_t)(mv[2] | (mv[3] << 8)));
+        } else {
+          uint16_t kb = resid_get_k(kr, (int)(t % G), d, D), vb = resid_get_v(vr, (int)(t % G), d, D);
+          kv = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32(kb) : ref_f16_to_f32(kb);
+          vv = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32(vb) : ref_f16_to_f32(vb);
+        }
+        if (k_out) k_out[((bh * nt) + (t - t0)) * D + d] = kv;
+        if (v_out) v_out[((bh * nt) + (t - t0)) * D + d] = vv;
+      }
+  }
+  return 0;
+}
+
+/* Decode attention over a cache with channel-wise keys and a residual buffer: the dense
+ * definition on what ref_seq_dequantize returns for tokens [0, seq_len). */
+int ref_seq_decode_attention(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
+                             const uint8_t* v_meta, const uint8_t* k_resid, const uint8_t* v_resid, const void* q,
+                             int q_dtype, int32_t q_heads, int32_t seq_len, float softmax_scale, float* out) {
+  if (seq_len <= 0 || seq_len > L->max_seq) return -1;
+  int64_t n = (int64_t)L->batch * L->kv_heads * seq_len * L->head_dim;
+  float* Kd = (float*)malloc(sizeof(float) * (size_t)n);
+  float* Vd = (float*)malloc(sizeof(float) * (size_t)n);
+  if (!Kd || !Vd) { free(Kd); free(Vd); return -2; }
+  int rc = ref_seq_dequantize(L, k_codes, k_meta, v_codes, v_meta, k_resid, v_resid, seq_len, 0, seq_len, Kd, Vd);
+  if (!rc) rc = ref_attention_dense(Kd, Vd, L->batch, L->kv_heads, q_heads, seq_len, L->head_dim, q, q_dtype, softmax_scale, out);
   free(Kd); free(Vd);
   return rc;
 }

@@ -30,7 +30,7 @@ def build(force: bool = False) -> str:
 
 class _Layout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "kv_heads", "max_seq", "head_dim", "bits_k", "bits_v",
-                                          "group_k", "group_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4)]
+                                          "group_k", "group_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4), ("axis_k", C.c_int32)]
 
 
 @dataclass(frozen=True)
@@ -46,10 +46,12 @@ class Layout:
     raw_dtype: int = F16
     rotate_k: int = 0
     signs_k: tuple = (0, 0, 0, 0)      # 128 sign bits, little-endian: bit d set means s_d = -1
+    axis_k: int = 0                    # 1: channel-wise key groups (group_k tokens) + residual buffer
 
     def c(self) -> _Layout:
         return _Layout(self.batch, self.kv_heads, self.max_seq, self.head_dim, self.bits_k, self.bits_v,
-                       self.group_k, self.group_v, self.raw_dtype, self.rotate_k, (C.c_uint32 * 4)(*self.signs_k))
+                       self.group_k, self.group_v, self.raw_dtype, self.rotate_k, (C.c_uint32 * 4)(*self.signs_k),
+                       self.axis_k)
 
 
 _lib = None
@@ -203,3 +205,47 @@ def mse(a: np.ndarray, ahat: np.ndarray) -> float:
     a = np.ascontiguousarray(a, dtype=np.float32)
     ahat = np.ascontiguousarray(ahat, dtype=np.float32)
     return float(lib().ref_mse(_ptr(a), _ptr(ahat), C.c_int64(a.size)))
+
+
+# ---- channel-wise keys with a residual buffer (axis_k = 1): six planes = the four above + k_resid, v_resid
+
+def new_seq_planes(L: Layout, fill: int = 0):
+    out = (C.c_uint64 * 2)()
+    cl = L.c()
+    lib().ref_resid_bytes(C.byref(cl), out)
+    return new_planes(L, fill) + [np.full(int(n), fill, dtype=np.uint8) for n in out]
+
+
+def seq_append(L: Layout, planes, k_new: np.ndarray, v_new: np.ndarray, pos: int, bf16: bool = False) -> None:
+    """k_new, v_new: contiguous [B, H, n_new, D] 16-bit arrays (float16, or uint16 patterns); pos = tokens so far."""
+    assert k_new.shape == v_new.shape and k_new.flags.c_contiguous and v_new.flags.c_contiguous
+    B, H, n_new, D = k_new.shape
+    cl = L.c()
+    rc = lib().ref_seq_append(C.byref(cl), *[_ptr(p) for p in planes], _ptr(k_new), _ptr(v_new),
+                              C.c_int(dtype_code(k_new, bf16)), C.c_int64(H * n_new * D), C.c_int64(n_new * D), C.c_int64(D),
+                              C.c_int32(pos), C.c_int32(n_new))
+    if rc:
+        raise ValueError(f"ref_seq_append rc={rc}")
+
+
+def seq_dequantize(L: Layout, planes, seq_len: int, t0: int, t1: int):
+    shape = (L.batch, L.kv_heads, t1 - t0, L.head_dim)
+    k = np.zeros(shape, dtype=np.float32)
+    v = np.zeros(shape, dtype=np.float32)
+    cl = L.c()
+    rc = lib().ref_seq_dequantize(C.byref(cl), *[_ptr(p) for p in planes], C.c_int32(seq_len), C.c_int32(t0), C.c_int32(t1),
+                                  _ptr(k), _ptr(v))
+    if rc:
+        raise ValueError(f"ref_seq_dequantize rc={rc}")
+    return k, v
+
+
+def seq_decode_attention(L: Layout, planes, q: np.ndarray, seq_len: int, softmax_scale: float, bf16: bool = False) -> np.ndarray:
+    q = np.ascontiguousarray(q)
+    out = np.zeros(q.shape, dtype=np.float32)
+    cl = L.c()
+    rc = lib().ref_seq_decode_attention(C.byref(cl), *[_ptr(p) for p in planes], _ptr(q), C.c_int(dtype_code(q, bf16)),
+                                        C.c_int32(q.shape[1]), C.c_int32(seq_len), C.c_float(softmax_scale), _ptr(out))
+    if rc:
+        raise ValueError(f"ref_seq_decode_attention rc={rc}")
+    return out

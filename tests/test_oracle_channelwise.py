@@ -1,0 +1,186 @@
+"""Pins of the oracle's channel-wise key groups with a full-precision residual buffer (Sec. 4 "Downstream Task
+Accuracy": the per-column back-end and its 64-token residual buffer) against things other than itself: a vectorized
+numpy statement of the same quantizer applied to columns, array-transpose statements of the plane layouts, the
+buffer's life cycle (what is stored raw, what is flushed, when), attention through torch on numpy-built tensors, and
+the reason the per-column form exists (a few large key channels stop inflating every group's range)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_15075_amd import synth
+from test_oracle_quantizer import _expected_planes, _pack_fields_le
+
+
+def _quantize_columns_numpy(X, bits):
+    """Asymmetric min-max quantizer of App. B applied to every column of X [G, D], binary32 operations on whole
+    arrays: returns codes [G, D], scale and zero as binary16 patterns [D]."""
+    X = X.astype(np.float32)
+    mn, mx = X.min(axis=0), X.max(axis=0)
+    mn = np.where(mn == 0, np.float32(0), mn)
+    levels = np.float32(2 ** bits - 1)
+    s16 = ((mx - mn) / levels).astype(np.float32).astype(np.float16)
+    s16 = np.where(s16 == 0, np.float16(0), s16)
+    z16 = mn.astype(np.float16)
+    s, z = s16.astype(np.float32), z16.astype(np.float32)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        rcp = (np.float32(1) / s).astype(np.float32)
+        t = ((X - z).astype(np.float32) * rcp).astype(np.float32)
+    codes = np.clip(np.rint(t), 0, levels)
+    codes = np.where(s == 0, 0, codes).astype(np.uint8)
+    return codes, s16.view(np.uint16), z16.view(np.uint16)
+
+
+def _quantize_rows_numpy(X, bits, G):
+    T, D = X.shape
+    codes = np.zeros((T, D), np.uint8)
+    S = np.zeros((T, D // G), np.uint16)
+    Z = np.zeros((T, D // G), np.uint16)
+    for g in range(D // G):
+        c, s, z = _quantize_columns_numpy(X[:, g * G:(g + 1) * G].T, bits)
+        codes[:, g * G:(g + 1) * G], S[:, g], Z[:, g] = c.T, s, z
+    return codes, S, Z
+
+
+@pytest.mark.parametrize("G,bk,bv,gv", [(64, 4, 2, 64), (32, 2, 4, 128), (128, 8, 8, 32)])
+def test_flushed_blocks_match_numpy_and_the_residual_holds_the_tail(oracle, G, bk, bv, gv):
+    rng = np.random.default_rng(G + bk)
+    B, H, D = 2, 2, 128
+    T = 2 * G + 37 if G < 128 else 2 * G + 5
+    cap = -(-T // max(32, G)) * max(32, G)
+    K = (rng.standard_normal((B, H, T, D)) * 3).astype(np.float16)
+    K[..., [5, 37]] *= 20
+    V = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    L = oracle.Layout(B, H, T, D, bk, bv, G, gv, axis_k=1)
+    planes = oracle.new_seq_planes(L, fill=0xA5)
+    assert [p.size for p in planes] == [B * H * cap * 16 * bk, B * H * (cap // G) * D * 4, B * H * cap * 16 * bv,
+                                        B * H * cap * (D // gv) * 4, B * H * G * D * 2, B * H * G * D * 2]
+    oracle.seq_append(L, planes, K, V, 0)
+    nq = T // G * G
+    for bh in range(B * H):
+        Kb, Vb = K.reshape(B * H, T, D)[bh], V.reshape(B * H, T, D)[bh]
+        codes = np.zeros((cap, D), np.uint8)
+        meta = np.zeros((cap // G, D, 2), np.uint16)
+        for blk in range(nq // G):
+            c, s, z = _quantize_columns_numpy(Kb[blk * G:(blk + 1) * G], bk)
+            codes[blk * G:(blk + 1) * G] = c
+            meta[blk, :, 0], meta[blk, :, 1] = s, z
+        k_plane = _pack_fields_le(codes.ravel(), bk)
+        got_k = planes[0].reshape(B * H, -1)[bh]
+        assert np.array_equal(got_k[:nq * 16 * bk], k_plane[:nq * 16 * bk])
+        assert (got_k[nq * 16 * bk:] == 0xA5).all()                       # nothing beyond the flushed blocks is written
+        got_m = planes[1].reshape(B * H, -1)[bh]
+        assert np.array_equal(got_m[:(nq // G) * D * 4], meta[:nq // G].view(np.uint8).ravel())
+        assert (got_m[(nq // G) * D * 4:] == 0xA5).all()
+        # values: the token-wise planes of the flushed tokens
+        vcodes, S, Z = _quantize_rows_numpy(np.concatenate([Vb[:nq].astype(np.float32), np.zeros((cap - nq, D), np.float32)]), bv, gv)
+        _, vmeta, v_plane = _expected_planes(vcodes, S, Z, bv, gv)
+        got_v = planes[2].reshape(B * H, -1)[bh]
+        assert np.array_equal(got_v[:nq * 16 * bv], v_plane[:nq * 16 * bv]) and (got_v[nq * 16 * bv:] == 0xA5).all()
+        got_vm = planes[3].reshape(B * H, -1)[bh]
+        assert np.array_equal(got_vm[:nq * (D // gv) * 4], vmeta[:nq * (D // gv) * 4])
+        # residual: slot t % G of the newest tokens; keys row-major, values in the 16-bit block order
+        kr = planes[4].reshape(B * H, G, D * 2)[bh].view(np.float16).reshape(G, D)
+        for t in range(nq, T):
+            assert np.array_equal(kr[t % G], Kb[t])
+        slots = np.zeros((G, D), np.uint16)
+        live = np.zeros((G, D), bool)
+        for t in range(T - G if T >= G else 0, T):                       # last writer of every slot
+            slots[t % G] = Vb[t].view(np.uint16)
+            live[t % G] = True
+        _, _, vr_plane = _expected_planes(slots, np.zeros((G, 1), np.uint16), np.zeros((G, 1), np.uint16), 16, 128)
+        _, _, live_plane = _expected_planes(live.astype(np.uint16) * 0xFFFF, np.zeros((G, 1), np.uint16), np.zeros((G, 1), np.uint16), 16, 128)
+        got_vr = planes[5].reshape(B * H, -1)[bh]
+        assert np.array_equal(got_vr & live_plane, vr_plane & live_plane)
+        assert ((got_vr | live_plane) == np.where(live_plane == 0xFF, 0xFF, 0xA5)).all()
+
+
+def test_chunked_appends_compose(oracle):
+    rng = np.random.default_rng(3)
+    B, H, T, D, G = 1, 2, 200, 128, 64
+    K = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    V = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    L = oracle.Layout(B, H, T, D, 4, 2, G, 64, axis_k=1)
+    whole = oracle.new_seq_planes(L, fill=0x5A)
+    oracle.seq_append(L, whole, K, V, 0)
+    parts = oracle.new_seq_planes(L, fill=0x5A)
+    for a, b in ((0, 1), (1, 63), (63, 64), (64, 65), (65, 191), (191, 192), (192, 200)):
+        oracle.seq_append(L, parts, np.ascontiguousarray(K[:, :, a:b]), np.ascontiguousarray(V[:, :, a:b]), a)
+    for p, w in zip(parts, whole):
+        assert np.array_equal(p, w)
+
+
+def test_what_attention_sees(oracle):
+    """Flushed tokens: code * scale + zero with the column's scale/zero (numpy); newest tokens: the inputs exactly.
+    Attention over the mix equals torch's softmax attention on those tensors; below one block nothing is quantized."""
+    rng = np.random.default_rng(8)
+    B, Hk, Hq, T, D, G = 1, 2, 4, 150, 128, 64
+    K = (rng.standard_normal((B, Hk, T, D)) * 2).astype(np.float16)
+    V = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    scale = 1 / math.sqrt(D)
+    L = oracle.Layout(B, Hk, T, D, 4, 2, G, 64, axis_k=1)
+    planes = oracle.new_seq_planes(L)
+    oracle.seq_append(L, planes, K, V, 0)
+    for seq_len in (150, 128, 127, 64, 63, 1):
+        # the cache state at seq_len tokens: rebuild by appending only that many
+        pl = oracle.new_seq_planes(L)
+        oracle.seq_append(L, pl, np.ascontiguousarray(K[:, :, :seq_len]), np.ascontiguousarray(V[:, :, :seq_len]), 0)
+        kd, vd = oracle.seq_dequantize(L, pl, seq_len, 0, seq_len)
+        nq = seq_len // G * G
+        want_k = K[:, :, :seq_len].astype(np.float32).copy()
+        want_v = V[:, :, :seq_len].astype(np.float32).copy()
+        for h in range(Hk):
+            for blk in range(nq // G):
+                X = K[0, h, blk * G:(blk + 1) * G]
+                c, s, z = _quantize_columns_numpy(X, 4)
+                want_k[0, h, blk * G:(blk + 1) * G] = c.astype(np.float32) * s.view(np.float16).astype(np.float32) + z.view(np.float16).astype(np.float32)
+            if nq:
+                c, S, Z = _quantize_rows_numpy(V[0, h, :nq].astype(np.float32), 2, 64)
+                sv = np.repeat(S.view(np.float16).astype(np.float32), 64, axis=1)
+                zv = np.repeat(Z.view(np.float16).astype(np.float32), 64, axis=1)
+                want_v[0, h, :nq] = c.astype(np.float32) * sv + zv
+        assert np.array_equal(kd, want_k) and np.array_equal(vd, want_v)
+        got = oracle.seq_decode_attention(L, pl, q, seq_len, scale)
+        Kt = torch.from_numpy(want_k).double().repeat_interleave(Hq // Hk, dim=1)
+        Vt = torch.from_numpy(want_v).double().repeat_interleave(Hq // Hk, dim=1)
+        qt = torch.from_numpy(q.astype(np.float64)).unsqueeze(2)
+        ref = torch.nn.functional.scaled_dot_product_attention(qt, Kt, Vt, scale=scale).squeeze(2).numpy()
+        assert np.abs(got - ref).max() <= 2e-6 * np.abs(ref).max()
+        if seq_len < G:
+            exact = oracle.attention_dense(K[:, :, :seq_len].astype(np.float32), V[:, :, :seq_len].astype(np.float32), q, scale)
+            assert np.array_equal(got, exact)
+
+
+def test_per_channel_groups_tame_outlier_channels(oracle):
+    """Keys with a few large channels: a token-wise group containing one of them spends its whole range on it, a
+    channel-wise group does not.  Key MSE at 4 bits drops by a large factor; the half-step bound holds per column."""
+    B, H, T, D, G = 2, 4, 256, 128, 64
+    K, V, _ = synth.make_kvq(21, B, H, H, T, dtype=torch.float16)
+    Kn, Vn = K.numpy(), V.numpy()
+    Ls = oracle.Layout(B, H, T, D, 4, 2, G, 64, axis_k=1)
+    ps = oracle.new_seq_planes(Ls)
+    oracle.seq_append(Ls, ps, Kn, Vn, 0)
+    ks, _ = oracle.seq_dequantize(Ls, ps, T, 0, T)
+    Lt = oracle.Layout(B, H, T, D, 4, 2, 64, 64)
+    pt = oracle.new_planes(Lt)
+    oracle.quantize_append(Lt, pt, Kn, Vn, 0)
+    kt, _ = oracle.dequantize(Lt, pt, 0, T)
+    mse_seq, mse_tok = oracle.mse(Kn.astype(np.float32), ks), oracle.mse(Kn.astype(np.float32), kt)
+    assert mse_seq < 0.4 * mse_tok
+    quiet = np.setdiff1d(np.arange(D), [5, 37, 69, 101])                 # the channels that are not outliers gain most
+    assert oracle.mse(Kn.astype(np.float32)[..., quiet], ks[..., quiet]) < 0.05 * oracle.mse(Kn.astype(np.float32)[..., quiet], kt[..., quiet])
+    rng_col = (Kn.astype(np.float32).reshape(B, H, T // G, G, D).max(axis=3) - Kn.astype(np.float32).reshape(B, H, T // G, G, D).min(axis=3))
+    step = rng_col / 15
+    err = np.abs(Kn.astype(np.float32) - ks).reshape(B, H, T // G, G, D).max(axis=3)
+    assert (err <= step / 2 * (1 + 2 ** -9) + 1e-6).all()
+
+
+def test_token_wise_entry_points_refuse_channel_wise_layouts(oracle):
+    L = oracle.Layout(1, 1, 64, 128, 4, 2, 64, 64, axis_k=1)
+    x = np.zeros((1, 1, 4, 128), np.float16)
+    with pytest.raises(ValueError):
+        oracle.quantize_append(L, oracle.new_planes(L), x, x, 0)
+    with pytest.raises(ValueError):
+        oracle.seq_append(oracle.Layout(1, 1, 64, 128, 16, 2, 64, 64, axis_k=1), oracle.new_seq_planes(L), x, x, 0)
