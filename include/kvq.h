@@ -35,6 +35,19 @@
  * binary32(1/sqrt(128)).  R k goes to the quantizer in binary32; R q is rounded once to binary16.
  * kvq_dequantize returns keys in the input basis (R^T of the stored reconstruction: butterflies, scale, signs).
  *
+ * Channel-wise keys (axis_k = KVQ_AXIS_SEQ; Sec. 4 "Downstream Task Accuracy": the per-column back-end with its
+ * 64-token full-precision residual buffer): a key group is 64 consecutive tokens of one channel (group_k must be
+ * 64).  The newest tokens are kept as their 16-bit input patterns in a residual buffer of 64 token slots, keys and
+ * values both (k_resid, v_resid in kvq_cache, sizes from kvq_residual_bytes); the token that completes a block of 64
+ * triggers the flush of that block: its key rows are quantized channel by channel (one scale/zero per channel and
+ * block, same arithmetic as above with the group running over tokens), its value rows token-wise as always.
+ * Attention reads tokens below floor(seq_len / 64) * 64 from the codes and the rest from the buffer.  Contract:
+ * tokens are appended in order starting at 0 (pos = number of tokens appended so far), in_dtype = raw_dtype, and
+ * seq_len of a decode call is that number.  bits 16 and rotate_k are not combined with it; axis_v stays
+ * KVQ_AXIS_HEAD_DIM.  Format: T_cap is a multiple of 64; k_meta is [B][H_kv][T_cap/64][D] entries {scale, zero},
+ * entry (t/64, d); k_resid is [B][H_kv][64][D] 16-bit patterns, token t in slot t%64; v_resid is [B][H_kv][2] blocks
+ * in the v_codes order with b_V = 16, token t in block (t%64)/32; the other planes are as below.
+ *
  * Storage format of one layer (sizes from kvq_cache_bytes; T_cap = max_seq rounded up to 32):
  *   k_codes  [B][H_kv][T_cap][D*b_K/8]      element d of a row at bits [d*b_K, (d+1)*b_K), little-endian
  *   k_meta   [B][H_kv][T_cap/16][D/G_K][16] entries {uint16 scale, uint16 zero} (binary16 patterns);
@@ -72,7 +85,8 @@ typedef enum { KVQ_F16 = 0, KVQ_BF16 = 1, KVQ_F32 = 2 } kvq_dtype;
 
 typedef enum {
   KVQ_AXIS_HEAD_DIM = 0, /* token-wise: groups of G channels inside one token row (Sec. 4, "per-row") */
-  KVQ_AXIS_SEQ = 1       /* channel-wise: groups along the sequence (Sec. 4, "per-column"); not built */
+  KVQ_AXIS_SEQ = 1       /* channel-wise: groups of tokens of one channel (Sec. 4, "per-column"); keys only, see
+                            "Channel-wise keys" above */
 } kvq_axis;
 
 /* Immutable description of one layer's cache.  head_dim must be 128.  bits in {2,4,8,16};
@@ -92,11 +106,15 @@ typedef struct {
  * A meta pointer may be NULL iff the matching bits == 16. */
 typedef struct {
   void *k_codes, *k_meta, *v_codes, *v_meta;
+  void *k_resid, *v_resid; /* residual buffers of channel-wise keys (axis_k = KVQ_AXIS_SEQ); NULL otherwise */
 } kvq_cache;
 
 /* Host only.  bytes_out = sizes of k_codes, k_meta, v_codes, v_meta.  Pins the paper's memory
  * claim (Sec. 1): K4V2 code bytes are 3/4 of K4V4's. */
 kvq_status kvq_cache_bytes(const kvq_layout* layout, size_t bytes_out[4]);
+
+/* Host only.  bytes_out = sizes of k_resid, v_resid: 0, 0 unless axis_k = KVQ_AXIS_SEQ. */
+kvq_status kvq_residual_bytes(const kvq_layout* layout, size_t bytes_out[2]);
 
 /* Host only.  Bytes of scratch kvq_decode_attention needs for (q_heads, seq_len): the partial
  * (max, sum, accumulator) records of its split-sequence pass.  May be 0 (enough (b, h_kv) streams to fill

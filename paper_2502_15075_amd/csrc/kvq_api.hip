@@ -21,7 +21,12 @@ kvq_status check_layout(const kvq_layout* L) {
   if (L->rotate_k != 0 && L->rotate_k != 1) return KVQ_ERR_INVALID_ARG;
   if (L->rotate_k && L->bits_k == 16) return KVQ_ERR_INVALID_ARG;   // the rotation exists for quantized keys only
   if (L->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;
-  if (L->axis_k != KVQ_AXIS_HEAD_DIM || L->axis_v != KVQ_AXIS_HEAD_DIM) return KVQ_ERR_UNSUPPORTED;
+  if (L->axis_v != KVQ_AXIS_HEAD_DIM) return KVQ_ERR_UNSUPPORTED;
+  if (L->axis_k == KVQ_AXIS_SEQ) {
+    // channel-wise keys: 64-token groups with a 64-slot residual buffer; quantized keys and values, no rotation
+    if (L->bits_k == 16 || L->bits_v == 16 || L->rotate_k) return KVQ_ERR_INVALID_ARG;
+    if (L->group_k != kvq::kSeqGroup) return KVQ_ERR_UNSUPPORTED;
+  }
   if ((int64_t)L->batch * L->kv_heads > 65535) return KVQ_ERR_UNSUPPORTED;
   if (L->max_seq > (1 << 24)) return KVQ_ERR_UNSUPPORTED;   // a (b,h) stream of any plane stays below 4 GiB
   return KVQ_OK;
@@ -32,6 +37,8 @@ kvq_status check_cache(const kvq_layout* L, const kvq_cache* c) {
   if (L->bits_k != 16 && !c->k_meta) return KVQ_ERR_INVALID_ARG;
   if (L->bits_v != 16 && !c->v_meta) return KVQ_ERR_INVALID_ARG;
   if (!aligned16(c->k_codes) || !aligned16(c->v_codes) || !aligned16(c->k_meta) || !aligned16(c->v_meta))
+    return KVQ_ERR_INVALID_ARG;
+  if (L->axis_k == KVQ_AXIS_SEQ && (!c->k_resid || !c->v_resid || !aligned16(c->k_resid) || !aligned16(c->v_resid)))
     return KVQ_ERR_INVALID_ARG;
   return KVQ_OK;
 }
@@ -50,6 +57,17 @@ kvq_status kvq_cache_bytes(const kvq_layout* layout, size_t bytes_out[4]) {
   bytes_out[1] = (size_t)(streams * g.km_stream);
   bytes_out[2] = (size_t)(streams * g.vc_stream);
   bytes_out[3] = (size_t)(streams * g.vm_stream);
+  return KVQ_OK;
+}
+
+kvq_status kvq_residual_bytes(const kvq_layout* layout, size_t bytes_out[2]) {
+  kvq_status st = check_layout(layout);
+  if (st != KVQ_OK) return st;
+  if (!bytes_out) return KVQ_ERR_INVALID_ARG;
+  const size_t n = layout->axis_k == KVQ_AXIS_SEQ
+                       ? (size_t)layout->batch * layout->kv_heads * kvq::kSeqGroup * kvq::kHeadDim * 2 : 0;
+  bytes_out[0] = n;
+  bytes_out[1] = n;
   return KVQ_OK;
 }
 
@@ -82,6 +100,12 @@ kvq_status kvq_quantize_append(const kvq_layout* layout, const kvq_cache* cache,
   if (!aligned16(k_new) || !aligned16(v_new) || stride_b % 8 || stride_h % 8 || stride_t % 8 || stride_t < layout->head_dim)
     return KVQ_ERR_INVALID_ARG;
   const kvq::Geom g = kvq::make_geom(*layout);
+  if (layout->axis_k == KVQ_AXIS_SEQ) {
+    if ((int)in_dtype != layout->raw_dtype) return KVQ_ERR_INVALID_ARG;   // the residual buffer keeps the input patterns
+    hipError_t e = kvq::launch_seq_append(g, *cache, k_new, v_new, in_dtype, stride_b, stride_h, stride_t, pos, n_new,
+                                          (hipStream_t)stream);
+    return e == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
+  }
   hipError_t e = kvq::launch_quantize_append(g, *cache, k_new, v_new, in_dtype, stride_b, stride_h, stride_t, pos, n_new,
                                              (hipStream_t)stream);
   return e == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
@@ -102,6 +126,7 @@ kvq_status decode_common(const kvq_layout* layout, const kvq_cache* cache, const
   if (!(softmax_scale > 0.0f) || softmax_scale > 3.0e38f) return KVQ_ERR_INVALID_ARG;   // positive and finite
   if (!aligned16(q) || !aligned16(out)) return KVQ_ERR_INVALID_ARG;
   const kvq::Geom g = kvq::make_geom(*layout);
+  if (layout->axis_k == KVQ_AXIS_SEQ) return KVQ_ERR_UNSUPPORTED;
   if (!kvq::decode_supported(g, q_heads)) return KVQ_ERR_UNSUPPORTED;
   if (layout->bits_k == 16 && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // matrix operands share a type
   if (layout->bits_k == 16 && app) return KVQ_ERR_UNSUPPORTED;          // fused append exists for quantized caches only

@@ -9,12 +9,15 @@ namespace kvq {
 
 constexpr int kHeadDim = 128;     // the only head_dim the kernels are written for
 constexpr int kBlockTokens = 32;  // value codes are stored in blocks of this many tokens
+constexpr int kSeqGroup = 64;     // channel-wise keys: tokens per key group = slots of the residual buffer
 
 // Geometry derived once on the host and passed by value to every kernel.
 struct Geom {
   int32_t batch, kv_heads, t_cap;   // t_cap = max_seq rounded up to kBlockTokens
   int32_t bits_k, bits_v, ng_k, ng_v, g_k, g_v;
   int32_t raw_dtype;
+  int32_t axis_k;                   // KVQ_AXIS_SEQ: channel-wise key groups of kSeqGroup tokens + residual buffer;
+                                    // then g_k = 128 and ng_k = 1 (one matrix column per head on the key side)
   int32_t rotate_k;                 // key rows are stored as codes of R k (randomized Hadamard rotation)
   uint32_t signs_k[4];              // bit d set: s_d = -1
   int64_t kc_stream, km_stream, vc_stream, vm_stream;   // bytes per (b,h) stream in each plane
@@ -25,9 +28,10 @@ inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 inline Geom make_geom(const kvq_layout& L) {
   Geom g{};
   g.batch = L.batch; g.kv_heads = L.kv_heads;
-  g.t_cap = (int32_t)round_up(L.max_seq, kBlockTokens);
+  g.axis_k = L.axis_k;
+  g.t_cap = (int32_t)round_up(L.max_seq, L.axis_k == KVQ_AXIS_SEQ ? kSeqGroup : kBlockTokens);
   g.bits_k = L.bits_k; g.bits_v = L.bits_v;
-  g.g_k = L.bits_k == 16 ? kHeadDim : L.group_k;
+  g.g_k = (L.bits_k == 16 || L.axis_k == KVQ_AXIS_SEQ) ? kHeadDim : L.group_k;
   g.g_v = L.bits_v == 16 ? kHeadDim : L.group_v;
   g.ng_k = kHeadDim / g.g_k; g.ng_v = kHeadDim / g.g_v;
   g.raw_dtype = L.raw_dtype;
@@ -35,7 +39,8 @@ inline Geom make_geom(const kvq_layout& L) {
   for (int i = 0; i < 4; ++i) g.signs_k[i] = L.rotate_k ? L.signs_k[i] : 0u;
   g.kc_stream = (int64_t)g.t_cap * (kHeadDim * L.bits_k / 8);
   g.vc_stream = (int64_t)g.t_cap * (kHeadDim * L.bits_v / 8);
-  g.km_stream = L.bits_k == 16 ? 0 : (int64_t)g.t_cap * g.ng_k * 4;
+  g.km_stream = L.bits_k == 16 ? 0 : L.axis_k == KVQ_AXIS_SEQ ? (int64_t)(g.t_cap / kSeqGroup) * kHeadDim * 4
+                                                                : (int64_t)g.t_cap * g.ng_k * 4;
   g.vm_stream = L.bits_v == 16 ? 0 : (int64_t)g.t_cap * g.ng_v * 4;
   return g;
 }
@@ -71,6 +76,9 @@ struct DecodeArgs {
 hipError_t launch_quantize_append(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new,
                                   int in_dtype, int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new,
                                   hipStream_t stream);
+// Channel-wise keys: tokens go to the residual buffer; completed blocks of kSeqGroup tokens are flushed.
+hipError_t launch_seq_append(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype,
+                             int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream);
 hipError_t launch_dequantize(const Geom& g, const kvq_cache& c, int32_t t0, int32_t t1, void* k_out, void* v_out,
                              int out_dtype, hipStream_t stream);
 hipError_t launch_reconstruction_error(const Geom& g, const kvq_cache& c, const void* k_ref, const void* v_ref,

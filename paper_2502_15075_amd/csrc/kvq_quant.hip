@@ -26,13 +26,71 @@ template <int B> __device__ __forceinline__ uint32_t pack_bytes(uint32_t w) {
   return w;
 }
 
+// Token row (0..63 of the span) -> (block, word family, field): the codes of the 8 channels d0..d0+7 of this lane go
+// to 8 words 4 apart; they are staged in LDS in storage order, one element per code.
+template <int BV>
+__device__ __forceinline__ void stage_value_codes(uint8_t* vstage, int row, int d0, const uint32_t codes[8]) {
+  constexpr int F = 32 / BV, P = 16 / BV, ES = BV == 16 ? 2 : 1;
+  const int sub = row >> 5, u = row & 31;
+  const int j = (u >> 2) & 3, i = 4 * (u >> 4) + (u & 3);
+  const int x = i & 1, v = i >> 1;
+  const int q = 4 * (d0 >> 4) + v;
+  const int e_idx = q / P, p = q % P;
+  const int word0 = sub * (128 * BV) + (e_idx >> 2) * 256 + (16 * j + (d0 & 15)) * 4 + (e_idx & 3);
+  const int a0 = (word0 * F + x * P + p) * ES;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int a = stage_phys(a0 + e * 4 * F * ES);
+    if (BV == 16) *reinterpret_cast<uint16_t*>(vstage + a) = (uint16_t)codes[e];
+    else vstage[a] = (uint8_t)codes[e];
+  }
+}
+
+// One thread per 32-bit word of the span (two blocks of 128*BV words): assemble the word from the staged codes and
+// store it; when the span is only partly covered by the new tokens [lo, hi), keep the fields of the other tokens.
+template <int BV>
+__device__ __forceinline__ void store_value_words(uint32_t* vc, const uint8_t* vstage, int tid, int lo, int hi) {
+  constexpr int F = 32 / BV, P = 16 / BV, ES = BV == 16 ? 2 : 1;
+  const bool full = lo == 0 && hi == kSpan;
+  for (int w = tid; w < 256 * BV; w += 256) {
+    const uint8_t* sp = vstage + stage_phys(w * F * ES);
+    uint32_t bits;
+    if (BV == 2) {
+      const uint4 r = *reinterpret_cast<const uint4*>(sp);
+      bits = pack_bytes<2>(r.x) | (pack_bytes<2>(r.y) << 8) | (pack_bytes<2>(r.z) << 16) | (pack_bytes<2>(r.w) << 24);
+    } else if (BV == 4) {
+      const uint2 r = *reinterpret_cast<const uint2*>(sp);
+      bits = pack_bytes<4>(r.x) | (pack_bytes<4>(r.y) << 16);
+    } else {
+      bits = *reinterpret_cast<const uint32_t*>(sp);            // 8-bit: four codes; 16-bit: two patterns
+    }
+    if (full) { vc[w] = bits; continue; }
+    // partially covered span: keep the fields of tokens outside [lo, hi)
+    const int sub = w / (128 * BV), wi = w % (128 * BV);
+    const int piece = wi >> 8, rem = wi & 255;
+    const int L = rem >> 2, m = rem & 3;
+    const int e_idx = 4 * piece + m;
+    const int j = L >> 4;
+    const uint32_t fmask = BV == 16 ? 0xFFFFu : ((1u << BV) - 1u);
+    uint32_t mask = 0;
+    for (int x = 0; x < 2; ++x)
+      for (int p = 0; p < P; ++p) {
+        const int q = e_idx * P + p;
+        const int v = q & 3;
+        const int i = 2 * v + x;
+        const int tt = 32 * sub + 16 * (i >> 2) + 4 * j + (i & 3);
+        if (tt >= lo && tt < hi) mask |= fmask << (16 * x + BV * p);
+      }
+    if (mask == 0) continue;
+    vc[w] = (bits & mask) | (vc[w] & ~mask);
+  }
+}
+
 // One workgroup = one 64-token span of one (b,h) stream, restricted to the new tokens in it.
 template <int BK, int BV, bool BF>
 __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_new,
                                                               const uint16_t* __restrict__ v_new, int64_t sb, int64_t sh,
                                                               int64_t st, int32_t pos, int32_t n_new) {
-  constexpr int F = 32 / BV;                      // codes per 32-bit word of the value plane
-  constexpr int P = 16 / BV;
   constexpr int ES = BV == 16 ? 2 : 1;            // bytes per staged element
   constexpr int kStageBytes = kSpan * kHeadDim * ES;
   __shared__ __attribute__((aligned(16))) uint8_t vstage[kStageBytes + (kStageBytes >> 4)];
@@ -113,58 +171,12 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         quantize8(x, BV, lpg, codes, &S, &Z);
         if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 / lpg, g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
       }
-      // token row -> (block, word family, field): the 8 channels of this lane go to 8 words 4 apart
-      const int sub = row >> 5, u = row & 31;
-      const int j = (u >> 2) & 3, i = 4 * (u >> 4) + (u & 3);
-      const int x = i & 1, v = i >> 1;
-      const int q = 4 * (d0 >> 4) + v;
-      const int e_idx = q / P, p = q % P;
-      const int word0 = sub * (128 * BV) + (e_idx >> 2) * 256 + (16 * j + (d0 & 15)) * 4 + (e_idx & 3);
-      const int a0 = (word0 * F + x * P + p) * ES;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int a = stage_phys(a0 + e * 4 * F * ES);
-        if (BV == 16) *reinterpret_cast<uint16_t*>(vstage + a) = (uint16_t)codes[e];
-        else vstage[a] = (uint8_t)codes[e];
-      }
+      stage_value_codes<BV>(vstage, row, d0, codes);
     }
   }
   __syncthreads();
 
-  // ---- values: one thread per 32-bit word of the span (two blocks of 128*BV words)
-  const bool full = lo == 0 && hi == kSpan;
-  for (int w = tid; w < 256 * BV; w += 256) {
-    const uint8_t* sp = vstage + stage_phys(w * F * ES);
-    uint32_t bits;
-    if (BV == 2) {
-      const uint4 r = *reinterpret_cast<const uint4*>(sp);
-      bits = pack_bytes<2>(r.x) | (pack_bytes<2>(r.y) << 8) | (pack_bytes<2>(r.z) << 16) | (pack_bytes<2>(r.w) << 24);
-    } else if (BV == 4) {
-      const uint2 r = *reinterpret_cast<const uint2*>(sp);
-      bits = pack_bytes<4>(r.x) | (pack_bytes<4>(r.y) << 16);
-    } else {
-      bits = *reinterpret_cast<const uint32_t*>(sp);            // 8-bit: four codes; 16-bit: two patterns
-    }
-    if (full) { vc[w] = bits; continue; }
-    // partially covered span: keep the fields of tokens outside [lo, hi)
-    const int sub = w / (128 * BV), wi = w % (128 * BV);
-    const int piece = wi >> 8, rem = wi & 255;
-    const int L = rem >> 2, m = rem & 3;
-    const int e_idx = 4 * piece + m;
-    const int j = L >> 4;
-    const uint32_t fmask = BV == 16 ? 0xFFFFu : ((1u << BV) - 1u);
-    uint32_t mask = 0;
-    for (int x = 0; x < 2; ++x)
-      for (int p = 0; p < P; ++p) {
-        const int q = e_idx * P + p;
-        const int v = q & 3;
-        const int i = 2 * v + x;
-        const int tt = 32 * sub + 16 * (i >> 2) + 4 * j + (i & 3);
-        if (tt >= lo && tt < hi) mask |= fmask << (16 * x + BV * p);
-      }
-    if (mask == 0) continue;
-    vc[w] = (bits & mask) | (vc[w] & ~mask);
-  }
+  store_value_words<BV>(vc, vstage, tid, lo, hi);
 }
 
 // The 8 codes of channels 8*oct .. 8*oct+7 of key row t: B consecutive bytes of the row-major bit string.
@@ -193,6 +205,144 @@ template <int B> __device__ __forceinline__ void value_codes8(const uint8_t* cs,
   const uint32_t* blk = reinterpret_cast<const uint32_t*>(cs + (t >> 5) * (int64_t)(512 * B)) + dw;
 #pragma unroll
   for (int e = 0; e < 8; ++e) code[e] = (blk[4 * e] >> bit) & (B == 16 ? 0xFFFFu : ((1u << B) - 1u));
+}
+
+// Pack the 8 codes of channels 8*lane16 .. +7 of one key row into the row-major bit string.
+template <int BK>
+__device__ __forceinline__ void store_key_codes(uint8_t* rowp, int lane16, const uint32_t codes[8]) {
+  if (BK == 8) {
+    const uint32_t w0 = codes[0] | (codes[1] << 8) | (codes[2] << 16) | (codes[3] << 24);
+    const uint32_t w1 = codes[4] | (codes[5] << 8) | (codes[6] << 16) | (codes[7] << 24);
+    reinterpret_cast<uint2*>(rowp)[lane16] = make_uint2(w0, w1);
+  } else {
+    uint32_t w = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) w |= codes[e] << (BK * e);
+    if (BK == 4) reinterpret_cast<uint32_t*>(rowp)[lane16] = w;
+    else reinterpret_cast<uint16_t*>(rowp)[lane16] = (uint16_t)w;
+  }
+}
+
+// Channel-wise keys (Sec. 4 "Downstream Task Accuracy": the per-column back-end with its residual buffer).
+// One workgroup = one block of kSeqGroup = 64 tokens of one (b,h) stream, restricted to the new tokens [lo, hi) in it.
+// New tokens that no later token of this call overwrites go to their residual slot as 16-bit patterns.  A block that
+// this call completes is flushed: rows below lo come back from the residual buffer, keys are quantized channel by
+// channel (the group is the 64 tokens of one channel), values token-wise exactly as in quantize_append_kernel.
+template <int BK, int BV, bool BF>
+__global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_new,
+                                                         const uint16_t* __restrict__ v_new, int64_t sb, int64_t sh,
+                                                         int64_t st, int32_t pos, int32_t n_new) {
+  static_assert(kSeqGroup == kSpan, "a flushed block is one value span");
+  constexpr int kStageBytes = kSpan * kHeadDim;
+  __shared__ __attribute__((aligned(16))) uint8_t vstage[kStageBytes + (kStageBytes >> 4)];
+  __shared__ float s_mn[4][kHeadDim], s_mx[4][kHeadDim];
+  const int tid = threadIdx.x;
+  const int bh = blockIdx.y;
+  const int b = bh / g.kv_heads, h = bh % g.kv_heads;
+  const int blk = pos / kSpan + blockIdx.x;
+  const int lo = max(pos, blk * kSpan) - blk * kSpan;
+  const int hi = min(pos + n_new, (blk + 1) * kSpan) - blk * kSpan;
+  const bool complete = hi == kSpan;                       // this call brings the block's last token
+  const int lane16 = tid & 15, rg = tid >> 4;
+  const int d0 = lane16 * 8;
+  uint8_t* kr = (uint8_t*)c.k_resid + (int64_t)bh * (kSeqGroup * kHeadDim * 2);
+  uint8_t* vr = (uint8_t*)c.v_resid + (int64_t)bh * (kSeqGroup * kHeadDim * 2);
+
+  uint4 kraw[4], vraw[4];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int row = rg + 16 * it;
+    const int64_t t = (int64_t)blk * kSpan + row;
+    if (row >= lo && row < hi) {
+      const int64_t src = (int64_t)b * sb + (int64_t)h * sh + (t - pos) * st + d0;
+      kraw[it] = *reinterpret_cast<const uint4*>(k_new + src);
+      vraw[it] = *reinterpret_cast<const uint4*>(v_new + src);
+      if (t + kSeqGroup >= (int64_t)pos + n_new) {         // the last token of this call that lands in slot `row`
+        *reinterpret_cast<uint4*>(kr + row * (kHeadDim * 2) + d0 * 2) = kraw[it];
+        const uint32_t rw[4] = {vraw[it].x, vraw[it].y, vraw[it].z, vraw[it].w};
+        int dw, bit;
+        v_field(row & 31, d0, 16, &dw, &bit);
+        uint16_t* blk16 = reinterpret_cast<uint16_t*>(vr + (row >> 5) * (512 * 16));
+#pragma unroll
+        for (int e = 0; e < 8; ++e) blk16[(dw + 4 * e) * 2 + (bit >> 4)] = (uint16_t)(rw[e >> 1] >> (16 * (e & 1)));
+      }
+    } else if (complete && row < lo) {                     // older tokens of the block being flushed
+      kraw[it] = *reinterpret_cast<const uint4*>(kr + row * (kHeadDim * 2) + d0 * 2);
+      uint32_t code[8];
+      value_codes8<16>(vr, row, d0, code);
+      vraw[it] = make_uint4(code[0] | (code[1] << 16), code[2] | (code[3] << 16), code[4] | (code[5] << 16),
+                            code[6] | (code[7] << 16));
+    }
+  }
+  if (!complete) return;                                   // uniform over the workgroup
+
+  uint8_t* kc = (uint8_t*)c.k_codes + (int64_t)bh * g.kc_stream;
+  uint32_t* km = (uint32_t*)((uint8_t*)c.k_meta + (int64_t)bh * g.km_stream) + (int64_t)blk * kHeadDim;
+  uint32_t* vm = (uint32_t*)((uint8_t*)c.v_meta + (int64_t)bh * g.vm_stream);
+  uint32_t* vc = (uint32_t*)((uint8_t*)c.v_codes + (int64_t)bh * g.vc_stream) + (int64_t)blk * (256 * BV);
+
+  // ---- keys: minimum and maximum of every channel over the 64 rows (4 rows here, 4 row groups per wavefront,
+  // 4 wavefronts through LDS)
+  float x[4][8];
+  float mn[8], mx[8];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const uint32_t rw[4] = {kraw[it].x, kraw[it].y, kraw[it].z, kraw[it].w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      x[it][e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
+      mn[e] = it == 0 ? x[it][e] : fminf(mn[e], x[it][e]);
+      mx[e] = it == 0 ? x[it][e] : fmaxf(mx[e], x[it][e]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    mn[e] = fminf(mn[e], __shfl_xor(mn[e], 16)); mn[e] = fminf(mn[e], __shfl_xor(mn[e], 32));
+    mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 16)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 32));
+  }
+  if ((rg & 3) == 0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { s_mn[tid >> 6][d0 + e] = mn[e]; s_mx[tid >> 6][d0 + e] = mx[e]; }
+  }
+  __syncthreads();
+  const float levels = (float)((1 << BK) - 1);
+  uint32_t codes[4][8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float lo_v = fminf(fminf(s_mn[0][d0 + e], s_mn[1][d0 + e]), fminf(s_mn[2][d0 + e], s_mn[3][d0 + e]));
+    const float hi_v = fmaxf(fmaxf(s_mx[0][d0 + e], s_mx[1][d0 + e]), fmaxf(s_mx[2][d0 + e], s_mx[3][d0 + e]));
+    uint16_t S, Z;
+    group_scale_zero(lo_v, hi_v, BK, &S, &Z);
+    if (rg == 0) km[d0 + e] = (uint32_t)S | ((uint32_t)Z << 16);
+    const float sc = widen16(S, false), z = widen16(Z, false);
+    const float rcp = 1.0f / sc;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) codes[it][e] = group_code(x[it][e], sc, z, rcp, levels);
+  }
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int64_t t = (int64_t)blk * kSpan + rg + 16 * it;
+    store_key_codes<BK>(kc + t * (16 * BK), lane16, codes[it]);
+  }
+
+  // ---- values: token-wise, as in quantize_append_kernel for a full span
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int row = rg + 16 * it;
+    const int64_t t = (int64_t)blk * kSpan + row;
+    const uint32_t rw[4] = {vraw[it].x, vraw[it].y, vraw[it].z, vraw[it].w};
+    float xv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) xv[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
+    uint32_t vcodes[8];
+    uint16_t S, Z;
+    const int lpg = g.g_v >> 3;
+    quantize8(xv, BV, lpg, vcodes, &S, &Z);
+    if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 / lpg, g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
+    stage_value_codes<BV>(vstage, row, d0, vcodes);
+  }
+  __syncthreads();
+  store_value_words<BV>(vc, vstage, tid, 0, kSpan);
 }
 
 // Reconstruction x^ = code * scale + zero of 8 consecutive channels d0..d0+7 (d0 a multiple of 8) of token t of
@@ -226,6 +376,15 @@ __device__ __forceinline__ void reconstruct8(const Geom& g, const kvq_cache& c, 
     return;
   }
   const uint32_t* ms = (const uint32_t*)((const uint8_t*)(which ? c.v_meta : c.k_meta) + bh * (which ? g.vm_stream : g.km_stream));
+  if (!which && g.axis_k == KVQ_AXIS_SEQ) {        // channel-wise keys: one scale/zero per channel and 64-token block
+    const uint4* mp = reinterpret_cast<const uint4*>(ms + (t / kSeqGroup) * kHeadDim + d0);
+    const uint4 m0 = mp[0], m1 = mp[1];
+    const uint32_t mm[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      val[e] = (float)code[e] * widen16((uint16_t)(mm[e] & 0xFFFF), false) + widen16((uint16_t)(mm[e] >> 16), false);
+    return;
+  }
   const uint32_t m = ms[meta_index(t, d0 / G, ng)];
   const float s = widen16((uint16_t)(m & 0xFFFF), false);
   const float z = widen16((uint16_t)(m >> 16), false);
@@ -355,6 +514,43 @@ hipError_t launch_quantize_append(const Geom& g, const kvq_cache& c, const void*
     case 4: return launch_qk<4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 8: return launch_qk<8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 16: return launch_qk<16>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+namespace {
+template <int BK, int BV>
+hipError_t launch_sa(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype, int64_t sb,
+                     int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
+  const int first = pos / kSeqGroup, last = (pos + n_new - 1) / kSeqGroup;
+  dim3 grid(last - first + 1, g.batch * g.kv_heads);
+  if (in_dtype == KVQ_BF16)
+    hipLaunchKernelGGL((seq_append_kernel<BK, BV, true>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
+                       (const uint16_t*)v_new, sb, sh, st, pos, n_new);
+  else
+    hipLaunchKernelGGL((seq_append_kernel<BK, BV, false>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
+                       (const uint16_t*)v_new, sb, sh, st, pos, n_new);
+  return hipGetLastError();
+}
+template <int BK>
+hipError_t launch_sak(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype, int64_t sb,
+                      int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
+  switch (g.bits_v) {
+    case 2: return launch_sa<BK, 2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 4: return launch_sa<BK, 4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 8: return launch_sa<BK, 8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+  }
+  return hipErrorInvalidValue;
+}
+}  // namespace
+
+hipError_t launch_seq_append(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype,
+                             int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
+  if (n_new == 0) return hipSuccess;
+  switch (g.bits_k) {
+    case 2: return launch_sak<2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 4: return launch_sak<4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 8: return launch_sak<8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
   }
   return hipErrorInvalidValue;
 }

@@ -121,4 +121,27 @@ __device__ __forceinline__ void quantize8(const float x[8], int bits, int lanes_
   }
 }
 
+// The same quantizer for a group that is not spread over neighbouring lanes (channel-wise key groups: the group runs
+// over tokens): stored scale/zero patterns from the group's minimum and maximum, then one code at a time.
+__device__ __forceinline__ void group_scale_zero(float mn, float mx, int bits, uint16_t* S, uint16_t* Z) {
+#pragma clang fp contract(off)
+  if (mn == 0.0f) mn = 0.0f;  // -0 -> +0
+  const float levels = (float)((1 << bits) - 1);
+  const float s32 = (mx - mn) / levels;
+  uint16_t sb = f32_to_f16_bits(s32);
+  if ((sb & 0x7FFFu) == 0) sb = 0;
+  *S = sb;
+  *Z = f32_to_f16_bits(mn);
+}
+
+// s, z: the stored scale/zero widened; rcp = 1 / s (unused when s == 0); levels = 2^bits - 1.
+__device__ __forceinline__ uint32_t group_code(float x, float s, float z, float rcp, float levels) {
+#pragma clang fp contract(off)
+  if (s == 0.0f) return 0u;
+  const float t = (x - z) * rcp;
+  float q = rintf(t);
+  q = fminf(fmaxf(q, 0.0f), levels);
+  return (uint32_t)q;
+}
+
 }  // namespace kvq

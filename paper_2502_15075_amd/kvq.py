@@ -34,7 +34,7 @@ class _CLayout(C.Structure):
 
 
 class _CCache(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_meta", "v_codes", "v_meta")]
+    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_meta", "v_codes", "v_meta", "k_resid", "v_resid")]
 
 
 _lib = None
@@ -48,6 +48,7 @@ def load():
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2502_15075_amd.build` (there is no fallback path)")
         lib = C.CDLL(LIB_PATH)
         lib.kvq_cache_bytes.argtypes = [C.POINTER(_CLayout), C.POINTER(C.c_size_t)]
+        lib.kvq_residual_bytes.argtypes = [C.POINTER(_CLayout), C.POINTER(C.c_size_t)]
         lib.kvq_decode_workspace_bytes.argtypes = [C.POINTER(_CLayout), C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
         lib.kvq_quantize_append.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int,
                                             C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p]
@@ -62,7 +63,7 @@ def load():
                                                  C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         lib.kvq_status_string.argtypes = [C.c_int]
         lib.kvq_status_string.restype = C.c_char_p
-        for f in ("kvq_cache_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
+        for f in ("kvq_cache_bytes", "kvq_residual_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
                   "kvq_decode_step", "kvq_dequantize", "kvq_reconstruction_error"):
             getattr(lib, f).restype = C.c_int
         _lib = lib
@@ -115,6 +116,13 @@ def cache_bytes(layout: Layout):
     return [int(v) for v in out]
 
 
+def residual_bytes(layout: Layout):
+    out = (C.c_size_t * 2)()
+    cl = layout.c()
+    _check(load().kvq_residual_bytes(C.byref(cl), out), "kvq_residual_bytes")
+    return [int(v) for v in out]
+
+
 def decode_workspace_bytes(layout: Layout, q_heads: int, seq_len: int) -> int:
     out = C.c_size_t()
     cl = layout.c()
@@ -123,11 +131,12 @@ def decode_workspace_bytes(layout: Layout, q_heads: int, seq_len: int) -> int:
 
 
 class Cache:
-    """Four caller-owned device planes (torch uint8 tensors) for one layer."""
+    """The caller-owned device planes (torch uint8 tensors) of one layer: codes and scale/zero of keys and values,
+    then the two residual buffers of channel-wise keys (None otherwise)."""
 
     def __init__(self, layout: Layout, device="cuda", fill=None):
         self.layout = layout
-        sizes = cache_bytes(layout)
+        sizes = cache_bytes(layout) + residual_bytes(layout)
         mk = (lambda n: torch.empty(n, dtype=torch.uint8, device=device)) if fill is None else \
              (lambda n: torch.full((n,), fill, dtype=torch.uint8, device=device))
         self.planes = [mk(n) if n else None for n in sizes]

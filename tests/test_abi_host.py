@@ -24,7 +24,8 @@ def test_every_declared_symbol_is_exported(kvq):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(kvq_[a-z_]+)\s*\(", header))
     assert {"kvq_cache_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
-            "kvq_decode_step", "kvq_dequantize", "kvq_reconstruction_error", "kvq_status_string"} <= declared
+            "kvq_decode_step", "kvq_dequantize", "kvq_reconstruction_error", "kvq_residual_bytes",
+            "kvq_status_string"} <= declared
     lib = C.CDLL(kvq.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), name
@@ -49,11 +50,18 @@ def test_cache_bytes_closed_forms(kvq):
     assert sum(kvq.cache_bytes(kvq.Layout(1, 1, 65, 128, 8, 8, 64, 64))) == 96 * 272        # capacity rounds up to 32
     raw = kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 16, 16, 64, 64))
     assert raw == [2 * 2 * 64 * 256, 0, 2 * 2 * 64 * 256, 0]
+    # channel-wise keys: capacity in blocks of 64 tokens, 4 bytes per channel and block, two 64-slot residual buffers
+    Ls = kvq.Layout(2, 3, 100, 128, 4, 2, 64, 32, axis_k=kvq.AXIS_SEQ)
+    assert kvq.cache_bytes(Ls) == [6 * 128 * 64, 6 * 2 * 512, 6 * 128 * 32, 6 * 128 * 16]
+    assert kvq.residual_bytes(Ls) == [6 * 64 * 256, 6 * 64 * 256]
+    assert kvq.residual_bytes(kvq.Layout(2, 3, 100)) == [0, 0]
 
 
 def test_sizes_agree_with_the_oracle(kvq, oracle):
     for args in ((1, 8, 1024, 128, 4, 2, 32, 32), (3, 2, 77, 128, 2, 8, 128, 64), (2, 2, 33, 128, 16, 4, 64, 32)):
         assert kvq.cache_bytes(kvq.Layout(*args)) == oracle.plane_bytes(oracle.Layout(*args))
+    Lg, Lo = kvq.Layout(3, 2, 77, 128, 4, 2, 64, 32, axis_k=kvq.AXIS_SEQ), oracle.Layout(3, 2, 77, 128, 4, 2, 64, 32, axis_k=1)
+    assert kvq.cache_bytes(Lg) + kvq.residual_bytes(Lg) == [p.size for p in oracle.new_seq_planes(Lo)]
 
 
 def test_workspace_plan(kvq):
@@ -76,7 +84,10 @@ def test_layout_errors(kvq):
         (kvq.Layout(0, 8, 64), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 0), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 3, 2), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, 128, 4, 5), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 48, 64), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 256), kvq.ERR_INVALID_ARG),
-        (kvq.Layout(1, 8, 64, 64), kvq.ERR_UNSUPPORTED), (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_k=1), kvq.ERR_UNSUPPORTED),
+        (kvq.Layout(1, 8, 64, 64), kvq.ERR_UNSUPPORTED), (kvq.Layout(1, 8, 64, 128, 4, 2, 32, 64, axis_k=1), kvq.ERR_UNSUPPORTED),
+        (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_v=1), kvq.ERR_UNSUPPORTED),
+        (kvq.Layout(1, 8, 64, 128, 16, 16, 64, 64, axis_k=1), kvq.ERR_INVALID_ARG),      # residual buffer + unquantized planes
+        (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_k=1, rotate_k=1), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_v=7), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, raw_dtype=2), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 1 << 25), kvq.ERR_UNSUPPORTED),

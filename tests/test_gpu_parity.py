@@ -555,3 +555,57 @@ def test_decode_step_replayed_from_a_hip_graph(kvq, oracle):
         kvq.decode_attention(Lg, cache, qd, T - 7, 1 / math.sqrt(128), torch.empty_like(eager), ws)
         torch.cuda.synchronize()
     _assert_planes_equal(cache, planes)
+
+
+# --------------------------------------------------------------------------- channel-wise keys + residual buffer
+
+def _seq_layouts(kvq, oracle, B, H, T, bk, bv, gv, raw=0):
+    return (kvq.Layout(B, H, T, 128, bk, bv, 64, gv, axis_k=kvq.AXIS_SEQ, raw_dtype=raw),
+            oracle.Layout(B, H, T, 128, bk, bv, 64, gv, raw_dtype=raw, axis_k=1))
+
+
+def _seq_fill_both(kvq, oracle, Lg, Lo, K, V, chunks, fill=0xA5):
+    cache = kvq.Cache(Lg, fill=fill)
+    planes = oracle.new_seq_planes(Lo, fill=fill)
+    bf = K.dtype == torch.bfloat16
+    Kd, Vd = K.cuda(), V.cuda()
+    for a, b in chunks:
+        kvq.quantize_append(Lg, cache, Kd[:, :, a:b], Vd[:, :, a:b], a)
+        oracle.seq_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, a:b])),
+                          np.ascontiguousarray(synth.to_numpy_bits(V[:, :, a:b])), a, bf16=bf)
+    torch.cuda.synchronize()
+    return cache, planes
+
+
+def _assert_seq_planes_equal(cache, planes):
+    names = ("k_codes", "k_meta", "v_codes", "v_meta", "k_resid", "v_resid")
+    for name, g, o in zip(names, cache.planes, planes):
+        g = g.cpu().numpy()
+        assert g.shape == o.shape, name
+        bad = np.flatnonzero(g != o)
+        assert bad.size == 0, f"{name}: {bad.size} bytes differ, first at {bad[:5]}"
+
+
+@pytest.mark.parametrize("bk,bv,gv", [(4, 2, 64), (2, 4, 128), (8, 8, 32), (4, 4, 64)])
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_channelwise_append_is_byte_identical(kvq, oracle, bk, bv, gv, dtype):
+    """Sec. 4, per-column keys with the 64-token residual buffer: all six planes (codes, scale/zero, residual
+    buffers; untouched bytes keep the fill pattern) equal the oracle's after ragged chunked appends, single tokens
+    and a bulk append over several blocks included."""
+    B, H, T = 2, 3, 333
+    K, V, _ = synth.make_kvq(70 + bk + bv, B, H, H, T, dtype=dtype)
+    raw = 1 if dtype == torch.bfloat16 else 0
+    Lg, Lo = _seq_layouts(kvq, oracle, B, H, T, bk, bv, gv, raw)
+    chunks = [(0, 1), (1, 2), (2, 63), (63, 64), (64, 70), (70, 128), (128, 129), (129, 330), (330, 333)]
+    cache, planes = _seq_fill_both(kvq, oracle, Lg, Lo, K, V, chunks)
+    _assert_seq_planes_equal(cache, planes)
+    cache2, planes2 = _seq_fill_both(kvq, oracle, Lg, Lo, K, V, [(0, T)])
+    _assert_seq_planes_equal(cache2, planes2)
+    # flushed tokens reconstruct bit-identically
+    nq = T // 64 * 64
+    ko = torch.empty(B, H, nq, 128, dtype=torch.float32, device="cuda")
+    vo = torch.empty_like(ko)
+    kvq.dequantize(Lg, cache, 0, nq, ko, vo)
+    kd, vd = oracle.seq_dequantize(Lo, planes, T, 0, nq)
+    assert np.array_equal(ko.cpu().numpy().view(np.uint32), kd.view(np.uint32))
+    assert np.array_equal(vo.cpu().numpy().view(np.uint32), vd.view(np.uint32))
