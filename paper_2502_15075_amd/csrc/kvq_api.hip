@@ -79,7 +79,8 @@ kvq_status kvq_decode_workspace_bytes(const kvq_layout* layout, int32_t q_heads,
   const kvq::Geom g = kvq::make_geom(*layout);
   const kvq::DecodePlan plan = kvq::plan_decode(g, seq_len);
   // one record of (head_dim + 2) floats per (batch, query head, split), padded to 16 bytes
-  *bytes_out = plan.n_splits == 1 ? 0 : (size_t)layout->batch * q_heads * plan.n_splits * (kvq::kHeadDim + 4) * sizeof(float);
+  const int32_t records = kvq::decode_records(g, seq_len, plan);
+  *bytes_out = records == 1 ? 0 : (size_t)layout->batch * q_heads * records * (kvq::kHeadDim + 4) * sizeof(float);
   return KVQ_OK;
 }
 
@@ -112,9 +113,10 @@ kvq_status kvq_quantize_append(const kvq_layout* layout, const kvq_cache* cache,
 }
 
 namespace {
-kvq_status decode_common(const kvq_layout* layout, const kvq_cache* cache, const void* q, kvq_dtype q_dtype, int32_t q_heads,
-                         int32_t seq_len, float softmax_scale, void* out, kvq_dtype out_dtype, void* workspace,
-                         size_t workspace_bytes, const kvq::AppendOne* app, void* stream) {
+// Everything that can be wrong with a decode call, checked without launching anything.
+kvq_status decode_check(const kvq_layout* layout, const kvq_cache* cache, const void* q, kvq_dtype q_dtype, int32_t q_heads,
+                        int32_t seq_len, float softmax_scale, void* out, kvq_dtype out_dtype, void* workspace,
+                        size_t workspace_bytes, bool fused_append) {
   kvq_status st = check_layout(layout);
   if (st != KVQ_OK) return st;
   st = check_cache(layout, cache);
@@ -126,14 +128,24 @@ kvq_status decode_common(const kvq_layout* layout, const kvq_cache* cache, const
   if (!(softmax_scale > 0.0f) || softmax_scale > 3.0e38f) return KVQ_ERR_INVALID_ARG;   // positive and finite
   if (!aligned16(q) || !aligned16(out)) return KVQ_ERR_INVALID_ARG;
   const kvq::Geom g = kvq::make_geom(*layout);
-  if (layout->axis_k == KVQ_AXIS_SEQ) return KVQ_ERR_UNSUPPORTED;
   if (!kvq::decode_supported(g, q_heads)) return KVQ_ERR_UNSUPPORTED;
+  if (layout->axis_k == KVQ_AXIS_SEQ && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // residual tail: as unquantized
   if (layout->bits_k == 16 && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // matrix operands share a type
-  if (layout->bits_k == 16 && app) return KVQ_ERR_UNSUPPORTED;          // fused append exists for quantized caches only
+  if (layout->bits_k == 16 && fused_append) return KVQ_ERR_UNSUPPORTED; // fused append exists for quantized caches only
   size_t need = 0;
   st = kvq_decode_workspace_bytes(layout, q_heads, seq_len, &need);
   if (st != KVQ_OK) return st;
   if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return KVQ_ERR_WORKSPACE;
+  return KVQ_OK;
+}
+
+kvq_status decode_common(const kvq_layout* layout, const kvq_cache* cache, const void* q, kvq_dtype q_dtype, int32_t q_heads,
+                         int32_t seq_len, float softmax_scale, void* out, kvq_dtype out_dtype, void* workspace,
+                         size_t workspace_bytes, const kvq::AppendOne* app, void* stream) {
+  kvq_status st = decode_check(layout, cache, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype, workspace,
+                               workspace_bytes, app != nullptr);
+  if (st != KVQ_OK) return st;
+  const kvq::Geom g = kvq::make_geom(*layout);
   const kvq::DecodePlan plan = kvq::plan_decode(g, seq_len);
   hipError_t e = kvq::launch_decode_attention(g, *cache, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype,
                                               (float*)workspace, plan, app, (hipStream_t)stream);
@@ -157,6 +169,18 @@ kvq_status kvq_decode_step(const kvq_layout* layout, const kvq_cache* cache, con
   if (pos >= layout->max_seq) return KVQ_ERR_CAPACITY;
   if (!k_new || !v_new || (in_dtype != KVQ_F16 && in_dtype != KVQ_BF16)) return KVQ_ERR_INVALID_ARG;
   if (!aligned16(k_new) || !aligned16(v_new) || stride_b % 8 || stride_h % 8) return KVQ_ERR_INVALID_ARG;
+  if (layout->axis_k == KVQ_AXIS_SEQ) {
+    // channel-wise keys: the new token goes through the residual buffer (and may flush a block): two calls in a row,
+    // the second one checked before the first one runs
+    kvq_status st = decode_check(layout, cache, q, q_dtype, q_heads, pos + 1, softmax_scale, out, out_dtype, workspace,
+                                 workspace_bytes, false);
+    if (st != KVQ_OK) return st;
+    st = kvq_quantize_append(layout, cache, k_new, v_new, in_dtype, stride_b, stride_h, layout->head_dim, pos, 1,
+                                        stream);
+    if (st != KVQ_OK) return st;
+    return decode_common(layout, cache, q, q_dtype, q_heads, pos + 1, softmax_scale, out, out_dtype, workspace,
+                         workspace_bytes, nullptr, stream);
+  }
   const kvq::AppendOne app{k_new, v_new, (int)in_dtype, stride_b, stride_h};
   return decode_common(layout, cache, q, q_dtype, q_heads, pos + 1, softmax_scale, out, out_dtype, workspace,
                        workspace_bytes, &app, stream);

@@ -21,6 +21,8 @@
 #include "kvq_internal.h"
 #include "kvq_quantizer.h"
 
+#include <type_traits>
+
 namespace kvq {
 namespace {
 
@@ -144,6 +146,7 @@ struct LaneCtx {
   const uint8_t* kc; const uint8_t* vc;   // (b,h) stream bases of the code planes (wave-uniform)
   const uint8_t* meta_base;               // this lane's scale/zero plane: key plane for lanes < 8 ng_k, else value plane
   uint32_t meta_mul, meta_off;            // bytes of that plane per 32-token step; this lane's offset inside them
+  uint32_t meta_step_mask;                // ~1 for the key lanes of channel-wise keys (one entry set per two steps)
   bool meta_lane;                         // lane < 8 (ng_k + ng_v)
   uint32_t kc_off, vc_off;                // this lane's byte offsets inside one step of the code planes
   uint32_t km_rd, vm_rd;                  // byte offsets of this lane's key / value scale-zero entries (tile 0) in the
@@ -176,7 +179,7 @@ __device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L,
       }
     }
   }
-  if (L.meta_lane) r.meta = ld16(L.meta_base + ((uint32_t)step * L.meta_mul + L.meta_off));
+  if (L.meta_lane) r.meta = ld16(L.meta_base + (((uint32_t)step & L.meta_step_mask) * L.meta_mul + L.meta_off));
   const uint32_t vo = (uint32_t)step * (512 * BV) + L.vc_off;
 #pragma unroll
   for (int k = 0; k < BV / 2; ++k) {
@@ -212,23 +215,88 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// ---- channel-wise keys (one scale/zero per channel and 64-token block) --------------------------------------------
+// The scale of channel d cannot leave the contraction over d, so it is folded into the query: per block the operand
+// q~[h,d] = q[h,d] * sK[blk,d] is rebuilt, as a high and a low binary16 part (22 significant bits: the product of two
+// 11-bit numbers is carried exactly), and the zero points enter as one constant per head and block,
+// sum_d q[h,d] zK[blk,d].  logit[t,h] = sum_d q~[h,d] cK[t,d] + that constant.
+struct KSeqState {
+  u32x4 qhi[4], qlo[4];    // query operands of the current block (low part times 2^11)
+  float zq_u;              // zero-point term of the current block, in code units
+};
+struct NoKSeq {};
+constexpr float kLoScale = 2048.0f, kInvLoScale = 1.0f / 2048.0f;
+
+// Rebuild the block's query operands from the staged query row (binary16 or bfloat16 patterns in LDS) and the block's
+// 128 scale/zero entries (first 512 bytes of the wavefront's LDS copy of the step's scale/zero bytes).
+template <int BK>
+__device__ __forceinline__ void kseq_rebuild(KSeqState& ks, const LaneCtx& L, const uint16_t* qrow, bool q_is_bf16, bool act) {
+  float zq = 0.f;
+#pragma unroll
+  for (int half32 = 0; half32 < 2; ++half32) {     // 16 channels at a time: matrix steps 2*half32 and 2*half32 + 1
+    float w[16];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const u32x4 qv = reinterpret_cast<const u32x4*>(qrow + 32 * L.j + 16 * half32)[k];
+      const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+      for (int quad = 0; quad < 2; ++quad) {
+        const u32x4 mv = *reinterpret_cast<const u32x4*>(L.meta_lds + 128 * L.j + 64 * half32 + 32 * k + 16 * quad);
+        const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint16_t qb16 = (uint16_t)(qw[(4 * quad + e) >> 1] >> (16 * (e & 1)));
+          const float qf = q_is_bf16 ? __uint_as_float((uint32_t)qb16 << 16) : (float)__builtin_bit_cast(_Float16, qb16);
+          w[8 * k + 4 * quad + e] = qf * meta_scale(mw[e]);
+          zq = fmaf(qf, meta_zero(mw[e]), zq);
+        }
+      }
+    }
+#pragma unroll
+    for (int mm = 0; mm < 2; ++mm) {
+      const int m = 2 * half32 + mm;
+      uint32_t hi[4] = {0u, 0u, 0u, 0u}, lo[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float val = w[k_slot_elem<BK>(m, i) - 16 * half32] / k_slot_scale<BK>(i);
+        const _Float16 h16 = (_Float16)val;
+        const _Float16 l16 = (_Float16)((val - (float)h16) * kLoScale);
+        hi[i >> 1] |= (uint32_t)__builtin_bit_cast(uint16_t, h16) << (16 * (i & 1));
+        lo[i >> 1] |= (uint32_t)__builtin_bit_cast(uint16_t, l16) << (16 * (i & 1));
+      }
+      ks.qhi[m] = act ? u32x4{hi[0], hi[1], hi[2], hi[3]} : u32x4{0u, 0u, 0u, 0u};
+      ks.qlo[m] = act ? u32x4{lo[0], lo[1], lo[2], lo[3]} : u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+  zq += __shfl_xor(zq, 16);
+  zq += __shfl_xor(zq, 32);
+  ks.zq_u = act ? zq * kCodeUnit : 0.f;
+}
+
 // One 32-token step.  MASKED: tokens at or beyond seq_len get weight 0 (garbage may sit there).
 // BK == BV == 16 is the unquantized cache: no scale/zero, operands are the stored patterns (BF: bfloat16).
 // NCK / NCV: column sets.  Columns are (group, head) pairs; when R * (groups) exceeds the 16 columns of a matrix tile
 // (8 heads with 32-channel groups) the groups are spread over two column sets: set cs carries group grp + cs*(16/R).
-template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool MASKED>
+// KS: KSeqState for channel-wise keys (then NEWBLK marks the first step of a 64-token block: the query operands are
+// rebuilt from that block's scale/zero entries), NoKSeq otherwise.
+template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool MASKED, bool NEWBLK = false, typename KS = NoKSeq>
 __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u32x4 (&qb)[NCK][4], const float (&qsum_u)[NCK],
-                                             float kappa, WaveState<NCV>& st, const LaneCtx& L, int step, int seq_len) {
+                                             float kappa, WaveState<NCV>& st, const LaneCtx& L, int step, int seq_len,
+                                             KS& ks, const uint16_t* qrow = nullptr, bool q_is_bf16 = false,
+                                             bool act_k = false) {
   constexpr bool RAW = BK == 16;
+  constexpr bool KSEQ = !__is_same(KS, NoKSeq);
   constexpr int kSetStride = (16 / R) * 64;      // bytes between the scale/zero entries of a lane's groups in two sets
   uint32_t kmeta[NCK][8], vmeta[NCV][8];
   if constexpr (!RAW) {
     // scale/zero bytes: plane order -> LDS -> the entries this lane needs (tokens 4j..4j+3 of both tiles, own groups)
     if (L.meta_lane) *reinterpret_cast<u32x4*>(L.meta_lds + L.lane * 16) = r.meta;
+    if constexpr (KSEQ && NEWBLK) kseq_rebuild<BK>(ks, L, qrow, q_is_bf16, act_k);
 #pragma unroll
     for (int x4 = 0; x4 < 2; ++x4) {
 #pragma unroll
       for (int cs = 0; cs < NCK; ++cs) {
+        if constexpr (KSEQ) continue;
         const u32x4 a = *reinterpret_cast<const u32x4*>(L.meta_lds + L.km_rd + cs * kSetStride + x4 * (64 * L.ngk));
         kmeta[cs][4 * x4 + 0] = a.x; kmeta[cs][4 * x4 + 1] = a.y; kmeta[cs][4 * x4 + 2] = a.z; kmeta[cs][4 * x4 + 3] = a.w;
       }
@@ -244,8 +312,23 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
   float s[8];
   {
     float part[8];
+    if constexpr (KSEQ) {
+      float4v h0 = {0.f, 0.f, 0.f, 0.f}, h1 = {0.f, 0.f, 0.f, 0.f}, l0 = {0.f, 0.f, 0.f, 0.f}, l1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {                // four independent accumulation chains
+        const u32x4 k0 = unpack_k<BK>(r.kc[0], m), k1 = unpack_k<BK>(r.kc[1], m);
+        h0 = mma<BF>(k0, ks.qhi[m], h0);
+        h1 = mma<BF>(k1, ks.qhi[m], h1);
+        l0 = mma<BF>(k0, ks.qlo[m], l0);
+        l1 = mma<BF>(k1, ks.qlo[m], l1);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        part[i] = fmaf(i < 4 ? l0[i & 3] : l1[i & 3], kInvLoScale, i < 4 ? h0[i & 3] : h1[i & 3]) + ks.zq_u;
+    }
 #pragma unroll
     for (int cs = 0; cs < NCK; ++cs) {
+      if constexpr (KSEQ) continue;
       float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int m = 0; m < 4; ++m) {                // two independent accumulation chains
@@ -403,11 +486,17 @@ __device__ __forceinline__ void append_one_values(const DecodeArgs& a, int bh, i
   blk[dw] = w;
 }
 
-template <int BK, int BV, int R, int NW, bool BF, int NCK, int NCV>
+// KSEQ: channel-wise keys (the caller passes the flushed part of the sequence: seq_len is a multiple of 64, nothing
+// is appended); a wavefront then walks whole 64-token blocks (pairs of steps), rebuilding its query operands per block.
+template <int BK, int BV, int R, int NW, bool BF, int NCK, int NCV, bool KSEQ = false>
 __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(const DecodeArgs a) {
   constexpr int kSetGroups = 16 / R;             // groups per column set
   constexpr bool RAW = BK == 16;
-  constexpr int kStages = ring_stages<BK, BV, NCK, NCV>();
+  static_assert(!KSEQ || (!RAW && NCK == 1), "channel-wise keys: quantized, one key column per head");
+  constexpr int kRing = ring_stages<BK, BV, NCK, NCV>();
+  constexpr int kStages = KSEQ ? 2 : kRing;      // blocks are two steps: an even ring keeps the phase (and the second
+                                                 // query operand needs the registers of a deeper ring)
+  constexpr int SPB = KSEQ ? 2 : 1;              // steps a wavefront takes in a row
   constexpr float kUnit = RAW ? 1.0f : kCodeUnit, kInvUnit = RAW ? 1.0f : kInvCodeUnit;
   __shared__ float sm_o[NW][R][kHeadDim];
   __shared__ float sm_m[NW][R], sm_l[NW][R];
@@ -440,15 +529,17 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   L.kc_off = L.c * (16 * BK) + L.j * (4 * BK);
   L.vc_off = lane * 16;
   {
-    const int nk = 8 * g.ng_k, nv = 8 * g.ng_v;
+    // channel-wise keys: 512 bytes of scale/zero per 64-token block (32 lanes), fetched with both steps of the block
+    const int nk = KSEQ ? 32 : 8 * g.ng_k, nv = 8 * g.ng_v;
     const bool is_k = lane < nk;
     L.meta_lane = !RAW && lane < nk + nv;
     L.meta_base = is_k ? (const uint8_t*)cache.k_meta + (int64_t)bh * g.km_stream
                        : (const uint8_t*)cache.v_meta + (int64_t)bh * g.vm_stream;
-    L.meta_mul = 128 * (is_k ? g.ng_k : g.ng_v);
+    L.meta_mul = is_k ? (KSEQ ? 256 : 128 * g.ng_k) : 128 * g.ng_v;
     L.meta_off = 16 * (is_k ? lane : lane - nk);
+    L.meta_step_mask = (KSEQ && is_k) ? ~1u : ~0u;
     L.km_rd = (L.gk * 16 + 4 * L.j) * 4;                       // key bytes come first in the LDS copy
-    L.vm_rd = 128 * g.ng_k + (L.gv * 16 + 4 * L.j) * 4;
+    L.vm_rd = 16 * nk + (L.gv * 16 + 4 * L.j) * 4;
     L.meta_lds = &sm_meta[wave][0];
   }
 
@@ -456,15 +547,15 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   const int n_steps = (seq_len + 31) >> 5;
   const int step_begin = split * steps_per_split;
   const int step_end = min(step_begin + steps_per_split, n_steps);
-  const int first = step_begin + wave;
-  auto step_of = [&](int i) { return first + NW * i; };
-  const int n_my = first < step_end ? (step_end - first + NW - 1) / NW : 0;
+  const int first = step_begin + SPB * wave;
+  auto step_of = [&](int i) { return KSEQ ? first + 2 * NW * (i >> 1) + (i & 1) : first + NW * i; };
+  const int n_my = first < step_end ? SPB * ((step_end - first + SPB * NW - 1) / (SPB * NW)) : 0;
   const bool ragged = (seq_len & 31) != 0;
   const bool own_tail = ragged && n_my > 0 && step_of(n_my - 1) == n_steps - 1;
   const int n_full = own_tail ? n_my - 1 : n_my;   // complete steps of this wavefront
   // fused decode step: the owner of the last step writes the new token first.  When the ring's first loads cannot
   // reach that step they are started before the (short) quantization, otherwise after it.
-  const bool do_append = !RAW && a.k_new != nullptr && split == n_splits - 1;
+  const bool do_append = !RAW && !KSEQ && a.k_new != nullptr && split == n_splits - 1;
   const bool early = !do_append || n_my > kStages;
   // register ring of kStages steps
   StepRegs<BK, BV> buf[kStages];
@@ -576,20 +667,33 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
 
   // ---- main loop, unrolled over the ring: compute a step, then refill its registers with the step kStages
   // ahead, so that kStages-1 steps of loads are always in flight behind the one being computed.
+  typename std::conditional<KSEQ, KSeqState, NoKSeq>::type ks;
+  const uint16_t* qrow = &sm_q[h][0];
+  // one complete step out of ring slot k (for channel-wise keys an even slot starts a block)
+  auto full_step = [&](int k, int i) {
+    if constexpr (KSEQ) {
+      if (k & 1) compute_step<BK, BV, R, BF, NCK, NCV, false, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
+      else compute_step<BK, BV, R, BF, NCK, NCV, false, true>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks, qrow, q_is_bf16, act_k);
+    } else {
+      compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
+    }
+  };
   int it = 0;
   for (; it + kStages <= n_full; it += kStages) {
 #pragma unroll
     for (int k = 0; k < kStages; ++k) {
-      compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(it + k), seq_len);
+      full_step(k, it + k);
       if (it + k + kStages < n_full) load_step<BK, BV>(buf[k], L, step_of(it + k + kStages));
     }
   }
 #pragma unroll
   for (int k = 0; k < kStages - 1; ++k)         // the last few complete steps are already in the ring
-    if (it + k < n_full) compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(it + k), seq_len);
-  if (own_tail) {                                 // ragged last step of the sequence: masked
-    load_step<BK, BV>(buf[0], L, n_steps - 1);
-    compute_step<BK, BV, R, BF, NCK, NCV, true>(buf[0], qb, qsum_u, kappa, st, L, n_steps - 1, seq_len);
+    if (it + k < n_full) full_step(k, it + k);
+  if constexpr (!KSEQ) {
+    if (own_tail) {                               // ragged last step of the sequence: masked
+      load_step<BK, BV>(buf[0], L, n_steps - 1);
+      compute_step<BK, BV, R, BF, NCK, NCV, true>(buf[0], qb, qsum_u, kappa, st, L, n_steps - 1, seq_len, ks);
+    }
   }
 
   // ---- wavefront totals: l and zacc over register classes and the 4 lane groups j; then this lane's output rows
@@ -633,7 +737,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       ll = fmaf(f, sm_l[w][hh], ll);
     }
     const int64_t hq = (int64_t)b * q_heads + hk * R + hh;
-    if (n_splits == 1) {
+    if (a.rec_splits == 1) {
       const float val = o / ll;
       if (out_dtype == KVQ_F32) ((float*)out)[hq * kHeadDim + d] = val;
       else if (out_dtype == KVQ_F16) ((_Float16*)out)[hq * kHeadDim + d] = (_Float16)val;
@@ -642,7 +746,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
         ((uint16_t*)out)[hq * kHeadDim + d] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
       }
     } else {
-      float* rec = ws + (hq * n_splits + split) * kRec;
+      float* rec = ws + (hq * a.rec_splits + a.rec_base + split) * kRec;
       rec[d] = o;
       if (d == 0) { rec[kHeadDim] = M; rec[kHeadDim + 1] = ll; }
     }
@@ -672,39 +776,48 @@ __global__ __launch_bounds__(128) void merge_kernel(const float* __restrict__ ws
   }
 }
 
-template <int BK, int BV, int R, bool BF, int NCK, int NCV>
+template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool KSEQ>
 void launch_nw(const DecodeArgs& a, const DecodePlan& plan, dim3 grid, hipStream_t stream) {
-  if (plan.waves_per_wg == 8) hipLaunchKernelGGL((decode_kernel<BK, BV, R, 8, BF, NCK, NCV>), grid, dim3(512), 0, stream, a);
-  else hipLaunchKernelGGL((decode_kernel<BK, BV, R, 4, BF, NCK, NCV>), grid, dim3(256), 0, stream, a);
+  if (plan.waves_per_wg == 8)
+    hipLaunchKernelGGL((decode_kernel<BK, BV, R, 8, BF, NCK, NCV, KSEQ>), grid, dim3(512), 0, stream, a);
+  else
+    hipLaunchKernelGGL((decode_kernel<BK, BV, R, 4, BF, NCK, NCV, KSEQ>), grid, dim3(256), 0, stream, a);
 }
 
-template <int BK, int BV, int R, bool BF = false>
+template <int BK, int BV, int R, bool BF = false, bool KSEQ = false>
 hipError_t launch_one(const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream) {
   dim3 grid(plan.n_splits, a.g.batch * a.g.kv_heads);
   // two column sets only where 8 heads meet four groups (32 columns); quantized caches only
   const bool k2 = R * a.g.ng_k > 16, v2 = R * a.g.ng_v > 16;
   if constexpr (R == 8 && BK != 16) {
-    if (k2 && v2) launch_nw<BK, BV, R, BF, 2, 2>(a, plan, grid, stream);
-    else if (k2) launch_nw<BK, BV, R, BF, 2, 1>(a, plan, grid, stream);
-    else if (v2) launch_nw<BK, BV, R, BF, 1, 2>(a, plan, grid, stream);
-    else launch_nw<BK, BV, R, BF, 1, 1>(a, plan, grid, stream);
+    if constexpr (KSEQ) {
+      if (k2) return hipErrorInvalidValue;
+      if (v2) launch_nw<BK, BV, R, BF, 1, 2, true>(a, plan, grid, stream);
+      else launch_nw<BK, BV, R, BF, 1, 1, true>(a, plan, grid, stream);
+    } else {
+      if (k2 && v2) launch_nw<BK, BV, R, BF, 2, 2, false>(a, plan, grid, stream);
+      else if (k2) launch_nw<BK, BV, R, BF, 2, 1, false>(a, plan, grid, stream);
+      else if (v2) launch_nw<BK, BV, R, BF, 1, 2, false>(a, plan, grid, stream);
+      else launch_nw<BK, BV, R, BF, 1, 1, false>(a, plan, grid, stream);
+    }
   } else {
     if (k2 || v2) return hipErrorInvalidValue;
-    launch_nw<BK, BV, R, BF, 1, 1>(a, plan, grid, stream);
+    launch_nw<BK, BV, R, BF, 1, 1, KSEQ>(a, plan, grid, stream);
   }
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || plan.n_splits == 1) return e;
-  hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128), 0, stream, a.ws, a.out, a.out_dtype, plan.n_splits);
+  // the records of this launch are all there is: merge them here (otherwise the caller adds launches and merges)
+  if (e != hipSuccess || a.rec_splits == 1 || a.rec_splits != plan.n_splits) return e;
+  hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128), 0, stream, a.ws, a.out, a.out_dtype, a.rec_splits);
   return hipGetLastError();
 }
 
-template <int BK, int BV, bool BF = false>
+template <int BK, int BV, bool BF = false, bool KSEQ = false>
 hipError_t launch_r(int R, const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream) {
   switch (R) {
-    case 1: return launch_one<BK, BV, 1, BF>(a, plan, stream);
-    case 2: return launch_one<BK, BV, 2, BF>(a, plan, stream);
-    case 4: return launch_one<BK, BV, 4, BF>(a, plan, stream);
-    case 8: return launch_one<BK, BV, 8, BF>(a, plan, stream);
+    case 1: return launch_one<BK, BV, 1, BF, KSEQ>(a, plan, stream);
+    case 2: return launch_one<BK, BV, 2, BF, KSEQ>(a, plan, stream);
+    case 4: return launch_one<BK, BV, 4, BF, KSEQ>(a, plan, stream);
+    case 8: return launch_one<BK, BV, 8, BF, KSEQ>(a, plan, stream);
   }
   return hipErrorInvalidValue;
 }
@@ -721,6 +834,13 @@ hipError_t KVQ_CAT(launch_decode_inst_, KVQ_INST_BK, KVQ_INST_BV)(int R, const D
 #if KVQ_INST_BK == 16
   return a.g.raw_dtype == KVQ_BF16 ? launch_r<16, 16, true>(R, a, plan, stream) : launch_r<16, 16, false>(R, a, plan, stream);
 #else
+  if (a.g.axis_k == KVQ_AXIS_SEQ) {
+#if KVQ_INST_BK <= 4 && KVQ_INST_BV <= 4
+    return launch_r<KVQ_INST_BK, KVQ_INST_BV, false, true>(R, a, plan, stream);
+#else
+    return hipErrorInvalidValue;                   // channel-wise keys: kernels for 2- and 4-bit codes only
+#endif
+  }
   return launch_r<KVQ_INST_BK, KVQ_INST_BV>(R, a, plan, stream);
 #endif
 }
@@ -738,14 +858,26 @@ bool decode_supported(const Geom& g, int32_t q_heads) {
   if (R != 1 && R != 2 && R != 4 && R != 8) return false;
   if ((g.bits_k == 16) != (g.bits_v == 16)) return false;      // one tensor unquantized, the other not: no kernel
   if (R * g.ng_k > 32 || R * g.ng_v > 32) return false;        // head x group columns: at most two 16-wide tiles
+  if (g.axis_k == KVQ_AXIS_SEQ && (g.bits_k > 4 || g.bits_v > 4)) return false;   // channel-wise keys: 2- and 4-bit codes
   return true;
+}
+
+// Partial records per (batch, query head) of one decode call.
+int32_t decode_records(const Geom& g, int32_t seq_len, const DecodePlan& plan) {
+  if (g.axis_k == KVQ_AXIS_SEQ) return plan.n_splits + (seq_len % kSeqGroup ? 1 : 0);
+  return plan.n_splits;
 }
 
 DecodePlan plan_decode(const Geom& g, int32_t seq_len) {
   // Fill the chip exactly once: 256 CUs x 4 SIMDs x KVQ_WAVES_PER_SIMD wavefronts, spread over the (b,h) streams.
   // Workgroups of 8 wavefronts halve the number of sequence splits (none at all from 256 streams up, where the
   // merge kernel and the workspace traffic disappear); each wavefront should still own a few steps.
-  const int n_steps = (seq_len + 31) / 32;
+  // Channel-wise keys: the plan covers the flushed tokens only (whole 64-token blocks, two steps each, taken in pairs);
+  // n_splits = 0 when nothing is flushed yet.  The residual tail is a launch of its own.
+  const bool seq = g.axis_k == KVQ_AXIS_SEQ;
+  const int unit = seq ? 2 : 1;
+  const int n_steps = seq ? seq_len / kSeqGroup * 2 : (seq_len + 31) / 32;
+  if (n_steps == 0) return DecodePlan{0, 0, 4};
   const int streams = g.batch * g.kv_heads;
   const int total_waves = 256 * 4 * KVQ_WAVES_PER_SIMD;
   int waves_per_stream = (total_waves + streams - 1) / streams;
@@ -756,7 +888,7 @@ DecodePlan plan_decode(const Geom& g, int32_t seq_len) {
   int splits = waves_per_stream / nw;
   if (splits < 1) splits = 1;
   int sps = (n_steps + splits - 1) / splits;
-  sps = (sps + nw - 1) / nw * nw;
+  sps = (sps + nw * unit - 1) / (nw * unit) * (nw * unit);
   splits = (n_steps + sps - 1) / sps;
   return DecodePlan{splits, sps, nw};
 }
@@ -771,6 +903,38 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
   a.seq_len = seq_len; a.softmax_scale = softmax_scale;
   a.ws = workspace; a.out = out; a.out_dtype = out_dtype;
   a.n_splits = plan.n_splits; a.steps_per_split = plan.steps_per_split;
+  a.rec_splits = plan.n_splits; a.rec_base = 0;
+  if (g.axis_k == KVQ_AXIS_SEQ) {
+    // channel-wise keys: flushed blocks from the codes (plan), the newest tokens from the residual buffer by the
+    // unquantized kernel, all partial records merged at the end
+    const int32_t n_flushed = seq_len / kSeqGroup * kSeqGroup, tail = seq_len - n_flushed;
+    const int32_t records = decode_records(g, seq_len, plan);
+    hipError_t e = hipSuccess;
+    if (n_flushed) {
+      a.seq_len = n_flushed; a.rec_splits = records; a.rec_base = 0;
+#define KVQ_CASE(BK_, BV_) \
+      if (g.bits_k == BK_ && g.bits_v == BV_) e = KVQ_CAT(launch_decode_inst_, BK_, BV_)(R, a, plan, stream);
+      KVQ_FOR_EACH_PAIR(KVQ_CASE)
+#undef KVQ_CASE
+      if (e != hipSuccess) return e;
+    }
+    if (tail) {
+      DecodeArgs t = a;
+      t.g.axis_k = KVQ_AXIS_HEAD_DIM; t.g.bits_k = t.g.bits_v = 16; t.g.g_k = t.g.g_v = kHeadDim; t.g.ng_k = t.g.ng_v = 1;
+      t.g.t_cap = kSeqGroup;
+      t.g.kc_stream = t.g.vc_stream = (int64_t)kSeqGroup * kHeadDim * 2; t.g.km_stream = t.g.vm_stream = 0;
+      t.cache.k_codes = c.k_resid; t.cache.v_codes = c.v_resid; t.cache.k_meta = t.cache.v_meta = nullptr;
+      t.seq_len = tail; t.n_splits = 1; t.steps_per_split = 4;
+      t.rec_splits = records; t.rec_base = records - 1;
+      e = launch_decode_inst_16_16(R, t, DecodePlan{1, 4, 4}, stream);
+      if (e != hipSuccess) return e;
+    }
+    if (records > 1 && !(n_flushed && !tail)) {     // (a launch that wrote all the records has merged them itself)
+      hipLaunchKernelGGL(merge_kernel, dim3(g.batch * q_heads), dim3(128), 0, stream, workspace, out, out_dtype, records);
+      e = hipGetLastError();
+    }
+    return e;
+  }
   if (app) {
     a.k_new = (const uint16_t*)app->k_new; a.v_new = (const uint16_t*)app->v_new;
     a.in_bf16 = app->in_dtype == KVQ_BF16 ? 1 : 0; a.nsb = app->stride_b; a.nsh = app->stride_h;

@@ -57,6 +57,7 @@ struct AppendOne {
   const void* k_new; const void* v_new; int in_dtype; int64_t stride_b, stride_h;
 };
 DecodePlan plan_decode(const Geom& g, int32_t seq_len);
+int32_t decode_records(const Geom& g, int32_t seq_len, const DecodePlan& plan);
 
 // Everything the decode kernels need, passed by value.
 struct DecodeArgs {
@@ -66,6 +67,9 @@ struct DecodeArgs {
   int32_t seq_len; float softmax_scale;
   float* ws; void* out; int out_dtype;
   int32_t n_splits, steps_per_split;
+  // partial records: a workgroup writes record rec_base + split of rec_splits per (batch, query head); rec_splits == 1
+  // means there is nothing to merge and the result goes straight to `out`
+  int32_t rec_splits, rec_base;
   // fused decode step: the token at position seq_len-1 is quantized from k_new/v_new ([B][H_kv][D], element strides
   // nsb, nsh) by the workgroup that owns the last step, before it is read.  k_new == nullptr: plain attention.
   const uint16_t* k_new; const uint16_t* v_new; int in_bf16; int64_t nsb, nsh;

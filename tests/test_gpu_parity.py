@@ -609,3 +609,73 @@ def test_channelwise_append_is_byte_identical(kvq, oracle, bk, bv, gv, dtype):
     kd, vd = oracle.seq_dequantize(Lo, planes, T, 0, nq)
     assert np.array_equal(ko.cpu().numpy().view(np.uint32), kd.view(np.uint32))
     assert np.array_equal(vo.cpu().numpy().view(np.uint32), vd.view(np.uint32))
+
+
+@pytest.mark.parametrize("R", [1, 2, 4, 8])
+@pytest.mark.parametrize("bk,bv,gv", [(4, 2, 64), (2, 4, 128), (4, 4, 32), (2, 2, 64)])
+def test_channelwise_attention(kvq, oracle, R, bk, bv, gv):
+    """Attention over channel-wise keys: flushed blocks from the codes, the newest tokens from the residual buffer.
+    Lengths: residual only, whole blocks only, both; the cache is rebuilt for every length (the buffer's content
+    depends on it)."""
+    B, H = 2, 2
+    for T in (333, 320, 130, 64, 63, 1):
+        K, V, q = synth.make_kvq(140 + R, B, H, H * R, T, dtype=torch.bfloat16)
+        Lg, Lo = _seq_layouts(kvq, oracle, B, H, 333, bk, bv, gv, raw=1)
+        cache, planes = _seq_fill_both(kvq, oracle, Lg, Lo, K, V, [(0, T)])
+        out = _decode(kvq, Lg, cache, q, T)
+        ref = oracle.seq_decode_attention(Lo, planes, synth.to_numpy_bits(q), T, 1 / math.sqrt(128), bf16=True)
+        err = _rel_err(out.cpu().numpy(), ref)
+        assert err < TOL, (T, err)
+
+
+def test_channelwise_attention_fp16_long_multi_split(kvq, oracle):
+    B, H, R, T = 1, 2, 4, 4200                       # several sequence splits of the flushed part plus a 40-token tail
+    K, V, q = synth.make_kvq(91, B, H, H * R, T, dtype=torch.float16)
+    Lg, Lo = _seq_layouts(kvq, oracle, B, H, T, 4, 2, 64)
+    cache, planes = _seq_fill_both(kvq, oracle, Lg, Lo, K, V, [(0, 4000), (4000, T)])
+    _assert_seq_planes_equal(cache, planes)
+    for seq_len in (T,):
+        out = _decode(kvq, Lg, cache, q, seq_len)
+        ref = oracle.seq_decode_attention(Lo, planes, q.numpy(), seq_len, 1 / math.sqrt(128))
+        assert _rel_err(out.cpu().numpy(), ref) < TOL
+
+
+def test_channelwise_decode_steps_cross_a_flush(kvq, oracle):
+    """kvq_decode_step on a cache with channel-wise keys: positions 60..69 include the token that completes block 0
+    (position 63: the buffer is flushed) and the first tokens of the next block."""
+    B, H, R, T0, nstep = 2, 2, 4, 60, 10
+    T = T0 + nstep
+    K, V, _ = synth.make_kvq(33, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _seq_layouts(kvq, oracle, B, H, T, 4, 2, 64, raw=1)
+    cache, planes = _seq_fill_both(kvq, oracle, Lg, Lo, K[:, :, :T0], V[:, :, :T0], [(0, T0)])
+    Kd, Vd = K.cuda(), V.cuda()
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    for i in range(nstep):
+        pos = T0 + i
+        _, _, q = synth.make_kvq(500 + i, B, H, H * R, 1, dtype=torch.bfloat16)
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), 1 / math.sqrt(128), out, ws)
+        torch.cuda.synchronize()
+        oracle.seq_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, pos:pos + 1])),
+                          np.ascontiguousarray(synth.to_numpy_bits(V[:, :, pos:pos + 1])), pos, bf16=True)
+        _assert_seq_planes_equal(cache, planes)
+        ref = oracle.seq_decode_attention(Lo, planes, synth.to_numpy_bits(q), pos + 1, 1 / math.sqrt(128), bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
+
+
+def test_channelwise_unsupported_combinations(kvq):
+    L8 = kvq.Layout(1, 2, 128, 128, 8, 8, 64, 64, axis_k=kvq.AXIS_SEQ)
+    cache = kvq.Cache(L8, fill=0)
+    q = torch.zeros(1, 2, 128, dtype=torch.float16, device="cuda")
+    out = torch.empty(1, 2, 128, dtype=torch.float32, device="cuda")
+    with pytest.raises(kvq.KvqError) as e:
+        kvq.decode_attention(L8, cache, q, 100, 0.1, out, None)
+    assert e.value.status == kvq.ERR_UNSUPPORTED                      # 8-bit codes: append only
+    L4 = kvq.Layout(1, 2, 128, 128, 4, 2, 64, 64, axis_k=kvq.AXIS_SEQ, raw_dtype=kvq.KVQ_BF16)
+    with pytest.raises(kvq.KvqError) as e:
+        kvq.decode_attention(L4, kvq.Cache(L4, fill=0), q, 100, 0.1, out, None)
+    assert e.value.status == kvq.ERR_UNSUPPORTED                      # query type differs from the buffer's
+    k = torch.zeros(1, 2, 4, 128, dtype=torch.float16, device="cuda")
+    with pytest.raises(kvq.KvqError) as e:
+        kvq.quantize_append(L4, kvq.Cache(L4, fill=0), k, k, 0)
+    assert e.value.status == kvq.ERR_INVALID_ARG                      # the buffer keeps patterns of raw_dtype
