@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the K4V2 decode hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--workload llama70b|llama8b|sweep|groups|rotation|stream131k]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--workload llama70b|llama8b|sweep|groups|rotation|channelwise|stream131k]
 
 One step = one pass of the whole hot path over one layer's batch: quantize-and-append the new
 token's K/V (B x H_kv rows) into the packed cache, then single-token decode attention over the
@@ -186,6 +186,45 @@ def run_rotation(args, kvq, synth) -> int:
     return 0
 
 
+def run_channelwise(args, kvq, synth) -> int:
+    """Token-wise against channel-wise key groups (Sec. 4 "Downstream Task Accuracy": the per-row and the per-column
+    back-end, the latter with its 64-token full-precision residual buffer) on the 8B layer shape, 64-element groups:
+    K2V2, K2V4, K4V2, K4V4 at context 32768 + 40 (so that the residual buffer holds 40 tokens).  Per line: key MSE over
+    the flushed tokens, attention-output error against exact attention on the original tensors (CPU oracle, batch
+    element 0), bulk append rate and decode time."""
+    import numpy as np
+    from oracle import ref
+    B, Hq, Hkv, D, G = 8, 32, 8, 128, 64
+    Tq, T = 32768, 32768 + 40
+    scale = 1.0 / math.sqrt(D)
+    K, V, q = synth.make_kvq(7, B, Hkv, Hq, T, D, dtype=torch.bfloat16, device="cuda")
+    want = ref.attention_dense(K[:1].float().cpu().numpy(), V[:1].float().cpu().numpy(),
+                               synth.to_numpy_bits(q[:1]), scale, bf16=True).astype(np.float64)
+    sums = torch.empty(B, Hkv, 2, dtype=torch.float64, device="cuda")
+    for bk, bv in ((2, 2), (2, 4), (4, 2), (4, 4)):
+        for axis in (kvq.AXIS_HEAD_DIM, kvq.AXIS_SEQ):
+            L = kvq.Layout(B, Hkv, T, D, bk, bv, G, G, axis_k=axis, raw_dtype=kvq.KVQ_BF16)
+            row_bytes = 16 * bk + 16 * bv + 2 * 4 * (D // G)
+            kv_bytes = B * Hkv * T * row_bytes
+            copies = 5
+            caches = [kvq.Cache(L, device="cuda") for _ in range(copies)]
+            ms_q = _time_loop(lambda i: kvq.quantize_append(L, caches[i % copies], K, V, 0), 50, 10)
+            ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, Hq, T)), dtype=torch.uint8, device="cuda")
+            out = torch.empty(B, Hq, D, dtype=torch.float32, device="cuda")
+            ms = _time_loop(lambda i: kvq.decode_attention(L, caches[i % copies], q, T, scale, out, ws), 1000, 200)
+            kvq.reconstruction_error(L, caches[0], K[:, :, :Tq], None, 0, sums)
+            mse_k = float(sums.sum(dim=(0, 1)).cpu().numpy()[0] / (B * Hkv * Tq * D))
+            got = out[:1].cpu().numpy().astype(np.float64)
+            rel_l2 = float((np.linalg.norm(got - want, axis=-1) / np.linalg.norm(want, axis=-1)).mean())
+            print(json.dumps({"workload": f"8B layer, B=8, T={T}, K{bk}V{bv} G=64, keys {'channel-wise + residual buffer' if axis else 'token-wise'}",
+                              "alloc": f"K{bk}V{bv}", "axis_k": int(axis), "mse_k_flushed": mse_k,
+                              "err_vs_exact_attention_mean_rel_l2": round(rel_l2, 5),
+                              "append_tok_s_bulk": round(B * T / ms_q * 1e3, 1),
+                              "decode_us": round(ms * 1e3, 2), "decode_GB_s": round(kv_bytes / ms / 1e6, 1)}), flush=True)
+            del caches
+    return 0
+
+
 def run_stream(args, kvq, synth) -> int:
     """Long-context streaming on the 8B layer shape at batch 1: fill 131072 tokens with kvq_quantize_append in chunks of
     2048, then 256 fused decode steps on the growing cache.  Quantize tok/s and decode GB/s are reported separately."""
@@ -243,7 +282,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=4000)
     ap.add_argument("--warmup", type=int, default=400)
     ap.add_argument("--layers", type=int, default=40, help="resident layer caches taken in turn")
-    ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS) + ["sweep", "groups", "rotation", "stream131k"],
+    ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS) + ["sweep", "groups", "rotation", "channelwise", "stream131k"],
                     help="llama70b (default, the headline line) / llama8b: one JSON line; sweep: bit-allocation sweep on the 8B "
                          "layer (one line per allocation and context); stream131k: chunked fill + growing-cache decode at 131072")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -268,6 +307,8 @@ def main() -> int:
         return run_groups(args, kvq, synth)
     if args.workload == "rotation":
         return run_rotation(args, kvq, synth)
+    if args.workload == "channelwise":
+        return run_channelwise(args, kvq, synth)
     if args.workload == "stream131k":
         return run_stream(args, kvq, synth)
     B, Hq, Hkv, T, desc = WORKLOADS[args.workload]
