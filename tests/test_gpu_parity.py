@@ -374,19 +374,19 @@ def _check_sampled_streams(kvq, oracle, B, Hq, Hkv, T, seed, sigma_k, samples, f
 
 
 def test_full_size_70b_layer_sampled_streams(kvq, oracle):
-    """BASELINE configs[3] as bench.py launches it (B=32, 64 query / 8 KV heads, context 32768): one 8-wavefront
+    """The 70B-layer workload as bench.py launches it (B=32, 64 query / 8 KV heads, context 32768): one 8-wavefront
     workgroup per stream, no sequence split, fused append."""
     _check_sampled_streams(kvq, oracle, 32, 64, 8, 32768, 1000, 3.3, [(0, 0), (13, 5), (31, 7)])
 
 
 def test_full_size_8b_layer_sampled_streams(kvq, oracle):
-    """BASELINE configs[1] (B=8, 32 query / 8 KV heads, context 8192): 4 sequence splits and the merge kernel."""
+    """The 8B-layer workload (B=8, 32 query / 8 KV heads, context 8192): 4 sequence splits and the merge kernel."""
     _check_sampled_streams(kvq, oracle, 8, 32, 8, 8192, 1, 4.0, [(0, 0), (3, 6), (7, 7)])
     _check_sampled_streams(kvq, oracle, 8, 32, 8, 8192, 1, 4.0, [(5, 2)], fused=False)
 
 
 def test_long_context_batch_1_sampled_streams(kvq, oracle):
-    """BASELINE configs[4] shape (B=1, context 131072, 32 splits per stream), ragged length on purpose."""
+    """The long-context workload (B=1, context 131072, 32 splits per stream), ragged length on purpose."""
     _check_sampled_streams(kvq, oracle, 1, 32, 8, 131072 - 5, 4, 4.0, [(0, 3)])
 
 
