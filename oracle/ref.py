@@ -8,7 +8,7 @@ from __future__ import annotations
 import ctypes as C
 import os
 import subprocess
-from dataclasses import dataclass
+from dataclasses import dataclass, replace
 
 import numpy as np
 
@@ -249,3 +249,26 @@ def seq_decode_attention(L: Layout, planes, q: np.ndarray, seq_len: int, softmax
     if rc:
         raise ValueError(f"ref_seq_decode_attention rc={rc}")
     return out
+
+
+# ---- sequences of different lengths in one batch: every batch element is a batch of one on its own slice of the planes
+
+def _element(L: Layout, planes, b: int):
+    return replace(L, batch=1), [p.reshape(L.batch, -1)[b] if p.size else p for p in planes]
+
+
+def decode_attention_varlen(L: Layout, planes, q: np.ndarray, seq_lens, softmax_scale: float, bf16: bool = False) -> np.ndarray:
+    """Batch element b attends over its first seq_lens[b] tokens (the uniform definition, element by element)."""
+    q = np.ascontiguousarray(q)
+    out = np.zeros((L.batch, q.shape[1], L.head_dim), dtype=np.float32)
+    for b in range(L.batch):
+        Lb, pb = _element(L, planes, b)
+        out[b] = decode_attention(Lb, pb, q[b:b + 1], int(seq_lens[b]), softmax_scale, bf16)[0]
+    return out
+
+
+def quantize_append_at(L: Layout, planes, k_new: np.ndarray, v_new: np.ndarray, pos, bf16: bool = False) -> None:
+    """One new token per batch element, stored at that element's own position pos[b]; k_new, v_new: [B, H, 1, D]."""
+    for b in range(L.batch):
+        Lb, pb = _element(L, planes, b)
+        quantize_append(Lb, pb, np.ascontiguousarray(k_new[b:b + 1]), np.ascontiguousarray(v_new[b:b + 1]), int(pos[b]), bf16)

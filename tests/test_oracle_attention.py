@@ -165,3 +165,38 @@ def test_eight_bits_approach_full_precision(oracle):
     assert e88 < 1e-2 and e88 < e44 < e22
     Ko, Vo, qo = synth.make_kvq(9, 4, 2, 8, 256, 128, dtype=torch.bfloat16)      # the heavy-outlier workload
     assert _alloc_error(oracle, Ko, Vo, qo, 8, 8, 64, True) < _alloc_error(oracle, Ko, Vo, qo, 4, 4, 64, True)
+
+
+def test_per_sequence_lengths_are_independent_batches_of_one(oracle):
+    """Ragged batch: element b of the result is what a cache holding ONLY that sequence's tokens gives (built from
+    scratch with batch 1), equal lengths reproduce the uniform call bit for bit, and per-element appends land where a
+    batch-1 append would put them."""
+    rng = np.random.default_rng(77)
+    B, Hk, Hq, T, D = 3, 2, 4, 90, 128
+    K = (rng.standard_normal((B, Hk, T, D)) * 2).astype(np.float16)
+    V = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    scale = 1 / np.sqrt(D)
+    L = oracle.Layout(B, Hk, T, D, 4, 2, 64, 64)
+    planes = oracle.new_planes(L)
+    oracle.quantize_append(L, planes, K, V, 0)
+    lens = [90, 1, 47]
+    got = oracle.decode_attention_varlen(L, planes, q, lens, scale)
+    for b, n in enumerate(lens):
+        L1 = oracle.Layout(1, Hk, T, D, 4, 2, 64, 64)
+        p1 = oracle.new_planes(L1)
+        oracle.quantize_append(L1, p1, np.ascontiguousarray(K[b:b + 1, :, :n]), np.ascontiguousarray(V[b:b + 1, :, :n]), 0)
+        want = oracle.decode_attention(L1, p1, q[b:b + 1], n, scale)
+        assert np.array_equal(got[b], want[0])
+    same = oracle.decode_attention_varlen(L, planes, q, [60, 60, 60], scale)
+    assert np.array_equal(same, oracle.decode_attention(L, planes, q, 60, scale))
+    # appends at per-element positions
+    pa = oracle.new_planes(L, fill=0x11)
+    pos = [5, 0, 33]
+    oracle.quantize_append_at(L, pa, np.ascontiguousarray(K[:, :, 7:8]), np.ascontiguousarray(V[:, :, 7:8]), pos)
+    for b, t in enumerate(pos):
+        L1 = oracle.Layout(1, Hk, T, D, 4, 2, 64, 64)
+        p1 = oracle.new_planes(L1, fill=0x11)
+        oracle.quantize_append(L1, p1, np.ascontiguousarray(K[b:b + 1, :, 7:8]), np.ascontiguousarray(V[b:b + 1, :, 7:8]), t)
+        for a, c in zip(pa, p1):
+            assert np.array_equal(a.reshape(B, -1)[b], c)
