@@ -170,6 +170,24 @@ kvq_status kvq_reconstruction_error(const kvq_layout* layout, const kvq_cache* c
                                     const void* v_ref, kvq_dtype ref_dtype, int64_t stride_b, int64_t stride_h,
                                     int64_t stride_t, int32_t t0, int32_t t1, double* sums, void* stream);
 
+/* The two calls above for sequences of different lengths in one batch (what a serving batch looks like):
+ *   seq_lens  device, int32[B]: batch element b attends over tokens [0, seq_lens[b]); values are clamped to
+ *             [1, max_seq_len] on the device.
+ *   pos       device, int32[B]: the new token of batch element b goes to position pos[b] (clamped to [0, max_pos]) and
+ *             its query attends over [0, pos[b]].
+ *   max_seq_len / max_pos  host: an upper bound of the device values; the launch and the workspace
+ *             (kvq_decode_workspace_bytes(layout, q_heads, max_seq_len), max_seq_len = max_pos + 1) are planned for it.
+ * Everything else as in the uniform calls.  Not available with channel-wise keys (KVQ_ERR_UNSUPPORTED). */
+kvq_status kvq_decode_attention_varlen(const kvq_layout* layout, const kvq_cache* cache, const void* q,
+                                       kvq_dtype q_dtype, int32_t q_heads, const int32_t* seq_lens,
+                                       int32_t max_seq_len, float softmax_scale, void* out, kvq_dtype out_dtype,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+kvq_status kvq_decode_step_varlen(const kvq_layout* layout, const kvq_cache* cache, const void* k_new,
+                                  const void* v_new, kvq_dtype in_dtype, int64_t stride_b, int64_t stride_h,
+                                  const int32_t* pos, int32_t max_pos, const void* q, kvq_dtype q_dtype,
+                                  int32_t q_heads, float softmax_scale, void* out, kvq_dtype out_dtype, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
 /* Reconstruct tokens [t0, t1) as x^ = code * scale + zero (App. B "Dequantization"):
  *   k_out, v_out  [B][H_kv][t1-t0][D] contiguous of out_dtype; either may be NULL to skip it.
  * KVQ_F32 output is exactly the binary32 value; 16-bit outputs round it once. */

@@ -139,16 +139,19 @@ kvq_status decode_check(const kvq_layout* layout, const kvq_cache* cache, const 
   return KVQ_OK;
 }
 
+// seq_lens (device, may be null) + lens_offset: per-sequence lengths inside the bound seq_len.
 kvq_status decode_common(const kvq_layout* layout, const kvq_cache* cache, const void* q, kvq_dtype q_dtype, int32_t q_heads,
                          int32_t seq_len, float softmax_scale, void* out, kvq_dtype out_dtype, void* workspace,
-                         size_t workspace_bytes, const kvq::AppendOne* app, void* stream) {
+                         size_t workspace_bytes, const kvq::AppendOne* app, void* stream,
+                         const int32_t* seq_lens = nullptr, int32_t lens_offset = 0) {
   kvq_status st = decode_check(layout, cache, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype, workspace,
                                workspace_bytes, app != nullptr);
   if (st != KVQ_OK) return st;
+  if (seq_lens && layout->axis_k == KVQ_AXIS_SEQ) return KVQ_ERR_UNSUPPORTED;
   const kvq::Geom g = kvq::make_geom(*layout);
   const kvq::DecodePlan plan = kvq::plan_decode(g, seq_len);
   hipError_t e = kvq::launch_decode_attention(g, *cache, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype,
-                                              (float*)workspace, plan, app, (hipStream_t)stream);
+                                              (float*)workspace, plan, app, (hipStream_t)stream, seq_lens, lens_offset);
   return e == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
 }
 }  // namespace
@@ -184,6 +187,30 @@ kvq_status kvq_decode_step(const kvq_layout* layout, const kvq_cache* cache, con
   const kvq::AppendOne app{k_new, v_new, (int)in_dtype, stride_b, stride_h};
   return decode_common(layout, cache, q, q_dtype, q_heads, pos + 1, softmax_scale, out, out_dtype, workspace,
                        workspace_bytes, &app, stream);
+}
+
+kvq_status kvq_decode_attention_varlen(const kvq_layout* layout, const kvq_cache* cache, const void* q, kvq_dtype q_dtype,
+                                       int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len, float softmax_scale,
+                                       void* out, kvq_dtype out_dtype, void* workspace, size_t workspace_bytes,
+                                       void* stream) {
+  if (!seq_lens || (reinterpret_cast<uintptr_t>(seq_lens) & 3u)) return KVQ_ERR_INVALID_ARG;
+  return decode_common(layout, cache, q, q_dtype, q_heads, max_seq_len, softmax_scale, out, out_dtype, workspace,
+                       workspace_bytes, nullptr, stream, seq_lens, 0);
+}
+
+kvq_status kvq_decode_step_varlen(const kvq_layout* layout, const kvq_cache* cache, const void* k_new, const void* v_new,
+                                  kvq_dtype in_dtype, int64_t stride_b, int64_t stride_h, const int32_t* pos,
+                                  int32_t max_pos, const void* q, kvq_dtype q_dtype, int32_t q_heads, float softmax_scale,
+                                  void* out, kvq_dtype out_dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!layout) return KVQ_ERR_INVALID_ARG;
+  if (!pos || (reinterpret_cast<uintptr_t>(pos) & 3u) || max_pos < 0) return KVQ_ERR_INVALID_ARG;
+  if (max_pos >= layout->max_seq) return KVQ_ERR_CAPACITY;
+  if (!k_new || !v_new || (in_dtype != KVQ_F16 && in_dtype != KVQ_BF16)) return KVQ_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || stride_b % 8 || stride_h % 8) return KVQ_ERR_INVALID_ARG;
+  if (layout->axis_k == KVQ_AXIS_SEQ) return KVQ_ERR_UNSUPPORTED;
+  const kvq::AppendOne app{k_new, v_new, (int)in_dtype, stride_b, stride_h};
+  return decode_common(layout, cache, q, q_dtype, q_heads, max_pos + 1, softmax_scale, out, out_dtype, workspace,
+                       workspace_bytes, &app, stream, pos, 1);
 }
 
 kvq_status kvq_dequantize(const kvq_layout* layout, const kvq_cache* cache, int32_t t0, int32_t t1, void* k_out,

@@ -419,12 +419,11 @@ constexpr int kRec = kHeadDim + 4;
 // row, the next 16 the value row (8 channels per lane).  Same arithmetic and bytes as the bulk quantize-append kernel.
 // Value codes go to `vstage` (128 bytes of LDS); after a barrier append_one_values() puts them into the block.
 template <int BK, int BV>
-__device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, int hk, int tid, uint8_t* vstage) {
+__device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, int hk, int tid, uint8_t* vstage, int64_t t) {
   const Geom& g = a.g;
   if (tid >= 32) return;
   const bool is_v = tid >= 16;
   const int lane16 = tid & 15, d0 = lane16 * 8;
-  const int64_t t = a.seq_len - 1;
   const uint16_t* src = (is_v ? a.v_new : a.k_new) + (int64_t)b * a.nsb + (int64_t)hk * a.nsh + d0;
   const u32x4 raw = *reinterpret_cast<const u32x4*>(src);
   const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
@@ -468,11 +467,10 @@ __device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, i
 // (read-modify-write; the other fields of the word belong to other tokens of the same 32-token block).  With 2-bit
 // codes channels d and d+16 share a word, so the thread of the even 16-channel tile writes both.
 template <int BV>
-__device__ __forceinline__ void append_one_values(const DecodeArgs& a, int bh, int tid, const uint8_t* vstage) {
+__device__ __forceinline__ void append_one_values(const DecodeArgs& a, int bh, int tid, const uint8_t* vstage, int64_t t) {
   if (tid >= kHeadDim) return;
   if (BV == 2 && ((tid >> 4) & 1)) return;
   const Geom& g = a.g;
-  const int64_t t = a.seq_len - 1;
   uint32_t* blk = (uint32_t*)((uint8_t*)a.cache.v_codes + (int64_t)bh * g.vc_stream) + (t >> 5) * (int64_t)(128 * BV);
   const uint32_t fmask = (1u << BV) - 1u;
   int dw, bit;
@@ -507,8 +505,8 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   const Geom& g = a.g;
   const kvq_cache& cache = a.cache;
   const uint16_t* __restrict__ q = a.q;
-  const int q_bf16 = a.q_bf16, q_heads = a.q_heads, seq_len = a.seq_len, out_dtype = a.out_dtype;
-  const int n_splits = a.n_splits, steps_per_split = a.steps_per_split;
+  const int q_bf16 = a.q_bf16, q_heads = a.q_heads, out_dtype = a.out_dtype;
+  const int steps_per_split = a.steps_per_split;
   const float softmax_scale = a.softmax_scale;
   float* __restrict__ ws = a.ws;
   void* __restrict__ out = a.out;
@@ -517,6 +515,9 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int split = blockIdx.x, bh = blockIdx.y;
   const int b = bh / g.kv_heads, hk = bh % g.kv_heads;
+  // this sequence's length: its own when the caller gave per-sequence lengths, inside what the launch was planned for
+  int seq_len = a.seq_len;
+  if (a.seq_lens) seq_len = min(max(a.seq_lens[b] + a.lens_offset, 1), a.seq_len);
 
   LaneCtx L;
   L.lane = lane; L.c = lane & 15; L.j = lane >> 4;
@@ -555,7 +556,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   const int n_full = own_tail ? n_my - 1 : n_my;   // complete steps of this wavefront
   // fused decode step: the owner of the last step writes the new token first.  When the ring's first loads cannot
   // reach that step they are started before the (short) quantization, otherwise after it.
-  const bool do_append = !RAW && !KSEQ && a.k_new != nullptr && split == n_splits - 1;
+  const bool do_append = !RAW && !KSEQ && a.k_new != nullptr && split == (n_steps - 1) / steps_per_split;
   const bool early = !do_append || n_my > kStages;
   // register ring of kStages steps
   StepRegs<BK, BV> buf[kStages];
@@ -566,9 +567,9 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   }
   if (do_append) {                                 // uniform over the workgroup
     if constexpr (!RAW) {
-      append_one<BK, BV>(a, bh, b, hk, tid, sm_vnew);
+      append_one<BK, BV>(a, bh, b, hk, tid, sm_vnew, seq_len - 1);
       __syncthreads();
-      append_one_values<BV>(a, bh, tid, sm_vnew);
+      append_one_values<BV>(a, bh, tid, sm_vnew, seq_len - 1);
     }
     __threadfence_block();                         // writer and readers share this workgroup: a workgroup-scope
                                                    // release is enough (no L2 write-back/invalidate across XCDs)
@@ -895,9 +896,11 @@ DecodePlan plan_decode(const Geom& g, int32_t seq_len) {
 
 hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void* q, int q_dtype, int32_t q_heads,
                                    int32_t seq_len, float softmax_scale, void* out, int out_dtype, float* workspace,
-                                   const DecodePlan& plan, const AppendOne* app, hipStream_t stream) {
+                                   const DecodePlan& plan, const AppendOne* app, hipStream_t stream,
+                                   const int32_t* seq_lens, int32_t lens_offset) {
   const int R = q_heads / g.kv_heads;
   DecodeArgs a{};
+  a.seq_lens = seq_lens; a.lens_offset = lens_offset;
   a.g = g; a.cache = c;
   a.q = (const uint16_t*)q; a.q_bf16 = q_dtype == KVQ_BF16 ? 1 : 0; a.q_heads = q_heads;
   a.seq_len = seq_len; a.softmax_scale = softmax_scale;

@@ -65,6 +65,9 @@ struct DecodeArgs {
   kvq_cache cache;
   const uint16_t* q; int q_bf16; int32_t q_heads;
   int32_t seq_len; float softmax_scale;
+  // per-sequence lengths: batch element b attends over seq_lens[b] + lens_offset tokens (clamped to [1, seq_len]; seq_len
+  // is then the upper bound the launch was planned for); nullptr: every sequence has seq_len tokens
+  const int32_t* seq_lens; int32_t lens_offset;
   float* ws; void* out; int out_dtype;
   int32_t n_splits, steps_per_split;
   // partial records: a workgroup writes record rec_base + split of rec_splits per (batch, query head); rec_splits == 1
@@ -91,7 +94,8 @@ hipError_t launch_reconstruction_error(const Geom& g, const kvq_cache& c, const 
 // Returns hipErrorInvalidValue if no kernel instance exists for (bits, groups, head ratio).
 hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void* q, int q_dtype, int32_t q_heads,
                                    int32_t seq_len, float softmax_scale, void* out, int out_dtype, float* workspace,
-                                   const DecodePlan& plan, const AppendOne* append, hipStream_t stream);
+                                   const DecodePlan& plan, const AppendOne* append, hipStream_t stream,
+                                   const int32_t* seq_lens = nullptr, int32_t lens_offset = 0);
 bool decode_supported(const Geom& g, int32_t q_heads);
 
 #if defined(__HIPCC__)

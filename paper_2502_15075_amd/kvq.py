@@ -57,6 +57,12 @@ def load():
         lib.kvq_decode_step.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int, C.c_int64,
                                         C.c_int64, C.c_int32, C.c_void_p, C.c_int, C.c_int32, C.c_float, C.c_void_p, C.c_int,
                                         C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.kvq_decode_attention_varlen.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_int, C.c_int32,
+                                                    C.c_void_p, C.c_int32, C.c_float, C.c_void_p, C.c_int, C.c_void_p,
+                                                    C.c_size_t, C.c_void_p]
+        lib.kvq_decode_step_varlen.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int,
+                                               C.c_int64, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p, C.c_int, C.c_int32,
+                                               C.c_float, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
         lib.kvq_dequantize.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_int32, C.c_int32, C.c_void_p,
                                        C.c_void_p, C.c_int, C.c_void_p]
         lib.kvq_reconstruction_error.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int,
@@ -64,7 +70,8 @@ def load():
         lib.kvq_status_string.argtypes = [C.c_int]
         lib.kvq_status_string.restype = C.c_char_p
         for f in ("kvq_cache_bytes", "kvq_residual_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
-                  "kvq_decode_step", "kvq_dequantize", "kvq_reconstruction_error"):
+                  "kvq_decode_step", "kvq_dequantize", "kvq_reconstruction_error", "kvq_decode_attention_varlen",
+                  "kvq_decode_step_varlen"):
             getattr(lib, f).restype = C.c_int
         _lib = lib
     return _lib
@@ -210,3 +217,36 @@ def reconstruction_error(layout: Layout, cache: Cache, k_ref, v_ref, t0: int, su
                                          ref.stride(1), ref.stride(2), t0, t0 + ref.shape[2], _p(sums), _stream_ptr())
     _check(st, "kvq_reconstruction_error")
     return sums
+
+
+def decode_attention_varlen(layout: Layout, cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,
+                            softmax_scale: float, out: torch.Tensor, workspace) -> torch.Tensor:
+    """As decode_attention with one length per batch element: seq_lens is an int32 device tensor [B], max_seq_len an
+    upper bound of its values (the workspace is sized for it)."""
+    assert q.is_contiguous() and out.is_contiguous() and q.dim() == 3 and out.shape == q.shape
+    assert seq_lens.dtype == torch.int32 and seq_lens.is_contiguous() and seq_lens.numel() == layout.batch
+    cl, cc = layout.c(), cache.c()
+    st = load().kvq_decode_attention_varlen(C.byref(cl), C.byref(cc), _p(q), _DTYPES[q.dtype], q.shape[1], _p(seq_lens),
+                                            max_seq_len, C.c_float(softmax_scale), _p(out), _DTYPES[out.dtype], _p(workspace),
+                                            0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                            _stream_ptr())
+    _check(st, "kvq_decode_attention_varlen")
+    return out
+
+
+def decode_step_varlen(layout: Layout, cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, pos: torch.Tensor,
+                       max_pos: int, q: torch.Tensor, softmax_scale: float, out: torch.Tensor, workspace) -> torch.Tensor:
+    """As decode_step with one position per batch element: pos is an int32 device tensor [B], max_pos its upper bound."""
+    if k_new.dim() == 4:
+        assert k_new.shape[2] == 1
+        k_new, v_new = k_new[:, :, 0], v_new[:, :, 0]
+    assert k_new.shape == v_new.shape and k_new.stride() == v_new.stride() and k_new.stride(2) == 1
+    assert q.is_contiguous() and out.is_contiguous() and out.shape == q.shape
+    assert pos.dtype == torch.int32 and pos.is_contiguous() and pos.numel() == layout.batch
+    cl, cc = layout.c(), cache.c()
+    st = load().kvq_decode_step_varlen(C.byref(cl), C.byref(cc), _p(k_new), _p(v_new), _DTYPES[k_new.dtype], k_new.stride(0),
+                                       k_new.stride(1), _p(pos), max_pos, _p(q), _DTYPES[q.dtype], q.shape[1],
+                                       C.c_float(softmax_scale), _p(out), _DTYPES[out.dtype], _p(workspace),
+                                       0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_ptr())
+    _check(st, "kvq_decode_step_varlen")
+    return out

@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported(kvq):
     declared = set(re.findall(r"\b(kvq_[a-z_]+)\s*\(", header))
     assert {"kvq_cache_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
             "kvq_decode_step", "kvq_dequantize", "kvq_reconstruction_error", "kvq_residual_bytes",
-            "kvq_status_string"} <= declared
+            "kvq_decode_attention_varlen", "kvq_decode_step_varlen", "kvq_status_string"} <= declared
     lib = C.CDLL(kvq.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), name
@@ -138,6 +138,17 @@ def test_call_errors_are_caught_before_any_launch(kvq):
         return lib.kvq_decode_step(C.byref(cl), C.byref(good), p(k), p(0x51000), 1, 256, 128, pos, p(0x52000), 1, 8,
                                    C.c_float(0.1), p(0x60000), 2, p(0x70000), 1 << 20, None)
     assert ds(100) == kvq.ERR_CAPACITY and ds(-1) == kvq.ERR_INVALID_ARG and ds(5, 0) == kvq.ERR_INVALID_ARG
+
+    def dv(lens, bound):
+        return lib.kvq_decode_attention_varlen(C.byref(cl), C.byref(good), p(0x50000), 1, 8, p(lens), bound, C.c_float(0.1),
+                                               p(0x60000), 2, p(0x70000), 1 << 20, None)
+    assert dv(0, 50) == kvq.ERR_INVALID_ARG and dv(0x80002, 50) == kvq.ERR_INVALID_ARG
+    assert dv(0x80000, 101) == kvq.ERR_CAPACITY and dv(0x80000, 0) == kvq.ERR_INVALID_ARG
+
+    def dsv(pos, bound):
+        return lib.kvq_decode_step_varlen(C.byref(cl), C.byref(good), p(0x50000), p(0x51000), 1, 256, 128, p(pos), bound,
+                                          p(0x52000), 1, 8, C.c_float(0.1), p(0x60000), 2, p(0x70000), 1 << 20, None)
+    assert dsv(0, 5) == kvq.ERR_INVALID_ARG and dsv(0x80000, -1) == kvq.ERR_INVALID_ARG and dsv(0x80000, 100) == kvq.ERR_CAPACITY
 
     def dq(t0, t1, ko, vo, dt):
         return lib.kvq_dequantize(C.byref(cl), C.byref(good), t0, t1, p(ko), p(vo), dt, None)

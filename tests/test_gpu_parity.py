@@ -679,3 +679,69 @@ def test_channelwise_unsupported_combinations(kvq):
     with pytest.raises(kvq.KvqError) as e:
         kvq.quantize_append(L4, kvq.Cache(L4, fill=0), k, k, 0)
     assert e.value.status == kvq.ERR_INVALID_ARG                      # the buffer keeps patterns of raw_dtype
+
+
+# --------------------------------------------------------------------------- per-sequence lengths
+
+@pytest.mark.parametrize("R,bk,bv,gk,gv", [(4, 4, 2, 64, 64), (8, 4, 2, 32, 64), (1, 2, 4, 64, 128), (8, 8, 8, 64, 64)])
+def test_attention_with_per_sequence_lengths(kvq, oracle, R, bk, bv, gk, gv):
+    """A ragged batch: every batch element attends over its own length (1, a few tokens, ragged and full steps, the
+    full capacity), planned for the longest; lengths beyond the bound are clamped to it."""
+    B, H, T = 6, 2, 2100
+    K, V, q = synth.make_kvq(150 + R, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, T)])
+    qn = synth.to_numpy_bits(q)
+    for lens, bound in (([2100, 1, 33, 1024, 777, 64], 2100), ([5, 1, 33, 64, 31, 17], 64), ([300, 300, 300, 300, 300, 300], 300),
+                        ([9999, 1, 2, 3, 4, 5], 600)):
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, bound)), dtype=torch.uint8, device="cuda")
+        out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+        kvq.decode_attention_varlen(Lg, cache, q.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"), bound,
+                                    1 / math.sqrt(128), out, ws)
+        torch.cuda.synchronize()
+        ref = oracle.decode_attention_varlen(Lo, planes, qn, [min(n, bound) for n in lens], 1 / math.sqrt(128), bf16=True)
+        err = _rel_err(out.cpu().numpy(), ref)
+        assert err < TOL, (lens, err)
+
+
+def test_decode_steps_with_per_sequence_positions(kvq, oracle):
+    """kvq_decode_step_varlen: each sequence appends its new token at its own position and attends over its own
+    context; planes stay byte-identical to the oracle's over several steps (block boundaries included)."""
+    B, H, R, T = 4, 2, 4, 700
+    K, V, _ = synth.make_kvq(160, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, 4, 2, 64, 64)
+    start = [0, 30, 63, 600]
+    cache = kvq.Cache(Lg, fill=0xA5)
+    planes = oracle.new_planes(Lo, fill=0xA5)
+    Kd, Vd = K.cuda(), V.cuda()
+    for b, n in enumerate(start):                            # prefill every sequence to its own length
+        if n == 0:
+            continue
+        Lg1 = kvq.Layout(1, H, T, 128, 4, 2, 64, 64)
+        sub = kvq.Cache.__new__(kvq.Cache)
+        sub.layout = Lg1
+        sub.planes = [None if p is None else p.view(B, -1)[b] for p in cache.planes]
+        kvq.quantize_append(Lg1, sub, Kd[b:b + 1, :, :n], Vd[b:b + 1, :, :n], 0)
+        Lo1, pb = oracle._element(Lo, planes, b)
+        oracle.quantize_append(Lo1, pb, np.ascontiguousarray(synth.to_numpy_bits(K[b:b + 1, :, :n])),
+                               np.ascontiguousarray(synth.to_numpy_bits(V[b:b + 1, :, :n])), 0, bf16=True)
+    torch.cuda.synchronize()
+    _assert_planes_equal(cache, planes)
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    for i in range(5):
+        pos = [n + i for n in start]
+        idx = torch.tensor(pos, device="cuda")
+        k1 = Kd[torch.arange(B, device="cuda"), :, idx].contiguous()          # [B, H, D]: row pos[b] of sequence b
+        v1 = Vd[torch.arange(B, device="cuda"), :, idx].contiguous()
+        _, _, q = synth.make_kvq(600 + i, B, H, H * R, 1, dtype=torch.bfloat16)
+        bound = max(pos)
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, bound + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step_varlen(Lg, cache, k1, v1, torch.tensor(pos, dtype=torch.int32, device="cuda"), bound, q.cuda(),
+                               1 / math.sqrt(128), out, ws)
+        torch.cuda.synchronize()
+        kn = np.stack([synth.to_numpy_bits(K[b, :, pos[b]:pos[b] + 1]) for b in range(B)])
+        vn = np.stack([synth.to_numpy_bits(V[b, :, pos[b]:pos[b] + 1]) for b in range(B)])
+        oracle.quantize_append_at(Lo, planes, kn, vn, pos, bf16=True)
+        _assert_planes_equal(cache, planes)
+        ref = oracle.decode_attention_varlen(Lo, planes, synth.to_numpy_bits(q), [p + 1 for p in pos], 1 / math.sqrt(128), bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
