@@ -339,7 +339,7 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
       for (int i = 0; i < 8; ++i) {
         const float d = i < 4 ? d0[i & 3] : d1[i & 3];
         float pt = d;
-        if constexpr (!RAW) pt = fmaf(d, meta_scale(kmeta[cs][i]), meta_zero(kmeta[cs][i]) * qsum_u[cs]);
+        if constexpr (!RAW) pt = fmaf(d, meta_scale(kmeta[cs][i]), fmaf(meta_zero(kmeta[cs][i]), qsum_u[cs], 0.0f));
         part[i] = cs == 0 ? pt : part[i] + pt;
       }
     }
