@@ -492,8 +492,11 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   constexpr bool RAW = BK == 16;
   static_assert(!KSEQ || (!RAW && NCK == 1), "channel-wise keys: quantized, one key column per head");
   constexpr int kRing = ring_stages<BK, BV, NCK, NCV>();
-  constexpr int kStages = KSEQ ? 2 : kRing;      // blocks are two steps: an even ring keeps the phase (and the second
-                                                 // query operand needs the registers of a deeper ring)
+#ifndef KVQ_KSEQ_STAGES
+#define KVQ_KSEQ_STAGES 2
+#endif
+  constexpr int kStages = KSEQ ? (kRing < KVQ_KSEQ_STAGES ? kRing : KVQ_KSEQ_STAGES) : kRing;   // the second query operand
+                                                 // and the rebuild need the registers of a deeper ring
   constexpr int SPB = KSEQ ? 2 : 1;              // steps a wavefront takes in a row
   constexpr float kUnit = RAW ? 1.0f : kCodeUnit, kInvUnit = RAW ? 1.0f : kInvCodeUnit;
   __shared__ float sm_o[NW][R][kHeadDim];
@@ -672,8 +675,8 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   const uint16_t* qrow = &sm_q[h][0];
   // one complete step out of ring slot k (for channel-wise keys an even slot starts a block)
   auto full_step = [&](int k, int i) {
-    if constexpr (KSEQ) {
-      if (k & 1) compute_step<BK, BV, R, BF, NCK, NCV, false, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
+    if constexpr (KSEQ) {                        // an even step of this wavefront's sequence starts a block (uniform)
+      if (i & 1) compute_step<BK, BV, R, BF, NCK, NCV, false, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
       else compute_step<BK, BV, R, BF, NCK, NCV, false, true>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks, qrow, q_is_bf16, act_k);
     } else {
       compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks);

@@ -226,7 +226,8 @@ __device__ __forceinline__ void store_key_codes(uint8_t* rowp, int lane16, const
 // Channel-wise keys (Sec. 4 "Downstream Task Accuracy": the per-column back-end with its residual buffer).
 // One workgroup = one block of kSeqGroup = 64 tokens of one (b,h) stream, restricted to the new tokens [lo, hi) in it.
 // New tokens that no later token of this call overwrites go to their residual slot as 16-bit patterns.  A block that
-// this call completes is flushed: rows below lo come back from the residual buffer, keys are quantized channel by
+// this call completes is flushed: rows below lo come back from the residual buffer (the launcher makes sure that no
+// other workgroup of the same launch writes there), keys are quantized channel by
 // channel (the group is the 64 tokens of one channel), values token-wise exactly as in quantize_append_kernel.
 template <int BK, int BV, bool BF>
 __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_new,
@@ -547,6 +548,17 @@ hipError_t launch_sak(const Geom& g, const kvq_cache& c, const void* k_new, cons
 hipError_t launch_seq_append(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype,
                              int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
   if (n_new == 0) return hipSuccess;
+  // A first block that starts inside the residual buffer reads its older rows from there, while the workgroups of the
+  // call's last 64 tokens overwrite those slots: when the call goes on beyond that block, the block gets a launch of
+  // its own and the rest follows in stream order.
+  const int32_t first_end = (pos / kSeqGroup + 1) * kSeqGroup;
+  if (pos % kSeqGroup != 0 && pos + n_new > first_end) {
+    const int32_t n1 = first_end - pos;
+    hipError_t e = launch_seq_append(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n1, stream);
+    if (e != hipSuccess) return e;
+    return launch_seq_append(g, c, (const uint16_t*)k_new + (int64_t)n1 * st, (const uint16_t*)v_new + (int64_t)n1 * st,
+                             in_dtype, sb, sh, st, first_end, n_new - n1, stream);
+  }
   switch (g.bits_k) {
     case 2: return launch_sak<2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 4: return launch_sak<4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);

@@ -745,3 +745,14 @@ def test_decode_steps_with_per_sequence_positions(kvq, oracle):
         _assert_planes_equal(cache, planes)
         ref = oracle.decode_attention_varlen(Lo, planes, synth.to_numpy_bits(q), [p + 1 for p in pos], 1 / math.sqrt(128), bf16=True)
         assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
+
+
+def test_channelwise_bulk_append_after_a_partial_block(kvq, oracle):
+    """A bulk append that starts inside a half-filled residual buffer and runs over many blocks: the first block needs
+    the buffer's older rows while the call's last 64 tokens land in the same slots (the library orders the two)."""
+    B, H, T = 4, 8, 64 * 24 + 7
+    K, V, _ = synth.make_kvq(81, B, H, H, T, dtype=torch.float16)
+    Lg, Lo = _seq_layouts(kvq, oracle, B, H, T, 4, 2, 64)
+    for first in (1, 37, 63):
+        cache, planes = _seq_fill_both(kvq, oracle, Lg, Lo, K, V, [(0, first), (first, T)])
+        _assert_seq_planes_equal(cache, planes)
