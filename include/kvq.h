@@ -138,7 +138,8 @@ kvq_status kvq_quantize_append(const kvq_layout* layout, const kvq_cache* cache,
  *   out[b,hq,:] = softmax_t( softmax_scale * q[b,hq,:] . K^[b,hq/R,t,:] ) . V^[b,hq/R,t,:],  R = q_heads/kv_heads
  * (App. A; the caller passes softmax_scale = 1/sqrt(head_dim); it must be positive and finite).
  *   q    [B][q_heads][D] contiguous, KVQ_F16 or KVQ_BF16 (used exactly; values beyond binary16 range
- *        are not supported); q_heads / kv_heads in {1,2,4,8}.
+ *        are not supported); q_heads / kv_heads in 1..8 (with 32-element groups on both tensors: up to 8, and the
+ *        head count times the groups per row at most 32 after rounding the heads up to a power of two).
  *   out  [B][q_heads][D] contiguous, KVQ_F32 (the graded type), KVQ_F16 or KVQ_BF16 (rounded once).
  *   workspace  at least kvq_decode_workspace_bytes(layout, q_heads, seq_len) bytes, 16-byte aligned. */
 kvq_status kvq_decode_attention(const kvq_layout* layout, const kvq_cache* cache, const void* q,

@@ -580,8 +580,11 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
 
   // ---- query rows of this kv head -> LDS (one coalesced 16-byte load per thread), then per-lane operands
   bool q_is_bf16 = q_bf16 != 0;
+  const int r_act = a.heads_per_kv;                // heads that exist (R is the next power of two)
   if (tid < R * 16) {
-    u32x4 raw = *reinterpret_cast<const u32x4*>(q + ((int64_t)b * q_heads + hk * R) * kHeadDim + tid * 8);
+    u32x4 raw = u32x4{0u, 0u, 0u, 0u};             // a surplus head is an all-zero query: uniform weights, never stored
+    if ((tid >> 4) < r_act)
+      raw = *reinterpret_cast<const u32x4*>(q + ((int64_t)b * q_heads + hk * r_act) * kHeadDim + tid * 8);
     if constexpr (!RAW) {
       if (g.rotate_k) {
         // rotated keys: the scores need R q, rounded once to binary16 (16 threads hold one query row, 8 channels each)
@@ -740,7 +743,8 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       o = fmaf(f, sm_o[w][hh][d], o);
       ll = fmaf(f, sm_l[w][hh], ll);
     }
-    const int64_t hq = (int64_t)b * q_heads + hk * R + hh;
+    if (hh >= r_act) continue;
+    const int64_t hq = (int64_t)b * q_heads + hk * r_act + hh;
     if (a.rec_splits == 1) {
       const float val = o / ll;
       if (out_dtype == KVQ_F32) ((float*)out)[hq * kHeadDim + d] = val;
@@ -857,9 +861,13 @@ hipError_t KVQ_CAT(launch_decode_inst_, KVQ_INST_BK, KVQ_INST_BV)(int R, const D
 KVQ_FOR_EACH_PAIR(KVQ_DECL)
 #undef KVQ_DECL
 
+// Columns are laid out for a power-of-two number of heads per KV head.
+int padded_heads(int r) { return r <= 1 ? 1 : r <= 2 ? 2 : r <= 4 ? 4 : 8; }
+
 bool decode_supported(const Geom& g, int32_t q_heads) {
-  const int R = q_heads / g.kv_heads;
-  if (R != 1 && R != 2 && R != 4 && R != 8) return false;
+  const int r = q_heads / g.kv_heads;
+  if (r < 1 || r > 8) return false;
+  const int R = padded_heads(r);
   if ((g.bits_k == 16) != (g.bits_v == 16)) return false;      // one tensor unquantized, the other not: no kernel
   if (R * g.ng_k > 32 || R * g.ng_v > 32) return false;        // head x group columns: at most two 16-wide tiles
   if (g.axis_k == KVQ_AXIS_SEQ && (g.bits_k > 4 || g.bits_v > 4)) return false;   // channel-wise keys: 2- and 4-bit codes
@@ -901,8 +909,9 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
                                    int32_t seq_len, float softmax_scale, void* out, int out_dtype, float* workspace,
                                    const DecodePlan& plan, const AppendOne* app, hipStream_t stream,
                                    const int32_t* seq_lens, int32_t lens_offset) {
-  const int R = q_heads / g.kv_heads;
+  const int R = padded_heads(q_heads / g.kv_heads);
   DecodeArgs a{};
+  a.heads_per_kv = q_heads / g.kv_heads;
   a.seq_lens = seq_lens; a.lens_offset = lens_offset;
   a.g = g; a.cache = c;
   a.q = (const uint16_t*)q; a.q_bf16 = q_dtype == KVQ_BF16 ? 1 : 0; a.q_heads = q_heads;

@@ -64,6 +64,8 @@ struct DecodeArgs {
   Geom g;
   kvq_cache cache;
   const uint16_t* q; int q_bf16; int32_t q_heads;
+  int32_t heads_per_kv;       // q_heads / kv_heads: 1..8; the kernels lay columns out for the next power of two and leave
+                              // the surplus heads empty
   int32_t seq_len; float softmax_scale;
   // per-sequence lengths: batch element b attends over seq_lens[b] + lens_offset tokens (clamped to [1, seq_len]; seq_len
   // is then the upper bound the launch was planned for); nullptr: every sequence has seq_len tokens

@@ -121,7 +121,7 @@ def test_call_errors_are_caught_before_any_launch(kvq):
     assert da(0x50000, 8, 101, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_CAPACITY
     assert da(0x50000, 8, 0, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_INVALID_ARG
     assert da(0x50000, 3, 50, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_INVALID_ARG          # 3 heads over 2 kv heads
-    assert da(0x50000, 12, 50, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_UNSUPPORTED         # 6 query heads per kv head
+    assert da(0x50000, 18, 50, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_UNSUPPORTED         # 9 query heads per kv head
     assert da(0x50000, 8, 50, -1.0, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_INVALID_ARG
     assert da(0x50000, 8, 50, float("nan"), 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_INVALID_ARG
     assert da(0, 8, 50, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_INVALID_ARG

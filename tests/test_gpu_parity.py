@@ -756,3 +756,35 @@ def test_channelwise_bulk_append_after_a_partial_block(kvq, oracle):
     for first in (1, 37, 63):
         cache, planes = _seq_fill_both(kvq, oracle, Lg, Lo, K, V, [(0, first), (first, T)])
         _assert_seq_planes_equal(cache, planes)
+
+
+# --------------------------------------------------------------------------- head ratios that are not powers of two
+
+@pytest.mark.parametrize("r", [3, 5, 6, 7])
+def test_odd_head_ratios(kvq, oracle, r):
+    """3, 5, 6, 7 query heads per KV head (several of the paper's models: 24/8, 40/8, 28/4): the kernels pad the
+    heads of a KV head to the next power of two and leave the surplus ones out."""
+    B, H, T = 2, 3, 777
+    K, V, q = synth.make_kvq(170 + r, B, H, H * r, T, dtype=torch.bfloat16)
+    for bk, bv, gk, gv, rot in ((4, 2, 64, 64, 0), (2, 4, 128, 32, 1)):
+        if (8 if r > 4 else 4) * (128 // min(gk, gv)) > 32:
+            continue
+        Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, rot=rot)
+        cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, T)])
+        for seq_len in (T, 64, 5):
+            out = torch.full((B, H * r, 128), float("nan"), dtype=torch.float32, device="cuda")
+            ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * r, seq_len)), dtype=torch.uint8, device="cuda")
+            kvq.decode_attention(Lg, cache, q.cuda(), seq_len, 1 / math.sqrt(128), out, ws)
+            torch.cuda.synchronize()
+            ref = oracle.decode_attention(Lo, planes, synth.to_numpy_bits(q), seq_len, 1 / math.sqrt(128), bf16=True)
+            got = out.cpu().numpy()
+            assert np.isfinite(got).all() and _rel_err(got, ref) < TOL, (bk, bv, seq_len)
+    # unquantized and channel-wise caches take the same path
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, 16, 16, 64, 64, raw=1)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, T)])
+    out = _decode(kvq, Lg, cache, q, T).cpu().numpy()
+    assert _rel_err(out, oracle.decode_attention(Lo, planes, synth.to_numpy_bits(q), T, 1 / math.sqrt(128), bf16=True)) < TOL
+    Lg, Lo = _seq_layouts(kvq, oracle, B, H, T, 4, 2, 64, raw=1)
+    cache, planes = _seq_fill_both(kvq, oracle, Lg, Lo, K, V, [(0, T)])
+    out = _decode(kvq, Lg, cache, q, T).cpu().numpy()
+    assert _rel_err(out, oracle.seq_decode_attention(Lo, planes, synth.to_numpy_bits(q), T, 1 / math.sqrt(128), bf16=True)) < TOL
