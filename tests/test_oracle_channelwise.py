@@ -184,3 +184,30 @@ def test_token_wise_entry_points_refuse_channel_wise_layouts(oracle):
         oracle.quantize_append(L, oracle.new_planes(L), x, x, 0)
     with pytest.raises(ValueError):
         oracle.seq_append(oracle.Layout(1, 1, 64, 128, 16, 2, 64, 64, axis_k=1), oracle.new_seq_planes(L), x, x, 0)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4, 8])
+def test_group_quantizer_equals_the_numpy_statement_bit_for_bit(oracle, bits):
+    """The oracle's one-group routine (a C loop) against the whole-array numpy statement of the same arithmetic
+    (binary32, one rounding per operation) on groups built to hit ties, constant groups, tiny and huge ranges."""
+    rng = np.random.default_rng(bits)
+    groups = []
+    for n in (32, 64, 128):
+        for _ in range(60):
+            scale = 2.0 ** rng.integers(-12, 10)
+            x = rng.standard_normal(n) * scale
+            kind = rng.integers(0, 5)
+            if kind == 0:
+                x = np.round(x / scale * 4) / 4 * scale                # dyadic grid: exact ties
+            elif kind == 1:
+                x[:] = x[0]                                            # constant group
+            elif kind == 2:
+                x[rng.integers(0, n)] *= 50                            # one outlier
+            elif kind == 3:
+                x = np.abs(x)                                          # minimum near zero, -0 never
+            groups.append(x.astype(np.float16).astype(np.float32))
+    for x in groups:
+        codes, S, Z = oracle.quantize_group(x, bits)
+        c2, s2, z2 = _quantize_columns_numpy(x[:, None], bits)
+        assert S == int(s2[0]) and Z == int(z2[0])
+        assert np.array_equal(codes, c2[:, 0])
