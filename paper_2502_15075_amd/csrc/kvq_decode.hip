@@ -124,11 +124,11 @@ template <int BV> __device__ __forceinline__ u32x4 unpack_v(const uint32_t* w, i
 #endif
 
 // Ring depth per instantiation: a step costs 2 b_K + 2 b_V + 4 registers per lane (and the scheduler wants room to
-// start a refill before the old contents are dead); deeper rings for the narrow formats, one step for unquantized.
+// start a refill before the old contents are dead); deeper rings for the narrow formats, two steps for the wide ones.
 template <int BK, int BV, int NCK = 1, int NCV = 1>
 constexpr int ring_stages() {
   constexpr int regs = 2 * BK + 2 * BV + 4;
-  constexpr int base = regs <= 16 ? KVQ_STAGES : regs <= 20 ? 3 : regs <= 40 ? 2 : 1;
+  constexpr int base = regs <= 16 ? KVQ_STAGES : regs <= 20 ? 3 : 2;
   constexpr int less = (NCK == 2 ? 2 : 0) + (NCV == 2 ? 1 : 0);   // a second column set costs registers (query operand,
   return base - less >= 1 ? base - less : 1;                      // scale/zero entries, weights)
 }
