@@ -90,6 +90,9 @@ typedef struct {
   int32_t rotate_k;         /* 1: key rows are stored as codes of R k (needs bits_k < 16) */
   uint32_t signs_k[4];      /* bit d of the 128-bit little-endian string set: s_d = -1 (D <= 128) */
   int32_t axis_k;           /* 0: key groups along head_dim (token-wise); 1: along tokens (channel-wise) */
+  int32_t rotate_v;         /* 1: value rows are stored as codes of R_v v (needs bits_v < 16); the attention output is
+                               taken back with R_v^T.  The paper's rotation study covers none / keys / values / both. */
+  uint32_t signs_v[4];
 } ref_layout;
 
 /* ------------------------------------------------------------------ number formats */
@@ -286,6 +289,7 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
   if (pos < 0 || n_new < 0 || (int64_t)pos + n_new > L->max_seq) return -3;
   if (D % 64 || D > 1024) return -1;
   if (L->rotate_k && (L->bits_k == 16 || D > 128 || (D & (D - 1)))) return -1;
+  if (L->rotate_v && (L->bits_v == 16 || D > 128 || (D & (D - 1)))) return -1;
   if (L->axis_k != 0) return -1;                            /* channel-wise keys: ref_seq_append */
   uint64_t pb[4];
   ref_plane_bytes(L, pb);
@@ -318,9 +322,9 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
           continue;
         }
         for (int d = 0; d < D; ++d) row[d] = load_elem(src, in_dtype, base + d);
-        if (!which && L->rotate_k) {                        /* keys only: quantize R k instead of k */
+        if (which ? L->rotate_v : L->rotate_k) {            /* quantize R x instead of x */
           memcpy(plain, row, sizeof(float) * (size_t)D);
-          ref_rotate(plain, D, L->signs_k, row);
+          ref_rotate(plain, D, which ? L->signs_v : L->signs_k, row);
         }
         for (int g = 0; g < D / G; ++g) {
           uint16_t S, Z;
@@ -387,13 +391,17 @@ int ref_dequantize_stored(const ref_layout* L, const uint8_t* k_codes, const uin
 int ref_dequantize(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
                    const uint8_t* v_meta, int32_t t0, int32_t t1, float* k_out, float* v_out) {
   int rc = ref_dequantize_stored(L, k_codes, k_meta, v_codes, v_meta, t0, t1, k_out, v_out);
-  if (rc || !L->rotate_k || !k_out) return rc;
+  if (rc) return rc;
   int D = L->head_dim;
   int64_t rows = (int64_t)L->batch * L->kv_heads * (t1 - t0);
   float* tmp = (float*)malloc(sizeof(float) * (size_t)D);
-  for (int64_t r = 0; r < rows; ++r) {
-    ref_unrotate(k_out + r * D, D, L->signs_k, tmp);
-    memcpy(k_out + r * D, tmp, sizeof(float) * (size_t)D);
+  for (int which = 0; which < 2; ++which) {
+    float* out = which ? v_out : k_out;
+    if (!out || !(which ? L->rotate_v : L->rotate_k)) continue;
+    for (int64_t r = 0; r < rows; ++r) {
+      ref_unrotate(out + r * D, D, which ? L->signs_v : L->signs_k, tmp);
+      memcpy(out + r * D, tmp, sizeof(float) * (size_t)D);
+    }
   }
   free(tmp);
   return 0;
@@ -439,7 +447,8 @@ int ref_attention_dense(const float* K, const float* V, int32_t batch, int32_t k
 
 /* Decode attention over the packed cache = reconstruct tokens [0, seq_len) as stored, then the
  * dense definition above (with rotate_k: of the rotated query against the rotated keys, which is
- * the same bilinear form because R is orthogonal).  out: [B][H_q][D] binary32. */
+ * the same bilinear form because R is orthogonal; rotated values are reconstructed in the input
+ * basis first, so the output is in the input basis too).  out: [B][H_q][D] binary32. */
 int ref_decode_attention(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
                          const uint8_t* v_meta, const void* q, int q_dtype, int32_t q_heads, int32_t seq_len,
                          float softmax_scale, float* out) {
@@ -448,7 +457,9 @@ int ref_decode_attention(const ref_layout* L, const uint8_t* k_codes, const uint
   float* Kd = (float*)malloc(sizeof(float) * (size_t)n);
   float* Vd = (float*)malloc(sizeof(float) * (size_t)n);
   if (!Kd || !Vd) { free(Kd); free(Vd); return -2; }
-  int rc = ref_dequantize_stored(L, k_codes, k_meta, v_codes, v_meta, 0, seq_len, Kd, Vd);
+  /* keys as stored (rotated keys meet the rotated query); values in the input basis (R_v^T of the stored rows) */
+  int rc = ref_dequantize_stored(L, k_codes, k_meta, v_codes, v_meta, 0, seq_len, Kd, NULL);
+  if (!rc) rc = ref_dequantize(L, k_codes, k_meta, v_codes, v_meta, 0, seq_len, NULL, Vd);
   if (!rc && L->rotate_k) {
     /* scores against rotated keys need the rotated query: q' = binary16(R q), row by row */
     int D = L->head_dim;
@@ -481,7 +492,7 @@ int ref_resid_bytes(const ref_layout* L, uint64_t out[2]) {
 
 static int seq_layout_ok(const ref_layout* L) {
   int G = L->group_k, D = L->head_dim;
-  if (L->axis_k != 1 || L->rotate_k) return 0;
+  if (L->axis_k != 1 || L->rotate_k || L->rotate_v) return 0;
   if (G != 32 && G != 64 && G != 128) return 0;
   if (D % 64 || D > 1024 || D % L->group_v) return 0;
   if ((L->bits_k != 2 && L->bits_k != 4 && L->bits_k != 8) || (L->bits_v != 2 && L->bits_v != 4 && L->bits_v != 8)) return 0;

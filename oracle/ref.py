@@ -30,7 +30,7 @@ def build(force: bool = False) -> str:
 
 class _Layout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "kv_heads", "max_seq", "head_dim", "bits_k", "bits_v",
-                                          "group_k", "group_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4), ("axis_k", C.c_int32)]
+                                          "group_k", "group_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4), ("axis_k", C.c_int32), ("rotate_v", C.c_int32), ("signs_v", C.c_uint32 * 4)]
 
 
 @dataclass(frozen=True)
@@ -47,11 +47,13 @@ class Layout:
     rotate_k: int = 0
     signs_k: tuple = (0, 0, 0, 0)      # 128 sign bits, little-endian: bit d set means s_d = -1
     axis_k: int = 0                    # 1: channel-wise key groups (group_k tokens) + residual buffer
+    rotate_v: int = 0
+    signs_v: tuple = (0, 0, 0, 0)
 
     def c(self) -> _Layout:
         return _Layout(self.batch, self.kv_heads, self.max_seq, self.head_dim, self.bits_k, self.bits_v,
                        self.group_k, self.group_v, self.raw_dtype, self.rotate_k, (C.c_uint32 * 4)(*self.signs_k),
-                       self.axis_k)
+                       self.axis_k, self.rotate_v, (C.c_uint32 * 4)(*self.signs_v))
 
 
 _lib = None

@@ -165,3 +165,77 @@ def test_rotation_lowers_key_error_and_attention_error(oracle):
                     float((np.linalg.norm(out - exact, axis=-1) / np.linalg.norm(exact, axis=-1)).mean()))
     assert res[1][0] < 0.5 * res[0][0]
     assert res[1][1] < res[0][1]
+
+
+SIGNS_V = (0x243F6A88, 0x85A308D3, 0x13198A2E, 0x03707344)
+
+
+def test_value_rotation_format_and_inverse(oracle):
+    """rotate_v: the value planes are the plain planes of the rows R_v v (numpy butterflies), the key planes do not
+    move, and dequantize hands back R_v^T of the stored reconstruction."""
+    B, H, T = 1, 2, 70
+    K, V, _ = synth.make_kvq(14, B, H, H, T, dtype=torch.float16)
+    Kn, Vn = K.numpy(), V.numpy()
+    s = _sign_vector(SIGNS_V).astype(np.float32)
+    c = np.float32(1.0 / math.sqrt(128.0))
+    Vrot = np.stack([_fwht_f32(s * r) * c for r in Vn.astype(np.float32).reshape(-1, 128)]).reshape(Vn.shape)
+    for bk, bv, gk, gv in ((4, 2, 64, 64), (2, 4, 32, 128)):
+        Lr = oracle.Layout(B, H, T, 128, bk, bv, gk, gv, rotate_v=1, signs_v=SIGNS_V)
+        Lp = oracle.Layout(B, H, T, 128, bk, bv, gk, gv)
+        pr, pp, p0 = oracle.new_planes(Lr), oracle.new_planes(Lp), oracle.new_planes(Lp)
+        oracle.quantize_append(Lr, pr, Kn, Vn, 0)
+        oracle.quantize_append(Lp, pp, np.ascontiguousarray(Kn.astype(np.float32)), np.ascontiguousarray(Vrot), 0)
+        oracle.quantize_append(Lp, p0, Kn, Vn, 0)
+        for a, b in zip(pr, pp):
+            assert np.array_equal(a, b)
+        assert np.array_equal(pr[0], p0[0]) and np.array_equal(pr[1], p0[1]) and not np.array_equal(pr[2], p0[2])
+        _, vs = oracle.dequantize(Lr, pr, 0, T, stored=True)
+        _, vu = oracle.dequantize(Lr, pr, 0, T)
+        want = np.stack([(_fwht_f32(r) * c) * s for r in vs.reshape(-1, 128)]).reshape(vs.shape)
+        assert np.array_equal(vu, want)
+
+
+def test_attention_with_both_rotations_is_the_same_function(oracle):
+    """out = R_v^T (softmax(q' K'^T) V') with q' = R_k q: with 8-bit codes it stays close to exact attention on the
+    original tensors, and it equals the matrix form evaluated here with scipy's Hadamard matrix in binary64."""
+    B, Hk, Hq, T = 1, 2, 4, 96
+    K, V, q = synth.make_kvq(15, B, Hk, Hq, T, dtype=torch.float16)
+    scale = 1 / math.sqrt(128)
+    L = oracle.Layout(B, Hk, T, 128, 8, 8, 32, 32, rotate_k=1, signs_k=SIGNS, rotate_v=1, signs_v=SIGNS_V)
+    planes = oracle.new_planes(L)
+    oracle.quantize_append(L, planes, K.numpy(), V.numpy(), 0)
+    got = oracle.decode_attention(L, planes, q.numpy(), T, scale).astype(np.float64)
+    exact = oracle.attention_dense(K.float().numpy(), V.float().numpy(), q.numpy(), scale)
+    assert np.abs(got - exact).max() / np.abs(exact).max() < 0.1
+    Ks, Vs = oracle.dequantize(L, planes, 0, T, stored=True)
+    Hm = scipy.linalg.hadamard(128).astype(np.float64)
+    sk, sv = _sign_vector(SIGNS), _sign_vector(SIGNS_V)
+    qr = np.stack([oracle.rotate(r, SIGNS) for r in q.numpy().astype(np.float32).reshape(-1, 128)]).astype(np.float16)
+    out_rot = oracle.attention_dense(Ks, Vs, qr.reshape(B, Hq, 128), scale).astype(np.float64)
+    want = (out_rot @ Hm) / math.sqrt(128) * sv                         # R_v^T y = diag(s_v) H y / sqrt(n)
+    assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
+
+
+def test_rotating_values_does_not_help(oracle):
+    """Sec. 5.3: the gains come from the keys; value rotation alone is unnecessary.  On values without outlier
+    channels the rotated 2-bit value cache has the same reconstruction error (a rotation keeps an isotropic
+    distribution isotropic), so the attention error of value-only rotation stays at the unrotated level while
+    key-only rotation lowers it."""
+    B, H, T = 8, 8, 128
+    scale = 1 / math.sqrt(128)
+    K, V, q = synth.make_kvq(16, B, H, H, T, dtype=torch.float16)
+    Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
+    exact = oracle.attention_dense(Kn.astype(np.float32), Vn.astype(np.float32), qn, scale).astype(np.float64)
+    err, mse_v = {}, {}
+    for name, rk, rv in (("none", 0, 0), ("key", 1, 0), ("value", 0, 1), ("both", 1, 1)):
+        L = oracle.Layout(B, H, T, 128, 4, 2, 64, 64, rotate_k=rk, signs_k=SIGNS, rotate_v=rv, signs_v=SIGNS_V)
+        planes = oracle.new_planes(L)
+        oracle.quantize_append(L, planes, Kn, Vn, 0)
+        _, Vh = oracle.dequantize(L, planes, 0, T)
+        mse_v[name] = oracle.mse(Vn.astype(np.float32), Vh)
+        out = oracle.decode_attention(L, planes, qn, T, scale).astype(np.float64)
+        err[name] = float((np.linalg.norm(out - exact, axis=-1) / np.linalg.norm(exact, axis=-1)).mean())
+    assert 0.9 < mse_v["value"] / mse_v["none"] < 1.1
+    assert err["key"] < err["none"] and err["both"] < err["none"]
+    assert err["value"] > 0.9 * err["none"]
+    assert err["both"] > 0.9 * err["key"]
