@@ -34,6 +34,9 @@
  * addition and one binary32 subtraction (lower index minus higher index), then one multiplication by
  * binary32(1/sqrt(128)).  R k goes to the quantizer in binary32; R q is rounded once to binary16.
  * kvq_dequantize returns keys in the input basis (R^T of the stored reconstruction: butterflies, scale, signs).
+ * rotate_v = 1 does the same to value rows with R_v built from signs_v (the paper's study compares no rotation,
+ * keys, values, both, and finds that values gain nothing): the attention kernels accumulate in the rotated basis and
+ * apply R_v^T to the normalized output (binary32 butterflies) before it is stored.
  *
  * Channel-wise keys (axis_k = KVQ_AXIS_SEQ; Sec. 4 "Downstream Task Accuracy": the per-column back-end with its
  * 64-token full-precision residual buffer): a key group is 64 consecutive tokens of one channel (group_k must be
@@ -103,6 +106,8 @@ typedef struct {
   int32_t raw_dtype;
   int32_t rotate_k;     /* 0 / 1: key-only randomized Hadamard rotation (see "Rotation" above); needs bits_k < 16 */
   uint32_t signs_k[4];  /* the 128 signs of the rotation: bit d%32 of word d/32 set means s_d = -1 */
+  int32_t rotate_v;     /* 0 / 1: the same rotation for value rows, with its own signs; needs bits_v < 16 */
+  uint32_t signs_v[4];
 } kvq_layout;
 
 /* Caller-owned device buffers of at least the sizes kvq_cache_bytes reports (16-byte aligned).

@@ -430,13 +430,14 @@ __device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, i
   float x[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), a.in_bf16);
-  if (g.rotate_k) {                                // keys only; both 16-lane rows run the butterflies, the value row
+  if (g.rotate_k | g.rotate_v) {                   // both 16-lane rows run the butterflies; a row that is not rotated
     float xr[8];                                   // keeps its own numbers
 #pragma unroll
     for (int e = 0; e < 8; ++e) xr[e] = x[e];
-    rotate8(xr, lane16, rot_sign_bits(g.signs_k, lane16));
+    rotate8(xr, lane16, is_v ? rot_sign_bits(g.signs_v, lane16) : rot_sign_bits(g.signs_k, lane16));
+    const bool take = is_v ? g.rotate_v != 0 : g.rotate_k != 0;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = is_v ? x[e] : xr[e];
+    for (int e = 0; e < 8; ++e) x[e] = take ? xr[e] : x[e];
   }
   uint32_t codes[8];
   uint16_t S, Z;
@@ -482,6 +483,23 @@ __device__ __forceinline__ void append_one_values(const DecodeArgs& a, int bh, i
     w = (w & ~(fmask << bit2)) | ((uint32_t)vstage[tid + 16] << bit2);
   }
   blk[dw] = w;
+}
+
+// Final output of rotated values: the normalized row sits in the rotated basis (LDS, 128 floats); 16 threads take it
+// back with R_v^T (8 channels each) and store it in the output type.
+__device__ __forceinline__ void store_unrotated_row(const float* row, int lane16, const uint32_t signs[4], void* out,
+                                                    int out_dtype, int64_t hq) {
+  float x[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x[e] = row[8 * lane16 + e];
+  unrotate8(x, lane16, rot_sign_bits(signs, lane16));
+  const int64_t o = hq * kHeadDim + 8 * lane16;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    if (out_dtype == KVQ_F32) ((float*)out)[o + e] = x[e];
+    else if (out_dtype == KVQ_F16) ((_Float16*)out)[o + e] = (_Float16)x[e];
+    else ((uint16_t*)out)[o + e] = f32_to_bf16_bits(x[e]);
+  }
 }
 
 // KSEQ: channel-wise keys (the caller passes the flushed part of the sequence: seq_len is a multiple of 64, nothing
@@ -747,6 +765,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
     const int64_t hq = (int64_t)b * q_heads + hk * r_act + hh;
     if (a.rec_splits == 1) {
       const float val = o / ll;
+      if (g.rotate_v) { sm_o[0][hh][d] = val; continue; }      // (only this thread touches element (hh, d))
       if (out_dtype == KVQ_F32) ((float*)out)[hq * kHeadDim + d] = val;
       else if (out_dtype == KVQ_F16) ((_Float16*)out)[hq * kHeadDim + d] = (_Float16)val;
       else {
@@ -759,11 +778,19 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       if (d == 0) { rec[kHeadDim] = M; rec[kHeadDim + 1] = ll; }
     }
   }
+  if (a.rec_splits == 1 && g.rotate_v) {             // uniform over the workgroup
+    __syncthreads();
+    if (tid < R * 16 && (tid >> 4) < r_act)
+      store_unrotated_row(&sm_o[0][tid >> 4][0], tid & 15, g.signs_v, out, out_dtype,
+                          (int64_t)b * q_heads + hk * r_act + (tid >> 4));
+  }
 }
 
-// Combine the split records of one (b, hq): log-sum-exp merge, then normalize.
+// Combine the split records of one (b, hq): log-sum-exp merge, then normalize (and take rotated values back).
+struct RotV { int32_t on; uint32_t signs[4]; };
 __global__ __launch_bounds__(128) void merge_kernel(const float* __restrict__ ws, void* __restrict__ out, int out_dtype,
-                                                    int32_t n_splits) {
+                                                    int32_t n_splits, RotV rot) {
+  __shared__ float row[kHeadDim];
   const int64_t hq = blockIdx.x;
   const int d = threadIdx.x;
   const float* rec = ws + hq * n_splits * kRec;
@@ -776,12 +803,23 @@ __global__ __launch_bounds__(128) void merge_kernel(const float* __restrict__ ws
     l = fmaf(f, rec[s * kRec + kHeadDim + 1], l);
   }
   const float val = o / l;
+  if (rot.on) {                                      // uniform
+    row[d] = val;
+    __syncthreads();
+    if (d < 16) store_unrotated_row(row, d, rot.signs, out, out_dtype, hq);
+    return;
+  }
   if (out_dtype == KVQ_F32) ((float*)out)[hq * kHeadDim + d] = val;
   else if (out_dtype == KVQ_F16) ((_Float16*)out)[hq * kHeadDim + d] = (_Float16)val;
   else {
     uint32_t u = __float_as_uint(val);
     ((uint16_t*)out)[hq * kHeadDim + d] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
   }
+}
+
+inline RotV rot_v_of(const Geom& g) {
+  RotV r{g.rotate_v, {g.signs_v[0], g.signs_v[1], g.signs_v[2], g.signs_v[3]}};
+  return r;
 }
 
 template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool KSEQ>
@@ -815,7 +853,8 @@ hipError_t launch_one(const DecodeArgs& a, const DecodePlan& plan, hipStream_t s
   hipError_t e = hipGetLastError();
   // the records of this launch are all there is: merge them here (otherwise the caller adds launches and merges)
   if (e != hipSuccess || a.rec_splits == 1 || a.rec_splits != plan.n_splits) return e;
-  hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128), 0, stream, a.ws, a.out, a.out_dtype, a.rec_splits);
+  hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128), 0, stream, a.ws, a.out, a.out_dtype, a.rec_splits,
+                     rot_v_of(a.g));
   return hipGetLastError();
 }
 
@@ -945,7 +984,8 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
       if (e != hipSuccess) return e;
     }
     if (records > 1 && !(n_flushed && !tail)) {     // (a launch that wrote all the records has merged them itself)
-      hipLaunchKernelGGL(merge_kernel, dim3(g.batch * q_heads), dim3(128), 0, stream, workspace, out, out_dtype, records);
+      hipLaunchKernelGGL(merge_kernel, dim3(g.batch * q_heads), dim3(128), 0, stream, workspace, out, out_dtype, records,
+                         rot_v_of(g));
       e = hipGetLastError();
     }
     return e;

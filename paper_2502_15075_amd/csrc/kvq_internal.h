@@ -20,6 +20,8 @@ struct Geom {
                                     // then g_k = 128 and ng_k = 1 (one matrix column per head on the key side)
   int32_t rotate_k;                 // key rows are stored as codes of R k (randomized Hadamard rotation)
   uint32_t signs_k[4];              // bit d set: s_d = -1
+  int32_t rotate_v;                 // value rows are stored as codes of R_v v; outputs are taken back with R_v^T
+  uint32_t signs_v[4];
   int64_t kc_stream, km_stream, vc_stream, vm_stream;   // bytes per (b,h) stream in each plane
 };
 
@@ -37,6 +39,8 @@ inline Geom make_geom(const kvq_layout& L) {
   g.raw_dtype = L.raw_dtype;
   g.rotate_k = L.rotate_k;
   for (int i = 0; i < 4; ++i) g.signs_k[i] = L.rotate_k ? L.signs_k[i] : 0u;
+  g.rotate_v = L.rotate_v;
+  for (int i = 0; i < 4; ++i) g.signs_v[i] = L.rotate_v ? L.signs_v[i] : 0u;
   g.kc_stream = (int64_t)g.t_cap * (kHeadDim * L.bits_k / 8);
   g.vc_stream = (int64_t)g.t_cap * (kHeadDim * L.bits_v / 8);
   g.km_stream = L.bits_k == 16 ? 0 : L.axis_k == KVQ_AXIS_SEQ ? (int64_t)(g.t_cap / kSeqGroup) * kHeadDim * 4

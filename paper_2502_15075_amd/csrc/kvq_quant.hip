@@ -166,6 +166,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         float x[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
+        if (g.rotate_v) rotate8(x, lane16, rot_sign_bits(g.signs_v, lane16));
         uint16_t S, Z;
         const int lpg = g.g_v >> 3;
         quantize8(x, BV, lpg, codes, &S, &Z);
@@ -411,7 +412,8 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Geom g, kvq_cache c, in
     if (!out) continue;
     float val[8];
     reconstruct8(g, c, which, bh, t, d0, val);
-    if (!which && g.rotate_k) unrotate8(val, oct, rot_sign_bits(g.signs_k, oct));   // 16 threads = one row, all here
+    if (which ? g.rotate_v : g.rotate_k)                                             // 16 threads = one row, all here
+      unrotate8(val, oct, rot_sign_bits(which ? g.signs_v : g.signs_k, oct));
     const int64_t o = row * kHeadDim + d0;
     if (out_dtype == KVQ_F32) {
       float* p = (float*)out + o;
@@ -453,8 +455,8 @@ __global__ __launch_bounds__(256) void sq_error_kernel(Geom g, kvq_cache c, cons
       float x[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), ref_bf16 != 0);
-      // rotated keys are compared in the rotated basis: ||R k - y||_2 = ||k - R^T y||_2
-      if (!which && g.rotate_k) rotate8(x, tid & 15, rot_sign_bits(g.signs_k, tid & 15));
+      // rotated rows are compared in the rotated basis: ||R x - y||_2 = ||x - R^T y||_2
+      if (which ? g.rotate_v : g.rotate_k) rotate8(x, tid & 15, rot_sign_bits(which ? g.signs_v : g.signs_k, tid & 15));
       float sq = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {

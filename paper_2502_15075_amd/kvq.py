@@ -30,7 +30,7 @@ class KvqError(RuntimeError):
 
 class _CLayout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "kv_heads", "max_seq", "head_dim", "bits_k", "bits_v", "group_k",
-                                          "group_v", "axis_k", "axis_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4)]
+                                          "group_v", "axis_k", "axis_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4), ("rotate_v", C.c_int32), ("signs_v", C.c_uint32 * 4)]
 
 
 class _CCache(C.Structure):
@@ -97,10 +97,13 @@ class Layout:
     raw_dtype: int = KVQ_F16
     rotate_k: int = 0
     signs_k: tuple = (0, 0, 0, 0)
+    rotate_v: int = 0
+    signs_v: tuple = (0, 0, 0, 0)
 
     def c(self) -> _CLayout:
         return _CLayout(self.batch, self.kv_heads, self.max_seq, self.head_dim, self.bits_k, self.bits_v, self.group_k,
-                        self.group_v, self.axis_k, self.axis_v, self.raw_dtype, self.rotate_k, (C.c_uint32 * 4)(*self.signs_k))
+                        self.group_v, self.axis_k, self.axis_v, self.raw_dtype, self.rotate_k, (C.c_uint32 * 4)(*self.signs_k),
+                        self.rotate_v, (C.c_uint32 * 4)(*self.signs_v))
 
 
 def _check(status: int, where: str) -> None:

@@ -91,7 +91,9 @@ def test_layout_errors(kvq):
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_v=7), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, raw_dtype=2), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 1 << 25), kvq.ERR_UNSUPPORTED),
-        (kvq.Layout(1, 8, 64, rotate_k=2), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 64, rotate_k=2), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, rotate_v=-1), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 64, 128, 4, 16, rotate_v=1), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_k=1, rotate_v=1), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 16, 16, rotate_k=1), kvq.ERR_INVALID_ARG),        # rotation needs quantized keys
     ]
     for layout, want in bad:

@@ -28,10 +28,14 @@ def kvq():
 SIGNS = (0x9E3779B9, 0x7F4A7C15, 0xF39CC060, 0x5CEDC834)      # the 128 signs of the key rotation used in these tests
 
 
-def _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, raw=0, rot=0):
+SIGNS_V = (0x243F6A88, 0x85A308D3, 0x13198A2E, 0x03707344)    # ... and of the value rotation
+
+
+def _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, raw=0, rot=0, rotv=0):
     signs = SIGNS if rot else (0, 0, 0, 0)
-    return (kvq.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw, rotate_k=rot, signs_k=signs),
-            oracle.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw, rotate_k=rot, signs_k=signs))
+    signs_v = SIGNS_V if rotv else (0, 0, 0, 0)
+    return (kvq.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw, rotate_k=rot, signs_k=signs, rotate_v=rotv, signs_v=signs_v),
+            oracle.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw, rotate_k=rot, signs_k=signs, rotate_v=rotv, signs_v=signs_v))
 
 
 def _fill_both(kvq, oracle, Lg, Lo, K, V, chunks, fill=0xA5):
@@ -788,3 +792,57 @@ def test_odd_head_ratios(kvq, oracle, r):
     cache, planes = _seq_fill_both(kvq, oracle, Lg, Lo, K, V, [(0, T)])
     out = _decode(kvq, Lg, cache, q, T).cpu().numpy()
     assert _rel_err(out, oracle.seq_decode_attention(Lo, planes, synth.to_numpy_bits(q), T, 1 / math.sqrt(128), bf16=True)) < TOL
+
+
+# --------------------------------------------------------------------------- value rotation (none / keys / values / both)
+
+@pytest.mark.parametrize("rot,rotv", [(0, 1), (1, 1)])
+@pytest.mark.parametrize("R,bk,bv,gk,gv", [(1, 4, 2, 64, 64), (4, 2, 4, 32, 128), (8, 4, 2, 64, 64), (5, 8, 8, 64, 64)])
+def test_value_rotation(kvq, oracle, rot, rotv, R, bk, bv, gk, gv):
+    """Rotated value rows: byte-identical planes, bit-identical reconstruction in the input basis, squared error in
+    the rotated basis, and attention whose output is taken back with R_v^T (single workgroup per stream and the
+    split + merge path; binary32 and binary16 outputs)."""
+    B, H, T = 2, 2, 2100
+    K, V, q = synth.make_kvq(180 + R, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, rot=rot, rotv=rotv)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, 1), (1, 130), (130, T)])
+    _assert_planes_equal(cache, planes)
+    ko = torch.empty(B, H, 90, 128, dtype=torch.float32, device="cuda")
+    vo = torch.empty_like(ko)
+    kvq.dequantize(Lg, cache, 10, 100, ko, vo)
+    kd, vd = oracle.dequantize(Lo, planes, 10, 100)
+    assert np.array_equal(ko.cpu().numpy().view(np.uint32), kd.view(np.uint32))
+    assert np.array_equal(vo.cpu().numpy().view(np.uint32), vd.view(np.uint32))
+    sums = torch.empty(B, H, 2, dtype=torch.float64, device="cuda")
+    kvq.reconstruction_error(Lg, cache, K.cuda(), V.cuda(), 0, sums)
+    _, Vh = oracle.dequantize(Lo, planes, 0, T)
+    assert float(sums[..., 1].sum()) == pytest.approx(oracle.mse(V.float().numpy(), Vh) * V.numel(), rel=2e-5)
+    qn = synth.to_numpy_bits(q)
+    for seq_len in (T, 257, 64, 1):
+        ref = oracle.decode_attention(Lo, planes, qn, seq_len, 1 / math.sqrt(128), bf16=True)
+        out = _decode(kvq, Lg, cache, q, seq_len)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, seq_len
+    half = _decode(kvq, Lg, cache, q, T, out_dtype=torch.float16)
+    full = _decode(kvq, Lg, cache, q, T)
+    assert torch.equal(half, full.to(torch.float16))
+
+
+def test_value_rotation_fused_decode_steps(kvq, oracle):
+    B, H, R, T0, nstep = 2, 2, 8, 60, 6
+    T = T0 + nstep
+    K, V, _ = synth.make_kvq(190, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, 4, 2, 64, 64, rot=1, rotv=1)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K[:, :, :T0], V[:, :, :T0], [(0, T0)])
+    Kd, Vd = K.cuda(), V.cuda()
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    for i in range(nstep):
+        pos = T0 + i
+        _, _, q = synth.make_kvq(700 + i, B, H, H * R, 1, dtype=torch.bfloat16)
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), 1 / math.sqrt(128), out, ws)
+        torch.cuda.synchronize()
+        oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, pos:pos + 1])),
+                               np.ascontiguousarray(synth.to_numpy_bits(V[:, :, pos:pos + 1])), pos, bf16=True)
+        _assert_planes_equal(cache, planes)
+        ref = oracle.decode_attention(Lo, planes, synth.to_numpy_bits(q), pos + 1, 1 / math.sqrt(128), bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
