@@ -146,7 +146,8 @@ def run_groups(args, kvq, synth) -> int:
 
 def run_rotation(args, kvq, synth) -> int:
     """Rotation case study (Sec. 4 "Integration with Rotation-Based Methods", Sec. 5.3) on the 8B layer shape at context
-    32768, 64-channel groups: K2V2, K2V4, K4V2, K4V4 without rotation and with key-only rotation.  Per line: key MSE
+    32768, 64-channel groups: K2V2, K2V4, K4V2, K4V4 under the four strategies of the study (no rotation, keys only,
+    values only, both).  Per line: key MSE
     (kvq_reconstruction_error), attention-output error against exact attention on the original tensors (CPU oracle,
     batch element 0), bulk quantize-append rate and fused decode-step time, so that what the rotation buys and what
     its butterflies cost are on one line."""
@@ -155,13 +156,15 @@ def run_rotation(args, kvq, synth) -> int:
     B, Hq, Hkv, D, T, G = 8, 32, 8, 128, 32768, 64
     scale = 1.0 / math.sqrt(D)
     signs = (0x9E3779B9, 0x7F4A7C15, 0xF39CC060, 0x5CEDC834)
+    signs_v = (0x243F6A88, 0x85A308D3, 0x13198A2E, 0x03707344)
     K, V, q = synth.make_kvq(6, B, Hkv, Hq, T, D, dtype=torch.bfloat16, device="cuda")
     want = ref.attention_dense(K[:1].float().cpu().numpy(), V[:1].float().cpu().numpy(),
                                synth.to_numpy_bits(q[:1]), scale, bf16=True).astype(np.float64)
     sums = torch.empty(B, Hkv, 2, dtype=torch.float64, device="cuda")
     for bk, bv in ((2, 2), (2, 4), (4, 2), (4, 4)):
-        for rot in (0, 1):
-            L = kvq.Layout(B, Hkv, T, D, bk, bv, G, G, raw_dtype=kvq.KVQ_BF16, rotate_k=rot, signs_k=signs if rot else (0, 0, 0, 0))
+        for rot, rotv in ((0, 0), (1, 0), (0, 1), (1, 1)):
+            L = kvq.Layout(B, Hkv, T, D, bk, bv, G, G, raw_dtype=kvq.KVQ_BF16, rotate_k=rot, signs_k=signs if rot else (0, 0, 0, 0),
+                           rotate_v=rotv, signs_v=signs_v if rotv else (0, 0, 0, 0))
             row_bytes = 16 * bk + 16 * bv + 2 * 4 * (D // G)
             kv_bytes = B * Hkv * T * row_bytes
             copies = 5
@@ -176,8 +179,9 @@ def run_rotation(args, kvq, synth) -> int:
             n = B * Hkv * T * D
             got = out[:1].cpu().numpy().astype(np.float64)
             rel_l2 = float((np.linalg.norm(got - want, axis=-1) / np.linalg.norm(want, axis=-1)).mean())
-            print(json.dumps({"workload": f"8B layer, B=8, T={T}, K{bk}V{bv} G=64, key rotation {'on' if rot else 'off'}",
-                              "alloc": f"K{bk}V{bv}", "rotate_k": rot, "mse_k": float(tot[0] / n), "mse_v": float(tot[1] / n),
+            name = {(0, 0): "none", (1, 0): "keys", (0, 1): "values", (1, 1): "both"}[(rot, rotv)]
+            print(json.dumps({"workload": f"8B layer, B=8, T={T}, K{bk}V{bv} G=64, rotation: {name}",
+                              "alloc": f"K{bk}V{bv}", "rotation": name, "rotate_k": rot, "rotate_v": rotv, "mse_k": float(tot[0] / n), "mse_v": float(tot[1] / n),
                               "err_vs_exact_attention_mean_rel_l2": round(rel_l2, 5),
                               "quantize_tok_s_bulk": round(B * T / ms_q * 1e3, 1),
                               "quantize_GB_s": round(B * Hkv * T * (512 + row_bytes) / ms_q / 1e6, 1),
