@@ -84,7 +84,8 @@ enum { REF_F16 = 0, REF_BF16 = 1, REF_F32 = 2 };
 
 typedef struct {
   int32_t batch, kv_heads, max_seq, head_dim;
-  int32_t bits_k, bits_v;   /* 2, 4, 8, or 16 = keep the 16-bit input unquantized */
+  int32_t bits_k, bits_v;   /* 1, 2, 3, 4, 6, 8, or 16 = keep the 16-bit input unquantized; 1, 3 and 6 are quantizer
+                               widths only: their codes are stored in 2-, 4- and 8-bit fields (field_bits) */
   int32_t group_k, group_v; /* G: consecutive head_dim elements sharing one scale/zero */
   int32_t raw_dtype;        /* REF_F16 or REF_BF16: meaning of the planes when bits == 16 */
   int32_t rotate_k;         /* 1: key rows are stored as codes of R k (needs bits_k < 16) */
@@ -147,6 +148,12 @@ static float load_elem(const void* base, int dtype, int64_t idx) {
 
 /* ------------------------------------------------------------------ sizes */
 
+/* Storage field of a b-bit code: the next of 2, 4, 8 (the paper's per-column back-end sweeps
+ * {1,2,4,6,8} bits and Table 1 uses 3-bit keys; this format packs power-of-two fields only, so
+ * 1-, 3- and 6-bit codes keep the accuracy of their width but take the space of the next field). */
+int ref_field_bits(int b) { return b == 1 ? 2 : b == 3 ? 4 : b == 6 ? 8 : b; }
+static int bits_allowed(int b) { return b == 1 || b == 2 || b == 3 || b == 4 || b == 6 || b == 8; }
+
 static int64_t cap_tokens(const ref_layout* L) {
   int64_t unit = (L->axis_k == 1 && L->group_k > 32) ? L->group_k : 32;
   return ((int64_t)L->max_seq + unit - 1) / unit * unit;
@@ -156,9 +163,9 @@ static int64_t cap_tokens(const ref_layout* L) {
 int ref_plane_bytes(const ref_layout* L, uint64_t out[4]) {
   int64_t rows = (int64_t)L->batch * L->kv_heads * cap_tokens(L);
   int D = L->head_dim;
-  out[0] = (uint64_t)(rows * (D * L->bits_k / 8));
+  out[0] = (uint64_t)(rows * (D * ref_field_bits(L->bits_k) / 8));
   out[1] = L->bits_k == 16 ? 0 : L->axis_k == 1 ? (uint64_t)(rows / L->group_k * D * 4) : (uint64_t)(rows * (D / L->group_k) * 4);
-  out[2] = (uint64_t)(rows * (D * L->bits_v / 8));
+  out[2] = (uint64_t)(rows * (D * ref_field_bits(L->bits_v) / 8));
   out[3] = L->bits_v == 16 ? 0 : (uint64_t)(rows * (D / L->group_v) * 4);
   return 0;
 }
@@ -305,7 +312,8 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
     uint8_t* mplane = which ? v_meta : k_meta;
     int64_t cstream = (int64_t)(pb[which ? 2 : 0] / (uint64_t)streams);
     int64_t mstream = (int64_t)(pb[which ? 3 : 1] / (uint64_t)streams);
-    if (b != 16 && (D % G || (b != 2 && b != 4 && b != 8))) { free(row); free(plain); free(codes); return -1; }
+    int f = ref_field_bits(b);                              /* bits a code occupies in the planes */
+    if (b != 16 && (D % G || !bits_allowed(b))) { free(row); free(plain); free(codes); return -1; }
     for (int64_t bh = 0; bh < streams; ++bh) {
       int64_t bi = bh / L->kv_heads, hi = bh % L->kv_heads;
       uint8_t* cs = cplane + bh * cstream;
@@ -334,8 +342,8 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
           m[2] = (uint8_t)(Z & 0xFF); m[3] = (uint8_t)(Z >> 8);
         }
         for (int d = 0; d < D; ++d) {
-          if (!which) put_bits_le(cs, k_bit_offset(t, d, D, b), b, codes[d]);
-          else { int64_t wb; int bit; v_position(t, d, D, b, &wb, &bit); put_bits_le(cs + wb, bit, b, codes[d]); }
+          if (!which) put_bits_le(cs, k_bit_offset(t, d, D, f), f, codes[d]);
+          else { int64_t wb; int bit; v_position(t, d, D, f, &wb, &bit); put_bits_le(cs + wb, bit, f, codes[d]); }
         }
       }
     }
@@ -370,8 +378,9 @@ int ref_dequantize_stored(const ref_layout* L, const uint8_t* k_codes, const uin
       for (int64_t t = t0; t < t1; ++t)
         for (int d = 0; d < D; ++d) {
           uint32_t code;
-          if (!which) code = get_bits_le(cs, k_bit_offset(t, d, D, b), b);
-          else { int64_t wb; int bit; v_position(t, d, D, b, &wb, &bit); code = get_bits_le(cs + wb, bit, b); }
+          int f = ref_field_bits(b);
+          if (!which) code = get_bits_le(cs, k_bit_offset(t, d, D, f), f);
+          else { int64_t wb; int bit; v_position(t, d, D, f, &wb, &bit); code = get_bits_le(cs + wb, bit, f); }
           float val;
           if (b == 16) val = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32((uint16_t)code) : ref_f16_to_f32((uint16_t)code);
           else {

@@ -211,3 +211,45 @@ def test_group_quantizer_equals_the_numpy_statement_bit_for_bit(oracle, bits):
         c2, s2, z2 = _quantize_columns_numpy(x[:, None], bits)
         assert S == int(s2[0]) and Z == int(z2[0])
         assert np.array_equal(codes, c2[:, 0])
+
+
+@pytest.mark.parametrize("bits,field", [(1, 2), (3, 4), (6, 8)])
+def test_odd_widths_live_in_power_of_two_fields(oracle, bits, field):
+    """1-, 3- and 6-bit codes (the per-column back-end's grid {1,2,4,6,8}, Table 1's 3-bit keys) are quantized with
+    2^b - 1 steps and stored in the next power-of-two field: planes = the field-width layout of numpy's b-bit codes,
+    sizes those of the field width, reconstruction = code * scale + zero."""
+    rng = np.random.default_rng(bits)
+    B, H, T, D, G = 1, 2, 64, 128, 64
+    x = (rng.standard_normal((B, H, T, D)) * 2).astype(np.float16)
+    L = oracle.Layout(B, H, T, D, bits, bits, G, G)
+    assert oracle.plane_bytes(L) == oracle.plane_bytes(oracle.Layout(B, H, T, D, field, field, G, G))
+    planes = oracle.new_planes(L)
+    oracle.quantize_append(L, planes, x, x, 0)
+    kd, vd = oracle.dequantize(L, planes, 0, T)
+    for bh in range(B * H):
+        rows = x.reshape(B * H, T, D)[bh].astype(np.float32)
+        codes, S, Z = _quantize_rows_numpy(rows, bits, G)
+        assert codes.max() <= 2 ** bits - 1
+        k_plane, meta, v_plane = _expected_planes(codes, S, Z, field, G)
+        got = [p.reshape(B * H, -1)[bh] for p in planes]
+        assert np.array_equal(got[0], k_plane) and np.array_equal(got[1], meta)
+        assert np.array_equal(got[2], v_plane) and np.array_equal(got[3], meta)
+        want = codes.astype(np.float32) * np.repeat(S.view(np.float16).astype(np.float32), G, axis=1) \
+            + np.repeat(Z.view(np.float16).astype(np.float32), G, axis=1)
+        assert np.array_equal(kd.reshape(B * H, T, D)[bh], want) and np.array_equal(vd.reshape(B * H, T, D)[bh], want)
+
+
+def test_three_bit_keys_against_four_bit_keys_through_the_cache(oracle):
+    """Table 1 reports key MSE at 3 and 4 bits with a ratio of 4.5-4.7; (15/7)^2 = 4.59 for 2^b - 1 steps.  Through
+    the whole cache path (append, planes, dequantize) on dense Gaussian keys the ratio lands there."""
+    rng = np.random.default_rng(33)
+    B, H, T, D = 2, 4, 256, 128
+    K = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    mse = {}
+    for b in (3, 4):
+        L = oracle.Layout(B, H, T, D, b, 2, 64, 64)
+        planes = oracle.new_planes(L)
+        oracle.quantize_append(L, planes, K, K, 0)
+        kd, _ = oracle.dequantize(L, planes, 0, T)
+        mse[b] = oracle.mse(K.astype(np.float32), kd)
+    assert mse[3] / mse[4] == pytest.approx((15 / 7) ** 2, rel=0.06)
