@@ -95,7 +95,9 @@ typedef enum {
                             "Channel-wise keys" above */
 } kvq_axis;
 
-/* Immutable description of one layer's cache.  head_dim must be 128.  bits in {2,4,8,16};
+/* Immutable description of one layer's cache.  head_dim must be 128.  bits in {1,2,3,4,6,8,16}: 1, 3 and 6 (the
+ * per-column back-end's grid {1,2,4,6,8}, Table 1's 3-bit keys) are quantizer widths only -- 2^b - 1 steps, codes
+ * stored in the next of the 2-, 4-, 8-bit fields, so they cost the memory of that field;
  * group in {32,64,128} (ignored for bits == 16).  raw_dtype (KVQ_F16 / KVQ_BF16) is the element
  * type of a plane whose bits == 16. */
 typedef struct {

@@ -441,7 +441,7 @@ __device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, i
   }
   uint32_t codes[8];
   uint16_t S, Z;
-  const int bits = is_v ? BV : BK;
+  const int bits = is_v ? g.qbits_v : g.qbits_k;   // quantizer width (the field is BV / BK wide)
   const int G = is_v ? g.g_v : g.g_k, ng = is_v ? g.ng_v : g.ng_k;
   const int lpg = G >> 3;
   quantize8(x, bits, lpg, codes, &S, &Z);

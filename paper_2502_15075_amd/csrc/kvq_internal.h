@@ -14,7 +14,8 @@ constexpr int kSeqGroup = 64;     // channel-wise keys: tokens per key group = s
 // Geometry derived once on the host and passed by value to every kernel.
 struct Geom {
   int32_t batch, kv_heads, t_cap;   // t_cap = max_seq rounded up to kBlockTokens
-  int32_t bits_k, bits_v, ng_k, ng_v, g_k, g_v;
+  int32_t bits_k, bits_v, ng_k, ng_v, g_k, g_v;   // bits: the storage field of a code (2, 4, 8; 16 = unquantized)
+  int32_t qbits_k, qbits_v;         // quantizer widths: 2^qbits - 1 steps (1, 3, 6 live in the next larger field)
   int32_t raw_dtype;
   int32_t axis_k;                   // KVQ_AXIS_SEQ: channel-wise key groups of kSeqGroup tokens + residual buffer;
                                     // then g_k = 128 and ng_k = 1 (one matrix column per head on the key side)
@@ -26,13 +27,15 @@ struct Geom {
 };
 
 inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+inline int field_bits(int b) { return b == 1 ? 2 : b == 3 ? 4 : b == 6 ? 8 : b; }
 
 inline Geom make_geom(const kvq_layout& L) {
   Geom g{};
   g.batch = L.batch; g.kv_heads = L.kv_heads;
   g.axis_k = L.axis_k;
   g.t_cap = (int32_t)round_up(L.max_seq, L.axis_k == KVQ_AXIS_SEQ ? kSeqGroup : kBlockTokens);
-  g.bits_k = L.bits_k; g.bits_v = L.bits_v;
+  g.bits_k = field_bits(L.bits_k); g.bits_v = field_bits(L.bits_v);
+  g.qbits_k = L.bits_k; g.qbits_v = L.bits_v;
   g.g_k = (L.bits_k == 16 || L.axis_k == KVQ_AXIS_SEQ) ? kHeadDim : L.group_k;
   g.g_v = L.bits_v == 16 ? kHeadDim : L.group_v;
   g.ng_k = kHeadDim / g.g_k; g.ng_v = kHeadDim / g.g_v;
@@ -41,8 +44,8 @@ inline Geom make_geom(const kvq_layout& L) {
   for (int i = 0; i < 4; ++i) g.signs_k[i] = L.rotate_k ? L.signs_k[i] : 0u;
   g.rotate_v = L.rotate_v;
   for (int i = 0; i < 4; ++i) g.signs_v[i] = L.rotate_v ? L.signs_v[i] : 0u;
-  g.kc_stream = (int64_t)g.t_cap * (kHeadDim * L.bits_k / 8);
-  g.vc_stream = (int64_t)g.t_cap * (kHeadDim * L.bits_v / 8);
+  g.kc_stream = (int64_t)g.t_cap * (kHeadDim * g.bits_k / 8);
+  g.vc_stream = (int64_t)g.t_cap * (kHeadDim * g.bits_v / 8);
   g.km_stream = L.bits_k == 16 ? 0 : L.axis_k == KVQ_AXIS_SEQ ? (int64_t)(g.t_cap / kSeqGroup) * kHeadDim * 4
                                                                 : (int64_t)g.t_cap * g.ng_k * 4;
   g.vm_stream = L.bits_v == 16 ? 0 : (int64_t)g.t_cap * g.ng_v * 4;

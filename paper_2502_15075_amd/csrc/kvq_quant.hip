@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         uint32_t codes[8];
         uint16_t S, Z;
         const int lpg = g.g_k >> 3;
-        quantize8(x, BK, lpg, codes, &S, &Z);
+        quantize8(x, g.qbits_k, lpg, codes, &S, &Z);
         if ((lane16 & (lpg - 1)) == 0) km[meta_index(t, lane16 / lpg, g.ng_k)] = (uint32_t)S | ((uint32_t)Z << 16);
         uint8_t* rowp = kc + t * (16 * BK);
         if (BK == 8) {
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         if (g.rotate_v) rotate8(x, lane16, rot_sign_bits(g.signs_v, lane16));
         uint16_t S, Z;
         const int lpg = g.g_v >> 3;
-        quantize8(x, BV, lpg, codes, &S, &Z);
+        quantize8(x, g.qbits_v, lpg, codes, &S, &Z);
         if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 / lpg, g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
       }
       stage_value_codes<BV>(vstage, row, d0, codes);
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
     uint32_t vcodes[8];
     uint16_t S, Z;
     const int lpg = g.g_v >> 3;
-    quantize8(xv, BV, lpg, vcodes, &S, &Z);
+    quantize8(xv, g.qbits_v, lpg, vcodes, &S, &Z);
     if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 / lpg, g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
     stage_value_codes<BV>(vstage, row, d0, vcodes);
   }

@@ -50,6 +50,9 @@ def test_cache_bytes_closed_forms(kvq):
     assert sum(kvq.cache_bytes(kvq.Layout(1, 1, 65, 128, 8, 8, 64, 64))) == 96 * 272        # capacity rounds up to 32
     raw = kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 16, 16, 64, 64))
     assert raw == [2 * 2 * 64 * 256, 0, 2 * 2 * 64 * 256, 0]
+    # 1-, 3-, 6-bit quantizer widths take the space of the 2-, 4-, 8-bit fields they are stored in
+    assert kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 3, 1)) == kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 4, 2))
+    assert kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 6, 6)) == kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 8, 8))
     # channel-wise keys: capacity in blocks of 64 tokens, 4 bytes per channel and block, two 64-slot residual buffers
     Ls = kvq.Layout(2, 3, 100, 128, 4, 2, 64, 32, axis_k=kvq.AXIS_SEQ)
     assert kvq.cache_bytes(Ls) == [6 * 128 * 64, 6 * 2 * 512, 6 * 128 * 32, 6 * 128 * 16]
@@ -82,7 +85,8 @@ def _status(fn, *a):
 def test_layout_errors(kvq):
     bad = [
         (kvq.Layout(0, 8, 64), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 0), kvq.ERR_INVALID_ARG),
-        (kvq.Layout(1, 8, 64, 128, 3, 2), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, 128, 4, 5), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 64, 128, 7, 2), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, 128, 4, 5), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 64, 128, 3, 2, 64, 64, axis_k=1), kvq.ERR_UNSUPPORTED),     # channel-wise keys: field widths only
         (kvq.Layout(1, 8, 64, 128, 4, 2, 48, 64), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 256), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 64), kvq.ERR_UNSUPPORTED), (kvq.Layout(1, 8, 64, 128, 4, 2, 32, 64, axis_k=1), kvq.ERR_UNSUPPORTED),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_v=1), kvq.ERR_UNSUPPORTED),

@@ -846,3 +846,40 @@ def test_value_rotation_fused_decode_steps(kvq, oracle):
         _assert_planes_equal(cache, planes)
         ref = oracle.decode_attention(Lo, planes, synth.to_numpy_bits(q), pos + 1, 1 / math.sqrt(128), bf16=True)
         assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
+
+
+# --------------------------------------------------------------------------- 1-, 3- and 6-bit quantizer widths
+
+@pytest.mark.parametrize("bk,bv", [(3, 2), (6, 3), (1, 6), (3, 3), (4, 1)])
+def test_odd_quantizer_widths(kvq, oracle, bk, bv):
+    """Widths 1, 3, 6 (the per-column back-end's grid, Table 1's 3-bit keys): 2^b - 1 steps, codes in the next
+    power-of-two field.  Planes byte-identical, reconstruction bit-identical, attention within tolerance, fused steps."""
+    B, H, R, T0 = 2, 2, 4, 200
+    T = T0 + 3
+    K, V, q = synth.make_kvq(200 + 10 * bk + bv, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, 64, 32)
+    assert kvq.cache_bytes(Lg) == oracle.plane_bytes(Lo)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K[:, :, :T0], V[:, :, :T0], [(0, 70), (70, T0)])
+    _assert_planes_equal(cache, planes)
+    ko = torch.empty(B, H, T0, 128, dtype=torch.float32, device="cuda")
+    vo = torch.empty_like(ko)
+    kvq.dequantize(Lg, cache, 0, T0, ko, vo)
+    kd, vd = oracle.dequantize(Lo, planes, 0, T0)
+    assert np.array_equal(ko.cpu().numpy().view(np.uint32), kd.view(np.uint32))
+    assert np.array_equal(vo.cpu().numpy().view(np.uint32), vd.view(np.uint32))
+    qn = synth.to_numpy_bits(q)
+    for seq_len in (T0, 33):
+        out = _decode(kvq, Lg, cache, q, seq_len)
+        ref = oracle.decode_attention(Lo, planes, qn, seq_len, 1 / math.sqrt(128), bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, seq_len
+    Kd, Vd = K.cuda(), V.cuda()
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    for pos in range(T0, T):
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), 1 / math.sqrt(128), out, ws)
+        torch.cuda.synchronize()
+        oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, pos:pos + 1])),
+                               np.ascontiguousarray(synth.to_numpy_bits(V[:, :, pos:pos + 1])), pos, bf16=True)
+        _assert_planes_equal(cache, planes)
+        ref = oracle.decode_attention(Lo, planes, qn, pos + 1, 1 / math.sqrt(128), bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
