@@ -54,6 +54,12 @@
  * entry (t/64, d); k_resid is [B][H_kv][64][D] 16-bit patterns, token t in slot t%64; v_resid is [B][H_kv][2] blocks
  * in the v_codes order with b_V = 16, token t in block (t%64)/32; the other planes are as below.
  *
+ * Paged planes (page_tokens = P != 0; what a serving stack with a block table does): each plane is a pool
+ * [n_pages][H_kv][...one head's share of a contiguous cache of capacity P...], and token t of sequence b lives in pool
+ * page page_table[b][t / P] at local position t % P.  kvq_cache_bytes reports the pool sizes.  Every call takes the
+ * table as it is at launch time; pages of different sequences must not alias unless they are only read.  Not combined
+ * with channel-wise keys.
+ *
  * Storage format of one layer (sizes from kvq_cache_bytes; T_cap = max_seq rounded up to 32):
  *   k_codes  [B][H_kv][T_cap][D*b_K/8]      element d of a row at bits [d*b_K, (d+1)*b_K), little-endian
  *   k_meta   [B][H_kv][T_cap/16][D/G_K][16] entries {uint16 scale, uint16 zero} (binary16 patterns);
@@ -110,6 +116,9 @@ typedef struct {
   uint32_t signs_k[4];  /* the 128 signs of the rotation: bit d%32 of word d/32 set means s_d = -1 */
   int32_t rotate_v;     /* 0 / 1: the same rotation for value rows, with its own signs; needs bits_v < 16 */
   uint32_t signs_v[4];
+  int32_t page_tokens;  /* 0: every (b, h) stream is contiguous.  Otherwise (a power of two, 64..65536) the planes are
+                           pools of n_pages pages found through kvq_cache.page_table; see "Paged planes" above */
+  int32_t n_pages;      /* pages in the pool (page_tokens != 0) */
 } kvq_layout;
 
 /* Caller-owned device buffers of at least the sizes kvq_cache_bytes reports (16-byte aligned).
@@ -117,6 +126,8 @@ typedef struct {
 typedef struct {
   void *k_codes, *k_meta, *v_codes, *v_meta;
   void *k_resid, *v_resid; /* residual buffers of channel-wise keys (axis_k = KVQ_AXIS_SEQ); NULL otherwise */
+  const int32_t* page_table; /* paged planes: device, int32 [B][ceil(max_seq / page_tokens)]: logical page -> pool page
+                                (each in [0, n_pages); entries of pages no call touches are never read); else NULL */
 } kvq_cache;
 
 /* Host only.  bytes_out = sizes of k_codes, k_meta, v_codes, v_meta.  Pins the paper's memory

@@ -274,3 +274,32 @@ def quantize_append_at(L: Layout, planes, k_new: np.ndarray, v_new: np.ndarray, 
     for b in range(L.batch):
         Lb, pb = _element(L, planes, b)
         quantize_append(Lb, pb, np.ascontiguousarray(k_new[b:b + 1]), np.ascontiguousarray(v_new[b:b + 1]), int(pos[b]), bf16)
+
+
+# ---- paged planes: the same per-head layouts inside fixed-size pages of a pool, found through a page table
+
+def paged_plane_bytes(L: Layout, page_tokens: int, n_pages: int):
+    """Sizes of the four pool planes: n_pages pages, each holding page_tokens tokens of every KV head in the layout of a
+    contiguous cache of that capacity."""
+    one = plane_bytes(replace(L, batch=1, max_seq=page_tokens))
+    return [n * n_pages for n in one]
+
+
+def gather_pages(L: Layout, pool, table: np.ndarray, page_tokens: int, n_pages: int):
+    """Contiguous planes (capacity = pages per sequence x page_tokens) assembled from the pool: logical page p of batch
+    element b is pool page table[b][p]."""
+    B, H = L.batch, L.kv_heads
+    pages_per_seq = table.shape[1]
+    out = []
+    for plane in pool:
+        if plane.size == 0:
+            out.append(plane)
+            continue
+        per_head = plane.size // (n_pages * H)                 # bytes of one head's share of a page
+        src = plane.reshape(n_pages, H, per_head)
+        dst = np.zeros((B, H, pages_per_seq, per_head), dtype=np.uint8)
+        for b in range(B):
+            for p in range(pages_per_seq):
+                dst[b, :, p] = src[table[b, p]]
+        out.append(dst.reshape(-1))
+    return out

@@ -23,6 +23,12 @@ kvq_status check_layout(const kvq_layout* L) {
   if (L->rotate_k && L->bits_k == 16) return KVQ_ERR_INVALID_ARG;   // the rotation exists for quantized keys only
   if (L->rotate_v != 0 && L->rotate_v != 1) return KVQ_ERR_INVALID_ARG;
   if (L->rotate_v && L->bits_v == 16) return KVQ_ERR_INVALID_ARG;
+  if (L->page_tokens) {
+    if (L->page_tokens < 64 || L->page_tokens > 65536 || (L->page_tokens & (L->page_tokens - 1)) || L->n_pages <= 0)
+      return KVQ_ERR_INVALID_ARG;
+    if (L->axis_k == KVQ_AXIS_SEQ) return KVQ_ERR_UNSUPPORTED;
+    if ((int64_t)L->n_pages * L->kv_heads * L->page_tokens > ((int64_t)1 << 40)) return KVQ_ERR_UNSUPPORTED;
+  }
   if (L->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;
   if (L->axis_v != KVQ_AXIS_HEAD_DIM) return KVQ_ERR_UNSUPPORTED;
   if (L->axis_k == KVQ_AXIS_SEQ) {
@@ -44,6 +50,7 @@ kvq_status check_cache(const kvq_layout* L, const kvq_cache* c) {
     return KVQ_ERR_INVALID_ARG;
   if (L->axis_k == KVQ_AXIS_SEQ && (!c->k_resid || !c->v_resid || !aligned16(c->k_resid) || !aligned16(c->v_resid)))
     return KVQ_ERR_INVALID_ARG;
+  if (L->page_tokens && (!c->page_table || (reinterpret_cast<uintptr_t>(c->page_table) & 3u))) return KVQ_ERR_INVALID_ARG;
   return KVQ_OK;
 }
 
@@ -56,7 +63,7 @@ kvq_status kvq_cache_bytes(const kvq_layout* layout, size_t bytes_out[4]) {
   if (st != KVQ_OK) return st;
   if (!bytes_out) return KVQ_ERR_INVALID_ARG;
   const kvq::Geom g = kvq::make_geom(*layout);
-  const int64_t streams = (int64_t)g.batch * g.kv_heads;
+  const int64_t streams = layout->page_tokens ? (int64_t)layout->n_pages * g.kv_heads : (int64_t)g.batch * g.kv_heads;
   bytes_out[0] = (size_t)(streams * g.kc_stream);
   bytes_out[1] = (size_t)(streams * g.km_stream);
   bytes_out[2] = (size_t)(streams * g.vc_stream);
@@ -132,6 +139,7 @@ kvq_status decode_check(const kvq_layout* layout, const kvq_cache* cache, const 
   if (!(softmax_scale > 0.0f) || softmax_scale > 3.0e38f) return KVQ_ERR_INVALID_ARG;   // positive and finite
   if (!aligned16(q) || !aligned16(out)) return KVQ_ERR_INVALID_ARG;
   const kvq::Geom g = kvq::make_geom(*layout);
+  if (layout->page_tokens) return KVQ_ERR_UNSUPPORTED;
   if (!kvq::decode_supported(g, q_heads)) return KVQ_ERR_UNSUPPORTED;
   if (layout->axis_k == KVQ_AXIS_SEQ && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // residual tail: as unquantized
   if (layout->bits_k == 16 && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // matrix operands share a type

@@ -24,6 +24,10 @@ struct Geom {
   int32_t rotate_v;                 // value rows are stored as codes of R_v v; outputs are taken back with R_v^T
   uint32_t signs_v[4];
   int64_t kc_stream, km_stream, vc_stream, vm_stream;   // bytes per (b,h) stream in each plane
+  // paged planes: a "stream" is then one head's share of one page (t_cap = page_tokens), the pool holds
+  // n_pages * kv_heads of them, and sequence b finds its pages through the table (pages_per_seq entries per sequence)
+  int32_t page_shift;               // log2(page_tokens), 0 = not paged
+  int32_t pages_per_seq;
 };
 
 inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
@@ -34,6 +38,12 @@ inline Geom make_geom(const kvq_layout& L) {
   g.batch = L.batch; g.kv_heads = L.kv_heads;
   g.axis_k = L.axis_k;
   g.t_cap = (int32_t)round_up(L.max_seq, L.axis_k == KVQ_AXIS_SEQ ? kSeqGroup : kBlockTokens);
+  g.page_shift = 0; g.pages_per_seq = 0;
+  if (L.page_tokens) {
+    while ((1 << g.page_shift) < L.page_tokens) ++g.page_shift;
+    g.pages_per_seq = (L.max_seq + L.page_tokens - 1) / L.page_tokens;
+    g.t_cap = L.page_tokens;                       // the unit every plane is laid out for
+  }
   g.bits_k = field_bits(L.bits_k); g.bits_v = field_bits(L.bits_v);
   g.qbits_k = L.bits_k; g.qbits_v = L.bits_v;
   g.g_k = (L.bits_k == 16 || L.axis_k == KVQ_AXIS_SEQ) ? kHeadDim : L.group_k;
@@ -109,6 +119,14 @@ bool decode_supported(const Geom& g, int32_t q_heads);
 
 #if defined(__HIPCC__)
 // ---- device-side address helpers (the storage order documented in kvq.h) ----
+
+// Index of (b, h, token t) in the row order of the planes: every plane is [stream][t_cap tokens] with a stream per
+// (b, h) when contiguous and per (pool page, h) when paged, so one "virtual token" number addresses all four planes.
+__device__ inline int64_t virtual_token(const Geom& g, const int32_t* __restrict__ page_table, int b, int h, int64_t t) {
+  if (g.page_shift == 0) return ((int64_t)b * g.kv_heads + h) * g.t_cap + t;
+  const int64_t page = page_table[(int64_t)b * g.pages_per_seq + (t >> g.page_shift)];
+  return ((page * g.kv_heads + h) << g.page_shift) + (t & ((1 << g.page_shift) - 1));
+}
 
 // dword index of meta entry (token t, group g) inside one (b,h) stream
 __host__ __device__ inline int64_t meta_index(int64_t t, int g, int ng) { return ((t >> 4) * ng + g) * 16 + (t & 15); }

@@ -103,10 +103,12 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
   const int lane16 = tid & 15;
   const int d0 = lane16 * 8;
 
-  uint8_t* kc = (uint8_t*)c.k_codes + (int64_t)bh * g.kc_stream;
-  uint32_t* km = (uint32_t*)((uint8_t*)c.k_meta + (int64_t)bh * g.km_stream);
-  uint32_t* vm = (uint32_t*)((uint8_t*)c.v_meta + (int64_t)bh * g.vm_stream);
-  uint32_t* vc = (uint32_t*)((uint8_t*)c.v_codes + (int64_t)bh * g.vc_stream) + (int64_t)blk * (256 * BV);
+  // rows of all four planes are addressed by the span's first token in plane order (a span never straddles a page)
+  const int64_t tv0 = virtual_token(g, c.page_table, b, h, (int64_t)blk * kSpan);
+  uint8_t* kc = (uint8_t*)c.k_codes;
+  uint32_t* km = (uint32_t*)c.k_meta;
+  uint32_t* vm = (uint32_t*)c.v_meta;
+  uint32_t* vc = (uint32_t*)c.v_codes + (tv0 >> 5) * (128 * BV);
 
   // each thread owns 8 channels of rows (tid/16) + 16*it, it = 0..3: issue all eight 16-byte loads, then quantize
   uint4 kraw[4], vraw[4];
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
   for (int it = 0; it < 4; ++it) {
     const int row = (tid >> 4) + 16 * it;
     if (row < lo || row >= hi) continue;           // whole 16-lane rows take the same branch
-    const int64_t t = (int64_t)blk * kSpan + row;
+    const int64_t t = tv0 + row;
     // ---- keys: row-major codes
     {
       const uint4 raw = kraw[it];
@@ -348,7 +350,8 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
 }
 
 // Reconstruction x^ = code * scale + zero of 8 consecutive channels d0..d0+7 (d0 a multiple of 8) of token t of
-// stream bh (which = 0: keys, 1: values), as binary32 values; a 16-bit plane is widened exactly.
+// stream bh (which = 0: keys, 1: values), as binary32 values; a 16-bit plane is widened exactly.  Callers pass
+// bh = 0 and t = the token's number in plane order (virtual_token), which covers contiguous and paged planes alike.
 __device__ __forceinline__ void reconstruct8(const Geom& g, const kvq_cache& c, int which, int64_t bh, int64_t t, int d0,
                                              float val[8]) {
   const int b = which ? g.bits_v : g.bits_k;
@@ -404,14 +407,14 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Geom g, kvq_cache c, in
   const int oct = (int)(idx & 15);
   const int64_t row = idx >> 4;
   const int64_t bh = row / nt;
-  const int64_t t = t0 + row % nt;
+  const int64_t t = virtual_token(g, c.page_table, (int)(bh / g.kv_heads), (int)(bh % g.kv_heads), t0 + row % nt);
   const int d0 = oct * 8;
 
   for (int which = 0; which < 2; ++which) {
     void* out = which ? v_out : k_out;
     if (!out) continue;
     float val[8];
-    reconstruct8(g, c, which, bh, t, d0, val);
+    reconstruct8(g, c, which, 0, t, d0, val);
     if (which ? g.rotate_v : g.rotate_k)                                             // 16 threads = one row, all here
       unrotate8(val, oct, rot_sign_bits(which ? g.signs_v : g.signs_k, oct));
     const int64_t o = row * kHeadDim + d0;
@@ -450,7 +453,7 @@ __global__ __launch_bounds__(256) void sq_error_kernel(Geom g, kvq_cache c, cons
     for (int which = 0; which < 2; ++which) {
       if (!(which ? v_ref : k_ref)) continue;
       float val[8];
-      reconstruct8(g, c, which, bh, t0 + r, d0, val);
+      reconstruct8(g, c, which, 0, virtual_token(g, c.page_table, (int)b, (int)h, t0 + r), d0, val);
       const uint32_t rw[4] = {raw[which].x, raw[which].y, raw[which].z, raw[which].w};
       float x[8];
 #pragma unroll

@@ -30,11 +30,12 @@ class KvqError(RuntimeError):
 
 class _CLayout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "kv_heads", "max_seq", "head_dim", "bits_k", "bits_v", "group_k",
-                                          "group_v", "axis_k", "axis_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4), ("rotate_v", C.c_int32), ("signs_v", C.c_uint32 * 4)]
+                                          "group_v", "axis_k", "axis_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4), ("rotate_v", C.c_int32), ("signs_v", C.c_uint32 * 4),
+                                                                       ("page_tokens", C.c_int32), ("n_pages", C.c_int32)]
 
 
 class _CCache(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_meta", "v_codes", "v_meta", "k_resid", "v_resid")]
+    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_meta", "v_codes", "v_meta", "k_resid", "v_resid", "page_table")]
 
 
 _lib = None
@@ -99,11 +100,13 @@ class Layout:
     signs_k: tuple = (0, 0, 0, 0)
     rotate_v: int = 0
     signs_v: tuple = (0, 0, 0, 0)
+    page_tokens: int = 0
+    n_pages: int = 0
 
     def c(self) -> _CLayout:
         return _CLayout(self.batch, self.kv_heads, self.max_seq, self.head_dim, self.bits_k, self.bits_v, self.group_k,
                         self.group_v, self.axis_k, self.axis_v, self.raw_dtype, self.rotate_k, (C.c_uint32 * 4)(*self.signs_k),
-                        self.rotate_v, (C.c_uint32 * 4)(*self.signs_v))
+                        self.rotate_v, (C.c_uint32 * 4)(*self.signs_v), self.page_tokens, self.n_pages)
 
 
 def _check(status: int, where: str) -> None:
@@ -152,7 +155,8 @@ class Cache:
         self.planes = [mk(n) if n else None for n in sizes]
 
     def c(self) -> _CCache:
-        return _CCache(*[(0 if p is None else p.data_ptr()) for p in self.planes])
+        table = getattr(self, "page_table", None)          # int32 device tensor [B, pages per sequence] of a paged cache
+        return _CCache(*[(0 if p is None else p.data_ptr()) for p in self.planes], 0 if table is None else table.data_ptr())
 
     def nbytes(self) -> int:
         return sum(0 if p is None else p.numel() for p in self.planes)

@@ -883,3 +883,58 @@ def test_odd_quantizer_widths(kvq, oracle, bk, bv):
         _assert_planes_equal(cache, planes)
         ref = oracle.decode_attention(Lo, planes, qn, pos + 1, 1 / math.sqrt(128), bf16=True)
         assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
+
+
+# --------------------------------------------------------------------------- paged planes
+
+def _paged_setup(kvq, oracle, B, H, T, bk, bv, gk, gv, P, seed, raw=0, extra_pages=3):
+    """A pool with a shuffled page table (a few pages left unused) and the oracle's contiguous twin of the same capacity."""
+    pps = -(-T // P)
+    n_pages = B * pps + extra_pages
+    rng = np.random.default_rng(seed)
+    table = rng.permutation(n_pages)[:B * pps].reshape(B, pps).astype(np.int32)
+    Lg = kvq.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw, page_tokens=P, n_pages=n_pages)
+    Lo = oracle.Layout(B, H, pps * P, 128, bk, bv, gk, gv, raw_dtype=raw)
+    cache = kvq.Cache(Lg, fill=0xA5)
+    cache.page_table = torch.from_numpy(table).cuda()
+    assert [0 if p is None else p.numel() for p in cache.planes[:4]] == oracle.paged_plane_bytes(Lo, P, n_pages)
+    return Lg, Lo, cache, oracle.new_planes(Lo, fill=0xA5), table, n_pages
+
+
+def _assert_paged_equal(oracle, Lo, cache, planes, table, P, n_pages):
+    pool = [np.zeros(0, np.uint8) if p is None else p.cpu().numpy() for p in cache.planes[:4]]
+    got = oracle.gather_pages(Lo, pool, table, P, n_pages)
+    for name, g, o in zip(("k_codes", "k_meta", "v_codes", "v_meta"), got, planes):
+        bad = np.flatnonzero(g != o)
+        assert bad.size == 0, f"{name}: {bad.size} bytes differ, first at {bad[:5]}"
+    used = np.zeros(n_pages, bool)
+    used[table.ravel()] = True
+    for p in pool:                                             # pages outside the table keep the fill pattern
+        if p.size:
+            assert (p.reshape(n_pages, -1)[~used] == 0xA5).all()
+
+
+@pytest.mark.parametrize("bk,bv,gk,gv,P", [(4, 2, 64, 64, 64), (2, 4, 32, 128, 256), (8, 8, 64, 64, 128), (16, 16, 64, 64, 64)])
+def test_paged_append_and_reconstruction(kvq, oracle, bk, bv, gk, gv, P):
+    B, H, T = 3, 2, 333
+    K, V, _ = synth.make_kvq(210 + bk, B, H, H, T, dtype=torch.bfloat16)
+    raw = 1
+    Lg, Lo, cache, planes, table, n_pages = _paged_setup(kvq, oracle, B, H, T, bk, bv, gk, gv, P, seed=bk, raw=raw)
+    Kd, Vd = K.cuda(), V.cuda()
+    for a, b in [(0, 1), (1, 70), (70, 128), (128, 129), (129, T)]:
+        kvq.quantize_append(Lg, cache, Kd[:, :, a:b], Vd[:, :, a:b], a)
+        oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, a:b])),
+                               np.ascontiguousarray(synth.to_numpy_bits(V[:, :, a:b])), a, bf16=True)
+    torch.cuda.synchronize()
+    _assert_paged_equal(oracle, Lo, cache, planes, table, P, n_pages)
+    ko = torch.empty(B, H, 200, 128, dtype=torch.float32, device="cuda")
+    vo = torch.empty_like(ko)
+    kvq.dequantize(Lg, cache, 50, 250, ko, vo)
+    kd, vd = oracle.dequantize(Lo, planes, 50, 250)
+    assert np.array_equal(ko.cpu().numpy().view(np.uint32), kd.view(np.uint32))
+    assert np.array_equal(vo.cpu().numpy().view(np.uint32), vd.view(np.uint32))
+    if bk != 16:
+        sums = torch.empty(B, H, 2, dtype=torch.float64, device="cuda")
+        kvq.reconstruction_error(Lg, cache, Kd, Vd, 0, sums)
+        Kh, Vh = oracle.dequantize(Lo, planes, 0, T)
+        assert float(sums[..., 0].sum()) == pytest.approx(oracle.mse(K.float().numpy(), Kh) * K.numel(), rel=1e-6)

@@ -319,3 +319,28 @@ def test_code_bytes_k4v2_are_three_quarters_of_k4v4(oracle):
     assert sum(c) == 8 * 1024 * 128
     d = oracle.plane_bytes(oracle.Layout(1, 1, 65, 128, 8, 8, 64, 64))
     assert sum(d) == 96 * 272                                      # capacity rounds 65 tokens up to 96
+
+
+def test_paged_gather_is_a_permutation_of_page_sized_chunks(oracle):
+    """Paged pools: scattering a contiguous cache into shuffled pool pages with plain numpy slicing and gathering it
+    back through the page table gives the same bytes; pool sizes are pages x heads x (one head's share of a page)."""
+    rng = np.random.default_rng(5)
+    B, H, P, pps = 2, 3, 64, 4
+    L = oracle.Layout(B, H, P * pps, 128, 4, 2, 32, 64)
+    planes = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in oracle.plane_bytes(L)]
+    n_pages = B * pps + 2
+    table = rng.permutation(n_pages)[:B * pps].reshape(B, pps).astype(np.int32)
+    sizes = oracle.paged_plane_bytes(L, P, n_pages)
+    assert sizes == [n_pages * H * P * 64, n_pages * H * P * 16, n_pages * H * P * 32, n_pages * H * P * 8]
+    pool = []
+    for plane, n in zip(planes, sizes):
+        per_head = n // (n_pages * H)
+        dst = np.zeros((n_pages, H, per_head), np.uint8)
+        src = plane.reshape(B, H, pps, per_head)
+        for b in range(B):
+            for p in range(pps):
+                dst[table[b, p]] = src[b, :, p]
+        pool.append(dst.reshape(-1))
+    back = oracle.gather_pages(L, pool, table, P, n_pages)
+    for a, b in zip(back, planes):
+        assert np.array_equal(a, b)
