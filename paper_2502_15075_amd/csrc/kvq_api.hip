@@ -139,7 +139,6 @@ kvq_status decode_check(const kvq_layout* layout, const kvq_cache* cache, const 
   if (!(softmax_scale > 0.0f) || softmax_scale > 3.0e38f) return KVQ_ERR_INVALID_ARG;   // positive and finite
   if (!aligned16(q) || !aligned16(out)) return KVQ_ERR_INVALID_ARG;
   const kvq::Geom g = kvq::make_geom(*layout);
-  if (layout->page_tokens) return KVQ_ERR_UNSUPPORTED;
   if (!kvq::decode_supported(g, q_heads)) return KVQ_ERR_UNSUPPORTED;
   if (layout->axis_k == KVQ_AXIS_SEQ && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // residual tail: as unquantized
   if (layout->bits_k == 16 && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // matrix operands share a type

@@ -160,13 +160,18 @@ __device__ __forceinline__ u32x4 ld16(const uint8_t* p) {
   return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
 }
 
-template <int BK, int BV>
-__device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L, int step) {
-  // uniform 64-bit stream base + 32-bit offset (a (b,h) stream of any plane is below 4 GiB)
-  const uint32_t ko = (uint32_t)step * (512 * BK) + L.kc_off;
+// WIDE (paged planes): `step` counts 32-token steps in plane order from the plane base, so the uniform part of the
+// address is formed in 64 bits; otherwise it counts inside the (b,h) stream that the bases point to.
+template <int BK, int BV, bool WIDE = false>
+__device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L, int64_t step) {
+  // uniform 64-bit base + 32-bit offset (a (b,h) stream of any plane is below 4 GiB)
+  const uint8_t* kbase = WIDE ? L.kc + step * (512 * BK) : L.kc;
+  const uint8_t* vbase = WIDE ? L.vc + step * (512 * BV) : L.vc;
+  const uint8_t* mbase = WIDE ? L.meta_base + (step & (int64_t)(int32_t)L.meta_step_mask) * L.meta_mul : L.meta_base;
+  const uint32_t ko = (WIDE ? 0u : (uint32_t)step * (512 * BK)) + L.kc_off;
 #pragma unroll
   for (int x4 = 0; x4 < 2; ++x4) {
-    const uint8_t* p = L.kc + (ko + x4 * (256 * BK));
+    const uint8_t* p = kbase + (ko + x4 * (256 * BK));
     if (BK == 2) {
       typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
       const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
@@ -179,11 +184,11 @@ __device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L,
       }
     }
   }
-  if (L.meta_lane) r.meta = ld16(L.meta_base + (((uint32_t)step & L.meta_step_mask) * L.meta_mul + L.meta_off));
-  const uint32_t vo = (uint32_t)step * (512 * BV) + L.vc_off;
+  if (L.meta_lane) r.meta = ld16(mbase + ((WIDE ? 0u : ((uint32_t)step & L.meta_step_mask) * L.meta_mul) + L.meta_off));
+  const uint32_t vo = (WIDE ? 0u : (uint32_t)step * (512 * BV)) + L.vc_off;
 #pragma unroll
   for (int k = 0; k < BV / 2; ++k) {
-    const u32x4 v = ld16(L.vc + (vo + k * 1024));
+    const u32x4 v = ld16(vbase + (vo + k * 1024));
     r.vc[4 * k + 0] = v.x; r.vc[4 * k + 1] = v.y; r.vc[4 * k + 2] = v.z; r.vc[4 * k + 3] = v.w;
   }
 }
@@ -504,8 +509,10 @@ __device__ __forceinline__ void store_unrotated_row(const float* row, int lane16
 
 // KSEQ: channel-wise keys (the caller passes the flushed part of the sequence: seq_len is a multiple of 64, nothing
 // is appended); a wavefront then walks whole 64-token blocks (pairs of steps), rebuilding its query operands per block.
-template <int BK, int BV, int R, int NW, bool BF, int NCK, int NCV, bool KSEQ = false>
+// PAGED: the planes are pools of pages; a step's data is found through this sequence's row of the page table.
+template <int BK, int BV, int R, int NW, bool BF, int NCK, int NCV, bool KSEQ = false, bool PAGED = false>
 __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(const DecodeArgs a) {
+  static_assert(!(KSEQ && PAGED), "channel-wise keys are not paged");
   constexpr int kSetGroups = 16 / R;             // groups per column set
   constexpr bool RAW = BK == 16;
   static_assert(!KSEQ || (!RAW && NCK == 1), "channel-wise keys: quantized, one key column per head");
@@ -546,8 +553,9 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   const int h = L.c % R, grp = L.c / R;
   const bool act_k = grp < g.ng_k, act_v = grp < g.ng_v;
   L.gk = act_k ? grp : 0; L.gv = act_v ? grp : 0;
-  L.kc = (const uint8_t*)cache.k_codes + (int64_t)bh * g.kc_stream;
-  L.vc = (const uint8_t*)cache.v_codes + (int64_t)bh * g.vc_stream;
+  const int64_t bh_base = PAGED ? 0 : bh;           // paged: rows are numbered from the plane base (virtual_token)
+  L.kc = (const uint8_t*)cache.k_codes + bh_base * g.kc_stream;
+  L.vc = (const uint8_t*)cache.v_codes + bh_base * g.vc_stream;
   L.kc_off = L.c * (16 * BK) + L.j * (4 * BK);
   L.vc_off = lane * 16;
   {
@@ -555,8 +563,8 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
     const int nk = KSEQ ? 32 : 8 * g.ng_k, nv = 8 * g.ng_v;
     const bool is_k = lane < nk;
     L.meta_lane = !RAW && lane < nk + nv;
-    L.meta_base = is_k ? (const uint8_t*)cache.k_meta + (int64_t)bh * g.km_stream
-                       : (const uint8_t*)cache.v_meta + (int64_t)bh * g.vm_stream;
+    L.meta_base = is_k ? (const uint8_t*)cache.k_meta + bh_base * g.km_stream
+                       : (const uint8_t*)cache.v_meta + bh_base * g.vm_stream;
     L.meta_mul = is_k ? (KSEQ ? 256 : 128 * g.ng_k) : 128 * g.ng_v;
     L.meta_off = 16 * (is_k ? lane : lane - nk);
     L.meta_step_mask = (KSEQ && is_k) ? ~1u : ~0u;
@@ -572,6 +580,17 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   const int first = step_begin + SPB * wave;
   auto step_of = [&](int i) { return KSEQ ? first + 2 * NW * (i >> 1) + (i & 1) : first + NW * i; };
   const int n_my = first < step_end ? SPB * ((step_end - first + SPB * NW - 1) / (SPB * NW)) : 0;
+  // paged: logical step -> step number in plane order (page of the pool, this head's share of it, step inside it)
+  const int32_t* __restrict__ my_pages = PAGED ? cache.page_table + (int64_t)b * g.pages_per_seq : nullptr;
+  const int step_shift = g.page_shift - 5;
+  auto fetch = [&](StepRegs<BK, BV>& dst, int step) {
+    if constexpr (PAGED) {
+      const int64_t page = my_pages[step >> step_shift];
+      load_step<BK, BV, true>(dst, L, ((page * g.kv_heads + hk) << step_shift) + (step & ((1 << step_shift) - 1)));
+    } else {
+      load_step<BK, BV>(dst, L, step);
+    }
+  };
   const bool ragged = (seq_len & 31) != 0;
   const bool own_tail = ragged && n_my > 0 && step_of(n_my - 1) == n_steps - 1;
   const int n_full = own_tail ? n_my - 1 : n_my;   // complete steps of this wavefront
@@ -584,13 +603,15 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   if (early) {
 #pragma unroll
     for (int k = 0; k < kStages; ++k)
-      if (k < n_full) load_step<BK, BV>(buf[k], L, step_of(k));
+      if (k < n_full) fetch(buf[k], step_of(k));
   }
   if (do_append) {                                 // uniform over the workgroup
     if constexpr (!RAW) {
-      append_one<BK, BV>(a, bh, b, hk, tid, sm_vnew, seq_len - 1);
+      // (paged: the new token's row number in plane order, with the stream index 0)
+      const int64_t t_new = PAGED ? virtual_token(g, cache.page_table, b, hk, seq_len - 1) : (int64_t)seq_len - 1;
+      append_one<BK, BV>(a, PAGED ? 0 : bh, b, hk, tid, sm_vnew, t_new);
       __syncthreads();
-      append_one_values<BV>(a, bh, tid, sm_vnew, seq_len - 1);
+      append_one_values<BV>(a, PAGED ? 0 : bh, tid, sm_vnew, t_new);
     }
     __threadfence_block();                         // writer and readers share this workgroup: a workgroup-scope
                                                    // release is enough (no L2 write-back/invalidate across XCDs)
@@ -636,7 +657,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   if (!early) {
 #pragma unroll
     for (int k = 0; k < kStages; ++k)
-      if (k < n_full) load_step<BK, BV>(buf[k], L, step_of(k));
+      if (k < n_full) fetch(buf[k], step_of(k));
   }
   auto widen = [&](uint16_t bits) -> float {
     return q_is_bf16 ? __uint_as_float((uint32_t)bits << 16) : (float)__builtin_bit_cast(_Float16, bits);
@@ -708,7 +729,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
 #pragma unroll
     for (int k = 0; k < kStages; ++k) {
       full_step(k, it + k);
-      if (it + k + kStages < n_full) load_step<BK, BV>(buf[k], L, step_of(it + k + kStages));
+      if (it + k + kStages < n_full) fetch(buf[k], step_of(it + k + kStages));
     }
   }
 #pragma unroll
@@ -716,7 +737,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
     if (it + k < n_full) full_step(k, it + k);
   if constexpr (!KSEQ) {
     if (own_tail) {                               // ragged last step of the sequence: masked
-      load_step<BK, BV>(buf[0], L, n_steps - 1);
+      fetch(buf[0], n_steps - 1);
       compute_step<BK, BV, R, BF, NCK, NCV, true>(buf[0], qb, qsum_u, kappa, st, L, n_steps - 1, seq_len, ks);
     }
   }
@@ -822,35 +843,43 @@ inline RotV rot_v_of(const Geom& g) {
   return r;
 }
 
-template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool KSEQ>
+template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool KSEQ, bool PAGED>
 void launch_nw(const DecodeArgs& a, const DecodePlan& plan, dim3 grid, hipStream_t stream) {
   if (plan.waves_per_wg == 8)
-    hipLaunchKernelGGL((decode_kernel<BK, BV, R, 8, BF, NCK, NCV, KSEQ>), grid, dim3(512), 0, stream, a);
+    hipLaunchKernelGGL((decode_kernel<BK, BV, R, 8, BF, NCK, NCV, KSEQ, PAGED>), grid, dim3(512), 0, stream, a);
   else
-    hipLaunchKernelGGL((decode_kernel<BK, BV, R, 4, BF, NCK, NCV, KSEQ>), grid, dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((decode_kernel<BK, BV, R, 4, BF, NCK, NCV, KSEQ, PAGED>), grid, dim3(256), 0, stream, a);
+}
+
+// column sets: two only where 8 heads meet four groups (32 columns); quantized caches only
+template <int BK, int BV, int R, bool BF, bool KSEQ, bool PAGED>
+hipError_t launch_sets(const DecodeArgs& a, const DecodePlan& plan, dim3 grid, hipStream_t stream) {
+  const bool k2 = R * a.g.ng_k > 16, v2 = R * a.g.ng_v > 16;
+  if constexpr (R == 8 && BK != 16) {
+    if constexpr (KSEQ) {
+      if (k2) return hipErrorInvalidValue;
+      if (v2) launch_nw<BK, BV, R, BF, 1, 2, true, false>(a, plan, grid, stream);
+      else launch_nw<BK, BV, R, BF, 1, 1, true, false>(a, plan, grid, stream);
+    } else {
+      if (k2 && v2) launch_nw<BK, BV, R, BF, 2, 2, false, PAGED>(a, plan, grid, stream);
+      else if (k2) launch_nw<BK, BV, R, BF, 2, 1, false, PAGED>(a, plan, grid, stream);
+      else if (v2) launch_nw<BK, BV, R, BF, 1, 2, false, PAGED>(a, plan, grid, stream);
+      else launch_nw<BK, BV, R, BF, 1, 1, false, PAGED>(a, plan, grid, stream);
+    }
+  } else {
+    if (k2 || v2) return hipErrorInvalidValue;
+    launch_nw<BK, BV, R, BF, 1, 1, KSEQ, PAGED>(a, plan, grid, stream);
+  }
+  return hipGetLastError();
 }
 
 template <int BK, int BV, int R, bool BF = false, bool KSEQ = false>
 hipError_t launch_one(const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream) {
   dim3 grid(plan.n_splits, a.g.batch * a.g.kv_heads);
-  // two column sets only where 8 heads meet four groups (32 columns); quantized caches only
-  const bool k2 = R * a.g.ng_k > 16, v2 = R * a.g.ng_v > 16;
-  if constexpr (R == 8 && BK != 16) {
-    if constexpr (KSEQ) {
-      if (k2) return hipErrorInvalidValue;
-      if (v2) launch_nw<BK, BV, R, BF, 1, 2, true>(a, plan, grid, stream);
-      else launch_nw<BK, BV, R, BF, 1, 1, true>(a, plan, grid, stream);
-    } else {
-      if (k2 && v2) launch_nw<BK, BV, R, BF, 2, 2, false>(a, plan, grid, stream);
-      else if (k2) launch_nw<BK, BV, R, BF, 2, 1, false>(a, plan, grid, stream);
-      else if (v2) launch_nw<BK, BV, R, BF, 1, 2, false>(a, plan, grid, stream);
-      else launch_nw<BK, BV, R, BF, 1, 1, false>(a, plan, grid, stream);
-    }
-  } else {
-    if (k2 || v2) return hipErrorInvalidValue;
-    launch_nw<BK, BV, R, BF, 1, 1, KSEQ>(a, plan, grid, stream);
-  }
-  hipError_t e = hipGetLastError();
+  hipError_t e;
+  if constexpr (KSEQ) e = launch_sets<BK, BV, R, BF, true, false>(a, plan, grid, stream);
+  else e = a.g.page_shift ? launch_sets<BK, BV, R, BF, false, true>(a, plan, grid, stream)
+                          : launch_sets<BK, BV, R, BF, false, false>(a, plan, grid, stream);
   // the records of this launch are all there is: merge them here (otherwise the caller adds launches and merges)
   if (e != hipSuccess || a.rec_splits == 1 || a.rec_splits != plan.n_splits) return e;
   hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128), 0, stream, a.ws, a.out, a.out_dtype, a.rec_splits,

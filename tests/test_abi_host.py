@@ -50,6 +50,9 @@ def test_cache_bytes_closed_forms(kvq):
     assert sum(kvq.cache_bytes(kvq.Layout(1, 1, 65, 128, 8, 8, 64, 64))) == 96 * 272        # capacity rounds up to 32
     raw = kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 16, 16, 64, 64))
     assert raw == [2 * 2 * 64 * 256, 0, 2 * 2 * 64 * 256, 0]
+    # paged planes: pool of n_pages pages, each one head's share of a 256-token cache per KV head
+    assert kvq.cache_bytes(kvq.Layout(5, 2, 1000, 128, 4, 2, 64, 64, page_tokens=256, n_pages=11)) == \
+        [11 * 2 * 256 * 64, 11 * 2 * 256 * 8, 11 * 2 * 256 * 32, 11 * 2 * 256 * 8]
     # 1-, 3-, 6-bit quantizer widths take the space of the 2-, 4-, 8-bit fields they are stored in
     assert kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 3, 1)) == kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 4, 2))
     assert kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 6, 6)) == kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 8, 8))
@@ -95,6 +98,9 @@ def test_layout_errors(kvq):
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_v=7), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, raw_dtype=2), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 1 << 25), kvq.ERR_UNSUPPORTED),
+        (kvq.Layout(1, 8, 64, page_tokens=48, n_pages=4), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, page_tokens=32, n_pages=4), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 64, page_tokens=64, n_pages=0), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_k=1, page_tokens=64, n_pages=4), kvq.ERR_UNSUPPORTED),
         (kvq.Layout(1, 8, 64, rotate_k=2), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, rotate_v=-1), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 4, 16, rotate_v=1), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_k=1, rotate_v=1), kvq.ERR_INVALID_ARG),
@@ -121,6 +127,8 @@ def test_call_errors_are_caught_before_any_launch(kvq):
     assert qa(good, 0x50000, 0x60000, 0, 25600, 12800, 100, 0, 1) == kvq.ERR_INVALID_ARG          # rows overlap
     assert qa(kvq._CCache(0x10000, 0, 0x30000, 0x40000), 0x50000, 0x60000, 0, 25600, 12800, 128, 0, 1) == kvq.ERR_INVALID_ARG
     assert qa(good, 0x50000, 0x60000, 0, 25600, 12800, 128, 100, 0) == kvq.OK                     # empty append: no launch
+    Lp = kvq.Layout(2, 2, 100, page_tokens=64, n_pages=8).c()                                       # paged layout without a table
+    assert lib.kvq_quantize_append(C.byref(Lp), C.byref(good), p(0x50000), p(0x60000), 0, 25600, 12800, 128, 0, 1, None) == kvq.ERR_INVALID_ARG
 
     def da(q, heads, seq, scale, out, odt, ws, wsb):
         return lib.kvq_decode_attention(C.byref(cl), C.byref(good), p(q), 1, heads, seq, C.c_float(scale), p(out), odt, p(ws), wsb, None)

@@ -938,3 +938,46 @@ def test_paged_append_and_reconstruction(kvq, oracle, bk, bv, gk, gv, P):
         kvq.reconstruction_error(Lg, cache, Kd, Vd, 0, sums)
         Kh, Vh = oracle.dequantize(Lo, planes, 0, T)
         assert float(sums[..., 0].sum()) == pytest.approx(oracle.mse(K.float().numpy(), Kh) * K.numel(), rel=1e-6)
+
+
+@pytest.mark.parametrize("R,bk,bv,gk,gv,P", [(4, 4, 2, 64, 64, 64), (8, 4, 2, 32, 64, 256), (1, 2, 4, 64, 128, 128), (8, 8, 8, 64, 64, 64),
+                                             (5, 16, 16, 64, 64, 64)])
+def test_paged_attention(kvq, oracle, R, bk, bv, gk, gv, P):
+    """Attention over pool pages found through a shuffled page table: uniform and per-sequence lengths, several
+    sequence splits, and fused steps that run across a page boundary."""
+    B, H, T0 = 3, 2, 2100
+    T = T0 + 70
+    K, V, q = synth.make_kvq(220 + R, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo, cache, planes, table, n_pages = _paged_setup(kvq, oracle, B, H, T, bk, bv, gk, gv, P, seed=R, raw=1)
+    Kd, Vd = K.cuda(), V.cuda()
+    kvq.quantize_append(Lg, cache, Kd[:, :, :T0], Vd[:, :, :T0], 0)
+    oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, :T0])),
+                           np.ascontiguousarray(synth.to_numpy_bits(V[:, :, :T0])), 0, bf16=True)
+    qn = synth.to_numpy_bits(q)
+    for seq_len in (T0, 257, 64, 1):
+        out = _decode(kvq, Lg, cache, q, seq_len)
+        ref = oracle.decode_attention(Lo, planes, qn, seq_len, 1 / math.sqrt(128), bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, seq_len
+    lens = [T0, 100, 1]
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, T0)), dtype=torch.uint8, device="cuda")
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    kvq.decode_attention_varlen(Lg, cache, q.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"), T0, 1 / math.sqrt(128), out, ws)
+    torch.cuda.synchronize()
+    ref = oracle.decode_attention_varlen(Lo, planes, qn, lens, 1 / math.sqrt(128), bf16=True)
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+    if bk == 16:
+        return                                                  # (no fused append for unquantized caches)
+    for pos in list(range(T0, T0 + 6)) + list(range(T0 + 6, T, 9)):
+        if pos > T0 + 5:                                        # skip ahead with a plain append, then step again
+            a = pos - 8
+            kvq.quantize_append(Lg, cache, Kd[:, :, a:pos], Vd[:, :, a:pos], a)
+            oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, a:pos])),
+                                   np.ascontiguousarray(synth.to_numpy_bits(V[:, :, a:pos])), a, bf16=True)
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), 1 / math.sqrt(128), out, ws)
+        torch.cuda.synchronize()
+        oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, pos:pos + 1])),
+                               np.ascontiguousarray(synth.to_numpy_bits(V[:, :, pos:pos + 1])), pos, bf16=True)
+        ref = oracle.decode_attention(Lo, planes, qn, pos + 1, 1 / math.sqrt(128), bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
+    _assert_paged_equal(oracle, Lo, cache, planes, table, P, n_pages)
