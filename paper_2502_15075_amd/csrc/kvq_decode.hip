@@ -581,11 +581,24 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   auto step_of = [&](int i) { return KSEQ ? first + 2 * NW * (i >> 1) + (i & 1) : first + NW * i; };
   const int n_my = first < step_end ? SPB * ((step_end - first + SPB * NW - 1) / (SPB * NW)) : 0;
   // paged: logical step -> step number in plane order (page of the pool, this head's share of it, step inside it)
+  // (this workgroup's slice of its table row is copied to LDS first: a page number is needed before every step's
+  // loads can be issued, and a global load in front of them costs the ring most of its depth)
+  constexpr int kPageSlots = PAGED ? 2048 : 1;
+  __shared__ int32_t sm_pages[kPageSlots];
   const int32_t* __restrict__ my_pages = PAGED ? cache.page_table + (int64_t)b * g.pages_per_seq : nullptr;
   const int step_shift = g.page_shift - 5;
+  const int page0 = step_begin >> step_shift;
+  const int n_pages_mine = step_end > step_begin ? ((step_end - 1) >> step_shift) - page0 + 1 : 0;
+  const bool pages_in_lds = n_pages_mine <= kPageSlots;
+  if constexpr (PAGED) {
+    if (pages_in_lds) {
+      for (int i = tid; i < n_pages_mine; i += 64 * NW) sm_pages[i] = my_pages[page0 + i];
+      __syncthreads();
+    }
+  }
   auto fetch = [&](StepRegs<BK, BV>& dst, int step) {
     if constexpr (PAGED) {
-      const int64_t page = my_pages[step >> step_shift];
+      const int64_t page = pages_in_lds ? sm_pages[(step >> step_shift) - page0] : my_pages[step >> step_shift];
       load_step<BK, BV, true>(dst, L, ((page * g.kv_heads + hk) << step_shift) + (step & ((1 << step_shift) - 1)));
     } else {
       load_step<BK, BV>(dst, L, step);
