@@ -222,15 +222,15 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
 
 // ---- channel-wise keys (one scale/zero per channel and 64-token block) --------------------------------------------
 // The scale of channel d cannot leave the contraction over d, so it is folded into the query: per block the operand
-// q~[h,d] = q[h,d] * sK[blk,d] is rebuilt, as a high and a low binary16 part (22 significant bits: the product of two
-// 11-bit numbers is carried exactly), and the zero points enter as one constant per head and block,
+// q~[h,d] = q[h,d] * sK[blk,d] is rebuilt, as a high and a low binary16 part (the product of two 11-bit numbers has
+// 22 bits; the low part carries the rest down to an absolute 2^-25, far below what the scores resolve), and the zero
+// points enter as one constant per head and block,
 // sum_d q[h,d] zK[blk,d].  logit[t,h] = sum_d q~[h,d] cK[t,d] + that constant.
 struct KSeqState {
-  u32x4 qhi[4], qlo[4];    // query operands of the current block (low part times 2^11)
+  u32x4 qhi[4], qlo[4];    // query operands of the current block: high and low binary16 parts
   float zq_u;              // zero-point term of the current block, in code units
 };
 struct NoKSeq {};
-constexpr float kLoScale = 2048.0f, kInvLoScale = 1.0f / 2048.0f;
 
 // Rebuild the block's query operands from the staged query row (binary16 or bfloat16 patterns in LDS) and the block's
 // 128 scale/zero entries (first 512 bytes of the wavefront's LDS copy of the step's scale/zero bytes).
@@ -265,7 +265,7 @@ __device__ __forceinline__ void kseq_rebuild(KSeqState& ks, const LaneCtx& L, co
       for (int i = 0; i < 8; ++i) {
         const float val = w[k_slot_elem<BK>(m, i) - 16 * half32] / k_slot_scale<BK>(i);
         const _Float16 h16 = (_Float16)val;
-        const _Float16 l16 = (_Float16)((val - (float)h16) * kLoScale);
+        const _Float16 l16 = (_Float16)(val - (float)h16);     // (unscaled: a binary16 subnormal still resolves 2^-25)
         hi[i >> 1] |= (uint32_t)__builtin_bit_cast(uint16_t, h16) << (16 * (i & 1));
         lo[i >> 1] |= (uint32_t)__builtin_bit_cast(uint16_t, l16) << (16 * (i & 1));
       }
@@ -318,18 +318,17 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
   {
     float part[8];
     if constexpr (KSEQ) {
-      float4v h0 = {0.f, 0.f, 0.f, 0.f}, h1 = {0.f, 0.f, 0.f, 0.f}, l0 = {0.f, 0.f, 0.f, 0.f}, l1 = {0.f, 0.f, 0.f, 0.f};
+      float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int m = 0; m < 4; ++m) {                // four independent accumulation chains
+      for (int m = 0; m < 4; ++m) {                // two accumulation chains, high and low part into the same one
         const u32x4 k0 = unpack_k<BK>(r.kc[0], m), k1 = unpack_k<BK>(r.kc[1], m);
-        h0 = mma<BF>(k0, ks.qhi[m], h0);
-        h1 = mma<BF>(k1, ks.qhi[m], h1);
-        l0 = mma<BF>(k0, ks.qlo[m], l0);
-        l1 = mma<BF>(k1, ks.qlo[m], l1);
+        d0 = mma<BF>(k0, ks.qhi[m], d0);
+        d1 = mma<BF>(k1, ks.qhi[m], d1);
+        d0 = mma<BF>(k0, ks.qlo[m], d0);
+        d1 = mma<BF>(k1, ks.qlo[m], d1);
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
-        part[i] = fmaf(i < 4 ? l0[i & 3] : l1[i & 3], kInvLoScale, i < 4 ? h0[i & 3] : h1[i & 3]) + ks.zq_u;
+      for (int i = 0; i < 8; ++i) part[i] = (i < 4 ? d0[i & 3] : d1[i & 3]) + ks.zq_u;
     }
 #pragma unroll
     for (int cs = 0; cs < NCK; ++cs) {
@@ -730,8 +729,9 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   const uint16_t* qrow = &sm_q[h][0];
   // one complete step out of ring slot k (for channel-wise keys an even slot starts a block)
   auto full_step = [&](int k, int i) {
-    if constexpr (KSEQ) {                        // an even step of this wavefront's sequence starts a block (uniform)
-      if (i & 1) compute_step<BK, BV, R, BF, NCK, NCV, false, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
+    if constexpr (KSEQ) {                        // an even step of this wavefront's sequence starts a block (uniform;
+      const int odd = kStages % 2 == 0 ? (k & 1) : (i & 1);      // with an even ring it is the ring slot's parity)
+      if (odd) compute_step<BK, BV, R, BF, NCK, NCV, false, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
       else compute_step<BK, BV, R, BF, NCK, NCV, false, true>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks, qrow, q_is_bf16, act_k);
     } else {
       compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
