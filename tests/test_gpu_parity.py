@@ -981,3 +981,43 @@ def test_paged_attention(kvq, oracle, R, bk, bv, gk, gv, P):
         ref = oracle.decode_attention(Lo, planes, qn, pos + 1, 1 / math.sqrt(128), bf16=True)
         assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
     _assert_paged_equal(oracle, Lo, cache, planes, table, P, n_pages)
+
+
+# --------------------------------------------------------------------------- numerical extremes of the attention
+
+@pytest.mark.parametrize("case", ["uniform", "one_hot", "huge_logits", "wide_values", "tiny_everything", "late_maximum"])
+def test_attention_extremes(kvq, oracle, case):
+    """Inputs at the edges of what the kernel's scaled softmax has to carry: all scores equal, one token owning the
+    whole weight, scores in the thousands, value groups at the documented scale limit (range / (2^b - 1) = 32), values
+    and keys near the bottom of binary16, and a running maximum that keeps rising until the last token."""
+    rng = np.random.default_rng(7)
+    B, H, R, T = 1, 2, 4, 1300
+    K = rng.standard_normal((B, H, T, 128)).astype(np.float32)
+    V = rng.standard_normal((B, H, T, 128)).astype(np.float32)
+    q = rng.standard_normal((B, H * R, 128)).astype(np.float32)
+    if case == "uniform":
+        K[:] = 0.0
+    elif case == "one_hot":
+        K *= 0.01
+        K[:, :, 777] = 40.0 * np.sign(q[:, ::R])                     # one key aligned with every head's query sign
+    elif case == "huge_logits":
+        q *= 60.0
+        K *= 8.0
+    elif case == "wide_values":
+        V = rng.uniform(-1, 1, size=V.shape).astype(np.float32) * 47.0   # 2-bit groups: range up to 94, scale up to 31.3
+    elif case == "tiny_everything":
+        K *= 2.0 ** -10
+        V *= 2.0 ** -12
+    elif case == "late_maximum":
+        ramp = np.linspace(0.0, 30.0, T, dtype=np.float32)[None, None, :, None]
+        K = K * 0.05 + ramp * np.sign(q[:, ::R])[:, :, None, :] / 128 * 11.3
+    Kt, Vt, qt = torch.from_numpy(K).to(torch.float16), torch.from_numpy(V).to(torch.float16), torch.from_numpy(q).to(torch.float16)
+    for bk, bv in ((4, 2), (8, 8)):
+        Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, 64, 64)
+        cache, planes = _fill_both(kvq, oracle, Lg, Lo, Kt, Vt, [(0, T)])
+        _assert_planes_equal(cache, planes)
+        for seq_len in (T, 800):
+            out = _decode(kvq, Lg, cache, qt, seq_len).cpu().numpy()
+            ref = oracle.decode_attention(Lo, planes, qt.numpy(), seq_len, 1 / math.sqrt(128))
+            assert np.isfinite(out).all(), (case, bk)
+            assert _rel_err(out, ref) < TOL, (case, bk, seq_len, _rel_err(out, ref))
