@@ -450,7 +450,7 @@ __device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, i
   const int lpg = G >> 3;
   quantize8(x, bits, lpg, codes, &S, &Z);
   uint32_t* meta = (uint32_t*)((uint8_t*)(is_v ? a.cache.v_meta : a.cache.k_meta) + (int64_t)bh * (is_v ? g.vm_stream : g.km_stream));
-  if ((lane16 & (lpg - 1)) == 0) meta[meta_index(t, lane16 / lpg, ng)] = (uint32_t)S | ((uint32_t)Z << 16);
+  if ((lane16 & (lpg - 1)) == 0) meta[meta_index(t, lane16 >> lpg_shift(lpg), ng)] = (uint32_t)S | ((uint32_t)Z << 16);
   if (!is_v) {
     uint8_t* rowp = (uint8_t*)a.cache.k_codes + (int64_t)bh * g.kc_stream + t * (16 * BK);
     uint32_t w0 = 0, w1 = 0;
@@ -661,7 +661,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       for (int e = 0; e < 8; ++e) part += widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), !f16_now);
       const int lpg = g.g_k >> 3;                    // lanes per key group: 4, 8 or 16
       for (int off = 1; off < lpg; off <<= 1) part += __shfl_xor(part, off, 16);
-      if (((tid & 15) & (lpg - 1)) == 0) sm_qsum[tid >> 4][(tid & 15) / lpg] = part;
+      if (((tid & 15) & (lpg - 1)) == 0) sm_qsum[tid >> 4][(tid & 15) >> lpg_shift(lpg)] = part;
     }
   }
   if constexpr (!RAW) q_is_bf16 = q_is_bf16 && !g.rotate_k;      // the staged rotated query is binary16

@@ -141,7 +141,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         uint16_t S, Z;
         const int lpg = g.g_k >> 3;
         quantize8(x, g.qbits_k, lpg, codes, &S, &Z);
-        if ((lane16 & (lpg - 1)) == 0) km[meta_index(t, lane16 / lpg, g.ng_k)] = (uint32_t)S | ((uint32_t)Z << 16);
+        if ((lane16 & (lpg - 1)) == 0) km[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_k)] = (uint32_t)S | ((uint32_t)Z << 16);
         uint8_t* rowp = kc + t * (16 * BK);
         if (BK == 8) {
           uint32_t w0 = codes[0] | (codes[1] << 8) | (codes[2] << 16) | (codes[3] << 24);
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         uint16_t S, Z;
         const int lpg = g.g_v >> 3;
         quantize8(x, g.qbits_v, lpg, codes, &S, &Z);
-        if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 / lpg, g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
+        if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
       }
       stage_value_codes<BV>(vstage, row, d0, codes);
     }
@@ -342,7 +342,7 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
     uint16_t S, Z;
     const int lpg = g.g_v >> 3;
     quantize8(xv, g.qbits_v, lpg, vcodes, &S, &Z);
-    if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 / lpg, g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
+    if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
     stage_value_codes<BV>(vstage, row, d0, vcodes);
   }
   __syncthreads();

@@ -85,19 +85,40 @@ __device__ __forceinline__ void unrotate8(float x[8], int lane16, uint32_t sign_
   }
 }
 
+// log2 of the lanes per group (4, 8 or 16 lanes of 8 channels: groups of 32, 64, 128 channels)
+__device__ __forceinline__ int lpg_shift(int lanes_per_group) { return lanes_per_group == 4 ? 2 : lanes_per_group == 8 ? 3 : 4; }
+
+// Minimum / maximum written as the machine instructions themselves (inputs are finite by contract, so the
+// canonicalizing copies a C fmin / fmax needs are dead weight; -0 orders below +0 and is folded away afterwards).
+__device__ __forceinline__ float min3f(float a, float b, float c) {
+  float r; asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c)); return r;
+}
+__device__ __forceinline__ float max3f(float a, float b, float c) {
+  float r; asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c)); return r;
+}
+__device__ __forceinline__ float min2f(float a, float b) { float r; asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+__device__ __forceinline__ float max2f(float a, float b) { float r; asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+// Value of x in the lane a data-parallel-primitive control word selects (quad permutes and mirrors of a 16-lane
+// row).  The builtin, not assembly: the compiler then keeps the wait states such an instruction needs.
+template <int CTRL>
+__device__ __forceinline__ float lane_dpp(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+
 // Quantize 8 consecutive elements held by this lane; the group spans `lanes_per_group`
 // neighbouring lanes (a power of two <= 16, aligned).  Returns the 8 codes, and the stored
 // scale/zero patterns through S, Z.
 __device__ __forceinline__ void quantize8(const float x[8], int bits, int lanes_per_group, uint32_t codes[8],
                                           uint16_t* S, uint16_t* Z) {
 #pragma clang fp contract(off)
-  float mn = x[0], mx = x[0];
-#pragma unroll
-  for (int e = 1; e < 8; ++e) { mn = fminf(mn, x[e]); mx = fmaxf(mx, x[e]); }
-  for (int off = 1; off < lanes_per_group; off <<= 1) {
-    mn = fminf(mn, __shfl_xor(mn, off, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, off, 16));
-  }
+  float mn = min3f(min3f(x[0], x[1], x[2]), min3f(x[3], x[4], x[5]), min2f(x[6], x[7]));
+  float mx = max3f(max3f(x[0], x[1], x[2]), max3f(x[3], x[4], x[5]), max2f(x[6], x[7]));
+  // the group's lanes are an aligned run of 4, 8 or 16 inside a 16-lane row: two quad exchanges, then the mirror
+  // images of the 8- and 16-lane runs (after the quad steps every quad is uniform, so a mirror is as good as an xor)
+  mn = min2f(mn, lane_dpp<0xB1>(mn)); mx = max2f(mx, lane_dpp<0xB1>(mx));       // quad_perm [1,0,3,2]
+  mn = min2f(mn, lane_dpp<0x4E>(mn)); mx = max2f(mx, lane_dpp<0x4E>(mx));       // quad_perm [2,3,0,1]
+  if (lanes_per_group >= 8) { mn = min2f(mn, lane_dpp<0x141>(mn)); mx = max2f(mx, lane_dpp<0x141>(mx)); }   // row_half_mirror
+  if (lanes_per_group >= 16) { mn = min2f(mn, lane_dpp<0x140>(mn)); mx = max2f(mx, lane_dpp<0x140>(mx)); }  // row_mirror
   if (mn == 0.0f) mn = 0.0f;  // -0 -> +0
   const float levels = (float)((1 << bits) - 1);
   float s32 = (mx - mn) / levels;
@@ -116,7 +137,7 @@ __device__ __forceinline__ void quantize8(const float x[8], int bits, int lanes_
   for (int e = 0; e < 8; ++e) {
     float t = (x[e] - z) * rcp;
     float q = rintf(t);
-    q = fminf(fmaxf(q, 0.0f), levels);
+    q = __builtin_amdgcn_fmed3f(q, 0.0f, levels);     // clip to [0, levels] in one instruction
     codes[e] = (uint32_t)q;
   }
 }
