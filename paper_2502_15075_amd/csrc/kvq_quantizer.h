@@ -102,7 +102,7 @@ __device__ __forceinline__ float max2f(float a, float b) { float r; asm("v_max_f
 // row).  The builtin, not assembly: the compiler then keeps the wait states such an instruction needs.
 template <int CTRL>
 __device__ __forceinline__ float lane_dpp(float x) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
 }
 
 // Quantize 8 consecutive elements held by this lane; the group spans `lanes_per_group`
