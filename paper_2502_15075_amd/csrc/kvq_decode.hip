@@ -10,14 +10,19 @@
 // k), which the matrix unit multiplies exactly, so "unpacking" is one AND per two codes; the
 // power-of-two position factors are divided out of the query operand once per wavefront.
 //
-// Work split: one workgroup (4 wavefronts) walks a contiguous range of 32-token steps of one
-// (batch, kv head); each wavefront takes every 4th step and carries all R query heads of that kv
+// Work split: one workgroup (4 or 8 wavefronts) walks a contiguous range of 32-token steps of one
+// (batch, kv head); its wavefronts interleave the steps and each carries all query heads of that kv
 // head as matrix columns (column c = g*R + h: key group g, head h), so every cache byte is read
-// once.  Each wavefront keeps a ring of KVQ_STAGES steps in registers: after a step is computed its
-// registers are refilled with the step KVQ_STAGES ahead, so several steps of streaming loads are
-// always in flight per wavefront (the kernel is bound by bytes in flight, not by arithmetic).
-// Wavefronts merge through LDS, workgroups through a workspace of (max, sum, acc) records and a
-// small second kernel.
+// once.  Each wavefront keeps a ring of steps in registers: after a step is computed its registers
+// are refilled with the step one ring length ahead, so several steps of streaming loads are always
+// in flight per wavefront.  Wavefronts merge through LDS, workgroups through a workspace of
+// (max, sum, acc) records and a small second kernel.
+//
+// Variants of the same kernel (template parameters): unquantized rows as operands (bits = 16),
+// two column sets (8 heads with 32-channel groups), channel-wise key groups (Sec. 4 "Downstream Task
+// Accuracy": the scale moves into a per-block query operand), paged planes (a page-table lookup per
+// step), per-sequence lengths, the fused append of a decode step, Hadamard-rotated keys and values
+// (Sec. 4 "Integration with Rotation-Based Methods").
 #include "kvq_internal.h"
 #include "kvq_quantizer.h"
 

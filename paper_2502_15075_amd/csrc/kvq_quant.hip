@@ -1,4 +1,5 @@
-// Quantize-append and dequantize kernels (gfx950).
+// Quantize-append (token-wise groups; channel-wise key groups with their residual buffer), dequantize and
+// reconstruction-error kernels (gfx950).
 //
 // The quantizer is the b-bit uniform scalar quantizer of App. B ("Preliminaries": scale factor,
 // round, clip, reconstruct) of arXiv 2502.15075 in its group-wise asymmetric min-max form; the
