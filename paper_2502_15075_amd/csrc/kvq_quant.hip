@@ -578,6 +578,7 @@ hipError_t launch_dequantize(const Geom& g, const kvq_cache& c, int32_t t0, int3
   const int64_t total = (int64_t)g.batch * g.kv_heads * (t1 - t0) * 16;
   if (total == 0) return hipSuccess;
   const int64_t blocks = (total + 255) / 256;
+  if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;      // more than one launch can take: the caller splits [t0, t1)
   hipLaunchKernelGGL(dequantize_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, g, c, t0, t1, k_out, v_out, out_dtype);
   return hipGetLastError();
 }
