@@ -143,8 +143,8 @@ template <int BK, int BV>
 struct StepRegs {
   uint32_t kc[2][BK];            // tile x4: row 16*x4 + c, this lane's 32 channels
   uint32_t vc[2 * BV];           // value codes: piece k, dword m at [4k + m]
-  u32x4 meta;                    // 16 bytes of the step's scale/zero bytes, in plane order (lanes < 8 (ng_k + ng_v));
-                                 // redistributed through LDS when the step is computed
+  u32x4 meta;                    // 16 bytes of the step's scale/zero bytes, in plane order (lane l < 8 (ng_k + ng_v) holds
+                                 // bytes 16 l ..); redistributed through LDS when the step is computed
 };
 
 struct LaneCtx {
@@ -152,7 +152,6 @@ struct LaneCtx {
   const uint8_t* meta_base;               // this lane's scale/zero plane: key plane for lanes < 8 ng_k, else value plane
   uint32_t meta_mul, meta_off;            // bytes of that plane per 32-token step; this lane's offset inside them
   uint32_t meta_step_mask;                // ~1 for the key lanes of channel-wise keys (one entry set per two steps)
-  bool meta_lane;                         // lane < 8 (ng_k + ng_v)
   uint32_t kc_off, vc_off;                // this lane's byte offsets inside one step of the code planes
   uint32_t km_rd, vm_rd;                  // byte offsets of this lane's key / value scale-zero entries (tile 0) in the
                                           // wavefront's LDS copy of a step's scale/zero bytes
@@ -167,13 +166,17 @@ __device__ __forceinline__ u32x4 ld16(const uint8_t* p) {
 
 // WIDE (paged planes): `step` counts 32-token steps in plane order from the plane base, so the uniform part of the
 // address is formed in 64 bits; otherwise it counts inside the (b,h) stream that the bases point to.
+// lane_mask: ~0, or 0 for a refill past the wavefront's last step, which still issues its loads (every lane then reads
+// the first 16 bytes of each part of the step it is given: one cache line per load, the data is never used).  A load
+// that may or may not be issued sits behind a branch, and with a branch between the loads the compiler can no longer
+// count how many newer loads follow a ring slot's: it then drains the ring before every use.
 template <int BK, int BV, bool WIDE = false>
-__device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L, int64_t step) {
+__device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L, int64_t step, uint32_t lane_mask = ~0u) {
   // uniform 64-bit base + 32-bit offset (a (b,h) stream of any plane is below 4 GiB)
   const uint8_t* kbase = WIDE ? L.kc + step * (512 * BK) : L.kc;
   const uint8_t* vbase = WIDE ? L.vc + step * (512 * BV) : L.vc;
   const uint8_t* mbase = WIDE ? L.meta_base + (step & (int64_t)(int32_t)L.meta_step_mask) * L.meta_mul : L.meta_base;
-  const uint32_t ko = (WIDE ? 0u : (uint32_t)step * (512 * BK)) + L.kc_off;
+  const uint32_t ko = (WIDE ? 0u : (uint32_t)step * (512 * BK)) + (L.kc_off & lane_mask);
 #pragma unroll
   for (int x4 = 0; x4 < 2; ++x4) {
     const uint8_t* p = kbase + (ko + x4 * (256 * BK));
@@ -189,8 +192,10 @@ __device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L,
       }
     }
   }
-  if (L.meta_lane) r.meta = ld16(mbase + ((WIDE ? 0u : ((uint32_t)step & L.meta_step_mask) * L.meta_mul) + L.meta_off));
-  const uint32_t vo = (WIDE ? 0u : (uint32_t)step * (512 * BV)) + L.vc_off;
+  // (every lane loads, for the same reason: lanes beyond the scale/zero bytes repeat the last 16 of them)
+  if constexpr (BK != 16)
+    r.meta = ld16(mbase + ((WIDE ? 0u : ((uint32_t)step & L.meta_step_mask) * L.meta_mul) + (L.meta_off & lane_mask)));
+  const uint32_t vo = (WIDE ? 0u : (uint32_t)step * (512 * BV)) + (L.vc_off & lane_mask);
 #pragma unroll
   for (int k = 0; k < BV / 2; ++k) {
     const u32x4 v = ld16(vbase + (vo + k * 1024));
@@ -300,7 +305,7 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
   uint32_t kmeta[NCK][8], vmeta[NCV][8];
   if constexpr (!RAW) {
     // scale/zero bytes: plane order -> LDS -> the entries this lane needs (tokens 4j..4j+3 of both tiles, own groups)
-    if (L.meta_lane) *reinterpret_cast<u32x4*>(L.meta_lds + L.lane * 16) = r.meta;
+    *reinterpret_cast<u32x4*>(L.meta_lds + L.lane * 16) = r.meta;     // (lanes beyond the bytes fill slots nobody reads)
     if constexpr (KSEQ && NEWBLK) kseq_rebuild<BK>(ks, L, qrow, q_is_bf16, act_k);
 #pragma unroll
     for (int x4 = 0; x4 < 2; ++x4) {
@@ -565,12 +570,12 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   {
     // channel-wise keys: 512 bytes of scale/zero per 64-token block (32 lanes), fetched with both steps of the block
     const int nk = KSEQ ? 32 : 8 * g.ng_k, nv = 8 * g.ng_v;
-    const bool is_k = lane < nk;
-    L.meta_lane = !RAW && lane < nk + nv;
+    const int ml = min(lane, nk + nv - 1);       // lanes beyond the scale/zero bytes of a step repeat the last 16
+    const bool is_k = ml < nk;
     L.meta_base = is_k ? (const uint8_t*)cache.k_meta + bh_base * g.km_stream
                        : (const uint8_t*)cache.v_meta + bh_base * g.vm_stream;
     L.meta_mul = is_k ? (KSEQ ? 256 : 128 * g.ng_k) : 128 * g.ng_v;
-    L.meta_off = 16 * (is_k ? lane : lane - nk);
+    L.meta_off = 16 * (is_k ? ml : ml - nk);
     L.meta_step_mask = (KSEQ && is_k) ? ~1u : ~0u;
     L.km_rd = (L.gk * 16 + 4 * L.j) * 4;                       // key bytes come first in the LDS copy
     L.vm_rd = 16 * nk + (L.gv * 16 + 4 * L.j) * 4;
@@ -600,12 +605,12 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       __syncthreads();
     }
   }
-  auto fetch = [&](StepRegs<BK, BV>& dst, int step) {
+  auto fetch = [&](StepRegs<BK, BV>& dst, int step, uint32_t lane_mask = ~0u) {
     if constexpr (PAGED) {
       const int64_t page = pages_in_lds ? sm_pages[(step >> step_shift) - page0] : my_pages[step >> step_shift];
-      load_step<BK, BV, true>(dst, L, ((page * g.kv_heads + hk) << step_shift) + (step & ((1 << step_shift) - 1)));
+      load_step<BK, BV, true>(dst, L, ((page * g.kv_heads + hk) << step_shift) + (step & ((1 << step_shift) - 1)), lane_mask);
     } else {
-      load_step<BK, BV>(dst, L, step);
+      load_step<BK, BV>(dst, L, step, lane_mask);
     }
   };
   const bool ragged = (seq_len & 31) != 0;
@@ -616,12 +621,17 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   const bool do_append = !RAW && !KSEQ && a.k_new != nullptr && split == (n_steps - 1) / steps_per_split;
   const bool early = !do_append || n_my > kStages;
   // register ring of kStages steps
+  // Ring slot k is refilled with the wavefront's i-th step; past its last complete step the loads are still issued, at
+  // that last step and collapsed to one cache line each (see load_step), so that no load of the ring is conditional.
   StepRegs<BK, BV> buf[kStages];
-  if (early) {
+  auto refill = [&](int k, int i) { fetch(buf[k], step_of(min(i, n_full - 1)), i < n_full ? ~0u : 0u); };
+  auto fill_ring = [&]() {
+    if (n_full > 0) {
 #pragma unroll
-    for (int k = 0; k < kStages; ++k)
-      if (k < n_full) fetch(buf[k], step_of(k));
-  }
+      for (int k = 0; k < kStages; ++k) refill(k, k);
+    }
+  };
+  if (early) fill_ring();
   if (do_append) {                                 // uniform over the workgroup
     if constexpr (!RAW) {
       // (paged: the new token's row number in plane order, with the stream index 0)
@@ -671,11 +681,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   }
   if constexpr (!RAW) q_is_bf16 = q_is_bf16 && !g.rotate_k;      // the staged rotated query is binary16
   __syncthreads();
-  if (!early) {
-#pragma unroll
-    for (int k = 0; k < kStages; ++k)
-      if (k < n_full) fetch(buf[k], step_of(k));
-  }
+  if (!early) fill_ring();
   auto widen = [&](uint16_t bits) -> float {
     return q_is_bf16 ? __uint_as_float((uint32_t)bits << 16) : (float)__builtin_bit_cast(_Float16, bits);
   };
@@ -747,7 +753,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
 #pragma unroll
     for (int k = 0; k < kStages; ++k) {
       full_step(k, it + k);
-      if (it + k + kStages < n_full) fetch(buf[k], step_of(it + k + kStages));
+      refill(k, it + k + kStages);
     }
   }
 #pragma unroll
