@@ -67,19 +67,31 @@ __device__ __forceinline__ float sum_over_groups(float x) {
 // ---- key codes: one lane holds 32 consecutive channels of one token (BK dwords) -------------
 // Matrix step m (0..3) consumes 8 of them; slot i of that step is channel k_slot_elem(m,i) of the
 // lane's 32, stored times k_slot_scale(i).
-template <int BK> __device__ __forceinline__ int k_slot_elem(int m, int i) {
+template <int BK> __device__ __forceinline__ constexpr int k_slot_elem(int m, int i) {
   const int v = i >> 1, x = i & 1;
   if (BK == 16) return 8 * m + i;
   if (BK == 4) return 8 * m + v + 4 * x;
   if (BK == 8) return 8 * m + 4 * (v >> 1) + (v & 1) + 2 * x;
   return 16 * (m >> 1) + 4 * (m & 1) + v + 8 * x;  // BK == 2
 }
-template <int BK> __device__ __forceinline__ float k_slot_scale(int i) {
+template <int BK> __device__ __forceinline__ constexpr float k_slot_scale(int i) {
   const int v = i >> 1;
   if (BK == 4) return (v & 1) ? 16.0f : 1.0f;
   if (BK == 8 || BK == 16) return 1.0f;
   return (float)(1 << (2 * v));  // BK == 2
 }
+// The same factor as a function of the channel (the slot a channel lands in fixes it): channel d's code is left at bit
+// 4 (d % 2) of its 16-bit lane for 4-bit codes, at bit 2 (d % 4) for 2-bit codes.
+template <int BK> __device__ __forceinline__ constexpr float k_chan_scale(int d) {
+  return BK == 4 ? ((d & 1) ? 16.0f : 1.0f) : BK == 2 ? (float)(1 << (2 * (d & 3))) : 1.0f;
+}
+template <int BK> constexpr bool k_chan_scale_matches() {
+  for (int m = 0; m < 4; ++m)
+    for (int i = 0; i < 8; ++i)
+      if (k_chan_scale<BK>(k_slot_elem<BK>(m, i)) != k_slot_scale<BK>(i)) return false;
+  return true;
+}
+static_assert(k_chan_scale_matches<2>() && k_chan_scale_matches<4>() && k_chan_scale_matches<8>(), "slot factors");
 template <int BK> __device__ __forceinline__ u32x4 unpack_k(const uint32_t* w, int m) {
   u32x4 a;
   if (BK == 16) {
@@ -233,59 +245,65 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
 // ---- channel-wise keys (one scale/zero per channel and 64-token block) --------------------------------------------
 // The scale of channel d cannot leave the contraction over d, so it is folded into the query: per block the operand
 // q~[h,d] = q[h,d] * sK[blk,d] is rebuilt, as a high and a low binary16 part (the product of two 11-bit numbers has
-// 22 bits; the low part carries the rest down to an absolute 2^-25, far below what the scores resolve), and the zero
-// points enter as one constant per head and block,
+// 22 bits; the low part carries the rest down to an absolute 2^-25, far below what the scores resolve).  The two parts
+// are two matrix columns of the same head (column group 0 the high part, group 1 the low part: at most 8 heads fill
+// 16 columns), so one matrix instruction multiplies the codes by both and the sum over column groups that the
+// token-wise kernel uses for its key groups adds them.  The zero points enter as one constant per head and block,
 // sum_d q[h,d] zK[blk,d].  logit[t,h] = sum_d q~[h,d] cK[t,d] + that constant.
 struct KSeqState {
-  u32x4 qhi[4], qlo[4];    // query operands of the current block: high and low binary16 parts
-  float zq_u;              // zero-point term of the current block, in code units
+  u32x4 qop[4];            // query operand of the current block: this lane's part (high or low) of its head
+  float zq_u;              // zero-point term of the current block, in code units (lanes of the high part; else 0)
 };
 struct NoKSeq {};
 
-// Rebuild the block's query operands from the staged query row (binary16 or bfloat16 patterns in LDS) and the block's
-// 128 scale/zero entries (first 512 bytes of the wavefront's LDS copy of the step's scale/zero bytes).
+// Rebuild the block's query operand from the staged query row and the block's 128 scale/zero entries (first 512 bytes
+// of the wavefront's LDS copy of the step's scale/zero bytes).
+// qrow: the head's query in binary32, channel d divided by k_chan_scale(d) (LDS; an all-zero row for a lane whose
+// column carries nothing on the key side).  low_part: 1.0f in the lanes of the low part, 0.0f in those of the high part.
+// The high part is the product rounded toward zero, h = rtz16(v); every lane forms v - low_part * h and converts
+// again: v's own high part where low_part is 0, the exact rest where it is 1 — the same instructions in both.
 template <int BK>
-__device__ __forceinline__ void kseq_rebuild(KSeqState& ks, const LaneCtx& L, const uint16_t* qrow, bool q_is_bf16, bool act) {
-  float zq = 0.f;
+__device__ __forceinline__ void kseq_rebuild(KSeqState& ks, const LaneCtx& L, const float* qrow, float low_part) {
+  constexpr int NC = BK == 4 ? 2 : BK == 2 ? 4 : 1;          // classes of channels by k_chan_scale
+  typedef __fp16 half2v __attribute__((ext_vector_type(2)));
+  float zc[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) zc[c] = 0.f;
+  const float nlow = -low_part;
 #pragma unroll
   for (int half32 = 0; half32 < 2; ++half32) {     // 16 channels at a time: matrix steps 2*half32 and 2*half32 + 1
     float w[16];
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
-      const u32x4 qv = reinterpret_cast<const u32x4*>(qrow + 32 * L.j + 16 * half32)[k];
-      const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
+    for (int quad = 0; quad < 4; ++quad) {
+      const float4v qf = *reinterpret_cast<const float4v*>(qrow + 32 * L.j + 16 * half32 + 4 * quad);
+      const u32x4 mv = *reinterpret_cast<const u32x4*>(L.meta_lds + 128 * L.j + 64 * half32 + 16 * quad);
+      const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
 #pragma unroll
-      for (int quad = 0; quad < 2; ++quad) {
-        const u32x4 mv = *reinterpret_cast<const u32x4*>(L.meta_lds + 128 * L.j + 64 * half32 + 32 * k + 16 * quad);
-        const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const uint16_t qb16 = (uint16_t)(qw[(4 * quad + e) >> 1] >> (16 * (e & 1)));
-          const float qf = q_is_bf16 ? __uint_as_float((uint32_t)qb16 << 16) : (float)__builtin_bit_cast(_Float16, qb16);
-          w[8 * k + 4 * quad + e] = qf * meta_scale(mw[e]);
-          zq = fmaf(qf, meta_zero(mw[e]), zq);
-        }
+      for (int e = 0; e < 4; ++e) {
+        w[4 * quad + e] = fmaf(qf[e], meta_scale(mw[e]), 0.0f);
+        zc[e % NC] = fmaf(qf[e], meta_zero(mw[e]), zc[e % NC]);
       }
     }
 #pragma unroll
     for (int mm = 0; mm < 2; ++mm) {
       const int m = 2 * half32 + mm;
-      uint32_t hi[4] = {0u, 0u, 0u, 0u}, lo[4] = {0u, 0u, 0u, 0u};
+      uint32_t op[4];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float val = w[k_slot_elem<BK>(m, i) - 16 * half32] / k_slot_scale<BK>(i);
-        const _Float16 h16 = (_Float16)val;
-        const _Float16 l16 = (_Float16)(val - (float)h16);     // (unscaled: a binary16 subnormal still resolves 2^-25)
-        hi[i >> 1] |= (uint32_t)__builtin_bit_cast(uint16_t, h16) << (16 * (i & 1));
-        lo[i >> 1] |= (uint32_t)__builtin_bit_cast(uint16_t, l16) << (16 * (i & 1));
+      for (int v = 0; v < 4; ++v) {
+        const float a = w[k_slot_elem<BK>(m, 2 * v) - 16 * half32], b = w[k_slot_elem<BK>(m, 2 * v + 1) - 16 * half32];
+        const half2v h = __builtin_amdgcn_cvt_pkrtz(a, b);
+        const float xa = fmaf((float)h.x, nlow, a), xb = fmaf((float)h.y, nlow, b);
+        op[v] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(xa, xb));
       }
-      ks.qhi[m] = act ? u32x4{hi[0], hi[1], hi[2], hi[3]} : u32x4{0u, 0u, 0u, 0u};
-      ks.qlo[m] = act ? u32x4{lo[0], lo[1], lo[2], lo[3]} : u32x4{0u, 0u, 0u, 0u};
+      ks.qop[m] = u32x4{op[0], op[1], op[2], op[3]};
     }
   }
+  float zq = 0.f;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) zq = fmaf(zc[c], k_chan_scale<BK>(c), zq);
   zq += __shfl_xor(zq, 16);
   zq += __shfl_xor(zq, 32);
-  ks.zq_u = act ? zq * kCodeUnit : 0.f;
+  ks.zq_u = zq * (kCodeUnit - kCodeUnit * low_part);          // (only the high part's column adds the constant)
 }
 
 // One 32-token step.  MASKED: tokens at or beyond seq_len get weight 0 (garbage may sit there).
@@ -297,8 +315,7 @@ __device__ __forceinline__ void kseq_rebuild(KSeqState& ks, const LaneCtx& L, co
 template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool MASKED, bool NEWBLK = false, typename KS = NoKSeq>
 __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u32x4 (&qb)[NCK][4], const float (&qsum_u)[NCK],
                                              float kappa, WaveState<NCV>& st, const LaneCtx& L, int step, int seq_len,
-                                             KS& ks, const uint16_t* qrow = nullptr, bool q_is_bf16 = false,
-                                             bool act_k = false) {
+                                             KS& ks, const float* qrow = nullptr, float kseq_low = 0.f) {
   constexpr bool RAW = BK == 16;
   constexpr bool KSEQ = !__is_same(KS, NoKSeq);
   constexpr int kSetStride = (16 / R) * 64;      // bytes between the scale/zero entries of a lane's groups in two sets
@@ -306,7 +323,7 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
   if constexpr (!RAW) {
     // scale/zero bytes: plane order -> LDS -> the entries this lane needs (tokens 4j..4j+3 of both tiles, own groups)
     *reinterpret_cast<u32x4*>(L.meta_lds + L.lane * 16) = r.meta;     // (lanes beyond the bytes fill slots nobody reads)
-    if constexpr (KSEQ && NEWBLK) kseq_rebuild<BK>(ks, L, qrow, q_is_bf16, act_k);
+    if constexpr (KSEQ && NEWBLK) kseq_rebuild<BK>(ks, L, qrow, kseq_low);
 #pragma unroll
     for (int x4 = 0; x4 < 2; ++x4) {
 #pragma unroll
@@ -330,12 +347,9 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
     if constexpr (KSEQ) {
       float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int m = 0; m < 4; ++m) {                // two accumulation chains, high and low part into the same one
-        const u32x4 k0 = unpack_k<BK>(r.kc[0], m), k1 = unpack_k<BK>(r.kc[1], m);
-        d0 = mma<BF>(k0, ks.qhi[m], d0);
-        d1 = mma<BF>(k1, ks.qhi[m], d1);
-        d0 = mma<BF>(k0, ks.qlo[m], d0);
-        d1 = mma<BF>(k1, ks.qlo[m], d1);
+      for (int m = 0; m < 4; ++m) {                // two independent accumulation chains (the two 16-token tiles)
+        d0 = mma<BF>(unpack_k<BK>(r.kc[0], m), ks.qop[m], d0);
+        d1 = mma<BF>(unpack_k<BK>(r.kc[1], m), ks.qop[m], d1);
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) part[i] = (i < 4 ? d0[i & 3] : d1[i & 3]) + ks.zq_u;
@@ -529,13 +543,16 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
 #ifndef KVQ_KSEQ_STAGES
 #define KVQ_KSEQ_STAGES 2
 #endif
-  constexpr int kStages = KSEQ ? (kRing < KVQ_KSEQ_STAGES ? kRing : KVQ_KSEQ_STAGES) : kRing;   // the second query operand
-                                                 // and the rebuild need the registers of a deeper ring
+  // (channel-wise keys: the rebuild leaves registers for two steps, and the kernel, bound by its vector instructions,
+  // measures no faster with a deeper ring)
+  constexpr int kStages = KSEQ ? (kRing < KVQ_KSEQ_STAGES ? kRing : KVQ_KSEQ_STAGES) : kRing;
   constexpr int SPB = KSEQ ? 2 : 1;              // steps a wavefront takes in a row
   constexpr float kUnit = RAW ? 1.0f : kCodeUnit, kInvUnit = RAW ? 1.0f : kInvCodeUnit;
   __shared__ float sm_o[NW][R][kHeadDim];
   __shared__ float sm_m[NW][R], sm_l[NW][R];
   __shared__ __attribute__((aligned(16))) uint16_t sm_q[R][kHeadDim];
+  // channel-wise keys: the query in binary32, channel d divided by k_chan_scale(d); row R is all zero
+  __shared__ __attribute__((aligned(16))) float sm_qf[KSEQ ? R + 1 : 1][kHeadDim];
   __shared__ __attribute__((aligned(16))) uint8_t sm_meta[NW][1024];
   __shared__ uint8_t sm_vnew[kHeadDim];
   __shared__ float sm_qsum[R][4];
@@ -667,6 +684,12 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       }
     }
     reinterpret_cast<u32x4*>(&sm_q[0][0])[tid] = raw;
+    if constexpr (KSEQ) {
+      const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        sm_qf[tid >> 4][8 * (tid & 15) + e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), q_is_bf16) / k_chan_scale<BK>(e);
+    }
     if constexpr (!RAW) {
       // per-group sums of the (staged) query: the zero points of a key group enter the scores through them
       const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
@@ -679,6 +702,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       if (((tid & 15) & (lpg - 1)) == 0) sm_qsum[tid >> 4][(tid & 15) >> lpg_shift(lpg)] = part;
     }
   }
+  if constexpr (KSEQ) { if (tid < kHeadDim) sm_qf[R][tid] = 0.f; }
   if constexpr (!RAW) q_is_bf16 = q_is_bf16 && !g.rotate_k;      // the staged rotated query is binary16
   __syncthreads();
   if (!early) fill_ring();
@@ -737,13 +761,13 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   // ---- main loop, unrolled over the ring: compute a step, then refill its registers with the step kStages
   // ahead, so that kStages-1 steps of loads are always in flight behind the one being computed.
   typename std::conditional<KSEQ, KSeqState, NoKSeq>::type ks;
-  const uint16_t* qrow = &sm_q[h][0];
+  const float* qrow = &sm_qf[KSEQ ? (grp < 2 ? h : R) : 0][0];   // (column groups 0 and 1 carry the key side)
   // one complete step out of ring slot k (for channel-wise keys an even slot starts a block)
   auto full_step = [&](int k, int i) {
     if constexpr (KSEQ) {                        // an even step of this wavefront's sequence starts a block (uniform;
       const int odd = kStages % 2 == 0 ? (k & 1) : (i & 1);      // with an even ring it is the ring slot's parity)
       if (odd) compute_step<BK, BV, R, BF, NCK, NCV, false, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
-      else compute_step<BK, BV, R, BF, NCK, NCV, false, true>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks, qrow, q_is_bf16, act_k);
+      else compute_step<BK, BV, R, BF, NCK, NCV, false, true>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks, qrow, grp == 1 ? 1.0f : 0.0f);
     } else {
       compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
     }
