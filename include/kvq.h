@@ -47,7 +47,7 @@
  * Attention reads tokens below floor(seq_len / 64) * 64 from the codes and the rest from the buffer.  Contract:
  * tokens are appended in order starting at 0 (pos = number of tokens appended so far), in_dtype = raw_dtype, and
  * seq_len of a decode call is that number.  bits 16 and rotate_k are not combined with it; axis_v stays
- * KVQ_AXIS_HEAD_DIM.  Attention needs 2- or 4-bit codes and a query of raw_dtype (KVQ_ERR_UNSUPPORTED otherwise);
+ * KVQ_AXIS_HEAD_DIM.  Attention needs a query of raw_dtype (KVQ_ERR_UNSUPPORTED otherwise);
  * kvq_decode_step is the append followed by the attention (several launches).  kvq_dequantize and
  * kvq_reconstruction_error read the codes only: the caller keeps t1 at or below the number of flushed tokens.
  * Format: T_cap is a multiple of 64; k_meta is [B][H_kv][T_cap/64][D] entries {scale, zero},

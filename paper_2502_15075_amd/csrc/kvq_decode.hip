@@ -958,13 +958,7 @@ hipError_t KVQ_CAT(launch_decode_inst_, KVQ_INST_BK, KVQ_INST_BV)(int R, const D
 #if KVQ_INST_BK == 16
   return a.g.raw_dtype == KVQ_BF16 ? launch_r<16, 16, true>(R, a, plan, stream) : launch_r<16, 16, false>(R, a, plan, stream);
 #else
-  if (a.g.axis_k == KVQ_AXIS_SEQ) {
-#if KVQ_INST_BK <= 4 && KVQ_INST_BV <= 4
-    return launch_r<KVQ_INST_BK, KVQ_INST_BV, false, true>(R, a, plan, stream);
-#else
-    return hipErrorInvalidValue;                   // channel-wise keys: kernels for 2- and 4-bit codes only
-#endif
-  }
+  if (a.g.axis_k == KVQ_AXIS_SEQ) return launch_r<KVQ_INST_BK, KVQ_INST_BV, false, true>(R, a, plan, stream);
   return launch_r<KVQ_INST_BK, KVQ_INST_BV>(R, a, plan, stream);
 #endif
 }
@@ -986,7 +980,6 @@ bool decode_supported(const Geom& g, int32_t q_heads) {
   const int R = padded_heads(r);
   if ((g.bits_k == 16) != (g.bits_v == 16)) return false;      // one tensor unquantized, the other not: no kernel
   if (R * g.ng_k > 32 || R * g.ng_v > 32) return false;        // head x group columns: at most two 16-wide tiles
-  if (g.axis_k == KVQ_AXIS_SEQ && (g.bits_k > 4 || g.bits_v > 4)) return false;   // channel-wise keys: 2- and 4-bit codes
   return true;
 }
 

@@ -616,7 +616,7 @@ def test_channelwise_append_is_byte_identical(kvq, oracle, bk, bv, gv, dtype):
 
 
 @pytest.mark.parametrize("R", [1, 2, 4, 8])
-@pytest.mark.parametrize("bk,bv,gv", [(4, 2, 64), (2, 4, 128), (4, 4, 32), (2, 2, 64)])
+@pytest.mark.parametrize("bk,bv,gv", [(4, 2, 64), (2, 4, 128), (4, 4, 32), (2, 2, 64), (8, 8, 64), (8, 2, 128), (4, 8, 32)])
 def test_channelwise_attention(kvq, oracle, R, bk, bv, gv):
     """Attention over channel-wise keys: flushed blocks from the codes, the newest tokens from the residual buffer.
     Lengths: residual only, whole blocks only, both; the cache is rebuilt for every length (the buffer's content
@@ -668,13 +668,8 @@ def test_channelwise_decode_steps_cross_a_flush(kvq, oracle):
 
 
 def test_channelwise_unsupported_combinations(kvq):
-    L8 = kvq.Layout(1, 2, 128, 128, 8, 8, 64, 64, axis_k=kvq.AXIS_SEQ)
-    cache = kvq.Cache(L8, fill=0)
     q = torch.zeros(1, 2, 128, dtype=torch.float16, device="cuda")
     out = torch.empty(1, 2, 128, dtype=torch.float32, device="cuda")
-    with pytest.raises(kvq.KvqError) as e:
-        kvq.decode_attention(L8, cache, q, 100, 0.1, out, None)
-    assert e.value.status == kvq.ERR_UNSUPPORTED                      # 8-bit codes: append only
     L4 = kvq.Layout(1, 2, 128, 128, 4, 2, 64, 64, axis_k=kvq.AXIS_SEQ, raw_dtype=kvq.KVQ_BF16)
     with pytest.raises(kvq.KvqError) as e:
         kvq.decode_attention(L4, kvq.Cache(L4, fill=0), q, 100, 0.1, out, None)
