@@ -51,8 +51,14 @@
  * here in full because bytes are compared one by one):
  *
  *   capacity   T_cap = max_seq rounded up to a multiple of 32 tokens.
- *   k_codes    [B][H][T_cap][D*b_K/8] bytes; element d of a token row occupies bits
- *              [d*b_K, (d+1)*b_K) of the row read as a little-endian bit string.
+ *   k_codes    [B][H][T_cap][D*b_K/8] bytes; for b_K = 1, 2, 4, 8, 16 element d of a token row
+ *              occupies bits [d*b_K, (d+1)*b_K) of the row read as a little-endian bit string.
+ *              b_K = 3 and 6 keep a power-of-two low part and the rest of every code in two
+ *              runs: the row is cut into chunks of 32 channels (4*b_K bytes each); with
+ *              LO = 2 (b_K = 3) or 4 (b_K = 6) and HI = b_K - LO, element x of a chunk has
+ *              code mod 2^LO at bits [x*LO, (x+1)*LO) of the chunk and code >> LO at bits
+ *              [32*LO + x*HI, 32*LO + (x+1)*HI)  (a row of 3-bit codes is 48 bytes, of
+ *              6-bit codes 96: nothing is padded to a power of two).
  *   *_meta     [B][H][T_cap/16][D/G][16] entries of 4 bytes: little-endian uint16 scale
  *              then little-endian uint16 zero (both binary16 bit patterns); entry
  *              (t/16, g, t%16) belongs to token t, group g.
@@ -84,8 +90,9 @@ enum { REF_F16 = 0, REF_BF16 = 1, REF_F32 = 2 };
 
 typedef struct {
   int32_t batch, kv_heads, max_seq, head_dim;
-  int32_t bits_k, bits_v;   /* 1, 2, 3, 4, 6, 8, or 16 = keep the 16-bit input unquantized; 1, 3 and 6 are quantizer
-                               widths only: their codes are stored in 2-, 4- and 8-bit fields (field_bits) */
+  int32_t bits_k, bits_v;   /* 1, 2, 3, 4, 6, 8, or 16 = keep the 16-bit input unquantized.  Key codes are stored at
+                               their own width; value codes of widths 1, 3 and 6 are stored in 2-, 4- and 8-bit fields
+                               (field_bits): the blocked value layout has power-of-two fields only */
   int32_t group_k, group_v; /* G: consecutive head_dim elements sharing one scale/zero */
   int32_t raw_dtype;        /* REF_F16 or REF_BF16: meaning of the planes when bits == 16 */
   int32_t rotate_k;         /* 1: key rows are stored as codes of R k (needs bits_k < 16) */
@@ -163,7 +170,7 @@ static int64_t cap_tokens(const ref_layout* L) {
 int ref_plane_bytes(const ref_layout* L, uint64_t out[4]) {
   int64_t rows = (int64_t)L->batch * L->kv_heads * cap_tokens(L);
   int D = L->head_dim;
-  out[0] = (uint64_t)(rows * (D * ref_field_bits(L->bits_k) / 8));
+  out[0] = (uint64_t)(rows * (D * L->bits_k / 8));
   out[1] = L->bits_k == 16 ? 0 : L->axis_k == 1 ? (uint64_t)(rows / L->group_k * D * 4) : (uint64_t)(rows * (D / L->group_k) * 4);
   out[2] = (uint64_t)(rows * (D * ref_field_bits(L->bits_v) / 8));
   out[3] = L->bits_v == 16 ? 0 : (uint64_t)(rows * (D / L->group_v) * 4);
@@ -177,7 +184,7 @@ static int64_t meta_offset(int64_t t, int g, int ngroups) {
   return (((t / 16) * ngroups + g) * 16 + (t % 16)) * 4;
 }
 
-/* K codes: bit offset of (t, d) inside one (b,h) stream */
+/* K codes: bit offset of (t, d) inside one (b,h) stream, widths 1, 2, 4, 8, 16 */
 static int64_t k_bit_offset(int64_t t, int d, int D, int b) { return (t * D + d) * b; }
 
 /* V codes: byte offset of the 32-bit word and bit offset inside it, one (b,h) stream */
@@ -208,6 +215,21 @@ static uint32_t get_bits_le(const uint8_t* base, int64_t bit_offset, int nbits) 
     v |= (uint32_t)((base[pos / 8] >> (pos % 8)) & 1u) << k;
   }
   return v;
+}
+
+/* K codes of any width: widths 3 and 6 are stored as a low and a high run per 32-channel chunk (see the format) */
+static void k_put_code(uint8_t* cs, int64_t t, int d, int D, int b, uint32_t code) {
+  if (b != 3 && b != 6) { put_bits_le(cs, k_bit_offset(t, d, D, b), b, code); return; }
+  int lo = b == 3 ? 2 : 4, hi = b - lo, x = d % 32;
+  int64_t chunk = (t * D + (d - x)) * b;                    /* first bit of the chunk: 32 channels of b bits */
+  put_bits_le(cs, chunk + (int64_t)x * lo, lo, code & ((1u << lo) - 1u));
+  put_bits_le(cs, chunk + 32 * lo + (int64_t)x * hi, hi, code >> lo);
+}
+static uint32_t k_get_code(const uint8_t* cs, int64_t t, int d, int D, int b) {
+  if (b != 3 && b != 6) return get_bits_le(cs, k_bit_offset(t, d, D, b), b);
+  int lo = b == 3 ? 2 : 4, hi = b - lo, x = d % 32;
+  int64_t chunk = (t * D + (d - x)) * b;
+  return get_bits_le(cs, chunk + (int64_t)x * lo, lo) | (get_bits_le(cs, chunk + 32 * lo + (int64_t)x * hi, hi) << lo);
 }
 
 /* ------------------------------------------------------------------ Hadamard rotation */
@@ -312,7 +334,7 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
     uint8_t* mplane = which ? v_meta : k_meta;
     int64_t cstream = (int64_t)(pb[which ? 2 : 0] / (uint64_t)streams);
     int64_t mstream = (int64_t)(pb[which ? 3 : 1] / (uint64_t)streams);
-    int f = ref_field_bits(b);                              /* bits a code occupies in the planes */
+    int f = which ? ref_field_bits(b) : b;                  /* bits a code occupies in the planes */
     if (b != 16 && (D % G || !bits_allowed(b))) { free(row); free(plain); free(codes); return -1; }
     for (int64_t bh = 0; bh < streams; ++bh) {
       int64_t bi = bh / L->kv_heads, hi = bh % L->kv_heads;
@@ -342,7 +364,7 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
           m[2] = (uint8_t)(Z & 0xFF); m[3] = (uint8_t)(Z >> 8);
         }
         for (int d = 0; d < D; ++d) {
-          if (!which) put_bits_le(cs, k_bit_offset(t, d, D, f), f, codes[d]);
+          if (!which) k_put_code(cs, t, d, D, f, codes[d]);
           else { int64_t wb; int bit; v_position(t, d, D, f, &wb, &bit); put_bits_le(cs + wb, bit, f, codes[d]); }
         }
       }
@@ -378,8 +400,8 @@ int ref_dequantize_stored(const ref_layout* L, const uint8_t* k_codes, const uin
       for (int64_t t = t0; t < t1; ++t)
         for (int d = 0; d < D; ++d) {
           uint32_t code;
-          int f = ref_field_bits(b);
-          if (!which) code = get_bits_le(cs, k_bit_offset(t, d, D, f), f);
+          int f = which ? ref_field_bits(b) : b;
+          if (!which) code = k_get_code(cs, t, d, D, f);
           else { int64_t wb; int bit; v_position(t, d, D, f, &wb, &bit); code = get_bits_le(cs + wb, bit, f); }
           float val;
           if (b == 16) val = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32((uint16_t)code) : ref_f16_to_f32((uint16_t)code);

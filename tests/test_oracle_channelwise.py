@@ -213,16 +213,31 @@ def test_group_quantizer_equals_the_numpy_statement_bit_for_bit(oracle, bits):
         assert np.array_equal(codes, c2[:, 0])
 
 
+def _pack_key_rows_numpy(codes, bits):
+    """Key rows at their own width.  1 bit: a plain bit string.  3 and 6 bits: per chunk of 32 channels the low 2 (4)
+    bits of the 32 codes as one run of fields, then their high 1 (2) bits as a second run."""
+    if bits not in (3, 6):
+        return _pack_fields_le(codes.ravel(), bits)
+    lo = 2 if bits == 3 else 4
+    T, D = codes.shape
+    chunks = codes.reshape(T, D // 32, 32).astype(np.uint16)
+    low = _pack_fields_le((chunks & ((1 << lo) - 1)).ravel(), lo).reshape(T, D // 32, 4 * lo)
+    high = _pack_fields_le((chunks >> lo).ravel(), bits - lo).reshape(T, D // 32, 4 * (bits - lo))
+    return np.concatenate([low, high], axis=2).ravel()
+
+
 @pytest.mark.parametrize("bits,field", [(1, 2), (3, 4), (6, 8)])
-def test_odd_widths_live_in_power_of_two_fields(oracle, bits, field):
+def test_odd_widths_keys_at_their_width_values_in_power_of_two_fields(oracle, bits, field):
     """1-, 3- and 6-bit codes (the per-column back-end's grid {1,2,4,6,8}, Table 1's 3-bit keys) are quantized with
-    2^b - 1 steps and stored in the next power-of-two field: planes = the field-width layout of numpy's b-bit codes,
-    sizes those of the field width, reconstruction = code * scale + zero."""
+    2^b - 1 steps.  Key rows take D*b/8 bytes (3 and 6 bits as a low and a high run per 32 channels); value codes sit
+    in the next power-of-two field of the blocked layout.  Planes = numpy's packing of numpy's b-bit codes, sizes
+    accordingly, reconstruction = code * scale + zero."""
     rng = np.random.default_rng(bits)
     B, H, T, D, G = 1, 2, 64, 128, 64
     x = (rng.standard_normal((B, H, T, D)) * 2).astype(np.float16)
     L = oracle.Layout(B, H, T, D, bits, bits, G, G)
-    assert oracle.plane_bytes(L) == oracle.plane_bytes(oracle.Layout(B, H, T, D, field, field, G, G))
+    sizes, fsizes = oracle.plane_bytes(L), oracle.plane_bytes(oracle.Layout(B, H, T, D, field, field, G, G))
+    assert sizes[0] == B * H * T * D * bits // 8 and sizes[1:] == fsizes[1:]
     planes = oracle.new_planes(L)
     oracle.quantize_append(L, planes, x, x, 0)
     kd, vd = oracle.dequantize(L, planes, 0, T)
@@ -230,9 +245,9 @@ def test_odd_widths_live_in_power_of_two_fields(oracle, bits, field):
         rows = x.reshape(B * H, T, D)[bh].astype(np.float32)
         codes, S, Z = _quantize_rows_numpy(rows, bits, G)
         assert codes.max() <= 2 ** bits - 1
-        k_plane, meta, v_plane = _expected_planes(codes, S, Z, field, G)
+        _, meta, v_plane = _expected_planes(codes, S, Z, field, G)
         got = [p.reshape(B * H, -1)[bh] for p in planes]
-        assert np.array_equal(got[0], k_plane) and np.array_equal(got[1], meta)
+        assert np.array_equal(got[0], _pack_key_rows_numpy(codes, bits)) and np.array_equal(got[1], meta)
         assert np.array_equal(got[2], v_plane) and np.array_equal(got[3], meta)
         want = codes.astype(np.float32) * np.repeat(S.view(np.float16).astype(np.float32), G, axis=1) \
             + np.repeat(Z.view(np.float16).astype(np.float32), G, axis=1)
