@@ -285,7 +285,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=4000)
     ap.add_argument("--warmup", type=int, default=400)
-    ap.add_argument("--layers", type=int, default=40, help="resident layer caches taken in turn")
+    ap.add_argument("--layers", type=int, default=80, help="resident layer caches taken in turn")
     ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS) + ["sweep", "groups", "rotation", "channelwise", "stream131k"],
                     help="llama70b (default, the headline line) / llama8b: one JSON line; sweep: bit-allocation sweep on the 8B "
                          "layer (one line per allocation and context); stream131k: chunked fill + growing-cache decode at 131072")

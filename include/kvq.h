@@ -61,7 +61,12 @@
  * with channel-wise keys.
  *
  * Storage format of one layer (sizes from kvq_cache_bytes; T_cap = max_seq rounded up to 32):
- *   k_codes  [B][H_kv][T_cap][D*b_K/8]      element d of a row at bits [d*b_K, (d+1)*b_K), little-endian
+ *   k_codes  [B][H_kv][T_cap][D*b_K/8]      b_K in {1,2,4,8,16}: element d of a row at bits [d*b_K, (d+1)*b_K),
+ *                                           little-endian.  b_K = 3 and 6: the row is cut into chunks of 32
+ *                                           channels (4*b_K bytes); with LO = 2 (b_K = 3) or 4 (b_K = 6) and
+ *                                           HI = b_K - LO, element x of a chunk has code mod 2^LO at bits
+ *                                           [x*LO, (x+1)*LO) of the chunk and code >> LO at bits
+ *                                           32*LO + [x*HI, (x+1)*HI)
  *   k_meta   [B][H_kv][T_cap/16][D/G_K][16] entries {uint16 scale, uint16 zero} (binary16 patterns);
  *                                           entry (t/16, g, t%16) is token t, group g
  *   v_codes  [B][H_kv][T_cap/32][512*b_V]   32-token blocks laid out in the order a 16x16x32 matrix
@@ -101,9 +106,10 @@ typedef enum {
                             "Channel-wise keys" above */
 } kvq_axis;
 
-/* Immutable description of one layer's cache.  head_dim must be 128.  bits in {1,2,3,4,6,8,16}: 1, 3 and 6 (the
- * per-column back-end's grid {1,2,4,6,8}, Table 1's 3-bit keys) are quantizer widths only -- 2^b - 1 steps, codes
- * stored in the next of the 2-, 4-, 8-bit fields, so they cost the memory of that field;
+/* Immutable description of one layer's cache.  head_dim must be 128.  bits in {1,2,3,4,6,8,16} (the per-column
+ * back-end's grid {1,2,4,6,8}, Table 1's 3-bit keys): 2^b - 1 steps.  Key rows are stored at their own width (a row
+ * of 3-bit codes is 48 bytes).  Value codes of widths 1, 3 and 6 are stored in the next of the 2-, 4-, 8-bit fields
+ * of the blocked value layout, so they cost the memory of that field (b_V below is then the field width);
  * group in {32,64,128} (ignored for bits == 16).  raw_dtype (KVQ_F16 / KVQ_BF16) is the element
  * type of a plane whose bits == 16. */
 typedef struct {

@@ -66,24 +66,39 @@ __device__ __forceinline__ float sum_over_groups(float x) {
 
 // ---- key codes: one lane holds 32 consecutive channels of one token (BK dwords) -------------
 // Matrix step m (0..3) consumes 8 of them; slot i of that step is channel k_slot_elem(m,i) of the
-// lane's 32, stored times k_slot_scale(i).
+// lane's 32, left at bit k of its 16-bit lane, i.e. read as code * 2^k * 2^-24, so the query operand of the slot is
+// divided by k_slot_scale(i) = 2^k.
+//
+// Where the fields are left matters for accuracy.  A binary16 subnormal enters the matrix unit with the exponent
+// 2^-14 whatever its leading zeros, and the unit keeps about 24 bits below the largest product exponent of a dot
+// product: a code at bit 0 against an undivided query element loses everything below 2^-38 times that element (measured:
+// up to 3e-4 code units per 32-term dot product, which the scale of a coarse key format on outlier-heavy keys turns
+// into several 1e-3 of a logit), a code at bit k against the element divided by 2^k keeps 2^k times more.  The query
+// operand in turn must stay a normal binary16 number, so k stays at or below 6.  Hence: 2-bit fields are moved to bits
+// 4 and 6 (one more shift per matrix step), single bits to BASE..BASE+3; 4-bit fields stay at bits 0 and 4 and 8-bit
+// fields at bit 0 (their scales are small and the error stays at the level of the value side's weight rounding; moving
+// the 4-bit fields as well was measured: the same maximum error, 2.8 % more time for the headline format).
+// BASE: lowest bit of the moved 1- and 2-bit fields (the high run of 3- and 6-bit codes is moved higher, its query
+// operand carries the factor 2^LO and is still normal).
 template <int BK> __device__ __forceinline__ constexpr int k_slot_elem(int m, int i) {
   const int v = i >> 1, x = i & 1;
   if (BK == 16) return 8 * m + i;
+  if (BK == 1) return 4 * m + v + 16 * x;
   if (BK == 4) return 8 * m + v + 4 * x;
   if (BK == 8) return 8 * m + 4 * (v >> 1) + (v & 1) + 2 * x;
   return 16 * (m >> 1) + 4 * (m & 1) + v + 8 * x;  // BK == 2
 }
-template <int BK> __device__ __forceinline__ constexpr float k_slot_scale(int i) {
+template <int BK> constexpr int k_default_base() { return BK == 2 ? 4 : BK == 1 ? 3 : 0; }
+template <int BK, int BASE = k_default_base<BK>()> __device__ __forceinline__ constexpr float k_slot_scale(int i) {
   const int v = i >> 1;
   if (BK == 4) return (v & 1) ? 16.0f : 1.0f;
   if (BK == 8 || BK == 16) return 1.0f;
-  return (float)(1 << (2 * v));  // BK == 2
+  if (BK == 1) return (float)(1 << (BASE + v));
+  return (float)(1 << (BASE + 2 * (v & 1)));       // BK == 2
 }
-// The same factor as a function of the channel (the slot a channel lands in fixes it): channel d's code is left at bit
-// 4 (d % 2) of its 16-bit lane for 4-bit codes, at bit 2 (d % 4) for 2-bit codes.
+// The same factor as a function of the channel (the slot a channel lands in fixes it), default BASE.
 template <int BK> __device__ __forceinline__ constexpr float k_chan_scale(int d) {
-  return BK == 4 ? ((d & 1) ? 16.0f : 1.0f) : BK == 2 ? (float)(1 << (2 * (d & 3))) : 1.0f;
+  return BK == 4 ? ((d & 1) ? 16.0f : 1.0f) : BK == 2 ? ((d & 1) ? 64.0f : 16.0f) : 1.0f;
 }
 template <int BK> constexpr bool k_chan_scale_matches() {
   for (int m = 0; m < 4; ++m)
@@ -92,22 +107,41 @@ template <int BK> constexpr bool k_chan_scale_matches() {
   return true;
 }
 static_assert(k_chan_scale_matches<2>() && k_chan_scale_matches<4>() && k_chan_scale_matches<8>(), "slot factors");
-template <int BK> __device__ __forceinline__ u32x4 unpack_k(const uint32_t* w, int m) {
+// (shift left by s, right for negative s; s is a compile-time value after unrolling)
+__device__ __forceinline__ uint32_t shl_signed(uint32_t w, int s) { return s >= 0 ? w << s : w >> (-s); }
+template <int BK, int BASE = k_default_base<BK>()> __device__ __forceinline__ u32x4 unpack_k(const uint32_t* w, int m) {
   u32x4 a;
-  if (BK == 16) {
+  if constexpr (BK == 16) {
     a = u32x4{w[4 * m], w[4 * m + 1], w[4 * m + 2], w[4 * m + 3]};      // unquantized: the 16-bit patterns themselves
-  } else if (BK == 4) {
+  } else if constexpr (BK == 4) {
     const uint32_t lo = w[m], hi = w[m] >> 8;
     a = u32x4{lo & 0x000F000Fu, lo & 0x00F000F0u, hi & 0x000F000Fu, hi & 0x00F000F0u};
-  } else if (BK == 8) {
+  } else if constexpr (BK == 8) {
     const uint32_t w0 = w[2 * m], w1 = w[2 * m + 1];
     a = u32x4{w0 & 0x00FF00FFu, (w0 >> 8) & 0x00FF00FFu, w1 & 0x00FF00FFu, (w1 >> 8) & 0x00FF00FFu};
+  } else if constexpr (BK == 1) {
+    // bit 4m+v of each half (channels 4m+v and 16+4m+v) to bit BASE+v.  What a shift carries across the middle of the
+    // word lands outside the masks: left shifts reach bit 16+BASE-1 at most, right shifts bit 16-(4m-BASE) at least.
+    static_assert(BASE >= 0 && BASE <= 7, "single-bit fields stay below bit 11");
+    const uint32_t ws = shl_signed(w[0], BASE - 4 * m);
+    constexpr uint32_t k1 = 0x00010001u << BASE;
+    a = u32x4{ws & k1, ws & (k1 << 1), ws & (k1 << 2), ws & (k1 << 3)};
   } else {
-    const uint32_t ws = w[m >> 1] >> (8 * (m & 1));
-    a = u32x4{ws & 0x00030003u, ws & 0x000C000Cu, ws & 0x00300030u, ws & 0x00C000C0u};
+    // fields 0,1 of the byte (bits 0-3) and fields 2,3 (bits 4-7) both to bits BASE..BASE+3 (same remark on carries)
+    static_assert(BASE >= 4 && BASE <= 7, "two-bit fields stay below bit 11");
+    const int byte0 = 8 * (m & 1);
+    const uint32_t wl = shl_signed(w[m >> 1], BASE - byte0), wh = shl_signed(w[m >> 1], BASE - 4 - byte0);
+    constexpr uint32_t k2 = 0x00030003u << BASE;
+    a = u32x4{wl & k2, wl & (k2 << 2), wh & k2, wh & (k2 << 2)};
   }
   return a;
 }
+// Key codes of 3 and 6 bits are a low run (2 / 4 bits, the first dwords of the lane's 32 channels) and a high run
+// (1 / 2 bits, the rest): two operands, multiplied by the query separately (the high run's query operand carries the
+// factor 2^LO).
+template <int BK> constexpr int k_lo() { return key_lo_bits<BK>(); }
+template <int BK> constexpr int k_hi() { return key_hi_bits<BK>(); }
+template <int BK> constexpr int k_hi_base() { return BK == 3 ? 5 : 6; }   // high run: single bits from bit 5, pairs from bit 6
 
 // ---- value codes: one lane holds, per 32-token step, 2*BV dwords (index = 4*piece + dword) ----
 // Register v (0..3) of d-tile dt's operand holds slots 2v, 2v+1 and is left at bit offset v_slot_shift(v)
@@ -146,8 +180,10 @@ template <int BK, int BV, int NCK = 1, int NCV = 1>
 constexpr int ring_stages() {
   constexpr int regs = 2 * BK + 2 * BV + 4;
   constexpr int base = regs <= 16 ? KVQ_STAGES : regs <= 20 ? 3 : 2;
-  constexpr int less = (NCK == 2 ? 2 : 0) + (NCV == 2 ? 1 : 0);   // a second column set costs registers (query operand,
-  return base - less >= 1 ? base - less : 1;                      // scale/zero entries, weights)
+  constexpr int less = (NCK == 2 ? 2 : 0) + (NCV == 2 ? 1 : 0)    // a second column set costs registers (query operand,
+                       + (key_hi_bits<BK>() ? 1 : 0)              // scale/zero entries, weights), so does a high run
+                       + (BK == 2 && regs >= 16 ? 1 : 0);         // (moved 2-bit fields: two shifted copies of a word live)
+  return base - less >= 1 ? base - less : 1;
 }
 
 // Everything one lane loads for one 32-token step (two 16-token tiles).
@@ -178,6 +214,34 @@ __device__ __forceinline__ u32x4 ld16(const uint8_t* p) {
 
 // WIDE (paged planes): `step` counts 32-token steps in plane order from the plane base, so the uniform part of the
 // address is formed in 64 bits; otherwise it counts inside the (b,h) stream that the bases point to.
+// N consecutive dwords of a key tile (4 N bytes per lane: the lane's 32 channels), non-temporal; the address is a
+// multiple of 4 N bytes only when N is a power of two (3- and 6-bit rows), so the vector types carry that alignment.
+template <int N> __device__ __forceinline__ void load_dwords(uint32_t* dst, const uint8_t* p) {
+  typedef uint32_t v2 __attribute__((ext_vector_type(2), aligned(8)));
+  typedef uint32_t v3 __attribute__((ext_vector_type(3), aligned(4)));
+  typedef uint32_t v4a8 __attribute__((ext_vector_type(4), aligned(8)));
+  if constexpr (N == 1) {
+    dst[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p));
+  } else if constexpr (N == 2) {
+    const v2 v = __builtin_nontemporal_load(reinterpret_cast<const v2*>(p));
+    dst[0] = v.x; dst[1] = v.y;
+  } else if constexpr (N == 3) {
+    const v3 v = __builtin_nontemporal_load(reinterpret_cast<const v3*>(p));
+    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z;
+  } else if constexpr (N == 6) {
+    const v4a8 v = __builtin_nontemporal_load(reinterpret_cast<const v4a8*>(p));
+    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+    load_dwords<2>(dst + 4, p + 16);
+  } else {
+    static_assert(N % 4 == 0, "key tile piece");
+#pragma unroll
+    for (int k = 0; k < N / 4; ++k) {
+      const u32x4 v = ld16(p + 16 * k);
+      dst[4 * k + 0] = v.x; dst[4 * k + 1] = v.y; dst[4 * k + 2] = v.z; dst[4 * k + 3] = v.w;
+    }
+  }
+}
+
 // lane_mask: ~0, or 0 for a refill past the wavefront's last step, which still issues its loads (every lane then reads
 // the first 16 bytes of each part of the step it is given: one cache line per load, the data is never used).  A load
 // that may or may not be issued sits behind a branch, and with a branch between the loads the compiler can no longer
@@ -190,20 +254,7 @@ __device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L,
   const uint8_t* mbase = WIDE ? L.meta_base + (step & (int64_t)(int32_t)L.meta_step_mask) * L.meta_mul : L.meta_base;
   const uint32_t ko = (WIDE ? 0u : (uint32_t)step * (512 * BK)) + (L.kc_off & lane_mask);
 #pragma unroll
-  for (int x4 = 0; x4 < 2; ++x4) {
-    const uint8_t* p = kbase + (ko + x4 * (256 * BK));
-    if (BK == 2) {
-      typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-      const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
-      r.kc[x4][0] = v.x; r.kc[x4][1] = v.y;
-    } else {
-#pragma unroll
-      for (int k = 0; k < BK / 4; ++k) {
-        const u32x4 v = ld16(p + 16 * k);
-        r.kc[x4][4 * k + 0] = v.x; r.kc[x4][4 * k + 1] = v.y; r.kc[x4][4 * k + 2] = v.z; r.kc[x4][4 * k + 3] = v.w;
-      }
-    }
-  }
+  for (int x4 = 0; x4 < 2; ++x4) load_dwords<BK>(r.kc[x4], kbase + (ko + x4 * (256 * BK)));
   // (every lane loads, for the same reason: lanes beyond the scale/zero bytes repeat the last 16 of them)
   if constexpr (BK != 16)
     r.meta = ld16(mbase + ((WIDE ? 0u : ((uint32_t)step & L.meta_step_mask) * L.meta_mul) + (L.meta_off & lane_mask)));
@@ -264,7 +315,7 @@ struct NoKSeq {};
 // again: v's own high part where low_part is 0, the exact rest where it is 1 — the same instructions in both.
 template <int BK>
 __device__ __forceinline__ void kseq_rebuild(KSeqState& ks, const LaneCtx& L, const float* qrow, float low_part) {
-  constexpr int NC = BK == 4 ? 2 : BK == 2 ? 4 : 1;          // classes of channels by k_chan_scale
+  constexpr int NC = BK == 8 ? 1 : 2;                        // classes of channels by k_chan_scale (even / odd)
   typedef __fp16 half2v __attribute__((ext_vector_type(2)));
   float zc[NC];
 #pragma unroll
@@ -313,10 +364,12 @@ __device__ __forceinline__ void kseq_rebuild(KSeqState& ks, const LaneCtx& L, co
 // KS: KSeqState for channel-wise keys (then NEWBLK marks the first step of a 64-token block: the query operands are
 // rebuilt from that block's scale/zero entries), NoKSeq otherwise.
 template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool MASKED, bool NEWBLK = false, typename KS = NoKSeq>
-__device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u32x4 (&qb)[NCK][4], const float (&qsum_u)[NCK],
+__device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u32x4 (&qb)[NCK][4],
+                                             const u32x4 (&qbh)[NCK][4], const float (&qsum_u)[NCK],
                                              float kappa, WaveState<NCV>& st, const LaneCtx& L, int step, int seq_len,
                                              KS& ks, const float* qrow = nullptr, float kseq_low = 0.f) {
   constexpr bool RAW = BK == 16;
+  constexpr int KLO = k_lo<BK>(), KHI = k_hi<BK>();   // qbh: the query operand of the high run (3- and 6-bit keys)
   constexpr bool KSEQ = !__is_same(KS, NoKSeq);
   constexpr int kSetStride = (16 / R) * 64;      // bytes between the scale/zero entries of a lane's groups in two sets
   uint32_t kmeta[NCK][8], vmeta[NCV][8];
@@ -360,8 +413,12 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
       float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int m = 0; m < 4; ++m) {                // two independent accumulation chains
-        d0 = mma<BF>(unpack_k<BK>(r.kc[0], m), qb[cs][m], d0);
-        d1 = mma<BF>(unpack_k<BK>(r.kc[1], m), qb[cs][m], d1);
+        d0 = mma<BF>(unpack_k<KLO>(r.kc[0], m), qb[cs][m], d0);
+        d1 = mma<BF>(unpack_k<KLO>(r.kc[1], m), qb[cs][m], d1);
+        if constexpr (KHI != 0) {
+          d0 = mma<BF>(unpack_k<KHI, k_hi_base<BK>()>(r.kc[0] + KLO, m), qbh[cs][m], d0);
+          d1 = mma<BF>(unpack_k<KHI, k_hi_base<BK>()>(r.kc[1] + KLO, m), qbh[cs][m], d1);
+        }
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -476,16 +533,7 @@ __device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, i
   uint32_t* meta = (uint32_t*)((uint8_t*)(is_v ? a.cache.v_meta : a.cache.k_meta) + (int64_t)bh * (is_v ? g.vm_stream : g.km_stream));
   if ((lane16 & (lpg - 1)) == 0) meta[meta_index(t, lane16 >> lpg_shift(lpg), ng)] = (uint32_t)S | ((uint32_t)Z << 16);
   if (!is_v) {
-    uint8_t* rowp = (uint8_t*)a.cache.k_codes + (int64_t)bh * g.kc_stream + t * (16 * BK);
-    uint32_t w0 = 0, w1 = 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      if (BK == 8) { if (e < 4) w0 |= codes[e] << (8 * e); else w1 |= codes[e] << (8 * (e - 4)); }
-      else w0 |= codes[e] << (BK * e);
-    }
-    if (BK == 4) reinterpret_cast<uint32_t*>(rowp)[lane16] = w0;
-    else if (BK == 2) reinterpret_cast<uint16_t*>(rowp)[lane16] = (uint16_t)w0;
-    else reinterpret_cast<uint2*>(rowp)[lane16] = make_uint2(w0, w1);
+    store_key_codes<BK>((uint8_t*)a.cache.k_codes + (int64_t)bh * g.kc_stream + t * (16 * BK), lane16, codes);
   } else {
 #pragma unroll
     for (int e = 0; e < 8; ++e) vstage[d0 + e] = (uint8_t)codes[e];
@@ -711,7 +759,9 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   };
   // column c of set cs carries head h restricted to key group grp + cs*kSetGroups (zero elsewhere); this lane's 32
   // channels are 32j..32j+31 and lie in one group
+  constexpr int KLO = k_lo<BK>(), KHI = k_hi<BK>();
   u32x4 qb[NCK][4];
+  u32x4 qbh[NCK][4];                             // operand of the high run of 3- and 6-bit key codes (else unused)
   float qsum_u[NCK];
   {
     uint16_t mych[32];
@@ -729,16 +779,21 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       const bool mine = act && ((32 * L.j) / g.g_k == gcs);
 #pragma unroll
       for (int m = 0; m < 4; ++m) {
-        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        uint32_t w[4] = {0u, 0u, 0u, 0u}, wh[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          const uint16_t bits = mych[k_slot_elem<BK>(m, i)];
+          const uint16_t bits = mych[k_slot_elem<KLO>(m, i)];
           uint32_t e;                              // unquantized: the query's own 16-bit pattern (same type as the cache)
           if constexpr (RAW) e = bits;
-          else e = __builtin_bit_cast(uint16_t, (_Float16)(widen(bits) / k_slot_scale<BK>(i)));
+          else e = __builtin_bit_cast(uint16_t, (_Float16)(widen(bits) / k_slot_scale<KLO>(i)));
           if (mine) w[i >> 1] |= e << (16 * (i & 1));
+          if constexpr (KHI != 0) {                // high run: its own slot order, and the codes' factor 2^LO
+            const float qh = widen(mych[k_slot_elem<KHI>(m, i)]) * ((float)(1 << KLO) / k_slot_scale<KHI, k_hi_base<BK>()>(i));
+            if (mine) wh[i >> 1] |= (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)qh) << (16 * (i & 1));
+          }
         }
         qb[cs][m] = u32x4{w[0], w[1], w[2], w[3]};
+        qbh[cs][m] = u32x4{wh[0], wh[1], wh[2], wh[3]};
       }
       float qsum = 0.f;
       if constexpr (!RAW) { if (act) qsum = sm_qsum[h][gcs]; }
@@ -766,10 +821,10 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   auto full_step = [&](int k, int i) {
     if constexpr (KSEQ) {                        // an even step of this wavefront's sequence starts a block (uniform;
       const int odd = kStages % 2 == 0 ? (k & 1) : (i & 1);      // with an even ring it is the ring slot's parity)
-      if (odd) compute_step<BK, BV, R, BF, NCK, NCV, false, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
-      else compute_step<BK, BV, R, BF, NCK, NCV, false, true>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks, qrow, grp == 1 ? 1.0f : 0.0f);
+      if (odd) compute_step<BK, BV, R, BF, NCK, NCV, false, false>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
+      else compute_step<BK, BV, R, BF, NCK, NCV, false, true>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), seq_len, ks, qrow, grp == 1 ? 1.0f : 0.0f);
     } else {
-      compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
+      compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
     }
   };
   int it = 0;
@@ -786,7 +841,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   if constexpr (!KSEQ) {
     if (own_tail) {                               // ragged last step of the sequence: masked
       fetch(buf[0], n_steps - 1);
-      compute_step<BK, BV, R, BF, NCK, NCV, true>(buf[0], qb, qsum_u, kappa, st, L, n_steps - 1, seq_len, ks);
+      compute_step<BK, BV, R, BF, NCK, NCV, true>(buf[0], qb, qbh, qsum_u, kappa, st, L, n_steps - 1, seq_len, ks);
     }
   }
 
@@ -958,14 +1013,17 @@ hipError_t KVQ_CAT(launch_decode_inst_, KVQ_INST_BK, KVQ_INST_BV)(int R, const D
 #if KVQ_INST_BK == 16
   return a.g.raw_dtype == KVQ_BF16 ? launch_r<16, 16, true>(R, a, plan, stream) : launch_r<16, 16, false>(R, a, plan, stream);
 #else
+#if KVQ_INST_BK == 2 || KVQ_INST_BK == 4 || KVQ_INST_BK == 8
   if (a.g.axis_k == KVQ_AXIS_SEQ) return launch_r<KVQ_INST_BK, KVQ_INST_BV, false, true>(R, a, plan, stream);
+#endif
   return launch_r<KVQ_INST_BK, KVQ_INST_BV>(R, a, plan, stream);
 #endif
 }
 
 #else
 // ---- dispatcher translation unit ----------------------------------------------------------------------------------------
-#define KVQ_FOR_EACH_PAIR(X) X(4, 2) X(2, 4) X(4, 4) X(8, 8) X(2, 2) X(8, 4) X(8, 2) X(4, 8) X(2, 8) X(16, 16)
+#define KVQ_FOR_EACH_PAIR(X) X(4, 2) X(2, 4) X(4, 4) X(8, 8) X(2, 2) X(8, 4) X(8, 2) X(4, 8) X(2, 8) X(16, 16) \
+  X(3, 2) X(3, 4) X(3, 8) X(6, 2) X(6, 4) X(6, 8) X(1, 2) X(1, 4) X(1, 8)
 #define KVQ_DECL(BK_, BV_) \
   hipError_t KVQ_CAT(launch_decode_inst_, BK_, BV_)(int R, const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream);
 KVQ_FOR_EACH_PAIR(KVQ_DECL)

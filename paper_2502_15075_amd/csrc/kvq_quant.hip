@@ -143,18 +143,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         const int lpg = g.g_k >> 3;
         quantize8(x, g.qbits_k, lpg, codes, &S, &Z);
         if ((lane16 & (lpg - 1)) == 0) km[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_k)] = (uint32_t)S | ((uint32_t)Z << 16);
-        uint8_t* rowp = kc + t * (16 * BK);
-        if (BK == 8) {
-          uint32_t w0 = codes[0] | (codes[1] << 8) | (codes[2] << 16) | (codes[3] << 24);
-          uint32_t w1 = codes[4] | (codes[5] << 8) | (codes[6] << 16) | (codes[7] << 24);
-          reinterpret_cast<uint2*>(rowp)[lane16] = make_uint2(w0, w1);
-        } else {
-          uint32_t w = 0;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) w |= codes[e] << (BK * e);
-          if (BK == 4) reinterpret_cast<uint32_t*>(rowp)[lane16] = w;
-          else reinterpret_cast<uint16_t*>(rowp)[lane16] = (uint16_t)w;
-        }
+        store_key_codes<BK>(kc + t * (16 * BK), lane16, codes);
       }
     }
     // ---- values: scale/zero straight to memory, codes to their place in the staged words
@@ -183,25 +172,6 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
   store_value_words<BV>(vc, vstage, tid, lo, hi);
 }
 
-// The 8 codes of channels 8*oct .. 8*oct+7 of key row t: B consecutive bytes of the row-major bit string.
-template <int B> __device__ __forceinline__ void key_codes8(const uint8_t* cs, int64_t t, int oct, uint32_t code[8]) {
-  const uint8_t* p = cs + t * (16 * B) + oct * B;
-  if (B == 16) {
-    const uint4 w = *reinterpret_cast<const uint4*>(p);
-    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) code[e] = (ww[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-  } else if (B == 8) {
-    const uint2 w = *reinterpret_cast<const uint2*>(p);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) code[e] = ((e < 4 ? w.x : w.y) >> (8 * (e & 3))) & 0xFFu;
-  } else {
-    const uint32_t w = B == 4 ? *reinterpret_cast<const uint32_t*>(p) : (uint32_t)*reinterpret_cast<const uint16_t*>(p);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) code[e] = (w >> (B * e)) & ((1u << B) - 1u);
-  }
-}
-
 // The 8 codes of channels d0 .. d0+7 (d0 a multiple of 8) of value row t: the same field of 8 words 16 bytes apart.
 template <int B> __device__ __forceinline__ void value_codes8(const uint8_t* cs, int64_t t, int d0, uint32_t code[8]) {
   int dw, bit;
@@ -209,22 +179,6 @@ template <int B> __device__ __forceinline__ void value_codes8(const uint8_t* cs,
   const uint32_t* blk = reinterpret_cast<const uint32_t*>(cs + (t >> 5) * (int64_t)(512 * B)) + dw;
 #pragma unroll
   for (int e = 0; e < 8; ++e) code[e] = (blk[4 * e] >> bit) & (B == 16 ? 0xFFFFu : ((1u << B) - 1u));
-}
-
-// Pack the 8 codes of channels 8*lane16 .. +7 of one key row into the row-major bit string.
-template <int BK>
-__device__ __forceinline__ void store_key_codes(uint8_t* rowp, int lane16, const uint32_t codes[8]) {
-  if (BK == 8) {
-    const uint32_t w0 = codes[0] | (codes[1] << 8) | (codes[2] << 16) | (codes[3] << 24);
-    const uint32_t w1 = codes[4] | (codes[5] << 8) | (codes[6] << 16) | (codes[7] << 24);
-    reinterpret_cast<uint2*>(rowp)[lane16] = make_uint2(w0, w1);
-  } else {
-    uint32_t w = 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) w |= codes[e] << (BK * e);
-    if (BK == 4) reinterpret_cast<uint32_t*>(rowp)[lane16] = w;
-    else reinterpret_cast<uint16_t*>(rowp)[lane16] = (uint16_t)w;
-  }
 }
 
 // Channel-wise keys (Sec. 4 "Downstream Task Accuracy": the per-column back-end with its residual buffer).
@@ -368,11 +322,15 @@ __device__ __forceinline__ void reconstruct8(const Geom& g, const kvq_cache& c, 
       default: value_codes8<16>(cs, t, d0, code); break;
     }
   } else {
+    const uint8_t* rowp = cs + t * (16 * b);
     switch (b) {
-      case 2: key_codes8<2>(cs, t, d0 >> 3, code); break;
-      case 4: key_codes8<4>(cs, t, d0 >> 3, code); break;
-      case 8: key_codes8<8>(cs, t, d0 >> 3, code); break;
-      default: key_codes8<16>(cs, t, d0 >> 3, code); break;
+      case 1: load_key_codes<1>(rowp, d0 >> 3, code); break;
+      case 2: load_key_codes<2>(rowp, d0 >> 3, code); break;
+      case 3: load_key_codes<3>(rowp, d0 >> 3, code); break;
+      case 4: load_key_codes<4>(rowp, d0 >> 3, code); break;
+      case 6: load_key_codes<6>(rowp, d0 >> 3, code); break;
+      case 8: load_key_codes<8>(rowp, d0 >> 3, code); break;
+      default: load_key_codes<16>(rowp, d0 >> 3, code); break;
     }
   }
   if (b == 16) {
@@ -517,8 +475,11 @@ hipError_t launch_quantize_append(const Geom& g, const kvq_cache& c, const void*
                                   int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
   if (n_new == 0) return hipSuccess;
   switch (g.bits_k) {
+    case 1: return launch_qk<1>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 2: return launch_qk<2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 3: return launch_qk<3>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 4: return launch_qk<4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 6: return launch_qk<6>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 8: return launch_qk<8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 16: return launch_qk<16>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
   }

@@ -27,6 +27,76 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
   return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
+// ---- key rows ------------------------------------------------------------------------------------------------------------
+// A key row takes 16 b bytes.  Widths 1, 2, 4, 8 (and 16-bit patterns): channel d at bits [d b, (d+1) b) of the row read
+// as a little-endian bit string.  Widths 3 and 6 keep a power-of-two low part and the rest of every code in two runs:
+// the row is cut into chunks of 32 channels (4 b bytes); with LO = 2 (b = 3) or 4 (b = 6) and HI = b - LO, channel x
+// of a chunk has code mod 2^LO at bits [x LO, (x+1) LO) of the chunk and code >> LO at bits 32 LO + [x HI, (x+1) HI).
+// (The attention kernel multiplies the two runs by the query separately: each is a field width it can unpack with
+// one AND per two codes.)
+template <int B> __host__ __device__ constexpr int key_lo_bits() { return B == 3 ? 2 : B == 6 ? 4 : B; }
+template <int B> __host__ __device__ constexpr int key_hi_bits() { return B - key_lo_bits<B>(); }
+
+// n-bit fields of the 8 codes, first code lowest
+template <int N> __device__ __forceinline__ uint32_t pack8(const uint32_t codes[8], int shift) {
+  uint32_t w = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) w |= ((codes[e] >> shift) & ((1u << N) - 1u)) << (N * e);
+  return w;
+}
+template <int NBYTES> __device__ __forceinline__ void store_bytes(uint8_t* p, uint32_t w) {
+  if (NBYTES == 1) *p = (uint8_t)w;
+  else if (NBYTES == 2) *reinterpret_cast<uint16_t*>(p) = (uint16_t)w;
+  else *reinterpret_cast<uint32_t*>(p) = w;
+}
+template <int NBYTES> __device__ __forceinline__ uint32_t load_bytes(const uint8_t* p) {
+  if (NBYTES == 1) return *p;
+  if (NBYTES == 2) return *reinterpret_cast<const uint16_t*>(p);
+  return *reinterpret_cast<const uint32_t*>(p);
+}
+
+// Store the 8 codes of channels 8*lane16 .. 8*lane16+7 of one key row (rowp: first byte of the row).
+template <int BK>
+__device__ __forceinline__ void store_key_codes(uint8_t* rowp, int lane16, const uint32_t codes[8]) {
+  constexpr int LO = key_lo_bits<BK>(), HI = key_hi_bits<BK>();
+  if constexpr (BK == 8) {
+    const uint32_t w0 = codes[0] | (codes[1] << 8) | (codes[2] << 16) | (codes[3] << 24);
+    const uint32_t w1 = codes[4] | (codes[5] << 8) | (codes[6] << 16) | (codes[7] << 24);
+    reinterpret_cast<uint2*>(rowp)[lane16] = make_uint2(w0, w1);
+  } else if constexpr (HI == 0) {
+    store_bytes<BK>(rowp + lane16 * BK, pack8<BK>(codes, 0));              // 8 codes of b bits = b bytes
+  } else {
+    uint8_t* chunk = rowp + (lane16 >> 2) * (4 * BK);                      // 4 lanes = 32 channels = one chunk
+    store_bytes<LO>(chunk + (lane16 & 3) * LO, pack8<LO>(codes, 0));
+    store_bytes<HI>(chunk + 4 * LO + (lane16 & 3) * HI, pack8<HI>(codes, LO));
+  }
+}
+
+// The 8 codes of channels 8*oct .. 8*oct+7 of a key row.
+template <int B> __device__ __forceinline__ void load_key_codes(const uint8_t* rowp, int oct, uint32_t code[8]) {
+  constexpr int LO = key_lo_bits<B>(), HI = key_hi_bits<B>();
+  if constexpr (B == 16) {
+    const uint4 w = *reinterpret_cast<const uint4*>(rowp + oct * 16);
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) code[e] = (ww[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+  } else if constexpr (B == 8) {
+    const uint2 w = *reinterpret_cast<const uint2*>(rowp + oct * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) code[e] = ((e < 4 ? w.x : w.y) >> (8 * (e & 3))) & 0xFFu;
+  } else if constexpr (HI == 0) {
+    const uint32_t w = load_bytes<B>(rowp + oct * B);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) code[e] = (w >> (B * e)) & ((1u << B) - 1u);
+  } else {
+    const uint8_t* chunk = rowp + (oct >> 2) * (4 * B);
+    const uint32_t lo = load_bytes<LO>(chunk + (oct & 3) * LO), hi = load_bytes<HI>(chunk + 4 * LO + (oct & 3) * HI);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      code[e] = ((lo >> (LO * e)) & ((1u << LO) - 1u)) | (((hi >> (HI * e)) & ((1u << HI) - 1u)) << LO);
+  }
+}
+
 // ---- randomized Hadamard rotation of a 128-channel row (Sec. 4 "Integration with Rotation-Based Methods") ----
 // The row is held 8 consecutive channels per lane by 16 neighbouring lanes (lane16 = channel / 8).  R = H diag(s) /
 // sqrt(128): signs, then the butterflies over strides 1, 2, 4 (inside the lane) and 8, 16, 32, 64 (partner lane

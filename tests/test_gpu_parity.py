@@ -845,10 +845,11 @@ def test_value_rotation_fused_decode_steps(kvq, oracle):
 
 # --------------------------------------------------------------------------- 1-, 3- and 6-bit quantizer widths
 
-@pytest.mark.parametrize("bk,bv", [(3, 2), (6, 3), (1, 6), (3, 3), (4, 1)])
+@pytest.mark.parametrize("bk,bv", [(3, 2), (6, 3), (1, 6), (3, 3), (4, 1), (6, 4), (1, 2), (3, 8), (6, 2)])
 def test_odd_quantizer_widths(kvq, oracle, bk, bv):
-    """Widths 1, 3, 6 (the per-column back-end's grid, Table 1's 3-bit keys): 2^b - 1 steps, codes in the next
-    power-of-two field.  Planes byte-identical, reconstruction bit-identical, attention within tolerance, fused steps."""
+    """Widths 1, 3, 6 (the per-column back-end's grid, Table 1's 3-bit keys): 2^b - 1 steps; key rows at their own
+    width (3 and 6 bits as a low and a high run per 32 channels), value codes in the next power-of-two field.
+    Planes byte-identical, reconstruction bit-identical, attention within tolerance, fused steps."""
     B, H, R, T0 = 2, 2, 4, 200
     T = T0 + 3
     K, V, q = synth.make_kvq(200 + 10 * bk + bv, B, H, H * R, T, dtype=torch.bfloat16)
@@ -880,6 +881,30 @@ def test_odd_quantizer_widths(kvq, oracle, bk, bv):
         assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
 
 
+@pytest.mark.parametrize("R", [1, 2, 8])
+@pytest.mark.parametrize("bk,bv,gk,gv", [(3, 2, 64, 64), (6, 4, 32, 128), (1, 2, 128, 64), (3, 4, 32, 32)])
+def test_packed_odd_width_keys_attention(kvq, oracle, R, bk, bv, gk, gv):
+    """3- and 6-bit key rows are a low and a high run, which the kernel multiplies by the query separately; 1-bit rows
+    a bit string.  Head ratios 1, 2, 8, all group sizes (two column sets included), long enough for several splits,
+    ragged lengths, per-sequence lengths."""
+    B, H, T = 2, 2, 2500
+    K, V, q = synth.make_kvq(900 + 10 * bk + R, B, H, H * R, T, dtype=torch.float16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, 1000), (1000, T)])
+    _assert_planes_equal(cache, planes)
+    for seq_len in (T, 2049, 31):
+        out = _decode(kvq, Lg, cache, q, seq_len)
+        ref = oracle.decode_attention(Lo, planes, q.numpy(), seq_len, 1 / math.sqrt(128))
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, seq_len
+    lens = np.array([T, 777], dtype=np.int32)
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, T)), dtype=torch.uint8, device="cuda")
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    kvq.decode_attention_varlen(Lg, cache, q.cuda(), torch.from_numpy(lens).cuda(), T, 1 / math.sqrt(128), out, ws)
+    torch.cuda.synchronize()
+    ref = oracle.decode_attention_varlen(Lo, planes, q.numpy(), lens, 1 / math.sqrt(128))
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+
+
 # --------------------------------------------------------------------------- paged planes
 
 def _paged_setup(kvq, oracle, B, H, T, bk, bv, gk, gv, P, seed, raw=0, extra_pages=3):
@@ -909,7 +934,8 @@ def _assert_paged_equal(oracle, Lo, cache, planes, table, P, n_pages):
             assert (p.reshape(n_pages, -1)[~used] == 0xA5).all()
 
 
-@pytest.mark.parametrize("bk,bv,gk,gv,P", [(4, 2, 64, 64, 64), (2, 4, 32, 128, 256), (8, 8, 64, 64, 128), (16, 16, 64, 64, 64)])
+@pytest.mark.parametrize("bk,bv,gk,gv,P", [(4, 2, 64, 64, 64), (2, 4, 32, 128, 256), (8, 8, 64, 64, 128), (16, 16, 64, 64, 64),
+                                           (3, 2, 64, 64, 64), (1, 4, 128, 32, 128)])
 def test_paged_append_and_reconstruction(kvq, oracle, bk, bv, gk, gv, P):
     B, H, T = 3, 2, 333
     K, V, _ = synth.make_kvq(210 + bk, B, H, H, T, dtype=torch.bfloat16)
@@ -936,7 +962,7 @@ def test_paged_append_and_reconstruction(kvq, oracle, bk, bv, gk, gv, P):
 
 
 @pytest.mark.parametrize("R,bk,bv,gk,gv,P", [(4, 4, 2, 64, 64, 64), (8, 4, 2, 32, 64, 256), (1, 2, 4, 64, 128, 128), (8, 8, 8, 64, 64, 64),
-                                             (5, 16, 16, 64, 64, 64)])
+                                             (5, 16, 16, 64, 64, 64), (8, 3, 2, 64, 64, 128), (2, 6, 4, 32, 64, 64)])
 def test_paged_attention(kvq, oracle, R, bk, bv, gk, gv, P):
     """Attention over pool pages found through a shuffled page table: uniform and per-sequence lengths, several
     sequence splits, and fused steps that run across a page boundary."""
