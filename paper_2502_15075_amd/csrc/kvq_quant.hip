@@ -322,16 +322,14 @@ __device__ __forceinline__ void reconstruct8(const Geom& g, const kvq_cache& c, 
       default: value_codes8<16>(cs, t, d0, code); break;
     }
   } else {
-    const uint8_t* rowp = cs + t * (16 * b);
-    switch (b) {
-      case 1: load_key_codes<1>(rowp, d0 >> 3, code); break;
-      case 2: load_key_codes<2>(rowp, d0 >> 3, code); break;
-      case 3: load_key_codes<3>(rowp, d0 >> 3, code); break;
-      case 4: load_key_codes<4>(rowp, d0 >> 3, code); break;
-      case 6: load_key_codes<6>(rowp, d0 >> 3, code); break;
-      case 8: load_key_codes<8>(rowp, d0 >> 3, code); break;
-      default: load_key_codes<16>(rowp, d0 >> 3, code); break;
-    }
+    // (the common widths first: the chain is walked once per row and tensor)
+    if (b == 4) load_key_codes<4>(cs + t * 64, d0 >> 3, code);
+    else if (b == 2) load_key_codes<2>(cs + t * 32, d0 >> 3, code);
+    else if (b == 8) load_key_codes<8>(cs + t * 128, d0 >> 3, code);
+    else if (b == 16) load_key_codes<16>(cs + t * 256, d0 >> 3, code);
+    else if (b == 3) load_key_codes<3>(cs + t * 48, d0 >> 3, code);
+    else if (b == 6) load_key_codes<6>(cs + t * 96, d0 >> 3, code);
+    else load_key_codes<1>(cs + t * 16, d0 >> 3, code);
   }
   if (b == 16) {
     const bool raw_bf16 = g.raw_dtype == KVQ_BF16;

@@ -37,11 +37,16 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
 template <int B> __host__ __device__ constexpr int key_lo_bits() { return B == 3 ? 2 : B == 6 ? 4 : B; }
 template <int B> __host__ __device__ constexpr int key_hi_bits() { return B - key_lo_bits<B>(); }
 
-// n-bit fields of the 8 codes, first code lowest
-template <int N> __device__ __forceinline__ uint32_t pack8(const uint32_t codes[8], int shift) {
+// n-bit fields of the 8 codes, first code lowest: bits [shift, shift + N) of every code (MASK: the codes have bits
+// above shift + N; otherwise nothing needs to be cut off)
+template <int N, bool MASK> __device__ __forceinline__ uint32_t pack8(const uint32_t codes[8], int shift) {
   uint32_t w = 0;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) w |= ((codes[e] >> shift) & ((1u << N) - 1u)) << (N * e);
+  for (int e = 0; e < 8; ++e) {
+    uint32_t c = codes[e] >> shift;
+    if (MASK) c &= (1u << N) - 1u;
+    w |= c << (N * e);
+  }
   return w;
 }
 template <int NBYTES> __device__ __forceinline__ void store_bytes(uint8_t* p, uint32_t w) {
@@ -64,11 +69,11 @@ __device__ __forceinline__ void store_key_codes(uint8_t* rowp, int lane16, const
     const uint32_t w1 = codes[4] | (codes[5] << 8) | (codes[6] << 16) | (codes[7] << 24);
     reinterpret_cast<uint2*>(rowp)[lane16] = make_uint2(w0, w1);
   } else if constexpr (HI == 0) {
-    store_bytes<BK>(rowp + lane16 * BK, pack8<BK>(codes, 0));              // 8 codes of b bits = b bytes
+    store_bytes<BK>(rowp + lane16 * BK, pack8<BK, false>(codes, 0));              // 8 codes of b bits = b bytes
   } else {
     uint8_t* chunk = rowp + (lane16 >> 2) * (4 * BK);                      // 4 lanes = 32 channels = one chunk
-    store_bytes<LO>(chunk + (lane16 & 3) * LO, pack8<LO>(codes, 0));
-    store_bytes<HI>(chunk + 4 * LO + (lane16 & 3) * HI, pack8<HI>(codes, LO));
+    store_bytes<LO>(chunk + (lane16 & 3) * LO, pack8<LO, true>(codes, 0));
+    store_bytes<HI>(chunk + 4 * LO + (lane16 & 3) * HI, pack8<HI, false>(codes, LO));
   }
 }
 
