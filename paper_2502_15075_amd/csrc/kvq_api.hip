@@ -261,6 +261,11 @@ kvq_status kvq_reconstruction_error(const kvq_layout* layout, const kvq_cache* c
   return e == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
 }
 
+kvq_status kvq_selftest_quantizer(uint32_t* counters, void* stream) {
+  if (!counters || (reinterpret_cast<uintptr_t>(counters) & 7u)) return KVQ_ERR_INVALID_ARG;
+  return kvq::launch_selftest_quantizer(counters, (hipStream_t)stream) == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
+}
+
 const char* kvq_status_string(kvq_status status) {
   switch (status) {
     case KVQ_OK: return "ok";

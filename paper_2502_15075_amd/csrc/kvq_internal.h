@@ -108,6 +108,7 @@ hipError_t launch_seq_append(const Geom& g, const kvq_cache& c, const void* k_ne
                              int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream);
 hipError_t launch_dequantize(const Geom& g, const kvq_cache& c, int32_t t0, int32_t t1, void* k_out, void* v_out,
                              int out_dtype, hipStream_t stream);
+hipError_t launch_selftest_quantizer(uint32_t* counters, hipStream_t stream);
 hipError_t launch_reconstruction_error(const Geom& g, const kvq_cache& c, const void* k_ref, const void* v_ref,
                                        int ref_dtype, int64_t sb, int64_t sh, int64_t st, int32_t t0, int32_t t1,
                                        double* sums, hipStream_t stream);

@@ -274,7 +274,7 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
     group_scale_zero(lo_v, hi_v, BK, &S, &Z);
     if (rg == 0) km[d0 + e] = (uint32_t)S | ((uint32_t)Z << 16);
     const float sc = widen16(S, false), z = widen16(Z, false);
-    const float rcp = 1.0f / sc;
+    const float rcp = sc == 0.0f ? 0.0f : rcp_scale(sc);      // (unused when the scale is 0)
 #pragma unroll
     for (int it = 0; it < 4; ++it) codes[it][e] = group_code(x[it][e], sc, z, rcp, levels);
   }
@@ -435,6 +435,32 @@ __global__ __launch_bounds__(256) void sq_error_kernel(Geom g, kvq_cache c, cons
   }
 }
 
+// Checks the quantizer's fast divisions on the device it runs on: counters[0] counts the binary16 scales whose fast
+// reciprocal differs from IEEE division (all 31743 positive finite patterns), counters[1] the sampled quotients
+// (2^24 numerators per level count, spread over the binary32 exponent range) that differ.
+__global__ __launch_bounds__(256) void selftest_quantizer_kernel(uint32_t* counters) {
+#pragma clang fp contract(off)
+  const uint32_t u = blockIdx.x * 256 + threadIdx.x;          // 0 .. 65535
+  uint32_t bad_rcp = 0, bad_div = 0;
+  if (u >= 1 && u < 0x7C00) {
+    const float s = widen16((uint16_t)u, false);
+    if (rcp_scale(s) != 1.0f / s) bad_rcp = 1;
+  }
+  const int widths[6] = {1, 2, 3, 4, 6, 8};
+  for (uint32_t i = 0; i < 256; ++i) {
+    const uint32_t bits = (uint32_t)(((uint64_t)(u * 256u + i) * 0x7F800000ull) >> 24);   // every 128th binary32 >= 0
+    const float x = __uint_as_float(bits);
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+      const float levels = (float)((1 << widths[k]) - 1);
+      const float fast = div_levels(x, levels, inv_levels(widths[k])), exact = x / levels;
+      if (fast != exact || f32_to_f16_bits(fast) != f32_to_f16_bits(exact)) ++bad_div;
+    }
+  }
+  if (bad_rcp) atomicAdd(counters, bad_rcp);
+  if (bad_div) atomicAdd(counters + 1, bad_div);
+}
+
 __global__ __launch_bounds__(256) void zero_f64_kernel(double* p, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = 0.0;
@@ -539,6 +565,12 @@ hipError_t launch_dequantize(const Geom& g, const kvq_cache& c, int32_t t0, int3
   const int64_t blocks = (total + 255) / 256;
   if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;      // more than one launch can take: the caller splits [t0, t1)
   hipLaunchKernelGGL(dequantize_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, g, c, t0, t1, k_out, v_out, out_dtype);
+  return hipGetLastError();
+}
+
+hipError_t launch_selftest_quantizer(uint32_t* counters, hipStream_t stream) {
+  hipLaunchKernelGGL(zero_f64_kernel, dim3(1), dim3(256), 0, stream, (double*)counters, (int64_t)1);   // 8 bytes = 2 counters
+  hipLaunchKernelGGL(selftest_quantizer_kernel, dim3(256), dim3(256), 0, stream, counters);
   return hipGetLastError();
 }
 

@@ -180,6 +180,35 @@ __device__ __forceinline__ float lane_dpp(float x) {
   return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
 }
 
+// ---- the two divisions of the quantizer, correctly rounded in three operations each ---------------------------------
+// (mx - mn) / levels with levels = 2^b - 1 in {1, 3, 7, 15, 63, 255}: with c = RN(1 / levels), q0 = RN(x c),
+// r = x - levels q0 (one fused multiply-add, exact), q1 = RN(q0 + r c) is the correctly rounded quotient (the classical
+// correction step for a correctly rounded reciprocal; checked against IEEE division for every non-negative finite
+// binary32 x and each of these divisors on a CPU).
+__device__ __forceinline__ float inv_levels(int bits) {
+  return bits == 4 ? 1.0f / 15.0f : bits == 2 ? 1.0f / 3.0f : bits == 8 ? 1.0f / 255.0f
+       : bits == 3 ? 1.0f / 7.0f : bits == 6 ? 1.0f / 63.0f : 1.0f;          // (constants: rounded by the compiler)
+}
+__device__ __forceinline__ float div_levels(float x, float levels, float c) {
+  const float q0 = x * c;
+  const float r = __builtin_fmaf(-levels, q0, x);
+  float q1 = __builtin_fmaf(r, c, q0);
+  // The quotient is rounded to binary32 here and to binary16 afterwards.  Left to itself the compiler merges this
+  // multiply-add with the conversion that follows into one mixed-precision instruction, which rounds the exact sum
+  // once, straight to binary16, and lands on the other side of a tie: the value is made opaque so that it cannot.
+  asm("" : "+v"(q1));
+  return q1;
+}
+// 1 / s for a stored scale s (a positive binary16 value widened to binary32): one refinement of the hardware's
+// reciprocal approximation, y1 = y0 + y0 (1 - s y0).  This is the correctly rounded reciprocal for every one of the
+// 31743 possible scales on gfx950 (kvq_selftest_quantizer checks exactly that on the device it runs on); it is not for
+// arbitrary binary32 inputs.
+__device__ __forceinline__ float rcp_scale(float s) {
+  const float y0 = __builtin_amdgcn_rcpf(s);
+  const float e = __builtin_fmaf(-s, y0, 1.0f);
+  return __builtin_fmaf(e, y0, y0);
+}
+
 // Quantize 8 consecutive elements held by this lane; the group spans `lanes_per_group`
 // neighbouring lanes (a power of two <= 16, aligned).  Returns the 8 codes, and the stored
 // scale/zero patterns through S, Z.
@@ -196,7 +225,7 @@ __device__ __forceinline__ void quantize8(const float x[8], int bits, int lanes_
   if (lanes_per_group >= 16) { mn = min2f(mn, lane_dpp<0x140>(mn)); mx = max2f(mx, lane_dpp<0x140>(mx)); }  // row_mirror
   if (mn == 0.0f) mn = 0.0f;  // -0 -> +0
   const float levels = (float)((1 << bits) - 1);
-  float s32 = (mx - mn) / levels;
+  float s32 = div_levels(mx - mn, levels, inv_levels(bits));
   uint16_t sb = f32_to_f16_bits(s32);
   if ((sb & 0x7FFFu) == 0) sb = 0;
   uint16_t zb = f32_to_f16_bits(mn);
@@ -207,7 +236,7 @@ __device__ __forceinline__ void quantize8(const float x[8], int bits, int lanes_
     for (int e = 0; e < 8; ++e) codes[e] = 0;
     return;
   }
-  float rcp = 1.0f / s;
+  float rcp = rcp_scale(s);
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     float t = (x[e] - z) * rcp;
@@ -223,7 +252,7 @@ __device__ __forceinline__ void group_scale_zero(float mn, float mx, int bits, u
 #pragma clang fp contract(off)
   if (mn == 0.0f) mn = 0.0f;  // -0 -> +0
   const float levels = (float)((1 << bits) - 1);
-  const float s32 = (mx - mn) / levels;
+  const float s32 = div_levels(mx - mn, levels, inv_levels(bits));
   uint16_t sb = f32_to_f16_bits(s32);
   if ((sb & 0x7FFFu) == 0) sb = 0;
   *S = sb;

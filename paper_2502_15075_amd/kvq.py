@@ -68,11 +68,12 @@ def load():
                                        C.c_void_p, C.c_int, C.c_void_p]
         lib.kvq_reconstruction_error.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int,
                                                  C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        lib.kvq_selftest_quantizer.argtypes = [C.c_void_p, C.c_void_p]
         lib.kvq_status_string.argtypes = [C.c_int]
         lib.kvq_status_string.restype = C.c_char_p
         for f in ("kvq_cache_bytes", "kvq_residual_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
                   "kvq_decode_step", "kvq_dequantize", "kvq_reconstruction_error", "kvq_decode_attention_varlen",
-                  "kvq_decode_step_varlen"):
+                  "kvq_decode_step_varlen", "kvq_selftest_quantizer"):
             getattr(lib, f).restype = C.c_int
         _lib = lib
     return _lib
@@ -224,6 +225,14 @@ def reconstruction_error(layout: Layout, cache: Cache, k_ref, v_ref, t0: int, su
                                          ref.stride(1), ref.stride(2), t0, t0 + ref.shape[2], _p(sums), _stream_ptr())
     _check(st, "kvq_reconstruction_error")
     return sums
+
+
+def selftest_quantizer(counters: torch.Tensor) -> torch.Tensor:
+    """counters: int32/uint32 device tensor of 2 elements, overwritten with the numbers of scales and of sampled quotients
+    whose fast division differs from IEEE division on this device (both must be 0)."""
+    assert counters.numel() == 2 and counters.element_size() == 4 and counters.is_contiguous()
+    _check(load().kvq_selftest_quantizer(_p(counters), _stream_ptr()), "kvq_selftest_quantizer")
+    return counters
 
 
 def decode_attention_varlen(layout: Layout, cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,

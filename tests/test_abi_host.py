@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported(kvq):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(kvq_[a-z_]+)\s*\(", header))
     assert {"kvq_cache_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
-            "kvq_decode_step", "kvq_dequantize", "kvq_reconstruction_error", "kvq_residual_bytes",
+            "kvq_decode_step", "kvq_dequantize", "kvq_reconstruction_error", "kvq_residual_bytes", "kvq_selftest_quantizer",
             "kvq_decode_attention_varlen", "kvq_decode_step_varlen", "kvq_status_string"} <= declared
     lib = C.CDLL(kvq.LIB_PATH)
     for name in declared:

@@ -843,6 +843,17 @@ def test_value_rotation_fused_decode_steps(kvq, oracle):
         assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
 
 
+# --------------------------------------------------------------------------- the quantizer's divisions on this device
+
+def test_fast_divisions_of_the_quantizer_are_correctly_rounded_on_this_device(kvq):
+    """App. B's scale factor (max - min) / (2^b - 1) and the division by the stored scale are computed in three
+    operations each; bit-exact codes need both to equal IEEE division: every binary16 scale, 10^8 sampled quotients."""
+    counters = torch.full((2,), 123, dtype=torch.int32, device="cuda")
+    kvq.selftest_quantizer(counters)
+    torch.cuda.synchronize()
+    assert counters.tolist() == [0, 0]
+
+
 # --------------------------------------------------------------------------- 1-, 3- and 6-bit quantizer widths
 
 @pytest.mark.parametrize("bk,bv", [(3, 2), (6, 3), (1, 6), (3, 3), (4, 1), (6, 4), (1, 2), (3, 8), (6, 2)])
