@@ -224,7 +224,7 @@ kvq_status kvq_dequantize(const kvq_layout* layout, const kvq_cache* cache, int3
  * kernels compute them in three operations each (a multiplication by the rounded reciprocal of 2^b - 1 with one exact
  * correction step; one refinement of the hardware's reciprocal approximation of the stored scale), which is exact
  * for every possible scale on gfx950.  This call checks it on the device it runs on.
- * counters: DEVICE pointer to two uint32 (8-byte aligned), overwritten asynchronously on `stream`:
+ * counters: DEVICE pointer to two uint32, overwritten asynchronously on `stream`:
  *   counters[0] = how many of the 31743 positive finite binary16 scales get a reciprocal that differs from IEEE division,
  *   counters[1] = how many of 6 x 2^24 sampled quotients x / (2^b - 1), b in {1,2,3,4,6,8}, differ from IEEE division.
  * Both must read 0.  KVQ_ERR_INVALID_ARG for a null or misaligned pointer. */

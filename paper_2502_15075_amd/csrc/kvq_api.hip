@@ -262,7 +262,7 @@ kvq_status kvq_reconstruction_error(const kvq_layout* layout, const kvq_cache* c
 }
 
 kvq_status kvq_selftest_quantizer(uint32_t* counters, void* stream) {
-  if (!counters || (reinterpret_cast<uintptr_t>(counters) & 7u)) return KVQ_ERR_INVALID_ARG;
+  if (!counters || (reinterpret_cast<uintptr_t>(counters) & 3u)) return KVQ_ERR_INVALID_ARG;
   return kvq::launch_selftest_quantizer(counters, (hipStream_t)stream) == hipSuccess ? KVQ_OK : KVQ_ERR_DEVICE;
 }
 

@@ -461,6 +461,10 @@ __global__ __launch_bounds__(256) void selftest_quantizer_kernel(uint32_t* count
   if (bad_div) atomicAdd(counters + 1, bad_div);
 }
 
+__global__ __launch_bounds__(64) void zero_u32_kernel(uint32_t* p, int n) {
+  if ((int)threadIdx.x < n) p[threadIdx.x] = 0u;
+}
+
 __global__ __launch_bounds__(256) void zero_f64_kernel(double* p, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = 0.0;
@@ -569,7 +573,7 @@ hipError_t launch_dequantize(const Geom& g, const kvq_cache& c, int32_t t0, int3
 }
 
 hipError_t launch_selftest_quantizer(uint32_t* counters, hipStream_t stream) {
-  hipLaunchKernelGGL(zero_f64_kernel, dim3(1), dim3(256), 0, stream, (double*)counters, (int64_t)1);   // 8 bytes = 2 counters
+  hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(64), 0, stream, counters, 2);
   hipLaunchKernelGGL(selftest_quantizer_kernel, dim3(256), dim3(256), 0, stream, counters);
   return hipGetLastError();
 }
