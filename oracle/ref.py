@@ -276,6 +276,24 @@ def quantize_append_at(L: Layout, planes, k_new: np.ndarray, v_new: np.ndarray, 
         quantize_append(Lb, pb, np.ascontiguousarray(k_new[b:b + 1]), np.ascontiguousarray(v_new[b:b + 1]), int(pos[b]), bf16)
 
 
+def seq_decode_attention_varlen(L: Layout, planes, q: np.ndarray, seq_lens, softmax_scale: float, bf16: bool = False) -> np.ndarray:
+    """Channel-wise keys, one length per batch element: element b has had seq_lens[b] tokens appended and attends over
+    all of them (its flushed blocks from the codes, the rest from its residual buffer)."""
+    q = np.ascontiguousarray(q)
+    out = np.zeros((L.batch, q.shape[1], L.head_dim), dtype=np.float32)
+    for b in range(L.batch):
+        Lb, pb = _element(L, planes, b)
+        out[b] = seq_decode_attention(Lb, pb, q[b:b + 1], int(seq_lens[b]), softmax_scale, bf16)[0]
+    return out
+
+
+def seq_append_at(L: Layout, planes, k_new: np.ndarray, v_new: np.ndarray, pos, bf16: bool = False) -> None:
+    """Channel-wise keys: one new token per batch element, element b having pos[b] tokens so far; k_new, v_new: [B, H, 1, D]."""
+    for b in range(L.batch):
+        Lb, pb = _element(L, planes, b)
+        seq_append(Lb, pb, np.ascontiguousarray(k_new[b:b + 1]), np.ascontiguousarray(v_new[b:b + 1]), int(pos[b]), bf16)
+
+
 # ---- paged planes: the same per-head layouts inside fixed-size pages of a pool, found through a page table
 
 def paged_plane_bytes(L: Layout, page_tokens: int, n_pages: int):

@@ -268,3 +268,40 @@ def test_three_bit_keys_against_four_bit_keys_through_the_cache(oracle):
         kd, _ = oracle.dequantize(L, planes, 0, T)
         mse[b] = oracle.mse(K.astype(np.float32), kd)
     assert mse[3] / mse[4] == pytest.approx((15 / 7) ** 2, rel=0.06)
+
+
+def test_ragged_batch_is_each_sequence_on_its_own(oracle):
+    """Per-sequence lengths with channel-wise keys: a batch whose elements have had different numbers of tokens appended
+    (one of them exactly a block, one below a block, one several blocks plus a tail) holds, element by element, the
+    planes of a batch of one filled the same way, and attends like it."""
+    B, H, R, D = 3, 2, 2, 128
+    lens = [64, 37, 150]
+    K, V, q = synth.make_kvq(77, B, H, H * R, max(lens), dtype=torch.float16)
+    L = oracle.Layout(B, H, 160, D, 4, 2, 64, 64, axis_k=1)
+    planes = oracle.new_seq_planes(L, fill=0x5A)
+    Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
+    for t in range(max(lens)):                               # token by token, only the sequences that still grow
+        live = [b for b in range(B) if t < lens[b]]
+        for b in live:                                       # element by element, on that element's slice of the planes
+            Lb, pb = _element_of(oracle, L, planes, b)
+            oracle.seq_append(Lb, pb, np.ascontiguousarray(Kn[b:b + 1, :, t:t + 1]), np.ascontiguousarray(Vn[b:b + 1, :, t:t + 1]), t)
+    scale = 1 / math.sqrt(D)
+    got = oracle.seq_decode_attention_varlen(L, planes, qn, lens, scale)
+    for b in range(B):
+        L1 = oracle.Layout(1, H, 160, D, 4, 2, 64, 64, axis_k=1)
+        p1 = oracle.new_seq_planes(L1, fill=0x5A)
+        oracle.seq_append(L1, p1, np.ascontiguousarray(Kn[b:b + 1, :, :lens[b]]), np.ascontiguousarray(Vn[b:b + 1, :, :lens[b]]), 0)
+        want = oracle.seq_decode_attention(L1, p1, qn[b:b + 1], lens[b], scale)
+        assert np.array_equal(got[b], want[0])
+        for whole, single in zip(planes, p1):
+            assert np.array_equal(whole.reshape(B, -1)[b], single)
+    # one more token for every element at its own position
+    Kx, Vx, _ = synth.make_kvq(78, B, H, H * R, 1, dtype=torch.float16)
+    oracle.seq_append_at(L, planes, Kx.numpy(), Vx.numpy(), lens)
+    got = oracle.seq_decode_attention_varlen(L, planes, qn, [n + 1 for n in lens], scale)
+    assert np.isfinite(got).all() and got.shape == (B, H * R, D)
+
+
+def _element_of(oracle, L, planes, b):
+    from dataclasses import replace
+    return replace(L, batch=1), [p.reshape(L.batch, -1)[b] if p.size else p for p in planes]
