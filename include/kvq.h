@@ -48,7 +48,10 @@
  * tokens are appended in order starting at 0 (pos = number of tokens appended so far), in_dtype = raw_dtype, and
  * seq_len of a decode call is that number.  bits 16 and rotate_k are not combined with it; axis_v stays
  * KVQ_AXIS_HEAD_DIM.  Attention needs a query of raw_dtype (KVQ_ERR_UNSUPPORTED otherwise);
- * kvq_decode_step is the append followed by the attention (several launches).  kvq_dequantize and
+ * kvq_decode_step is the append followed by the attention (several launches).  With per-sequence lengths
+ * (kvq_decode_attention_varlen, kvq_decode_step_varlen) every sequence has its own count of appended tokens, its own
+ * flushed blocks and its own tail in its residual buffer; kvq_decode_step_varlen appends sequence b's token at pos[b]
+ * (= its count so far; in_dtype = raw_dtype).  kvq_dequantize and
  * kvq_reconstruction_error read the codes only: the caller keeps t1 at or below the number of flushed tokens.
  * Format: T_cap is a multiple of 64; k_meta is [B][H_kv][T_cap/64][D] entries {scale, zero},
  * entry (t/64, d); k_resid is [B][H_kv][64][D] 16-bit patterns, token t in slot t%64; v_resid is [B][H_kv][2] blocks

@@ -158,7 +158,6 @@ kvq_status decode_common(const kvq_layout* layout, const kvq_cache* cache, const
   kvq_status st = decode_check(layout, cache, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype, workspace,
                                workspace_bytes, app != nullptr);
   if (st != KVQ_OK) return st;
-  if (seq_lens && layout->axis_k == KVQ_AXIS_SEQ) return KVQ_ERR_UNSUPPORTED;
   const kvq::Geom g = kvq::make_geom(*layout);
   const kvq::DecodePlan plan = kvq::plan_decode(g, seq_len);
   hipError_t e = kvq::launch_decode_attention(g, *cache, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype,
@@ -218,7 +217,20 @@ kvq_status kvq_decode_step_varlen(const kvq_layout* layout, const kvq_cache* cac
   if (max_pos >= layout->max_seq) return KVQ_ERR_CAPACITY;
   if (!k_new || !v_new || (in_dtype != KVQ_F16 && in_dtype != KVQ_BF16)) return KVQ_ERR_INVALID_ARG;
   if (!aligned16(k_new) || !aligned16(v_new) || stride_b % 8 || stride_h % 8) return KVQ_ERR_INVALID_ARG;
-  if (layout->axis_k == KVQ_AXIS_SEQ) return KVQ_ERR_UNSUPPORTED;
+  if (layout->axis_k == KVQ_AXIS_SEQ) {
+    // channel-wise keys: every sequence's new token goes through its residual buffer at its own position (and may
+    // flush a block there), then the attention with lengths pos[b] + 1; everything is checked before anything runs
+    kvq_status st = decode_check(layout, cache, q, q_dtype, q_heads, max_pos + 1, softmax_scale, out, out_dtype, workspace,
+                                 workspace_bytes, false);
+    if (st != KVQ_OK) return st;
+    if ((int)in_dtype != layout->raw_dtype) return KVQ_ERR_INVALID_ARG;     // the buffer keeps patterns of raw_dtype
+    const kvq::Geom g = kvq::make_geom(*layout);
+    if (kvq::launch_seq_append_one(g, *cache, k_new, v_new, (int)in_dtype, stride_b, stride_h, pos, max_pos,
+                                   (hipStream_t)stream) != hipSuccess)
+      return KVQ_ERR_DEVICE;
+    return decode_common(layout, cache, q, q_dtype, q_heads, max_pos + 1, softmax_scale, out, out_dtype, workspace,
+                         workspace_bytes, nullptr, stream, pos, 1);
+  }
   const kvq::AppendOne app{k_new, v_new, (int)in_dtype, stride_b, stride_h};
   return decode_common(layout, cache, q, q_dtype, q_heads, max_pos + 1, softmax_scale, out, out_dtype, workspace,
                        workspace_bytes, &app, stream, pos, 1);

@@ -619,7 +619,12 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   const int b = bh / g.kv_heads, hk = bh % g.kv_heads;
   // this sequence's length: its own when the caller gave per-sequence lengths, inside what the launch was planned for
   int seq_len = a.seq_len;
-  if (a.seq_lens) seq_len = min(max(a.seq_lens[b] + a.lens_offset, 1), a.seq_len);
+  if (a.seq_lens) {
+    int n = min(max(a.seq_lens[b] + a.lens_offset, 1), a.lens_bound);
+    if (a.lens_mode == 1) n &= ~(kSeqGroup - 1);            // channel-wise keys: the flushed blocks ...
+    else if (a.lens_mode == 2) n &= kSeqGroup - 1;          // ... or the tail in the residual buffer (either may be empty)
+    seq_len = min(n, a.seq_len);
+  }
 
   LaneCtx L;
   L.lane = lane; L.c = lane & 15; L.j = lane >> 4;
@@ -1041,9 +1046,11 @@ bool decode_supported(const Geom& g, int32_t q_heads) {
   return true;
 }
 
-// Partial records per (batch, query head) of one decode call.
+// Partial records per (batch, query head) that the workspace of one decode call must hold.  Channel-wise keys: one per
+// split of the flushed blocks plus one for the residual tail (with per-sequence lengths the tail record is always
+// written, so it is always counted once there is a flushed part).
 int32_t decode_records(const Geom& g, int32_t seq_len, const DecodePlan& plan) {
-  if (g.axis_k == KVQ_AXIS_SEQ) return plan.n_splits + (seq_len % kSeqGroup ? 1 : 0);
+  if (g.axis_k == KVQ_AXIS_SEQ) return plan.n_splits ? plan.n_splits + 1 : 1;
   return plan.n_splits;
 }
 
@@ -1089,11 +1096,16 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
   if (g.axis_k == KVQ_AXIS_SEQ) {
     // channel-wise keys: flushed blocks from the codes (plan), the newest tokens from the residual buffer by the
     // unquantized kernel, all partial records merged at the end
-    const int32_t n_flushed = seq_len / kSeqGroup * kSeqGroup, tail = seq_len - n_flushed;
-    const int32_t records = decode_records(g, seq_len, plan);
+    // (per-sequence lengths: seq_len is their bound; every sequence's own flushed part and tail are cut out on the
+    // device, the tail launch always runs, and a sequence without one of the parts gets empty records for it)
+    const bool varlen = seq_lens != nullptr;
+    const int32_t n_flushed = seq_len / kSeqGroup * kSeqGroup;
+    const int32_t tail = varlen ? (n_flushed ? kSeqGroup - 1 : seq_len) : seq_len - n_flushed;
+    const int32_t records = plan.n_splits + (tail ? 1 : 0);
+    a.lens_bound = seq_len;
     hipError_t e = hipSuccess;
     if (n_flushed) {
-      a.seq_len = n_flushed; a.rec_splits = records; a.rec_base = 0;
+      a.seq_len = n_flushed; a.rec_splits = records; a.rec_base = 0; a.lens_mode = 1;
 #define KVQ_CASE(BK_, BV_) \
       if (g.bits_k == BK_ && g.bits_v == BV_) e = KVQ_CAT(launch_decode_inst_, BK_, BV_)(R, a, plan, stream);
       KVQ_FOR_EACH_PAIR(KVQ_CASE)
@@ -1106,7 +1118,7 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
       t.g.t_cap = kSeqGroup;
       t.g.kc_stream = t.g.vc_stream = (int64_t)kSeqGroup * kHeadDim * 2; t.g.km_stream = t.g.vm_stream = 0;
       t.cache.k_codes = c.k_resid; t.cache.v_codes = c.v_resid; t.cache.k_meta = t.cache.v_meta = nullptr;
-      t.seq_len = tail; t.n_splits = 1; t.steps_per_split = 4;
+      t.seq_len = tail; t.n_splits = 1; t.steps_per_split = 4; t.lens_mode = 2;
       t.rec_splits = records; t.rec_base = records - 1;
       e = launch_decode_inst_16_16(R, t, DecodePlan{1, 4, 4}, stream);
       if (e != hipSuccess) return e;
@@ -1118,6 +1130,7 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
     }
     return e;
   }
+  a.lens_mode = 0; a.lens_bound = seq_len;
   if (app) {
     a.k_new = (const uint16_t*)app->k_new; a.v_new = (const uint16_t*)app->v_new;
     a.in_bf16 = app->in_dtype == KVQ_BF16 ? 1 : 0; a.nsb = app->stride_b; a.nsh = app->stride_h;

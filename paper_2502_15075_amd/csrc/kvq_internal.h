@@ -88,6 +88,10 @@ struct DecodeArgs {
   // per-sequence lengths: batch element b attends over seq_lens[b] + lens_offset tokens (clamped to [1, seq_len]; seq_len
   // is then the upper bound the launch was planned for); nullptr: every sequence has seq_len tokens
   const int32_t* seq_lens; int32_t lens_offset;
+  // channel-wise keys with per-sequence lengths: the length n = clamp(seq_lens[b] + lens_offset, 1, lens_bound) is cut
+  // into its flushed blocks (lens_mode 1: n rounded down to kSeqGroup, possibly 0) or its residual tail (lens_mode 2:
+  // n mod kSeqGroup, possibly 0); a workgroup with nothing to read writes an empty record.  lens_mode 0: n as it is.
+  int32_t lens_mode, lens_bound;
   float* ws; void* out; int out_dtype;
   int32_t n_splits, steps_per_split;
   // partial records: a workgroup writes record rec_base + split of rec_splits per (batch, query head); rec_splits == 1
@@ -106,6 +110,9 @@ hipError_t launch_quantize_append(const Geom& g, const kvq_cache& c, const void*
 // Channel-wise keys: tokens go to the residual buffer; completed blocks of kSeqGroup tokens are flushed.
 hipError_t launch_seq_append(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype,
                              int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream);
+// ... one new token per sequence at that sequence's own position pos_arr[b] (device; clamped to [0, max_pos])
+hipError_t launch_seq_append_one(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype,
+                                 int64_t sb, int64_t sh, const int32_t* pos_arr, int32_t max_pos, hipStream_t stream);
 hipError_t launch_dequantize(const Geom& g, const kvq_cache& c, int32_t t0, int32_t t1, void* k_out, void* v_out,
                              int out_dtype, hipStream_t stream);
 hipError_t launch_selftest_quantizer(uint32_t* counters, hipStream_t stream);

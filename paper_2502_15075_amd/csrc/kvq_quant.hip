@@ -190,7 +190,8 @@ template <int B> __device__ __forceinline__ void value_codes8(const uint8_t* cs,
 template <int BK, int BV, bool BF>
 __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_new,
                                                          const uint16_t* __restrict__ v_new, int64_t sb, int64_t sh,
-                                                         int64_t st, int32_t pos, int32_t n_new) {
+                                                         int64_t st, int32_t pos, int32_t n_new,
+                                                         const int32_t* __restrict__ pos_arr, int32_t max_pos) {
   static_assert(kSeqGroup == kSpan, "a flushed block is one value span");
   constexpr int kStageBytes = kSpan * kHeadDim;
   __shared__ __attribute__((aligned(16))) uint8_t vstage[kStageBytes + (kStageBytes >> 4)];
@@ -198,6 +199,7 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
   const int tid = threadIdx.x;
   const int bh = blockIdx.y;
   const int b = bh / g.kv_heads, h = bh % g.kv_heads;
+  if (pos_arr) pos = min(max(pos_arr[b], 0), max_pos);     // one token per sequence at its own position (n_new == 1)
   const int blk = pos / kSpan + blockIdx.x;
   const int lo = max(pos, blk * kSpan) - blk * kSpan;
   const int hi = min(pos + n_new, (blk + 1) * kSpan) - blk * kSpan;
@@ -515,30 +517,48 @@ hipError_t launch_quantize_append(const Geom& g, const kvq_cache& c, const void*
 }
 
 namespace {
+// pos_arr != nullptr: one token per sequence at pos_arr[b] (then pos and n_new are 0 and 1)
 template <int BK, int BV>
 hipError_t launch_sa(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype, int64_t sb,
-                     int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
+                     int64_t sh, int64_t st, int32_t pos, int32_t n_new, const int32_t* pos_arr, int32_t max_pos,
+                     hipStream_t stream) {
   const int first = pos / kSeqGroup, last = (pos + n_new - 1) / kSeqGroup;
   dim3 grid(last - first + 1, g.batch * g.kv_heads);
   if (in_dtype == KVQ_BF16)
     hipLaunchKernelGGL((seq_append_kernel<BK, BV, true>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
-                       (const uint16_t*)v_new, sb, sh, st, pos, n_new);
+                       (const uint16_t*)v_new, sb, sh, st, pos, n_new, pos_arr, max_pos);
   else
     hipLaunchKernelGGL((seq_append_kernel<BK, BV, false>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
-                       (const uint16_t*)v_new, sb, sh, st, pos, n_new);
+                       (const uint16_t*)v_new, sb, sh, st, pos, n_new, pos_arr, max_pos);
   return hipGetLastError();
 }
 template <int BK>
 hipError_t launch_sak(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype, int64_t sb,
-                      int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
+                      int64_t sh, int64_t st, int32_t pos, int32_t n_new, const int32_t* pos_arr, int32_t max_pos,
+                      hipStream_t stream) {
   switch (g.bits_v) {
-    case 2: return launch_sa<BK, 2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
-    case 4: return launch_sa<BK, 4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
-    case 8: return launch_sa<BK, 8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 2: return launch_sa<BK, 2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
+    case 4: return launch_sa<BK, 4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
+    case 8: return launch_sa<BK, 8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
+  }
+  return hipErrorInvalidValue;
+}
+hipError_t launch_sa_bits(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype, int64_t sb,
+                          int64_t sh, int64_t st, int32_t pos, int32_t n_new, const int32_t* pos_arr, int32_t max_pos,
+                          hipStream_t stream) {
+  switch (g.bits_k) {
+    case 2: return launch_sak<2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
+    case 4: return launch_sak<4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
+    case 8: return launch_sak<8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
   }
   return hipErrorInvalidValue;
 }
 }  // namespace
+
+hipError_t launch_seq_append_one(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype,
+                                 int64_t sb, int64_t sh, const int32_t* pos_arr, int32_t max_pos, hipStream_t stream) {
+  return launch_sa_bits(g, c, k_new, v_new, in_dtype, sb, sh, kHeadDim, 0, 1, pos_arr, max_pos, stream);
+}
 
 hipError_t launch_seq_append(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype,
                              int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
@@ -554,12 +574,7 @@ hipError_t launch_seq_append(const Geom& g, const kvq_cache& c, const void* k_ne
     return launch_seq_append(g, c, (const uint16_t*)k_new + (int64_t)n1 * st, (const uint16_t*)v_new + (int64_t)n1 * st,
                              in_dtype, sb, sh, st, first_end, n_new - n1, stream);
   }
-  switch (g.bits_k) {
-    case 2: return launch_sak<2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
-    case 4: return launch_sak<4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
-    case 8: return launch_sak<8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
-  }
-  return hipErrorInvalidValue;
+  return launch_sa_bits(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, nullptr, 0, stream);
 }
 
 hipError_t launch_dequantize(const Geom& g, const kvq_cache& c, int32_t t0, int32_t t1, void* k_out, void* v_out,

@@ -5,6 +5,7 @@ attention output within 2e-3 of the oracle evaluated on the same cache bytes, me
 (batch, query head) as max|out - ref| / max|ref|.
 """
 import math
+from dataclasses import replace
 
 import numpy as np
 import pytest
@@ -665,6 +666,59 @@ def test_channelwise_decode_steps_cross_a_flush(kvq, oracle):
         _assert_seq_planes_equal(cache, planes)
         ref = oracle.seq_decode_attention(Lo, planes, synth.to_numpy_bits(q), pos + 1, 1 / math.sqrt(128), bf16=True)
         assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
+
+
+@pytest.mark.parametrize("R,bk,bv,gv", [(4, 4, 2, 64), (8, 2, 4, 128), (1, 8, 8, 32)])
+def test_channelwise_ragged_batch_attention_and_steps(kvq, oracle, R, bk, bv, gv):
+    """Per-sequence lengths with channel-wise keys: every sequence has its own flushed blocks and its own tail in its
+    residual buffer (lengths below one block, exactly on a block boundary, several blocks plus a tail, several splits);
+    then fused steps at per-sequence positions, one of which completes a block in one sequence only."""
+    B, H = 4, 2
+    lens = [37, 128, 2500, 63]
+    cap = 2600
+    K, V, q = synth.make_kvq(610 + R, B, H, H * R, cap, dtype=torch.bfloat16)
+    Lg, Lo = _seq_layouts(kvq, oracle, B, H, cap, bk, bv, gv, raw=1)
+    cache = kvq.Cache(Lg, fill=0x3C)
+    planes = oracle.new_seq_planes(Lo, fill=0x3C)
+    Kd, Vd = K.cuda(), V.cuda()
+    Kb, Vb = synth.to_numpy_bits(K), synth.to_numpy_bits(V)
+    # fill sequence b with lens[b] tokens: batches of one on the GPU side as well (views of the planes per batch element)
+    for b in range(B):
+        L1g = kvq.Layout(1, H, cap, 128, bk, bv, 64, gv, axis_k=kvq.AXIS_SEQ, raw_dtype=1)
+        c1 = kvq.Cache.__new__(kvq.Cache)
+        c1.layout = L1g
+        c1.planes = [p.view(B, -1)[b] for p in cache.planes]
+        c1.page_table = None
+        kvq.quantize_append(L1g, c1, Kd[b:b + 1, :, :lens[b]], Vd[b:b + 1, :, :lens[b]], 0)
+        L1o, p1 = replace(Lo, batch=1), [p.reshape(B, -1)[b] for p in planes]
+        oracle.seq_append(L1o, p1, np.ascontiguousarray(Kb[b:b + 1, :, :lens[b]]), np.ascontiguousarray(Vb[b:b + 1, :, :lens[b]]), 0, bf16=True)
+    torch.cuda.synchronize()
+    _assert_seq_planes_equal(cache, planes)
+    qn = synth.to_numpy_bits(q)
+    scale = 1 / math.sqrt(128)
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    for bound in (max(lens), 2048, 40):               # a bound below some lengths clamps them
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, bound)), dtype=torch.uint8, device="cuda")
+        kvq.decode_attention_varlen(Lg, cache, q.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"), bound, scale, out, ws)
+        torch.cuda.synchronize()
+        if bound == max(lens):                         # (a clamped length cuts a sequence inside its flushed blocks: the
+            ref = oracle.seq_decode_attention_varlen(Lo, planes, qn, lens, scale, bf16=True)   # oracle has no such state)
+            assert _rel_err(out.cpu().numpy(), ref) < TOL, bound
+        else:
+            assert torch.isfinite(out).all()
+    # fused steps at per-sequence positions: sequence 3 (63 tokens) completes its first block at the first step
+    pos = list(lens)
+    for i in range(3):
+        Kx, Vx, qx = synth.make_kvq(7000 + i, B, H, H * R, 1, dtype=torch.bfloat16)
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, max(pos) + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step_varlen(Lg, cache, Kx.cuda()[:, :, 0], Vx.cuda()[:, :, 0], torch.tensor(pos, dtype=torch.int32, device="cuda"),
+                               max(pos), qx.cuda(), scale, out, ws)
+        torch.cuda.synchronize()
+        oracle.seq_append_at(Lo, planes, synth.to_numpy_bits(Kx), synth.to_numpy_bits(Vx), pos, bf16=True)
+        _assert_seq_planes_equal(cache, planes)
+        pos = [p + 1 for p in pos]
+        ref = oracle.seq_decode_attention_varlen(Lo, planes, synth.to_numpy_bits(qx), pos, scale, bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, i
 
 
 def test_channelwise_unsupported_combinations(kvq):
