@@ -60,8 +60,9 @@
  * Paged planes (page_tokens = P != 0; what a serving stack with a block table does): each plane is a pool
  * [n_pages][H_kv][...one head's share of a contiguous cache of capacity P...], and token t of sequence b lives in pool
  * page page_table[b][t / P] at local position t % P.  kvq_cache_bytes reports the pool sizes.  Every call takes the
- * table as it is at launch time; pages of different sequences must not alias unless they are only read.  Not combined
- * with channel-wise keys.
+ * table as it is at launch time; pages of different sequences must not alias unless they are only read.  With
+ * channel-wise keys the four code and scale/zero planes are paged the same way (a 64-token block never straddles a page;
+ * k_meta holds P/64 blocks per page and head) and the residual buffers stay per sequence.
  *
  * Storage format of one layer (sizes from kvq_cache_bytes; T_cap = max_seq rounded up to 32):
  *   k_codes  [B][H_kv][T_cap][D*b_K/8]      b_K in {1,2,4,8,16}: element d of a row at bits [d*b_K, (d+1)*b_K),

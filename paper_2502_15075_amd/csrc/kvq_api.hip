@@ -26,7 +26,6 @@ kvq_status check_layout(const kvq_layout* L) {
   if (L->page_tokens) {
     if (L->page_tokens < 64 || L->page_tokens > 65536 || (L->page_tokens & (L->page_tokens - 1)) || L->n_pages <= 0)
       return KVQ_ERR_INVALID_ARG;
-    if (L->axis_k == KVQ_AXIS_SEQ) return KVQ_ERR_UNSUPPORTED;
     if ((int64_t)L->n_pages * L->kv_heads * L->page_tokens > ((int64_t)1 << 40)) return KVQ_ERR_UNSUPPORTED;
   }
   if (L->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;

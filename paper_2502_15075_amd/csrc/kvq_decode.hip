@@ -583,7 +583,6 @@ __device__ __forceinline__ void store_unrotated_row(const float* row, int lane16
 // PAGED: the planes are pools of pages; a step's data is found through this sequence's row of the page table.
 template <int BK, int BV, int R, int NW, bool BF, int NCK, int NCV, bool KSEQ = false, bool PAGED = false>
 __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(const DecodeArgs a) {
-  static_assert(!(KSEQ && PAGED), "channel-wise keys are not paged");
   constexpr int kSetGroups = 16 / R;             // groups per column set
   constexpr bool RAW = BK == 16;
   static_assert(!KSEQ || (!RAW && NCK == 1), "channel-wise keys: quantized, one key column per head");
@@ -966,8 +965,8 @@ hipError_t launch_sets(const DecodeArgs& a, const DecodePlan& plan, dim3 grid, h
   if constexpr (R == 8 && BK != 16) {
     if constexpr (KSEQ) {
       if (k2) return hipErrorInvalidValue;
-      if (v2) launch_nw<BK, BV, R, BF, 1, 2, true, false>(a, plan, grid, stream);
-      else launch_nw<BK, BV, R, BF, 1, 1, true, false>(a, plan, grid, stream);
+      if (v2) launch_nw<BK, BV, R, BF, 1, 2, true, PAGED>(a, plan, grid, stream);
+      else launch_nw<BK, BV, R, BF, 1, 1, true, PAGED>(a, plan, grid, stream);
     } else {
       if (k2 && v2) launch_nw<BK, BV, R, BF, 2, 2, false, PAGED>(a, plan, grid, stream);
       else if (k2) launch_nw<BK, BV, R, BF, 2, 1, false, PAGED>(a, plan, grid, stream);
@@ -985,9 +984,8 @@ template <int BK, int BV, int R, bool BF = false, bool KSEQ = false>
 hipError_t launch_one(const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream) {
   dim3 grid(plan.n_splits, a.g.batch * a.g.kv_heads);
   hipError_t e;
-  if constexpr (KSEQ) e = launch_sets<BK, BV, R, BF, true, false>(a, plan, grid, stream);
-  else e = a.g.page_shift ? launch_sets<BK, BV, R, BF, false, true>(a, plan, grid, stream)
-                          : launch_sets<BK, BV, R, BF, false, false>(a, plan, grid, stream);
+  e = a.g.page_shift ? launch_sets<BK, BV, R, BF, KSEQ, true>(a, plan, grid, stream)
+                     : launch_sets<BK, BV, R, BF, KSEQ, false>(a, plan, grid, stream);
   // the records of this launch are all there is: merge them here (otherwise the caller adds launches and merges)
   if (e != hipSuccess || a.rec_splits == 1 || a.rec_splits != plan.n_splits) return e;
   hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128), 0, stream, a.ws, a.out, a.out_dtype, a.rec_splits,
@@ -1115,7 +1113,7 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
     if (tail) {
       DecodeArgs t = a;
       t.g.axis_k = KVQ_AXIS_HEAD_DIM; t.g.bits_k = t.g.bits_v = 16; t.g.g_k = t.g.g_v = kHeadDim; t.g.ng_k = t.g.ng_v = 1;
-      t.g.t_cap = kSeqGroup;
+      t.g.t_cap = kSeqGroup; t.g.page_shift = 0; t.cache.page_table = nullptr;     // (the buffers are per sequence, never paged)
       t.g.kc_stream = t.g.vc_stream = (int64_t)kSeqGroup * kHeadDim * 2; t.g.km_stream = t.g.vm_stream = 0;
       t.cache.k_codes = c.k_resid; t.cache.v_codes = c.v_resid; t.cache.k_meta = t.cache.v_meta = nullptr;
       t.seq_len = tail; t.n_splits = 1; t.steps_per_split = 4; t.lens_mode = 2;

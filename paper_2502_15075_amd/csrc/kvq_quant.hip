@@ -237,10 +237,12 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
   }
   if (!complete) return;                                   // uniform over the workgroup
 
-  uint8_t* kc = (uint8_t*)c.k_codes + (int64_t)bh * g.kc_stream;
-  uint32_t* km = (uint32_t*)((uint8_t*)c.k_meta + (int64_t)bh * g.km_stream) + (int64_t)blk * kHeadDim;
-  uint32_t* vm = (uint32_t*)((uint8_t*)c.v_meta + (int64_t)bh * g.vm_stream);
-  uint32_t* vc = (uint32_t*)((uint8_t*)c.v_codes + (int64_t)bh * g.vc_stream) + (int64_t)blk * (256 * BV);
+  // rows of all four planes are addressed by the block's first token in plane order (a block never straddles a page)
+  const int64_t tv0 = virtual_token(g, c.page_table, b, h, (int64_t)blk * kSpan);
+  uint8_t* kc = (uint8_t*)c.k_codes;
+  uint32_t* km = (uint32_t*)c.k_meta + (tv0 / kSeqGroup) * kHeadDim;
+  uint32_t* vm = (uint32_t*)c.v_meta;
+  uint32_t* vc = (uint32_t*)c.v_codes + (tv0 >> 5) * (128 * BV);
 
   // ---- keys: minimum and maximum of every channel over the 64 rows (4 rows here, 4 row groups per wavefront,
   // 4 wavefronts through LDS)
@@ -282,7 +284,7 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
   }
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
-    const int64_t t = (int64_t)blk * kSpan + rg + 16 * it;
+    const int64_t t = tv0 + rg + 16 * it;
     store_key_codes<BK>(kc + t * (16 * BK), lane16, codes[it]);
   }
 
@@ -290,7 +292,7 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
     const int row = rg + 16 * it;
-    const int64_t t = (int64_t)blk * kSpan + row;
+    const int64_t t = tv0 + row;
     const uint32_t rw[4] = {vraw[it].x, vraw[it].y, vraw[it].z, vraw[it].w};
     float xv[8];
 #pragma unroll

@@ -102,7 +102,6 @@ def test_layout_errors(kvq):
         (kvq.Layout(1, 8, 1 << 25), kvq.ERR_UNSUPPORTED),
         (kvq.Layout(1, 8, 64, page_tokens=48, n_pages=4), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, page_tokens=32, n_pages=4), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, page_tokens=64, n_pages=0), kvq.ERR_INVALID_ARG),
-        (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_k=1, page_tokens=64, n_pages=4), kvq.ERR_UNSUPPORTED),
         (kvq.Layout(1, 8, 64, rotate_k=2), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, rotate_v=-1), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 4, 16, rotate_v=1), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_k=1, rotate_v=1), kvq.ERR_INVALID_ARG),

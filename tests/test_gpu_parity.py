@@ -999,6 +999,72 @@ def _assert_paged_equal(oracle, Lo, cache, planes, table, P, n_pages):
             assert (p.reshape(n_pages, -1)[~used] == 0xA5).all()
 
 
+@pytest.mark.parametrize("R,bk,bv,gv,P", [(4, 4, 2, 64, 64), (8, 2, 4, 128, 256), (2, 8, 8, 32, 128)])
+def test_paged_channelwise_keys(kvq, oracle, R, bk, bv, gv, P):
+    """Channel-wise keys in a paged pool: the four code/scale planes live in pages found through the table (a 64-token
+    block never straddles a page), the residual buffers stay per sequence.  Appends (ragged chunks, bulk), the flushed
+    tokens' reconstruction, attention with a tail, with several splits, with per-sequence lengths, and fused steps
+    across a flush and a page boundary."""
+    B, H, T0 = 2, 2, 2230
+    T = T0 + 80
+    pps = -(-T // P)
+    n_pages = B * pps + 2
+    table = np.random.default_rng(bk + P).permutation(n_pages)[:B * pps].reshape(B, pps).astype(np.int32)
+    Lg = kvq.Layout(B, H, T, 128, bk, bv, 64, gv, axis_k=kvq.AXIS_SEQ, raw_dtype=1, page_tokens=P, n_pages=n_pages)
+    Lo = oracle.Layout(B, H, pps * P, 128, bk, bv, 64, gv, raw_dtype=1, axis_k=1)
+    cache = kvq.Cache(Lg, fill=0xA5)
+    cache.page_table = torch.from_numpy(table).cuda()
+    planes = oracle.new_seq_planes(Lo, fill=0xA5)
+    K, V, q = synth.make_kvq(830 + R, B, H, H * R, T, dtype=torch.bfloat16)
+    Kd, Vd, Kb, Vb = K.cuda(), V.cuda(), synth.to_numpy_bits(K), synth.to_numpy_bits(V)
+
+    def both_append(a, b):
+        kvq.quantize_append(Lg, cache, Kd[:, :, a:b], Vd[:, :, a:b], a)
+        oracle.seq_append(Lo, planes, np.ascontiguousarray(Kb[:, :, a:b]), np.ascontiguousarray(Vb[:, :, a:b]), a, bf16=True)
+
+    def check_planes():
+        torch.cuda.synchronize()
+        pool = [p.cpu().numpy() for p in cache.planes[:4]]
+        got = oracle.gather_pages(Lo, pool, table, P, n_pages) + [p.cpu().numpy() for p in cache.planes[4:]]
+        for name, g, o in zip(("k_codes", "k_meta", "v_codes", "v_meta", "k_resid", "v_resid"), got, planes):
+            bad = np.flatnonzero(g != o)
+            assert bad.size == 0, f"{name}: {bad.size} bytes differ, first at {bad[:5]}"
+
+    for a, b in [(0, 1), (1, 63), (63, 64), (64, 200), (200, T0)]:
+        both_append(a, b)
+    check_planes()
+    nq = T0 // 64 * 64
+    ko = torch.empty(B, H, nq, 128, dtype=torch.float32, device="cuda")
+    vo = torch.empty_like(ko)
+    kvq.dequantize(Lg, cache, 0, nq, ko, vo)
+    kd, vd = oracle.seq_dequantize(Lo, planes, T0, 0, nq)
+    assert np.array_equal(ko.cpu().numpy().view(np.uint32), kd.view(np.uint32))
+    assert np.array_equal(vo.cpu().numpy().view(np.uint32), vd.view(np.uint32))
+    scale = 1 / math.sqrt(128)
+    qn = synth.to_numpy_bits(q)
+    out = _decode(kvq, Lg, cache, q, T0)
+    ref = oracle.seq_decode_attention(Lo, planes, qn, T0, scale, bf16=True)
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+    # fused steps: uniform positions, across the flush at 2239 -> 2240 and (P = 64, 128, 256) a page boundary at 2304
+    outs = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    for pos in range(T0, T):
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), scale, outs, ws)
+        oracle.seq_append(Lo, planes, np.ascontiguousarray(Kb[:, :, pos:pos + 1]), np.ascontiguousarray(Vb[:, :, pos:pos + 1]), pos, bf16=True)
+        if pos in (T0, 2239, 2240, 2303, 2304, T - 1):
+            check_planes()
+            ref = oracle.seq_decode_attention(Lo, planes, qn, pos + 1, scale, bf16=True)
+            assert _rel_err(outs.cpu().numpy(), ref) < TOL, pos
+    # a second pool-resident batch state is not needed for per-sequence lengths: shorter views of the same sequences
+    # are not valid states (the buffer holds the newest tokens), so only the full lengths are compared
+    lens = [T, T]
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, T)), dtype=torch.uint8, device="cuda")
+    kvq.decode_attention_varlen(Lg, cache, q.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"), T, scale, outs, ws)
+    torch.cuda.synchronize()
+    ref = oracle.seq_decode_attention_varlen(Lo, planes, qn, lens, scale, bf16=True)
+    assert _rel_err(outs.cpu().numpy(), ref) < TOL
+
+
 @pytest.mark.parametrize("bk,bv,gk,gv,P", [(4, 2, 64, 64, 64), (2, 4, 32, 128, 256), (8, 8, 64, 64, 128), (16, 16, 64, 64, 64),
                                            (3, 2, 64, 64, 64), (1, 4, 128, 32, 128)])
 def test_paged_append_and_reconstruction(kvq, oracle, bk, bv, gk, gv, P):
