@@ -308,54 +308,57 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
   store_value_words<BV>(vc, vstage, tid, 0, kSpan);
 }
 
-// Reconstruction x^ = code * scale + zero of 8 consecutive channels d0..d0+7 (d0 a multiple of 8) of token t of
-// stream bh (which = 0: keys, 1: values), as binary32 values; a 16-bit plane is widened exactly.  Callers pass
-// bh = 0 and t = the token's number in plane order (virtual_token), which covers contiguous and paged planes alike.
-__device__ __forceinline__ void reconstruct8(const Geom& g, const kvq_cache& c, int which, int64_t bh, int64_t t, int d0,
-                                             float val[8]) {
-  const int b = which ? g.bits_v : g.bits_k;
-  const int G = which ? g.g_v : g.g_k;
-  const int ng = which ? g.ng_v : g.ng_k;
-  const uint8_t* cs = (const uint8_t*)(which ? c.v_codes : c.k_codes) + bh * (which ? g.vc_stream : g.kc_stream);
+// Reconstruction x^ = code * scale + zero of 8 consecutive channels d0..d0+7 (d0 a multiple of 8) of the token with
+// number t in plane order (virtual_token: contiguous and paged planes alike), as binary32 values; a 16-bit plane is
+// widened exactly.  B: what a code takes in its plane (compile time); IS_V: values, else keys.
+template <int B, bool IS_V>
+__device__ __forceinline__ void reconstruct8_t(const Geom& g, const kvq_cache& c, int64_t t, int d0, float val[8]) {
   uint32_t code[8];
-  if (which) {
-    switch (b) {
-      case 2: value_codes8<2>(cs, t, d0, code); break;
-      case 4: value_codes8<4>(cs, t, d0, code); break;
-      case 8: value_codes8<8>(cs, t, d0, code); break;
-      default: value_codes8<16>(cs, t, d0, code); break;
-    }
-  } else {
-    // (the common widths first: the chain is walked once per row and tensor)
-    if (b == 4) load_key_codes<4>(cs + t * 64, d0 >> 3, code);
-    else if (b == 2) load_key_codes<2>(cs + t * 32, d0 >> 3, code);
-    else if (b == 8) load_key_codes<8>(cs + t * 128, d0 >> 3, code);
-    else if (b == 16) load_key_codes<16>(cs + t * 256, d0 >> 3, code);
-    else if (b == 3) load_key_codes<3>(cs + t * 48, d0 >> 3, code);
-    else if (b == 6) load_key_codes<6>(cs + t * 96, d0 >> 3, code);
-    else load_key_codes<1>(cs + t * 16, d0 >> 3, code);
-  }
-  if (b == 16) {
+  if constexpr (IS_V) value_codes8<B>((const uint8_t*)c.v_codes, t, d0, code);
+  else load_key_codes<B>((const uint8_t*)c.k_codes + t * (16 * B), d0 >> 3, code);
+  if constexpr (B == 16) {
     const bool raw_bf16 = g.raw_dtype == KVQ_BF16;
 #pragma unroll
     for (int e = 0; e < 8; ++e) val[e] = widen16((uint16_t)code[e], raw_bf16);
-    return;
-  }
-  const uint32_t* ms = (const uint32_t*)((const uint8_t*)(which ? c.v_meta : c.k_meta) + bh * (which ? g.vm_stream : g.km_stream));
-  if (!which && g.axis_k == KVQ_AXIS_SEQ) {        // channel-wise keys: one scale/zero per channel and 64-token block
-    const uint4* mp = reinterpret_cast<const uint4*>(ms + (t / kSeqGroup) * kHeadDim + d0);
-    const uint4 m0 = mp[0], m1 = mp[1];
-    const uint32_t mm[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+  } else {
+    const uint32_t* ms = (const uint32_t*)(IS_V ? c.v_meta : c.k_meta);
+    if (!IS_V && g.axis_k == KVQ_AXIS_SEQ) {       // channel-wise keys: one scale/zero per channel and 64-token block
+      const uint4* mp = reinterpret_cast<const uint4*>(ms + (t / kSeqGroup) * kHeadDim + d0);
+      const uint4 m0 = mp[0], m1 = mp[1];
+      const uint32_t mm[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-      val[e] = (float)code[e] * widen16((uint16_t)(mm[e] & 0xFFFF), false) + widen16((uint16_t)(mm[e] >> 16), false);
-    return;
-  }
-  const uint32_t m = ms[meta_index(t, d0 / G, ng)];
-  const float s = widen16((uint16_t)(m & 0xFFFF), false);
-  const float z = widen16((uint16_t)(m >> 16), false);
+      for (int e = 0; e < 8; ++e)
+        val[e] = (float)code[e] * widen16((uint16_t)(mm[e] & 0xFFFF), false) + widen16((uint16_t)(mm[e] >> 16), false);
+      return;
+    }
+    const int G = IS_V ? g.g_v : g.g_k, ng = IS_V ? g.ng_v : g.ng_k;
+    const uint32_t m = ms[meta_index(t, d0 / G, ng)];
+    const float s = widen16((uint16_t)(m & 0xFFFF), false);
+    const float z = widen16((uint16_t)(m >> 16), false);
 #pragma unroll
-  for (int e = 0; e < 8; ++e) val[e] = (float)code[e] * s + z;
+    for (int e = 0; e < 8; ++e) val[e] = (float)code[e] * s + z;
+  }
+}
+
+// The same with the widths read from the geometry (the dequantize kernel: one token per thread, no loop to specialize).
+__device__ __forceinline__ void reconstruct8(const Geom& g, const kvq_cache& c, int which, int64_t t, int d0, float val[8]) {
+  if (which) {
+    switch (g.bits_v) {
+      case 2: return reconstruct8_t<2, true>(g, c, t, d0, val);
+      case 4: return reconstruct8_t<4, true>(g, c, t, d0, val);
+      case 8: return reconstruct8_t<8, true>(g, c, t, d0, val);
+      default: return reconstruct8_t<16, true>(g, c, t, d0, val);
+    }
+  }
+  switch (g.bits_k) {
+    case 1: return reconstruct8_t<1, false>(g, c, t, d0, val);
+    case 2: return reconstruct8_t<2, false>(g, c, t, d0, val);
+    case 3: return reconstruct8_t<3, false>(g, c, t, d0, val);
+    case 4: return reconstruct8_t<4, false>(g, c, t, d0, val);
+    case 6: return reconstruct8_t<6, false>(g, c, t, d0, val);
+    case 8: return reconstruct8_t<8, false>(g, c, t, d0, val);
+    default: return reconstruct8_t<16, false>(g, c, t, d0, val);
+  }
 }
 
 // One thread = 8 consecutive channels of one token.
@@ -375,7 +378,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Geom g, kvq_cache c, in
     void* out = which ? v_out : k_out;
     if (!out) continue;
     float val[8];
-    reconstruct8(g, c, which, 0, t, d0, val);
+    reconstruct8(g, c, which, t, d0, val);
     if (which ? g.rotate_v : g.rotate_k)                                             // 16 threads = one row, all here
       unrotate8(val, oct, rot_sign_bits(which ? g.signs_v : g.signs_k, oct));
     const int64_t o = row * kHeadDim + d0;
@@ -395,6 +398,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Geom g, kvq_cache c, in
 // One thread = 8 consecutive channels of one token; a workgroup walks 16-token slabs of one (b,h) stream with
 // stride gridDim.x; differences and the squares of a thread's 8 channels in binary32, everything above that summed
 // in binary64, one atomic add per wavefront and tensor.
+template <int BK, int BV>
 __global__ __launch_bounds__(256) void sq_error_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_ref,
                                                        const uint16_t* __restrict__ v_ref, int ref_bf16, int64_t sb,
                                                        int64_t sh, int64_t st, int32_t t0, int32_t t1,
@@ -414,7 +418,9 @@ __global__ __launch_bounds__(256) void sq_error_kernel(Geom g, kvq_cache c, cons
     for (int which = 0; which < 2; ++which) {
       if (!(which ? v_ref : k_ref)) continue;
       float val[8];
-      reconstruct8(g, c, which, 0, virtual_token(g, c.page_table, (int)b, (int)h, t0 + r), d0, val);
+      const int64_t tv = virtual_token(g, c.page_table, (int)b, (int)h, t0 + r);
+      if (which) reconstruct8_t<BV, true>(g, c, tv, d0, val);
+      else reconstruct8_t<BK, false>(g, c, tv, d0, val);
       const uint32_t rw[4] = {raw[which].x, raw[which].y, raw[which].z, raw[which].w};
       float x[8];
 #pragma unroll
@@ -606,8 +612,16 @@ hipError_t launch_reconstruction_error(const Geom& g, const kvq_cache& c, const 
   const int64_t slabs = ((int64_t)(t1 - t0) + 15) / 16;
   int64_t per_stream = (8192 + streams - 1) / streams;          // about 32 workgroups per compute unit in all
   if (per_stream > slabs) per_stream = slabs;
-  hipLaunchKernelGGL(sq_error_kernel, dim3((unsigned)per_stream, streams), dim3(256), 0, stream, g, c,
-                     (const uint16_t*)k_ref, (const uint16_t*)v_ref, ref_dtype == KVQ_BF16 ? 1 : 0, sb, sh, st, t0, t1, sums);
+  const dim3 grid((unsigned)per_stream, streams);
+  const int bf = ref_dtype == KVQ_BF16 ? 1 : 0;
+#define KVQ_ERR_CASE(BK_, BV_)                                                                                          \
+  if (g.bits_k == BK_ && g.bits_v == BV_)                                                                               \
+    hipLaunchKernelGGL((sq_error_kernel<BK_, BV_>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_ref,           \
+                       (const uint16_t*)v_ref, bf, sb, sh, st, t0, t1, sums);
+#define KVQ_ERR_ROW(BK_) KVQ_ERR_CASE(BK_, 2) KVQ_ERR_CASE(BK_, 4) KVQ_ERR_CASE(BK_, 8) KVQ_ERR_CASE(BK_, 16)
+  KVQ_ERR_ROW(1) KVQ_ERR_ROW(2) KVQ_ERR_ROW(3) KVQ_ERR_ROW(4) KVQ_ERR_ROW(6) KVQ_ERR_ROW(8) KVQ_ERR_ROW(16)
+#undef KVQ_ERR_ROW
+#undef KVQ_ERR_CASE
   return hipGetLastError();
 }
 
