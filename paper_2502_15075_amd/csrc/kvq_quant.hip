@@ -436,12 +436,20 @@ __global__ __launch_bounds__(256) void sq_error_kernel(Geom g, kvq_cache c, cons
       acc[which] += (double)sq;
     }
   }
+  // one atomic per workgroup and tensor: every head's two sums are hit by all the workgroups of that head, and atomics
+  // on one address are served one after the other
+  __shared__ double part[2][4];
 #pragma unroll
   for (int which = 0; which < 2; ++which) {
     double v = acc[which];
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-    if ((tid & 63) == 0 && v != 0.0) atomicAdd(sums + bh * 2 + which, v);
+    if ((tid & 63) == 0) part[which][tid >> 6] = v;
+  }
+  __syncthreads();
+  if (tid < 2) {
+    const double v = (part[tid][0] + part[tid][1]) + (part[tid][2] + part[tid][3]);
+    if (v != 0.0) atomicAdd(sums + bh * 2 + tid, v);
   }
 }
 
@@ -610,7 +618,8 @@ hipError_t launch_reconstruction_error(const Geom& g, const kvq_cache& c, const 
   hipLaunchKernelGGL(zero_f64_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, sums, n);
   if (t1 == t0) return hipGetLastError();
   const int64_t slabs = ((int64_t)(t1 - t0) + 15) / 16;
-  int64_t per_stream = (8192 + streams - 1) / streams;          // about 32 workgroups per compute unit in all
+  // about 32 workgroups per compute unit in all (measured: fewer leave latency exposed, more pile up on the atomics)
+  int64_t per_stream = (8192 + streams - 1) / streams;
   if (per_stream > slabs) per_stream = slabs;
   const dim3 grid((unsigned)per_stream, streams);
   const int bf = ref_dtype == KVQ_BF16 ? 1 : 0;
