@@ -155,9 +155,10 @@ static float load_elem(const void* base, int dtype, int64_t idx) {
 
 /* ------------------------------------------------------------------ sizes */
 
-/* Storage field of a b-bit code: the next of 2, 4, 8 (the paper's per-column back-end sweeps
- * {1,2,4,6,8} bits and Table 1 uses 3-bit keys; this format packs power-of-two fields only, so
- * 1-, 3- and 6-bit codes keep the accuracy of their width but take the space of the next field). */
+/* Storage field of a b-bit VALUE code: the next of 2, 4, 8 (the paper's per-column back-end sweeps
+ * {1,2,4,6,8} bits and Table 1 uses 3-bit keys; the blocked value layout packs power-of-two fields only, so
+ * 1-, 3- and 6-bit value codes keep the accuracy of their width but take the space of the next field; key
+ * rows are packed at their own width, see the format above). */
 int ref_field_bits(int b) { return b == 1 ? 2 : b == 3 ? 4 : b == 6 ? 8 : b; }
 static int bits_allowed(int b) { return b == 1 || b == 2 || b == 3 || b == 4 || b == 6 || b == 8; }
 

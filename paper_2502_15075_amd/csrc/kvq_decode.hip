@@ -7,8 +7,9 @@
 //
 // Both inner sums over codes are 16x16x32 f16 matrix instructions.  A b-bit code c placed in the
 // low mantissa bits of a binary16 lane is the subnormal c * 2^-24 (or c * 2^(k-24) when left at bit
-// k), which the matrix unit multiplies exactly, so "unpacking" is one AND per two codes; the
-// power-of-two position factors are divided out of the query operand once per wavefront.
+// k): the products with the query are exact and the sum is taken in a window of about 24 bits (see
+// the note at k_slot_elem), so "unpacking" is one AND per two codes; the power-of-two position
+// factors are divided out of the query operand once per wavefront.
 //
 // Work split: one workgroup (4 or 8 wavefronts) walks a contiguous range of 32-token steps of one
 // (batch, kv head); its wavefronts interleave the steps and each carries all query heads of that kv
@@ -18,8 +19,9 @@
 // in flight per wavefront.  Wavefronts merge through LDS, workgroups through a workspace of
 // (max, sum, acc) records and a small second kernel.
 //
-// Variants of the same kernel (template parameters): unquantized rows as operands (bits = 16),
-// two column sets (8 heads with 32-channel groups), channel-wise key groups (Sec. 4 "Downstream Task
+// Variants of the same kernel (template parameters): unquantized rows as operands (bits = 16), key
+// codes of 3 and 6 bits as a low and a high run with a query operand each, two column sets (8 heads
+// with 32-channel groups), channel-wise key groups (Sec. 4 "Downstream Task
 // Accuracy": the scale moves into a per-block query operand), paged planes (a page-table lookup per
 // step), per-sequence lengths, the fused append of a decode step, Hadamard-rotated keys and values
 // (Sec. 4 "Integration with Rotation-Based Methods").
@@ -863,13 +865,12 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
     const int gcs = grp + cs * kSetGroups;                     // the value group this lane's column carries in set cs
     if (gcs < g.ng_v) {
       const int dtg = 8 / g.ng_v;                              // d-tiles per value group
-      for (int dt = gcs * dtg; dt < (gcs + 1) * dtg; ++dt)
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-          float av = 0.f;
+      for (int dt = 0; dt < 8; ++dt)                           // (all eight tiles with their registers named at compile
+        if (dt / dtg == gcs) {                                 // time; the stores of the other groups' tiles are skipped)
+          float* dst = &sm_o[wave][h][16 * dt + 4 * L.j];
 #pragma unroll
-          for (int k = 0; k < 8; ++k) if (k == dt) av = st.acc[k][rr];   // static register indexing
-          sm_o[wave][h][16 * dt + 4 * L.j + rr] = fmaf(av, kInvUnit, z);
+          for (int rr = 0; rr < 4; ++rr) dst[rr] = fmaf(st.acc[dt][rr], kInvUnit, z);
         }
     }
   }
