@@ -62,6 +62,14 @@ def test_cache_bytes_closed_forms(kvq):
     Ls = kvq.Layout(2, 3, 100, 128, 4, 2, 64, 32, axis_k=kvq.AXIS_SEQ)
     assert kvq.cache_bytes(Ls) == [6 * 128 * 64, 6 * 2 * 512, 6 * 128 * 32, 6 * 128 * 16]
     assert kvq.residual_bytes(Ls) == [6 * 64 * 256, 6 * 64 * 256]
+    # ... in paged planes: the pool holds the code and scale/zero planes (128/64 blocks of scale/zero per page and head),
+    # the residual buffers stay per sequence
+    Lp = kvq.Layout(2, 3, 1000, 128, 4, 2, 64, 32, axis_k=kvq.AXIS_SEQ, page_tokens=128, n_pages=20)
+    assert kvq.cache_bytes(Lp) == [20 * 3 * 128 * 64, 20 * 3 * 2 * 512, 20 * 3 * 128 * 32, 20 * 3 * 128 * 16]
+    assert kvq.residual_bytes(Lp) == [6 * 64 * 256, 6 * 64 * 256]
+    # the workspace of a channel-wise cache always counts the record of the residual tail once there are flushed blocks
+    assert kvq.decode_workspace_bytes(Ls, 12, 63) == 0
+    assert kvq.decode_workspace_bytes(Ls, 12, 64) == kvq.decode_workspace_bytes(Ls, 12, 100) > 0
     assert kvq.residual_bytes(kvq.Layout(2, 3, 100)) == [0, 0]
 
 
