@@ -440,7 +440,7 @@ def test_reconstruction_error_of_unquantized_planes_is_zero(kvq, oracle):
 
 # --------------------------------------------------------------------------- key-only Hadamard rotation
 
-@pytest.mark.parametrize("bk,bv,gk,gv", [(4, 2, 64, 64), (2, 4, 32, 128), (8, 8, 128, 32), (2, 2, 64, 64)])
+@pytest.mark.parametrize("bk,bv,gk,gv", [(4, 2, 64, 64), (2, 4, 32, 128), (8, 8, 128, 32), (2, 2, 64, 64), (3, 2, 64, 64), (6, 3, 32, 64)])
 @pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
 def test_rotated_keys_planes_and_reconstruction_are_identical(kvq, oracle, bk, bv, gk, gv, dtype):
     """Sec. 4 rotation case study, key-only: ragged chunked appends give the oracle's bytes, kvq_dequantize gives the
@@ -470,7 +470,7 @@ def test_rotated_keys_planes_and_reconstruction_are_identical(kvq, oracle, bk, b
 
 
 @pytest.mark.parametrize("R", [1, 2, 4, 8])
-@pytest.mark.parametrize("bk,bv,gk,gv", [(4, 2, 64, 64), (2, 4, 64, 128), (8, 8, 64, 64)])
+@pytest.mark.parametrize("bk,bv,gk,gv", [(4, 2, 64, 64), (2, 4, 64, 128), (8, 8, 64, 64), (3, 2, 64, 64)])
 def test_rotated_keys_attention(kvq, oracle, R, bk, bv, gk, gv):
     B, H, T = 2, 2, 333
     K, V, q = synth.make_kvq(130 + R, B, H, H * R, T, dtype=torch.bfloat16)
@@ -494,7 +494,7 @@ def test_rotated_keys_small_groups_eight_heads_fp16_and_multi_split(kvq, oracle)
     assert _rel_err(out.cpu().numpy(), ref) < TOL
 
 
-@pytest.mark.parametrize("bk,bv,gk,gv,R", [(4, 2, 64, 64, 8), (4, 2, 32, 32, 4), (2, 4, 64, 128, 1)])
+@pytest.mark.parametrize("bk,bv,gk,gv,R", [(4, 2, 64, 64, 8), (4, 2, 32, 32, 4), (2, 4, 64, 128, 1), (3, 2, 64, 64, 4), (1, 4, 64, 64, 2)])
 def test_rotated_keys_fused_decode_steps(kvq, oracle, bk, bv, gk, gv, R):
     B, H, T0, nstep = 2, 2, 60, 6
     T = T0 + nstep
