@@ -1173,3 +1173,120 @@ def test_attention_extremes(kvq, oracle, case):
             ref = oracle.decode_attention(Lo, planes, qt.numpy(), seq_len, 1 / math.sqrt(128))
             assert np.isfinite(out).all(), (case, bk)
             assert _rel_err(out, ref) < TOL, (case, bk, seq_len, _rel_err(out, ref))
+
+
+# --------------------------------------------------------------------------- random configurations
+
+def _random_case(rng):
+    while True:
+        bk, bv = (int(rng.choice([1, 2, 3, 4, 6, 8])) for _ in range(2))
+        gk, gv = (int(rng.choice([32, 64, 128])) for _ in range(2))
+        r = int(rng.integers(1, 9))
+        R = 1 if r <= 1 else 2 if r <= 2 else 4 if r <= 4 else 8
+        if R * (128 // gk) <= 32 and R * (128 // gv) <= 32:
+            break
+    return dict(bk=bk, bv=bv, gk=gk, gv=gv, r=r, B=int(rng.integers(1, 4)), H=int(rng.integers(1, 4)),
+                T=int(rng.integers(1, 700)), bf16=bool(rng.integers(0, 2)), rot=int(rng.integers(0, 3) == 0),
+                rotv=int(rng.integers(0, 4) == 0), seed=int(rng.integers(0, 1 << 30)))
+
+
+@pytest.mark.parametrize("case", range(64))
+def test_random_token_wise_configurations(kvq, oracle, case):
+    """Seeded random layouts (all widths, group sizes, head ratios 1..8, rotations, both input types), ragged chunked
+    appends, attention at the full and at a shorter length, per-sequence lengths, two fused steps: planes byte-identical,
+    outputs within tolerance."""
+    c = _random_case(np.random.default_rng(4242 + case))
+    B, H, r, T = c["B"], c["H"], c["r"], c["T"]
+    dtype = torch.bfloat16 if c["bf16"] else torch.float16
+    K, V, q = synth.make_kvq(c["seed"], B, H, H * r, T + 2, dtype=dtype)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T + 2, c["bk"], c["bv"], c["gk"], c["gv"], raw=int(c["bf16"]), rot=c["rot"], rotv=c["rotv"])
+    rng = np.random.default_rng(c["seed"])
+    cuts = sorted(set([0, T] + [int(x) for x in rng.integers(0, T + 1, size=3)]))
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K[:, :, :T], V[:, :, :T], list(zip(cuts[:-1], cuts[1:])))
+    _assert_planes_equal(cache, planes)
+    qn = synth.to_numpy_bits(q) if c["bf16"] else q.numpy()
+    scale = 1 / math.sqrt(128)
+    for seq_len in {T, max(1, T // 3)}:
+        out = _decode(kvq, Lg, cache, q, seq_len)
+        ref = oracle.decode_attention(Lo, planes, qn, seq_len, scale, bf16=c["bf16"])
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, (c, seq_len)
+    lens = [int(x) for x in rng.integers(1, T + 1, size=B)]
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * r, T + 2)), dtype=torch.uint8, device="cuda")
+    out = torch.empty(B, H * r, 128, dtype=torch.float32, device="cuda")
+    kvq.decode_attention_varlen(Lg, cache, q.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"), T, scale, out, ws)
+    torch.cuda.synchronize()
+    ref = oracle.decode_attention_varlen(Lo, planes, qn, lens, scale, bf16=c["bf16"])
+    assert _rel_err(out.cpu().numpy(), ref) < TOL, (c, lens)
+    Kd, Vd = K.cuda(), V.cuda()
+    Kb = synth.to_numpy_bits(K) if c["bf16"] else K.numpy()
+    Vb = synth.to_numpy_bits(V) if c["bf16"] else V.numpy()
+    for pos in (T, T + 1):
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), scale, out, ws)
+        torch.cuda.synchronize()
+        oracle.quantize_append(Lo, planes, np.ascontiguousarray(Kb[:, :, pos:pos + 1]), np.ascontiguousarray(Vb[:, :, pos:pos + 1]),
+                               pos, bf16=c["bf16"])
+        _assert_planes_equal(cache, planes)
+        ref = oracle.decode_attention(Lo, planes, qn, pos + 1, scale, bf16=c["bf16"])
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, (c, pos)
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_channelwise_configurations(kvq, oracle, case):
+    """Seeded random channel-wise caches (2/4/8-bit codes, value group sizes, head ratios, contiguous or paged, both
+    input types): ragged chunked appends, attention over flushed blocks plus tail, fused steps across whatever boundary
+    the lengths happen to produce; all six planes byte-identical, outputs within tolerance."""
+    rng = np.random.default_rng(9000 + case)
+    bk, bv = (int(rng.choice([2, 4, 8])) for _ in range(2))
+    gv = int(rng.choice([32, 64, 128]))
+    r = int(rng.integers(1, 9))
+    if (1 if r <= 1 else 2 if r <= 2 else 4 if r <= 4 else 8) * (128 // gv) > 32:
+        gv = 64
+    B, H, T = int(rng.integers(1, 4)), int(rng.integers(1, 3)), int(rng.integers(1, 600))
+    bf16 = bool(rng.integers(0, 2))
+    P = int(rng.choice([0, 64, 128, 256]))
+    cap = T + 3
+    dtype = torch.bfloat16 if bf16 else torch.float16
+    K, V, q = synth.make_kvq(int(rng.integers(0, 1 << 30)), B, H, H * r, cap, dtype=dtype)
+    if P:
+        pps = -(-cap // P)
+        n_pages = B * pps + 1
+        table = rng.permutation(n_pages)[:B * pps].reshape(B, pps).astype(np.int32)
+        Lg = kvq.Layout(B, H, cap, 128, bk, bv, 64, gv, axis_k=kvq.AXIS_SEQ, raw_dtype=int(bf16), page_tokens=P, n_pages=n_pages)
+        Lo = oracle.Layout(B, H, pps * P, 128, bk, bv, 64, gv, raw_dtype=int(bf16), axis_k=1)
+    else:
+        Lg, Lo = _seq_layouts(kvq, oracle, B, H, cap, bk, bv, gv, raw=int(bf16))
+    cache = kvq.Cache(Lg, fill=0x5A)
+    if P:
+        cache.page_table = torch.from_numpy(table).cuda()
+    planes = oracle.new_seq_planes(Lo, fill=0x5A)
+    Kd, Vd = K.cuda(), V.cuda()
+    Kb = synth.to_numpy_bits(K) if bf16 else K.numpy()
+    Vb = synth.to_numpy_bits(V) if bf16 else V.numpy()
+
+    def check_planes():
+        torch.cuda.synchronize()
+        got = [p.cpu().numpy() for p in cache.planes]
+        if P:
+            got = oracle.gather_pages(Lo, got[:4], table, P, n_pages) + got[4:]
+        for name, g, o in zip(("k_codes", "k_meta", "v_codes", "v_meta", "k_resid", "v_resid"), got, planes):
+            bad = np.flatnonzero(g != o)
+            assert bad.size == 0, f"{name}: {bad.size} bytes differ, first at {bad[:5]}"
+
+    cuts = sorted(set([0, T] + [int(x) for x in rng.integers(0, T + 1, size=3)]))
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        kvq.quantize_append(Lg, cache, Kd[:, :, a:b], Vd[:, :, a:b], a)
+        oracle.seq_append(Lo, planes, np.ascontiguousarray(Kb[:, :, a:b]), np.ascontiguousarray(Vb[:, :, a:b]), a, bf16=bf16)
+    check_planes()
+    qn = synth.to_numpy_bits(q) if bf16 else q.numpy()
+    scale = 1 / math.sqrt(128)
+    out = _decode(kvq, Lg, cache, q, T)
+    ref = oracle.seq_decode_attention(Lo, planes, qn, T, scale, bf16=bf16)
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+    outs = torch.empty(B, H * r, 128, dtype=torch.float32, device="cuda")
+    for pos in range(T, T + 3):
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * r, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), scale, outs, ws)
+        oracle.seq_append(Lo, planes, np.ascontiguousarray(Kb[:, :, pos:pos + 1]), np.ascontiguousarray(Vb[:, :, pos:pos + 1]), pos, bf16=bf16)
+        check_planes()
+        ref = oracle.seq_decode_attention(Lo, planes, qn, pos + 1, scale, bf16=bf16)
+        assert _rel_err(outs.cpu().numpy(), ref) < TOL, pos
