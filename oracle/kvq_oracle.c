@@ -62,12 +62,15 @@
  *   *_meta     [B][H][T_cap/16][D/G][16] entries of 4 bytes: little-endian uint16 scale
  *              then little-endian uint16 zero (both binary16 bit patterns); entry
  *              (t/16, g, t%16) belongs to token t, group g.
- *   v_codes    [B][H][T_cap/32][512*b_V] bytes: blocks of 32 tokens.  Inside a block the
+ *   v_codes    [B][H][T_cap/32][512*b_V] bytes: blocks of 32 tokens (b_V here: the field a code takes, 1, 2, 4, 8 or
+ *              16; codes of 3 and 6 bits sit in the low bits of 4- and 8-bit fields).  Inside a block the
  *              code of (token t, channel d) lives in a little-endian 32-bit word found as
  *                u = t%32; x4 = u/16; j = (u%16)/4; r = u%4; i = 4*x4 + r; x = i%2; v = i/2;
  *                q = 4*(d/16) + v; P = 16/b_V; e = q/P; p = q%P;
  *                word byte offset = (e/4)*(8*D) + (16*j + d%16)*16 + 4*(e%4);
- *                bit offset inside the word = 16*x + b_V*p.
+ *                bit offset inside the word = 16*x + b_V*p;
+ *              b_V = 1 (P = 16) has one piece of D/64 words per lane instead:
+ *                word byte offset = (16*j + d%16)*(D/16) + 4*e   (8 bytes per lane for D = 128).
  *              (For D = 128 the stride 8*D is 1024 bytes: one 16-byte piece per wavefront
  *              lane.  The order is the one in which a 16x16x32 matrix instruction wants a
  *              "tokens x channels" operand, so a decode kernel needs no transpose.)
@@ -91,7 +94,7 @@ enum { REF_F16 = 0, REF_BF16 = 1, REF_F32 = 2 };
 typedef struct {
   int32_t batch, kv_heads, max_seq, head_dim;
   int32_t bits_k, bits_v;   /* 1, 2, 3, 4, 6, 8, or 16 = keep the 16-bit input unquantized.  Key codes are stored at
-                               their own width; value codes of widths 1, 3 and 6 are stored in 2-, 4- and 8-bit fields
+                               their own width; value codes of widths 3 and 6 are stored in 4- and 8-bit fields
                                (field_bits): the blocked value layout has power-of-two fields only */
   int32_t group_k, group_v; /* G: consecutive head_dim elements sharing one scale/zero */
   int32_t raw_dtype;        /* REF_F16 or REF_BF16: meaning of the planes when bits == 16 */
@@ -155,11 +158,11 @@ static float load_elem(const void* base, int dtype, int64_t idx) {
 
 /* ------------------------------------------------------------------ sizes */
 
-/* Storage field of a b-bit VALUE code: the next of 2, 4, 8 (the paper's per-column back-end sweeps
- * {1,2,4,6,8} bits and Table 1 uses 3-bit keys; the blocked value layout packs power-of-two fields only, so
- * 1-, 3- and 6-bit value codes keep the accuracy of their width but take the space of the next field; key
- * rows are packed at their own width, see the format above). */
-int ref_field_bits(int b) { return b == 1 ? 2 : b == 3 ? 4 : b == 6 ? 8 : b; }
+/* Storage field of a b-bit VALUE code (the paper's per-column back-end sweeps {1,2,4,6,8} bits and Table 1 has
+ * 3-bit caches): the blocked value layout packs power-of-two fields only, so 3- and 6-bit value codes keep the
+ * accuracy of their width but take the space of the next field (4, 8); 1-bit value codes and key rows of every
+ * width are packed at their own width, see the format above. */
+int ref_field_bits(int b) { return b == 3 ? 4 : b == 6 ? 8 : b; }
 static int bits_allowed(int b) { return b == 1 || b == 2 || b == 3 || b == 4 || b == 6 || b == 8; }
 
 static int64_t cap_tokens(const ref_layout* L) {
@@ -198,7 +201,10 @@ static void v_position(int64_t t, int d, int D, int b, int64_t* word_byte, int* 
   int q = 4 * (d / 16) + v;
   int P = 16 / b;
   int e = q / P, p = q % P;
-  *word_byte = blk * (32 * (int64_t)D * b / 8) + (int64_t)(e / 4) * (8 * D) + (16 * j + d % 16) * 16 + 4 * (e % 4);
+  if (b == 1)                     /* 1-bit codes: a lane piece is D/64 words (8 bytes for D = 128), one piece per block */
+    *word_byte = blk * (4 * (int64_t)D) + (16 * j + d % 16) * (D / 16) + 4 * e;
+  else
+    *word_byte = blk * (32 * (int64_t)D * b / 8) + (int64_t)(e / 4) * (8 * D) + (16 * j + d % 16) * 16 + 4 * (e % 4);
   *bit = 16 * x + b * p;
 }
 

@@ -226,12 +226,12 @@ def _pack_key_rows_numpy(codes, bits):
     return np.concatenate([low, high], axis=2).ravel()
 
 
-@pytest.mark.parametrize("bits,field", [(1, 2), (3, 4), (6, 8)])
+@pytest.mark.parametrize("bits,field", [(1, 1), (3, 4), (6, 8)])
 def test_odd_widths_keys_at_their_width_values_in_power_of_two_fields(oracle, bits, field):
     """1-, 3- and 6-bit codes (the per-column back-end's grid {1,2,4,6,8}, Table 1's 3-bit keys) are quantized with
-    2^b - 1 steps.  Key rows take D*b/8 bytes (3 and 6 bits as a low and a high run per 32 channels); value codes sit
-    in the next power-of-two field of the blocked layout.  Planes = numpy's packing of numpy's b-bit codes, sizes
-    accordingly, reconstruction = code * scale + zero."""
+    2^b - 1 steps.  Key rows take D*b/8 bytes (3 and 6 bits as a low and a high run per 32 channels); value codes of
+    3 and 6 bits sit in the next power-of-two field of the blocked layout, 1-bit value codes take one bit.  Planes =
+    numpy's packing of numpy's b-bit codes, sizes accordingly, reconstruction = code * scale + zero."""
     rng = np.random.default_rng(bits)
     B, H, T, D, G = 1, 2, 64, 128, 64
     x = (rng.standard_normal((B, H, T, D)) * 2).astype(np.float16)

@@ -231,13 +231,15 @@ def _expected_planes(codes, S, Z, b, G):
     W = A.transpose(0, 5, 1, 3, 2, 6, 4)                                # blk dt x4 rh j dl x
     W = W.reshape(T // 32, (D // 16) * 4 // P, P, 4, 16, 2)             # blk e p j dl x      ((dt,x4,rh) -> (e,p))
     W = W.transpose(0, 1, 3, 4, 5, 2)                                   # blk e j dl x p
+    if b == 1:                                                          # one piece: the lane's D/64 words side by side
+        return k_plane, meta, _pack_fields_le(W.transpose(0, 2, 3, 1, 4, 5).ravel(), b)
     W = W.reshape(T // 32, (D // 16) * 4 // P // 4, 4, 4, 16, 2, P)     # blk piece m j dl x p
     W = W.transpose(0, 1, 3, 4, 2, 5, 6)                                # blk piece j dl m x p
     v_plane = _pack_fields_le(W.ravel(), b)
     return k_plane, meta, v_plane
 
 
-@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("bits", [1, 2, 4, 8])
 @pytest.mark.parametrize("G", [32, 128])
 def test_plane_layouts_against_array_transposes(oracle, bits, G):
     rng = np.random.default_rng(bits + G)
