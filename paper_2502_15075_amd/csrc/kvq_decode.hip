@@ -145,17 +145,21 @@ template <int BK> constexpr int k_lo() { return key_lo_bits<BK>(); }
 template <int BK> constexpr int k_hi() { return key_hi_bits<BK>(); }
 template <int BK> constexpr int k_hi_base() { return BK == 3 ? 5 : 6; }   // high run: single bits from bit 5, pairs from bit 6
 
-// ---- value codes: one lane holds, per 32-token step, 2*BV dwords (index = 4*piece + dword) ----
+// ---- value codes: one lane holds, per 32-token step, 2*BV dwords (index = 4*piece + dword; 1-bit codes: one piece
+// of two dwords, d-tile dt's 8 codes in nibble dt%4 of each half of dword dt/4) ----
 // Register v (0..3) of d-tile dt's operand holds slots 2v, 2v+1 and is left at bit offset v_slot_shift(v)
 // of its 16-bit lane, i.e. it reads as code * 2^shift * 2^-24; the softmax weight of those slots is
 // divided by 2^shift instead (an exponent offset, free).
 template <int BV> __device__ __forceinline__ constexpr int v_slot_shift(int v) {
-  return BV == 2 ? 2 * v : (BV == 4 ? 4 * (v & 1) : 0);
+  return BV == 1 ? v : BV == 2 ? 2 * v : (BV == 4 ? 4 * (v & 1) : 0);
 }
 template <int BV> __device__ __forceinline__ u32x4 unpack_v(const uint32_t* w, int dt) {
   u32x4 a;
   if (BV == 16) {
     a = u32x4{w[4 * dt], w[4 * dt + 1], w[4 * dt + 2], w[4 * dt + 3]};
+  } else if (BV == 1) {
+    const uint32_t ws = w[dt >> 2] >> (4 * (dt & 3));
+    a = u32x4{ws & 0x00010001u, ws & 0x00020002u, ws & 0x00040004u, ws & 0x00080008u};
   } else if (BV == 2) {
     const uint32_t ws = w[dt >> 1] >> (8 * (dt & 1));
     a = u32x4{ws & 0x00030003u, ws & 0x000C000Cu, ws & 0x00300030u, ws & 0x00C000C0u};
@@ -261,6 +265,7 @@ __device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L,
   if constexpr (BK != 16)
     r.meta = ld16(mbase + ((WIDE ? 0u : ((uint32_t)step & L.meta_step_mask) * L.meta_mul) + (L.meta_off & lane_mask)));
   const uint32_t vo = (WIDE ? 0u : (uint32_t)step * (512 * BV)) + (L.vc_off & lane_mask);
+  if constexpr (BV == 1) load_dwords<2>(r.vc, vbase + vo);
 #pragma unroll
   for (int k = 0; k < BV / 2; ++k) {
     const u32x4 v = ld16(vbase + (vo + k * 1024));
@@ -544,21 +549,24 @@ __device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, i
 
 // Second half of the fused append: thread d < 128 inserts channel d's code of token seq_len-1 into its 32-bit word
 // (read-modify-write; the other fields of the word belong to other tokens of the same 32-token block).  With 2-bit
-// codes channels d and d+16 share a word, so the thread of the even 16-channel tile writes both.
+// codes channels d and d+16 share a word (with 1-bit codes d, d+16, d+32 and d+48), so the thread of the first of
+// those 16-channel tiles writes them all.
 template <int BV>
 __device__ __forceinline__ void append_one_values(const DecodeArgs& a, int bh, int tid, const uint8_t* vstage, int64_t t) {
+  constexpr int NF = BV == 1 ? 4 : BV == 2 ? 2 : 1;       // 16-channel tiles with a field in the same word
   if (tid >= kHeadDim) return;
-  if (BV == 2 && ((tid >> 4) & 1)) return;
+  if ((tid >> 4) & (NF - 1)) return;
   const Geom& g = a.g;
   uint32_t* blk = (uint32_t*)((uint8_t*)a.cache.v_codes + (int64_t)bh * g.vc_stream) + (t >> 5) * (int64_t)(128 * BV);
   const uint32_t fmask = (1u << BV) - 1u;
   int dw, bit;
   v_field((int)(t & 31), tid, BV, &dw, &bit);
-  uint32_t w = (blk[dw] & ~(fmask << bit)) | ((uint32_t)vstage[tid] << bit);
-  if (BV == 2) {
-    int dw2, bit2;
-    v_field((int)(t & 31), tid + 16, BV, &dw2, &bit2);    // same word, the neighbouring tile's field
-    w = (w & ~(fmask << bit2)) | ((uint32_t)vstage[tid + 16] << bit2);
+  uint32_t w = blk[dw];
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
+    int dwf, bitf;
+    v_field((int)(t & 31), tid + 16 * f, BV, &dwf, &bitf);   // same word, the neighbouring tiles' fields
+    w = (w & ~(fmask << bitf)) | ((uint32_t)vstage[tid + 16 * f] << bitf);
   }
   blk[dw] = w;
 }
@@ -637,7 +645,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   L.kc = (const uint8_t*)cache.k_codes + bh_base * g.kc_stream;
   L.vc = (const uint8_t*)cache.v_codes + bh_base * g.vc_stream;
   L.kc_off = L.c * (16 * BK) + L.j * (4 * BK);
-  L.vc_off = lane * 16;
+  L.vc_off = lane * (BV == 1 ? 8 : 16);
   {
     // channel-wise keys: 512 bytes of scale/zero per 64-token block (32 lanes), fetched with both steps of the block
     const int nk = KSEQ ? 32 : 8 * g.ng_k, nv = 8 * g.ng_v;
@@ -1027,7 +1035,8 @@ hipError_t KVQ_CAT(launch_decode_inst_, KVQ_INST_BK, KVQ_INST_BV)(int R, const D
 #else
 // ---- dispatcher translation unit ----------------------------------------------------------------------------------------
 #define KVQ_FOR_EACH_PAIR(X) X(4, 2) X(2, 4) X(4, 4) X(8, 8) X(2, 2) X(8, 4) X(8, 2) X(4, 8) X(2, 8) X(16, 16) \
-  X(3, 2) X(3, 4) X(3, 8) X(6, 2) X(6, 4) X(6, 8) X(1, 2) X(1, 4) X(1, 8)
+  X(3, 2) X(3, 4) X(3, 8) X(6, 2) X(6, 4) X(6, 8) X(1, 2) X(1, 4) X(1, 8) \
+  X(1, 1) X(2, 1) X(3, 1) X(4, 1) X(6, 1) X(8, 1)
 #define KVQ_DECL(BK_, BV_) \
   hipError_t KVQ_CAT(launch_decode_inst_, BK_, BV_)(int R, const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream);
 KVQ_FOR_EACH_PAIR(KVQ_DECL)

@@ -15,8 +15,8 @@ constexpr int kSeqGroup = 64;     // channel-wise keys: tokens per key group = s
 struct Geom {
   int32_t batch, kv_heads, t_cap;   // t_cap = max_seq rounded up to kBlockTokens
   int32_t bits_k, bits_v, ng_k, ng_v, g_k, g_v;   // bits: what a code takes in its plane (16 = unquantized): keys their
-                                    // own width (1, 2, 3, 4, 6, 8), values the power-of-two field (2, 4, 8)
-  int32_t qbits_k, qbits_v;         // quantizer widths: 2^qbits - 1 steps (value widths 1, 3, 6 live in the next larger field)
+                                    // own width (1, 2, 3, 4, 6, 8), values the power-of-two field (1, 2, 4, 8)
+  int32_t qbits_k, qbits_v;         // quantizer widths: 2^qbits - 1 steps (value widths 3 and 6 live in the next larger field)
   int32_t raw_dtype;
   int32_t axis_k;                   // KVQ_AXIS_SEQ: channel-wise key groups of kSeqGroup tokens + residual buffer;
                                     // then g_k = 128 and ng_k = 1 (one matrix column per head on the key side)
@@ -32,7 +32,7 @@ struct Geom {
 };
 
 inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
-inline int field_bits(int b) { return b == 1 ? 2 : b == 3 ? 4 : b == 6 ? 8 : b; }
+inline int field_bits(int b) { return b == 3 ? 4 : b == 6 ? 8 : b; }
 
 inline Geom make_geom(const kvq_layout& L) {
   Geom g{};
@@ -141,7 +141,7 @@ __device__ inline int64_t virtual_token(const Geom& g, const int32_t* __restrict
 __host__ __device__ inline int64_t meta_index(int64_t t, int g, int ng) { return ((t >> 4) * ng + g) * 16 + (t & 15); }
 
 // Position of value code (u = token inside its 32-token block, d) for bit width b:
-// dword index inside the block and bit offset inside the dword.
+// dword index inside the block and bit offset inside the dword.  A lane's piece is 4 dwords, for 1-bit codes 2.
 __host__ __device__ inline void v_field(int u, int d, int b, int* dword, int* bit) {
   int x4 = u >> 4, j = (u >> 2) & 3, r = u & 3;
   int i = 4 * x4 + r;
@@ -149,7 +149,7 @@ __host__ __device__ inline void v_field(int u, int d, int b, int* dword, int* bi
   int q = 4 * (d >> 4) + v;
   int P = 16 / b;
   int e = q / P, p = q % P;
-  *dword = (e >> 2) * 256 + (16 * j + (d & 15)) * 4 + (e & 3);
+  *dword = b == 1 ? (16 * j + (d & 15)) * 2 + e : (e >> 2) * 256 + (16 * j + (d & 15)) * 4 + (e & 3);
   *bit = 16 * x + b * p;
 }
 #endif

@@ -22,26 +22,28 @@ __device__ __forceinline__ int stage_phys(int a) { return a + ((a >> 8) << 4); }
 // Pack the codes held one per byte in w (first code in the lowest byte) into adjacent b-bit fields.
 // (Bytes of tokens that were not staged hold garbage: they are masked to b bits so that they stay inside their field.)
 template <int B> __device__ __forceinline__ uint32_t pack_bytes(uint32_t w) {
+  if (B == 1) { w &= 0x01010101u; return (w | (w >> 7) | (w >> 14) | (w >> 21)) & 0xFu; }
   if (B == 2) { w &= 0x03030303u; return (w | (w >> 6) | (w >> 12) | (w >> 18)) & 0xFFu; }
   if (B == 4) return (w & 0xFu) | ((w >> 4) & 0xF0u) | ((w >> 8) & 0xF00u) | ((w >> 12) & 0xF000u);
   return w;
 }
 
 // Token row (0..63 of the span) -> (block, word family, field): the codes of the 8 channels d0..d0+7 of this lane go
-// to 8 words 4 apart; they are staged in LDS in storage order, one element per code.
+// to 8 words one lane piece (LW = 4 words, 2 for 1-bit codes) apart; they are staged in LDS in storage order, one
+// element per code.
 template <int BV>
 __device__ __forceinline__ void stage_value_codes(uint8_t* vstage, int row, int d0, const uint32_t codes[8]) {
-  constexpr int F = 32 / BV, P = 16 / BV, ES = BV == 16 ? 2 : 1;
+  constexpr int F = 32 / BV, P = 16 / BV, ES = BV == 16 ? 2 : 1, LW = BV == 1 ? 2 : 4;
   const int sub = row >> 5, u = row & 31;
   const int j = (u >> 2) & 3, i = 4 * (u >> 4) + (u & 3);
   const int x = i & 1, v = i >> 1;
   const int q = 4 * (d0 >> 4) + v;
   const int e_idx = q / P, p = q % P;
-  const int word0 = sub * (128 * BV) + (e_idx >> 2) * 256 + (16 * j + (d0 & 15)) * 4 + (e_idx & 3);
+  const int word0 = sub * (128 * BV) + (BV == 1 ? 0 : (e_idx >> 2) * 256) + (16 * j + (d0 & 15)) * LW + (e_idx & (LW - 1));
   const int a0 = (word0 * F + x * P + p) * ES;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const int a = stage_phys(a0 + e * 4 * F * ES);
+    const int a = stage_phys(a0 + e * LW * F * ES);
     if (BV == 16) *reinterpret_cast<uint16_t*>(vstage + a) = (uint16_t)codes[e];
     else vstage[a] = (uint8_t)codes[e];
   }
@@ -56,7 +58,11 @@ __device__ __forceinline__ void store_value_words(uint32_t* vc, const uint8_t* v
   for (int w = tid; w < 256 * BV; w += 256) {
     const uint8_t* sp = vstage + stage_phys(w * F * ES);
     uint32_t bits;
-    if (BV == 2) {
+    if (BV == 1) {
+      const uint4 r0 = *reinterpret_cast<const uint4*>(sp), r1 = *reinterpret_cast<const uint4*>(sp + 16);
+      bits = pack_bytes<1>(r0.x) | (pack_bytes<1>(r0.y) << 4) | (pack_bytes<1>(r0.z) << 8) | (pack_bytes<1>(r0.w) << 12) |
+             (pack_bytes<1>(r1.x) << 16) | (pack_bytes<1>(r1.y) << 20) | (pack_bytes<1>(r1.z) << 24) | (pack_bytes<1>(r1.w) << 28);
+    } else if (BV == 2) {
       const uint4 r = *reinterpret_cast<const uint4*>(sp);
       bits = pack_bytes<2>(r.x) | (pack_bytes<2>(r.y) << 8) | (pack_bytes<2>(r.z) << 16) | (pack_bytes<2>(r.w) << 24);
     } else if (BV == 4) {
@@ -69,7 +75,7 @@ __device__ __forceinline__ void store_value_words(uint32_t* vc, const uint8_t* v
     // partially covered span: keep the fields of tokens outside [lo, hi)
     const int sub = w / (128 * BV), wi = w % (128 * BV);
     const int piece = wi >> 8, rem = wi & 255;
-    const int L = rem >> 2, m = rem & 3;
+    const int L = BV == 1 ? wi >> 1 : rem >> 2, m = BV == 1 ? wi & 1 : rem & 3;
     const int e_idx = 4 * piece + m;
     const int j = L >> 4;
     const uint32_t fmask = BV == 16 ? 0xFFFFu : ((1u << BV) - 1u);
@@ -172,13 +178,14 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
   store_value_words<BV>(vc, vstage, tid, lo, hi);
 }
 
-// The 8 codes of channels d0 .. d0+7 (d0 a multiple of 8) of value row t: the same field of 8 words 16 bytes apart.
+// The 8 codes of channels d0 .. d0+7 (d0 a multiple of 8) of value row t: the same field of 8 words one lane piece
+// (16 bytes, 8 for 1-bit codes) apart.
 template <int B> __device__ __forceinline__ void value_codes8(const uint8_t* cs, int64_t t, int d0, uint32_t code[8]) {
   int dw, bit;
   v_field((int)(t & 31), d0, B, &dw, &bit);
   const uint32_t* blk = reinterpret_cast<const uint32_t*>(cs + (t >> 5) * (int64_t)(512 * B)) + dw;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) code[e] = (blk[4 * e] >> bit) & (B == 16 ? 0xFFFFu : ((1u << B) - 1u));
+  for (int e = 0; e < 8; ++e) code[e] = (blk[(B == 1 ? 2 : 4) * e] >> bit) & (B == 16 ? 0xFFFFu : ((1u << B) - 1u));
 }
 
 // Channel-wise keys (Sec. 4 "Downstream Task Accuracy": the per-column back-end with its residual buffer).
@@ -344,6 +351,7 @@ __device__ __forceinline__ void reconstruct8_t(const Geom& g, const kvq_cache& c
 __device__ __forceinline__ void reconstruct8(const Geom& g, const kvq_cache& c, int which, int64_t t, int d0, float val[8]) {
   if (which) {
     switch (g.bits_v) {
+      case 1: return reconstruct8_t<1, true>(g, c, t, d0, val);
       case 2: return reconstruct8_t<2, true>(g, c, t, d0, val);
       case 4: return reconstruct8_t<4, true>(g, c, t, d0, val);
       case 8: return reconstruct8_t<8, true>(g, c, t, d0, val);
@@ -508,6 +516,7 @@ template <int BK>
 hipError_t launch_qk(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype, int64_t sb,
                      int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
   switch (g.bits_v) {
+    case 1: return launch_q<BK, 1>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 2: return launch_q<BK, 2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 4: return launch_q<BK, 4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 8: return launch_q<BK, 8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
@@ -627,7 +636,7 @@ hipError_t launch_reconstruction_error(const Geom& g, const kvq_cache& c, const 
   if (g.bits_k == BK_ && g.bits_v == BV_)                                                                               \
     hipLaunchKernelGGL((sq_error_kernel<BK_, BV_>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_ref,           \
                        (const uint16_t*)v_ref, bf, sb, sh, st, t0, t1, sums);
-#define KVQ_ERR_ROW(BK_) KVQ_ERR_CASE(BK_, 2) KVQ_ERR_CASE(BK_, 4) KVQ_ERR_CASE(BK_, 8) KVQ_ERR_CASE(BK_, 16)
+#define KVQ_ERR_ROW(BK_) KVQ_ERR_CASE(BK_, 1) KVQ_ERR_CASE(BK_, 2) KVQ_ERR_CASE(BK_, 4) KVQ_ERR_CASE(BK_, 8) KVQ_ERR_CASE(BK_, 16)
   KVQ_ERR_ROW(1) KVQ_ERR_ROW(2) KVQ_ERR_ROW(3) KVQ_ERR_ROW(4) KVQ_ERR_ROW(6) KVQ_ERR_ROW(8) KVQ_ERR_ROW(16)
 #undef KVQ_ERR_ROW
 #undef KVQ_ERR_CASE
