@@ -62,14 +62,15 @@
  *   *_meta     [B][H][T_cap/16][D/G][16] entries of 4 bytes: little-endian uint16 scale
  *              then little-endian uint16 zero (both binary16 bit patterns); entry
  *              (t/16, g, t%16) belongs to token t, group g.
- *   v_codes    [B][H][T_cap/32][512*b_V] bytes: blocks of 32 tokens (b_V here: the field a code takes, 1, 2, 4, 8 or
- *              16; codes of 3 and 6 bits sit in the low bits of 4- and 8-bit fields).  Inside a block the
+ *   v_codes    [B][H][T_cap/32][512*b_V] bytes: blocks of 32 tokens.  b_V = 3 and 6: a block is a block of LO-bit
+ *              fields (LO = 2, 4) holding code mod 2^LO followed by a block of (b_V - LO)-bit fields holding
+ *              code >> LO, each laid out as follows for its own field width.  Inside a block of b-bit fields the
  *              code of (token t, channel d) lives in a little-endian 32-bit word found as
  *                u = t%32; x4 = u/16; j = (u%16)/4; r = u%4; i = 4*x4 + r; x = i%2; v = i/2;
- *                q = 4*(d/16) + v; P = 16/b_V; e = q/P; p = q%P;
+ *                q = 4*(d/16) + v; P = 16/b; e = q/P; p = q%P;
  *                word byte offset = (e/4)*(8*D) + (16*j + d%16)*16 + 4*(e%4);
- *                bit offset inside the word = 16*x + b_V*p;
- *              b_V = 1 (P = 16) has one piece of D/64 words per lane instead:
+ *                bit offset inside the word = 16*x + b*p;
+ *              b = 1 (P = 16) has one piece of D/64 words per lane instead:
  *                word byte offset = (16*j + d%16)*(D/16) + 4*e   (8 bytes per lane for D = 128).
  *              (For D = 128 the stride 8*D is 1024 bytes: one 16-byte piece per wavefront
  *              lane.  The order is the one in which a 16x16x32 matrix instruction wants a
@@ -93,9 +94,8 @@ enum { REF_F16 = 0, REF_BF16 = 1, REF_F32 = 2 };
 
 typedef struct {
   int32_t batch, kv_heads, max_seq, head_dim;
-  int32_t bits_k, bits_v;   /* 1, 2, 3, 4, 6, 8, or 16 = keep the 16-bit input unquantized.  Key codes are stored at
-                               their own width; value codes of widths 3 and 6 are stored in 4- and 8-bit fields
-                               (field_bits): the blocked value layout has power-of-two fields only */
+  int32_t bits_k, bits_v;   /* 1, 2, 3, 4, 6, 8, or 16 = keep the 16-bit input unquantized.  Codes of both tensors
+                               are stored at their own width */
   int32_t group_k, group_v; /* G: consecutive head_dim elements sharing one scale/zero */
   int32_t raw_dtype;        /* REF_F16 or REF_BF16: meaning of the planes when bits == 16 */
   int32_t rotate_k;         /* 1: key rows are stored as codes of R k (needs bits_k < 16) */
@@ -158,11 +158,6 @@ static float load_elem(const void* base, int dtype, int64_t idx) {
 
 /* ------------------------------------------------------------------ sizes */
 
-/* Storage field of a b-bit VALUE code (the paper's per-column back-end sweeps {1,2,4,6,8} bits and Table 1 has
- * 3-bit caches): the blocked value layout packs power-of-two fields only, so 3- and 6-bit value codes keep the
- * accuracy of their width but take the space of the next field (4, 8); 1-bit value codes and key rows of every
- * width are packed at their own width, see the format above. */
-int ref_field_bits(int b) { return b == 3 ? 4 : b == 6 ? 8 : b; }
 static int bits_allowed(int b) { return b == 1 || b == 2 || b == 3 || b == 4 || b == 6 || b == 8; }
 
 static int64_t cap_tokens(const ref_layout* L) {
@@ -176,7 +171,7 @@ int ref_plane_bytes(const ref_layout* L, uint64_t out[4]) {
   int D = L->head_dim;
   out[0] = (uint64_t)(rows * (D * L->bits_k / 8));
   out[1] = L->bits_k == 16 ? 0 : L->axis_k == 1 ? (uint64_t)(rows / L->group_k * D * 4) : (uint64_t)(rows * (D / L->group_k) * 4);
-  out[2] = (uint64_t)(rows * (D * ref_field_bits(L->bits_v) / 8));
+  out[2] = (uint64_t)(rows * (D * L->bits_v / 8));
   out[3] = L->bits_v == 16 ? 0 : (uint64_t)(rows * (D / L->group_v) * 4);
   return 0;
 }
@@ -191,10 +186,9 @@ static int64_t meta_offset(int64_t t, int g, int ngroups) {
 /* K codes: bit offset of (t, d) inside one (b,h) stream, widths 1, 2, 4, 8, 16 */
 static int64_t k_bit_offset(int64_t t, int d, int D, int b) { return (t * D + d) * b; }
 
-/* V codes: byte offset of the 32-bit word and bit offset inside it, one (b,h) stream */
-static void v_position(int64_t t, int d, int D, int b, int64_t* word_byte, int* bit) {
-  int64_t blk = t / 32;
-  int u = (int)(t % 32);
+/* V codes, one 32-token block of b-bit fields (b = 1, 2, 4, 8, 16): byte offset of the 32-bit word of (u = t%32, d)
+ * inside the block and bit offset inside the word */
+static void v_in_block(int u, int d, int D, int b, int64_t* word_byte, int* bit) {
   int x4 = u / 16, j = (u % 16) / 4, r = u % 4;
   int i = 4 * x4 + r;
   int x = i % 2, v = i / 2;
@@ -202,9 +196,9 @@ static void v_position(int64_t t, int d, int D, int b, int64_t* word_byte, int* 
   int P = 16 / b;
   int e = q / P, p = q % P;
   if (b == 1)                     /* 1-bit codes: a lane piece is D/64 words (8 bytes for D = 128), one piece per block */
-    *word_byte = blk * (4 * (int64_t)D) + (16 * j + d % 16) * (D / 16) + 4 * e;
+    *word_byte = (16 * j + d % 16) * (D / 16) + 4 * e;
   else
-    *word_byte = blk * (32 * (int64_t)D * b / 8) + (int64_t)(e / 4) * (8 * D) + (16 * j + d % 16) * 16 + 4 * (e % 4);
+    *word_byte = (int64_t)(e / 4) * (8 * D) + (16 * j + d % 16) * 16 + 4 * (e % 4);
   *bit = 16 * x + b * p;
 }
 
@@ -237,6 +231,31 @@ static uint32_t k_get_code(const uint8_t* cs, int64_t t, int d, int D, int b) {
   int lo = b == 3 ? 2 : 4, hi = b - lo, x = d % 32;
   int64_t chunk = (t * D + (d - x)) * b;
   return get_bits_le(cs, chunk + (int64_t)x * lo, lo) | (get_bits_le(cs, chunk + 32 * lo + (int64_t)x * hi, hi) << lo);
+}
+
+/* V codes of any width in one (b,h) stream: a block of 32 tokens takes 4*D*b bytes; widths 3 and 6 keep the codes' low
+ * 2 (4) bits as a block of 2-bit (4-bit) fields followed by their high 1 (2) bits as a block of 1-bit (2-bit) fields */
+static void v_put_code(uint8_t* cs, int64_t t, int d, int D, int b, uint32_t code) {
+  uint8_t* blk = cs + (t / 32) * (4 * (int64_t)D * b);
+  int u = (int)(t % 32), bit;
+  int64_t wb;
+  if (b != 3 && b != 6) { v_in_block(u, d, D, b, &wb, &bit); put_bits_le(blk + wb, bit, b, code); return; }
+  int lo = b == 3 ? 2 : 4, hi = b - lo;
+  v_in_block(u, d, D, lo, &wb, &bit);
+  put_bits_le(blk + wb, bit, lo, code & ((1u << lo) - 1u));
+  v_in_block(u, d, D, hi, &wb, &bit);
+  put_bits_le(blk + 4 * (int64_t)D * lo + wb, bit, hi, code >> lo);
+}
+static uint32_t v_get_code(const uint8_t* cs, int64_t t, int d, int D, int b) {
+  const uint8_t* blk = cs + (t / 32) * (4 * (int64_t)D * b);
+  int u = (int)(t % 32), bit;
+  int64_t wb;
+  if (b != 3 && b != 6) { v_in_block(u, d, D, b, &wb, &bit); return get_bits_le(blk + wb, bit, b); }
+  int lo = b == 3 ? 2 : 4, hi = b - lo;
+  v_in_block(u, d, D, lo, &wb, &bit);
+  uint32_t code = get_bits_le(blk + wb, bit, lo);
+  v_in_block(u, d, D, hi, &wb, &bit);
+  return code | (get_bits_le(blk + 4 * (int64_t)D * lo + wb, bit, hi) << lo);
 }
 
 /* ------------------------------------------------------------------ Hadamard rotation */
@@ -341,7 +360,6 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
     uint8_t* mplane = which ? v_meta : k_meta;
     int64_t cstream = (int64_t)(pb[which ? 2 : 0] / (uint64_t)streams);
     int64_t mstream = (int64_t)(pb[which ? 3 : 1] / (uint64_t)streams);
-    int f = which ? ref_field_bits(b) : b;                  /* bits a code occupies in the planes */
     if (b != 16 && (D % G || !bits_allowed(b))) { free(row); free(plain); free(codes); return -1; }
     for (int64_t bh = 0; bh < streams; ++bh) {
       int64_t bi = bh / L->kv_heads, hi = bh % L->kv_heads;
@@ -354,7 +372,7 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
           for (int d = 0; d < D; ++d) {
             uint32_t bits16 = ((const uint16_t*)src)[base + d];
             if (!which) put_bits_le(cs, k_bit_offset(t, d, D, 16), 16, bits16);
-            else { int64_t wb; int bit; v_position(t, d, D, 16, &wb, &bit); put_bits_le(cs + wb, bit, 16, bits16); }
+            else v_put_code(cs, t, d, D, 16, bits16);
           }
           continue;
         }
@@ -371,8 +389,8 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
           m[2] = (uint8_t)(Z & 0xFF); m[3] = (uint8_t)(Z >> 8);
         }
         for (int d = 0; d < D; ++d) {
-          if (!which) k_put_code(cs, t, d, D, f, codes[d]);
-          else { int64_t wb; int bit; v_position(t, d, D, f, &wb, &bit); put_bits_le(cs + wb, bit, f, codes[d]); }
+          if (!which) k_put_code(cs, t, d, D, b, codes[d]);
+          else v_put_code(cs, t, d, D, b, codes[d]);
         }
       }
     }
@@ -407,9 +425,8 @@ int ref_dequantize_stored(const ref_layout* L, const uint8_t* k_codes, const uin
       for (int64_t t = t0; t < t1; ++t)
         for (int d = 0; d < D; ++d) {
           uint32_t code;
-          int f = which ? ref_field_bits(b) : b;
-          if (!which) code = k_get_code(cs, t, d, D, f);
-          else { int64_t wb; int bit; v_position(t, d, D, f, &wb, &bit); code = get_bits_le(cs + wb, bit, f); }
+          if (!which) code = k_get_code(cs, t, d, D, b);
+          else code = v_get_code(cs, t, d, D, b);
           float val;
           if (b == 16) val = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32((uint16_t)code) : ref_f16_to_f32((uint16_t)code);
           else {
@@ -543,9 +560,7 @@ static uint16_t resid_get_k(const uint8_t* rs, int slot, int d, int D) {
   return (uint16_t)(p[0] | (p[1] << 8));
 }
 static uint16_t resid_get_v(const uint8_t* rs, int slot, int d, int D) {
-  int64_t wb; int bit;
-  v_position(slot, d, D, 16, &wb, &bit);
-  return (uint16_t)get_bits_le(rs + wb, bit, 16);
+  return (uint16_t)v_get_code(rs, slot, d, D, 16);
 }
 
 /* Append tokens [pos, pos+n_new) to a cache with channel-wise keys: every token goes to its
@@ -580,9 +595,7 @@ int ref_seq_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, uint8
       for (int d = 0; d < D; ++d) {                           /* the newest token stays in full precision */
         uint32_t kb = ((const uint16_t*)k_new)[base + d], vb = ((const uint16_t*)v_new)[base + d];
         put_bits_le(kr, ((int64_t)slot * D + d) * 16, 16, kb);
-        int64_t wb; int bit;
-        v_position(slot, d, D, 16, &wb, &bit);
-        put_bits_le(vr + wb, bit, 16, vb);
+        v_put_code(vr, slot, d, D, 16, vb);
       }
       if (slot != G - 1) continue;
       /* flush the block that just filled up */
@@ -611,11 +624,7 @@ int ref_seq_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, uint8
           m[0] = (uint8_t)(S & 0xFF); m[1] = (uint8_t)(S >> 8);
           m[2] = (uint8_t)(Z & 0xFF); m[3] = (uint8_t)(Z >> 8);
         }
-        for (int d = 0; d < D; ++d) {
-          int64_t wb; int bit;
-          v_position(t0 + i, d, D, bv, &wb, &bit);
-          put_bits_le(vc + wb, bit, bv, codes[d]);
-        }
+        for (int d = 0; d < D; ++d) v_put_code(vc, t0 + i, d, D, bv, codes[d]);
       }
     }
   }
@@ -651,10 +660,8 @@ int ref_seq_dequantize(const ref_layout* L, const uint8_t* k_codes, const uint8_
         if (t < n_flushed) {
           const uint8_t* m = km + ((t / G) * D + d) * 4;
           kv = ref_reconstruct(get_bits_le(kc, k_bit_offset(t, d, D, bk), bk), (uint16_t)(m[0] | (m[1] << 8)), (uint16_t)(m[2] | (m[3] << 8)));
-          int64_t wb; int bit;
-          v_position(t, d, D, bv, &wb, &bit);
           const uint8_t* mv = vm + meta_offset(t, d / GV, D / GV);
-          vv = ref_reconstruct(get_bits_le(vc + wb, bit, bv), (uint16_t)(mv[0] | (mv[1] << 8)), (uint16_t)(mv[2] | (mv[3] << 8)));
+          vv = ref_reconstruct(v_get_code(vc, t, d, D, bv), (uint16_t)(mv[0] | (mv[1] << 8)), (uint16_t)(mv[2] | (mv[3] << 8)));
         } else {
           uint16_t kb = resid_get_k(kr, (int)(t % G), d, D), vb = resid_get_v(vr, (int)(t % G), d, D);
           kv = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32(kb) : ref_f16_to_f32(kb);

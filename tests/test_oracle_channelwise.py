@@ -226,18 +226,30 @@ def _pack_key_rows_numpy(codes, bits):
     return np.concatenate([low, high], axis=2).ravel()
 
 
-@pytest.mark.parametrize("bits,field", [(1, 1), (3, 4), (6, 8)])
-def test_odd_widths_keys_at_their_width_values_in_power_of_two_fields(oracle, bits, field):
+def _pack_value_blocks_numpy(codes, S, Z, bits, G):
+    """Value blocks at their own width.  3 and 6 bits: per 32-token block the block of the codes' low 2 (4) bits in the
+    2-bit (4-bit) layout, then the block of their high 1 (2) bits in the 1-bit (2-bit) layout."""
+    if bits not in (3, 6):
+        return _expected_planes(codes, S, Z, bits, G)[2]
+    lo = 2 if bits == 3 else 4
+    T = codes.shape[0]
+    low = _expected_planes(codes & ((1 << lo) - 1), S, Z, lo, G)[2].reshape(T // 32, 512 * lo)
+    high = _expected_planes(codes >> lo, S, Z, bits - lo, G)[2].reshape(T // 32, 512 * (bits - lo))
+    return np.concatenate([low, high], axis=1).ravel()
+
+
+@pytest.mark.parametrize("bits", [1, 3, 6])
+def test_odd_widths_are_packed_at_their_own_width(oracle, bits):
     """1-, 3- and 6-bit codes (the per-column back-end's grid {1,2,4,6,8}, Table 1's 3-bit keys) are quantized with
-    2^b - 1 steps.  Key rows take D*b/8 bytes (3 and 6 bits as a low and a high run per 32 channels); value codes of
-    3 and 6 bits sit in the next power-of-two field of the blocked layout, 1-bit value codes take one bit.  Planes =
+    2^b - 1 steps and take b bits in both tensors: key rows D*b/8 bytes (3 and 6 bits as a low and a high run per 32
+    channels), value blocks 512*b bytes (3 and 6 bits as a block of low parts and a block of high parts).  Planes =
     numpy's packing of numpy's b-bit codes, sizes accordingly, reconstruction = code * scale + zero."""
     rng = np.random.default_rng(bits)
     B, H, T, D, G = 1, 2, 64, 128, 64
     x = (rng.standard_normal((B, H, T, D)) * 2).astype(np.float16)
     L = oracle.Layout(B, H, T, D, bits, bits, G, G)
-    sizes, fsizes = oracle.plane_bytes(L), oracle.plane_bytes(oracle.Layout(B, H, T, D, field, field, G, G))
-    assert sizes[0] == B * H * T * D * bits // 8 and sizes[1:] == fsizes[1:]
+    sizes, fsizes = oracle.plane_bytes(L), oracle.plane_bytes(oracle.Layout(B, H, T, D, 8, 8, G, G))
+    assert sizes[0] == sizes[2] == B * H * T * D * bits // 8 and sizes[1::2] == fsizes[1::2]
     planes = oracle.new_planes(L)
     oracle.quantize_append(L, planes, x, x, 0)
     kd, vd = oracle.dequantize(L, planes, 0, T)
@@ -245,7 +257,7 @@ def test_odd_widths_keys_at_their_width_values_in_power_of_two_fields(oracle, bi
         rows = x.reshape(B * H, T, D)[bh].astype(np.float32)
         codes, S, Z = _quantize_rows_numpy(rows, bits, G)
         assert codes.max() <= 2 ** bits - 1
-        _, meta, v_plane = _expected_planes(codes, S, Z, field, G)
+        meta, v_plane = _expected_planes(codes, S, Z, 8, G)[1], _pack_value_blocks_numpy(codes, S, Z, bits, G)
         got = [p.reshape(B * H, -1)[bh] for p in planes]
         assert np.array_equal(got[0], _pack_key_rows_numpy(codes, bits)) and np.array_equal(got[1], meta)
         assert np.array_equal(got[2], v_plane) and np.array_equal(got[3], meta)
