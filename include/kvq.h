@@ -80,7 +80,10 @@
  *                                           the code of (t, d) sits in the little-endian 32-bit word at
  *                                           byte (e/4)*1024 + (16*j + d%16)*16 + 4*(e%4) of the block,
  *                                           at bit 16*x + b_V*p; for b_V = 1 (a block is 512 bytes, P = 16) at
- *                                           byte (16*j + d%16)*8 + 4*e, bit 16*x + p.
+ *                                           byte (16*j + d%16)*8 + 4*e, bit 16*x + p.  b_V = 3 and 6: the block
+ *                                           is a block of LO-bit fields (LO = 2, 4) holding code mod 2^LO
+ *                                           followed by a block of (b_V - LO)-bit fields holding code >> LO,
+ *                                           each in the order just given for its field width.
  *   v_meta   as k_meta with G_V.
  *   bits == 16 keeps the 16-bit input patterns (raw_dtype) in the same positions; no meta plane.
  */
@@ -113,9 +116,7 @@ typedef enum {
 
 /* Immutable description of one layer's cache.  head_dim must be 128.  bits in {1,2,3,4,6,8,16} (the per-column
  * back-end's grid {1,2,4,6,8}, Table 1's 3-bit keys): 2^b - 1 steps.  Key rows are stored at their own width (a row
- * of 3-bit codes is 48 bytes), and so are 1-bit value codes (16 bytes a token).  Value codes of widths 3 and 6 are
- * stored in the 4- and 8-bit fields of the blocked value layout, so they cost the memory of that field (b_V in the
- * storage format is then the field width);
+ * of 3-bit codes is 48 bytes), and so are value codes (a 32-token block of b-bit codes is 512 b bytes);
  * group in {32,64,128} (ignored for bits == 16).  raw_dtype (KVQ_F16 / KVQ_BF16) is the element
  * type of a plane whose bits == 16. */
 typedef struct {

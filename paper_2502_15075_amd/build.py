@@ -22,7 +22,8 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.j
 # pair) and once without (plan + dispatch), so that the instances build in parallel.
 DECODE_PAIRS = [(4, 2), (2, 4), (4, 4), (8, 8), (2, 2), (8, 4), (8, 2), (4, 8), (2, 8), (16, 16),
                 (3, 2), (3, 4), (3, 8), (6, 2), (6, 4), (6, 8), (1, 2), (1, 4), (1, 8),
-                (1, 1), (2, 1), (3, 1), (4, 1), (6, 1), (8, 1)]
+                (1, 1), (2, 1), (3, 1), (4, 1), (6, 1), (8, 1),
+                (1, 3), (2, 3), (3, 3), (4, 3), (6, 3), (8, 3), (1, 6), (2, 6), (3, 6), (4, 6), (6, 6), (8, 6)]
 # (source, object name, extra flags).  The quantizer must round every operation once: no contraction.
 UNITS = [("kvq_api.hip", "kvq_api.o", []),
          ("kvq_quant.hip", "kvq_quant.o", ["-ffp-contract=off"]),

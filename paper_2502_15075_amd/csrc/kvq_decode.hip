@@ -47,7 +47,6 @@ __device__ __forceinline__ float4v mma(u32x4 a, u32x4 b, float4v c) {
 
 constexpr float kCodeUnit = 5.9604644775390625e-08f;  // 2^-24: value of a code's lowest mantissa bit
 constexpr float kInvCodeUnit = 16777216.0f;
-constexpr float kPShift = 10.0f;                      // softmax weights are carried times 2^10 (binary16 headroom)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;
 
@@ -150,9 +149,21 @@ template <int BK> constexpr int k_hi_base() { return BK == 3 ? 5 : 6; }   // hig
 // Register v (0..3) of d-tile dt's operand holds slots 2v, 2v+1 and is left at bit offset v_slot_shift(v)
 // of its 16-bit lane, i.e. it reads as code * 2^shift * 2^-24; the softmax weight of those slots is
 // divided by 2^shift instead (an exponent offset, free).
-template <int BV> __device__ __forceinline__ constexpr int v_slot_shift(int v) {
-  return BV == 1 ? v : BV == 2 ? 2 * v : (BV == 4 ? 4 * (v & 1) : 0);
+// Value codes of 3 and 6 bits are a block of low parts (2 / 4 bits) and a block of high parts (1 / 2 bits): two
+// operands per d-tile; v_slot_shift is the low part's, and the high part's weights carry the factor v_hi_factor.
+template <int BV> constexpr int v_lo() { return key_lo_bits<BV>(); }
+template <int BV> constexpr int v_hi() { return key_hi_bits<BV>(); }
+template <int B> __device__ __forceinline__ constexpr int field_slot_shift(int v) {
+  return B == 1 ? v : B == 2 ? 2 * v : (B == 4 ? 4 * (v & 1) : 0);
 }
+template <int BV> __device__ __forceinline__ constexpr int v_slot_shift(int v) { return field_slot_shift<v_lo<BV>()>(v); }
+// code = lo + 2^LO hi, and the two operands sit at different bit offsets of their 16-bit lanes
+template <int BV> __device__ __forceinline__ constexpr float v_hi_factor(int v) {
+  return (float)(1 << (v_lo<BV>() + field_slot_shift<v_lo<BV>()>(v))) / (float)(1 << field_slot_shift<(v_hi<BV>() ? v_hi<BV>() : 1)>(v));
+}
+// Softmax weights are carried times 2^p_shift: 2^10 leaves binary16 headroom for weight x value scale up to 64; the
+// high part's weights are up to 2^LO larger, and the scale of a 1-bit group is its whole range (2^8: up to 255).
+template <int BV> constexpr float p_shift() { return BV == 1 ? 8.0f : 10.0f - (float)(v_hi<BV>() ? v_lo<BV>() : 0); }
 template <int BV> __device__ __forceinline__ u32x4 unpack_v(const uint32_t* w, int dt) {
   u32x4 a;
   if (BV == 16) {
@@ -188,6 +199,7 @@ constexpr int ring_stages() {
   constexpr int base = regs <= 16 ? KVQ_STAGES : regs <= 20 ? 3 : 2;
   constexpr int less = (NCK == 2 ? 2 : 0) + (NCV == 2 ? 1 : 0)    // a second column set costs registers (query operand,
                        + (key_hi_bits<BK>() ? 1 : 0)              // scale/zero entries, weights), so does a high run
+                       + (key_hi_bits<BV>() ? 1 : 0)              // of keys or a high part of values (its weights)
                        + (BK == 2 && regs >= 16 ? 1 : 0);         // (moved 2-bit fields: two shifted copies of a word live)
   return base - less >= 1 ? base - less : 1;
 }
@@ -264,13 +276,18 @@ __device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L,
   // (every lane loads, for the same reason: lanes beyond the scale/zero bytes repeat the last 16 of them)
   if constexpr (BK != 16)
     r.meta = ld16(mbase + ((WIDE ? 0u : ((uint32_t)step & L.meta_step_mask) * L.meta_mul) + (L.meta_off & lane_mask)));
-  const uint32_t vo = (WIDE ? 0u : (uint32_t)step * (512 * BV)) + (L.vc_off & lane_mask);
+  constexpr int VLO = v_lo<BV>(), VHI = v_hi<BV>();
+  const uint32_t vstep = WIDE ? 0u : (uint32_t)step * (512 * BV);
+  const uint32_t vo = vstep + (L.vc_off & lane_mask);
   if constexpr (BV == 1) load_dwords<2>(r.vc, vbase + vo);
 #pragma unroll
-  for (int k = 0; k < BV / 2; ++k) {
+  for (int k = 0; k < VLO / 2; ++k) {
     const u32x4 v = ld16(vbase + (vo + k * 1024));
     r.vc[4 * k + 0] = v.x; r.vc[4 * k + 1] = v.y; r.vc[4 * k + 2] = v.z; r.vc[4 * k + 3] = v.w;
   }
+  // the block of high parts follows the block of low parts: 8 bytes per lane (single bits) or 16 (pairs)
+  if constexpr (VHI == 1) load_dwords<2>(r.vc + 2 * VLO, vbase + (vstep + 512 * VLO + ((L.vc_off >> 1) & lane_mask)));
+  if constexpr (VHI == 2) load_dwords<4>(r.vc + 2 * VLO, vbase + (vstep + 512 * VLO + (L.vc_off & lane_mask)));
 }
 
 __device__ __forceinline__ float meta_scale(uint32_t m) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(m & 0xFFFFu)); }
@@ -280,8 +297,8 @@ template <int NCV>
 struct WaveState {
   float4v acc[8];       // out^T tile dt: rows d = 16*dt + 4*j + r, column c
   float m;              // running max of this lane's head, in log2 units
-  float noff[4];        // kPShift - m - v_slot_shift(v): exponent offset of the slots in operand register v
-  float l[4];           // per register class v: this lane's share of sum_t p * 2^(kPShift - shift(v))
+  float noff[4];        // p_shift - m - v_slot_shift(v): exponent offset of the slots in operand register v
+  float l[4];           // per register class v: this lane's share of sum_t p * 2^(p_shift - shift(v))
   float zacc[NCV][4];   // same, weighted by zV[t, g] for this lane's value group of each column set
 };
 
@@ -459,12 +476,14 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
       st.l[v] *= f;
 #pragma unroll
       for (int cs = 0; cs < NCV; ++cs) st.zacc[cs][v] *= f;
-      st.noff[v] = kPShift - (float)v_slot_shift<BV>(v) - m_new;
+      st.noff[v] = p_shift<BV>() - (float)v_slot_shift<BV>(v) - m_new;
     }
     st.m = m_new;
   }
   // ---- softmax weights; quantized values: their binary16 products with the value scale, and the value-zero term
+  constexpr int VLO = v_lo<BV>(), VHI = v_hi<BV>();
   uint32_t pw[NCV][4], pl[4];                    // pl: low-order bfloat16 part of the weights (bfloat16 cache only)
+  uint32_t pwh[NCV][4];                          // weights of the high parts of 3- and 6-bit value codes
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int v = i >> 1;
@@ -478,6 +497,10 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
         if (MASKED && !valid[i]) vm = 0u;
         st.zacc[cs][v] = fmaf(p, meta_zero(vm), st.zacc[cs][v]);
         if (i & 1) mix_hi(pw[cs][v], p, vm); else mix_lo(pw[cs][v], p, vm);
+        if constexpr (VHI != 0) {
+          const float ph = p * v_hi_factor<BV>(v);
+          if (i & 1) mix_hi(pwh[cs][v], ph, vm); else mix_lo(pwh[cs][v], ph, vm);
+        }
       }
     } else if constexpr (!BF) {
       if (i & 1) mix_hi(pw[0][v], p, 0x3C00u); else mix_lo(pw[0][v], p, 0x3C00u);    // times binary16 1.0
@@ -493,7 +516,9 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
     constexpr int kDtPerSet = 8 / NCV;           // value groups of set 0 own the first d-tiles, of set 1 the rest
     const int cs = dt / kDtPerSet;
     const u32x4 pb = u32x4{pw[cs][0], pw[cs][1], pw[cs][2], pw[cs][3]};
-    u32x4 a = unpack_v<BV>(r.vc, dt);
+    u32x4 a = unpack_v<VLO>(r.vc, dt);
+    if constexpr (VHI != 0)
+      st.acc[dt] = mma<BF>(unpack_v<VHI>(r.vc + 2 * VLO, dt), u32x4{pwh[cs][0], pwh[cs][1], pwh[cs][2], pwh[cs][3]}, st.acc[dt]);
     if constexpr (RAW && MASKED) {               // unquantized garbage may be Inf/NaN: clear the slots beyond seq_len
       uint32_t* aw = reinterpret_cast<uint32_t*>(&a);
 #pragma unroll
@@ -533,7 +558,7 @@ __device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, i
   }
   uint32_t codes[8];
   uint16_t S, Z;
-  const int bits = is_v ? g.qbits_v : g.qbits_k;   // quantizer width (the field is BV / BK wide)
+  const int bits = is_v ? BV : BK;
   const int G = is_v ? g.g_v : g.g_k, ng = is_v ? g.ng_v : g.ng_k;
   const int lpg = G >> 3;
   quantize8(x, bits, lpg, codes, &S, &Z);
@@ -549,26 +574,32 @@ __device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, i
 
 // Second half of the fused append: thread d < 128 inserts channel d's code of token seq_len-1 into its 32-bit word
 // (read-modify-write; the other fields of the word belong to other tokens of the same 32-token block).  With 2-bit
-// codes channels d and d+16 share a word (with 1-bit codes d, d+16, d+32 and d+48), so the thread of the first of
-// those 16-channel tiles writes them all.
-template <int BV>
-__device__ __forceinline__ void append_one_values(const DecodeArgs& a, int bh, int tid, const uint8_t* vstage, int64_t t) {
-  constexpr int NF = BV == 1 ? 4 : BV == 2 ? 2 : 1;       // 16-channel tiles with a field in the same word
-  if (tid >= kHeadDim) return;
-  if ((tid >> 4) & (NF - 1)) return;
-  const Geom& g = a.g;
-  uint32_t* blk = (uint32_t*)((uint8_t*)a.cache.v_codes + (int64_t)bh * g.vc_stream) + (t >> 5) * (int64_t)(128 * BV);
-  const uint32_t fmask = (1u << BV) - 1u;
+// fields channels d and d+16 share a word (with 1-bit fields d, d+16, d+32 and d+48), so the thread of the first of
+// those 16-channel tiles writes them all.  `blk`: a block of B-bit fields; the field is bits [shift, shift + B) of the
+// staged code.
+template <int B>
+__device__ __forceinline__ void append_fields(uint32_t* blk, int tid, const uint8_t* vstage, int u, int shift) {
+  constexpr int NF = B == 1 ? 4 : B == 2 ? 2 : 1;         // 16-channel tiles with a field in the same word
+  if (tid >= kHeadDim || ((tid >> 4) & (NF - 1))) return;
+  const uint32_t fmask = (1u << B) - 1u;
   int dw, bit;
-  v_field((int)(t & 31), tid, BV, &dw, &bit);
+  v_field(u, tid, B, &dw, &bit);
   uint32_t w = blk[dw];
 #pragma unroll
   for (int f = 0; f < NF; ++f) {
     int dwf, bitf;
-    v_field((int)(t & 31), tid + 16 * f, BV, &dwf, &bitf);   // same word, the neighbouring tiles' fields
-    w = (w & ~(fmask << bitf)) | ((uint32_t)vstage[tid + 16 * f] << bitf);
+    v_field(u, tid + 16 * f, B, &dwf, &bitf);             // same word, the neighbouring tiles' fields
+    w = (w & ~(fmask << bitf)) | ((((uint32_t)vstage[tid + 16 * f] >> shift) & fmask) << bitf);
   }
   blk[dw] = w;
+}
+template <int BV>
+__device__ __forceinline__ void append_one_values(const DecodeArgs& a, int bh, int tid, const uint8_t* vstage, int64_t t) {
+  constexpr int VLO = v_lo<BV>(), VHI = v_hi<BV>();
+  const Geom& g = a.g;
+  uint32_t* blk = (uint32_t*)((uint8_t*)a.cache.v_codes + (int64_t)bh * g.vc_stream) + (t >> 5) * (int64_t)(128 * BV);
+  append_fields<VLO>(blk, tid, vstage, (int)(t & 31), 0);
+  if constexpr (VHI != 0) append_fields<VHI>(blk + 128 * VLO, tid, vstage, (int)(t & 31), VLO);
 }
 
 // Final output of rotated values: the normalized row sits in the rotated basis (LDS, 128 floats); 16 threads take it
@@ -1036,7 +1067,8 @@ hipError_t KVQ_CAT(launch_decode_inst_, KVQ_INST_BK, KVQ_INST_BV)(int R, const D
 // ---- dispatcher translation unit ----------------------------------------------------------------------------------------
 #define KVQ_FOR_EACH_PAIR(X) X(4, 2) X(2, 4) X(4, 4) X(8, 8) X(2, 2) X(8, 4) X(8, 2) X(4, 8) X(2, 8) X(16, 16) \
   X(3, 2) X(3, 4) X(3, 8) X(6, 2) X(6, 4) X(6, 8) X(1, 2) X(1, 4) X(1, 8) \
-  X(1, 1) X(2, 1) X(3, 1) X(4, 1) X(6, 1) X(8, 1)
+  X(1, 1) X(2, 1) X(3, 1) X(4, 1) X(6, 1) X(8, 1) \
+  X(1, 3) X(2, 3) X(3, 3) X(4, 3) X(6, 3) X(8, 3) X(1, 6) X(2, 6) X(3, 6) X(4, 6) X(6, 6) X(8, 6)
 #define KVQ_DECL(BK_, BV_) \
   hipError_t KVQ_CAT(launch_decode_inst_, BK_, BV_)(int R, const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream);
 KVQ_FOR_EACH_PAIR(KVQ_DECL)

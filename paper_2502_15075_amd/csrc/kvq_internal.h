@@ -14,9 +14,7 @@ constexpr int kSeqGroup = 64;     // channel-wise keys: tokens per key group = s
 // Geometry derived once on the host and passed by value to every kernel.
 struct Geom {
   int32_t batch, kv_heads, t_cap;   // t_cap = max_seq rounded up to kBlockTokens
-  int32_t bits_k, bits_v, ng_k, ng_v, g_k, g_v;   // bits: what a code takes in its plane (16 = unquantized): keys their
-                                    // own width (1, 2, 3, 4, 6, 8), values the power-of-two field (1, 2, 4, 8)
-  int32_t qbits_k, qbits_v;         // quantizer widths: 2^qbits - 1 steps (value widths 3 and 6 live in the next larger field)
+  int32_t bits_k, bits_v, ng_k, ng_v, g_k, g_v;   // bits: 1, 2, 3, 4, 6, 8 (2^b - 1 steps, b bits per code in the plane), 16 = unquantized
   int32_t raw_dtype;
   int32_t axis_k;                   // KVQ_AXIS_SEQ: channel-wise key groups of kSeqGroup tokens + residual buffer;
                                     // then g_k = 128 and ng_k = 1 (one matrix column per head on the key side)
@@ -32,7 +30,6 @@ struct Geom {
 };
 
 inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
-inline int field_bits(int b) { return b == 3 ? 4 : b == 6 ? 8 : b; }
 
 inline Geom make_geom(const kvq_layout& L) {
   Geom g{};
@@ -45,8 +42,7 @@ inline Geom make_geom(const kvq_layout& L) {
     g.pages_per_seq = (L.max_seq + L.page_tokens - 1) / L.page_tokens;
     g.t_cap = L.page_tokens;                       // the unit every plane is laid out for
   }
-  g.bits_k = L.bits_k; g.bits_v = field_bits(L.bits_v);       // key rows are packed at their own width
-  g.qbits_k = L.bits_k; g.qbits_v = L.bits_v;
+  g.bits_k = L.bits_k; g.bits_v = L.bits_v;                   // every code is packed at its own width
   g.g_k = (L.bits_k == 16 || L.axis_k == KVQ_AXIS_SEQ) ? kHeadDim : L.group_k;
   g.g_v = L.bits_v == 16 ? kHeadDim : L.group_v;
   g.ng_k = kHeadDim / g.g_k; g.ng_v = kHeadDim / g.g_v;

@@ -49,13 +49,15 @@ __device__ __forceinline__ void stage_value_codes(uint8_t* vstage, int row, int 
   }
 }
 
-// One thread per 32-bit word of the span (two blocks of 128*BV words): assemble the word from the staged codes and
+// One thread per 32-bit word of the span (two blocks of 128*BV words, BW words apart in the plane: a block of 3- or
+// 6-bit codes is a block of low parts followed by a block of high parts): assemble the word from the staged codes and
 // store it; when the span is only partly covered by the new tokens [lo, hi), keep the fields of the other tokens.
-template <int BV>
-__device__ __forceinline__ void store_value_words(uint32_t* vc, const uint8_t* vstage, int tid, int lo, int hi) {
+template <int BV, int BW = 128 * BV>
+__device__ __forceinline__ void store_value_words(uint32_t* vcp, const uint8_t* vstage, int tid, int lo, int hi) {
   constexpr int F = 32 / BV, P = 16 / BV, ES = BV == 16 ? 2 : 1;
   const bool full = lo == 0 && hi == kSpan;
   for (int w = tid; w < 256 * BV; w += 256) {
+    uint32_t* vc = vcp + (w / (128 * BV)) * (BW - 128 * BV);      // vc[w]: the word's place in the plane
     const uint8_t* sp = vstage + stage_phys(w * F * ES);
     uint32_t bits;
     if (BV == 1) {
@@ -99,8 +101,10 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
                                                               const uint16_t* __restrict__ v_new, int64_t sb, int64_t sh,
                                                               int64_t st, int32_t pos, int32_t n_new) {
   constexpr int ES = BV == 16 ? 2 : 1;            // bytes per staged element
+  constexpr int VLO = key_lo_bits<BV>(), VHI = key_hi_bits<BV>();   // 3- and 6-bit value codes: low and high parts
   constexpr int kStageBytes = kSpan * kHeadDim * ES;
-  __shared__ __attribute__((aligned(16))) uint8_t vstage[kStageBytes + (kStageBytes >> 4)];
+  constexpr int kStagePadded = kStageBytes + (kStageBytes >> 4);
+  __shared__ __attribute__((aligned(16))) uint8_t vstage[kStagePadded * (VHI ? 2 : 1)];
   const int tid = threadIdx.x;
   const int bh = blockIdx.y;
   const int b = bh / g.kv_heads, h = bh % g.kv_heads;
@@ -147,7 +151,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         uint32_t codes[8];
         uint16_t S, Z;
         const int lpg = g.g_k >> 3;
-        quantize8(x, g.qbits_k, lpg, codes, &S, &Z);
+        quantize8(x, BK, lpg, codes, &S, &Z);
         if ((lane16 & (lpg - 1)) == 0) km[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_k)] = (uint32_t)S | ((uint32_t)Z << 16);
         store_key_codes<BK>(kc + t * (16 * BK), lane16, codes);
       }
@@ -167,25 +171,51 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         if (g.rotate_v) rotate8(x, lane16, rot_sign_bits(g.signs_v, lane16));
         uint16_t S, Z;
         const int lpg = g.g_v >> 3;
-        quantize8(x, g.qbits_v, lpg, codes, &S, &Z);
+        quantize8(x, BV, lpg, codes, &S, &Z);
         if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
       }
-      stage_value_codes<BV>(vstage, row, d0, codes);
+      if constexpr (VHI == 0) {
+        stage_value_codes<BV>(vstage, row, d0, codes);
+      } else {                                     // (the low parts are cut to their field when the words are packed)
+        uint32_t high[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) high[e] = codes[e] >> VLO;
+        stage_value_codes<VLO>(vstage, row, d0, codes);
+        stage_value_codes<VHI>(vstage + kStagePadded, row, d0, high);
+      }
     }
   }
   __syncthreads();
 
-  store_value_words<BV>(vc, vstage, tid, lo, hi);
+  if constexpr (VHI == 0) {
+    store_value_words<BV>(vc, vstage, tid, lo, hi);
+  } else {
+    store_value_words<VLO, 128 * BV>(vc, vstage, tid, lo, hi);
+    store_value_words<VHI, 128 * BV>(vc + 128 * VLO, vstage + kStagePadded, tid, lo, hi);
+  }
 }
 
-// The 8 codes of channels d0 .. d0+7 (d0 a multiple of 8) of value row t: the same field of 8 words one lane piece
-// (16 bytes, 8 for 1-bit codes) apart.
-template <int B> __device__ __forceinline__ void value_codes8(const uint8_t* cs, int64_t t, int d0, uint32_t code[8]) {
+// The 8 fields of channels d0 .. d0+7 (d0 a multiple of 8) of token u in a 32-token block of B-bit fields: the same
+// field of 8 words one lane piece (16 bytes, 8 for 1-bit fields) apart.
+template <int B> __device__ __forceinline__ void block_fields8(const uint8_t* blkp, int u, int d0, uint32_t code[8]) {
   int dw, bit;
-  v_field((int)(t & 31), d0, B, &dw, &bit);
-  const uint32_t* blk = reinterpret_cast<const uint32_t*>(cs + (t >> 5) * (int64_t)(512 * B)) + dw;
+  v_field(u, d0, B, &dw, &bit);
+  const uint32_t* blk = reinterpret_cast<const uint32_t*>(blkp) + dw;
 #pragma unroll
   for (int e = 0; e < 8; ++e) code[e] = (blk[(B == 1 ? 2 : 4) * e] >> bit) & (B == 16 ? 0xFFFFu : ((1u << B) - 1u));
+}
+// The 8 codes of channels d0 .. d0+7 of value row t (3- and 6-bit codes: low parts from the block's first part, high
+// parts from its second).
+template <int B> __device__ __forceinline__ void value_codes8(const uint8_t* cs, int64_t t, int d0, uint32_t code[8]) {
+  constexpr int LO = key_lo_bits<B>(), HI = key_hi_bits<B>();
+  const uint8_t* blk = cs + (t >> 5) * (int64_t)(512 * B);
+  block_fields8<LO>(blk, (int)(t & 31), d0, code);
+  if constexpr (HI != 0) {
+    uint32_t high[8];
+    block_fields8<HI>(blk + 512 * LO, (int)(t & 31), d0, high);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) code[e] |= high[e] << LO;
+  }
 }
 
 // Channel-wise keys (Sec. 4 "Downstream Task Accuracy": the per-column back-end with its residual buffer).
@@ -307,7 +337,7 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
     uint32_t vcodes[8];
     uint16_t S, Z;
     const int lpg = g.g_v >> 3;
-    quantize8(xv, g.qbits_v, lpg, vcodes, &S, &Z);
+    quantize8(xv, BV, lpg, vcodes, &S, &Z);
     if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
     stage_value_codes<BV>(vstage, row, d0, vcodes);
   }
@@ -353,7 +383,9 @@ __device__ __forceinline__ void reconstruct8(const Geom& g, const kvq_cache& c, 
     switch (g.bits_v) {
       case 1: return reconstruct8_t<1, true>(g, c, t, d0, val);
       case 2: return reconstruct8_t<2, true>(g, c, t, d0, val);
+      case 3: return reconstruct8_t<3, true>(g, c, t, d0, val);
       case 4: return reconstruct8_t<4, true>(g, c, t, d0, val);
+      case 6: return reconstruct8_t<6, true>(g, c, t, d0, val);
       case 8: return reconstruct8_t<8, true>(g, c, t, d0, val);
       default: return reconstruct8_t<16, true>(g, c, t, d0, val);
     }
@@ -518,7 +550,9 @@ hipError_t launch_qk(const Geom& g, const kvq_cache& c, const void* k_new, const
   switch (g.bits_v) {
     case 1: return launch_q<BK, 1>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 2: return launch_q<BK, 2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 3: return launch_q<BK, 3>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 4: return launch_q<BK, 4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
+    case 6: return launch_q<BK, 6>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 8: return launch_q<BK, 8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
     case 16: return launch_q<BK, 16>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, stream);
   }
@@ -636,7 +670,8 @@ hipError_t launch_reconstruction_error(const Geom& g, const kvq_cache& c, const 
   if (g.bits_k == BK_ && g.bits_v == BV_)                                                                               \
     hipLaunchKernelGGL((sq_error_kernel<BK_, BV_>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_ref,           \
                        (const uint16_t*)v_ref, bf, sb, sh, st, t0, t1, sums);
-#define KVQ_ERR_ROW(BK_) KVQ_ERR_CASE(BK_, 1) KVQ_ERR_CASE(BK_, 2) KVQ_ERR_CASE(BK_, 4) KVQ_ERR_CASE(BK_, 8) KVQ_ERR_CASE(BK_, 16)
+#define KVQ_ERR_ROW(BK_) KVQ_ERR_CASE(BK_, 1) KVQ_ERR_CASE(BK_, 2) KVQ_ERR_CASE(BK_, 3) KVQ_ERR_CASE(BK_, 4) \
+  KVQ_ERR_CASE(BK_, 6) KVQ_ERR_CASE(BK_, 8) KVQ_ERR_CASE(BK_, 16)
   KVQ_ERR_ROW(1) KVQ_ERR_ROW(2) KVQ_ERR_ROW(3) KVQ_ERR_ROW(4) KVQ_ERR_ROW(6) KVQ_ERR_ROW(8) KVQ_ERR_ROW(16)
 #undef KVQ_ERR_ROW
 #undef KVQ_ERR_CASE

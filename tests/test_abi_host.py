@@ -53,13 +53,12 @@ def test_cache_bytes_closed_forms(kvq):
     # paged planes: pool of n_pages pages, each one head's share of a 256-token cache per KV head
     assert kvq.cache_bytes(kvq.Layout(5, 2, 1000, 128, 4, 2, 64, 64, page_tokens=256, n_pages=11)) == \
         [11 * 2 * 256 * 64, 11 * 2 * 256 * 8, 11 * 2 * 256 * 32, 11 * 2 * 256 * 8]
-    # key rows take 16 b bytes at every width and 1-bit value codes 16 bytes a token; 3- and 6-bit value codes take
-    # the space of the 4- and 8-bit fields they are stored in
+    # codes of both tensors take 16 b bytes per token at every width
     k3v1 = kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 3, 1))
     assert k3v1 == [4 * 64 * 48, k3v1[1], 4 * 64 * 16, k3v1[3]] and k3v1[1::2] == kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 4, 2))[1::2]
     assert sum(kvq.cache_bytes(kvq.Layout(32, 8, 32768, 128, 4, 1, 64, 64))) == 96 * 32 * 8 * 32768
-    assert kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 6, 6)) == [4 * 64 * 96] + kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 8, 8))[1:]
-    assert kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 1, 3))[0] == 4 * 64 * 16
+    assert kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 6, 6))[0::2] == [4 * 64 * 96, 4 * 64 * 96]
+    assert kvq.cache_bytes(kvq.Layout(2, 2, 64, 128, 1, 3))[0::2] == [4 * 64 * 16, 4 * 64 * 48]
     # channel-wise keys: capacity in blocks of 64 tokens, 4 bytes per channel and block, two 64-slot residual buffers
     Ls = kvq.Layout(2, 3, 100, 128, 4, 2, 64, 32, axis_k=kvq.AXIS_SEQ)
     assert kvq.cache_bytes(Ls) == [6 * 128 * 64, 6 * 2 * 512, 6 * 128 * 32, 6 * 128 * 16]

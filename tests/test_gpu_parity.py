@@ -397,7 +397,7 @@ def test_long_context_batch_1_sampled_streams(kvq, oracle):
 
 # --------------------------------------------------------------------------- reconstruction error (MSE numerator)
 
-@pytest.mark.parametrize("bk,bv,gk,gv", [(4, 2, 64, 64), (2, 4, 32, 128), (8, 8, 128, 32), (4, 4, 64, 32), (6, 1, 64, 64)])
+@pytest.mark.parametrize("bk,bv,gk,gv", [(4, 2, 64, 64), (2, 4, 32, 128), (8, 8, 128, 32), (4, 4, 64, 32), (6, 1, 64, 64), (3, 3, 32, 64), (8, 6, 64, 128)])
 @pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
 def test_reconstruction_error_matches_the_oracle(kvq, oracle, bk, bv, gk, gv, dtype):
     """Per-head squared error of tokens [t0, t1) against the oracle's MSE of its own reconstruction of the same bytes
@@ -911,11 +911,11 @@ def test_fast_divisions_of_the_quantizer_are_correctly_rounded_on_this_device(kv
 # --------------------------------------------------------------------------- 1-, 3- and 6-bit quantizer widths
 
 @pytest.mark.parametrize("bk,bv", [(3, 2), (6, 3), (1, 6), (3, 3), (4, 1), (6, 4), (1, 2), (3, 8), (6, 2), (1, 1), (2, 1),
-                                   (6, 1), (8, 1)])
+                                   (6, 1), (8, 1), (4, 3), (8, 6), (2, 6), (6, 6), (8, 3)])
 def test_odd_quantizer_widths(kvq, oracle, bk, bv):
     """Widths 1, 3, 6 (the per-column back-end's grid, Table 1's 3-bit keys): 2^b - 1 steps; key rows at their own
-    width (3 and 6 bits as a low and a high run per 32 channels), 1-bit value codes one bit each, 3- and 6-bit value
-    codes in the next power-of-two field.
+    width (3 and 6 bits as a low and a high run per 32 channels), value blocks at their own width too (3 and 6 bits
+    as a block of low parts and a block of high parts).
     Planes byte-identical, reconstruction bit-identical, attention within tolerance, fused steps."""
     B, H, R, T0 = 2, 2, 4, 200
     T = T0 + 3
@@ -983,6 +983,32 @@ def test_one_bit_values_attention(kvq, oracle, R, bk, gk, gv):
     rotv = 1 if bk == 6 else 0
     Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, 1, gk, gv, rotv=rotv)
     assert kvq.cache_bytes(Lg)[2] == B * H * 2528 * 16
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, 1), (1, 1000), (1000, T)])
+    _assert_planes_equal(cache, planes)
+    for seq_len in (T, 2049, 31):
+        out = _decode(kvq, Lg, cache, q, seq_len)
+        ref = oracle.decode_attention(Lo, planes, q.numpy(), seq_len, 1 / math.sqrt(128))
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, seq_len
+    lens = np.array([T, 777], dtype=np.int32)
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, T)), dtype=torch.uint8, device="cuda")
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    kvq.decode_attention_varlen(Lg, cache, q.cuda(), torch.from_numpy(lens).cuda(), T, 1 / math.sqrt(128), out, ws)
+    torch.cuda.synchronize()
+    ref = oracle.decode_attention_varlen(Lo, planes, q.numpy(), lens, 1 / math.sqrt(128))
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+
+
+@pytest.mark.parametrize("R", [1, 2, 8])
+@pytest.mark.parametrize("bk,bv,gk,gv", [(4, 3, 64, 64), (8, 6, 32, 128), (2, 3, 128, 32), (3, 6, 64, 32), (6, 3, 64, 128)])
+def test_three_and_six_bit_values_attention(kvq, oracle, R, bk, bv, gk, gv):
+    """3- and 6-bit value blocks are a block of low parts and a block of high parts, which the kernel multiplies by the
+    softmax weights separately (the high parts' weights carry 2^LO).  Head ratios 1, 2, 8, all value group sizes (two
+    column sets included), several splits, ragged lengths, per-sequence lengths, rotated values."""
+    B, H, T = 2, 2, 2500
+    K, V, q = synth.make_kvq(1700 + 10 * bk + R, B, H, H * R, T, dtype=torch.float16)
+    rotv = 1 if bk == 8 else 0
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, rotv=rotv)
+    assert kvq.cache_bytes(Lg)[2] == B * H * 2528 * 16 * bv
     cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, [(0, 1), (1, 1000), (1000, T)])
     _assert_planes_equal(cache, planes)
     for seq_len in (T, 2049, 31):
@@ -1094,7 +1120,8 @@ def test_paged_channelwise_keys(kvq, oracle, R, bk, bv, gv, P):
 
 
 @pytest.mark.parametrize("bk,bv,gk,gv,P", [(4, 2, 64, 64, 64), (2, 4, 32, 128, 256), (8, 8, 64, 64, 128), (16, 16, 64, 64, 64),
-                                           (3, 2, 64, 64, 64), (1, 4, 128, 32, 128), (4, 1, 64, 32, 64)])
+                                           (3, 2, 64, 64, 64), (1, 4, 128, 32, 128), (4, 1, 64, 32, 64),
+                                           (4, 3, 64, 64, 128), (6, 6, 32, 64, 64)])
 def test_paged_append_and_reconstruction(kvq, oracle, bk, bv, gk, gv, P):
     B, H, T = 3, 2, 333
     K, V, _ = synth.make_kvq(210 + bk, B, H, H, T, dtype=torch.bfloat16)
@@ -1122,7 +1149,8 @@ def test_paged_append_and_reconstruction(kvq, oracle, bk, bv, gk, gv, P):
 
 @pytest.mark.parametrize("R,bk,bv,gk,gv,P", [(4, 4, 2, 64, 64, 64), (8, 4, 2, 32, 64, 256), (1, 2, 4, 64, 128, 128), (8, 8, 8, 64, 64, 64),
                                              (5, 16, 16, 64, 64, 64), (8, 3, 2, 64, 64, 128), (2, 6, 4, 32, 64, 64),
-                                             (8, 4, 1, 64, 64, 64), (3, 8, 1, 32, 128, 256)])
+                                             (8, 4, 1, 64, 64, 64), (3, 8, 1, 32, 128, 256), (4, 4, 3, 64, 64, 64),
+                                             (8, 8, 6, 64, 32, 128)])
 def test_paged_attention(kvq, oracle, R, bk, bv, gk, gv, P):
     """Attention over pool pages found through a shuffled page table: uniform and per-sequence lengths, several
     sequence splits, and fused steps that run across a page boundary."""
@@ -1193,7 +1221,7 @@ def test_attention_extremes(kvq, oracle, case):
         ramp = np.linspace(0.0, 30.0, T, dtype=np.float32)[None, None, :, None]
         K = K * 0.05 + ramp * np.sign(q[:, ::R])[:, :, None, :] / 128 * 11.3
     Kt, Vt, qt = torch.from_numpy(K).to(torch.float16), torch.from_numpy(V).to(torch.float16), torch.from_numpy(q).to(torch.float16)
-    for bk, bv in ((4, 2), (8, 8)):
+    for bk, bv in ((4, 2), (8, 8), (4, 3), (8, 6), (4, 1)):
         Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, 64, 64)
         cache, planes = _fill_both(kvq, oracle, Lg, Lo, Kt, Vt, [(0, T)])
         _assert_planes_equal(cache, planes)
