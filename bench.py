@@ -61,14 +61,15 @@ def _time_loop(fn, steps, warmup):
 
 def run_sweep(args, kvq, synth) -> int:
     """Bit-allocation sweep on the Llama-3-8B layer shape (B=8, H_q=32, H_kv=8, D=128, bf16, 64-channel groups):
-    K4V2, K2V4, K3V2 (48-byte key rows), K4V4, K8V8 and the unquantized bf16 cache at contexts 2048 / 8192 / 32768.  Per line: attention-output
+    K4V2, K2V4, K3V2 (48-byte key rows), K4V1 (16-byte value rows), K4V3, K4V4, K8V8 and the unquantized bf16 cache at
+    contexts 2048 / 8192 / 32768.  Per line: attention-output
     error against exact attention on the ORIGINAL tensors (CPU oracle, batch element 0) and effective GB/s of
     kvq_decode_attention over rotating cache copies (more bytes than the 256 MB last-level cache)."""
     import numpy as np
     from oracle import ref
     B, Hq, Hkv, D, G = 8, 32, 8, 128, 64
     scale = 1.0 / math.sqrt(D)
-    allocs = [("K4V2", 4, 2), ("K2V4", 2, 4), ("K3V2", 3, 2), ("K4V4", 4, 4), ("K8V8", 8, 8), ("bf16", 16, 16)]
+    allocs = [("K4V2", 4, 2), ("K2V4", 2, 4), ("K3V2", 3, 2), ("K4V1", 4, 1), ("K4V3", 4, 3), ("K4V4", 4, 4), ("K8V8", 8, 8), ("bf16", 16, 16)]
     for T in (2048, 8192, 32768):
         K, V, q = synth.make_kvq(2, B, Hkv, Hq, T, D, dtype=torch.bfloat16, device="cuda")
         want = ref.attention_dense(K[:1].float().cpu().numpy(), V[:1].float().cpu().numpy(),
