@@ -550,7 +550,7 @@ static int seq_layout_ok(const ref_layout* L) {
   if (L->axis_k != 1 || L->rotate_k || L->rotate_v) return 0;
   if (G != 32 && G != 64 && G != 128) return 0;
   if (D % 64 || D > 1024 || D % L->group_v) return 0;
-  if ((L->bits_k != 2 && L->bits_k != 4 && L->bits_k != 8) || (L->bits_v != 2 && L->bits_v != 4 && L->bits_v != 8)) return 0;
+  if ((L->bits_k != 2 && L->bits_k != 4 && L->bits_k != 8) || !bits_allowed(L->bits_v)) return 0;
   return 1;
 }
 

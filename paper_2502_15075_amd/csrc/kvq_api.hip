@@ -34,7 +34,7 @@ kvq_status check_layout(const kvq_layout* L) {
     // channel-wise keys: 64-token groups with a 64-slot residual buffer; quantized keys and values, no rotation
     if (L->bits_k == 16 || L->bits_v == 16 || L->rotate_k || L->rotate_v) return KVQ_ERR_INVALID_ARG;
     if (L->group_k != kvq::kSeqGroup) return KVQ_ERR_UNSUPPORTED;
-    if (!field_width(L->bits_k) || !field_width(L->bits_v)) return KVQ_ERR_UNSUPPORTED;
+    if (!field_width(L->bits_k)) return KVQ_ERR_UNSUPPORTED;      // (values: every width)
   }
   if ((int64_t)L->batch * L->kv_heads > 65535) return KVQ_ERR_UNSUPPORTED;
   if (L->max_seq > (1 << 24)) return KVQ_ERR_UNSUPPORTED;   // a (b,h) stream of any plane stays below 4 GiB

@@ -913,7 +913,9 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
         }
     }
   }
-  if (grp == 0 && L.j == 0) { sm_m[wave][h] = st.m; sm_l[wave][h] = l; }
+  // (records of kernels that carry their weights times different powers of two meet in one merge when channel-wise keys
+  // add the residual tail: the difference to 2^10 goes into the record's maximum)
+  if (grp == 0 && L.j == 0) { sm_m[wave][h] = st.m + (10.0f - p_shift<BV>()); sm_l[wave][h] = l; }
   __syncthreads();
 
   // ---- merge the wavefronts; write a partial record, or the result when there is one split

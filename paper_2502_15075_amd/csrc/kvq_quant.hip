@@ -95,16 +95,43 @@ __device__ __forceinline__ void store_value_words(uint32_t* vcp, const uint8_t* 
   }
 }
 
+// Bytes of LDS that stage the codes of one span: one staging area per part of a code (3- and 6-bit value codes are a
+// low part and a high part, each packed into a block of its own).
+template <int BV> constexpr int stage_area() { return kSpan * kHeadDim * (BV == 16 ? 2 : 1) * 17 / 16; }
+template <int BV> constexpr int stage_total() { return stage_area<BV>() * (key_hi_bits<BV>() ? 2 : 1); }
+
+template <int BV>
+__device__ __forceinline__ void stage_value_row(uint8_t* vstage, int row, int d0, const uint32_t codes[8]) {
+  constexpr int VLO = key_lo_bits<BV>(), VHI = key_hi_bits<BV>();
+  if constexpr (VHI == 0) {
+    stage_value_codes<BV>(vstage, row, d0, codes);
+  } else {                                         // (the low parts are cut to their field when the words are packed)
+    uint32_t high[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) high[e] = codes[e] >> VLO;
+    stage_value_codes<VLO>(vstage, row, d0, codes);
+    stage_value_codes<VHI>(vstage + stage_area<BV>(), row, d0, high);
+  }
+}
+
+// vc: the span's first block in the plane
+template <int BV>
+__device__ __forceinline__ void store_value_span(uint32_t* vc, const uint8_t* vstage, int tid, int lo, int hi) {
+  constexpr int VLO = key_lo_bits<BV>(), VHI = key_hi_bits<BV>();
+  if constexpr (VHI == 0) {
+    store_value_words<BV>(vc, vstage, tid, lo, hi);
+  } else {
+    store_value_words<VLO, 128 * BV>(vc, vstage, tid, lo, hi);
+    store_value_words<VHI, 128 * BV>(vc + 128 * VLO, vstage + stage_area<BV>(), tid, lo, hi);
+  }
+}
+
 // One workgroup = one 64-token span of one (b,h) stream, restricted to the new tokens in it.
 template <int BK, int BV, bool BF>
 __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_new,
                                                               const uint16_t* __restrict__ v_new, int64_t sb, int64_t sh,
                                                               int64_t st, int32_t pos, int32_t n_new) {
-  constexpr int ES = BV == 16 ? 2 : 1;            // bytes per staged element
-  constexpr int VLO = key_lo_bits<BV>(), VHI = key_hi_bits<BV>();   // 3- and 6-bit value codes: low and high parts
-  constexpr int kStageBytes = kSpan * kHeadDim * ES;
-  constexpr int kStagePadded = kStageBytes + (kStageBytes >> 4);
-  __shared__ __attribute__((aligned(16))) uint8_t vstage[kStagePadded * (VHI ? 2 : 1)];
+  __shared__ __attribute__((aligned(16))) uint8_t vstage[stage_total<BV>()];
   const int tid = threadIdx.x;
   const int bh = blockIdx.y;
   const int b = bh / g.kv_heads, h = bh % g.kv_heads;
@@ -174,25 +201,12 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         quantize8(x, BV, lpg, codes, &S, &Z);
         if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
       }
-      if constexpr (VHI == 0) {
-        stage_value_codes<BV>(vstage, row, d0, codes);
-      } else {                                     // (the low parts are cut to their field when the words are packed)
-        uint32_t high[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) high[e] = codes[e] >> VLO;
-        stage_value_codes<VLO>(vstage, row, d0, codes);
-        stage_value_codes<VHI>(vstage + kStagePadded, row, d0, high);
-      }
+      stage_value_row<BV>(vstage, row, d0, codes);
     }
   }
   __syncthreads();
 
-  if constexpr (VHI == 0) {
-    store_value_words<BV>(vc, vstage, tid, lo, hi);
-  } else {
-    store_value_words<VLO, 128 * BV>(vc, vstage, tid, lo, hi);
-    store_value_words<VHI, 128 * BV>(vc + 128 * VLO, vstage + kStagePadded, tid, lo, hi);
-  }
+  store_value_span<BV>(vc, vstage, tid, lo, hi);
 }
 
 // The 8 fields of channels d0 .. d0+7 (d0 a multiple of 8) of token u in a 32-token block of B-bit fields: the same
@@ -230,8 +244,7 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
                                                          int64_t st, int32_t pos, int32_t n_new,
                                                          const int32_t* __restrict__ pos_arr, int32_t max_pos) {
   static_assert(kSeqGroup == kSpan, "a flushed block is one value span");
-  constexpr int kStageBytes = kSpan * kHeadDim;
-  __shared__ __attribute__((aligned(16))) uint8_t vstage[kStageBytes + (kStageBytes >> 4)];
+  __shared__ __attribute__((aligned(16))) uint8_t vstage[stage_total<BV>()];
   __shared__ float s_mn[4][kHeadDim], s_mx[4][kHeadDim];
   const int tid = threadIdx.x;
   const int bh = blockIdx.y;
@@ -339,10 +352,10 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
     const int lpg = g.g_v >> 3;
     quantize8(xv, BV, lpg, vcodes, &S, &Z);
     if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
-    stage_value_codes<BV>(vstage, row, d0, vcodes);
+    stage_value_row<BV>(vstage, row, d0, vcodes);
   }
   __syncthreads();
-  store_value_words<BV>(vc, vstage, tid, 0, kSpan);
+  store_value_span<BV>(vc, vstage, tid, 0, kSpan);
 }
 
 // Reconstruction x^ = code * scale + zero of 8 consecutive channels d0..d0+7 (d0 a multiple of 8) of the token with
@@ -596,8 +609,11 @@ hipError_t launch_sak(const Geom& g, const kvq_cache& c, const void* k_new, cons
                       int64_t sh, int64_t st, int32_t pos, int32_t n_new, const int32_t* pos_arr, int32_t max_pos,
                       hipStream_t stream) {
   switch (g.bits_v) {
+    case 1: return launch_sa<BK, 1>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
     case 2: return launch_sa<BK, 2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
+    case 3: return launch_sa<BK, 3>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
     case 4: return launch_sa<BK, 4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
+    case 6: return launch_sa<BK, 6>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
     case 8: return launch_sa<BK, 8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
   }
   return hipErrorInvalidValue;
