@@ -550,7 +550,7 @@ static int seq_layout_ok(const ref_layout* L) {
   if (L->axis_k != 1 || L->rotate_k || L->rotate_v) return 0;
   if (G != 32 && G != 64 && G != 128) return 0;
   if (D % 64 || D > 1024 || D % L->group_v) return 0;
-  if ((L->bits_k != 2 && L->bits_k != 4 && L->bits_k != 8) || !bits_allowed(L->bits_v)) return 0;
+  if (!bits_allowed(L->bits_k) || !bits_allowed(L->bits_v)) return 0;
   return 1;
 }
 
@@ -610,7 +610,7 @@ int ref_seq_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, uint8
         uint8_t* m = km + (blk * D + d) * 4;
         m[0] = (uint8_t)(S & 0xFF); m[1] = (uint8_t)(S >> 8);
         m[2] = (uint8_t)(Z & 0xFF); m[3] = (uint8_t)(Z >> 8);
-        for (int i = 0; i < G; ++i) put_bits_le(kc, k_bit_offset(t0 + i, d, D, bk), bk, codes[i]);
+        for (int i = 0; i < G; ++i) k_put_code(kc, t0 + i, d, D, bk, codes[i]);
       }
       for (int i = 0; i < G; ++i) {                           /* values: token-wise groups as always */
         for (int d = 0; d < D; ++d) {
@@ -659,7 +659,7 @@ int ref_seq_dequantize(const ref_layout* L, const uint8_t* k_codes, const uint8_
         float kv, vv;
         if (t < n_flushed) {
           const uint8_t* m = km + ((t / G) * D + d) * 4;
-          kv = ref_reconstruct(get_bits_le(kc, k_bit_offset(t, d, D, bk), bk), (uint16_t)(m[0] | (m[1] << 8)), (uint16_t)(m[2] | (m[3] << 8)));
+          kv = ref_reconstruct(k_get_code(kc, t, d, D, bk), (uint16_t)(m[0] | (m[1] << 8)), (uint16_t)(m[2] | (m[3] << 8)));
           const uint8_t* mv = vm + meta_offset(t, d / GV, D / GV);
           vv = ref_reconstruct(v_get_code(vc, t, d, D, bv), (uint16_t)(mv[0] | (mv[1] << 8)), (uint16_t)(mv[2] | (mv[3] << 8)));
         } else {

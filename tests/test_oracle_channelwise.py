@@ -43,7 +43,8 @@ def _quantize_rows_numpy(X, bits, G):
     return codes, S, Z
 
 
-@pytest.mark.parametrize("G,bk,bv,gv", [(64, 4, 2, 64), (32, 2, 4, 128), (128, 8, 8, 32)])
+@pytest.mark.parametrize("G,bk,bv,gv", [(64, 4, 2, 64), (32, 2, 4, 128), (128, 8, 8, 32), (64, 6, 1, 64), (64, 3, 6, 32),
+                                        (32, 1, 3, 64)])
 def test_flushed_blocks_match_numpy_and_the_residual_holds_the_tail(oracle, G, bk, bv, gv):
     rng = np.random.default_rng(G + bk)
     B, H, D = 2, 2, 128
@@ -66,7 +67,7 @@ def test_flushed_blocks_match_numpy_and_the_residual_holds_the_tail(oracle, G, b
             c, s, z = _quantize_columns_numpy(Kb[blk * G:(blk + 1) * G], bk)
             codes[blk * G:(blk + 1) * G] = c
             meta[blk, :, 0], meta[blk, :, 1] = s, z
-        k_plane = _pack_fields_le(codes.ravel(), bk)
+        k_plane = _pack_key_rows_numpy(codes, bk)
         got_k = planes[0].reshape(B * H, -1)[bh]
         assert np.array_equal(got_k[:nq * 16 * bk], k_plane[:nq * 16 * bk])
         assert (got_k[nq * 16 * bk:] == 0xA5).all()                       # nothing beyond the flushed blocks is written
@@ -75,7 +76,7 @@ def test_flushed_blocks_match_numpy_and_the_residual_holds_the_tail(oracle, G, b
         assert (got_m[(nq // G) * D * 4:] == 0xA5).all()
         # values: the token-wise planes of the flushed tokens
         vcodes, S, Z = _quantize_rows_numpy(np.concatenate([Vb[:nq].astype(np.float32), np.zeros((cap - nq, D), np.float32)]), bv, gv)
-        _, vmeta, v_plane = _expected_planes(vcodes, S, Z, bv, gv)
+        vmeta, v_plane = _expected_planes(vcodes, S, Z, 8, gv)[1], _pack_value_blocks_numpy(vcodes, S, Z, bv, gv)
         got_v = planes[2].reshape(B * H, -1)[bh]
         assert np.array_equal(got_v[:nq * 16 * bv], v_plane[:nq * 16 * bv]) and (got_v[nq * 16 * bv:] == 0xA5).all()
         got_vm = planes[3].reshape(B * H, -1)[bh]
