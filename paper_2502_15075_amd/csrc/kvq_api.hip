@@ -4,7 +4,6 @@
 namespace {
 
 bool bits_ok(int b) { return b == 1 || b == 2 || b == 3 || b == 4 || b == 6 || b == 8 || b == 16; }
-bool field_width(int b) { return b == 2 || b == 4 || b == 8; }
 bool group_ok(int g) { return g == 32 || g == 64 || g == 128; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -34,7 +33,6 @@ kvq_status check_layout(const kvq_layout* L) {
     // channel-wise keys: 64-token groups with a 64-slot residual buffer; quantized keys and values, no rotation
     if (L->bits_k == 16 || L->bits_v == 16 || L->rotate_k || L->rotate_v) return KVQ_ERR_INVALID_ARG;
     if (L->group_k != kvq::kSeqGroup) return KVQ_ERR_UNSUPPORTED;
-    if (!field_width(L->bits_k)) return KVQ_ERR_UNSUPPORTED;      // (values: every width)
   }
   if ((int64_t)L->batch * L->kv_heads > 65535) return KVQ_ERR_UNSUPPORTED;
   if (L->max_seq > (1 << 24)) return KVQ_ERR_UNSUPPORTED;   // a (b,h) stream of any plane stays below 4 GiB

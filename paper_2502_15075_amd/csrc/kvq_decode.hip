@@ -329,7 +329,14 @@ struct KSeqState {
   u32x4 qop[4];            // query operand of the current block: this lane's part (high or low) of its head
   float zq_u;              // zero-point term of the current block, in code units (lanes of the high part; else 0)
 };
+struct KSeqState2 : KSeqState {
+  u32x4 qoph[4];           // the same for the high run of 3- and 6-bit key codes (carries the factor 2^LO)
+};
 struct NoKSeq {};
+// 2-, 4- and 8-bit keys: the staged query row is already divided by the position factor of each channel's code
+// (k_chan_scale).  1-, 3- and 6-bit keys: the row is staged as it is and the factors of each run's slots are applied
+// when the operands are built.
+template <int BK> constexpr bool kseq_prescaled() { return BK == 2 || BK == 4 || BK == 8; }
 
 // Rebuild the block's query operand from the staged query row and the block's 128 scale/zero entries (first 512 bytes
 // of the wavefront's LDS copy of the step's scale/zero bytes).
@@ -381,6 +388,55 @@ __device__ __forceinline__ void kseq_rebuild(KSeqState& ks, const LaneCtx& L, co
   ks.zq_u = zq * (kCodeUnit - kCodeUnit * low_part);          // (only the high part's column adds the constant)
 }
 
+// The same for 1-, 3- and 6-bit keys: all 32 products q[d] sK[d] of the lane first (a single-bit run takes a matrix
+// step's channels from both halves of the 32), then one operand set per run, each slot divided by the power of two at
+// which the run's codes are left in their 16-bit lanes, the high run's times 2^LO.
+template <int BK, typename KS>
+__device__ __forceinline__ void kseq_rebuild_runs(KS& ks, const LaneCtx& L, const float* qrow, float low_part) {
+  constexpr int KLO = k_lo<BK>(), KHI = k_hi<BK>();
+  typedef __fp16 half2v __attribute__((ext_vector_type(2)));
+  const float nlow = -low_part;
+  float w[32];
+  float zq = 0.f;
+#pragma unroll
+  for (int quad = 0; quad < 8; ++quad) {
+    const float4v qf = *reinterpret_cast<const float4v*>(qrow + 32 * L.j + 4 * quad);
+    const u32x4 mv = *reinterpret_cast<const u32x4*>(L.meta_lds + 128 * L.j + 16 * quad);
+    const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      w[4 * quad + e] = fmaf(qf[e], meta_scale(mw[e]), 0.0f);
+      zq = fmaf(qf[e], meta_zero(mw[e]), zq);
+    }
+  }
+  auto part16 = [&](float a, float b) -> uint32_t {          // this lane's part (high or low) of the pair, see above
+    const half2v h = __builtin_amdgcn_cvt_pkrtz(a, b);
+    const float xa = fmaf((float)h.x, nlow, a), xb = fmaf((float)h.y, nlow, b);
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(xa, xb));
+  };
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    uint32_t op[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float f = 1.0f / k_slot_scale<KLO>(2 * v);
+      op[v] = part16(w[k_slot_elem<KLO>(m, 2 * v)] * f, w[k_slot_elem<KLO>(m, 2 * v + 1)] * f);
+    }
+    ks.qop[m] = u32x4{op[0], op[1], op[2], op[3]};
+    if constexpr (KHI != 0) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const float f = (float)(1 << KLO) / k_slot_scale<KHI, k_hi_base<BK>()>(2 * v);
+        op[v] = part16(w[k_slot_elem<KHI>(m, 2 * v)] * f, w[k_slot_elem<KHI>(m, 2 * v + 1)] * f);
+      }
+      ks.qoph[m] = u32x4{op[0], op[1], op[2], op[3]};
+    }
+  }
+  zq += __shfl_xor(zq, 16);
+  zq += __shfl_xor(zq, 32);
+  ks.zq_u = zq * (kCodeUnit - kCodeUnit * low_part);
+}
+
 // One 32-token step.  MASKED: tokens at or beyond seq_len get weight 0 (garbage may sit there).
 // BK == BV == 16 is the unquantized cache: no scale/zero, operands are the stored patterns (BF: bfloat16).
 // NCK / NCV: column sets.  Columns are (group, head) pairs; when R * (groups) exceeds the 16 columns of a matrix tile
@@ -400,7 +456,10 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
   if constexpr (!RAW) {
     // scale/zero bytes: plane order -> LDS -> the entries this lane needs (tokens 4j..4j+3 of both tiles, own groups)
     *reinterpret_cast<u32x4*>(L.meta_lds + L.lane * 16) = r.meta;     // (lanes beyond the bytes fill slots nobody reads)
-    if constexpr (KSEQ && NEWBLK) kseq_rebuild<BK>(ks, L, qrow, kseq_low);
+    if constexpr (KSEQ && NEWBLK) {
+      if constexpr (kseq_prescaled<BK>()) kseq_rebuild<BK>(ks, L, qrow, kseq_low);
+      else kseq_rebuild_runs<BK>(ks, L, qrow, kseq_low);
+    }
 #pragma unroll
     for (int x4 = 0; x4 < 2; ++x4) {
 #pragma unroll
@@ -425,8 +484,12 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
       float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int m = 0; m < 4; ++m) {                // two independent accumulation chains (the two 16-token tiles)
-        d0 = mma<BF>(unpack_k<BK>(r.kc[0], m), ks.qop[m], d0);
-        d1 = mma<BF>(unpack_k<BK>(r.kc[1], m), ks.qop[m], d1);
+        d0 = mma<BF>(unpack_k<KLO>(r.kc[0], m), ks.qop[m], d0);
+        d1 = mma<BF>(unpack_k<KLO>(r.kc[1], m), ks.qop[m], d1);
+        if constexpr (KHI != 0) {
+          d0 = mma<BF>(unpack_k<KHI, k_hi_base<BK>()>(r.kc[0] + KLO, m), ks.qoph[m], d0);
+          d1 = mma<BF>(unpack_k<KHI, k_hi_base<BK>()>(r.kc[1] + KLO, m), ks.qoph[m], d1);
+        }
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) part[i] = (i < 4 ? d0[i & 3] : d1[i & 3]) + ks.zq_u;
@@ -781,7 +844,8 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
       for (int e = 0; e < 8; ++e)
-        sm_qf[tid >> 4][8 * (tid & 15) + e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), q_is_bf16) / k_chan_scale<BK>(e);
+        sm_qf[tid >> 4][8 * (tid & 15) + e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), q_is_bf16) /
+                                              (kseq_prescaled<BK>() ? k_chan_scale<BK>(e) : 1.0f);
     }
     if constexpr (!RAW) {
       // per-group sums of the (staged) query: the zero points of a key group enter the scores through them
@@ -860,7 +924,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
 
   // ---- main loop, unrolled over the ring: compute a step, then refill its registers with the step kStages
   // ahead, so that kStages-1 steps of loads are always in flight behind the one being computed.
-  typename std::conditional<KSEQ, KSeqState, NoKSeq>::type ks;
+  typename std::conditional<KSEQ, typename std::conditional<k_hi<BK>() != 0, KSeqState2, KSeqState>::type, NoKSeq>::type ks;
   const float* qrow = &sm_qf[KSEQ ? (grp < 2 ? h : R) : 0][0];   // (column groups 0 and 1 carry the key side)
   // one complete step out of ring slot k (for channel-wise keys an even slot starts a block)
   auto full_step = [&](int k, int i) {
@@ -1058,9 +1122,7 @@ hipError_t KVQ_CAT(launch_decode_inst_, KVQ_INST_BK, KVQ_INST_BV)(int R, const D
 #if KVQ_INST_BK == 16
   return a.g.raw_dtype == KVQ_BF16 ? launch_r<16, 16, true>(R, a, plan, stream) : launch_r<16, 16, false>(R, a, plan, stream);
 #else
-#if KVQ_INST_BK == 2 || KVQ_INST_BK == 4 || KVQ_INST_BK == 8
   if (a.g.axis_k == KVQ_AXIS_SEQ) return launch_r<KVQ_INST_BK, KVQ_INST_BV, false, true>(R, a, plan, stream);
-#endif
   return launch_r<KVQ_INST_BK, KVQ_INST_BV>(R, a, plan, stream);
 #endif
 }

@@ -622,7 +622,10 @@ hipError_t launch_sa_bits(const Geom& g, const kvq_cache& c, const void* k_new, 
                           int64_t sh, int64_t st, int32_t pos, int32_t n_new, const int32_t* pos_arr, int32_t max_pos,
                           hipStream_t stream) {
   switch (g.bits_k) {
+    case 1: return launch_sak<1>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
     case 2: return launch_sak<2>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
+    case 3: return launch_sak<3>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
+    case 6: return launch_sak<6>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
     case 4: return launch_sak<4>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
     case 8: return launch_sak<8>(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n_new, pos_arr, max_pos, stream);
   }

@@ -100,7 +100,6 @@ def test_layout_errors(kvq):
     bad = [
         (kvq.Layout(0, 8, 64), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 0), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 7, 2), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, 128, 4, 5), kvq.ERR_INVALID_ARG),
-        (kvq.Layout(1, 8, 64, 128, 3, 2, 64, 64, axis_k=1), kvq.ERR_UNSUPPORTED),     # channel-wise keys: field widths only
         (kvq.Layout(1, 8, 64, 128, 4, 2, 48, 64), kvq.ERR_INVALID_ARG), (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 256), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 64), kvq.ERR_UNSUPPORTED), (kvq.Layout(1, 8, 64, 128, 4, 2, 32, 64, axis_k=1), kvq.ERR_UNSUPPORTED),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_v=1), kvq.ERR_UNSUPPORTED),

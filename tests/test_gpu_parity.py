@@ -591,7 +591,8 @@ def _assert_seq_planes_equal(cache, planes):
         assert bad.size == 0, f"{name}: {bad.size} bytes differ, first at {bad[:5]}"
 
 
-@pytest.mark.parametrize("bk,bv,gv", [(4, 2, 64), (2, 4, 128), (8, 8, 32), (4, 4, 64), (4, 1, 64), (8, 6, 128), (2, 3, 32)])
+@pytest.mark.parametrize("bk,bv,gv", [(4, 2, 64), (2, 4, 128), (8, 8, 32), (4, 4, 64), (4, 1, 64), (8, 6, 128), (2, 3, 32),
+                                      (6, 2, 64), (3, 3, 128), (1, 4, 32)])
 @pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
 def test_channelwise_append_is_byte_identical(kvq, oracle, bk, bv, gv, dtype):
     """Sec. 4, per-column keys with the 64-token residual buffer: all six planes (codes, scale/zero, residual
@@ -618,7 +619,8 @@ def test_channelwise_append_is_byte_identical(kvq, oracle, bk, bv, gv, dtype):
 
 @pytest.mark.parametrize("R", [1, 2, 4, 8])
 @pytest.mark.parametrize("bk,bv,gv", [(4, 2, 64), (2, 4, 128), (4, 4, 32), (2, 2, 64), (8, 8, 64), (8, 2, 128), (4, 8, 32),
-                                      (4, 1, 64), (8, 6, 32), (2, 3, 128), (8, 1, 32), (4, 6, 64)])
+                                      (4, 1, 64), (8, 6, 32), (2, 3, 128), (8, 1, 32), (4, 6, 64),
+                                      (6, 2, 64), (6, 1, 128), (3, 2, 32), (1, 2, 64), (6, 6, 64), (3, 8, 64)])
 def test_channelwise_attention(kvq, oracle, R, bk, bv, gv):
     """Attention over channel-wise keys: flushed blocks from the codes, the newest tokens from the residual buffer.
     Lengths: residual only, whole blocks only, both; the cache is rebuilt for every length (the buffer's content
@@ -669,7 +671,8 @@ def test_channelwise_decode_steps_cross_a_flush(kvq, oracle):
         assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
 
 
-@pytest.mark.parametrize("R,bk,bv,gv", [(4, 4, 2, 64), (8, 2, 4, 128), (1, 8, 8, 32), (8, 4, 1, 64), (2, 8, 6, 64)])
+@pytest.mark.parametrize("R,bk,bv,gv", [(4, 4, 2, 64), (8, 2, 4, 128), (1, 8, 8, 32), (8, 4, 1, 64), (2, 8, 6, 64), (8, 6, 2, 64),
+                                       (4, 3, 4, 128)])
 def test_channelwise_ragged_batch_attention_and_steps(kvq, oracle, R, bk, bv, gv):
     """Per-sequence lengths with channel-wise keys: every sequence has its own flushed blocks and its own tail in its
     residual buffer (lengths below one block, exactly on a block boundary, several blocks plus a tail, several splits);
@@ -1055,7 +1058,7 @@ def _assert_paged_equal(oracle, Lo, cache, planes, table, P, n_pages):
 
 
 @pytest.mark.parametrize("R,bk,bv,gv,P", [(4, 4, 2, 64, 64), (8, 2, 4, 128, 256), (2, 8, 8, 32, 128), (8, 4, 1, 64, 64),
-                                         (4, 8, 3, 32, 128)])
+                                         (4, 8, 3, 32, 128), (8, 6, 2, 64, 64), (2, 1, 4, 64, 256)])
 def test_paged_channelwise_keys(kvq, oracle, R, bk, bv, gv, P):
     """Channel-wise keys in a paged pool: the four code/scale planes live in pages found through the table (a 64-token
     block never straddles a page), the residual buffers stay per sequence.  Appends (ragged chunks, bulk), the flushed
@@ -1291,11 +1294,11 @@ def test_random_token_wise_configurations(kvq, oracle, case):
 
 @pytest.mark.parametrize("case", range(24))
 def test_random_channelwise_configurations(kvq, oracle, case):
-    """Seeded random channel-wise caches (2/4/8-bit keys, values of every width, value group sizes, head ratios, contiguous or paged, both
+    """Seeded random channel-wise caches (every width for keys and values, value group sizes, head ratios, contiguous or paged, both
     input types): ragged chunked appends, attention over flushed blocks plus tail, fused steps across whatever boundary
     the lengths happen to produce; all six planes byte-identical, outputs within tolerance."""
     rng = np.random.default_rng(9000 + case)
-    bk, bv = int(rng.choice([2, 4, 8])), int(rng.choice([1, 2, 3, 4, 6, 8]))
+    bk, bv = (int(rng.choice([1, 2, 3, 4, 6, 8])) for _ in range(2))
     gv = int(rng.choice([32, 64, 128]))
     r = int(rng.integers(1, 9))
     if (1 if r <= 1 else 2 if r <= 2 else 4 if r <= 4 else 8) * (128 // gv) > 32:
