@@ -194,7 +194,7 @@ def run_rotation(args, kvq, synth) -> int:
 def run_channelwise(args, kvq, synth) -> int:
     """Token-wise against channel-wise key groups (Sec. 4 "Downstream Task Accuracy": the per-row and the per-column
     back-end, the latter with its 64-token full-precision residual buffer) on the 8B layer shape, 64-element groups:
-    K2V2, K2V4, K4V2, K4V4 at context 32768 + 40 (so that the residual buffer holds 40 tokens).  Per line: key MSE over
+    K2V2, K2V4, K4V2, K4V4, K4V1, K6V2 at context 32768 + 40 (so that the residual buffer holds 40 tokens).  Per line: key MSE over
     the flushed tokens, attention-output error against exact attention on the original tensors (CPU oracle, batch
     element 0), bulk append rate and decode time."""
     import numpy as np
@@ -206,7 +206,7 @@ def run_channelwise(args, kvq, synth) -> int:
     want = ref.attention_dense(K[:1].float().cpu().numpy(), V[:1].float().cpu().numpy(),
                                synth.to_numpy_bits(q[:1]), scale, bf16=True).astype(np.float64)
     sums = torch.empty(B, Hkv, 2, dtype=torch.float64, device="cuda")
-    for bk, bv in ((2, 2), (2, 4), (4, 2), (4, 4)):
+    for bk, bv in ((2, 2), (2, 4), (4, 2), (4, 4), (4, 1), (6, 2)):
         for axis in (kvq.AXIS_HEAD_DIM, kvq.AXIS_SEQ):
             L = kvq.Layout(B, Hkv, T, D, bk, bv, G, G, axis_k=axis, raw_dtype=kvq.KVQ_BF16)
             row_bytes = 16 * bk + 16 * bv + 2 * 4 * (D // G)
