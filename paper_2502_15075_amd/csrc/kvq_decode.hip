@@ -1021,26 +1021,51 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
 }
 
 // Combine the split records of one (b, hq): log-sum-exp merge, then normalize (and take rotated values back).
+// 512 threads: four groups of 128 channels, group k takes the records s = k, k+4, ...  Every load is independent of
+// the ones before it (the maxima first, by one thread per record; then the weighted sums with the loop unrolled), so
+// the kernel costs a few memory latencies rather than one per record.
 struct RotV { int32_t on; uint32_t signs[4]; };
-__global__ __launch_bounds__(128) void merge_kernel(const float* __restrict__ ws, void* __restrict__ out, int out_dtype,
-                                                    int32_t n_splits, RotV rot) {
+constexpr int kMergeGroups = 4;
+__global__ __launch_bounds__(128 * kMergeGroups) void merge_kernel(const float* __restrict__ ws, void* __restrict__ out,
+                                                                   int out_dtype, int32_t n_splits, RotV rot) {
   __shared__ float row[kHeadDim];
+  __shared__ float s_part[kMergeGroups][kHeadDim + 1];     // partial sums of o (128) and l (1) per group
+  __shared__ float s_max[128 * kMergeGroups / 64];
   const int64_t hq = blockIdx.x;
-  const int d = threadIdx.x;
+  const int tid = threadIdx.x, d = tid & (kHeadDim - 1), grp = tid >> 7;
   const float* rec = ws + hq * n_splits * kRec;
+  // maximum over the records
   float M = kNegBig;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, rec[s * kRec + kHeadDim]);
+  for (int s = tid; s < n_splits; s += 128 * kMergeGroups) M = fmaxf(M, rec[s * kRec + kHeadDim]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+  if ((tid & 63) == 0) s_max[tid >> 6] = M;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < 128 * kMergeGroups / 64; ++w) M = fmaxf(M, s_max[w]);
+  // weighted sums of this group's records
   float o = 0.f, l = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
+#pragma unroll 8
+  for (int s = grp; s < n_splits; s += kMergeGroups) {
     const float f = exp2f(rec[s * kRec + kHeadDim] - M);
     o = fmaf(f, rec[s * kRec + d], o);
     l = fmaf(f, rec[s * kRec + kHeadDim + 1], l);
   }
+  s_part[grp][d] = o;
+  if (d == 0) s_part[grp][kHeadDim] = l;
+  __syncthreads();
+  if (grp != 0) {
+    if (!rot.on) return;
+  } else {
+    o = 0.f; l = 0.f;
+#pragma unroll
+    for (int k = 0; k < kMergeGroups; ++k) { o += s_part[k][d]; l += s_part[k][kHeadDim]; }
+  }
   const float val = o / l;
   if (rot.on) {                                      // uniform
-    row[d] = val;
+    if (grp == 0) row[d] = val;
     __syncthreads();
-    if (d < 16) store_unrotated_row(row, d, rot.signs, out, out_dtype, hq);
+    if (tid < 16) store_unrotated_row(row, tid, rot.signs, out, out_dtype, hq);
     return;
   }
   if (out_dtype == KVQ_F32) ((float*)out)[hq * kHeadDim + d] = val;
@@ -1094,7 +1119,7 @@ hipError_t launch_one(const DecodeArgs& a, const DecodePlan& plan, hipStream_t s
                      : launch_sets<BK, BV, R, BF, KSEQ, false>(a, plan, grid, stream);
   // the records of this launch are all there is: merge them here (otherwise the caller adds launches and merges)
   if (e != hipSuccess || a.rec_splits == 1 || a.rec_splits != plan.n_splits) return e;
-  hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128), 0, stream, a.ws, a.out, a.out_dtype, a.rec_splits,
+  hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128 * kMergeGroups), 0, stream, a.ws, a.out, a.out_dtype, a.rec_splits,
                      rot_v_of(a.g));
   return hipGetLastError();
 }
@@ -1228,7 +1253,7 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
       if (e != hipSuccess) return e;
     }
     if (records > 1 && !(n_flushed && !tail)) {     // (a launch that wrote all the records has merged them itself)
-      hipLaunchKernelGGL(merge_kernel, dim3(g.batch * q_heads), dim3(128), 0, stream, workspace, out, out_dtype, records,
+      hipLaunchKernelGGL(merge_kernel, dim3(g.batch * q_heads), dim3(128 * kMergeGroups), 0, stream, workspace, out, out_dtype, records,
                          rot_v_of(g));
       e = hipGetLastError();
     }
