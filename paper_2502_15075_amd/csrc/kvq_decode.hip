@@ -140,8 +140,8 @@ template <int BK, int BASE = k_default_base<BK>()> __device__ __forceinline__ u3
 // Key codes of 3 and 6 bits are a low run (2 / 4 bits, the first dwords of the lane's 32 channels) and a high run
 // (1 / 2 bits, the rest): two operands, multiplied by the query separately (the high run's query operand carries the
 // factor 2^LO).
-template <int BK> constexpr int k_lo() { return key_lo_bits<BK>(); }
-template <int BK> constexpr int k_hi() { return key_hi_bits<BK>(); }
+template <int BK> constexpr int k_lo() { return code_lo_bits<BK>(); }
+template <int BK> constexpr int k_hi() { return code_hi_bits<BK>(); }
 template <int BK> constexpr int k_hi_base() { return BK == 3 ? 5 : 6; }   // high run: single bits from bit 5, pairs from bit 6
 
 // ---- value codes: one lane holds, per 32-token step, 2*BV dwords (index = 4*piece + dword; 1-bit codes: one piece
@@ -151,8 +151,8 @@ template <int BK> constexpr int k_hi_base() { return BK == 3 ? 5 : 6; }   // hig
 // divided by 2^shift instead (an exponent offset, free).
 // Value codes of 3 and 6 bits are a block of low parts (2 / 4 bits) and a block of high parts (1 / 2 bits): two
 // operands per d-tile; v_slot_shift is the low part's, and the high part's weights carry the factor v_hi_factor.
-template <int BV> constexpr int v_lo() { return key_lo_bits<BV>(); }
-template <int BV> constexpr int v_hi() { return key_hi_bits<BV>(); }
+template <int BV> constexpr int v_lo() { return code_lo_bits<BV>(); }
+template <int BV> constexpr int v_hi() { return code_hi_bits<BV>(); }
 template <int B> __device__ __forceinline__ constexpr int field_slot_shift(int v) {
   return B == 1 ? v : B == 2 ? 2 * v : (B == 4 ? 4 * (v & 1) : 0);
 }
@@ -198,8 +198,8 @@ constexpr int ring_stages() {
   constexpr int regs = 2 * BK + 2 * BV + 4;
   constexpr int base = regs <= 16 ? KVQ_STAGES : regs <= 20 ? 3 : 2;
   constexpr int less = (NCK == 2 ? 2 : 0) + (NCV == 2 ? 1 : 0)    // a second column set costs registers (query operand,
-                       + (key_hi_bits<BK>() ? 1 : 0)              // scale/zero entries, weights), so does a high run
-                       + (key_hi_bits<BV>() ? 1 : 0)              // of keys or a high part of values (its weights)
+                       + (code_hi_bits<BK>() ? 1 : 0)              // scale/zero entries, weights), so does a high run
+                       + (code_hi_bits<BV>() ? 1 : 0)              // of keys or a high part of values (its weights)
                        + (BK == 2 && regs >= 16 ? 1 : 0);         // (moved 2-bit fields: two shifted copies of a word live)
   return base - less >= 1 ? base - less : 1;
 }

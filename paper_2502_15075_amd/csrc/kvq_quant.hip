@@ -98,11 +98,11 @@ __device__ __forceinline__ void store_value_words(uint32_t* vcp, const uint8_t* 
 // Bytes of LDS that stage the codes of one span: one staging area per part of a code (3- and 6-bit value codes are a
 // low part and a high part, each packed into a block of its own).
 template <int BV> constexpr int stage_area() { return kSpan * kHeadDim * (BV == 16 ? 2 : 1) * 17 / 16; }
-template <int BV> constexpr int stage_total() { return stage_area<BV>() * (key_hi_bits<BV>() ? 2 : 1); }
+template <int BV> constexpr int stage_total() { return stage_area<BV>() * (code_hi_bits<BV>() ? 2 : 1); }
 
 template <int BV>
 __device__ __forceinline__ void stage_value_row(uint8_t* vstage, int row, int d0, const uint32_t codes[8]) {
-  constexpr int VLO = key_lo_bits<BV>(), VHI = key_hi_bits<BV>();
+  constexpr int VLO = code_lo_bits<BV>(), VHI = code_hi_bits<BV>();
   if constexpr (VHI == 0) {
     stage_value_codes<BV>(vstage, row, d0, codes);
   } else {                                         // (the low parts are cut to their field when the words are packed)
@@ -117,7 +117,7 @@ __device__ __forceinline__ void stage_value_row(uint8_t* vstage, int row, int d0
 // vc: the span's first block in the plane
 template <int BV>
 __device__ __forceinline__ void store_value_span(uint32_t* vc, const uint8_t* vstage, int tid, int lo, int hi) {
-  constexpr int VLO = key_lo_bits<BV>(), VHI = key_hi_bits<BV>();
+  constexpr int VLO = code_lo_bits<BV>(), VHI = code_hi_bits<BV>();
   if constexpr (VHI == 0) {
     store_value_words<BV>(vc, vstage, tid, lo, hi);
   } else {
@@ -143,10 +143,14 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
 
   // rows of all four planes are addressed by the span's first token in plane order (a span never straddles a page)
   const int64_t tv0 = virtual_token(g, c.page_table, b, h, (int64_t)blk * kSpan);
-  uint8_t* kc = (uint8_t*)c.k_codes;
-  uint32_t* km = (uint32_t*)c.k_meta;
-  uint32_t* vm = (uint32_t*)c.v_meta;
   uint32_t* vc = (uint32_t*)c.v_codes + (tv0 >> 5) * (128 * BV);
+  // tv0 is a multiple of 32 (of the page size when paged), so row (tid/16) + 16*it sits at position tid/16 of the
+  // span's it-th slab of 16 tokens in the scale/zero planes: one address per thread, a uniform stride per it
+  const int lpg_k = g.g_k >> 3, lpg_v = g.g_v >> 3;                  // lanes per group
+  uint8_t* kc = (uint8_t*)c.k_codes + (tv0 + (tid >> 4)) * (BK == 16 ? 256 : 16 * BK);
+  uint32_t* km = (uint32_t*)c.k_meta + meta_index(tv0 + (tid >> 4), lane16 >> lpg_shift(lpg_k), g.ng_k);
+  uint32_t* vm = (uint32_t*)c.v_meta + meta_index(tv0 + (tid >> 4), lane16 >> lpg_shift(lpg_v), g.ng_v);
+  const int km_step = 16 * g.ng_k, vm_step = 16 * g.ng_v;
 
   // each thread owns 8 channels of rows (tid/16) + 16*it, it = 0..3: issue all eight 16-byte loads, then quantize
   uint4 kraw[4], vraw[4];
@@ -163,13 +167,12 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
   for (int it = 0; it < 4; ++it) {
     const int row = (tid >> 4) + 16 * it;
     if (row < lo || row >= hi) continue;           // whole 16-lane rows take the same branch
-    const int64_t t = tv0 + row;
     // ---- keys: row-major codes
     {
       const uint4 raw = kraw[it];
       const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
       if (BK == 16) {
-        *reinterpret_cast<uint4*>(kc + t * 256 + d0 * 2) = raw;
+        *reinterpret_cast<uint4*>(kc + it * (16 * 256) + d0 * 2) = raw;
       } else {
         float x[8];
 #pragma unroll
@@ -177,10 +180,9 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         if (g.rotate_k) rotate8(x, lane16, rot_sign_bits(g.signs_k, lane16));   // whole 16-lane rows are here together
         uint32_t codes[8];
         uint16_t S, Z;
-        const int lpg = g.g_k >> 3;
-        quantize8(x, BK, lpg, codes, &S, &Z);
-        if ((lane16 & (lpg - 1)) == 0) km[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_k)] = (uint32_t)S | ((uint32_t)Z << 16);
-        store_key_codes<BK>(kc + t * (16 * BK), lane16, codes);
+        quantize8(x, BK, lpg_k, codes, &S, &Z);
+        if ((lane16 & (lpg_k - 1)) == 0) km[it * km_step] = (uint32_t)S | ((uint32_t)Z << 16);
+        store_key_codes<BK>(kc + it * (16 * 16 * BK), lane16, codes);
       }
     }
     // ---- values: scale/zero straight to memory, codes to their place in the staged words
@@ -197,9 +199,8 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
         if (g.rotate_v) rotate8(x, lane16, rot_sign_bits(g.signs_v, lane16));
         uint16_t S, Z;
-        const int lpg = g.g_v >> 3;
-        quantize8(x, BV, lpg, codes, &S, &Z);
-        if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
+        quantize8(x, BV, lpg_v, codes, &S, &Z);
+        if ((lane16 & (lpg_v - 1)) == 0) vm[it * vm_step] = (uint32_t)S | ((uint32_t)Z << 16);
       }
       stage_value_row<BV>(vstage, row, d0, codes);
     }
@@ -221,7 +222,7 @@ template <int B> __device__ __forceinline__ void block_fields8(const uint8_t* bl
 // The 8 codes of channels d0 .. d0+7 of value row t (3- and 6-bit codes: low parts from the block's first part, high
 // parts from its second).
 template <int B> __device__ __forceinline__ void value_codes8(const uint8_t* cs, int64_t t, int d0, uint32_t code[8]) {
-  constexpr int LO = key_lo_bits<B>(), HI = key_hi_bits<B>();
+  constexpr int LO = code_lo_bits<B>(), HI = code_hi_bits<B>();
   const uint8_t* blk = cs + (t >> 5) * (int64_t)(512 * B);
   block_fields8<LO>(blk, (int)(t & 31), d0, code);
   if constexpr (HI != 0) {

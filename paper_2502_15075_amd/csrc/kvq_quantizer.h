@@ -33,9 +33,10 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
 // the row is cut into chunks of 32 channels (4 b bytes); with LO = 2 (b = 3) or 4 (b = 6) and HI = b - LO, channel x
 // of a chunk has code mod 2^LO at bits [x LO, (x+1) LO) of the chunk and code >> LO at bits 32 LO + [x HI, (x+1) HI).
 // (The attention kernel multiplies the two runs by the query separately: each is a field width it can unpack with
-// one AND per two codes.)
-template <int B> __host__ __device__ constexpr int key_lo_bits() { return B == 3 ? 2 : B == 6 ? 4 : B; }
-template <int B> __host__ __device__ constexpr int key_hi_bits() { return B - key_lo_bits<B>(); }
+// one AND per two codes.)  Value codes of 3 and 6 bits are split the same way, one level up: a 32-token block is the
+// block of the low parts followed by the block of the high parts.
+template <int B> __host__ __device__ constexpr int code_lo_bits() { return B == 3 ? 2 : B == 6 ? 4 : B; }
+template <int B> __host__ __device__ constexpr int code_hi_bits() { return B - code_lo_bits<B>(); }
 
 // n-bit fields of the 8 codes, first code lowest: bits [shift, shift + N) of every code (MASK: the codes have bits
 // above shift + N; otherwise nothing needs to be cut off)
@@ -63,7 +64,7 @@ template <int NBYTES> __device__ __forceinline__ uint32_t load_bytes(const uint8
 // Store the 8 codes of channels 8*lane16 .. 8*lane16+7 of one key row (rowp: first byte of the row).
 template <int BK>
 __device__ __forceinline__ void store_key_codes(uint8_t* rowp, int lane16, const uint32_t codes[8]) {
-  constexpr int LO = key_lo_bits<BK>(), HI = key_hi_bits<BK>();
+  constexpr int LO = code_lo_bits<BK>(), HI = code_hi_bits<BK>();
   if constexpr (BK == 8) {
     const uint32_t w0 = codes[0] | (codes[1] << 8) | (codes[2] << 16) | (codes[3] << 24);
     const uint32_t w1 = codes[4] | (codes[5] << 8) | (codes[6] << 16) | (codes[7] << 24);
@@ -79,7 +80,7 @@ __device__ __forceinline__ void store_key_codes(uint8_t* rowp, int lane16, const
 
 // The 8 codes of channels 8*oct .. 8*oct+7 of a key row.
 template <int B> __device__ __forceinline__ void load_key_codes(const uint8_t* rowp, int oct, uint32_t code[8]) {
-  constexpr int LO = key_lo_bits<B>(), HI = key_hi_bits<B>();
+  constexpr int LO = code_lo_bits<B>(), HI = code_hi_bits<B>();
   if constexpr (B == 16) {
     const uint4 w = *reinterpret_cast<const uint4*>(rowp + oct * 16);
     const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
