@@ -15,9 +15,8 @@ namespace {
 constexpr int kSpan = 64;                // tokens one workgroup covers (two 32-token value blocks)
 
 // LDS staging of the value codes of one span, already in storage order: one element per code, the F = 32/b_V codes
-// of an output word adjacent (so a word is assembled from one wide LDS read), 16 bytes of padding after every 256
-// to spread the strided writes of the quantizing lanes over the banks.
-__device__ __forceinline__ int stage_phys(int a) { return a + ((a >> 8) << 4); }
+// of an output word adjacent (so a word is assembled from one wide LDS read).  (Padding the area against the bank
+// conflicts of the strided byte writes was measured: its address arithmetic costs more than the conflicts, 3 %.)
 
 // Pack the codes held one per byte in w (first code in the lowest byte) into adjacent b-bit fields.
 // (Bytes of tokens that were not staged hold garbage: they are masked to b bits so that they stay inside their field.)
@@ -43,7 +42,7 @@ __device__ __forceinline__ void stage_value_codes(uint8_t* vstage, int row, int 
   const int a0 = (word0 * F + x * P + p) * ES;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const int a = stage_phys(a0 + e * LW * F * ES);
+    const int a = a0 + e * LW * F * ES;
     if (BV == 16) *reinterpret_cast<uint16_t*>(vstage + a) = (uint16_t)codes[e];
     else vstage[a] = (uint8_t)codes[e];
   }
@@ -58,7 +57,7 @@ __device__ __forceinline__ void store_value_words(uint32_t* vcp, const uint8_t* 
   const bool full = lo == 0 && hi == kSpan;
   for (int w = tid; w < 256 * BV; w += 256) {
     uint32_t* vc = vcp + (w / (128 * BV)) * (BW - 128 * BV);      // vc[w]: the word's place in the plane
-    const uint8_t* sp = vstage + stage_phys(w * F * ES);
+    const uint8_t* sp = vstage + w * F * ES;
     uint32_t bits;
     if (BV == 1) {
       const uint4 r0 = *reinterpret_cast<const uint4*>(sp), r1 = *reinterpret_cast<const uint4*>(sp + 16);
@@ -97,7 +96,7 @@ __device__ __forceinline__ void store_value_words(uint32_t* vcp, const uint8_t* 
 
 // Bytes of LDS that stage the codes of one span: one staging area per part of a code (3- and 6-bit value codes are a
 // low part and a high part, each packed into a block of its own).
-template <int BV> constexpr int stage_area() { return kSpan * kHeadDim * (BV == 16 ? 2 : 1) * 17 / 16; }
+template <int BV> constexpr int stage_area() { return kSpan * kHeadDim * (BV == 16 ? 2 : 1); }
 template <int BV> constexpr int stage_total() { return stage_area<BV>() * (code_hi_bits<BV>() ? 2 : 1); }
 
 template <int BV>
