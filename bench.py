@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the K4V2 decode hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--workload llama70b|llama8b|sweep|groups|rotation|channelwise|stream131k]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layers L] [--workload llama70b|llama8b|sweep|widths|groups|rotation|channelwise|stream131k]
 
 One step = one pass of the whole hot path over one layer's batch: quantize-and-append the new
 token's K/V (B x H_kv rows) into the packed cache, then single-token decode attention over the
@@ -97,6 +97,37 @@ def run_sweep(args, kvq, synth) -> int:
                               "GB_s_cold": round(kv_bytes / ms / 1e6, 1), "us_cold": round(ms * 1e3, 2),
                               "GB_s_same_cache": round(kv_bytes / ms_hot / 1e6, 1),
                               "err_vs_exact_attention_mean_rel_l2": round(rel_l2, 5), "err_max_rel": round(rel_max, 5)}), flush=True)
+            del caches
+    return 0
+
+
+def run_widths(args, kvq, synth) -> int:
+    """Every allocation (b_K, b_V) in {1,2,3,4,6,8}^2 on the Llama-3-70B layer shape (B=32, H_q=64, H_kv=8, D=128, T=32768,
+    bf16, 64-channel groups): time of the fused decode step (append of the new token + attention) over four rotating
+    caches (2.3 to 7.5 GB, more than the last-level cache) and the packed bytes it has to read.  The caches are
+    quantized from seeded synthetic tensors, one 4096-token chunk generated at a time."""
+    B, Hq, Hkv, D, G, T = 32, 64, 8, 128, 64, 32768
+    scale = 1.0 / math.sqrt(D)
+    q = torch.randn(B, Hq, D, device="cuda").to(torch.bfloat16)
+    k1 = torch.randn(B, Hkv, D, device="cuda").to(torch.bfloat16)
+    v1 = torch.randn(B, Hkv, D, device="cuda").to(torch.bfloat16)
+    out = torch.empty(B, Hq, D, dtype=torch.float32, device="cuda")
+    chunks = [synth.make_kvq(11 + i, B, Hkv, Hq, 4096, D, dtype=torch.bfloat16, device="cuda")[:2] for i in range(2)]
+    for bk in (1, 2, 3, 4, 6, 8):
+        for bv in (1, 2, 3, 4, 6, 8):
+            L = kvq.Layout(B, Hkv, T, D, bk, bv, G, G, raw_dtype=kvq.KVQ_BF16)
+            kv_bytes = B * Hkv * T * (16 * bk + 16 * bv + 2 * (D // G) * 4)
+            caches = [kvq.Cache(L, device="cuda") for _ in range(4)]
+            for ci, c in enumerate(caches):
+                for t0 in range(0, T, 4096):
+                    K, V = chunks[(ci + t0 // 4096) % 2]
+                    kvq.quantize_append(L, c, K, V, t0)
+            ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, Hq, T)), dtype=torch.uint8, device="cuda")
+            ms = _time_loop(lambda i: kvq.decode_step(L, caches[i % 4], k1, v1, T - 1, q, scale, out, ws), 1500, 300)
+            print(json.dumps({"workload": f"configs[3]: 70B layer, B=32, T={T}, K{bk}V{bv} G=64", "alloc": f"K{bk}V{bv}",
+                              "bytes_per_row": kv_bytes // (B * Hkv * T), "kv_bytes": kv_bytes,
+                              "decode_step_us": round(ms * 1e3, 1), "GB_s": round(kv_bytes / ms / 1e6, 1),
+                              "pct_of_hbm_peak": round(kv_bytes / ms / 1e6 / 80.0, 1)}), flush=True)
             del caches
     return 0
 
@@ -287,7 +318,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=4000)
     ap.add_argument("--warmup", type=int, default=400)
     ap.add_argument("--layers", type=int, default=80, help="resident layer caches taken in turn")
-    ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS) + ["sweep", "groups", "rotation", "channelwise", "stream131k"],
+    ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS) + ["sweep", "widths", "groups", "rotation", "channelwise", "stream131k"],
                     help="llama70b (default, the headline line) / llama8b: one JSON line; sweep: bit-allocation sweep on the 8B "
                          "layer (one line per allocation and context); stream131k: chunked fill + growing-cache decode at 131072")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -308,6 +339,8 @@ def main() -> int:
     dev = "cuda"
     if args.workload == "sweep":
         return run_sweep(args, kvq, synth)
+    if args.workload == "widths":
+        return run_widths(args, kvq, synth)
     if args.workload == "groups":
         return run_groups(args, kvq, synth)
     if args.workload == "rotation":
