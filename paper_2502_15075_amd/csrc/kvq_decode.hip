@@ -161,9 +161,18 @@ template <int BV> __device__ __forceinline__ constexpr int v_slot_shift(int v) {
 template <int BV> __device__ __forceinline__ constexpr float v_hi_factor(int v) {
   return (float)(1 << (v_lo<BV>() + field_slot_shift<v_lo<BV>()>(v))) / (float)(1 << field_slot_shift<(v_hi<BV>() ? v_hi<BV>() : 1)>(v));
 }
-// Softmax weights are carried times 2^p_shift: 2^10 leaves binary16 headroom for weight x value scale up to 64; the
-// high part's weights are up to 2^LO larger, and the scale of a 1-bit group is its whole range (2^8: up to 255).
-template <int BV> constexpr float p_shift() { return BV == 1 ? 8.0f : 10.0f - (float)(v_hi<BV>() ? v_lo<BV>() : 0); }
+// Softmax weights are carried times 2^p_shift and divided by 2^shift of their slot: the largest of them is 2^10 (binary16
+// headroom for weight x value scale up to 64), so p_shift is 10 plus the smallest slot shift, where the high part's
+// slots count with their shift minus LO (their weights carry 2^LO).  The scale of a 1-bit group is its whole range:
+// two bits more headroom (scale up to 255).
+template <int BV> constexpr float p_shift() {
+  int m = field_slot_shift<v_lo<BV>()>(0);
+  if (v_hi<BV>()) {
+    const int h = field_slot_shift<(v_hi<BV>() ? v_hi<BV>() : 1)>(0) - v_lo<BV>();
+    m = h < m ? h : m;
+  }
+  return (float)(10 + m - (BV == 1 ? 2 : 0));
+}
 template <int BV> __device__ __forceinline__ u32x4 unpack_v(const uint32_t* w, int dt) {
   u32x4 a;
   if (BV == 16) {
@@ -193,13 +202,15 @@ template <int BV> __device__ __forceinline__ u32x4 unpack_v(const uint32_t* w, i
 
 // Ring depth per instantiation: a step costs 2 b_K + 2 b_V + 4 registers per lane (and the scheduler wants room to
 // start a refill before the old contents are dead); deeper rings for the narrow formats, two steps for the wide ones.
-template <int BK, int BV, int NCK = 1, int NCV = 1>
+template <int BK, int BV, int NCK = 1, int NCV = 1, bool ROTV = false>
 constexpr int ring_stages() {
   constexpr int regs = 2 * BK + 2 * BV + 4;
   constexpr int base = regs <= 16 ? KVQ_STAGES : regs <= 20 ? 3 : 2;
   constexpr int less = (NCK == 2 ? 2 : 0) + (NCV == 2 ? 1 : 0)    // a second column set costs registers (query operand,
                        + (code_hi_bits<BK>() ? 1 : 0)              // scale/zero entries, weights), so does a high run
                        + (code_hi_bits<BV>() ? 1 : 0)              // of keys or a high part of values (its weights)
+                       + (ROTV && code_hi_bits<BK>() && BV == 8 ? 1 : 0)   // (rotated values: the unrounded weights stay
+                                                                           // live; two runs of keys, the widest values)
                        + (BK == 2 && regs >= 16 ? 1 : 0);         // (moved 2-bit fields: two shifted copies of a word live)
   return base - less >= 1 ? base - less : 1;
 }
@@ -223,7 +234,10 @@ struct LaneCtx {
                                           // wavefront's LDS copy of a step's scale/zero bytes
   uint8_t* meta_lds;                      // that LDS copy (1 KB per wavefront)
   int lane, c, j, gk, gv, ngk, ngv;
+  static constexpr bool kRotV = false;
 };
+// Kernels for caches whose values are stored rotated (the output goes through R_v^T) mark their context so.
+struct LaneCtxRotV : LaneCtx { static constexpr bool kRotV = true; };
 
 // Cache bytes are read exactly once per decode step: streaming (non-temporal) loads.
 __device__ __forceinline__ u32x4 ld16(const uint8_t* p) {
@@ -303,12 +317,19 @@ struct WaveState {
 };
 
 // binary16 product of a binary32 weight and the binary16 held in the low half of `meta`, written to the
-// low / high half of `dst` (one rounding).
+// low / high half of `dst` (one rounding: the compiler turns the fused multiply-add with a converted operand and the
+// conversion of its result into one v_fma_mixlo/mixhi_f16).  Written in C and not as inline assembly on purpose: the
+// weight comes straight from v_exp_f32, and the result of a transcendental instruction may not be read by the next
+// vector instruction; the compiler keeps that distance for the instructions it emits itself, not for assembly text.
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void mix_lo(uint32_t& dst, float p, uint32_t meta) {
-  asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "=v"(dst) : "v"(p), "v"(meta));
+  const half2v r = {(_Float16)fmaf(p, meta_scale(meta), 0.0f), (_Float16)0.0f};
+  dst = __builtin_bit_cast(uint32_t, r);
 }
 __device__ __forceinline__ void mix_hi(uint32_t& dst, float p, uint32_t meta) {
-  asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "+v"(dst) : "v"(p), "v"(meta));
+  half2v r = __builtin_bit_cast(half2v, dst);
+  r.y = (_Float16)fmaf(p, meta_scale(meta), 0.0f);
+  dst = __builtin_bit_cast(uint32_t, r);
 }
 
 // Round-to-nearest-even bfloat16 pattern of a finite binary32.
@@ -443,10 +464,11 @@ __device__ __forceinline__ void kseq_rebuild_runs(KS& ks, const LaneCtx& L, cons
 // (8 heads with 32-channel groups) the groups are spread over two column sets: set cs carries group grp + cs*(16/R).
 // KS: KSeqState for channel-wise keys (then NEWBLK marks the first step of a 64-token block: the query operands are
 // rebuilt from that block's scale/zero entries), NoKSeq otherwise.
-template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool MASKED, bool NEWBLK = false, typename KS = NoKSeq>
+template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool MASKED, bool NEWBLK = false, typename KS = NoKSeq,
+          typename LC = LaneCtx>
 __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u32x4 (&qb)[NCK][4],
                                              const u32x4 (&qbh)[NCK][4], const float (&qsum_u)[NCK],
-                                             float kappa, WaveState<NCV>& st, const LaneCtx& L, int step, int seq_len,
+                                             float kappa, WaveState<NCV>& st, const LC& L, int step, int seq_len,
                                              KS& ks, const float* qrow = nullptr, float kseq_low = 0.f) {
   constexpr bool RAW = BK == 16;
   constexpr int KLO = k_lo<BK>(), KHI = k_hi<BK>();   // qbh: the query operand of the high run (3- and 6-bit keys)
@@ -547,11 +569,14 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
   constexpr int VLO = v_lo<BV>(), VHI = v_hi<BV>();
   uint32_t pw[NCV][4], pl[4];                    // pl: low-order bfloat16 part of the weights (bfloat16 cache only)
   uint32_t pwh[NCV][4];                          // weights of the high parts of 3- and 6-bit value codes
+  constexpr bool ROTV = !RAW && !KSEQ && LC::kRotV;   // (rotation is not combined with channel-wise keys)
+  float pv[ROTV ? 8 : 1];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int v = i >> 1;
     float p = __builtin_amdgcn_exp2f(fmaf(s[i], kappa, st.noff[v]));
     if (MASKED && !valid[i]) p = 0.f;
+    if constexpr (ROTV) pv[i] = p;
     st.l[v] += p;
     if constexpr (!RAW) {
 #pragma unroll
@@ -572,6 +597,31 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
       const uint32_t hi = bf16_rne(p);
       const uint32_t lo = bf16_rne(p - __uint_as_float(hi << 16));
       if (i & 1) { pw[0][v] |= hi << 16; pl[v] |= lo << 16; } else { pw[0][v] = hi; pl[v] = lo; }
+    }
+  }
+  if constexpr (ROTV) {
+    // Rotated values: the rounding error of a token's binary16 weight multiplies all of its group's codes alike, and
+    // R_v^T gathers what is common to the channels into single output channels (times sqrt(D) for one group per row),
+    // while the zero-point term beside it is summed with the unrounded weight.  What the rounding took from the weight
+    // is therefore given back at the middle of the code range, through the zero-point sum: the error left is the
+    // rounding error times the codes' distance from the middle, which has no common part to gather.
+    constexpr float kMidLo = 0.5f * (float)((1 << VLO) - 1);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int v = i >> 1;
+#pragma unroll
+      for (int cs = 0; cs < NCV; ++cs) {
+        uint32_t vm = vmeta[cs][i];
+        if (MASKED && !valid[i]) vm = 0u;
+        const float back = (float)__builtin_bit_cast(_Float16, (uint16_t)((i & 1) ? pw[cs][v] >> 16 : pw[cs][v] & 0xFFFFu));
+        st.zacc[cs][v] = fmaf(kMidLo, fmaf(pv[i], meta_scale(vm), -back), st.zacc[cs][v]);
+        if constexpr (VHI != 0) {
+          constexpr float kMidHi = 0.5f * (float)((1 << VHI) - 1) * (float)(1 << VLO);
+          const float f = v_hi_factor<BV>(v);
+          const float backh = (float)__builtin_bit_cast(_Float16, (uint16_t)((i & 1) ? pwh[cs][v] >> 16 : pwh[cs][v] & 0xFFFFu));
+          st.zacc[cs][v] = fmaf(kMidHi / f, fmaf(pv[i] * f, meta_scale(vm), -backh), st.zacc[cs][v]);
+        }
+      }
     }
   }
 #pragma unroll
@@ -685,12 +735,13 @@ __device__ __forceinline__ void store_unrotated_row(const float* row, int lane16
 // KSEQ: channel-wise keys (the caller passes the flushed part of the sequence: seq_len is a multiple of 64, nothing
 // is appended); a wavefront then walks whole 64-token blocks (pairs of steps), rebuilding its query operands per block.
 // PAGED: the planes are pools of pages; a step's data is found through this sequence's row of the page table.
-template <int BK, int BV, int R, int NW, bool BF, int NCK, int NCV, bool KSEQ = false, bool PAGED = false>
+// ROTV: the values are stored rotated (quantized caches with token-wise keys; compute_step then corrects its weights).
+template <int BK, int BV, int R, int NW, bool BF, int NCK, int NCV, bool KSEQ = false, bool PAGED = false, bool ROTV = false>
 __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(const DecodeArgs a) {
   constexpr int kSetGroups = 16 / R;             // groups per column set
   constexpr bool RAW = BK == 16;
   static_assert(!KSEQ || (!RAW && NCK == 1), "channel-wise keys: quantized, one key column per head");
-  constexpr int kRing = ring_stages<BK, BV, NCK, NCV>();
+  constexpr int kRing = ring_stages<BK, BV, NCK, NCV, ROTV>();
 #ifndef KVQ_KSEQ_STAGES
 #define KVQ_KSEQ_STAGES 2
 #endif
@@ -729,7 +780,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
     seq_len = min(n, a.seq_len);
   }
 
-  LaneCtx L;
+  std::conditional_t<ROTV, LaneCtxRotV, LaneCtx> L;
   L.lane = lane; L.c = lane & 15; L.j = lane >> 4;
   L.ngk = g.ng_k; L.ngv = g.ng_v;
   const int h = L.c % R, grp = L.c / R;
@@ -1083,6 +1134,15 @@ inline RotV rot_v_of(const Geom& g) {
 
 template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool KSEQ, bool PAGED>
 void launch_nw(const DecodeArgs& a, const DecodePlan& plan, dim3 grid, hipStream_t stream) {
+  if constexpr (BK != 16 && !KSEQ) {
+    if (a.g.rotate_v) {
+      if (plan.waves_per_wg == 8)
+        hipLaunchKernelGGL((decode_kernel<BK, BV, R, 8, BF, NCK, NCV, KSEQ, PAGED, true>), grid, dim3(512), 0, stream, a);
+      else
+        hipLaunchKernelGGL((decode_kernel<BK, BV, R, 4, BF, NCK, NCV, KSEQ, PAGED, true>), grid, dim3(256), 0, stream, a);
+      return;
+    }
+  }
   if (plan.waves_per_wg == 8)
     hipLaunchKernelGGL((decode_kernel<BK, BV, R, 8, BF, NCK, NCV, KSEQ, PAGED>), grid, dim3(512), 0, stream, a);
   else

@@ -200,3 +200,20 @@ def test_product_path_never_touches_the_oracle():
         assert not pat.search(open(os.path.join(ROOT, rel)).read()), rel
     for f in os.listdir(os.path.join(ROOT, "paper_2502_15075_amd", "csrc")):
         assert not pat.search(open(os.path.join(ROOT, "paper_2502_15075_amd", "csrc", f)).read()), f
+
+
+def test_inline_assembly_stays_away_from_transcendental_results():
+    """The compiler keeps the wait state between a transcendental instruction and a reader of its result only for
+    instructions it emits itself.  The decode kernels, whose softmax weights come straight from v_exp_f32, therefore
+    carry no instruction in inline assembly at all, and the assembly of the quantizer is limited to the minimum /
+    maximum instructions (their operands are converted inputs and lane permutes, never a reciprocal or exponential)."""
+    csrc = os.path.join(ROOT, "paper_2502_15075_amd", "csrc")
+    texts = {}
+    for name in sorted(os.listdir(csrc)):
+        src = open(os.path.join(csrc, name)).read()
+        texts[name] = [m for m in re.findall(r'\basm\s*(?:volatile)?\s*\(\s*"([^"]*)"', src) if m.strip()]
+    assert texts["kvq_decode.hip"] == [] and texts["kvq_api.hip"] == []
+    allowed = ("v_min3_f32", "v_max3_f32", "v_min_f32", "v_max_f32")
+    for name, found in texts.items():
+        for text in found:
+            assert text.split()[0] in allowed, (name, text)

@@ -1257,7 +1257,29 @@ def test_random_token_wise_configurations(kvq, oracle, case):
     """Seeded random layouts (all widths, group sizes, head ratios 1..8, rotations, both input types), ragged chunked
     appends, attention at the full and at a shorter length, per-sequence lengths, two fused steps: planes byte-identical,
     outputs within tolerance."""
-    c = _random_case(np.random.default_rng(4242 + case))
+    _run_token_wise_case(kvq, oracle, _random_case(np.random.default_rng(4242 + case)))
+
+
+# Rotated values with one group per row and few tokens: the rounding of a token's binary16 weight is common to all 128
+# codes of its row, and taking the output back with R_v^T gathers a common part into one channel, sqrt(128) times larger.
+# (Configurations that a wider random search found beyond the tolerance before the kernel gave the rounded-off part of
+# the weight back through the zero-point sum.)
+ROTATED_VALUE_CASES = [
+    dict(bk=6, bv=2, gk=64, gv=128, r=6, B=3, H=2, T=55, bf16=False, rot=1, rotv=1, seed=498434549),
+    dict(bk=2, bv=3, gk=64, gv=128, r=7, B=1, H=2, T=176, bf16=True, rot=0, rotv=1, seed=506620730),
+    dict(bk=8, bv=6, gk=64, gv=128, r=8, B=1, H=3, T=258, bf16=False, rot=1, rotv=1, seed=1019904077),
+    dict(bk=8, bv=4, gk=32, gv=128, r=8, B=3, H=2, T=238, bf16=False, rot=0, rotv=1, seed=980738354),
+    dict(bk=4, bv=1, gk=64, gv=128, r=8, B=2, H=2, T=97, bf16=False, rot=0, rotv=1, seed=31),
+    dict(bk=4, bv=8, gk=64, gv=64, r=4, B=2, H=2, T=130, bf16=True, rot=1, rotv=1, seed=32),
+]
+
+
+@pytest.mark.parametrize("case", range(len(ROTATED_VALUE_CASES)))
+def test_rotated_values_with_wide_groups(kvq, oracle, case):
+    _run_token_wise_case(kvq, oracle, ROTATED_VALUE_CASES[case])
+
+
+def _run_token_wise_case(kvq, oracle, c):
     B, H, r, T = c["B"], c["H"], c["r"], c["T"]
     dtype = torch.bfloat16 if c["bf16"] else torch.float16
     K, V, q = synth.make_kvq(c["seed"], B, H, H * r, T + 2, dtype=dtype)
