@@ -1030,14 +1030,15 @@ def test_three_and_six_bit_values_attention(kvq, oracle, R, bk, bv, gk, gv):
 
 # --------------------------------------------------------------------------- paged planes
 
-def _paged_setup(kvq, oracle, B, H, T, bk, bv, gk, gv, P, seed, raw=0, extra_pages=3):
+def _paged_setup(kvq, oracle, B, H, T, bk, bv, gk, gv, P, seed, raw=0, extra_pages=3, rot=0, rotv=0):
     """A pool with a shuffled page table (a few pages left unused) and the oracle's contiguous twin of the same capacity."""
     pps = -(-T // P)
     n_pages = B * pps + extra_pages
     rng = np.random.default_rng(seed)
     table = rng.permutation(n_pages)[:B * pps].reshape(B, pps).astype(np.int32)
-    Lg = kvq.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw, page_tokens=P, n_pages=n_pages)
-    Lo = oracle.Layout(B, H, pps * P, 128, bk, bv, gk, gv, raw_dtype=raw)
+    rotation = dict(rotate_k=rot, signs_k=SIGNS if rot else (0, 0, 0, 0), rotate_v=rotv, signs_v=SIGNS_V if rotv else (0, 0, 0, 0))
+    Lg = kvq.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw, page_tokens=P, n_pages=n_pages, **rotation)
+    Lo = oracle.Layout(B, H, pps * P, 128, bk, bv, gk, gv, raw_dtype=raw, **rotation)
     cache = kvq.Cache(Lg, fill=0xA5)
     cache.page_table = torch.from_numpy(table).cuda()
     assert [0 if p is None else p.numel() for p in cache.planes[:4]] == oracle.paged_plane_bytes(Lo, P, n_pages)
@@ -1193,6 +1194,42 @@ def test_paged_attention(kvq, oracle, R, bk, bv, gk, gv, P):
         oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, pos:pos + 1])),
                                np.ascontiguousarray(synth.to_numpy_bits(V[:, :, pos:pos + 1])), pos, bf16=True)
         ref = oracle.decode_attention(Lo, planes, qn, pos + 1, 1 / math.sqrt(128), bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
+    _assert_paged_equal(oracle, Lo, cache, planes, table, P, n_pages)
+
+
+@pytest.mark.parametrize("R,bk,bv,gk,gv,P,rot,rotv", [(8, 4, 2, 64, 64, 64, 1, 1), (4, 8, 4, 32, 128, 128, 0, 1), (8, 3, 6, 64, 128, 256, 1, 1),
+                                                      (2, 2, 1, 64, 64, 64, 0, 1), (8, 4, 8, 32, 32, 64, 1, 0), (7, 6, 3, 64, 128, 128, 0, 1)])
+def test_paged_rotated_attention(kvq, oracle, R, bk, bv, gk, gv, P, rot, rotv):
+    """Rotated keys and / or values in paged planes: attention at several lengths (one and several sequence splits,
+    ragged tails), per-sequence lengths, and fused steps across a page boundary."""
+    B, H, T0 = 2, 2, 1000
+    T = T0 + 40
+    K, V, q = synth.make_kvq(330 + R, B, H, H * R, T, dtype=torch.float16)
+    Lg, Lo, cache, planes, table, n_pages = _paged_setup(kvq, oracle, B, H, T, bk, bv, gk, gv, P, seed=R, rot=rot, rotv=rotv)
+    Kd, Vd = K.cuda(), V.cuda()
+    kvq.quantize_append(Lg, cache, Kd[:, :, :T0], Vd[:, :, :T0], 0)
+    oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, :T0])),
+                           np.ascontiguousarray(synth.to_numpy_bits(V[:, :, :T0])), 0)
+    _assert_paged_equal(oracle, Lo, cache, planes, table, P, n_pages)
+    scale = 1 / math.sqrt(128)
+    for seq_len in (T0, 238, 79, 32, 13):
+        out = _decode(kvq, Lg, cache, q, seq_len)
+        ref = oracle.decode_attention(Lo, planes, q.numpy(), seq_len, scale)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, seq_len
+    lens = [T0, 77]
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, T0)), dtype=torch.uint8, device="cuda")
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    kvq.decode_attention_varlen(Lg, cache, q.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"), T0, scale, out, ws)
+    torch.cuda.synchronize()
+    assert _rel_err(out.cpu().numpy(), oracle.decode_attention_varlen(Lo, planes, q.numpy(), lens, scale)) < TOL
+    for pos in range(T0, T):
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), scale, out, ws)
+        torch.cuda.synchronize()
+        oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, pos:pos + 1])),
+                               np.ascontiguousarray(synth.to_numpy_bits(V[:, :, pos:pos + 1])), pos)
+        ref = oracle.decode_attention(Lo, planes, q.numpy(), pos + 1, scale)
         assert _rel_err(out.cpu().numpy(), ref) < TOL, pos
     _assert_paged_equal(oracle, Lo, cache, planes, table, P, n_pages)
 
