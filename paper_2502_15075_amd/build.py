@@ -24,10 +24,11 @@ DECODE_PAIRS = [(4, 2), (2, 4), (4, 4), (8, 8), (2, 2), (8, 4), (8, 2), (4, 8), 
                 (3, 2), (3, 4), (3, 8), (6, 2), (6, 4), (6, 8), (1, 2), (1, 4), (1, 8),
                 (1, 1), (2, 1), (3, 1), (4, 1), (6, 1), (8, 1),
                 (1, 3), (2, 3), (3, 3), (4, 3), (6, 3), (8, 3), (1, 6), (2, 6), (3, 6), (4, 6), (6, 6), (8, 6)]
-# Bytes of scratch memory per lane an instance may use.  The channel-wise kernels of 3-bit keys beside 8-bit values in two
-# value column sets (8 heads per KV head, 32-channel value groups) sit at the 256-register limit with a ring of one step
-# already and keep three registers in scratch; they are bound by their vector instructions, not by their loads.
-SCRATCH_ALLOWED = {"kvq_decode_k3v8.o": 16}
+# Bytes of scratch memory per lane an instance may use.  The channel-wise kernels of 3- and 6-bit keys (two runs, a query
+# operand each) beside 6- or 8-bit values in two value column sets (8 heads per KV head, 32-channel value groups) sit at
+# the 256-register limit with a ring of one step already and keep three registers in scratch; they are bound by their
+# vector instructions, not by their loads.
+SCRATCH_ALLOWED = {f"kvq_decode_k{bk}v{bv}.o": 16 for bk in (3, 6) for bv in (6, 8)}
 # (source, object name, extra flags).  The quantizer must round every operation once: no contraction.
 UNITS = [("kvq_api.hip", "kvq_api.o", []),
          ("kvq_quant.hip", "kvq_quant.o", ["-ffp-contract=off"]),
@@ -56,13 +57,17 @@ def build_lib(verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=8) as ex:
         results = list(ex.map(_compile, UNITS))
-    objs = []
+    objs, failed = [], []
     for src, rc, log, obj in results:
         if verbose and log.strip():
             print(f"--- {src}\n{log}", file=sys.stderr)
         if rc != 0:
-            raise RuntimeError(f"hipcc failed on {src}:\n{log}")
+            failed.append(f"{src}:\n{log}")
         objs.append(obj)
+    if failed:                                     # every failing unit is named, and the library of an earlier build goes:
+        if os.path.exists(LIB):                    # nothing may load a library that the sources no longer produce
+            os.remove(LIB)
+        raise RuntimeError("hipcc failed on " + "\n".join(failed))
     r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}{r.stderr}")
