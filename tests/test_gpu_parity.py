@@ -1351,6 +1351,40 @@ def _run_token_wise_case(kvq, oracle, c):
         assert _rel_err(out.cpu().numpy(), ref) < TOL, (c, pos)
 
 
+@pytest.mark.parametrize("bk,bv", [(3, 8), (6, 8), (3, 6), (6, 6)])
+def test_channelwise_two_run_keys_with_wide_values_in_two_column_sets(kvq, oracle, bk, bv):
+    """8 heads per KV head and 32-channel value groups (two value column sets) over channel-wise keys of 3 and 6 bits
+    beside 6- and 8-bit values: the kernel instances with the highest register pressure (the only ones allowed to keep
+    registers in scratch memory).  Flushed blocks plus tail, then fused steps across a flush."""
+    B, H, r, T = 2, 2, 8, 250
+    cap = T + 8
+    K, V, q = synth.make_kvq(7100 + 10 * bk + bv, B, H, H * r, cap, dtype=torch.float16)
+    Lg, Lo = _seq_layouts(kvq, oracle, B, H, cap, bk, bv, 32, raw=0)
+    cache = kvq.Cache(Lg, fill=0x5A)
+    planes = oracle.new_seq_planes(Lo, fill=0x5A)
+    Kd, Vd = K.cuda(), V.cuda()
+
+    def check_planes():
+        torch.cuda.synchronize()
+        for name, g, o in zip(("k_codes", "k_meta", "v_codes", "v_meta", "k_resid", "v_resid"), cache.planes, planes):
+            bad = np.flatnonzero(g.cpu().numpy() != o)
+            assert bad.size == 0, f"{name}: {bad.size} bytes differ, first at {bad[:5]}"
+
+    kvq.quantize_append(Lg, cache, Kd[:, :, :T], Vd[:, :, :T], 0)
+    oracle.seq_append(Lo, planes, np.ascontiguousarray(K[:, :, :T].numpy()), np.ascontiguousarray(V[:, :, :T].numpy()), 0)
+    check_planes()
+    scale = 1 / math.sqrt(128)
+    out = _decode(kvq, Lg, cache, q, T)
+    assert _rel_err(out.cpu().numpy(), oracle.seq_decode_attention(Lo, planes, q.numpy(), T, scale)) < TOL
+    outs = torch.empty(B, H * r, 128, dtype=torch.float32, device="cuda")
+    for pos in range(T, cap):
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * r, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), scale, outs, ws)
+        oracle.seq_append(Lo, planes, np.ascontiguousarray(K[:, :, pos:pos + 1].numpy()), np.ascontiguousarray(V[:, :, pos:pos + 1].numpy()), pos)
+        check_planes()
+        assert _rel_err(outs.cpu().numpy(), oracle.seq_decode_attention(Lo, planes, q.numpy(), pos + 1, scale)) < TOL, pos
+
+
 @pytest.mark.parametrize("case", range(24))
 def test_random_channelwise_configurations(kvq, oracle, case):
     """Seeded random channel-wise caches (every width for keys and values, value group sizes, head ratios, contiguous or paged, both
