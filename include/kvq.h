@@ -103,7 +103,9 @@ typedef enum {
   KVQ_ERR_UNSUPPORTED = 2, /* a valid request this build has no kernel for (head_dim != 128, axis) */
   KVQ_ERR_CAPACITY = 3,    /* pos + n_new > max_seq, seq_len > max_seq */
   KVQ_ERR_WORKSPACE = 4,   /* workspace smaller than kvq_decode_workspace_bytes */
-  KVQ_ERR_DEVICE = 5       /* the HIP runtime reported an error at launch */
+  KVQ_ERR_DEVICE = 5,      /* the HIP runtime reported an error at launch */
+  KVQ_ERR_STATIC_SCRATCH = 6 /* kvq_decode_attention_static only: the call needs more partial-record bytes than
+                                KVQ_STATIC_SCRATCH_BYTES; use kvq_decode_attention with a workspace of the caller's */
 } kvq_status;
 
 typedef enum { KVQ_F16 = 0, KVQ_BF16 = 1, KVQ_F32 = 2 } kvq_dtype;
@@ -177,6 +179,22 @@ kvq_status kvq_decode_attention(const kvq_layout* layout, const kvq_cache* cache
                                 kvq_dtype q_dtype, int32_t q_heads, int32_t seq_len, float softmax_scale,
                                 void* out, kvq_dtype out_dtype, void* workspace, size_t workspace_bytes,
                                 void* stream);
+
+/* kvq_decode_attention for callers that cannot allocate device memory and so have no workspace to pass: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same arguments and the same
+ * results bit for bit, but the partial (max, sum, accumulator) records of a split sequence go to an array of
+ * KVQ_STATIC_SCRATCH_BYTES that is part of the library's device code (every GPU the library runs on holds its own copy
+ * until the process ends; the array's device address is looked up once per device, on the first call with that device
+ * current).  The call allocates nothing, frees nothing and calls no allocating routine.
+ *   - a call that needs more than KVQ_STATIC_SCRATCH_BYTES of records (kvq_decode_workspace_bytes tells) returns
+ *     KVQ_ERR_STATIC_SCRATCH and launches nothing;
+ *   - every call on one GPU shares that GPU's array, whatever its stream: calls that can overlap in time on one GPU
+ *     race on it (calls on one stream, or ordered by events, do not).  The array keeps the last call's records; nothing
+ *     in it has to start at zero, because every record a call reads is one that the same call wrote. */
+#define KVQ_STATIC_SCRATCH_BYTES ((size_t)4 << 20)
+kvq_status kvq_decode_attention_static(const kvq_layout* layout, const kvq_cache* cache, const void* q,
+                                       kvq_dtype q_dtype, int32_t q_heads, int32_t seq_len, float softmax_scale,
+                                       void* out, kvq_dtype out_dtype, void* stream);
 
 /* One autoregressive decode step in a single launch (Sec. 4: the cache grows by one quantized token per generated
  * token): quantize the new token's K/V row of every (b, h_kv) into position pos -- same bytes as

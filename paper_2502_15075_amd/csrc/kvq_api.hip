@@ -1,6 +1,8 @@
 // C ABI of libkvq: argument validation on the host, then one launcher call per entry point.
 #include "kvq_internal.h"
 
+#include <atomic>
+
 namespace {
 
 bool bits_ok(int b) { return b == 1 || b == 2 || b == 3 || b == 4 || b == 6 || b == 8 || b == 16; }
@@ -170,6 +172,50 @@ kvq_status kvq_decode_attention(const kvq_layout* layout, const kvq_cache* cache
                        workspace_bytes, nullptr, stream);
 }
 
+}  // extern "C"
+
+// ---- the entry point that allocates nothing: its partial records live in an array of the device code -----------------
+namespace {
+// One copy per GPU, held until the process ends.  In host code this name is only a handle for hipGetSymbolAddress: the
+// kernels get the device address that call returns, never the name.
+static __device__ __align__(256) unsigned char scratch[KVQ_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU (null: not looked up yet)
+
+// The address of this GPU's copy of `scratch` (the current device's), looked up once per device.
+hipError_t static_scratch(void** ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // (two threads racing here store the same address)
+  }
+  *ptr = p;
+  return hipSuccess;
+}
+}  // namespace
+
+extern "C" {
+
+kvq_status kvq_decode_attention_static(const kvq_layout* layout, const kvq_cache* cache, const void* q, kvq_dtype q_dtype,
+                                       int32_t q_heads, int32_t seq_len, float softmax_scale, void* out,
+                                       kvq_dtype out_dtype, void* stream) {
+  size_t need = 0;
+  kvq_status st = kvq_decode_workspace_bytes(layout, q_heads, seq_len, &need);
+  if (st != KVQ_OK) return st;
+  if (need > KVQ_STATIC_SCRATCH_BYTES) return KVQ_ERR_STATIC_SCRATCH;
+  void* ws = nullptr;
+  if (need && static_scratch(&ws) != hipSuccess) return KVQ_ERR_DEVICE;
+  return decode_common(layout, cache, q, q_dtype, q_heads, seq_len, softmax_scale, out, out_dtype, ws,
+                       need ? KVQ_STATIC_SCRATCH_BYTES : 0, nullptr, stream);
+}
+
 kvq_status kvq_decode_step(const kvq_layout* layout, const kvq_cache* cache, const void* k_new, const void* v_new,
                            kvq_dtype in_dtype, int64_t stride_b, int64_t stride_h, int32_t pos, const void* q,
                            kvq_dtype q_dtype, int32_t q_heads, float softmax_scale, void* out, kvq_dtype out_dtype,
@@ -283,6 +329,7 @@ const char* kvq_status_string(kvq_status status) {
     case KVQ_ERR_CAPACITY: return "beyond cache capacity";
     case KVQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case KVQ_ERR_DEVICE: return "HIP runtime error at launch";
+    case KVQ_ERR_STATIC_SCRATCH: return "needs more partial-record bytes than the static scratch array holds";
   }
   return "unknown status";
 }

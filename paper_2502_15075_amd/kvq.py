@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libkvq.so")
 
 KVQ_F16, KVQ_BF16, KVQ_F32 = 0, 1, 2
 AXIS_HEAD_DIM, AXIS_SEQ = 0, 1
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_WORKSPACE, ERR_DEVICE = range(6)
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_WORKSPACE, ERR_DEVICE, ERR_STATIC_SCRATCH = range(7)
+STATIC_SCRATCH_BYTES = 4 << 20
 
 _DTYPES = {torch.float16: KVQ_F16, torch.bfloat16: KVQ_BF16, torch.float32: KVQ_F32}
 
@@ -55,6 +56,8 @@ def load():
                                             C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p]
         lib.kvq_decode_attention.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_int, C.c_int32,
                                              C.c_int32, C.c_float, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.kvq_decode_attention_static.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_int, C.c_int32,
+                                                    C.c_int32, C.c_float, C.c_void_p, C.c_int, C.c_void_p]
         lib.kvq_decode_step.argtypes = [C.POINTER(_CLayout), C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int, C.c_int64,
                                         C.c_int64, C.c_int32, C.c_void_p, C.c_int, C.c_int32, C.c_float, C.c_void_p, C.c_int,
                                         C.c_void_p, C.c_size_t, C.c_void_p]
@@ -73,7 +76,7 @@ def load():
         lib.kvq_status_string.restype = C.c_char_p
         for f in ("kvq_cache_bytes", "kvq_residual_bytes", "kvq_decode_workspace_bytes", "kvq_quantize_append", "kvq_decode_attention",
                   "kvq_decode_step", "kvq_dequantize", "kvq_reconstruction_error", "kvq_decode_attention_varlen",
-                  "kvq_decode_step_varlen", "kvq_selftest_quantizer"):
+                  "kvq_decode_step_varlen", "kvq_selftest_quantizer", "kvq_decode_attention_static"):
             getattr(lib, f).restype = C.c_int
         _lib = lib
     return _lib
@@ -182,6 +185,18 @@ def decode_attention(layout: Layout, cache: Cache, q: torch.Tensor, seq_len: int
                                      C.c_float(softmax_scale), _p(out), _DTYPES[out.dtype], _p(workspace),
                                      0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_ptr())
     _check(st, "kvq_decode_attention")
+    return out
+
+
+def decode_attention_static(layout: Layout, cache: Cache, q: torch.Tensor, seq_len: int, softmax_scale: float,
+                            out: torch.Tensor) -> torch.Tensor:
+    """decode_attention without a workspace argument: the partial records go to the library's static device array
+    (at most STATIC_SCRATCH_BYTES of them; calls that overlap on one GPU race on it)."""
+    assert q.is_contiguous() and out.is_contiguous() and q.dim() == 3 and out.shape == q.shape
+    cl, cc = layout.c(), cache.c()
+    st = load().kvq_decode_attention_static(C.byref(cl), C.byref(cc), _p(q), _DTYPES[q.dtype], q.shape[1], seq_len,
+                                            C.c_float(softmax_scale), _p(out), _DTYPES[out.dtype], _stream_ptr())
+    _check(st, "kvq_decode_attention_static")
     return out
 
 

@@ -32,8 +32,8 @@ def test_every_declared_symbol_is_exported(kvq):
 
 
 def test_status_strings(kvq):
-    seen = {kvq.status_string(i) for i in range(6)}
-    assert len(seen) == 6 and "ok" in seen
+    seen = {kvq.status_string(i) for i in range(7)}
+    assert len(seen) == 7 and "ok" in seen
     assert kvq.status_string(99) == "unknown status"
 
 
