@@ -347,13 +347,36 @@ def test_error_codes_on_device(kvq):
 
 # --------------------------------------------------------------------------- full benchmark sizes, sampled streams
 
-def _check_sampled_streams(kvq, oracle, B, Hq, Hkv, T, seed, sigma_k, samples, fused=True):
-    """Fill a full-size K4V2 G=64 cache on the GPU exactly as bench.py does (chunks of 2048, last token through the
-    fused step), then compare a few (batch, kv head) streams with the oracle: plane bytes identical, output within TOL."""
+def _elementwise_err(out, ref, floor=1e-3):
+    """Largest |out - ref| / |ref| over the elements with |ref| >= floor * max|ref| of their row (reported beside the
+    per-head number, which small-magnitude channels cannot move)."""
+    out = out.astype(np.float64)
+    ref = ref.astype(np.float64)
+    big = np.abs(ref) >= floor * np.abs(ref).max(axis=-1, keepdims=True)
+    return float((np.abs(out - ref)[big] / np.abs(ref)[big]).max())
+
+
+def _check_sampled_streams(kvq, oracle, B, Hq, Hkv, T, seed, sigma_k, samples, fused=True, bk=4, bv=2, axis_seq=False,
+                           page_tokens=0):
+    """Fill a full-size G=64 cache on the GPU exactly as bench.py does (chunks of 2048, last token through the fused
+    step, or a plain append and kvq_decode_attention with fused=False), then compare a few (batch, kv head) streams
+    with the oracle: every plane's bytes identical, output within TOL.  bk = bv = 16: the unquantized bfloat16 cache.
+    axis_seq: channel-wise keys with their residual buffers.  page_tokens: planes as a pool of shuffled pages."""
     D, G, R = 128, 64, Hq // Hkv
     K, V, q = synth.make_kvq(seed, B, Hkv, Hq, T, D, dtype=torch.bfloat16, sigma_k=sigma_k, device="cuda")
-    Lg = kvq.Layout(B, Hkv, T, D, 4, 2, G, G)
+    kw = dict(raw_dtype=kvq.KVQ_BF16)
+    table = None
+    if axis_seq:
+        kw["axis_k"] = kvq.AXIS_SEQ
+    if page_tokens:
+        pps = -(-T // page_tokens)
+        n_pages = B * pps + 3
+        table = torch.from_numpy(np.random.default_rng(seed).permutation(n_pages)[:B * pps].reshape(B, pps).astype(np.int32)).cuda()
+        kw.update(page_tokens=page_tokens, n_pages=n_pages)
+    Lg = kvq.Layout(B, Hkv, T, D, bk, bv, G, G, **kw)
     cache = kvq.Cache(Lg, fill=0)                      # unwritten capacity beyond T compares equal to the oracle's zeros
+    if table is not None:
+        cache.page_table = table
     for a in range(0, T - 1, 2048):
         e = min(a + 2048, T - 1)
         kvq.quantize_append(Lg, cache, K[:, :, a:e], V[:, :, a:e], a)
@@ -365,16 +388,34 @@ def _check_sampled_streams(kvq, oracle, B, Hq, Hkv, T, seed, sigma_k, samples, f
         kvq.quantize_append(Lg, cache, K[:, :, T - 1:], V[:, :, T - 1:], T - 1)
         kvq.decode_attention(Lg, cache, q, T, 1 / math.sqrt(D), out, ws)
     torch.cuda.synchronize()
-    Lo = oracle.Layout(1, 1, T, D, 4, 2, G, G)
-    worst = 0.0
+    cap = -(-T // page_tokens) * page_tokens if page_tokens else T
+    Lo = oracle.Layout(1, 1, cap, D, bk, bv, G, G, raw_dtype=oracle.BF16, axis_k=1 if axis_seq else 0)
+    names = ("k_codes", "k_meta", "v_codes", "v_meta", "k_resid", "v_resid")
+    worst, worst_elem = 0.0, 0.0
     for b, h in samples:
-        planes = oracle.new_planes(Lo)
-        oracle.quantize_append(Lo, planes, synth.to_numpy_bits(K[b:b + 1, h:h + 1]), synth.to_numpy_bits(V[b:b + 1, h:h + 1]), 0, bf16=True)
-        for name, gp, op in zip(("k_codes", "k_meta", "v_codes", "v_meta"), cache.planes, planes):
-            got = gp.view(B * Hkv, -1)[b * Hkv + h].cpu().numpy()
+        kb, vb = synth.to_numpy_bits(K[b:b + 1, h:h + 1]), synth.to_numpy_bits(V[b:b + 1, h:h + 1])
+        qb = synth.to_numpy_bits(q[b:b + 1, h * R:(h + 1) * R])
+        if axis_seq:
+            planes = oracle.new_seq_planes(Lo)
+            oracle.seq_append(Lo, planes, kb, vb, 0, bf16=True)
+            ref = oracle.seq_decode_attention(Lo, planes, qb, T, 1 / math.sqrt(D), bf16=True)
+        else:
+            planes = oracle.new_planes(Lo)
+            oracle.quantize_append(Lo, planes, kb, vb, 0, bf16=True)
+            ref = oracle.decode_attention(Lo, planes, qb, T, 1 / math.sqrt(D), bf16=True)
+        for i, (name, gp, op) in enumerate(zip(names, cache.planes, planes)):
+            if gp is None:
+                assert op.size == 0, name
+                continue
+            if page_tokens and i < 4:                  # this stream's pages in logical order = its contiguous planes
+                got = gp.view(Lg.n_pages, Hkv, -1)[table[b].long(), h].reshape(-1).cpu().numpy()
+            else:
+                got = gp.view(B * Hkv, -1)[b * Hkv + h].cpu().numpy()
             assert np.array_equal(got, op), (name, b, h)
-        ref = oracle.decode_attention(Lo, planes, synth.to_numpy_bits(q[b:b + 1, h * R:(h + 1) * R]), T, 1 / math.sqrt(D), bf16=True)
-        worst = max(worst, _rel_err(out[b:b + 1, h * R:(h + 1) * R].cpu().numpy(), ref))
+        got = out[b:b + 1, h * R:(h + 1) * R].cpu().numpy()
+        worst = max(worst, _rel_err(got, ref))
+        worst_elem = max(worst_elem, _elementwise_err(got, ref))
+    print(f"K{bk}V{bv} B={B} T={T} axis_seq={axis_seq} pages={page_tokens}: per-head {worst:.2e}, element-wise (floor 1e-3) {worst_elem:.2e}")
     assert worst < TOL, worst
 
 
@@ -393,6 +434,25 @@ def test_full_size_8b_layer_sampled_streams(kvq, oracle):
 def test_long_context_batch_1_sampled_streams(kvq, oracle):
     """The long-context workload (B=1, context 131072, 32 splits per stream), ragged length on purpose."""
     _check_sampled_streams(kvq, oracle, 1, 32, 8, 131072 - 5, 4, 4.0, [(0, 3)])
+
+
+@pytest.mark.parametrize("bk,bv", [(2, 4), (4, 4), (8, 8), (16, 16), (2, 2)])
+def test_full_size_8b_allocation_sweep_sampled_streams(kvq, oracle, bk, bv):
+    """The allocation sweep's largest point (B=8, 32 query / 8 KV heads, context 32768, kvq_decode_attention as the
+    sweep launches it): the comparator allocations K2V4, K4V4, K8V8 (Sec. 1), K2V2, and the unquantized bfloat16 cache,
+    each with its own ring depth, 8-wavefront workgroups and 4 sequence splits."""
+    _check_sampled_streams(kvq, oracle, 8, 32, 8, 32768, 2, 4.0, [(6, 3)], fused=False, bk=bk, bv=bv)
+
+
+def test_full_size_70b_layer_channelwise_keys_sampled_streams(kvq, oracle):
+    """Channel-wise K4V2 at the 70B-layer shape with 40 tokens left in the residual buffers (Sec. 4 "Downstream Task
+    Accuracy"): flushed blocks from the codes, the tail through the unquantized kernel, one merge."""
+    _check_sampled_streams(kvq, oracle, 32, 64, 8, 32768 + 40, 1001, 3.3, [(0, 0), (21, 6)], fused=False, axis_seq=True)
+
+
+def test_full_size_70b_layer_paged_sampled_streams(kvq, oracle):
+    """Paged K4V2 at the 70B-layer shape: 64-token pages in shuffled order, fused append of the last token."""
+    _check_sampled_streams(kvq, oracle, 32, 64, 8, 32768, 1002, 3.3, [(0, 0), (30, 2)], page_tokens=64)
 
 
 # --------------------------------------------------------------------------- reconstruction error (MSE numerator)
