@@ -156,6 +156,14 @@ static float load_elem(const void* base, int dtype, int64_t idx) {
   return ((const float*)base)[idx];
 }
 
+/* Threads the loops over independent (batch, head) streams are shared out to (1 when built without OpenMP). */
+#ifdef _OPENMP
+#include <omp.h>
+int ref_threads(void) { return omp_get_max_threads(); }
+#else
+int ref_threads(void) { return 1; }
+#endif
+
 /* ------------------------------------------------------------------ sizes */
 
 static int bits_allowed(int b) { return b == 1 || b == 2 || b == 3 || b == 4 || b == 6 || b == 8; }
@@ -349,9 +357,10 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
   uint64_t pb[4];
   ref_plane_bytes(L, pb);
   int64_t streams = (int64_t)L->batch * L->kv_heads;
-  float* row = (float*)malloc(sizeof(float) * (size_t)D);
-  float* plain = (float*)malloc(sizeof(float) * (size_t)D);
-  uint8_t* codes = (uint8_t*)malloc((size_t)D);
+  for (int which = 0; which < 2; ++which) {
+    int b = which ? L->bits_v : L->bits_k, G = which ? L->group_v : L->group_k;
+    if (b != 16 && (D % G || !bits_allowed(b))) return -1;
+  }
   for (int which = 0; which < 2; ++which) {                 /* 0 = keys, 1 = values */
     int b = which ? L->bits_v : L->bits_k;
     int G = which ? L->group_v : L->group_k;
@@ -360,8 +369,13 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
     uint8_t* mplane = which ? v_meta : k_meta;
     int64_t cstream = (int64_t)(pb[which ? 2 : 0] / (uint64_t)streams);
     int64_t mstream = (int64_t)(pb[which ? 3 : 1] / (uint64_t)streams);
-    if (b != 16 && (D % G || !bits_allowed(b))) { free(row); free(plain); free(codes); return -1; }
+    /* the (b,h) streams are independent and write disjoint bytes: one thread each (only the loop is shared out; the
+     * arithmetic of a stream is untouched) */
+#pragma omp parallel for schedule(dynamic, 1)
     for (int64_t bh = 0; bh < streams; ++bh) {
+      float* row = (float*)malloc(sizeof(float) * (size_t)D);
+      float* plain = (float*)malloc(sizeof(float) * (size_t)D);
+      uint8_t* codes = (uint8_t*)malloc((size_t)D);
       int64_t bi = bh / L->kv_heads, hi = bh % L->kv_heads;
       uint8_t* cs = cplane + bh * cstream;
       uint8_t* ms = mplane ? mplane + bh * mstream : NULL;
@@ -393,9 +407,9 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
           else v_put_code(cs, t, d, D, b, codes[d]);
         }
       }
+      free(row); free(plain); free(codes);
     }
   }
-  free(row); free(plain); free(codes);
   return 0;
 }
 
@@ -419,6 +433,7 @@ int ref_dequantize_stored(const ref_layout* L, const uint8_t* k_codes, const uin
     if (!out) continue;
     int64_t cstream = (int64_t)(pb[which ? 2 : 0] / (uint64_t)streams);
     int64_t mstream = (int64_t)(pb[which ? 3 : 1] / (uint64_t)streams);
+#pragma omp parallel for schedule(dynamic, 1)
     for (int64_t bh = 0; bh < streams; ++bh) {
       const uint8_t* cs = cplane + bh * cstream;
       const uint8_t* ms = mplane ? mplane + bh * mstream : NULL;
@@ -472,10 +487,13 @@ int ref_attention_dense(const float* K, const float* V, int32_t batch, int32_t k
                         int32_t seq_len, int32_t D, const void* q, int q_dtype, float softmax_scale, float* out) {
   if (seq_len <= 0 || q_heads % kv_heads) return -1;
   int R = q_heads / kv_heads;
-  double* logit = (double*)malloc(sizeof(double) * (size_t)seq_len);
-  double* acc = (double*)malloc(sizeof(double) * (size_t)D);
-  for (int b = 0; b < batch; ++b)
-    for (int hq = 0; hq < q_heads; ++hq) {
+  /* every (b, h_q) output row is independent: one thread each, with its own logits and sums */
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t bq = 0; bq < (int64_t)batch * q_heads; ++bq) {
+    {
+      int b = (int)(bq / q_heads), hq = (int)(bq % q_heads);
+      double* logit = (double*)malloc(sizeof(double) * (size_t)seq_len);
+      double* acc = (double*)malloc(sizeof(double) * (size_t)D);
       int hk = hq / R;
       const float* Kh = K + ((int64_t)b * kv_heads + hk) * seq_len * D;
       const float* Vh = V + ((int64_t)b * kv_heads + hk) * seq_len * D;
@@ -495,8 +513,9 @@ int ref_attention_dense(const float* K, const float* V, int32_t batch, int32_t k
         for (int d = 0; d < D; ++d) acc[d] += p * (double)Vh[(int64_t)t * D + d];
       }
       for (int d = 0; d < D; ++d) out[qbase + d] = (float)(acc[d] / denom);
+      free(logit); free(acc);
     }
-  free(logit); free(acc);
+  }
   return 0;
 }
 

@@ -22,7 +22,7 @@ F16, BF16, F32 = 0, 1, 2
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (strict IEEE: no contraction, no fast-math)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
                "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
@@ -76,6 +76,11 @@ def lib():
         _lib.ref_quantize_group.restype = None
         _lib.ref_quantize_group.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
     return _lib
+
+
+def threads() -> int:
+    """Threads the oracle's loops over independent (batch, head) streams use (OMP_NUM_THREADS, else every core)."""
+    return int(lib().ref_threads())
 
 
 def _ptr(a):
