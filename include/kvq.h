@@ -152,9 +152,11 @@ kvq_status kvq_cache_bytes(const kvq_layout* layout, size_t bytes_out[4]);
 /* Host only.  bytes_out = sizes of k_resid, v_resid: 0, 0 unless axis_k = KVQ_AXIS_SEQ. */
 kvq_status kvq_residual_bytes(const kvq_layout* layout, size_t bytes_out[2]);
 
-/* Host only.  Bytes of scratch kvq_decode_attention needs for (q_heads, seq_len): the partial
- * (max, sum, accumulator) records of its split-sequence pass.  May be 0 (enough (b, h_kv) streams to fill
- * the chip without splitting the sequence); then the workspace pointer may be NULL. */
+/* Bytes of scratch kvq_decode_attention needs for (q_heads, seq_len): the partial (max, sum, accumulator) records of its
+ * split-sequence pass.  May be 0 (enough (b, h_kv) streams to fill the chip without splitting the sequence); then the
+ * workspace pointer may be NULL.  Never shrinks as seq_len grows: a workspace sized once for the longest sequence
+ * serves every shorter one.  Touches no device memory; the split plan follows the compute-unit count of the CURRENT
+ * device (256 when no device is usable), so size the workspace with the device current that the decode calls run on. */
 kvq_status kvq_decode_workspace_bytes(const kvq_layout* layout, int32_t q_heads, int32_t seq_len,
                                       size_t* bytes_out);
 
@@ -196,9 +198,10 @@ kvq_status kvq_decode_attention_static(const kvq_layout* layout, const kvq_cache
                                        kvq_dtype q_dtype, int32_t q_heads, int32_t seq_len, float softmax_scale,
                                        void* out, kvq_dtype out_dtype, void* stream);
 
-/* One autoregressive decode step in a single launch (Sec. 4: the cache grows by one quantized token per generated
- * token): quantize the new token's K/V row of every (b, h_kv) into position pos -- same bytes as
- * kvq_quantize_append with n_new = 1 -- then attend over tokens [0, pos].
+/* One autoregressive decode step (Sec. 4: the cache grows by one quantized token per generated token): quantize the new
+ * token's K/V row of every (b, h_kv) into position pos -- same bytes as kvq_quantize_append with n_new = 1 -- then
+ * attend over tokens [0, pos].  Token-wise keys: the append is fused into the attention kernel (one launch, plus the
+ * merge launch when the sequence is split).  Channel-wise keys: the append kernel, then the attention launches.
  *   k_new, v_new   [B][H_kv][D] of in_dtype (KVQ_F16 / KVQ_BF16), element strides given, D contiguous.
  *   everything else as in kvq_decode_attention with seq_len = pos + 1. */
 kvq_status kvq_decode_step(const kvq_layout* layout, const kvq_cache* cache, const void* k_new, const void* v_new,
@@ -227,7 +230,7 @@ kvq_status kvq_reconstruction_error(const kvq_layout* layout, const kvq_cache* c
  *             its query attends over [0, pos[b]].
  *   max_seq_len / max_pos  host: an upper bound of the device values; the launch and the workspace
  *             (kvq_decode_workspace_bytes(layout, q_heads, max_seq_len), max_seq_len = max_pos + 1) are planned for it.
- * Everything else as in the uniform calls.  Not available with channel-wise keys (KVQ_ERR_UNSUPPORTED). */
+ * Everything else as in the uniform calls; channel-wise keys included (see "Channel-wise keys" above). */
 kvq_status kvq_decode_attention_varlen(const kvq_layout* layout, const kvq_cache* cache, const void* q,
                                        kvq_dtype q_dtype, int32_t q_heads, const int32_t* seq_lens,
                                        int32_t max_seq_len, float softmax_scale, void* out, kvq_dtype out_dtype,

@@ -87,9 +87,9 @@ kvq_status kvq_decode_workspace_bytes(const kvq_layout* layout, int32_t q_heads,
   if (!bytes_out || q_heads <= 0 || q_heads % layout->kv_heads || seq_len <= 0) return KVQ_ERR_INVALID_ARG;
   if (seq_len > layout->max_seq) return KVQ_ERR_CAPACITY;
   const kvq::Geom g = kvq::make_geom(*layout);
-  const kvq::DecodePlan plan = kvq::plan_decode(g, seq_len);
-  // one record of (head_dim + 2) floats per (batch, query head, split), padded to 16 bytes
-  const int32_t records = kvq::decode_records(g, seq_len, plan);
+  // one record of (head_dim + 2) floats per (batch, query head, split), padded to 16 bytes; sized for the most records
+  // any length up to seq_len writes, so that the figure never shrinks as seq_len grows
+  const int32_t records = kvq::decode_records_bound(g, seq_len);
   *bytes_out = records == 1 ? 0 : (size_t)layout->batch * q_heads * records * (kvq::kHeadDim + 4) * sizeof(float);
   return KVQ_OK;
 }

@@ -28,6 +28,7 @@
 #include "kvq_internal.h"
 #include "kvq_quantizer.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace kvq {
@@ -1235,26 +1236,30 @@ bool decode_supported(const Geom& g, int32_t q_heads) {
   return true;
 }
 
-// Partial records per (batch, query head) that the workspace of one decode call must hold.  Channel-wise keys: one per
-// split of the flushed blocks plus one for the residual tail (with per-sequence lengths the tail record is always
-// written, so it is always counted once there is a flushed part).
-int32_t decode_records(const Geom& g, int32_t seq_len, const DecodePlan& plan) {
-  if (g.axis_k == KVQ_AXIS_SEQ) return plan.n_splits ? plan.n_splits + 1 : 1;
-  return plan.n_splits;
+// Compute units of the current device, asked once per device (a partitioned or binned part has fewer than the 256 of
+// a whole MI355X).  Without a usable device (the host-only size queries on a machine with no GPU) the whole part's count.
+int device_compute_units() {
+  constexpr int kFull = 256, kMaxDevices = 64;
+  static std::atomic<int> cached[kMaxDevices];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return kFull; }
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+      (void)hipGetLastError();
+      n = kFull;
+    }
+    cached[dev].store(n, std::memory_order_relaxed);
+  }
+  return n;
 }
 
-DecodePlan plan_decode(const Geom& g, int32_t seq_len) {
-  // Fill the chip exactly once: 256 CUs x 4 SIMDs x KVQ_WAVES_PER_SIMD wavefronts, spread over the (b,h) streams.
-  // Workgroups of 8 wavefronts halve the number of sequence splits (none at all from 256 streams up, where the
-  // merge kernel and the workspace traffic disappear); each wavefront should still own a few steps.
-  // Channel-wise keys: the plan covers the flushed tokens only (whole 64-token blocks, two steps each, taken in pairs);
-  // n_splits = 0 when nothing is flushed yet.  The residual tail is a launch of its own.
-  const bool seq = g.axis_k == KVQ_AXIS_SEQ;
-  const int unit = seq ? 2 : 1;
-  const int n_steps = seq ? seq_len / kSeqGroup * 2 : (seq_len + 31) / 32;
-  if (n_steps == 0) return DecodePlan{0, 0, 4};
+namespace {
+// Wavefronts per (b, h_kv) stream that fill the chip once, and what a sequence of n_steps steps can use of them.
+struct WaveBudget { int waves, nw, splits; };
+WaveBudget wave_budget(const Geom& g, int n_steps) {
   const int streams = g.batch * g.kv_heads;
-  const int total_waves = 256 * 4 * KVQ_WAVES_PER_SIMD;
+  const int total_waves = device_compute_units() * 4 * KVQ_WAVES_PER_SIMD;
   int waves_per_stream = (total_waves + streams - 1) / streams;
   const int max_waves = (n_steps + 1) / 2;                     // at least two steps per wavefront
   if (waves_per_stream > max_waves) waves_per_stream = max_waves;
@@ -1262,9 +1267,39 @@ DecodePlan plan_decode(const Geom& g, int32_t seq_len) {
   const int nw = waves_per_stream >= 8 ? 8 : 4;
   int splits = waves_per_stream / nw;
   if (splits < 1) splits = 1;
-  int sps = (n_steps + splits - 1) / splits;
+  return WaveBudget{waves_per_stream, nw, splits};
+}
+int plan_steps(const Geom& g, int32_t seq_len) {
+  return g.axis_k == KVQ_AXIS_SEQ ? seq_len / kSeqGroup * 2 : (seq_len + 31) / 32;
+}
+}  // namespace
+
+// Upper bound, over every length up to seq_len, of the partial records per (batch, query head) that one decode call
+// writes (channel-wise keys: one per split of the flushed blocks plus one for the residual tail): the number of splits
+// before the steps are dealt out never shrinks as the sequence grows, and dealing them out in whole multiples of the
+// workgroup's wavefronts only ever lowers it.  The workspace is sized for this bound, so a workspace sized once for the longest sequence serves every
+// shorter one (the exact count is not monotone in the length).
+int32_t decode_records_bound(const Geom& g, int32_t seq_len) {
+  const int n_steps = plan_steps(g, seq_len);
+  if (n_steps == 0) return 1;
+  const int splits = wave_budget(g, n_steps).splits;
+  return g.axis_k == KVQ_AXIS_SEQ ? splits + 1 : splits;
+}
+
+DecodePlan plan_decode(const Geom& g, int32_t seq_len) {
+  // Fill the chip exactly once: compute units x 4 SIMDs x KVQ_WAVES_PER_SIMD wavefronts, spread over the (b,h) streams.
+  // Workgroups of 8 wavefronts halve the number of sequence splits (none at all from 256 streams up, where the
+  // merge kernel and the workspace traffic disappear); each wavefront should still own a few steps.
+  // Channel-wise keys: the plan covers the flushed tokens only (whole 64-token blocks, two steps each, taken in pairs);
+  // n_splits = 0 when nothing is flushed yet.  The residual tail is a launch of its own.
+  const int unit = g.axis_k == KVQ_AXIS_SEQ ? 2 : 1;
+  const int n_steps = plan_steps(g, seq_len);
+  if (n_steps == 0) return DecodePlan{0, 0, 4};
+  const WaveBudget wb = wave_budget(g, n_steps);
+  const int nw = wb.nw;
+  int sps = (n_steps + wb.splits - 1) / wb.splits;
   sps = (sps + nw * unit - 1) / (nw * unit) * (nw * unit);
-  splits = (n_steps + sps - 1) / sps;
+  const int splits = (n_steps + sps - 1) / sps;
   return DecodePlan{splits, sps, nw};
 }
 

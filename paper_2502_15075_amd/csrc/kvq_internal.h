@@ -71,7 +71,8 @@ struct AppendOne {
   const void* k_new; const void* v_new; int in_dtype; int64_t stride_b, stride_h;
 };
 DecodePlan plan_decode(const Geom& g, int32_t seq_len);
-int32_t decode_records(const Geom& g, int32_t seq_len, const DecodePlan& plan);
+int32_t decode_records_bound(const Geom& g, int32_t seq_len);   // >= the records per head of every length up to seq_len
+int device_compute_units();                                      // of the current device (256 without one)
 
 // Everything the decode kernels need, passed by value.
 struct DecodeArgs {

@@ -217,3 +217,13 @@ def test_inline_assembly_stays_away_from_transcendental_results():
     for name, found in texts.items():
         for text in found:
             assert text.split()[0] in allowed, (name, text)
+
+
+def test_workspace_never_shrinks_as_the_sequence_grows(kvq):
+    """A caller sizes the workspace once for its longest sequence: the figure for a shorter one must not be larger
+    (the number of records a call actually writes is not monotone in the length; the reported size is its bound)."""
+    for B, H, Hq, axis in ((8, 8, 32, 0), (2, 8, 32, 0), (1, 8, 8, 0), (1, 1, 8, 0), (3, 2, 16, 1), (1, 8, 32, 1)):
+        L = kvq.Layout(B, H, 1 << 17, 128, 4, 2, 64, 64, axis_k=axis)
+        sizes = [kvq.decode_workspace_bytes(L, Hq, t) for t in list(range(1, 6000, 7)) + list(range(6000, 1 << 17, 997))]
+        assert all(a <= b for a, b in zip(sizes, sizes[1:])), (B, H, axis)
+        assert sizes[-1] > 0 and sizes[-1] % (132 * 4 * B * Hq) == 0
