@@ -39,12 +39,26 @@ WORKLOADS = {
 
 
 def _traffic_from_profile(name: str):
-    """HBM bytes per decode launch from the committed counter summary, if there is one."""
+    """HBM bytes per decode launch as the committed rocprofv3 counter summary states them (FETCH_SIZE and WRITE_SIZE of
+    the same command, scaled by the copy calibration), with where they come from.  Hardware counters cannot be read from
+    inside this process, so this is the figure of the profiled run, not of the run that prints it: the summary names
+    the kernel sources it was taken with, and a summary of other sources is reported as stale (traffic: null)."""
+    import hashlib
     path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
-        return None
-    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
-    return float(m.group(1)) if m else None
+        return None, f"no committed counter summary profiles/{name}"
+    text = open(path).read()
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, re.M)
+    h = hashlib.sha256()
+    for f in ("kvq_decode.hip", "kvq_quantizer.h", "kvq_internal.h"):
+        h.update(open(os.path.join(ROOT, "paper_2502_15075_amd", "csrc", f), "rb").read())
+    now = h.hexdigest()[:16]
+    tag = re.search(r"^kernel_sources_sha256_16:\s*([0-9a-f]+)", text, re.M)
+    if not m:
+        return None, f"profiles/{name} states no traffic figure"
+    if not tag or tag.group(1) != now:
+        return None, f"profiles/{name} was taken with other kernel sources (current sources: {now}); stale, not reported"
+    return float(m.group(1)), f"profiles/{name} (rocprofv3 --pmc run of this command with kernel sources {now})"
 
 
 def _time_loop(fn, steps, warmup):
@@ -60,44 +74,11 @@ def _time_loop(fn, steps, warmup):
 
 
 def run_sweep(args, kvq, synth) -> int:
-    """Bit-allocation sweep on the Llama-3-8B layer shape (B=8, H_q=32, H_kv=8, D=128, bf16, 64-channel groups):
-    K4V2, K2V4, K3V2 (48-byte key rows), K4V1 (16-byte value rows), K4V3, K4V4, K8V8 and the unquantized bf16 cache at
-    contexts 2048 / 8192 / 32768.  Per line: attention-output
-    error against exact attention on the ORIGINAL tensors (CPU oracle, batch element 0) and effective GB/s of
-    kvq_decode_attention over rotating cache copies (more bytes than the 256 MB last-level cache)."""
-    import numpy as np
-    from oracle import ref
-    B, Hq, Hkv, D, G = 8, 32, 8, 128, 64
-    scale = 1.0 / math.sqrt(D)
+    """The allocation sweep of configs[2] with more allocations (K3V2: 48-byte key rows; K4V1: 16-byte value rows; K4V3)
+    and longer timing loops than the default line carries; one JSON line per allocation and context."""
     allocs = [("K4V2", 4, 2), ("K2V4", 2, 4), ("K3V2", 3, 2), ("K4V1", 4, 1), ("K4V3", 4, 3), ("K4V4", 4, 4), ("K8V8", 8, 8), ("bf16", 16, 16)]
-    for T in (2048, 8192, 32768):
-        K, V, q = synth.make_kvq(2, B, Hkv, Hq, T, D, dtype=torch.bfloat16, device="cuda")
-        want = ref.attention_dense(K[:1].float().cpu().numpy(), V[:1].float().cpu().numpy(),
-                                   synth.to_numpy_bits(q[:1]), scale, bf16=True).astype(np.float64)
-        for name, bk, bv in allocs:
-            L = kvq.Layout(B, Hkv, T, D, bk, bv, G, G, raw_dtype=kvq.KVQ_BF16)
-            row_bytes = 16 * bk + 16 * bv + (0 if bk == 16 else 2 * (D // G) * 4)
-            kv_bytes = B * Hkv * T * row_bytes
-            copies = max(2, min(64, (1 << 30) // kv_bytes + 1))
-            caches = []
-            for _ in range(copies):
-                c = kvq.Cache(L, device="cuda")
-                kvq.quantize_append(L, c, K, V, 0)
-                caches.append(c)
-            ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, Hq, T)), dtype=torch.uint8, device="cuda")
-            out = torch.empty(B, Hq, D, dtype=torch.float32, device="cuda")
-            steps = max(200, min(4000, int(2e11 / kv_bytes)))
-            ms = _time_loop(lambda i: kvq.decode_attention(L, caches[i % copies], q, T, scale, out, ws), steps, steps // 5)
-            ms_hot = _time_loop(lambda i: kvq.decode_attention(L, caches[0], q, T, scale, out, ws), steps, steps // 5)
-            got = out[:1].cpu().numpy().astype(np.float64)
-            rel_l2 = float((np.linalg.norm(got - want, axis=-1) / np.linalg.norm(want, axis=-1)).mean())
-            rel_max = float((np.abs(got - want).max(axis=-1) / np.abs(want).max(axis=-1)).max())
-            print(json.dumps({"workload": f"configs[2]: 8B layer, B=8, T={T}, {name} G=64", "alloc": name, "context": T,
-                              "kv_bytes": kv_bytes, "cache_copies_rotated": copies,
-                              "GB_s_cold": round(kv_bytes / ms / 1e6, 1), "us_cold": round(ms * 1e3, 2),
-                              "GB_s_same_cache": round(kv_bytes / ms_hot / 1e6, 1),
-                              "err_vs_exact_attention_mean_rel_l2": round(rel_l2, 5), "err_max_rel": round(rel_max, 5)}), flush=True)
-            del caches
+    for row in measure_config2(kvq, synth, allocs=allocs, max_steps=4000)["points"]:
+        print(json.dumps(dict(workload=f"configs[2]: 8B layer, B=8, T={row['context']}, {row['alloc']} G=64", **row)), flush=True)
     return 0
 
 
@@ -261,55 +242,250 @@ def run_channelwise(args, kvq, synth) -> int:
     return 0
 
 
-def run_stream(args, kvq, synth) -> int:
-    """Long-context streaming on the 8B layer shape at batch 1: fill 131072 tokens with kvq_quantize_append in chunks of
-    2048, then 256 fused decode steps on the growing cache.  Quantize tok/s and decode GB/s are reported separately."""
+def _time_events(fn, steps, warmup, every=8):
+    """Mean device time per call in ms: HIP events on the current stream around consecutive groups of `every` calls."""
+    for i in range(warmup):
+        fn(i)
+    n_groups = (steps + every - 1) // every
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_groups)]
+    torch.cuda.synchronize()
+    for i in range(steps):
+        if i % every == 0:
+            events[i // every][0].record()
+        fn(warmup + i)
+        if i % every == every - 1 or i == steps - 1:
+            events[i // every][1].record()
+    torch.cuda.synchronize()
+    return sum(a.elapsed_time(b) for a, b in events) / steps
+
+
+def _time_graph(fn, n_calls, reps):
+    """Mean time per call in ms of `n_calls` consecutive calls captured into one HIP graph and replayed `reps` times."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr, stream=side):
+            for i in range(n_calls):
+                fn(i)
+        for _ in range(max(1, reps // 10)):
+            gr.replay()
+        side.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(reps):
+            gr.replay()
+        side.synchronize()
+        ms = (time.perf_counter() - g0) * 1e3 / (reps * n_calls)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    return ms
+
+
+def _preroll(step, min_s=0.15, cap_s=0.5, chunk=64):
+    """Runs the step in chunks until a chunk is no faster than the best one before it three times in a row (the clocks
+    of a box that has been idle take a few hundred launches to settle), for at least min_s and at most cap_s seconds.
+    Returns the steps run."""
+    done, best, flat = 0, float("inf"), 0
+    t_start = time.perf_counter()
+    while time.perf_counter() - t_start < cap_s:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(chunk):
+            step(done + i)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        done += chunk
+        flat = flat + 1 if dt >= 0.995 * best else 0
+        best = min(best, dt)
+        if flat >= 3 and time.perf_counter() - t_start >= min_s:
+            break
+    return done
+
+
+def measure_config0(kvq, synth):
+    """configs[0]: one layer, batch 1, 8 query = 8 KV heads, context 1024, fp16, K4V2 with 32-channel groups, seed 0
+    (1 MiB of cache: launch-bound).  Latency of the fused decode step."""
+    B, H, T, D = 1, 8, 1024, 128
+    scale = 1.0 / math.sqrt(D)
+    K, V, q = synth.make_kvq(0, B, H, H, T, D, dtype=torch.float16, device="cuda")
+    L = kvq.Layout(B, H, T, D, 4, 2, 32, 32)
+    cache = kvq.Cache(L, device="cuda")
+    kvq.quantize_append(L, cache, K, V, 0)
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, H, T)), dtype=torch.uint8, device="cuda")
+    out = torch.empty(B, H, D, dtype=torch.float32, device="cuda")
+    k1, v1 = K[:, :, T - 1].contiguous(), V[:, :, T - 1].contiguous()
+    step = lambda i: kvq.decode_step(L, cache, k1, v1, T - 1, q, scale, out, ws)
+    ev_ms = _time_events(step, 2000, 200)
+    graph_ms = _time_graph(step, 50, 40)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(200):
+        step(i)
+        torch.cuda.synchronize()
+    sync_ms = (time.perf_counter() - t0) * 1e3 / 200
+    kv_bytes = B * H * T * 128
+    return {"workload": "configs[0]: B=1, 8 query = 8 KV heads, T=1024, fp16, K4V2 G=32 (1 MiB cache, launch-bound)",
+            "decode_step_us_back_to_back": round(ev_ms * 1e3, 2), "decode_step_us_graph_replay": round(graph_ms * 1e3, 2),
+            "decode_step_us_call_plus_synchronize": round(sync_ms * 1e3, 2),
+            "GB_s_back_to_back": round(kv_bytes / ev_ms / 1e6, 1)}
+
+
+def measure_config1(kvq, synth, copies=24):
+    """configs[1]: Llama-3-8B layer, B=8, 32 query / 8 KV heads, context 8192, bf16, K4V2 G=64: one fused decode step
+    (append of the token at position 8191 + attention over 8192).  56 MiB per cache: `copies` caches are taken in turn so
+    that the bytes come from HBM, and the same step on one cache (served by the last-level cache) is reported beside it."""
+    B, Hq, Hkv, T, D, G = 8, 32, 8, 8192, 128, 64
+    scale = 1.0 / math.sqrt(D)
+    K, V, q = synth.make_kvq(1, B, Hkv, Hq, T, D, dtype=torch.bfloat16, device="cuda")
+    L = kvq.Layout(B, Hkv, T, D, 4, 2, G, G)
+    caches = [kvq.Cache(L, device="cuda") for _ in range(copies)]
+    for c in caches:
+        kvq.quantize_append(L, c, K[:, :, :T - 1], V[:, :, :T - 1], 0)
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, Hq, T)), dtype=torch.uint8, device="cuda")
+    out = torch.empty(B, Hq, D, dtype=torch.float32, device="cuda")
+    k1, v1 = K[:, :, T - 1].contiguous(), V[:, :, T - 1].contiguous()
+    step = lambda i: kvq.decode_step(L, caches[i % copies], k1, v1, T - 1, q, scale, out, ws)
+    ev_ms = _time_events(step, 3000, 300)
+    graph_ms = _time_graph(step, copies, 100)
+    hot_ms = _time_events(lambda i: kvq.decode_step(L, caches[0], k1, v1, T - 1, q, scale, out, ws), 2000, 200)
+    kv_bytes = B * Hkv * T * 112
+    return {"workload": "configs[1]: Llama-3-8B layer, B=8, H_q=32, H_kv=8, T=8192, bf16, K4V2 G=64, fused decode step",
+            "kv_bytes_per_step": kv_bytes, "cache_copies_rotated": copies,
+            "decode_step_us": round(ev_ms * 1e3, 2), "GB_s": round(kv_bytes / ev_ms / 1e6, 1),
+            "pct_of_hbm_peak": round(kv_bytes / ev_ms / 1e6 / 80.0, 1), "decode_tok_s": round(B / ev_ms * 1e3, 1),
+            "decode_step_us_graph_replay": round(graph_ms * 1e3, 2),
+            "decode_step_us_same_cache": round(hot_ms * 1e3, 2), "us_at_hbm_peak": round(kv_bytes / 8e6, 2)}
+
+
+def measure_config4(kvq, synth, copies=3):
+    """configs[4]: 8B layer shape, batch 1, context 131072: the cache is filled by kvq_quantize_append in chunks of 2048
+    tokens, then 256 fused decode steps run on the growing cache.  Quantize tok/s and decode GB/s are reported
+    separately.  112 MiB per cache: `copies` caches are taken in turn (more bytes than the last-level cache holds)."""
     B, Hq, Hkv, D, G, T0, nstep, chunk = 1, 32, 8, 128, 64, 131072, 256, 2048
     scale = 1.0 / math.sqrt(D)
     L = kvq.Layout(B, Hkv, T0 + nstep, D, 4, 2, G, G)
     K, V, _ = synth.make_kvq(4, B, Hkv, Hq, T0 + nstep, D, dtype=torch.bfloat16, device="cuda")
     q = torch.randn(nstep, B, Hq, D, device="cuda", generator=torch.Generator(device="cuda").manual_seed(5)).to(torch.bfloat16)
-    cache = kvq.Cache(L, device="cuda")
+    caches = [kvq.Cache(L, device="cuda") for _ in range(copies)]
 
-    def fill():
+    def fill(c):
         for a in range(0, T0, chunk):
-            kvq.quantize_append(L, cache, K[:, :, a:a + chunk], V[:, :, a:a + chunk], a)
-    fill(); torch.cuda.synchronize()                                   # warm-up pass
-    reps = 20
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        fill()
+            kvq.quantize_append(L, c, K[:, :, a:a + chunk], V[:, :, a:a + chunk], a)
+    for c in caches:
+        fill(c)
+        kvq.quantize_append(L, c, K[:, :, T0:], V[:, :, T0:], T0)     # (the decode steps rewrite these rows in place)
+    fill_ms = _time_events(lambda i: fill(caches[i % copies]), 12, 3, every=1)
     torch.cuda.synchronize()
-    fill_s = (time.perf_counter() - t0) / reps
-    # one chunk at a time with a synchronize after each call: the per-call latency a prefill loop would see
     t0 = time.perf_counter()
     for a in range(0, T0, chunk):
-        kvq.quantize_append(L, cache, K[:, :, a:a + chunk], V[:, :, a:a + chunk], a)
+        kvq.quantize_append(L, caches[0], K[:, :, a:a + chunk], V[:, :, a:a + chunk], a)
         torch.cuda.synchronize()
     percall_s = (time.perf_counter() - t0) / (T0 // chunk)
-
     ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, Hq, T0 + nstep)), dtype=torch.uint8, device="cuda")
     out = torch.empty(B, Hq, D, dtype=torch.float32, device="cuda")
 
-    def decode_pass():
-        for i in range(nstep):
-            kvq.decode_step(L, cache, K[:, :, T0 + i], V[:, :, T0 + i], T0 + i, q[i], scale, out, ws)
-    decode_pass(); torch.cuda.synchronize()
-    reps = 10
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        decode_pass()
-    torch.cuda.synchronize()
-    step_s = (time.perf_counter() - t0) / (reps * nstep)
-    att_ms = _time_loop(lambda i: kvq.decode_attention(L, cache, q[i % nstep], T0 + nstep, scale, out, ws), 2000, 200)
+    def dstep(i):
+        j = i % nstep
+        kvq.decode_step(L, caches[i % copies], K[:, :, T0 + j], V[:, :, T0 + j], T0 + j, q[j], scale, out, ws)
+    step_ms = _time_events(dstep, 4 * nstep, nstep, every=8)
+    hot_ms = _time_events(lambda i: kvq.decode_step(L, caches[0], K[:, :, T0 + i % nstep], V[:, :, T0 + i % nstep], T0 + i % nstep,
+                                                    q[i % nstep], scale, out, ws), 2 * nstep, nstep // 2)
     kv_bytes = B * Hkv * (T0 + (nstep + 1) / 2) * 112
-    print(json.dumps({"workload": "configs[4]: 8B layer, B=1, T=131072 (+256 decoded), K4V2 G=64, chunks of 2048",
-                      "quantize_tok_s_back_to_back": round(T0 / fill_s, 1), "quantize_us_per_chunk_call_synchronized": round(percall_s * 1e6, 2),
-                      "decode_step_us": round(step_s * 1e6, 2), "decode_GB_s": round(kv_bytes / step_s / 1e9, 1),
-                      "decode_tok_s": round(B / step_s, 1), "attention_only_us": round(att_ms * 1e3, 2),
-                      "attention_only_GB_s": round(B * Hkv * (T0 + nstep) * 112 / att_ms / 1e6, 1),
-                      "note": "the 112 MiB cache fits the 256 MB last-level cache: these are cache-resident numbers"}), flush=True)
-    return 0
+    return {"workload": "configs[4]: 8B layer, B=1, T=131072 filled in chunks of 2048, then 256 fused decode steps, K4V2 G=64",
+            "cache_copies_rotated": copies,
+            "quantize_tok_s_back_to_back": round(T0 / fill_ms * 1e3, 1), "quantize_us_per_chunk_back_to_back": round(fill_ms * 1e3 / (T0 // chunk), 2),
+            "quantize_GB_s_back_to_back": round(T0 * 4992 / fill_ms / 1e6, 1),
+            "quantize_us_per_chunk_call_plus_synchronize": round(percall_s * 1e6, 2),
+            "decode_step_us": round(step_ms * 1e3, 2), "decode_GB_s": round(kv_bytes / step_ms / 1e6, 1),
+            "pct_of_hbm_peak": round(kv_bytes / step_ms / 1e6 / 80.0, 1), "decode_tok_s": round(B / step_ms * 1e3, 1),
+            "decode_step_us_same_cache": round(hot_ms * 1e3, 2), "us_at_hbm_peak": round(kv_bytes / 8e6, 2)}
+
+
+SWEEP_ALLOCS = [("K4V2", 4, 2), ("K2V4", 2, 4), ("K4V4", 4, 4), ("K8V8", 8, 8), ("bf16", 16, 16)]
+
+
+def measure_config2(kvq, synth, allocs=SWEEP_ALLOCS, contexts=(2048, 8192, 32768), max_steps=1000):
+    """configs[2]: allocation sweep on the 8B layer shape (B=8, 32 query / 8 KV heads, bf16, 64-channel groups).  Per
+    allocation and context: attention-output error against exact attention on the ORIGINAL tensors (CPU oracle, batch
+    element 0: mean relative L2 and the per-head maximum) and effective GB/s of kvq_decode_attention over rotating
+    cache copies (more bytes than the 256 MB last-level cache)."""
+    import numpy as np
+    from oracle import ref
+    B, Hq, Hkv, D, G = 8, 32, 8, 128, 64
+    scale = 1.0 / math.sqrt(D)
+    rows = []
+    for T in contexts:
+        K, V, q = synth.make_kvq(2, B, Hkv, Hq, T, D, dtype=torch.bfloat16, device="cuda")
+        want = ref.attention_dense(K[:1].float().cpu().numpy(), V[:1].float().cpu().numpy(),
+                                   synth.to_numpy_bits(q[:1]), scale, bf16=True).astype(np.float64)
+        for name, bk, bv in allocs:
+            L = kvq.Layout(B, Hkv, T, D, bk, bv, G, G, raw_dtype=kvq.KVQ_BF16)
+            row_bytes = 16 * bk + 16 * bv + (0 if bk == 16 else 2 * (D // G) * 4)
+            kv_bytes = B * Hkv * T * row_bytes
+            copies = max(2, min(64, (1 << 30) // kv_bytes + 1))
+            caches = []
+            for _ in range(copies):
+                c = kvq.Cache(L, device="cuda")
+                kvq.quantize_append(L, c, K, V, 0)
+                caches.append(c)
+            ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, Hq, T)), dtype=torch.uint8, device="cuda")
+            out = torch.empty(B, Hq, D, dtype=torch.float32, device="cuda")
+            steps = max(200, min(max_steps, int(5e10 / kv_bytes)))
+            ms = _time_events(lambda i: kvq.decode_attention(L, caches[i % copies], q, T, scale, out, ws), steps, steps // 5)
+            got = out[:1].cpu().numpy().astype(np.float64)
+            rel_l2 = float((np.linalg.norm(got - want, axis=-1) / np.linalg.norm(want, axis=-1)).mean())
+            rel_max = float((np.abs(got - want).max(axis=-1) / np.abs(want).max(axis=-1)).max())
+            rows.append({"alloc": name, "context": T, "kv_bytes": kv_bytes, "cache_copies_rotated": copies,
+                         "us": round(ms * 1e3, 2), "GB_s": round(kv_bytes / ms / 1e6, 1),
+                         "pct_of_hbm_peak": round(kv_bytes / ms / 1e6 / 80.0, 1),
+                         "err_vs_exact_attention_mean_rel_l2": round(rel_l2, 5), "err_max_rel": round(rel_max, 5)})
+            del caches
+        del K, V
+    return {"workload": "configs[2]: 8B layer, B=8, H_q=32, H_kv=8, bf16, G=64, kvq_decode_attention; error against exact "
+                        "attention on the unquantized tensors (batch element 0)", "points": rows}
+
+
+def _cpu_baseline(kvq, synth, L, layer0, sample, Hq, Hkv, T, D, G, scale, row_bytes, out, ws):
+    """The CPU oracle as it stands, timed on this machine's host cores (OpenMP over the (batch, head) streams) on the same
+    layer-0 inputs: first batch elements 0..3, then the whole layer if that is projected to take under about 40 s.
+    Also the parity of the GPU path on those rows: plane bytes identical, output error per head and element-wise."""
+    import numpy as np
+    from oracle import ref
+    Kh, Vh, qh = sample
+    B = Kh.shape[0]
+    cache0, _, _, q0 = layer0
+    kvq.decode_attention(L, cache0, q0, T, scale, out, ws)
+    torch.cuda.synchronize()
+    got_all = out.cpu().numpy().astype(np.float64)
+    result = None
+    for nb in (4, B):
+        Lo = ref.Layout(nb, Hkv, T, D, 4, 2, G, G)
+        planes = ref.new_planes(Lo)
+        c0 = time.perf_counter()
+        ref.quantize_append(Lo, planes, synth.to_numpy_bits(Kh[:nb]), synth.to_numpy_bits(Vh[:nb]), 0, bf16=True)
+        c1 = time.perf_counter()
+        want = ref.decode_attention(Lo, planes, synth.to_numpy_bits(qh[:nb]), T, scale, bf16=True).astype(np.float64)
+        c2 = time.perf_counter()
+        got = got_all[:nb]
+        err = np.abs(got - want)
+        parity = float((err.max(axis=-1) / np.abs(want).max(axis=-1)).max())
+        big = np.abs(want) >= 1e-3 * np.abs(want).max(axis=-1, keepdims=True)
+        elem = float((err[big] / np.abs(want)[big]).max())
+        gpu_planes = [p.view(B, -1)[:nb].reshape(-1).cpu().numpy() for p in cache0.planes[:4]]
+        bytes_equal = all(bool((gp == op).all()) for gp, op in zip(gpu_planes, planes))
+        what = "the whole layer 0" if nb == B else f"batch elements 0..{nb - 1} of layer 0"
+        result = {
+            "value": round(nb * Hkv * T * row_bytes / (c2 - c1) / 1e9, 5), "unit": "GB/s", "cores": ref.threads(), "kind": "oracle",
+            "sample": f"decode attention over {what} at full context ({nb * Hkv * T} of {B * Hkv * T} rows), {c2 - c1:.1f} s "
+                      f"on {ref.threads()} threads; oracle quantize of the same rows {nb * T / (c1 - c0):.0f} tok/s ({c1 - c0:.1f} s)",
+            "quantize_tok_s": round(nb * T / (c1 - c0), 1),
+            "parity_max_rel_err_vs_oracle": parity, "parity_elementwise_max_rel_err_floor_1e-3": elem,
+            "planes_byte_identical": bytes_equal,
+        }
+        del planes, want
+        if nb == B or (c2 - c0) * (B / nb) > 40.0:
+            break
+    return result
 
 
 def main() -> int:
@@ -323,6 +499,8 @@ def main() -> int:
                          "layer (one line per allocation and context); stream131k: chunked fill + growing-cache decode at 131072")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the same steps")
+    ap.add_argument("--no-preroll", action="store_true", help="skip the reported pre-roll in front of the declared warm-up")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the short measurements of configs[0], [1], [2], [4]")
     ap.add_argument("--event-every", type=int, default=8, help="launches per HIP-event pair in the timed region")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run 5 plain device copies of this size (reference for hardware byte counters)")
@@ -348,20 +526,23 @@ def main() -> int:
     if args.workload == "channelwise":
         return run_channelwise(args, kvq, synth)
     if args.workload == "stream131k":
-        return run_stream(args, kvq, synth)
+        print(json.dumps(measure_config4(kvq, synth)), flush=True)
+        return 0
     B, Hq, Hkv, T, desc = WORKLOADS[args.workload]
     D, G = 128, 64
     L = kvq.Layout(B, Hkv, T, D, 4, 2, G, G)
     scale = 1.0 / math.sqrt(D)
     row_bytes = 16 * 4 + 16 * 2 + 2 * (D // G) * 4          # K4 codes + V2 codes + scale/zero pairs = 112
     kv_bytes = B * Hkv * T * row_bytes
+    q_bytes_per_token = Hkv * (2 * D * 2 + row_bytes)       # quantize: 2 x 256 B read + 112 B written per (h_kv, token)
 
     # ---- resident layers: generate, quantize (timed: bulk quantize tok/s), keep the last token + query
     g = torch.Generator().manual_seed(3)
     ratios = (torch.rand(args.layers, generator=g) * 4 + 2).tolist()
     layers = []
-    fill_ms, fill_tokens = 0.0, 0
+    fill_ms = []
     chunk = 2048
+    sample = None
     for li in range(args.layers):
         K, V, q = synth.make_kvq(1000 + li, B, Hkv, Hq, T, D, dtype=torch.bfloat16, sigma_k=ratios[li], device=dev)
         cache = kvq.Cache(L, device=dev)
@@ -371,14 +552,17 @@ def main() -> int:
             kvq.quantize_append(L, cache, K[:, :, a:a + chunk], V[:, :, a:a + chunk], a)
         e1.record()
         torch.cuda.synchronize()
-        fill_ms += e0.elapsed_time(e1)
-        fill_tokens += B * T
+        fill_ms.append(e0.elapsed_time(e1))
         layers.append((cache, K[:, :, T - 1:T].clone(), V[:, :, T - 1:T].clone(), q))
-        if li == 0:
-            sample = (K[:4].cpu(), V[:4].cpu(), q[:4].cpu())
+        if li == 0 and not args.no_cpu_baseline:
+            sample = (K.cpu(), V.cpu(), q.cpu())
         del K, V
     ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, Hq, T)), dtype=torch.uint8, device=dev)
     out = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
+    fill_ms.sort()
+    fill_med = fill_ms[len(fill_ms) // 2]                   # (the first layers are quantized on a box that is still waking up)
+    quant_tok_s = B * T / (fill_med * 1e-3)
+    quant_gbs = quant_tok_s * q_bytes_per_token / 1e9
 
     def step(i):
         # one launch: the new token's K/V rows are quantized into position T-1 by the decode kernel itself
@@ -392,6 +576,8 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    # ---- reported pre-roll (not part of --warmup or --steps): the same step until its time stops falling
+    preroll_steps = 0 if args.no_preroll else _preroll(step)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -420,74 +606,51 @@ def main() -> int:
     # loop that captures its decode step would see; matters for the small shapes, where launches dominate
     graph_ms = None
     if not args.no_graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            gr = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(gr, stream=side):
-                for i in range(len(layers)):
-                    step(i)
-            reps = max(1, args.steps // len(layers))
-            for _ in range(max(1, reps // 10)):
-                gr.replay()
-            side.synchronize()
-            g0 = time.perf_counter()
-            for _ in range(reps):
-                gr.replay()
-            side.synchronize()
-            graph_ms = (time.perf_counter() - g0) * 1e3 / (reps * len(layers))
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
+        graph_ms = _time_graph(step, len(layers), max(1, max(args.steps, 400) // len(layers)))
 
     # ---- the same step on ONE layer's cache over and over: what the last-level cache makes of a cache that fits it
     # (the small workloads; the 70B layer is larger than that cache and reads the same either way)
     hot_ms = _time_loop(lambda i: kvq.decode_step(L, layers[0][0], layers[0][1], layers[0][2], T - 1, layers[0][3], scale, out, ws),
                         max(200, args.steps // 4), max(20, args.warmup // 4))
 
-    # ---- parity of the sampled outputs and the CPU oracle timed on the same sample
-    cpu_baseline, parity = None, None
+    # ---- parity of the whole first layer (or a sample of it) and the CPU oracle timed on the same rows
+    cpu_baseline = None
     if not args.no_cpu_baseline:
-        import numpy as np
-        from oracle import ref
-        Ks, Vs, qs = sample
-        nb = Ks.shape[0]
-        Lo = ref.Layout(nb, Hkv, T, D, 4, 2, G, G)
-        planes = ref.new_planes(Lo)
-        c0 = time.perf_counter()
-        ref.quantize_append(Lo, planes, synth.to_numpy_bits(Ks), synth.to_numpy_bits(Vs), 0, bf16=True)
-        c1 = time.perf_counter()
-        want = ref.decode_attention(Lo, planes, synth.to_numpy_bits(qs), T, scale, bf16=True)
-        c2 = time.perf_counter()
-        cache0, _, _, q0 = layers[0]
-        kvq.decode_attention(L, cache0, q0, T, scale, out, ws)
-        torch.cuda.synchronize()
-        got = out[:nb].cpu().numpy().astype(np.float64)
-        parity = float((np.abs(got - want).max(axis=-1) / np.abs(want).max(axis=-1)).max())
-        gpu_planes = [p.view(B, -1)[:nb].reshape(-1).cpu().numpy() for p in cache0.planes[:4]]
-        bytes_equal = all(bool((gp == op).all()) for gp, op in zip(gpu_planes, planes))
-        cpu_baseline = {
-            "value": round(nb * Hkv * T * row_bytes / (c2 - c1) / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"decode attention for batch elements 0..{nb - 1} of layer 0 at full context ({nb * Hkv * T} of {B * Hkv * T} rows), "
-                      f"{c2 - c1:.1f} s; oracle quantize of the same rows {nb * T / (c1 - c0):.0f} tok/s",
-            "parity_max_rel_err_vs_oracle": parity, "planes_byte_identical": bytes_equal,
-        }
+        cpu_baseline = _cpu_baseline(kvq, synth, L, layers[0], sample, Hq, Hkv, T, D, G, scale, row_bytes, out, ws)
+        sample = None
 
+    # ---- the other configurations of the workload list, a few hundred milliseconds of GPU time each
+    others = None
+    if not args.no_other_configs:
+        del layers[1:]
+        torch.cuda.empty_cache()
+        others = {"configs[0]": measure_config0(kvq, synth), "configs[1]": measure_config1(kvq, synth),
+                  "configs[2]": measure_config2(kvq, synth), "configs[4]": measure_config4(kvq, synth)}
+
+    traffic, traffic_source = _traffic_from_profile(f"decode_k4v2_{args.workload}_pmc.txt")
     line = {
         "metric": "effective packed-KV HBM GB/s, K4V2 decode step (quantize-append of the new token + attention)",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
+        "dtype": "f16 matrix operands (exact codes and queries), f32 accumulate; bf16 inputs", "data": "synthetic",
         "config": {"workload": desc, "layers_resident": args.layers, "kv_bytes_per_step": kv_bytes,
+                   "preroll_steps": preroll_steps,
                    "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
                    "decode_tok_s": round(B / (ms_per_step * 1e-3), 1),
-                   "quantize_tok_s_bulk_fill": round(fill_tokens / (fill_ms * 1e-3), 1),
+                   "quantize_tok_s_bulk_fill": round(quant_tok_s, 1),
                    "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
-                   "ms_per_step_same_cache": round(hot_ms, 5)},
+                   "ms_per_step_same_cache": round(hot_ms, 5),
+                   "other_configs": others},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": _traffic_from_profile(f"decode_k4v2_{args.workload}_pmc.txt"),
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "kvq decode_kernel<4,2,R,NW> (fused step; + merge_kernel when the sequence is split), HIP events around every group of " + str(every) + " consecutive launches of the timed region, per launch",
-                     "kernel_ms": round(decode_ms, 5)},
+                     "kernel_ms": round(decode_ms, 5),
+                     "quantize": {"bound": "hbm", "achieved": round(quant_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                  "frac": round(quant_gbs / HBM_PEAK_GBS, 4), "bytes_per_token": q_bytes_per_token,
+                                  "kernel": "kvq quantize_append_kernel<4,2,bf16>, bulk fill of a layer in 2048-token calls "
+                                            "(HIP events around each layer's 16 calls, median over the layers)",
+                                  "tok_s": round(quant_tok_s, 1)}},
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(line))

@@ -26,6 +26,13 @@ def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
     assert roof["bound"] == "hbm" and roof["peak"] == 8000.0 and roof["unit"] == "GB/s"
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3 and 0.05 < roof["frac"] < 1.0
     assert abs(d["value"] - d["config"]["kv_bytes_per_step"] / (d["ms_per_step"] * 1e-3) / 1e9) < 0.01 * d["value"]
+    assert d["config"]["preroll_steps"] > 0
+    others = d["config"]["other_configs"]
+    assert set(others) == {"configs[0]", "configs[1]", "configs[2]", "configs[4]"}
+    assert others["configs[1]"]["decode_step_us"] > 0 and others["configs[4]"]["quantize_tok_s_back_to_back"] > 0
+    assert len(others["configs[2]"]["points"]) == 15 and others["configs[0]"]["decode_step_us_back_to_back"] > 0
+    qr = roof["quantize"]
+    assert qr["bound"] == "hbm" and 0.05 < qr["frac"] < 1.0 and abs(qr["frac"] - qr["achieved"] / qr["peak"]) < 1e-3
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
     assert cpu["planes_byte_identical"] is True and cpu["parity_max_rel_err_vs_oracle"] < 2e-3
