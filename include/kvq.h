@@ -14,9 +14,8 @@
  *     the given hipStream_t (passed as void*; NULL = the default stream) and returns.
  *   - Arguments are validated on the host before anything is launched; on error nothing ran.
  *   - Status codes only: the library never aborts, throws or prints.
- *   - Not checked (undefined results): non-finite inputs, |x| > 65504, a group whose
- *     range / (2^b - 1) exceeds 32 for values (the attention kernel scales softmax weights by the
- *     value scale in binary16), overlapping buffers, concurrent calls that write the same cache.
+ *   - Not checked (undefined results): non-finite inputs, |x| > 65504, overlapping buffers, concurrent
+ *     calls that write the same cache, a v_scale_exp array that was not zeroed with the cache it belongs to.
  *
  * Quantizer (per tensor X in {K, V}, bits b, group size G; one group = G consecutive head_dim
  * elements of one token row -- token-wise grouping, Sec. 4 "Downstream Task Accuracy"):
@@ -143,6 +142,13 @@ typedef struct {
   void *k_resid, *v_resid; /* residual buffers of channel-wise keys (axis_k = KVQ_AXIS_SEQ); NULL otherwise */
   const int32_t* page_table; /* paged planes: device, int32 [B][ceil(max_seq / page_tokens)]: logical page -> pool page
                                 (each in [0, n_pages); entries of pages no call touches are never read); else NULL */
+  int32_t* v_scale_exp;      /* device, int32 [B][H_kv], part of the cache's state whenever bits_v < 16 (else it may be
+                                NULL): the largest binary16 exponent field of any value scale of 64 or more stored in
+                                that (b, h) stream so far, 0 if there is none.  The caller zeroes it when the cache is
+                                created or a batch slot is handed to a new sequence; every call that stores value scales
+                                raises it, and the attention kernels read it: they form binary16 products of softmax
+                                weight and value scale, and a stream that holds such a scale gets that many bits of
+                                room (ordinary values, whose groups span less than 64 (2^b - 1), never touch it). */
 } kvq_cache;
 
 /* Host only.  bytes_out = sizes of k_codes, k_meta, v_codes, v_meta.  Pins the paper's memory

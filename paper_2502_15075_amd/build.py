@@ -24,11 +24,22 @@ DECODE_PAIRS = [(4, 2), (2, 4), (4, 4), (8, 8), (2, 2), (8, 4), (8, 2), (4, 8), 
                 (3, 2), (3, 4), (3, 8), (6, 2), (6, 4), (6, 8), (1, 2), (1, 4), (1, 8),
                 (1, 1), (2, 1), (3, 1), (4, 1), (6, 1), (8, 1),
                 (1, 3), (2, 3), (3, 3), (4, 3), (6, 3), (8, 3), (1, 6), (2, 6), (3, 6), (4, 6), (6, 6), (8, 6)]
-# Bytes of scratch memory per lane an instance may use.  The channel-wise kernels of 3- and 6-bit keys (two runs, a query
-# operand each) beside 6- or 8-bit values in two value column sets (8 heads per KV head, 32-channel value groups) sit at
-# the 256-register limit with a ring of one step already and keep three registers in scratch; they are bound by their
-# vector instructions, not by their loads.
-SCRATCH_ALLOWED = {f"kvq_decode_k{bk}v{bv}.o": 16 for bk in (3, 6) for bv in (6, 8)}
+# Bytes of scratch memory per lane a decode kernel may use: none, except the channel-wise kernels of 3- and 6-bit keys
+# (two runs, a query operand each) in two value column sets (8 heads per KV head, 32-channel value groups).  Those sit
+# at the 256-register limit with a ring of one step already and keep up to 25 registers in scratch; they are bound by
+# their vector instructions, not by their loads.
+SCRATCH_ALLOWED_TWO_RUN_TWO_SETS = 112
+
+
+def _scratch_allowed(kernel_name: str) -> int:
+    """kernel_name: the mangled decode_kernel<BK, BV, R, NW, BF, NCK, NCV, KSEQ, PAGED, ROTV> instance."""
+    m = re.search(r"decode_kernelILi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)ELb(\d)ELi(\d)ELi(\d)ELb(\d)ELb(\d)ELb(\d)", kernel_name)
+    if not m:
+        return 0
+    bk, _bv, _r, _nw, _bf, _nck, ncv, kseq, _paged, _rotv = (int(x) for x in m.groups())
+    return SCRATCH_ALLOWED_TWO_RUN_TWO_SETS if (bk in (3, 6) and kseq == 1 and ncv == 2) else 0
+
+
 # (source, object name, extra flags).  The quantizer must round every operation once: no contraction.
 UNITS = [("kvq_api.hip", "kvq_api.o", []),
          ("kvq_quant.hip", "kvq_quant.o", ["-ffp-contract=off"]),
@@ -45,8 +56,11 @@ def _compile(item):
     log = r.stdout + r.stderr
     if r.returncode == 0 and "-Rpass-analysis=kernel-resource-usage" in extra:
         # a decode kernel that spills would wait on scratch reloads in the middle of its load pipeline: refuse it
-        sizes = [int(m) for m in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", log)]
-        spills = [b for b in sizes if b > SCRATCH_ALLOWED.get(objname, 0)]
+        spills = []
+        for block in re.split(r"Function Name: ", log)[1:]:
+            m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", block)
+            if m and int(m.group(1)) > _scratch_allowed(block.split()[0]):
+                spills.append(int(m.group(1)))
         if spills:
             return objname, 1, f"{len(spills)} decode kernel(s) use scratch memory (register spills, up to {max(spills)} bytes per lane)", obj
         log = "\n".join(l for l in log.splitlines() if "remark:" not in l)

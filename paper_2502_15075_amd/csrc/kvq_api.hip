@@ -50,6 +50,7 @@ kvq_status check_cache(const kvq_layout* L, const kvq_cache* c) {
   if (L->axis_k == KVQ_AXIS_SEQ && (!c->k_resid || !c->v_resid || !aligned16(c->k_resid) || !aligned16(c->v_resid)))
     return KVQ_ERR_INVALID_ARG;
   if (L->page_tokens && (!c->page_table || (reinterpret_cast<uintptr_t>(c->page_table) & 3u))) return KVQ_ERR_INVALID_ARG;
+  if (L->bits_v != 16 && (!c->v_scale_exp || (reinterpret_cast<uintptr_t>(c->v_scale_exp) & 3u))) return KVQ_ERR_INVALID_ARG;
   return KVQ_OK;
 }
 

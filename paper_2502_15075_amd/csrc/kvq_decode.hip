@@ -165,7 +165,7 @@ template <int BV> __device__ __forceinline__ constexpr float v_hi_factor(int v) 
 // Softmax weights are carried times 2^p_shift and divided by 2^shift of their slot: the largest of them is 2^10 (binary16
 // headroom for weight x value scale up to 64), so p_shift is 10 plus the smallest slot shift, where the high part's
 // slots count with their shift minus LO (their weights carry 2^LO).  The scale of a 1-bit group is its whole range:
-// two bits more headroom (scale up to 255).
+// two bits more headroom (scale up to 255).  Larger scales: see weight_headroom.
 template <int BV> constexpr float p_shift() {
   int m = field_slot_shift<v_lo<BV>()>(0);
   if (v_hi<BV>()) {
@@ -210,8 +210,7 @@ constexpr int ring_stages() {
   constexpr int less = (NCK == 2 ? 2 : 0) + (NCV == 2 ? 1 : 0)    // a second column set costs registers (query operand,
                        + (code_hi_bits<BK>() ? 1 : 0)              // scale/zero entries, weights), so does a high run
                        + (code_hi_bits<BV>() ? 1 : 0)              // of keys or a high part of values (its weights)
-                       + (ROTV && code_hi_bits<BK>() && BV == 8 ? 1 : 0)   // (rotated values: the unrounded weights stay
-                                                                           // live; two runs of keys, the widest values)
+                       + (ROTV ? 1 : 0)                            // (rotated values: the unrounded weights stay live)
                        + (BK == 2 && regs >= 16 ? 1 : 0);         // (moved 2-bit fields: two shifted copies of a word live)
   return base - less >= 1 ? base - less : 1;
 }
@@ -315,7 +314,23 @@ struct WaveState {
   float noff[4];        // p_shift - m - v_slot_shift(v): exponent offset of the slots in operand register v
   float l[4];           // per register class v: this lane's share of sum_t p * 2^(p_shift - shift(v))
   float zacc[NCV][4];   // same, weighted by zV[t, g] for this lane's value group of each column set
+  float headroom;       // the running maximum is kept this far (in log2 units) above the largest logit seen, which holds
+                        // every weight below 2^-headroom of its usual size (see weight_headroom); wave-uniform
 };
+
+// The softmax weights go into the matrix unit as binary16 products p * 2^p_shift * scale_V, and the largest of them
+// (p = 1 at the running maximum) stays finite only for value scales below 2^(16 - p_shift) = 64 (256 for 1-bit values),
+// i.e. for groups whose range is below 64 (2^b - 1) -- while inputs may be as large as binary16 goes.  The append
+// kernels therefore keep, per (batch, kv head), the largest exponent field of any value scale they have stored
+// (kvq_cache.v_scale_exp), and an attention launch over a stream that holds a scale of 64 or more holds ALL its
+// weights down: the running maximum stays (that exponent - 5) above the logits, which divides every weight and every
+// sum by that power of two (the final division by the sum of weights takes it out again).  What it costs is resolution
+// of the smallest weights, which such a stream can spare: they multiply values of the same large scale.  Nothing of
+// this is in the loop: the offset rides in the multiply-add that turns a logit into log2 units.
+template <int BV> __device__ __forceinline__ float weight_headroom(int scale_exp_field) {
+  const int need = scale_exp_field - 15 - (BV == 1 ? 7 : 5);   // scales below 2^6 (1-bit values: 2^8) need nothing
+  return (float)(need < 0 ? 0 : need > 16 ? 16 : need);
+}
 
 // binary16 product of a binary32 weight and the binary16 held in the low half of `meta`, written to the
 // low / high half of `dst` (one rounding: the compiler turns the fused multiply-add with a converted operand and the
@@ -547,9 +562,9 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
     valid[i] = !MASKED || (step * 32 + 16 * (i >> 2) + 4 * L.j + (i & 3) < seq_len);
     if (MASKED && !valid[i]) s[i] = kNegBig;
   }
-  // ---- running max: only when some lane sees a larger logit than its current max
+  // ---- running max (kept st.headroom above the logits): only when some lane sees a larger logit than its current max
   float lmax = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-  float lx = lmax * kappa;
+  float lx = fmaf(lmax, kappa, st.headroom);
   if (__any(lx > st.m)) {
     lx = fmaxf(lx, __shfl_xor(lx, 16));
     lx = fmaxf(lx, __shfl_xor(lx, 32));
@@ -625,6 +640,11 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
       }
     }
   }
+  // (Nothing is scheduled across this point.  The matrix instructions below cannot start before the weights are
+  // complete anyway; left free, the scheduler pulls the unpacking of the value codes up into the softmax arithmetic,
+  // which costs the kernel a dozen registers it does not have: with the fence no instance of the token-wise kernels
+  // spills, without it most do.)
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) {
     constexpr int kDtPerSet = 8 / NCV;           // value groups of set 0 own the first d-tiles, of set 1 the rest
@@ -646,17 +666,20 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
 // Record layout in the workspace: [b][hq][split] x (kHeadDim + 4) floats = acc[128], m, l, 0, 0.
 constexpr int kRec = kHeadDim + 4;
 
-// Quantize the one new token of this (b,h) and store it at position pos = seq_len-1: the first 16 lanes take the key
-// row, the next 16 the value row (8 channels per lane).  Same arithmetic and bytes as the bulk quantize-append kernel.
-// Value codes go to `vstage` (128 bytes of LDS); after a barrier append_one_values() puts them into the block.
+// Fused decode step, first half: quantize the one new token of this (b,h) and store it at row t of the planes.  The
+// first 16 lanes take the key row, the next 16 the value row (8 channels per lane; `raw` holds the lane's 16 input
+// bytes, loaded by the caller).  Same arithmetic and bytes as the bulk quantize-append kernel.  The key codes and both
+// scale/zero entries go to memory from here; the value codes go to `vstage` (128 bytes of LDS), from where the threads
+// that own the block's words insert them after a barrier.  The reconstructed rows (code * scale + zero, one rounding as
+// in App. B "Dequantization") go to `hat` (LDS: 128 key elements, then 128 value elements): the new token joins the
+// attention from there, not from the cache.  bh: stream index in the planes (0 when paged: t is then a row number in
+// plane order); sbh: the (batch, kv head) pair, for the stream's largest value-scale exponent.
 template <int BK, int BV>
-__device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, int hk, int tid, uint8_t* vstage, int64_t t) {
+__device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int sbh, int tid, u32x4 raw, uint8_t* vstage, int64_t t,
+                                           float* hat) {
   const Geom& g = a.g;
-  if (tid >= 32) return;
   const bool is_v = tid >= 16;
   const int lane16 = tid & 15, d0 = lane16 * 8;
-  const uint16_t* src = (is_v ? a.v_new : a.k_new) + (int64_t)b * a.nsb + (int64_t)hk * a.nsh + d0;
-  const u32x4 raw = *reinterpret_cast<const u32x4*>(src);
   const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
   float x[8];
 #pragma unroll
@@ -676,7 +699,11 @@ __device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, i
   const int G = is_v ? g.g_v : g.g_k, ng = is_v ? g.ng_v : g.ng_k;
   const int lpg = G >> 3;
   quantize8(x, bits, lpg, codes, &S, &Z);
-  uint32_t* meta = (uint32_t*)((uint8_t*)(is_v ? a.cache.v_meta : a.cache.k_meta) + (int64_t)bh * (is_v ? g.vm_stream : g.km_stream));
+  if (is_v && (lane16 & (lpg - 1)) == 0) note_value_scale(a.cache.v_scale_exp + sbh, S);
+  // (picked by integer arithmetic: a per-lane choice among pointers of the argument block becomes a lookup in private memory)
+  const uintptr_t km = reinterpret_cast<uintptr_t>(a.cache.k_meta) + (uintptr_t)((int64_t)bh * g.km_stream);
+  const uintptr_t vm = reinterpret_cast<uintptr_t>(a.cache.v_meta) + (uintptr_t)((int64_t)bh * g.vm_stream);
+  uint32_t* meta = reinterpret_cast<uint32_t*>(km + (is_v ? vm - km : (uintptr_t)0));
   if ((lane16 & (lpg - 1)) == 0) meta[meta_index(t, lane16 >> lpg_shift(lpg), ng)] = (uint32_t)S | ((uint32_t)Z << 16);
   if (!is_v) {
     store_key_codes<BK>((uint8_t*)a.cache.k_codes + (int64_t)bh * g.kc_stream + t * (16 * BK), lane16, codes);
@@ -684,36 +711,35 @@ __device__ __forceinline__ void append_one(const DecodeArgs& a, int bh, int b, i
 #pragma unroll
     for (int e = 0; e < 8; ++e) vstage[d0 + e] = (uint8_t)codes[e];
   }
+  const float sc = widen16(S, false), zp = widen16(Z, false);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) hat[(is_v ? kHeadDim : 0) + d0 + e] = fmaf((float)codes[e], sc, zp);   // (exact product: one rounding)
 }
 
-// Second half of the fused append: thread d < 128 inserts channel d's code of token seq_len-1 into its 32-bit word
-// (read-modify-write; the other fields of the word belong to other tokens of the same 32-token block).  With 2-bit
-// fields channels d and d+16 share a word (with 1-bit fields d, d+16, d+32 and d+48), so the thread of the first of
-// those 16-channel tiles writes them all.  `blk`: a block of B-bit fields; the field is bits [shift, shift + B) of the
-// staged code.
-template <int B>
-__device__ __forceinline__ void append_fields(uint32_t* blk, int tid, const uint8_t* vstage, int u, int shift) {
-  constexpr int NF = B == 1 ? 4 : B == 2 ? 2 : 1;         // 16-channel tiles with a field in the same word
-  if (tid >= kHeadDim || ((tid >> 4) & (NF - 1))) return;
-  const uint32_t fmask = (1u << B) - 1u;
+// Second half of the fused append: thread d < 128 inserts channel d's code of the new token into its 32-bit word of
+// the 32-token block (the other fields of the word belong to other tokens of the block and keep their bits).  With
+// 2-bit fields channels d and d+16 share a word (with 1-bit fields d, d+16, d+32 and d+48), so the thread of the first
+// of those 16-channel tiles owns the word.  The word is loaded at the top of the kernel (field_word), long before the
+// codes exist, and stored from here.  `shift`: the field is bits [shift, shift + B) of the staged code.
+template <int B> constexpr int field_tiles() { return B == 1 ? 4 : B == 2 ? 2 : 1; }   // 16-channel tiles per word
+template <int B> __device__ __forceinline__ bool field_owner(int tid) {
+  return tid < kHeadDim && !((tid >> 4) & (field_tiles<B>() - 1));
+}
+template <int B> __device__ __forceinline__ int field_word(int tid, int u) {
   int dw, bit;
-  v_field(u, tid, B, &dw, &bit);
-  uint32_t w = blk[dw];
+  v_field(u, tid & (kHeadDim - 1), B, &dw, &bit);
+  return dw;
+}
+template <int B>
+__device__ __forceinline__ uint32_t field_insert(uint32_t w, int tid, const uint8_t* vstage, int u, int shift) {
+  const uint32_t fmask = (1u << B) - 1u;
 #pragma unroll
-  for (int f = 0; f < NF; ++f) {
+  for (int f = 0; f < field_tiles<B>(); ++f) {
     int dwf, bitf;
     v_field(u, tid + 16 * f, B, &dwf, &bitf);             // same word, the neighbouring tiles' fields
     w = (w & ~(fmask << bitf)) | ((((uint32_t)vstage[tid + 16 * f] >> shift) & fmask) << bitf);
   }
-  blk[dw] = w;
-}
-template <int BV>
-__device__ __forceinline__ void append_one_values(const DecodeArgs& a, int bh, int tid, const uint8_t* vstage, int64_t t) {
-  constexpr int VLO = v_lo<BV>(), VHI = v_hi<BV>();
-  const Geom& g = a.g;
-  uint32_t* blk = (uint32_t*)((uint8_t*)a.cache.v_codes + (int64_t)bh * g.vc_stream) + (t >> 5) * (int64_t)(128 * BV);
-  append_fields<VLO>(blk, tid, vstage, (int)(t & 31), 0);
-  if constexpr (VHI != 0) append_fields<VHI>(blk + 128 * VLO, tid, vstage, (int)(t & 31), VLO);
+  return w;
 }
 
 // Final output of rotated values: the normalized row sits in the rotated basis (LDS, 128 floats); 16 threads take it
@@ -757,7 +783,9 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   // channel-wise keys: the query in binary32, channel d divided by k_chan_scale(d); row R is all zero
   __shared__ __attribute__((aligned(16))) float sm_qf[KSEQ ? R + 1 : 1][kHeadDim];
   __shared__ __attribute__((aligned(16))) uint8_t sm_meta[NW][1024];
-  __shared__ uint8_t sm_vnew[kHeadDim];
+  __shared__ uint8_t sm_vnew[kHeadDim];          // fused step: the new token's value codes,
+  __shared__ float sm_hat[2][kHeadDim];           // its reconstructed key and value rows,
+  __shared__ float sm_mnew[R];                    // and its logit per head in log2 units
   __shared__ float sm_qsum[R][4];
   const Geom& g = a.g;
   const kvq_cache& cache = a.cache;
@@ -807,13 +835,25 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
     L.meta_lds = &sm_meta[wave][0];
   }
 
-  // ---- this wavefront's steps: step_begin + wave, +4, ...; start filling the ring right away
-  const int n_steps = (seq_len + 31) >> 5;
+  // ---- what this launch reads.  A fused decode step does not read its new token (position seq_len - 1) back from the
+  // cache: the workgroup that owns that position quantizes and stores it, and adds it to the attention as one more
+  // partial record, computed from the reconstruction it holds in registers (no store -> load round trip, no fence).
+  constexpr bool kCanAppend = !RAW && !KSEQ;
+  const bool fused = kCanAppend && a.k_new != nullptr;
+  const int n_att = fused ? seq_len - 1 : seq_len;        // tokens attended through the cache planes
+  const int n_steps = (n_att + 31) >> 5;
   const int step_begin = split * steps_per_split;
   const int step_end = min(step_begin + steps_per_split, n_steps);
+  const bool do_append = fused && split == ((seq_len + 31) / 32 - 1) / steps_per_split;   // uniform over the workgroup
+  // this wavefront's steps: step_begin + wave, + NW, ...; the last one may be the ragged tail of the sequence
   const int first = step_begin + SPB * wave;
   auto step_of = [&](int i) { return KSEQ ? first + 2 * NW * (i >> 1) + (i & 1) : first + NW * i; };
   const int n_my = first < step_end ? SPB * ((step_end - first + SPB * NW - 1) / (SPB * NW)) : 0;
+  const bool ragged = (n_att & 31) != 0;
+  const bool own_tail = ragged && n_my > 0 && step_of(n_my - 1) == n_steps - 1;
+  const int n_full = own_tail ? n_my - 1 : n_my;   // complete steps of this wavefront
+  // A step that is always there to load from: wavefronts with nothing to do still issue the ring's loads (see refill).
+  const int safe_step = min(step_begin, max(n_steps - 1, 0));
   // paged: logical step -> step number in plane order (page of the pool, this head's share of it, step inside it)
   // (this workgroup's slice of its table row is copied to LDS first: a page number is needed before every step's
   // loads can be issued, and a global load in front of them costs the ring most of its depth)
@@ -821,8 +861,9 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   __shared__ int32_t sm_pages[kPageSlots];
   const int32_t* __restrict__ my_pages = PAGED ? cache.page_table + (int64_t)b * g.pages_per_seq : nullptr;
   const int step_shift = g.page_shift - 5;
-  const int page0 = step_begin >> step_shift;
-  const int n_pages_mine = step_end > step_begin ? ((step_end - 1) >> step_shift) - page0 + 1 : 0;
+  const int page0 = safe_step >> step_shift;
+  const int last_needed = max(max(step_end - 1, safe_step), do_append ? (seq_len - 1) >> 5 : 0);
+  const int n_pages_mine = (last_needed >> step_shift) - page0 + 1;
   const bool pages_in_lds = n_pages_mine <= kPageSlots;
   if constexpr (PAGED) {
     if (pages_in_lds) {
@@ -830,52 +871,80 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
       __syncthreads();
     }
   }
+  auto page_of_step = [&](int step) -> int64_t {
+    return pages_in_lds ? sm_pages[(step >> step_shift) - page0] : my_pages[step >> step_shift];
+  };
   auto fetch = [&](StepRegs<BK, BV>& dst, int step, uint32_t lane_mask = ~0u) {
     if constexpr (PAGED) {
-      const int64_t page = pages_in_lds ? sm_pages[(step >> step_shift) - page0] : my_pages[step >> step_shift];
-      load_step<BK, BV, true>(dst, L, ((page * g.kv_heads + hk) << step_shift) + (step & ((1 << step_shift) - 1)), lane_mask);
+      load_step<BK, BV, true>(dst, L, ((page_of_step(step) * g.kv_heads + hk) << step_shift) + (step & ((1 << step_shift) - 1)), lane_mask);
     } else {
       load_step<BK, BV>(dst, L, step, lane_mask);
     }
   };
-  const bool ragged = (seq_len & 31) != 0;
-  const bool own_tail = ragged && n_my > 0 && step_of(n_my - 1) == n_steps - 1;
-  const int n_full = own_tail ? n_my - 1 : n_my;   // complete steps of this wavefront
-  // fused decode step: the owner of the last step writes the new token first.  When the ring's first loads cannot
-  // reach that step they are started before the (short) quantization, otherwise after it.
-  const bool do_append = !RAW && !KSEQ && a.k_new != nullptr && split == (n_steps - 1) / steps_per_split;
-  const bool early = !do_append || n_my > kStages;
-  // register ring of kStages steps
-  // Ring slot k is refilled with the wavefront's i-th step; past its last complete step the loads are still issued, at
-  // that last step and collapsed to one cache line each (see load_step), so that no load of the ring is conditional.
-  StepRegs<BK, BV> buf[kStages];
-  auto refill = [&](int k, int i) { fetch(buf[k], step_of(min(i, n_full - 1)), i < n_full ? ~0u : 0u); };
-  auto fill_ring = [&]() {
-    if (n_full > 0) {
-#pragma unroll
-      for (int k = 0; k < kStages; ++k) refill(k, k);
+
+  // ---- the small loads of the prologue go first, none of them behind a branch, so that they return ahead of the
+  // ring's first fill and the compiler can count what is in flight behind each: the query rows (every thread loads;
+  // threads beyond the rows re-read the first 16 bytes), and in a fused step the new token's rows and the words of the
+  // value block that take its codes (threads that have none of these re-read the query).
+  int stream_scale_exp = 0;                        // largest exponent field of the stream's value scales (weight_headroom)
+  if constexpr (!RAW) stream_scale_exp = cache.v_scale_exp[bh];
+  const int r_act = a.heads_per_kv;                // heads that exist (R is the next power of two)
+  const bool q_lane = tid < R * 16 && (tid >> 4) < r_act;
+  const uint16_t* qsrc = q + ((int64_t)b * q_heads + hk * r_act) * kHeadDim + (q_lane ? tid * 8 : 0);
+  u32x4 qraw = *reinterpret_cast<const u32x4*>(qsrc);
+  constexpr int VLO_ = v_lo<BV>(), VHI_ = v_hi<BV>();
+  u32x4 nraw = u32x4{0u, 0u, 0u, 0u};
+  uint32_t vw_lo = 0u, vw_hi = 0u;
+  uint32_t* vw_lo_p = nullptr; uint32_t* vw_hi_p = nullptr;
+  int64_t t_new = 0;
+  int u_new = 0;                                   // the new token's place in its 32-token block
+  if constexpr (kCanAppend) {
+    // (paged: the new token's row number in plane order, with the stream index 0)
+    if constexpr (PAGED) {
+      const int64_t pg = do_append ? page_of_step((seq_len - 1) >> 5) : 0;
+      t_new = ((pg * g.kv_heads + hk) << g.page_shift) + ((seq_len - 1) & ((1 << g.page_shift) - 1));
+    } else {
+      t_new = seq_len - 1;
     }
-  };
-  if (early) fill_ring();
-  if (do_append) {                                 // uniform over the workgroup
-    if constexpr (!RAW) {
-      // (paged: the new token's row number in plane order, with the stream index 0)
-      const int64_t t_new = PAGED ? virtual_token(g, cache.page_table, b, hk, seq_len - 1) : (int64_t)seq_len - 1;
-      append_one<BK, BV>(a, PAGED ? 0 : bh, b, hk, tid, sm_vnew, t_new);
-      __syncthreads();
-      append_one_values<BV>(a, PAGED ? 0 : bh, tid, sm_vnew, t_new);
+    // (the address is picked by integer arithmetic: a per-lane choice among pointers held in the argument block would
+    // be turned into a lookup in private memory)
+    const bool new_lane = do_append && tid < 32;
+    const int64_t row_off = ((int64_t)b * a.nsb + (int64_t)hk * a.nsh + (tid & 15) * 8) * 2;
+    const uintptr_t qp = reinterpret_cast<uintptr_t>(qsrc), kp = reinterpret_cast<uintptr_t>(a.k_new),
+                    vp = reinterpret_cast<uintptr_t>(a.v_new);
+    const uintptr_t nsrc = qp + (new_lane ? (kp - qp) + (tid >= 16 ? vp - kp : (uintptr_t)0) + (uintptr_t)row_off : (uintptr_t)0);
+    nraw = *reinterpret_cast<const u32x4*>(nsrc);
+    uint32_t* vblk = (uint32_t*)((uint8_t*)cache.v_codes + bh_base * g.vc_stream) + (t_new >> 5) * (int64_t)(128 * BV);
+    u_new = (int)(t_new & 31);
+    vw_lo_p = do_append && field_owner<VLO_>(tid) ? vblk + field_word<VLO_>(tid, u_new) : nullptr;
+    vw_lo = *(vw_lo_p ? vw_lo_p : reinterpret_cast<const uint32_t*>(qsrc));
+    if constexpr (VHI_ != 0) {
+      vw_hi_p = do_append && field_owner<VHI_>(tid) ? vblk + 128 * VLO_ + field_word<VHI_>(tid, u_new) : nullptr;
+      vw_hi = *(vw_hi_p ? vw_hi_p : reinterpret_cast<const uint32_t*>(qsrc));
     }
-    __threadfence_block();                         // writer and readers share this workgroup: a workgroup-scope
-                                                   // release is enough (no L2 write-back/invalidate across XCDs)
   }
 
-  // ---- query rows of this kv head -> LDS (one coalesced 16-byte load per thread), then per-lane operands
+  // ---- register ring of kStages steps, filled right away.
+  // Ring slot k is refilled with the wavefront's i-th step (the ragged tail included); past its last step the loads
+  // are still issued, at that last step (or at safe_step for a wavefront that has none) and collapsed to one cache line
+  // each (see load_step), so that no load of the ring is conditional.
+  StepRegs<BK, BV> buf[kStages];
+  auto refill = [&](int k, int i) {
+    fetch(buf[k], n_my > 0 ? step_of(min(i, n_my - 1)) : safe_step, i < n_my ? ~0u : 0u);
+  };
+#pragma unroll
+  for (int k = 0; k < kStages; ++k) refill(k, k);
+
+  // ---- fused step: quantize the new token (two 16-lane rows of the first wavefront), store keys and scale/zero, stage
+  // the value codes for the threads that own the block's words
+  if constexpr (kCanAppend) {
+    if (do_append && tid < 32) append_one<BK, BV>(a, PAGED ? 0 : bh, bh, tid, nraw, sm_vnew, t_new, &sm_hat[0][0]);
+  }
+
+  // ---- query rows of this kv head -> LDS, then per-lane operands
   bool q_is_bf16 = q_bf16 != 0;
-  const int r_act = a.heads_per_kv;                // heads that exist (R is the next power of two)
   if (tid < R * 16) {
-    u32x4 raw = u32x4{0u, 0u, 0u, 0u};             // a surplus head is an all-zero query: uniform weights, never stored
-    if ((tid >> 4) < r_act)
-      raw = *reinterpret_cast<const u32x4*>(q + ((int64_t)b * q_heads + hk * r_act) * kHeadDim + tid * 8);
+    u32x4 raw = q_lane ? qraw : u32x4{0u, 0u, 0u, 0u};   // a surplus head is an all-zero query: uniform weights, never stored
     if constexpr (!RAW) {
       if (g.rotate_k) {
         // rotated keys: the scores need R q, rounded once to binary16 (16 threads hold one query row, 8 channels each)
@@ -914,10 +983,31 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   if constexpr (KSEQ) { if (tid < kHeadDim) sm_qf[R][tid] = 0.f; }
   if constexpr (!RAW) q_is_bf16 = q_is_bf16 && !g.rotate_k;      // the staged rotated query is binary16
   __syncthreads();
-  if (!early) fill_ring();
   auto widen = [&](uint16_t bits) -> float {
     return q_is_bf16 ? __uint_as_float((uint32_t)bits << 16) : (float)__builtin_bit_cast(_Float16, bits);
   };
+  // ---- fused step, second half: the value codes go into their words (loaded at the top), and the new token becomes a
+  // partial record of its own: logit of every head against the reconstructed key row (maximum = that logit, sum = one
+  // weight of 1, accumulator = the reconstructed value row), which the merge below adds to the wavefronts' records
+  if constexpr (kCanAppend) {
+    if (do_append) {                               // uniform over the workgroup
+      if (vw_lo_p) *vw_lo_p = field_insert<VLO_>(vw_lo, tid, sm_vnew, u_new, 0);
+      if constexpr (VHI_ != 0) {
+        if (vw_hi_p) *vw_hi_p = field_insert<VHI_>(vw_hi, tid, sm_vnew, u_new, VLO_);
+      }
+      if (tid < R * 16) {                            // 16 threads per head: 8 channels each, then a sum over the 16
+        const int hh = tid >> 4, lane16 = tid & 15;
+        const u32x4 qv = *reinterpret_cast<const u32x4*>(&sm_q[hh][8 * lane16]);
+        const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
+        float part = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part = fmaf(widen((uint16_t)(qw[e >> 1] >> (16 * (e & 1)))), sm_hat[0][8 * lane16 + e], part);
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) part += __shfl_xor(part, off, 16);
+        if (lane16 == 0) sm_mnew[hh] = part * (softmax_scale * kLog2e);
+      }
+    }
+  }
   // column c of set cs carries head h restricted to key group grp + cs*kSetGroups (zero elsewhere); this lane's 32
   // channels are 32j..32j+31 and lie in one group
   constexpr int KLO = k_lo<BK>(), KHI = k_hi<BK>();
@@ -967,6 +1057,8 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) st.acc[dt] = float4v{0.f, 0.f, 0.f, 0.f};
   st.m = kNegBig;
+  st.headroom = 0.f;
+  if constexpr (!RAW) st.headroom = weight_headroom<BV>(stream_scale_exp);
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
     st.l[v] = 0.f; st.noff[v] = 0.f;
@@ -982,11 +1074,16 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   auto full_step = [&](int k, int i) {
     if constexpr (KSEQ) {                        // an even step of this wavefront's sequence starts a block (uniform;
       const int odd = kStages % 2 == 0 ? (k & 1) : (i & 1);      // with an even ring it is the ring slot's parity)
-      if (odd) compute_step<BK, BV, R, BF, NCK, NCV, false, false>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
-      else compute_step<BK, BV, R, BF, NCK, NCV, false, true>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), seq_len, ks, qrow, grp == 1 ? 1.0f : 0.0f);
+      if (odd) compute_step<BK, BV, R, BF, NCK, NCV, false, false>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), n_att, ks);
+      else compute_step<BK, BV, R, BF, NCK, NCV, false, true>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), n_att, ks, qrow, grp == 1 ? 1.0f : 0.0f);
     } else {
-      compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), seq_len, ks);
+      compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), n_att, ks);
     }
+  };
+  // the ragged tail of the sequence out of ring slot k (it came through the ring like every other step): masked
+  auto tail_step = [&](int k) {
+    if constexpr (!KSEQ)
+      compute_step<BK, BV, R, BF, NCK, NCV, true>(buf[k], qb, qbh, qsum_u, kappa, st, L, n_steps - 1, n_att, ks);
   };
   int it = 0;
   for (; it + kStages <= n_full; it += kStages) {
@@ -997,13 +1094,13 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
     }
   }
 #pragma unroll
-  for (int k = 0; k < kStages - 1; ++k)         // the last few complete steps are already in the ring
+  for (int k = 0; k < kStages - 1; ++k)          // the last few complete steps are already in the ring,
     if (it + k < n_full) full_step(k, it + k);
-  if constexpr (!KSEQ) {
-    if (own_tail) {                               // ragged last step of the sequence: masked
-      fetch(buf[0], n_steps - 1);
-      compute_step<BK, BV, R, BF, NCK, NCV, true>(buf[0], qb, qbh, qsum_u, kappa, st, L, n_steps - 1, seq_len, ks);
-    }
+  if (own_tail) {                                 // and so is the tail, in the slot after them
+    const int kt = n_full - it;
+#pragma unroll
+    for (int k = 0; k < kStages; ++k)
+      if (kt == k) tail_step(k);
   }
 
   // ---- wavefront totals: l and zacc over register classes and the 4 lane groups j; then this lane's output rows
@@ -1040,12 +1137,18 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
     float M = sm_m[0][hh];
 #pragma unroll
     for (int w = 1; w < NW; ++w) M = fmaxf(M, sm_m[w][hh]);
+    if (do_append) M = fmaxf(M, sm_mnew[hh]);
     float o = 0.f, ll = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
       const float f = exp2f(sm_m[w][hh] - M);
       o = fmaf(f, sm_o[w][hh][d], o);
       ll = fmaf(f, sm_l[w][hh], ll);
+    }
+    if (do_append) {                               // the new token: one weight of 1 (records carry their sums times 2^10)
+      const float f = 1024.0f * exp2f(sm_mnew[hh] - M);
+      o = fmaf(f, sm_hat[1][d], o);
+      ll += f;
     }
     if (hh >= r_act) continue;
     const int64_t hq = (int64_t)b * q_heads + hk * r_act + hh;
@@ -1215,10 +1318,12 @@ hipError_t KVQ_CAT(launch_decode_inst_, KVQ_INST_BK, KVQ_INST_BV)(int R, const D
 
 #else
 // ---- dispatcher translation unit ----------------------------------------------------------------------------------------
+#ifndef KVQ_FOR_EACH_PAIR      // (a development build may name fewer pairs on the command line)
 #define KVQ_FOR_EACH_PAIR(X) X(4, 2) X(2, 4) X(4, 4) X(8, 8) X(2, 2) X(8, 4) X(8, 2) X(4, 8) X(2, 8) X(16, 16) \
   X(3, 2) X(3, 4) X(3, 8) X(6, 2) X(6, 4) X(6, 8) X(1, 2) X(1, 4) X(1, 8) \
   X(1, 1) X(2, 1) X(3, 1) X(4, 1) X(6, 1) X(8, 1) \
   X(1, 3) X(2, 3) X(3, 3) X(4, 3) X(6, 3) X(8, 3) X(1, 6) X(2, 6) X(3, 6) X(4, 6) X(6, 6) X(8, 6)
+#endif
 #define KVQ_DECL(BK_, BV_) \
   hipError_t KVQ_CAT(launch_decode_inst_, BK_, BV_)(int R, const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream);
 KVQ_FOR_EACH_PAIR(KVQ_DECL)

@@ -199,7 +199,10 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
         if (g.rotate_v) rotate8(x, lane16, rot_sign_bits(g.signs_v, lane16));
         uint16_t S, Z;
         quantize8(x, BV, lpg_v, codes, &S, &Z);
-        if ((lane16 & (lpg_v - 1)) == 0) vm[it * vm_step] = (uint32_t)S | ((uint32_t)Z << 16);
+        if ((lane16 & (lpg_v - 1)) == 0) {
+          vm[it * vm_step] = (uint32_t)S | ((uint32_t)Z << 16);
+          note_value_scale(c.v_scale_exp + bh, S);
+        }
       }
       stage_value_row<BV>(vstage, row, d0, codes);
     }
@@ -351,7 +354,10 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
     uint16_t S, Z;
     const int lpg = g.g_v >> 3;
     quantize8(xv, BV, lpg, vcodes, &S, &Z);
-    if ((lane16 & (lpg - 1)) == 0) vm[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
+    if ((lane16 & (lpg - 1)) == 0) {
+      vm[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
+      note_value_scale(c.v_scale_exp + bh, S);
+    }
     stage_value_row<BV>(vstage, row, d0, vcodes);
   }
   __syncthreads();

@@ -247,6 +247,14 @@ __device__ __forceinline__ void quantize8(const float x[8], int bits, int lanes_
   }
 }
 
+// Value scales of 64 and more (a group range of 64 (2^b - 1) and up: legal, far from anything a model produces) need
+// room in the attention kernel's binary16 weights.  Every kernel that stores a value scale raises the stream's entry of
+// kvq_cache.v_scale_exp to the scale's exponent field when it is that large (a rare atomic; ordinary scales cost one
+// comparison per group).  S: the stored binary16 pattern.
+__device__ __forceinline__ void note_value_scale(int32_t* stream_exp, uint16_t S) {
+  if (S >= 0x5400u) atomicMax(stream_exp, (int32_t)(S >> 10));      // 0x5400 = 64.0
+}
+
 // The same quantizer for a group that is not spread over neighbouring lanes (channel-wise key groups: the group runs
 // over tokens): stored scale/zero patterns from the group's minimum and maximum, then one code at a time.
 __device__ __forceinline__ void group_scale_zero(float mn, float mx, int bits, uint16_t* S, uint16_t* Z) {

@@ -36,7 +36,8 @@ class _CLayout(C.Structure):
 
 
 class _CCache(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_meta", "v_codes", "v_meta", "k_resid", "v_resid", "page_table")]
+    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_meta", "v_codes", "v_meta", "k_resid", "v_resid", "page_table",
+                                          "v_scale_exp")]
 
 
 _lib = None
@@ -157,10 +158,24 @@ class Cache:
         mk = (lambda n: torch.empty(n, dtype=torch.uint8, device=device)) if fill is None else \
              (lambda n: torch.full((n,), fill, dtype=torch.uint8, device=device))
         self.planes = [mk(n) if n else None for n in sizes]
+        # per (batch, kv head): largest exponent field of the value scales of 64 and more stored so far; starts at zero
+        self.v_scale_exp = torch.zeros(layout.batch * layout.kv_heads, dtype=torch.int32, device=device)
 
     def c(self) -> _CCache:
         table = getattr(self, "page_table", None)          # int32 device tensor [B, pages per sequence] of a paged cache
-        return _CCache(*[(0 if p is None else p.data_ptr()) for p in self.planes], 0 if table is None else table.data_ptr())
+        return _CCache(*[(0 if p is None else p.data_ptr()) for p in self.planes], 0 if table is None else table.data_ptr(),
+                       self.v_scale_exp.data_ptr())
+
+    def batch_element(self, b: int, layout: "Layout") -> "Cache":
+        """A view of batch element b's share of every plane as a cache of batch 1 (`layout`: this cache's layout with
+        batch = 1; contiguous planes only)."""
+        assert layout.batch == 1 and layout.page_tokens == 0 and self.layout.page_tokens == 0
+        B = self.layout.batch
+        sub = Cache.__new__(Cache)
+        sub.layout = layout
+        sub.planes = [None if p is None else p.view(B, -1)[b] for p in self.planes]
+        sub.v_scale_exp = self.v_scale_exp.view(B, -1)[b]
+        return sub
 
     def nbytes(self) -> int:
         return sum(0 if p is None else p.numel() for p in self.planes)

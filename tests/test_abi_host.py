@@ -124,7 +124,7 @@ def test_call_errors_are_caught_before_any_launch(kvq):
     lib = kvq.load()
     L = kvq.Layout(2, 2, 100)
     cl = L.c()
-    good = kvq._CCache(0x10000, 0x20000, 0x30000, 0x40000)
+    good = kvq._CCache(0x10000, 0x20000, 0x30000, 0x40000, v_scale_exp=0x48000)
     p = C.c_void_p
     def qa(cache, k, v, dt, sb, sh, st, pos, n):
         return lib.kvq_quantize_append(C.byref(cl), C.byref(cache), p(k), p(v), dt, sb, sh, st, pos, n, None)
@@ -134,7 +134,10 @@ def test_call_errors_are_caught_before_any_launch(kvq):
     assert qa(good, 0x50000, 0x60000, 2, 25600, 12800, 128, 0, 1) == kvq.ERR_INVALID_ARG          # fp32 input
     assert qa(good, 0x50002, 0x60000, 0, 25600, 12800, 128, 0, 1) == kvq.ERR_INVALID_ARG          # misaligned rows
     assert qa(good, 0x50000, 0x60000, 0, 25600, 12800, 100, 0, 1) == kvq.ERR_INVALID_ARG          # rows overlap
-    assert qa(kvq._CCache(0x10000, 0, 0x30000, 0x40000), 0x50000, 0x60000, 0, 25600, 12800, 128, 0, 1) == kvq.ERR_INVALID_ARG
+    assert qa(kvq._CCache(0x10000, 0, 0x30000, 0x40000, v_scale_exp=0x48000), 0x50000, 0x60000, 0, 25600, 12800, 128, 0, 1) == kvq.ERR_INVALID_ARG
+    # quantized values need the stream's value-scale exponents (part of the cache's state)
+    assert qa(kvq._CCache(0x10000, 0x20000, 0x30000, 0x40000), 0x50000, 0x60000, 0, 25600, 12800, 128, 0, 1) == kvq.ERR_INVALID_ARG
+    assert qa(kvq._CCache(0x10000, 0x20000, 0x30000, 0x40000, v_scale_exp=0x48002), 0x50000, 0x60000, 0, 25600, 12800, 128, 0, 1) == kvq.ERR_INVALID_ARG
     assert qa(good, 0x50000, 0x60000, 0, 25600, 12800, 128, 100, 0) == kvq.OK                     # empty append: no launch
     Lp = kvq.Layout(2, 2, 100, page_tokens=64, n_pages=8).c()                                       # paged layout without a table
     assert lib.kvq_quantize_append(C.byref(Lp), C.byref(good), p(0x50000), p(0x60000), 0, 25600, 12800, 128, 0, 1, None) == kvq.ERR_INVALID_ARG
@@ -154,7 +157,7 @@ def test_call_errors_are_caught_before_any_launch(kvq):
         assert da(0x50000, 8, 100, 0.1, 0x60000, 2, 0, need) == kvq.ERR_WORKSPACE
     assert da(0x50000, 32, 50, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_UNSUPPORTED         # 16 query heads per kv head
     Lmix = kvq.Layout(2, 2, 100, 128, 16, 2, 64, 64).c()                                          # raw keys, quantized values
-    assert lib.kvq_decode_attention(C.byref(Lmix), C.byref(kvq._CCache(0x10000, 0, 0x30000, 0x40000)), p(0x50000), 0, 8, 50,
+    assert lib.kvq_decode_attention(C.byref(Lmix), C.byref(kvq._CCache(0x10000, 0, 0x30000, 0x40000, v_scale_exp=0x48000)), p(0x50000), 0, 8, 50,
                                     C.c_float(0.1), p(0x60000), 2, p(0x70000), 1 << 20, None) == kvq.ERR_UNSUPPORTED
 
     def ds(pos, k=0x50000):

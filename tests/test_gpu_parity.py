@@ -749,10 +749,7 @@ def test_channelwise_ragged_batch_attention_and_steps(kvq, oracle, R, bk, bv, gv
     # fill sequence b with lens[b] tokens: batches of one on the GPU side as well (views of the planes per batch element)
     for b in range(B):
         L1g = kvq.Layout(1, H, cap, 128, bk, bv, 64, gv, axis_k=kvq.AXIS_SEQ, raw_dtype=1)
-        c1 = kvq.Cache.__new__(kvq.Cache)
-        c1.layout = L1g
-        c1.planes = [p.view(B, -1)[b] for p in cache.planes]
-        c1.page_table = None
+        c1 = cache.batch_element(b, L1g)
         kvq.quantize_append(L1g, c1, Kd[b:b + 1, :, :lens[b]], Vd[b:b + 1, :, :lens[b]], 0)
         L1o, p1 = replace(Lo, batch=1), [p.reshape(B, -1)[b] for p in planes]
         oracle.seq_append(L1o, p1, np.ascontiguousarray(Kb[b:b + 1, :, :lens[b]]), np.ascontiguousarray(Vb[b:b + 1, :, :lens[b]]), 0, bf16=True)
@@ -835,9 +832,7 @@ def test_decode_steps_with_per_sequence_positions(kvq, oracle):
         if n == 0:
             continue
         Lg1 = kvq.Layout(1, H, T, 128, 4, 2, 64, 64)
-        sub = kvq.Cache.__new__(kvq.Cache)
-        sub.layout = Lg1
-        sub.planes = [None if p is None else p.view(B, -1)[b] for p in cache.planes]
+        sub = cache.batch_element(b, Lg1)
         kvq.quantize_append(Lg1, sub, Kd[b:b + 1, :, :n], Vd[b:b + 1, :, :n], 0)
         Lo1, pb = oracle._element(Lo, planes, b)
         oracle.quantize_append(Lo1, pb, np.ascontiguousarray(synth.to_numpy_bits(K[b:b + 1, :, :n])),
@@ -1299,7 +1294,7 @@ def test_paged_rotated_attention(kvq, oracle, R, bk, bv, gk, gv, P, rot, rotv):
 @pytest.mark.parametrize("case", ["uniform", "one_hot", "huge_logits", "wide_values", "tiny_everything", "late_maximum"])
 def test_attention_extremes(kvq, oracle, case):
     """Inputs at the edges of what the kernel's scaled softmax has to carry: all scores equal, one token owning the
-    whole weight, scores in the thousands, value groups at the documented scale limit (range / (2^b - 1) = 32), values
+    whole weight, scores in the thousands, value groups with scales up to 31 (2-bit codes), values
     and keys near the bottom of binary16, and a running maximum that keeps rising until the last token."""
     rng = np.random.default_rng(7)
     B, H, R, T = 1, 2, 4, 1300
@@ -1332,6 +1327,53 @@ def test_attention_extremes(kvq, oracle, case):
             ref = oracle.decode_attention(Lo, planes, qt.numpy(), seq_len, 1 / math.sqrt(128))
             assert np.isfinite(out).all(), (case, bk)
             assert _rel_err(out, ref) < TOL, (case, bk, seq_len, _rel_err(out, ref))
+
+
+@pytest.mark.parametrize("amplitude", [47.0, 50.0, 96.0, 300.0, 3000.0, 32000.0])
+@pytest.mark.parametrize("sharp", [False, True])
+def test_value_scales_beyond_the_weights_binary16_headroom(kvq, oracle, amplitude, sharp):
+    """The attention kernel forms binary16 products of softmax weight (times 2^10) and value scale: a 2-bit group of
+    range 3 x 64 and up meets the end of binary16 when the token carries a large weight.  Values up to the largest
+    binary16 magnitudes are legal input: amplitudes on both sides of that limit (2-bit scale 31, 33, 64, 200, 2000,
+    21000; smaller scales for the wider codes), with flat weights (no product overflows) and with one token owning the
+    weight (p = 1 meets the large scale), in the main loop, the ragged tail and the fused step.  The output must stay
+    finite and inside the same tolerance: the append kernels note the largest scale exponent of every stream, and the
+    attention kernel holds the weights of such a stream down by that many bits.  Some value groups are small on
+    purpose, so that large and ordinary scales meet in one sum."""
+    rng = np.random.default_rng(11)
+    B, H, R, T = 1, 2, 4, 1300 + 21
+    K = rng.standard_normal((B, H, T, 128)).astype(np.float32) * (0.02 if not sharp else 1.0)
+    q = rng.standard_normal((B, H * R, 128)).astype(np.float32)
+    if sharp:
+        K[:, :, 900] = 9.0 * np.sign(q[:, ::R])                       # one key aligned with a head's query: p = 1 there
+        K[:, :, T - 1] = 9.5 * np.sign(q[:, 1::R])                    # ... and the new token of the fused step for another
+    V = rng.uniform(-1, 1, size=(B, H, T, 128)).astype(np.float32) * amplitude
+    V[:, :, ::7] *= 1.0 / amplitude                                   # ordinary groups among the wide ones
+    Kt, Vt, qt = torch.from_numpy(K).to(torch.float16), torch.from_numpy(V).to(torch.float16), torch.from_numpy(q).to(torch.float16)
+    for bk, bv, gv in ((4, 2, 64), (8, 8, 32), (4, 3, 64), (2, 6, 128), (4, 1, 64), (4, 4, 64)):
+        Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, 64, gv)
+        cache, planes = _fill_both(kvq, oracle, Lg, Lo, Kt[:, :, :T - 1], Vt[:, :, :T - 1], [(0, T - 1)])
+        # the append kernel has noted the largest exponent field of the value scales of 64 and more (0: there is none)
+        cap = -(-T // 32) * 32
+        scales = planes[3].view(np.uint16).reshape(B * H, cap // 16, 128 // gv, 16, 2)[..., 0]     # [stream][tile][group][token]
+        written = (np.arange(cap // 16)[:, None, None] * 16 + np.arange(16)[None, None, :]) < T - 1
+        top = (np.where(written[None], scales, 0).reshape(B * H, -1).max(axis=1)).astype(np.int64)
+        want_exp = np.where(top >= 0x5400, top >> 10, 0)
+        assert np.array_equal(cache.v_scale_exp.cpu().numpy(), want_exp), (bk, bv)
+        for seq_len in (T - 1, 950, 901):
+            out = _decode(kvq, Lg, cache, qt, seq_len).cpu().numpy()
+            ref = oracle.decode_attention(Lo, planes, qt.numpy(), seq_len, 1 / math.sqrt(128))
+            assert np.isfinite(out).all(), (bk, bv, seq_len)
+            assert _rel_err(out, ref) < TOL, (bk, bv, seq_len, _rel_err(out, ref))
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, T)), dtype=torch.uint8, device="cuda")
+        out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+        kvq.decode_step(Lg, cache, Kt.cuda()[:, :, T - 1], Vt.cuda()[:, :, T - 1], T - 1, qt.cuda(), 1 / math.sqrt(128), out, ws)
+        torch.cuda.synchronize()
+        oracle.quantize_append(Lo, planes, np.ascontiguousarray(Kt[:, :, T - 1:].numpy()), np.ascontiguousarray(Vt[:, :, T - 1:].numpy()), T - 1)
+        _assert_planes_equal(cache, planes)
+        ref = oracle.decode_attention(Lo, planes, qt.numpy(), T, 1 / math.sqrt(128))
+        assert np.isfinite(out.cpu().numpy()).all(), (bk, bv)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, (bk, bv, _rel_err(out.cpu().numpy(), ref))
 
 
 # --------------------------------------------------------------------------- random configurations
