@@ -51,11 +51,11 @@ __device__ __forceinline__ void stage_value_codes(uint8_t* vstage, int row, int 
 // One thread per 32-bit word of the span (two blocks of 128*BV words, BW words apart in the plane: a block of 3- or
 // 6-bit codes is a block of low parts followed by a block of high parts): assemble the word from the staged codes and
 // store it; when the span is only partly covered by the new tokens [lo, hi), keep the fields of the other tokens.
-template <int BV, int BW = 128 * BV>
+template <int BV, int BW = 128 * BV, int SPAN = kSpan>
 __device__ __forceinline__ void store_value_words(uint32_t* vcp, const uint8_t* vstage, int tid, int lo, int hi) {
   constexpr int F = 32 / BV, P = 16 / BV, ES = BV == 16 ? 2 : 1;
-  const bool full = lo == 0 && hi == kSpan;
-  for (int w = tid; w < 256 * BV; w += 256) {
+  const bool full = lo == 0 && hi == SPAN;
+  for (int w = tid; w < (SPAN / 32) * 128 * BV; w += 256) {
     uint32_t* vc = vcp + (w / (128 * BV)) * (BW - 128 * BV);      // vc[w]: the word's place in the plane
     const uint8_t* sp = vstage + w * F * ES;
     uint32_t bits;
@@ -96,10 +96,10 @@ __device__ __forceinline__ void store_value_words(uint32_t* vcp, const uint8_t* 
 
 // Bytes of LDS that stage the codes of one span: one staging area per part of a code (3- and 6-bit value codes are a
 // low part and a high part, each packed into a block of its own).
-template <int BV> constexpr int stage_area() { return kSpan * kHeadDim * (BV == 16 ? 2 : 1); }
-template <int BV> constexpr int stage_total() { return stage_area<BV>() * (code_hi_bits<BV>() ? 2 : 1); }
+template <int BV, int SPAN = kSpan> constexpr int stage_area() { return SPAN * kHeadDim * (BV == 16 ? 2 : 1); }
+template <int BV, int SPAN = kSpan> constexpr int stage_total() { return stage_area<BV, SPAN>() * (code_hi_bits<BV>() ? 2 : 1); }
 
-template <int BV>
+template <int BV, int SPAN = kSpan>
 __device__ __forceinline__ void stage_value_row(uint8_t* vstage, int row, int d0, const uint32_t codes[8]) {
   constexpr int VLO = code_lo_bits<BV>(), VHI = code_hi_bits<BV>();
   if constexpr (VHI == 0) {
@@ -109,28 +109,30 @@ __device__ __forceinline__ void stage_value_row(uint8_t* vstage, int row, int d0
 #pragma unroll
     for (int e = 0; e < 8; ++e) high[e] = codes[e] >> VLO;
     stage_value_codes<VLO>(vstage, row, d0, codes);
-    stage_value_codes<VHI>(vstage + stage_area<BV>(), row, d0, high);
+    stage_value_codes<VHI>(vstage + stage_area<BV, SPAN>(), row, d0, high);
   }
 }
 
 // vc: the span's first block in the plane
-template <int BV>
+template <int BV, int SPAN = kSpan>
 __device__ __forceinline__ void store_value_span(uint32_t* vc, const uint8_t* vstage, int tid, int lo, int hi) {
   constexpr int VLO = code_lo_bits<BV>(), VHI = code_hi_bits<BV>();
   if constexpr (VHI == 0) {
-    store_value_words<BV>(vc, vstage, tid, lo, hi);
+    store_value_words<BV, 128 * BV, SPAN>(vc, vstage, tid, lo, hi);
   } else {
-    store_value_words<VLO, 128 * BV>(vc, vstage, tid, lo, hi);
-    store_value_words<VHI, 128 * BV>(vc + 128 * VLO, vstage + stage_area<BV>(), tid, lo, hi);
+    store_value_words<VLO, 128 * BV, SPAN>(vc, vstage, tid, lo, hi);
+    store_value_words<VHI, 128 * BV, SPAN>(vc + 128 * VLO, vstage + stage_area<BV, SPAN>(), tid, lo, hi);
   }
 }
 
-// One workgroup = one 64-token span of one (b,h) stream, restricted to the new tokens in it.
-template <int BK, int BV, bool BF>
+// One workgroup = one span of SPAN tokens (a multiple of 32: whole blocks of value codes) of one (b,h) stream, restricted
+// to the new tokens in it.
+template <int BK, int BV, bool BF, int SPAN>
 __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_new,
                                                               const uint16_t* __restrict__ v_new, int64_t sb, int64_t sh,
                                                               int64_t st, int32_t pos, int32_t n_new) {
-  __shared__ __attribute__((aligned(16))) uint8_t vstage[stage_total<BV>()];
+  constexpr int kSpan = SPAN;                      // (shadows the 64-token span of the other kernels in this file)
+  __shared__ __attribute__((aligned(16))) uint8_t vstage[stage_total<BV, SPAN>()];
   const int tid = threadIdx.x;
   const int bh = blockIdx.y;
   const int b = bh / g.kv_heads, h = bh % g.kv_heads;
@@ -151,10 +153,10 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
   uint32_t* vm = (uint32_t*)c.v_meta + meta_index(tv0 + (tid >> 4), lane16 >> lpg_shift(lpg_v), g.ng_v);
   const int km_step = 16 * g.ng_k, vm_step = 16 * g.ng_v;
 
-  // each thread owns 8 channels of rows (tid/16) + 16*it, it = 0..3: issue all eight 16-byte loads, then quantize
-  uint4 kraw[4], vraw[4];
+  // each thread owns 8 channels of rows (tid/16) + 16*it, it < SPAN/16: issue all its 16-byte loads, then quantize
+  uint4 kraw[SPAN / 16], vraw[SPAN / 16];
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
+  for (int it = 0; it < SPAN / 16; ++it) {
     const int row = (tid >> 4) + 16 * it;
     if (row >= lo && row < hi) {
       const int64_t src = (int64_t)b * sb + (int64_t)h * sh + ((int64_t)blk * kSpan + row - pos) * st + d0;
@@ -163,7 +165,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
     }
   }
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
+  for (int it = 0; it < SPAN / 16; ++it) {
     const int row = (tid >> 4) + 16 * it;
     if (row < lo || row >= hi) continue;           // whole 16-lane rows take the same branch
     // ---- keys: row-major codes
@@ -204,12 +206,12 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache 
           note_value_scale(c.v_scale_exp + bh, S);
         }
       }
-      stage_value_row<BV>(vstage, row, d0, codes);
+      stage_value_row<BV, SPAN>(vstage, row, d0, codes);
     }
   }
   __syncthreads();
 
-  store_value_span<BV>(vc, vstage, tid, lo, hi);
+  store_value_span<BV, SPAN>(vc, vstage, tid, lo, hi);
 }
 
 // The 8 fields of channels d0 .. d0+7 (d0 a multiple of 8) of token u in a 32-token block of B-bit fields: the same
@@ -553,13 +555,16 @@ namespace {
 template <int BK, int BV>
 hipError_t launch_q(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype, int64_t sb,
                     int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
-  const int first = pos / kSpan, last = (pos + n_new - 1) / kSpan;
+  // one workgroup per 32-token span (one block of value codes): against 64-token spans this doubles the workgroups of a
+  // small call (a 2048-token chunk of one sequence: 6.5 instead of 7.9 us) and costs a large one nothing
+  constexpr int kQSpan = 32;
+  const int first = pos / kQSpan, last = (pos + n_new - 1) / kQSpan;
   dim3 grid(last - first + 1, g.batch * g.kv_heads);
   if (in_dtype == KVQ_BF16)
-    hipLaunchKernelGGL((quantize_append_kernel<BK, BV, true>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
+    hipLaunchKernelGGL((quantize_append_kernel<BK, BV, true, kQSpan>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
                        (const uint16_t*)v_new, sb, sh, st, pos, n_new);
   else
-    hipLaunchKernelGGL((quantize_append_kernel<BK, BV, false>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
+    hipLaunchKernelGGL((quantize_append_kernel<BK, BV, false, kQSpan>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
                        (const uint16_t*)v_new, sb, sh, st, pos, n_new);
   return hipGetLastError();
 }

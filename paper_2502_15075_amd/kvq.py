@@ -7,6 +7,7 @@ below raises.
 from __future__ import annotations
 
 import ctypes as C
+import functools
 import os
 from dataclasses import dataclass
 
@@ -109,9 +110,15 @@ class Layout:
     n_pages: int = 0
 
     def c(self) -> _CLayout:
-        return _CLayout(self.batch, self.kv_heads, self.max_seq, self.head_dim, self.bits_k, self.bits_v, self.group_k,
-                        self.group_v, self.axis_k, self.axis_v, self.raw_dtype, self.rotate_k, (C.c_uint32 * 4)(*self.signs_k),
-                        self.rotate_v, (C.c_uint32 * 4)(*self.signs_v), self.page_tokens, self.n_pages)
+        return _layout_struct(self)
+
+
+@functools.lru_cache(maxsize=256)
+def _layout_struct(L: Layout) -> _CLayout:
+    """The C struct of a layout, built once per distinct layout (the library only reads it)."""
+    return _CLayout(L.batch, L.kv_heads, L.max_seq, L.head_dim, L.bits_k, L.bits_v, L.group_k, L.group_v, L.axis_k, L.axis_v,
+                    L.raw_dtype, L.rotate_k, (C.c_uint32 * 4)(*L.signs_k), L.rotate_v, (C.c_uint32 * 4)(*L.signs_v),
+                    L.page_tokens, L.n_pages)
 
 
 def _check(status: int, where: str) -> None:
@@ -163,8 +170,12 @@ class Cache:
 
     def c(self) -> _CCache:
         table = getattr(self, "page_table", None)          # int32 device tensor [B, pages per sequence] of a paged cache
-        return _CCache(*[(0 if p is None else p.data_ptr()) for p in self.planes], 0 if table is None else table.data_ptr(),
-                       self.v_scale_exp.data_ptr())
+        key = (None if table is None else table.data_ptr(), tuple(self.planes[i] is None for i in range(len(self.planes))))
+        if getattr(self, "_struct_key", None) != key:       # the planes never move: the struct is built once per table
+            self._struct = _CCache(*[(0 if p is None else p.data_ptr()) for p in self.planes],
+                                   0 if table is None else table.data_ptr(), self.v_scale_exp.data_ptr())
+            self._struct_key = key
+        return self._struct
 
     def batch_element(self, b: int, layout: "Layout") -> "Cache":
         """A view of batch element b's share of every plane as a cache of batch 1 (`layout`: this cache's layout with
