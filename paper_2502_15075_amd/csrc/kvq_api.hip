@@ -91,7 +91,9 @@ kvq_status kvq_decode_workspace_bytes(const kvq_layout* layout, int32_t q_heads,
   // one record of (head_dim + 2) floats per (batch, query head, split), padded to 16 bytes; sized for the most records
   // any length up to seq_len writes, so that the figure never shrinks as seq_len grows
   const int32_t records = kvq::decode_records_bound(g, seq_len);
-  *bytes_out = records == 1 ? 0 : (size_t)layout->batch * q_heads * records * (kvq::kHeadDim + 4) * sizeof(float);
+  // ... followed by one 64-bit counter of finished workgroups per (batch, kv head)
+  *bytes_out = records == 1 ? 0 : (size_t)layout->batch * q_heads * records * (kvq::kHeadDim + 4) * sizeof(float) +
+                                      (((size_t)layout->batch * layout->kv_heads * 8 + 15) & ~(size_t)15);
   return KVQ_OK;
 }
 

@@ -742,6 +742,21 @@ __device__ __forceinline__ uint32_t field_insert(uint32_t w, int tid, const uint
   return w;
 }
 
+// One output element in the caller's type (16-bit types: rounded once).
+__device__ __forceinline__ void store_out(void* out, int out_dtype, int64_t i, float val) {
+  if (out_dtype == KVQ_F32) ((float*)out)[i] = val;
+  else if (out_dtype == KVQ_F16) ((_Float16*)out)[i] = (_Float16)val;
+  else ((uint16_t*)out)[i] = (uint16_t)bf16_rne(val);
+}
+// Partial records travel between workgroups that may sit on different parts of the chip, each with a cache of its own:
+// their stores and loads are device-scope atomic accesses (performed where every compute unit sees them).
+__device__ __forceinline__ void store_device(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_device(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Final output of rotated values: the normalized row sits in the rotated basis (LDS, 128 floats); 16 threads take it
 // back with R_v^T (8 channels each) and store it in the output type.
 __device__ __forceinline__ void store_unrotated_row(const float* row, int lane16, const uint32_t signs[4], void* out,
@@ -932,8 +947,13 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   auto refill = [&](int k, int i) {
     fetch(buf[k], n_my > 0 ? step_of(min(i, n_my - 1)) : safe_step, i < n_my ? ~0u : 0u);
   };
+  // Only the first half of the ring goes out in front of the query staging: the memory pipeline of a compute unit
+  // takes in about what two steps of eight wavefronts ask for, a wavefront that issues more waits at the load until
+  // earlier data has come back, and the barrier of the staging below would wait for the slowest of them.  The second
+  // half follows the barrier, by when the first is on its way out of memory.
+  constexpr int kEarly = (kStages + 1) / 2;
 #pragma unroll
-  for (int k = 0; k < kStages; ++k) refill(k, k);
+  for (int k = 0; k < kEarly; ++k) refill(k, k);
 
   // ---- fused step: quantize the new token (two 16-lane rows of the first wavefront), store keys and scale/zero, stage
   // the value codes for the threads that own the block's words
@@ -983,6 +1003,8 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   if constexpr (KSEQ) { if (tid < kHeadDim) sm_qf[R][tid] = 0.f; }
   if constexpr (!RAW) q_is_bf16 = q_is_bf16 && !g.rotate_k;      // the staged rotated query is binary16
   __syncthreads();
+#pragma unroll
+  for (int k = kEarly; k < kStages; ++k) refill(k, k);       // the second half of the ring's first fill
   auto widen = [&](uint16_t bits) -> float {
     return q_is_bf16 ? __uint_as_float((uint32_t)bits << 16) : (float)__builtin_bit_cast(_Float16, bits);
   };
@@ -1155,19 +1177,80 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
     if (a.rec_splits == 1) {
       const float val = o / ll;
       if (g.rotate_v) { sm_o[0][hh][d] = val; continue; }      // (only this thread touches element (hh, d))
-      if (out_dtype == KVQ_F32) ((float*)out)[hq * kHeadDim + d] = val;
-      else if (out_dtype == KVQ_F16) ((_Float16*)out)[hq * kHeadDim + d] = (_Float16)val;
-      else {
-        uint32_t u = __float_as_uint(val);
-        ((uint16_t*)out)[hq * kHeadDim + d] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
-      }
+      store_out(out, out_dtype, hq * kHeadDim + d, val);
     } else {
+      // (device-scope stores: the record is read by a workgroup on another part of the chip, whose nearest cache is
+      // not this one)
       float* rec = ws + (hq * a.rec_splits + a.rec_base + split) * kRec;
-      rec[d] = o;
-      if (d == 0) { rec[kHeadDim] = M; rec[kHeadDim + 1] = ll; }
+      store_device(rec + d, o);
+      if (d == 0) { store_device(rec + kHeadDim, M); store_device(rec + kHeadDim + 1, ll); }
     }
   }
-  if (a.rec_splits == 1 && g.rotate_v) {             // uniform over the workgroup
+  bool wrote_rows = a.rec_splits == 1;               // this workgroup has left normalized rows (rotated values: in sm_o)
+  if (a.merge_tag != 0) {                            // uniform: the launch's workgroups merge their records themselves
+    // The workgroup of a (b, h_kv) stream that finishes last combines the stream's records: every workgroup counts
+    // itself in (one device-scope increment, issued after all its record stores have been acknowledged), and the one
+    // that brings the count to n_splits reads all records back.  Nobody waits for anybody.  Records and counter are
+    // device-scope atomic accesses, which go past the caches that are private to a part of the chip; a device-scope
+    // FENCE is not used on purpose: it writes back and invalidates the whole second-level cache of the workgroup's part
+    // of the chip, under the streaming loads of every other workgroup there, and was measured to cost the 8B-layer
+    // step 10 us (the barrier in front of the increment already waits for this workgroup's stores).  The counter word carries the launch's
+    // tag above the count, so that whatever the word held before this launch -- another launch's tag, or the bytes of
+    // a fresh workspace -- counts as zero; the last workgroup leaves the count at zero for a replay of the same launch.
+    __shared__ int sm_last;
+    __syncthreads();                                 // (all record stores of this workgroup are performed)
+    if (tid == 0) {
+      unsigned long long* cnt = reinterpret_cast<unsigned long long*>(ws + (int64_t)g.batch * q_heads * a.rec_splits * kRec) + bh;
+      const unsigned long long tag = a.merge_tag << 16;
+      unsigned long long seen = __hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), want;
+      do {
+        want = ((seen & ~0xFFFFull) == tag ? seen : tag) + 1ull;
+      } while (!__hip_atomic_compare_exchange_strong(cnt, &seen, want, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+      const int last = (int)(want & 0xFFFFull) == a.rec_splits;
+      if (last) __hip_atomic_store(cnt, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      sm_last = last;
+    }
+    __syncthreads();
+    if (sm_last) {                                   // uniform over the workgroup
+      const int n_rec = a.rec_splits;
+      for (int idx = tid; idx < r_act * kHeadDim; idx += 64 * NW) {
+        const int hh = idx / kHeadDim, d = idx % kHeadDim;
+        const int64_t hq = (int64_t)b * q_heads + hk * r_act + hh;
+        const float* rec = ws + hq * n_rec * kRec;
+        // eight records at a time, all 24 loads of a round in flight together (a record's maximum and sum are the same
+        // words for the 128 threads of a head); rounds are chained by a running maximum as in the main loop
+        float M = kNegBig, o = 0.f, ll = 0.f;
+        for (int s0 = 0; s0 < n_rec; s0 += 8) {
+          float ms[8], ls[8], os[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float* r2 = rec + min(s0 + j, n_rec - 1) * kRec;
+            ms[j] = load_device(r2 + kHeadDim); ls[j] = load_device(r2 + kHeadDim + 1); os[j] = load_device(r2 + d);
+          }
+          float Mc = M;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            if (s0 + j >= n_rec) { ms[j] = kNegBig; ls[j] = 0.f; os[j] = 0.f; }
+            Mc = fmaxf(Mc, ms[j]);
+          }
+          const float fo = exp2f(M - Mc);
+          o *= fo; ll *= fo;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float f = exp2f(ms[j] - Mc);
+            o = fmaf(f, os[j], o);
+            ll = fmaf(f, ls[j], ll);
+          }
+          M = Mc;
+        }
+        const float val = o / ll;
+        if (g.rotate_v) sm_o[0][hh][d] = val;
+        else store_out(out, out_dtype, hq * kHeadDim + d, val);
+      }
+      wrote_rows = true;
+    }
+  }
+  if (wrote_rows && g.rotate_v) {                    // uniform over the workgroup
     __syncthreads();
     if (tid < R * 16 && (tid >> 4) < r_act)
       store_unrotated_row(&sm_o[0][tid >> 4][0], tid & 15, g.signs_v, out, out_dtype,
@@ -1281,8 +1364,9 @@ hipError_t launch_one(const DecodeArgs& a, const DecodePlan& plan, hipStream_t s
   hipError_t e;
   e = a.g.page_shift ? launch_sets<BK, BV, R, BF, KSEQ, true>(a, plan, grid, stream)
                      : launch_sets<BK, BV, R, BF, KSEQ, false>(a, plan, grid, stream);
-  // the records of this launch are all there is: merge them here (otherwise the caller adds launches and merges)
-  if (e != hipSuccess || a.rec_splits == 1 || a.rec_splits != plan.n_splits) return e;
+  // the records of this launch are all there is: merge them, in the launch itself where that pays (merge_tag), else
+  // here (otherwise the caller adds launches and merges)
+  if (e != hipSuccess || a.rec_splits == 1 || a.rec_splits != plan.n_splits || a.merge_tag != 0) return e;
   hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128 * kMergeGroups), 0, stream, a.ws, a.out, a.out_dtype, a.rec_splits,
                      rot_v_of(a.g));
   return hipGetLastError();
@@ -1408,6 +1492,23 @@ DecodePlan plan_decode(const Geom& g, int32_t seq_len) {
   return DecodePlan{splits, sps, nw};
 }
 
+// A number that tells one launch's count of finished workgroups from whatever the counter word held before (48 bits,
+// never 0).  A replayed graph launch carries the same number again: the last workgroup of a launch leaves the count at 0.
+static unsigned long long next_merge_tag() {
+  static std::atomic<unsigned long long> counter{0x9E3779B97F4Aull};
+  unsigned long long t;
+  do { t = counter.fetch_add(0x632BE59BD9B5ull, std::memory_order_relaxed) & 0xFFFFFFFFFFFFull; } while (t == 0);
+  return t;
+}
+
+// Where the launch's own workgroups merge the records (two splits: the shapes that are bound by their launches; the 1 MiB
+// cache of one sequence of 8 heads and 1024 tokens steps in 11.5 us this way and in 15.7 us with the merge kernel).  With
+// four records and more the merge kernel is the faster way: the device-scope accesses of the counting and of reading
+// the records back cost the last workgroup two trips to memory of 1.5 to 2 us each, as many as the second kernel
+// needs, on top of slower record stores (measured: 22.4 against 20.9 us on the 8B layer's four splits, 64 against 30 us
+// with 32 splits, where the workgroups' increments of one counter also queue up behind each other).
+static unsigned long long merge_tag_for(int records) { return records == 2 ? next_merge_tag() : 0ull; }
+
 hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void* q, int q_dtype, int32_t q_heads,
                                    int32_t seq_len, float softmax_scale, void* out, int out_dtype, float* workspace,
                                    const DecodePlan& plan, const AppendOne* app, hipStream_t stream,
@@ -1422,6 +1523,7 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
   a.ws = workspace; a.out = out; a.out_dtype = out_dtype;
   a.n_splits = plan.n_splits; a.steps_per_split = plan.steps_per_split;
   a.rec_splits = plan.n_splits; a.rec_base = 0;
+  a.merge_tag = 0;
   if (g.axis_k == KVQ_AXIS_SEQ) {
     // channel-wise keys: flushed blocks from the codes (plan), the newest tokens from the residual buffer by the
     // unquantized kernel, all partial records merged at the end
@@ -1435,6 +1537,7 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
     hipError_t e = hipSuccess;
     if (n_flushed) {
       a.seq_len = n_flushed; a.rec_splits = records; a.rec_base = 0; a.lens_mode = 1;
+      a.merge_tag = !tail ? merge_tag_for(records) : 0;     // (a launch that writes every record may merge them itself)
 #define KVQ_CASE(BK_, BV_) \
       if (g.bits_k == BK_ && g.bits_v == BV_) e = KVQ_CAT(launch_decode_inst_, BK_, BV_)(R, a, plan, stream);
       KVQ_FOR_EACH_PAIR(KVQ_CASE)
@@ -1443,6 +1546,7 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
     }
     if (tail) {
       DecodeArgs t = a;
+      t.merge_tag = 0;
       t.g.axis_k = KVQ_AXIS_HEAD_DIM; t.g.bits_k = t.g.bits_v = 16; t.g.g_k = t.g.g_v = kHeadDim; t.g.ng_k = t.g.ng_v = 1;
       t.g.t_cap = kSeqGroup; t.g.page_shift = 0; t.cache.page_table = nullptr;     // (the buffers are per sequence, never paged)
       t.g.kc_stream = t.g.vc_stream = (int64_t)kSeqGroup * kHeadDim * 2; t.g.km_stream = t.g.vm_stream = 0;
@@ -1460,6 +1564,7 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
     return e;
   }
   a.lens_mode = 0; a.lens_bound = seq_len;
+  a.merge_tag = merge_tag_for(a.rec_splits);
   if (app) {
     a.k_new = (const uint16_t*)app->k_new; a.v_new = (const uint16_t*)app->v_new;
     a.in_bf16 = app->in_dtype == KVQ_BF16 ? 1 : 0; a.nsb = app->stride_b; a.nsh = app->stride_h;

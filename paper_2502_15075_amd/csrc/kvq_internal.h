@@ -94,6 +94,11 @@ struct DecodeArgs {
   // partial records: a workgroup writes record rec_base + split of rec_splits per (batch, query head); rec_splits == 1
   // means there is nothing to merge and the result goes straight to `out`
   int32_t rec_splits, rec_base;
+  // != 0: this launch writes all rec_splits records of every stream and merges them itself (the workgroup that finishes
+  // a stream last does it; the streams' counters, one 64-bit word per (batch, kv head), follow the records in the
+  // workspace); the number tells this launch's counts from what the words held before.  0: records are merged by
+  // merge_kernel, or there is one record and nothing to merge.
+  unsigned long long merge_tag;
   // fused decode step: the token at position seq_len-1 is quantized from k_new/v_new ([B][H_kv][D], element strides
   // nsb, nsh) by the workgroup that owns the last step, before it is read.  k_new == nullptr: plain attention.
   const uint16_t* k_new; const uint16_t* v_new; int in_bf16; int64_t nsb, nsh;

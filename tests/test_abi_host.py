@@ -84,9 +84,9 @@ def test_sizes_agree_with_the_oracle(kvq, oracle):
 def test_workspace_plan(kvq):
     # 256 (b,h) streams fill the chip without splitting the sequence: no workspace at all
     assert kvq.decode_workspace_bytes(kvq.Layout(32, 8, 32768), 64, 32768) == 0
-    # few streams, long context: (splits) x (B x H_q) records of 132 floats
+    # few streams, long context: (splits) x (B x H_q) records of 132 floats, then one 8-byte counter per (b, h_kv)
     n = kvq.decode_workspace_bytes(kvq.Layout(1, 8, 131072), 32, 131072)
-    assert n > 0 and n % (32 * 132 * 4) == 0
+    assert n > 64 and (n - 64) % (32 * 132 * 4) == 0
     assert kvq.decode_workspace_bytes(kvq.Layout(1, 8, 131072), 32, 40) <= n
 
 
@@ -229,4 +229,5 @@ def test_workspace_never_shrinks_as_the_sequence_grows(kvq):
         L = kvq.Layout(B, H, 1 << 17, 128, 4, 2, 64, 64, axis_k=axis)
         sizes = [kvq.decode_workspace_bytes(L, Hq, t) for t in list(range(1, 6000, 7)) + list(range(6000, 1 << 17, 997))]
         assert all(a <= b for a, b in zip(sizes, sizes[1:])), (B, H, axis)
-        assert sizes[-1] > 0 and sizes[-1] % (132 * 4 * B * Hq) == 0
+        counters = (B * H * 8 + 15) // 16 * 16
+        assert sizes[-1] > counters and (sizes[-1] - counters) % (132 * 4 * B * Hq) == 0
