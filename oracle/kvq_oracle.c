@@ -41,6 +41,11 @@
  *     by channel (one scale/zero per channel and block), the G_K value rows token-wise as
  *     always; attention reads tokens below floor(seq_len / G_K) * G_K from the codes and the
  *     rest from the buffer.  Tokens must be appended in order, starting at 0.
+ *     With rotate_k (the study's best setting, K4V2 with key-only rotation, on the per-column back-end of the
+ *     downstream runs: Sec. 5.3 and Sec. 4) the buffer still keeps the input rows; a flush quantizes R k of every
+ *     row, channel by channel in the rotated basis; attention takes the scores of the flushed tokens from the
+ *     rotated query (rounded once to binary16, as with token-wise keys) and those of the tail from the query
+ *     itself: the same bilinear form in exact arithmetic, since R is orthogonal.
  *
  * Arithmetic of the quantizer is IEEE binary32, round-to-nearest-even, one rounding per
  * written operation (build with -ffp-contract=off, no fast-math).  The decisions that
@@ -566,7 +571,8 @@ int ref_resid_bytes(const ref_layout* L, uint64_t out[2]) {
 
 static int seq_layout_ok(const ref_layout* L) {
   int G = L->group_k, D = L->head_dim;
-  if (L->axis_k != 1 || L->rotate_k || L->rotate_v) return 0;
+  if (L->axis_k != 1 || L->rotate_v) return 0;
+  if (L->rotate_k && (D > 128 || (D & (D - 1)))) return 0;
   if (G != 32 && G != 64 && G != 128) return 0;
   if (D % 64 || D > 1024 || D % L->group_v) return 0;
   if (!bits_allowed(L->bits_k) || !bits_allowed(L->bits_v)) return 0;
@@ -619,11 +625,18 @@ int ref_seq_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, uint8
       if (slot != G - 1) continue;
       /* flush the block that just filled up */
       int64_t blk = t / G, t0 = blk * G;
-      for (int d = 0; d < D; ++d) {                           /* keys: one group = G tokens of channel d */
-        for (int i = 0; i < G; ++i) {
+      float* rows = (float*)malloc(sizeof(float) * (size_t)G * (size_t)D);   /* the block's key rows (R k with rotate_k) */
+      float* plain = (float*)malloc(sizeof(float) * (size_t)D);
+      for (int i = 0; i < G; ++i) {
+        for (int d = 0; d < D; ++d) {
           uint16_t bits16 = resid_get_k(kr, i, d, D);
-          col[i] = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32(bits16) : ref_f16_to_f32(bits16);
+          plain[d] = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32(bits16) : ref_f16_to_f32(bits16);
         }
+        if (L->rotate_k) ref_rotate(plain, D, L->signs_k, rows + (size_t)i * D);
+        else memcpy(rows + (size_t)i * D, plain, sizeof(float) * (size_t)D);
+      }
+      for (int d = 0; d < D; ++d) {                           /* keys: one group = G tokens of channel d */
+        for (int i = 0; i < G; ++i) col[i] = rows[(size_t)i * D + d];
         uint16_t S, Z;
         ref_quantize_group(col, G, bk, codes, &S, &Z);
         uint8_t* m = km + (blk * D + d) * 4;
@@ -631,6 +644,7 @@ int ref_seq_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, uint8
         m[2] = (uint8_t)(Z & 0xFF); m[3] = (uint8_t)(Z >> 8);
         for (int i = 0; i < G; ++i) k_put_code(kc, t0 + i, d, D, bk, codes[i]);
       }
+      free(rows); free(plain);
       for (int i = 0; i < G; ++i) {                           /* values: token-wise groups as always */
         for (int d = 0; d < D; ++d) {
           uint16_t bits16 = resid_get_v(vr, i, d, D);
@@ -654,9 +668,9 @@ int ref_seq_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, uint8
 /* What attention sees of tokens [t0,t1) when the cache holds seq_len tokens: the reconstruction
  * of the flushed tokens (below floor(seq_len/G)*G), the 16-bit patterns of the rest, as binary32.
  * k_out, v_out: [B][H][t1-t0][D]. */
-int ref_seq_dequantize(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
-                       const uint8_t* v_meta, const uint8_t* k_resid, const uint8_t* v_resid, int32_t seq_len,
-                       int32_t t0, int32_t t1, float* k_out, float* v_out) {
+static int seq_dequantize_impl(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
+                               const uint8_t* v_meta, const uint8_t* k_resid, const uint8_t* v_resid, int32_t seq_len,
+                               int32_t t0, int32_t t1, float* k_out, float* v_out, int stored) {
   if (!seq_layout_ok(L)) return -1;
   if (t0 < 0 || t1 < t0 || t1 > seq_len || seq_len > L->max_seq) return -3;
   int D = L->head_dim, G = L->group_k, GV = L->group_v, bk = L->bits_k, bv = L->bits_v;
@@ -689,8 +703,24 @@ int ref_seq_dequantize(const ref_layout* L, const uint8_t* k_codes, const uint8_
         if (k_out) k_out[((bh * nt) + (t - t0)) * D + d] = kv;
         if (v_out) v_out[((bh * nt) + (t - t0)) * D + d] = vv;
       }
+    if (k_out && L->rotate_k && !stored) {                  /* flushed rows hold reconstructions of R k: back with R^T */
+      float* tmp = (float*)malloc(sizeof(float) * (size_t)D);
+      for (int64_t t = t0; t < t1 && t < n_flushed; ++t) {
+        float* row = k_out + ((bh * nt) + (t - t0)) * D;
+        ref_unrotate(row, D, L->signs_k, tmp);
+        memcpy(row, tmp, sizeof(float) * (size_t)D);
+      }
+      free(tmp);
+    }
   }
   return 0;
+}
+
+/* ... in the basis of the inputs (with rotate_k the flushed key rows are taken back with R^T) */
+int ref_seq_dequantize(const ref_layout* L, const uint8_t* k_codes, const uint8_t* k_meta, const uint8_t* v_codes,
+                       const uint8_t* v_meta, const uint8_t* k_resid, const uint8_t* v_resid, int32_t seq_len,
+                       int32_t t0, int32_t t1, float* k_out, float* v_out) {
+  return seq_dequantize_impl(L, k_codes, k_meta, v_codes, v_meta, k_resid, v_resid, seq_len, t0, t1, k_out, v_out, 0);
 }
 
 /* Decode attention over a cache with channel-wise keys and a residual buffer: the dense
@@ -703,8 +733,47 @@ int ref_seq_decode_attention(const ref_layout* L, const uint8_t* k_codes, const 
   float* Kd = (float*)malloc(sizeof(float) * (size_t)n);
   float* Vd = (float*)malloc(sizeof(float) * (size_t)n);
   if (!Kd || !Vd) { free(Kd); free(Vd); return -2; }
-  int rc = ref_seq_dequantize(L, k_codes, k_meta, v_codes, v_meta, k_resid, v_resid, seq_len, 0, seq_len, Kd, Vd);
-  if (!rc) rc = ref_attention_dense(Kd, Vd, L->batch, L->kv_heads, q_heads, seq_len, L->head_dim, q, q_dtype, softmax_scale, out);
+  /* keys as stored: flushed rows in the rotated basis when rotate_k, the tail as it came in */
+  int rc = seq_dequantize_impl(L, k_codes, k_meta, v_codes, v_meta, k_resid, v_resid, seq_len, 0, seq_len, Kd, Vd, 1);
+  if (!rc && !L->rotate_k)
+    rc = ref_attention_dense(Kd, Vd, L->batch, L->kv_heads, q_heads, seq_len, L->head_dim, q, q_dtype, softmax_scale, out);
+  else if (!rc) {
+    /* the dense definition with the query that belongs to each token's basis: binary16(R q) for the flushed tokens,
+     * q for the tail */
+    int D = L->head_dim, R = q_heads / L->kv_heads;
+    int64_t n_flushed = (int64_t)seq_len / L->group_k * L->group_k;
+    float* qp = (float*)malloc(sizeof(float) * (size_t)D);
+    float* qr = (float*)malloc(sizeof(float) * (size_t)D);
+    double* logit = (double*)malloc(sizeof(double) * (size_t)seq_len);
+    double* acc = (double*)malloc(sizeof(double) * (size_t)D);
+    for (int b = 0; b < L->batch; ++b)
+      for (int hq = 0; hq < q_heads; ++hq) {
+        int hk = hq / R;
+        const float* Kh = Kd + ((int64_t)b * L->kv_heads + hk) * seq_len * D;
+        const float* Vh = Vd + ((int64_t)b * L->kv_heads + hk) * seq_len * D;
+        int64_t qbase = ((int64_t)b * q_heads + hq) * D;
+        for (int d = 0; d < D; ++d) qp[d] = load_elem(q, q_dtype, qbase + d);
+        ref_rotate(qp, D, L->signs_k, qr);
+        for (int d = 0; d < D; ++d) qr[d] = ref_f16_to_f32(ref_f32_to_f16(qr[d]));
+        double mx = -INFINITY;
+        for (int t = 0; t < seq_len; ++t) {
+          const float* qt = t < n_flushed ? qr : qp;
+          double sdot = 0.0;
+          for (int d = 0; d < D; ++d) sdot += (double)qt[d] * (double)Kh[(int64_t)t * D + d];
+          logit[t] = (double)softmax_scale * sdot;
+          if (logit[t] > mx) mx = logit[t];
+        }
+        double denom = 0.0;
+        for (int d = 0; d < D; ++d) acc[d] = 0.0;
+        for (int t = 0; t < seq_len; ++t) {
+          double pw = exp(logit[t] - mx);
+          denom += pw;
+          for (int d = 0; d < D; ++d) acc[d] += pw * (double)Vh[(int64_t)t * D + d];
+        }
+        for (int d = 0; d < D; ++d) out[qbase + d] = (float)(acc[d] / denom);
+      }
+    free(qp); free(qr); free(logit); free(acc);
+  }
   free(Kd); free(Vd);
   return rc;
 }

@@ -318,3 +318,122 @@ def test_ragged_batch_is_each_sequence_on_its_own(oracle):
 def _element_of(oracle, L, planes, b):
     from dataclasses import replace
     return replace(L, batch=1), [p.reshape(L.batch, -1)[b] if p.size else p for p in planes]
+
+
+# --------------------------------------------------------------------------- key rotation on the per-column back-end
+
+ROT_SIGNS = (0x9E3779B9, 0x7F4A7C15, 0xF39CC060, 0x5CEDC834)
+
+
+def _rotate_rows(oracle, X, signs):
+    """R x for every row of X (the oracle's single-vector rotation, itself pinned against scipy's Hadamard matrix)."""
+    return np.stack([oracle.rotate(r, signs) for r in X.astype(np.float32)])
+
+
+@pytest.mark.parametrize("G,bk,bv", [(64, 4, 2), (32, 2, 4), (128, 8, 8), (64, 3, 2)])
+def test_rotated_channelwise_planes_are_those_of_the_rotated_rows(oracle, G, bk, bv):
+    """Sec. 5.3's best setting (key-only rotation) on Sec. 4's per-column keys: the flushed code and scale/zero planes
+    of a cache with rotate_k equal those of a cache WITHOUT rotation that is fed the rotated rows R k (binary32, no
+    rounding on the way to the quantizer); the residual buffers keep the input rows; value planes do not change."""
+    rng = np.random.default_rng(G * 7 + bk)
+    B, H, D = 1, 2, 128
+    T = 2 * G + 19
+    K = (rng.standard_normal((B, H, T, D)) * 3).astype(np.float16)
+    K[..., [5, 37, 69, 101]] *= 20
+    V = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    Lr = oracle.Layout(B, H, T, D, bk, bv, G, 64, axis_k=1, rotate_k=1, signs_k=ROT_SIGNS)
+    Lp = oracle.Layout(B, H, T, D, bk, bv, G, 64, axis_k=1)
+    rot = oracle.new_seq_planes(Lr, fill=0xA5)
+    oracle.seq_append(Lr, rot, K, V, 0)
+    nq = T // G * G
+    for h in range(H):
+        Kr = _rotate_rows(oracle, K[0, h, :nq], ROT_SIGNS)                       # binary32 rows R k
+        for blk in range(nq // G):
+            c, s, z = _quantize_columns_numpy(Kr[blk * G:(blk + 1) * G], bk)
+            meta = rot[1].reshape(B * H, -1)[h].view(np.uint16).reshape(-1, D, 2)[blk]
+            assert np.array_equal(meta[:, 0], s) and np.array_equal(meta[:, 1], z)
+            rows = rot[0].reshape(B * H, -1, 16 * bk)[h][blk * G:(blk + 1) * G]
+            assert np.array_equal(rows.ravel(), _pack_key_rows_numpy(c, bk)[:G * 16 * bk])
+        kr = rot[4].reshape(B * H, G, D * 2)[h].view(np.float16).reshape(G, D)
+        for t in range(nq, T):
+            assert np.array_equal(kr[t % G], K[0, h, t])                         # the buffer keeps the input row
+    plain = oracle.new_seq_planes(Lp, fill=0xA5)
+    oracle.seq_append(Lp, plain, K, V, 0)
+    for i in (2, 3, 5):
+        assert np.array_equal(rot[i], plain[i])                                  # values: untouched by the key rotation
+    assert not np.array_equal(rot[0], plain[0])
+
+
+def test_rotated_channelwise_attention(oracle):
+    """What attention computes with rotated channel-wise keys, written out with numpy and torch: flushed tokens score
+    binary16(R q) against the stored reconstruction of R k, tail tokens score q against the input rows, one softmax
+    over all, values as always.  And the reconstruction handed out is in the input basis: R^T of what is stored."""
+    rng = np.random.default_rng(21)
+    B, Hk, Hq, T, D, G = 1, 2, 4, 150, 128, 64
+    K = (rng.standard_normal((B, Hk, T, D)) * 2).astype(np.float16)
+    K[..., [5, 37]] *= 15
+    V = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    scale = 1 / math.sqrt(D)
+    L = oracle.Layout(B, Hk, T, D, 4, 2, G, 64, axis_k=1, rotate_k=1, signs_k=ROT_SIGNS)
+    for seq_len in (150, 128, 70, 63):
+        pl = oracle.new_seq_planes(L)
+        oracle.seq_append(L, pl, np.ascontiguousarray(K[:, :, :seq_len]), np.ascontiguousarray(V[:, :, :seq_len]), 0)
+        nq = seq_len // G * G
+        kd, vd = oracle.seq_dequantize(L, pl, seq_len, 0, seq_len)
+        got = oracle.seq_decode_attention(L, pl, q, seq_len, scale)
+        ref = np.zeros((B, Hq, D))
+        for hq in range(Hq):
+            hk = hq // (Hq // Hk)
+            stored = np.zeros((seq_len, D), np.float32)
+            for blk in range(nq // G):
+                Kr = _rotate_rows(oracle, K[0, hk, blk * G:(blk + 1) * G], ROT_SIGNS)
+                c, s, z = _quantize_columns_numpy(Kr, 4)
+                stored[blk * G:(blk + 1) * G] = c.astype(np.float32) * s.view(np.float16).astype(np.float32) + z.view(np.float16).astype(np.float32)
+            stored[nq:] = K[0, hk, nq:seq_len].astype(np.float32)
+            # the reconstruction in the input basis: R^T of the stored flushed rows, the tail as it is
+            back = stored.copy()
+            for t in range(nq):
+                back[t] = oracle.unrotate(stored[t], ROT_SIGNS)
+            assert np.array_equal(kd[0, hk], back)
+            qr = oracle.rotate(q[0, hq].astype(np.float32), ROT_SIGNS).astype(np.float16).astype(np.float64)
+            logits = np.concatenate([stored[:nq].astype(np.float64) @ qr, stored[nq:].astype(np.float64) @ q[0, hq].astype(np.float64)]) * scale
+            p = torch.softmax(torch.from_numpy(logits), dim=0).numpy()
+            ref[0, hq] = p @ vd[0, hk].astype(np.float64)
+        assert np.abs(got - ref).max() <= 2e-6 * np.abs(ref).max()
+    # the rotation leaves the scores where they were: with 8-bit keys the output stays close to exact attention
+    L8 = oracle.Layout(B, Hk, T, D, 8, 8, G, 64, axis_k=1, rotate_k=1, signs_k=ROT_SIGNS)
+    pl = oracle.new_seq_planes(L8)
+    oracle.seq_append(L8, pl, K, V, 0)
+    exact = oracle.attention_dense(K.astype(np.float32), V.astype(np.float32), q, scale)
+    got = oracle.seq_decode_attention(L8, pl, q, T, scale)
+    assert np.abs(got - exact).max() < 0.05 * np.abs(exact).max()
+
+
+def test_rotation_and_per_column_groups_on_outlier_channels(oracle):
+    """The two remedies for a few large key channels, and their combination (Sec. 5.3 on Sec. 4's back-end), on keys
+    that are independent draws with four channels scaled by 20: token-wise groups waste their range on the large
+    channel (MSE 1.5 at 4 bits), per-column groups isolate it (0.42), the rotation spreads it over all channels
+    (0.22); rotating in front of per-column groups neither helps nor hurts on such keys (columns of R k all have the
+    same spread): the combination is there for keys whose columns differ, not expected to win here."""
+    rng = np.random.default_rng(5)
+    B, H, T, D, G = 1, 4, 256, 128, 64
+    K = (rng.standard_normal((B, H, T, D)) * 2).astype(np.float32)
+    K[..., [5, 37, 69, 101]] *= 20
+    K16 = K.astype(np.float16)
+    V = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    err = {}
+    for axis in (0, 1):
+        for rot in (0, 1):
+            L = oracle.Layout(B, H, T, D, 4, 2, G, 64, axis_k=axis, rotate_k=rot, signs_k=ROT_SIGNS if rot else (0, 0, 0, 0))
+            if axis:
+                pl = oracle.new_seq_planes(L)
+                oracle.seq_append(L, pl, K16, V, 0)
+                kd, _ = oracle.seq_dequantize(L, pl, T, 0, T)
+            else:
+                pl = oracle.new_planes(L)
+                oracle.quantize_append(L, pl, K16, V, 0)
+                kd, _ = oracle.dequantize(L, pl, 0, T)
+            err[axis, rot] = oracle.mse(K16.astype(np.float32), kd)
+    assert err[0, 1] < err[1, 0] < 0.5 * err[0, 0]
+    assert abs(err[1, 1] / err[1, 0] - 1) < 0.15
