@@ -45,8 +45,10 @@
  * block, same arithmetic as above with the group running over tokens), its value rows token-wise as always.
  * Attention reads tokens below floor(seq_len / 64) * 64 from the codes and the rest from the buffer.  Contract:
  * tokens are appended in order starting at 0 (pos = number of tokens appended so far), in_dtype = raw_dtype, and
- * seq_len of a decode call is that number.  Every quantized width for keys and values; bits 16 and the rotations are
- * not combined with it; axis_v stays KVQ_AXIS_HEAD_DIM.  Attention needs a query of raw_dtype (KVQ_ERR_UNSUPPORTED otherwise);
+ * seq_len of a decode call is that number.  Every quantized width for keys and values; bits 16 and rotate_v are not
+ * combined with it; axis_v stays KVQ_AXIS_HEAD_DIM.  With rotate_k (Sec. 5.3's key-only rotation on this back-end) the
+ * buffer keeps the input rows, a flush quantizes R k of every row of the block, and attention scores the flushed tokens
+ * with binary16(R q) and the tail with q itself.  Attention needs a query of raw_dtype (KVQ_ERR_UNSUPPORTED otherwise);
  * kvq_decode_step is the append followed by the attention (several launches).  With per-sequence lengths
  * (kvq_decode_attention_varlen, kvq_decode_step_varlen) every sequence has its own count of appended tokens, its own
  * flushed blocks and its own tail in its residual buffer; kvq_decode_step_varlen appends sequence b's token at pos[b]

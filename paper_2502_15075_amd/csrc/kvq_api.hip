@@ -32,8 +32,8 @@ kvq_status check_layout(const kvq_layout* L) {
   if (L->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;
   if (L->axis_v != KVQ_AXIS_HEAD_DIM) return KVQ_ERR_UNSUPPORTED;
   if (L->axis_k == KVQ_AXIS_SEQ) {
-    // channel-wise keys: 64-token groups with a 64-slot residual buffer; quantized keys and values, no rotation
-    if (L->bits_k == 16 || L->bits_v == 16 || L->rotate_k || L->rotate_v) return KVQ_ERR_INVALID_ARG;
+    // channel-wise keys: 64-token groups with a 64-slot residual buffer; quantized keys and values; keys may be rotated
+    if (L->bits_k == 16 || L->bits_v == 16 || L->rotate_v) return KVQ_ERR_INVALID_ARG;
     if (L->group_k != kvq::kSeqGroup) return KVQ_ERR_UNSUPPORTED;
   }
   if ((int64_t)L->batch * L->kv_heads > 65535) return KVQ_ERR_UNSUPPORTED;

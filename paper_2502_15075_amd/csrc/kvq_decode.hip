@@ -983,9 +983,10 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
     reinterpret_cast<u32x4*>(&sm_q[0][0])[tid] = raw;
     if constexpr (KSEQ) {
       const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+      const bool staged_bf16 = q_is_bf16 && !g.rotate_k;       // (a rotated query has been rounded to binary16 above)
 #pragma unroll
       for (int e = 0; e < 8; ++e)
-        sm_qf[tid >> 4][8 * (tid & 15) + e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), q_is_bf16) /
+        sm_qf[tid >> 4][8 * (tid & 15) + e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), staged_bf16) /
                                               (kseq_prescaled<BK>() ? k_chan_scale<BK>(e) : 1.0f);
     }
     if constexpr (!RAW) {
@@ -1548,6 +1549,7 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
       DecodeArgs t = a;
       t.merge_tag = 0;
       t.g.axis_k = KVQ_AXIS_HEAD_DIM; t.g.bits_k = t.g.bits_v = 16; t.g.g_k = t.g.g_v = kHeadDim; t.g.ng_k = t.g.ng_v = 1;
+      t.g.rotate_k = 0;                                    // (the buffer holds the input rows: their scores take q itself)
       t.g.t_cap = kSeqGroup; t.g.page_shift = 0; t.cache.page_table = nullptr;     // (the buffers are per sequence, never paged)
       t.g.kc_stream = t.g.vc_stream = (int64_t)kSeqGroup * kHeadDim * 2; t.g.km_stream = t.g.vm_stream = 0;
       t.cache.k_codes = c.k_resid; t.cache.v_codes = c.v_resid; t.cache.k_meta = t.cache.v_meta = nullptr;

@@ -307,8 +307,12 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
   for (int it = 0; it < 4; ++it) {
     const uint32_t rw[4] = {kraw[it].x, kraw[it].y, kraw[it].z, kraw[it].w};
 #pragma unroll
+    for (int e = 0; e < 8; ++e) x[it][e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
+    // rotated keys: the block's rows are quantized as R k (the buffer keeps the input rows; the 16 lanes of a row are
+    // neighbours in one wavefront, and the whole workgroup is here)
+    if (g.rotate_k) rotate8(x[it], lane16, rot_sign_bits(g.signs_k, lane16));
+#pragma unroll
     for (int e = 0; e < 8; ++e) {
-      x[it][e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
       mn[e] = it == 0 ? x[it][e] : fminf(mn[e], x[it][e]);
       mx[e] = it == 0 ? x[it][e] : fmaxf(mx[e], x[it][e]);
     }

@@ -104,7 +104,6 @@ def test_layout_errors(kvq):
         (kvq.Layout(1, 8, 64, 64), kvq.ERR_UNSUPPORTED), (kvq.Layout(1, 8, 64, 128, 4, 2, 32, 64, axis_k=1), kvq.ERR_UNSUPPORTED),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_v=1), kvq.ERR_UNSUPPORTED),
         (kvq.Layout(1, 8, 64, 128, 16, 16, 64, 64, axis_k=1), kvq.ERR_INVALID_ARG),      # residual buffer + unquantized planes
-        (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_k=1, rotate_k=1), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_v=7), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, raw_dtype=2), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 1 << 25), kvq.ERR_UNSUPPORTED),

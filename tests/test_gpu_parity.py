@@ -795,6 +795,44 @@ def test_channelwise_unsupported_combinations(kvq):
     assert e.value.status == kvq.ERR_INVALID_ARG                      # the buffer keeps patterns of raw_dtype
 
 
+@pytest.mark.parametrize("R", [4, 8])
+@pytest.mark.parametrize("bk,bv,gv,dtype", [(4, 2, 64, torch.bfloat16), (2, 4, 128, torch.float16), (8, 8, 32, torch.bfloat16),
+                                            (3, 2, 64, torch.float16), (6, 1, 64, torch.bfloat16)])
+def test_channelwise_keys_with_key_rotation(kvq, oracle, R, bk, bv, gv, dtype):
+    """Sec. 5.3's key-only rotation on Sec. 4's per-column keys: six planes byte-identical after chunked appends that
+    flush blocks in the middle of a call, the reconstruction handed out in the input basis, attention over flushed
+    blocks (rotated query) plus residual tail (query itself), and decode steps across a flush."""
+    B, H, T = 2, 2, 333
+    raw = 1 if dtype == torch.bfloat16 else 0
+    K, V, q = synth.make_kvq(300 + bk + R, B, H, H * R, T, dtype=dtype)
+    Lg = kvq.Layout(B, H, T, 128, bk, bv, 64, gv, axis_k=kvq.AXIS_SEQ, raw_dtype=raw, rotate_k=1, signs_k=SIGNS)
+    Lo = oracle.Layout(B, H, T, 128, bk, bv, 64, gv, raw_dtype=raw, axis_k=1, rotate_k=1, signs_k=SIGNS)
+    T0 = 300
+    cache, planes = _seq_fill_both(kvq, oracle, Lg, Lo, K[:, :, :T0], V[:, :, :T0], [(0, 1), (1, 63), (63, 70), (70, 257), (257, T0)])
+    _assert_seq_planes_equal(cache, planes)
+    nq = T0 // 64 * 64
+    ko = torch.empty(B, H, nq, 128, dtype=torch.float32, device="cuda")
+    kvq.dequantize(Lg, cache, 0, nq, ko, None)
+    kd, _ = oracle.seq_dequantize(Lo, planes, T0, 0, nq)
+    assert np.abs(ko.cpu().numpy() - kd).max() <= 1e-5 * np.abs(kd).max()       # (R^T in binary32 on both sides)
+    qn = synth.to_numpy_bits(q) if raw else q.numpy()
+    out = _decode(kvq, Lg, cache, q, T0)
+    ref = oracle.seq_decode_attention(Lo, planes, qn, T0, 1 / math.sqrt(128), bf16=bool(raw))
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+    Kd, Vd = K.cuda(), V.cuda()
+    o2 = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    for pos in range(T0, T):                                   # 33 steps: the one at position 319 flushes a block
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), 1 / math.sqrt(128), o2, ws)
+        torch.cuda.synchronize()
+        oracle.seq_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, pos:pos + 1])),
+                          np.ascontiguousarray(synth.to_numpy_bits(V[:, :, pos:pos + 1])), pos, bf16=bool(raw))
+        if pos in (T0, 318, 319, 320, T - 1):
+            ref = oracle.seq_decode_attention(Lo, planes, qn, pos + 1, 1 / math.sqrt(128), bf16=bool(raw))
+            assert _rel_err(o2.cpu().numpy(), ref) < TOL, pos
+    _assert_seq_planes_equal(cache, planes)
+
+
 # --------------------------------------------------------------------------- per-sequence lengths
 
 @pytest.mark.parametrize("R,bk,bv,gk,gv", [(4, 4, 2, 64, 64), (8, 4, 2, 32, 64), (1, 2, 4, 64, 128), (8, 8, 8, 64, 64)])
