@@ -41,6 +41,11 @@
  *     by channel (one scale/zero per channel and block), the G_K value rows token-wise as
  *     always; attention reads tokens below floor(seq_len / G_K) * G_K from the codes and the
  *     rest from the buffer.  Tokens must be appended in order, starting at 0.
+ *     The buffer's length is a parameter of its own (resid_len): the downstream runs pair a 64-token buffer with
+ *     128-element groups, which can only be groups along head_dim (a 64-token flush cannot fill a 128-token group):
+ *     with axis_k = 0 and resid_len = RL the keys are token-wise as on the plain path, and the only difference to it
+ *     is that the newest n mod RL tokens are still in the buffer; with axis_k = 1 a flush of RL tokens quantizes
+ *     RL / G_K groups per channel.
  *     With rotate_k (the study's best setting, K4V2 with key-only rotation, on the per-column back-end of the
  *     downstream runs: Sec. 5.3 and Sec. 4) the buffer still keeps the input rows; a flush quantizes R k of every
  *     row, channel by channel in the rotated basis; attention takes the scores of the flushed tokens from the
@@ -82,12 +87,13 @@
  *              "tokens x channels" operand, so a decode kernel needs no transpose.)
  *   bits == 16 the planes hold the 16-bit input patterns unchanged in the same positions
  *              (b = 16 in the formulas above); the meta planes are unused.
- *   axis_k == 1 (channel-wise keys, G = group_k): T_cap = max_seq rounded up to a multiple of
- *              max(32, G); k_codes and the value planes as above;
- *              k_meta  [B][H][T_cap/G][D] entries (scale, zero as above): entry (t/G, d);
- *              k_resid [B][H][G][D] 16-bit patterns, token t in slot t % G, row-major;
- *              v_resid [B][H][G/32] blocks in the v_codes order with b = 16, token t in block
- *                      (t % G) / 32 at u = t % 32.
+ *   residual buffer (RL = resid_len slots; RL = group_k when resid_len is 0 and axis_k == 1): T_cap = max_seq rounded
+ *              up to a multiple of max(32, RL); all four planes as above for tokens below floor(n / RL) * RL, n the
+ *              number of tokens appended; with axis_k == 1 (channel-wise keys, G = group_k, RL a multiple of G)
+ *              k_meta is [B][H][T_cap/G][D] entries (scale, zero as above): entry (t/G, d);
+ *              k_resid [B][H][RL][D] 16-bit patterns, token t in slot t % RL, row-major;
+ *              v_resid [B][H][RL/32] blocks in the v_codes order with b = 16, token t in block
+ *                      (t % RL) / 32 at u = t % 32.
  */
 #include <math.h>
 #include <stddef.h>
@@ -109,7 +115,11 @@ typedef struct {
   int32_t rotate_v;         /* 1: value rows are stored as codes of R_v v (needs bits_v < 16); the attention output is
                                taken back with R_v^T.  The paper's rotation study covers none / keys / values / both. */
   uint32_t signs_v[4];
+  int32_t resid_len;        /* slots of the full-precision residual buffer: 0 = none (axis_k == 0) or group_k (axis_k == 1) */
 } ref_layout;
+
+/* tokens the residual buffer holds before it is flushed; 0: the layout has no buffer */
+static int resid_slots(const ref_layout* L) { return L->resid_len ? L->resid_len : (L->axis_k == 1 ? L->group_k : 0); }
 
 /* ------------------------------------------------------------------ number formats */
 
@@ -174,7 +184,7 @@ int ref_threads(void) { return 1; }
 static int bits_allowed(int b) { return b == 1 || b == 2 || b == 3 || b == 4 || b == 6 || b == 8; }
 
 static int64_t cap_tokens(const ref_layout* L) {
-  int64_t unit = (L->axis_k == 1 && L->group_k > 32) ? L->group_k : 32;
+  int64_t unit = resid_slots(L) > 32 ? resid_slots(L) : 32;
   return ((int64_t)L->max_seq + unit - 1) / unit * unit;
 }
 
@@ -358,7 +368,7 @@ int ref_quantize_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, 
   if (D % 64 || D > 1024) return -1;
   if (L->rotate_k && (L->bits_k == 16 || D > 128 || (D & (D - 1)))) return -1;
   if (L->rotate_v && (L->bits_v == 16 || D > 128 || (D & (D - 1)))) return -1;
-  if (L->axis_k != 0) return -1;                            /* channel-wise keys: ref_seq_append */
+  if (L->axis_k != 0 || L->resid_len != 0) return -1;       /* channel-wise keys, residual buffer: ref_seq_append */
   uint64_t pb[4];
   ref_plane_bytes(L, pb);
   int64_t streams = (int64_t)L->batch * L->kv_heads;
@@ -424,7 +434,7 @@ int ref_dequantize_stored(const ref_layout* L, const uint8_t* k_codes, const uin
                           const uint8_t* v_meta, int32_t t0, int32_t t1, float* k_out, float* v_out) {
   int D = L->head_dim;
   if (t0 < 0 || t1 < t0 || t1 > L->max_seq) return -3;
-  if (L->axis_k != 0) return -1;                            /* channel-wise keys: ref_seq_dequantize */
+  if (L->axis_k != 0 || L->resid_len != 0) return -1;       /* channel-wise keys, residual buffer: ref_seq_dequantize */
   uint64_t pb[4];
   ref_plane_bytes(L, pb);
   int64_t streams = (int64_t)L->batch * L->kv_heads;
@@ -563,7 +573,7 @@ int ref_decode_attention(const ref_layout* L, const uint8_t* k_codes, const uint
 
 /* bytes of k_resid and v_resid (axis_k == 1) */
 int ref_resid_bytes(const ref_layout* L, uint64_t out[2]) {
-  uint64_t n = (uint64_t)L->batch * L->kv_heads * L->group_k * L->head_dim * 2;
+  uint64_t n = (uint64_t)L->batch * L->kv_heads * resid_slots(L) * L->head_dim * 2;
   out[0] = n;
   out[1] = n;
   return 0;
@@ -571,7 +581,10 @@ int ref_resid_bytes(const ref_layout* L, uint64_t out[2]) {
 
 static int seq_layout_ok(const ref_layout* L) {
   int G = L->group_k, D = L->head_dim;
-  if (L->axis_k != 1 || L->rotate_v) return 0;
+  int RL = resid_slots(L);
+  if ((L->axis_k != 0 && L->axis_k != 1) || L->rotate_v) return 0;
+  if (RL != 32 && RL != 64 && RL != 128) return 0;
+  if (L->axis_k == 1 ? (RL % G != 0) : (D % G != 0)) return 0;
   if (L->rotate_k && (D > 128 || (D & (D - 1)))) return 0;
   if (G != 32 && G != 64 && G != 128) return 0;
   if (D % 64 || D > 1024 || D % L->group_v) return 0;
@@ -598,11 +611,11 @@ int ref_seq_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, uint8
   if (!seq_layout_ok(L)) return -1;
   if (in_dtype != L->raw_dtype) return -1;
   if (pos < 0 || n_new < 0 || (int64_t)pos + n_new > L->max_seq) return -3;
-  int D = L->head_dim, G = L->group_k, GV = L->group_v, bk = L->bits_k, bv = L->bits_v;
+  int D = L->head_dim, G = L->group_k, GV = L->group_v, bk = L->bits_k, bv = L->bits_v, RL = resid_slots(L);
   uint64_t pb[4];
   ref_plane_bytes(L, pb);
   int64_t streams = (int64_t)L->batch * L->kv_heads;
-  int64_t rstream = (int64_t)G * D * 2;
+  int64_t rstream = (int64_t)RL * D * 2;
   float* col = (float*)malloc(sizeof(float) * (size_t)(G > D ? G : D));
   uint8_t* codes = (uint8_t*)malloc((size_t)(G > D ? G : D));
   for (int64_t bh = 0; bh < streams; ++bh) {
@@ -615,19 +628,19 @@ int ref_seq_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, uint8
     uint8_t* vr = v_resid + bh * rstream;
     for (int64_t tn = 0; tn < n_new; ++tn) {
       int64_t t = pos + tn;
-      int slot = (int)(t % G);
+      int slot = (int)(t % RL);
       int64_t base = bi * stride_b + hi * stride_h + tn * stride_t;
       for (int d = 0; d < D; ++d) {                           /* the newest token stays in full precision */
         uint32_t kb = ((const uint16_t*)k_new)[base + d], vb = ((const uint16_t*)v_new)[base + d];
         put_bits_le(kr, ((int64_t)slot * D + d) * 16, 16, kb);
         v_put_code(vr, slot, d, D, 16, vb);
       }
-      if (slot != G - 1) continue;
-      /* flush the block that just filled up */
-      int64_t blk = t / G, t0 = blk * G;
-      float* rows = (float*)malloc(sizeof(float) * (size_t)G * (size_t)D);   /* the block's key rows (R k with rotate_k) */
+      if (slot != RL - 1) continue;
+      /* flush the RL tokens that fill the buffer */
+      int64_t t0 = t + 1 - RL;
+      float* rows = (float*)malloc(sizeof(float) * (size_t)RL * (size_t)D);  /* the buffer's key rows (R k with rotate_k) */
       float* plain = (float*)malloc(sizeof(float) * (size_t)D);
-      for (int i = 0; i < G; ++i) {
+      for (int i = 0; i < RL; ++i) {
         for (int d = 0; d < D; ++d) {
           uint16_t bits16 = resid_get_k(kr, i, d, D);
           plain[d] = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32(bits16) : ref_f16_to_f32(bits16);
@@ -635,17 +648,31 @@ int ref_seq_append(const ref_layout* L, uint8_t* k_codes, uint8_t* k_meta, uint8
         if (L->rotate_k) ref_rotate(plain, D, L->signs_k, rows + (size_t)i * D);
         else memcpy(rows + (size_t)i * D, plain, sizeof(float) * (size_t)D);
       }
-      for (int d = 0; d < D; ++d) {                           /* keys: one group = G tokens of channel d */
-        for (int i = 0; i < G; ++i) col[i] = rows[(size_t)i * D + d];
-        uint16_t S, Z;
-        ref_quantize_group(col, G, bk, codes, &S, &Z);
-        uint8_t* m = km + (blk * D + d) * 4;
-        m[0] = (uint8_t)(S & 0xFF); m[1] = (uint8_t)(S >> 8);
-        m[2] = (uint8_t)(Z & 0xFF); m[3] = (uint8_t)(Z >> 8);
-        for (int i = 0; i < G; ++i) k_put_code(kc, t0 + i, d, D, bk, codes[i]);
+      if (L->axis_k == 1) {
+        for (int sub = 0; sub < RL / G; ++sub)                /* keys: one group = G tokens of channel d */
+          for (int d = 0; d < D; ++d) {
+            for (int i = 0; i < G; ++i) col[i] = rows[(size_t)(sub * G + i) * D + d];
+            uint16_t S, Z;
+            ref_quantize_group(col, G, bk, codes, &S, &Z);
+            uint8_t* m = km + (((t0 + sub * G) / G) * D + d) * 4;
+            m[0] = (uint8_t)(S & 0xFF); m[1] = (uint8_t)(S >> 8);
+            m[2] = (uint8_t)(Z & 0xFF); m[3] = (uint8_t)(Z >> 8);
+            for (int i = 0; i < G; ++i) k_put_code(kc, t0 + sub * G + i, d, D, bk, codes[i]);
+          }
+      } else {
+        for (int i = 0; i < RL; ++i) {                        /* keys token-wise: groups of G channels of one row */
+          for (int g = 0; g < D / G; ++g) {
+            uint16_t S, Z;
+            ref_quantize_group(rows + (size_t)i * D + g * G, G, bk, codes + g * G, &S, &Z);
+            uint8_t* m = km + meta_offset(t0 + i, g, D / G);
+            m[0] = (uint8_t)(S & 0xFF); m[1] = (uint8_t)(S >> 8);
+            m[2] = (uint8_t)(Z & 0xFF); m[3] = (uint8_t)(Z >> 8);
+          }
+          for (int d = 0; d < D; ++d) k_put_code(kc, t0 + i, d, D, bk, codes[d]);
+        }
       }
       free(rows); free(plain);
-      for (int i = 0; i < G; ++i) {                           /* values: token-wise groups as always */
+      for (int i = 0; i < RL; ++i) {                          /* values: token-wise groups as always */
         for (int d = 0; d < D; ++d) {
           uint16_t bits16 = resid_get_v(vr, i, d, D);
           col[d] = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32(bits16) : ref_f16_to_f32(bits16);
@@ -673,12 +700,12 @@ static int seq_dequantize_impl(const ref_layout* L, const uint8_t* k_codes, cons
                                int32_t t0, int32_t t1, float* k_out, float* v_out, int stored) {
   if (!seq_layout_ok(L)) return -1;
   if (t0 < 0 || t1 < t0 || t1 > seq_len || seq_len > L->max_seq) return -3;
-  int D = L->head_dim, G = L->group_k, GV = L->group_v, bk = L->bits_k, bv = L->bits_v;
+  int D = L->head_dim, G = L->group_k, GV = L->group_v, bk = L->bits_k, bv = L->bits_v, RL = resid_slots(L);
   uint64_t pb[4];
   ref_plane_bytes(L, pb);
   int64_t streams = (int64_t)L->batch * L->kv_heads;
-  int64_t rstream = (int64_t)G * D * 2;
-  int64_t n_flushed = (int64_t)seq_len / G * G;
+  int64_t rstream = (int64_t)RL * D * 2;
+  int64_t n_flushed = (int64_t)seq_len / RL * RL;
   int64_t nt = t1 - t0;
   for (int64_t bh = 0; bh < streams; ++bh) {
     const uint8_t* kc = k_codes + bh * (int64_t)(pb[0] / (uint64_t)streams);
@@ -691,12 +718,12 @@ static int seq_dequantize_impl(const ref_layout* L, const uint8_t* k_codes, cons
       for (int d = 0; d < D; ++d) {
         float kv, vv;
         if (t < n_flushed) {
-          const uint8_t* m = km + ((t / G) * D + d) * 4;
+          const uint8_t* m = L->axis_k == 1 ? km + ((t / G) * D + d) * 4 : km + meta_offset(t, d / G, D / G);
           kv = ref_reconstruct(k_get_code(kc, t, d, D, bk), (uint16_t)(m[0] | (m[1] << 8)), (uint16_t)(m[2] | (m[3] << 8)));
           const uint8_t* mv = vm + meta_offset(t, d / GV, D / GV);
           vv = ref_reconstruct(v_get_code(vc, t, d, D, bv), (uint16_t)(mv[0] | (mv[1] << 8)), (uint16_t)(mv[2] | (mv[3] << 8)));
         } else {
-          uint16_t kb = resid_get_k(kr, (int)(t % G), d, D), vb = resid_get_v(vr, (int)(t % G), d, D);
+          uint16_t kb = resid_get_k(kr, (int)(t % RL), d, D), vb = resid_get_v(vr, (int)(t % RL), d, D);
           kv = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32(kb) : ref_f16_to_f32(kb);
           vv = L->raw_dtype == REF_BF16 ? ref_bf16_to_f32(vb) : ref_f16_to_f32(vb);
         }
@@ -741,7 +768,7 @@ int ref_seq_decode_attention(const ref_layout* L, const uint8_t* k_codes, const 
     /* the dense definition with the query that belongs to each token's basis: binary16(R q) for the flushed tokens,
      * q for the tail */
     int D = L->head_dim, R = q_heads / L->kv_heads;
-    int64_t n_flushed = (int64_t)seq_len / L->group_k * L->group_k;
+    int64_t n_flushed = (int64_t)seq_len / resid_slots(L) * resid_slots(L);
     float* qp = (float*)malloc(sizeof(float) * (size_t)D);
     float* qr = (float*)malloc(sizeof(float) * (size_t)D);
     double* logit = (double*)malloc(sizeof(double) * (size_t)seq_len);

@@ -20,7 +20,10 @@ F16, BF16, F32 = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (strict IEEE: no contraction, no fast-math)."""
+    """Compile the oracle with gcc (strict IEEE: no contraction, no fast-math).  KVQ_ORACLE_LIB names a library built
+    some other way from the same source (a sanitizer build, say) to load instead."""
+    if os.environ.get("KVQ_ORACLE_LIB"):
+        return os.environ["KVQ_ORACLE_LIB"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
                "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
@@ -30,7 +33,8 @@ def build(force: bool = False) -> str:
 
 class _Layout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "kv_heads", "max_seq", "head_dim", "bits_k", "bits_v",
-                                          "group_k", "group_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4), ("axis_k", C.c_int32), ("rotate_v", C.c_int32), ("signs_v", C.c_uint32 * 4)]
+                                          "group_k", "group_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4), ("axis_k", C.c_int32), ("rotate_v", C.c_int32), ("signs_v", C.c_uint32 * 4),
+                                                                                          ("resid_len", C.c_int32)]
 
 
 @dataclass(frozen=True)
@@ -49,11 +53,12 @@ class Layout:
     axis_k: int = 0                    # 1: channel-wise key groups (group_k tokens) + residual buffer
     rotate_v: int = 0
     signs_v: tuple = (0, 0, 0, 0)
+    resid_len: int = 0                 # slots of the residual buffer: 0 = none (axis_k 0) or group_k (axis_k 1)
 
     def c(self) -> _Layout:
         return _Layout(self.batch, self.kv_heads, self.max_seq, self.head_dim, self.bits_k, self.bits_v,
                        self.group_k, self.group_v, self.raw_dtype, self.rotate_k, (C.c_uint32 * 4)(*self.signs_k),
-                       self.axis_k, self.rotate_v, (C.c_uint32 * 4)(*self.signs_v))
+                       self.axis_k, self.rotate_v, (C.c_uint32 * 4)(*self.signs_v), self.resid_len)
 
 
 _lib = None

@@ -437,3 +437,84 @@ def test_rotation_and_per_column_groups_on_outlier_channels(oracle):
             err[axis, rot] = oracle.mse(K16.astype(np.float32), kd)
     assert err[0, 1] < err[1, 0] < 0.5 * err[0, 0]
     assert abs(err[1, 1] / err[1, 0] - 1) < 0.15
+
+
+# --------------------------------------------------------------------------- the buffer's length as a parameter of its own
+
+@pytest.mark.parametrize("G,RL,bk,bv", [(128, 64, 4, 2), (64, 64, 2, 4), (32, 128, 8, 8), (128, 32, 3, 2)])
+def test_token_wise_keys_behind_a_residual_buffer(oracle, G, RL, bk, bv):
+    """The downstream runs' pairing (Sec. 4: a 64-token full-precision buffer in front of 128-element groups, which can
+    only run along head_dim): keys token-wise as on the plain path, the newest n mod RL tokens still in the buffer.
+    Flushed planes = the plain token-wise planes of the same tokens (that path has its own numpy pins), nothing is
+    written beyond them, the buffer holds the tail, attention sees reconstruction + tail."""
+    rng = np.random.default_rng(G + RL)
+    B, Hk, Hq, D = 1, 2, 4, 128
+    T = 2 * RL + 21
+    K = (rng.standard_normal((B, Hk, T, D)) * 3).astype(np.float16)
+    V = rng.standard_normal((B, Hk, T, D)).astype(np.float16)
+    q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    L = oracle.Layout(B, Hk, T, D, bk, bv, G, 64, resid_len=RL)
+    pl = oracle.new_seq_planes(L, fill=0xA5)
+    cap = -(-T // max(32, RL)) * max(32, RL)
+    assert [p.size for p in pl] == [B * Hk * cap * 16 * bk, B * Hk * cap * (D // G) * 4, B * Hk * cap * 16 * bv,
+                                    B * Hk * cap * 2 * 4, B * Hk * RL * D * 2, B * Hk * RL * D * 2]
+    for a, b in ((0, 1), (1, RL - 1), (RL - 1, RL + 3), (RL + 3, T)):
+        oracle.seq_append(L, pl, np.ascontiguousarray(K[:, :, a:b]), np.ascontiguousarray(V[:, :, a:b]), a)
+    nq = T // RL * RL
+    Lp = oracle.Layout(B, Hk, cap, D, bk, bv, G, 64)
+    plain = oracle.new_planes(Lp, fill=0xA5)
+    oracle.quantize_append(Lp, plain, np.ascontiguousarray(K[:, :, :nq]), np.ascontiguousarray(V[:, :, :nq]), 0)
+    for got, want in zip(pl[:4], plain):
+        assert np.array_equal(got, want)                                 # flushed tokens as on the plain path, the rest untouched
+    kr = pl[4].reshape(B * Hk, RL, D * 2).view(np.float16).reshape(B * Hk, RL, D)
+    for t in range(nq, T):
+        assert np.array_equal(kr[:, t % RL], K.reshape(B * Hk, T, D)[:, t])
+    kd, vd = oracle.seq_dequantize(L, pl, T, 0, T)
+    kp, vp = oracle.dequantize(Lp, plain, 0, nq)
+    assert np.array_equal(kd[:, :, :nq], kp) and np.array_equal(vd[:, :, :nq], vp)
+    assert np.array_equal(kd[:, :, nq:], K[:, :, nq:].astype(np.float32)) and np.array_equal(vd[:, :, nq:], V[:, :, nq:].astype(np.float32))
+    got = oracle.seq_decode_attention(L, pl, q, T, 1 / math.sqrt(D))
+    Kt = torch.from_numpy(kd).double().repeat_interleave(Hq // Hk, dim=1)
+    Vt = torch.from_numpy(vd).double().repeat_interleave(Hq // Hk, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q.astype(np.float64)).unsqueeze(2), Kt, Vt,
+                                                           scale=1 / math.sqrt(D)).squeeze(2).numpy()
+    assert np.abs(got - ref).max() <= 2e-6 * np.abs(ref).max()
+    # the plain entry points refuse a layout with a buffer (its tail is not in the planes)
+    with pytest.raises(ValueError):
+        oracle.quantize_append(L, pl[:4], K, V, 0)
+
+
+@pytest.mark.parametrize("G,RL,bk", [(32, 64, 4), (32, 128, 2), (64, 128, 8), (128, 128, 4)])
+def test_channel_wise_groups_shorter_than_the_buffer(oracle, G, RL, bk):
+    """A flush of RL tokens quantizes RL / G groups per channel (numpy column quantizer per group), and happens only
+    when the buffer is full: with 32-token groups and a 64-token buffer, tokens 64..95 of a 100-token sequence are
+    still in the buffer although they would fill a group."""
+    rng = np.random.default_rng(G * 3 + RL)
+    B, H, D = 1, 2, 128
+    T = 2 * RL + RL // 2 + 5
+    K = (rng.standard_normal((B, H, T, D)) * 3).astype(np.float16)
+    K[..., [5, 37]] *= 20
+    V = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    L = oracle.Layout(B, H, T, D, bk, 2, G, 64, axis_k=1, resid_len=RL)
+    pl = oracle.new_seq_planes(L, fill=0xA5)
+    oracle.seq_append(L, pl, K, V, 0)
+    nq = T // RL * RL
+    cap = -(-T // RL) * RL
+    assert pl[1].size == B * H * (cap // G) * D * 4 and pl[4].size == B * H * RL * D * 2
+    for h in range(H):
+        for grp in range(nq // G):
+            c, s, z = _quantize_columns_numpy(K[0, h, grp * G:(grp + 1) * G], bk)
+            meta = pl[1].reshape(B * H, -1)[h].view(np.uint16).reshape(-1, D, 2)[grp]
+            assert np.array_equal(meta[:, 0], s) and np.array_equal(meta[:, 1], z)
+            rows = pl[0].reshape(B * H, -1, 16 * bk)[h][grp * G:(grp + 1) * G]
+            assert np.array_equal(rows.ravel(), _pack_key_rows_numpy(c, bk)[:G * 16 * bk])
+        assert (pl[0].reshape(B * H, -1)[h][nq * 16 * bk:] == 0xA5).all()            # nothing beyond the flushed tokens
+        assert (pl[1].reshape(B * H, -1)[h][(nq // G) * D * 4:] == 0xA5).all()
+        kr = pl[4].reshape(B * H, RL, D * 2)[h].view(np.float16).reshape(RL, D)
+        for t in range(nq, T):
+            assert np.array_equal(kr[t % RL], K[0, h, t])
+    parts = oracle.new_seq_planes(L, fill=0xA5)
+    for a, b in ((0, 3), (3, RL), (RL, RL + 1), (RL + 1, T)):
+        oracle.seq_append(L, parts, np.ascontiguousarray(K[:, :, a:b]), np.ascontiguousarray(V[:, :, a:b]), a)
+    for x, y in zip(parts, pl):
+        assert np.array_equal(x, y)
