@@ -135,13 +135,20 @@ typedef struct {
   int32_t page_tokens;  /* 0: every (b, h) stream is contiguous.  Otherwise (a power of two, 64..65536) the planes are
                            pools of n_pages pages found through kvq_cache.page_table; see "Paged planes" above */
   int32_t n_pages;      /* pages in the pool (page_tokens != 0) */
+  int32_t resid_len;    /* slots of the full-precision residual buffer: 0 (none; with axis_k = KVQ_AXIS_SEQ: 64, the
+                           group length) or 64.  With axis_k = KVQ_AXIS_HEAD_DIM and 64 the keys stay token-wise and the
+                           cache differs from the plain one only in that the newest seq_len mod 64 tokens are still in
+                           the buffer (Sec. 4 "Downstream Task Accuracy": a 64-token buffer in front of 128-element
+                           groups); everything said under "Channel-wise keys" about the buffer, the flush, the
+                           appends in order and the calls holds for it, with the keys of a flushed block quantized row
+                           by row as on the plain path.  rotate_k may be combined with it, bits 16 and rotate_v not. */
 } kvq_layout;
 
 /* Caller-owned device buffers of at least the sizes kvq_cache_bytes reports (16-byte aligned).
  * A meta pointer may be NULL iff the matching bits == 16. */
 typedef struct {
   void *k_codes, *k_meta, *v_codes, *v_meta;
-  void *k_resid, *v_resid; /* residual buffers of channel-wise keys (axis_k = KVQ_AXIS_SEQ); NULL otherwise */
+  void *k_resid, *v_resid; /* residual buffers (axis_k = KVQ_AXIS_SEQ, or resid_len = 64); NULL otherwise */
   const int32_t* page_table; /* paged planes: device, int32 [B][ceil(max_seq / page_tokens)]: logical page -> pool page
                                 (each in [0, n_pages); entries of pages no call touches are never read); else NULL */
   int32_t* v_scale_exp;      /* device, int32 [B][H_kv], part of the cache's state whenever bits_v < 16 (else it may be
@@ -157,7 +164,8 @@ typedef struct {
  * claim (Sec. 1): K4V2 code bytes are 3/4 of K4V4's. */
 kvq_status kvq_cache_bytes(const kvq_layout* layout, size_t bytes_out[4]);
 
-/* Host only.  bytes_out = sizes of k_resid, v_resid: 0, 0 unless axis_k = KVQ_AXIS_SEQ. */
+/* Host only.  bytes_out = sizes of k_resid, v_resid: 0, 0 unless the layout has a residual buffer (axis_k =
+ * KVQ_AXIS_SEQ, or resid_len = 64). */
 kvq_status kvq_residual_bytes(const kvq_layout* layout, size_t bytes_out[2]);
 
 /* Bytes of scratch kvq_decode_attention needs for (q_heads, seq_len): the partial (max, sum, accumulator) records of its

@@ -31,10 +31,13 @@ kvq_status check_layout(const kvq_layout* L) {
   }
   if (L->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;
   if (L->axis_v != KVQ_AXIS_HEAD_DIM) return KVQ_ERR_UNSUPPORTED;
-  if (L->axis_k == KVQ_AXIS_SEQ) {
-    // channel-wise keys: 64-token groups with a 64-slot residual buffer; quantized keys and values; keys may be rotated
+  if (L->resid_len < 0) return KVQ_ERR_INVALID_ARG;
+  if (L->resid_len != 0 && L->resid_len != kvq::kSeqGroup) return KVQ_ERR_UNSUPPORTED;
+  if (kvq::has_residual(*L)) {
+    // a 64-slot residual buffer: quantized keys and values; keys may be rotated
     if (L->bits_k == 16 || L->bits_v == 16 || L->rotate_v) return KVQ_ERR_INVALID_ARG;
-    if (L->group_k != kvq::kSeqGroup) return KVQ_ERR_UNSUPPORTED;
+    // channel-wise keys: groups of 64 tokens, the buffer's length
+    if (L->axis_k == KVQ_AXIS_SEQ && L->group_k != kvq::kSeqGroup) return KVQ_ERR_UNSUPPORTED;
   }
   if ((int64_t)L->batch * L->kv_heads > 65535) return KVQ_ERR_UNSUPPORTED;
   if (L->max_seq > (1 << 24)) return KVQ_ERR_UNSUPPORTED;   // a (b,h) stream of any plane stays below 4 GiB
@@ -47,7 +50,7 @@ kvq_status check_cache(const kvq_layout* L, const kvq_cache* c) {
   if (L->bits_v != 16 && !c->v_meta) return KVQ_ERR_INVALID_ARG;
   if (!aligned16(c->k_codes) || !aligned16(c->v_codes) || !aligned16(c->k_meta) || !aligned16(c->v_meta))
     return KVQ_ERR_INVALID_ARG;
-  if (L->axis_k == KVQ_AXIS_SEQ && (!c->k_resid || !c->v_resid || !aligned16(c->k_resid) || !aligned16(c->v_resid)))
+  if (kvq::has_residual(*L) && (!c->k_resid || !c->v_resid || !aligned16(c->k_resid) || !aligned16(c->v_resid)))
     return KVQ_ERR_INVALID_ARG;
   if (L->page_tokens && (!c->page_table || (reinterpret_cast<uintptr_t>(c->page_table) & 3u))) return KVQ_ERR_INVALID_ARG;
   if (L->bits_v != 16 && (!c->v_scale_exp || (reinterpret_cast<uintptr_t>(c->v_scale_exp) & 3u))) return KVQ_ERR_INVALID_ARG;
@@ -75,7 +78,7 @@ kvq_status kvq_residual_bytes(const kvq_layout* layout, size_t bytes_out[2]) {
   kvq_status st = check_layout(layout);
   if (st != KVQ_OK) return st;
   if (!bytes_out) return KVQ_ERR_INVALID_ARG;
-  const size_t n = layout->axis_k == KVQ_AXIS_SEQ
+  const size_t n = kvq::has_residual(*layout)
                        ? (size_t)layout->batch * layout->kv_heads * kvq::kSeqGroup * kvq::kHeadDim * 2 : 0;
   bytes_out[0] = n;
   bytes_out[1] = n;
@@ -114,7 +117,7 @@ kvq_status kvq_quantize_append(const kvq_layout* layout, const kvq_cache* cache,
   if (!aligned16(k_new) || !aligned16(v_new) || stride_b % 8 || stride_h % 8 || stride_t % 8 || stride_t < layout->head_dim)
     return KVQ_ERR_INVALID_ARG;
   const kvq::Geom g = kvq::make_geom(*layout);
-  if (layout->axis_k == KVQ_AXIS_SEQ) {
+  if (kvq::has_residual(*layout)) {
     if ((int)in_dtype != layout->raw_dtype) return KVQ_ERR_INVALID_ARG;   // the residual buffer keeps the input patterns
     hipError_t e = kvq::launch_seq_append(g, *cache, k_new, v_new, in_dtype, stride_b, stride_h, stride_t, pos, n_new,
                                           (hipStream_t)stream);
@@ -142,7 +145,7 @@ kvq_status decode_check(const kvq_layout* layout, const kvq_cache* cache, const 
   if (!aligned16(q) || !aligned16(out)) return KVQ_ERR_INVALID_ARG;
   const kvq::Geom g = kvq::make_geom(*layout);
   if (!kvq::decode_supported(g, q_heads)) return KVQ_ERR_UNSUPPORTED;
-  if (layout->axis_k == KVQ_AXIS_SEQ && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // residual tail: as unquantized
+  if (kvq::has_residual(*layout) && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // residual tail: as unquantized
   if (layout->bits_k == 16 && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // matrix operands share a type
   if (layout->bits_k == 16 && fused_append) return KVQ_ERR_UNSUPPORTED; // fused append exists for quantized caches only
   size_t need = 0;
@@ -228,8 +231,8 @@ kvq_status kvq_decode_step(const kvq_layout* layout, const kvq_cache* cache, con
   if (pos >= layout->max_seq) return KVQ_ERR_CAPACITY;
   if (!k_new || !v_new || (in_dtype != KVQ_F16 && in_dtype != KVQ_BF16)) return KVQ_ERR_INVALID_ARG;
   if (!aligned16(k_new) || !aligned16(v_new) || stride_b % 8 || stride_h % 8) return KVQ_ERR_INVALID_ARG;
-  if (layout->axis_k == KVQ_AXIS_SEQ) {
-    // channel-wise keys: the new token goes through the residual buffer (and may flush a block): two calls in a row,
+  if (kvq::has_residual(*layout)) {
+    // the new token goes through the residual buffer (and may flush a block): two calls in a row,
     // the second one checked before the first one runs
     kvq_status st = decode_check(layout, cache, q, q_dtype, q_heads, pos + 1, softmax_scale, out, out_dtype, workspace,
                                  workspace_bytes, false);
@@ -263,8 +266,8 @@ kvq_status kvq_decode_step_varlen(const kvq_layout* layout, const kvq_cache* cac
   if (max_pos >= layout->max_seq) return KVQ_ERR_CAPACITY;
   if (!k_new || !v_new || (in_dtype != KVQ_F16 && in_dtype != KVQ_BF16)) return KVQ_ERR_INVALID_ARG;
   if (!aligned16(k_new) || !aligned16(v_new) || stride_b % 8 || stride_h % 8) return KVQ_ERR_INVALID_ARG;
-  if (layout->axis_k == KVQ_AXIS_SEQ) {
-    // channel-wise keys: every sequence's new token goes through its residual buffer at its own position (and may
+  if (kvq::has_residual(*layout)) {
+    // every sequence's new token goes through its residual buffer at its own position (and may
     // flush a block there), then the attention with lengths pos[b] + 1; everything is checked before anything runs
     kvq_status st = decode_check(layout, cache, q, q_dtype, q_heads, max_pos + 1, softmax_scale, out, out_dtype, workspace,
                                  workspace_bytes, false);

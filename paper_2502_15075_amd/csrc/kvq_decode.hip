@@ -1460,12 +1460,12 @@ WaveBudget wave_budget(const Geom& g, int n_steps) {
   return WaveBudget{waves_per_stream, nw, splits};
 }
 int plan_steps(const Geom& g, int32_t seq_len) {
-  return g.axis_k == KVQ_AXIS_SEQ ? seq_len / kSeqGroup * 2 : (seq_len + 31) / 32;
+  return g.resid ? seq_len / kSeqGroup * 2 : (seq_len + 31) / 32;      // (a residual buffer: the flushed tokens only)
 }
 }  // namespace
 
 // Upper bound, over every length up to seq_len, of the partial records per (batch, query head) that one decode call
-// writes (channel-wise keys: one per split of the flushed blocks plus one for the residual tail): the number of splits
+// writes (with a residual buffer: one per split of the flushed blocks plus one for the tail in the buffer): the number of splits
 // before the steps are dealt out never shrinks as the sequence grows, and dealing them out in whole multiples of the
 // workgroup's wavefronts only ever lowers it.  The workspace is sized for this bound, so a workspace sized once for the longest sequence serves every
 // shorter one (the exact count is not monotone in the length).
@@ -1473,7 +1473,7 @@ int32_t decode_records_bound(const Geom& g, int32_t seq_len) {
   const int n_steps = plan_steps(g, seq_len);
   if (n_steps == 0) return 1;
   const int splits = wave_budget(g, n_steps).splits;
-  return g.axis_k == KVQ_AXIS_SEQ ? splits + 1 : splits;
+  return g.resid ? splits + 1 : splits;
 }
 
 DecodePlan plan_decode(const Geom& g, int32_t seq_len) {
@@ -1525,9 +1525,9 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
   a.n_splits = plan.n_splits; a.steps_per_split = plan.steps_per_split;
   a.rec_splits = plan.n_splits; a.rec_base = 0;
   a.merge_tag = 0;
-  if (g.axis_k == KVQ_AXIS_SEQ) {
-    // channel-wise keys: flushed blocks from the codes (plan), the newest tokens from the residual buffer by the
-    // unquantized kernel, all partial records merged at the end
+  if (g.resid) {
+    // a residual buffer: flushed blocks from the codes (plan; channel-wise or token-wise keys), the newest tokens from
+    // the buffer by the unquantized kernel, all partial records merged at the end
     // (per-sequence lengths: seq_len is their bound; every sequence's own flushed part and tail are cut out on the
     // device, the tail launch always runs, and a sequence without one of the parts gets empty records for it)
     const bool varlen = seq_lens != nullptr;
@@ -1550,6 +1550,7 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
       t.merge_tag = 0;
       t.g.axis_k = KVQ_AXIS_HEAD_DIM; t.g.bits_k = t.g.bits_v = 16; t.g.g_k = t.g.g_v = kHeadDim; t.g.ng_k = t.g.ng_v = 1;
       t.g.rotate_k = 0;                                    // (the buffer holds the input rows: their scores take q itself)
+      t.g.resid = 0;
       t.g.t_cap = kSeqGroup; t.g.page_shift = 0; t.cache.page_table = nullptr;     // (the buffers are per sequence, never paged)
       t.g.kc_stream = t.g.vc_stream = (int64_t)kSeqGroup * kHeadDim * 2; t.g.km_stream = t.g.vm_stream = 0;
       t.cache.k_codes = c.k_resid; t.cache.v_codes = c.v_resid; t.cache.k_meta = t.cache.v_meta = nullptr;

@@ -9,7 +9,10 @@ namespace kvq {
 
 constexpr int kHeadDim = 128;     // the only head_dim the kernels are written for
 constexpr int kBlockTokens = 32;  // value codes are stored in blocks of this many tokens
-constexpr int kSeqGroup = 64;     // channel-wise keys: tokens per key group = slots of the residual buffer
+constexpr int kSeqGroup = 64;     // slots of the residual buffer = tokens per group of channel-wise keys
+
+// A layout with a residual buffer: channel-wise keys always, token-wise keys when resid_len says so.
+inline bool has_residual(const kvq_layout& L) { return L.axis_k == KVQ_AXIS_SEQ || L.resid_len != 0; }
 
 // Geometry derived once on the host and passed by value to every kernel.
 struct Geom {
@@ -18,6 +21,8 @@ struct Geom {
   int32_t raw_dtype;
   int32_t axis_k;                   // KVQ_AXIS_SEQ: channel-wise key groups of kSeqGroup tokens + residual buffer;
                                     // then g_k = 128 and ng_k = 1 (one matrix column per head on the key side)
+  int32_t resid;                    // slots of the residual buffer (kSeqGroup), 0 without one: the planes then hold the
+                                    // tokens below seq_len rounded down to it, the buffer the rest
   int32_t rotate_k;                 // key rows are stored as codes of R k (randomized Hadamard rotation)
   uint32_t signs_k[4];              // bit d set: s_d = -1
   int32_t rotate_v;                 // value rows are stored as codes of R_v v; outputs are taken back with R_v^T
@@ -35,7 +40,8 @@ inline Geom make_geom(const kvq_layout& L) {
   Geom g{};
   g.batch = L.batch; g.kv_heads = L.kv_heads;
   g.axis_k = L.axis_k;
-  g.t_cap = (int32_t)round_up(L.max_seq, L.axis_k == KVQ_AXIS_SEQ ? kSeqGroup : kBlockTokens);
+  g.resid = has_residual(L) ? kSeqGroup : 0;
+  g.t_cap = (int32_t)round_up(L.max_seq, g.resid ? kSeqGroup : kBlockTokens);
   g.page_shift = 0; g.pages_per_seq = 0;
   if (L.page_tokens) {
     while ((1 << g.page_shift) < L.page_tokens) ++g.page_shift;

@@ -243,7 +243,9 @@ template <int B> __device__ __forceinline__ void value_codes8(const uint8_t* cs,
 // this call completes is flushed: rows below lo come back from the residual buffer (the launcher makes sure that no
 // other workgroup of the same launch writes there), keys are quantized channel by
 // channel (the group is the 64 tokens of one channel), values token-wise exactly as in quantize_append_kernel.
-template <int BK, int BV, bool BF>
+// KTOK: the keys of a flushed block are quantized row by row like the values (a residual buffer in front of token-wise
+// keys); otherwise channel by channel.
+template <int BK, int BV, bool BF, bool KTOK>
 __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_new,
                                                          const uint16_t* __restrict__ v_new, int64_t sb, int64_t sh,
                                                          int64_t st, int32_t pos, int32_t n_new,
@@ -295,10 +297,29 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
   // rows of all four planes are addressed by the block's first token in plane order (a block never straddles a page)
   const int64_t tv0 = virtual_token(g, c.page_table, b, h, (int64_t)blk * kSpan);
   uint8_t* kc = (uint8_t*)c.k_codes;
-  uint32_t* km = (uint32_t*)c.k_meta + (tv0 / kSeqGroup) * kHeadDim;
+  uint32_t* km = (uint32_t*)c.k_meta + (tv0 / kSeqGroup) * kHeadDim;      // channel-wise keys: the block's 128 entries
+  uint32_t* km_tok = (uint32_t*)c.k_meta;                                  // token-wise keys: entries by token and group
   uint32_t* vm = (uint32_t*)c.v_meta;
   uint32_t* vc = (uint32_t*)c.v_codes + (tv0 >> 5) * (128 * BV);
 
+  if constexpr (KTOK) {
+    // ---- keys token-wise: every row on its own, exactly as quantize_append_kernel does it
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int64_t t = tv0 + rg + 16 * it;
+      const uint32_t rw[4] = {kraw[it].x, kraw[it].y, kraw[it].z, kraw[it].w};
+      float xk[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xk[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
+      if (g.rotate_k) rotate8(xk, lane16, rot_sign_bits(g.signs_k, lane16));
+      uint32_t kcodes[8];
+      uint16_t S, Z;
+      const int lpg = g.g_k >> 3;
+      quantize8(xk, BK, lpg, kcodes, &S, &Z);
+      if ((lane16 & (lpg - 1)) == 0) km_tok[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_k)] = (uint32_t)S | ((uint32_t)Z << 16);
+      store_key_codes<BK>(kc + t * (16 * BK), lane16, kcodes);
+    }
+  } else {
   // ---- keys: minimum and maximum of every channel over the 64 rows (4 rows here, 4 row groups per wavefront,
   // 4 wavefronts through LDS)
   float x[4][8];
@@ -345,6 +366,7 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
   for (int it = 0; it < 4; ++it) {
     const int64_t t = tv0 + rg + 16 * it;
     store_key_codes<BK>(kc + t * (16 * BK), lane16, codes[it]);
+  }
   }
 
   // ---- values: token-wise, as in quantize_append_kernel for a full span
@@ -611,12 +633,13 @@ hipError_t launch_sa(const Geom& g, const kvq_cache& c, const void* k_new, const
                      hipStream_t stream) {
   const int first = pos / kSeqGroup, last = (pos + n_new - 1) / kSeqGroup;
   dim3 grid(last - first + 1, g.batch * g.kv_heads);
-  if (in_dtype == KVQ_BF16)
-    hipLaunchKernelGGL((seq_append_kernel<BK, BV, true>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
-                       (const uint16_t*)v_new, sb, sh, st, pos, n_new, pos_arr, max_pos);
-  else
-    hipLaunchKernelGGL((seq_append_kernel<BK, BV, false>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
-                       (const uint16_t*)v_new, sb, sh, st, pos, n_new, pos_arr, max_pos);
+  const bool bf = in_dtype == KVQ_BF16, ktok = g.axis_k != KVQ_AXIS_SEQ;
+#define KVQ_SA_LAUNCH(BF_, KTOK_)                                                                                        \
+  hipLaunchKernelGGL((seq_append_kernel<BK, BV, BF_, KTOK_>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new, \
+                     (const uint16_t*)v_new, sb, sh, st, pos, n_new, pos_arr, max_pos)
+  if (bf) { if (ktok) KVQ_SA_LAUNCH(true, true); else KVQ_SA_LAUNCH(true, false); }
+  else { if (ktok) KVQ_SA_LAUNCH(false, true); else KVQ_SA_LAUNCH(false, false); }
+#undef KVQ_SA_LAUNCH
   return hipGetLastError();
 }
 template <int BK>

@@ -33,7 +33,8 @@ class KvqError(RuntimeError):
 class _CLayout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "kv_heads", "max_seq", "head_dim", "bits_k", "bits_v", "group_k",
                                           "group_v", "axis_k", "axis_v", "raw_dtype", "rotate_k")] + [("signs_k", C.c_uint32 * 4), ("rotate_v", C.c_int32), ("signs_v", C.c_uint32 * 4),
-                                                                       ("page_tokens", C.c_int32), ("n_pages", C.c_int32)]
+                                                                       ("page_tokens", C.c_int32), ("n_pages", C.c_int32),
+                                                                       ("resid_len", C.c_int32)]
 
 
 class _CCache(C.Structure):
@@ -108,6 +109,7 @@ class Layout:
     signs_v: tuple = (0, 0, 0, 0)
     page_tokens: int = 0
     n_pages: int = 0
+    resid_len: int = 0
 
     def c(self) -> _CLayout:
         return _layout_struct(self)
@@ -118,7 +120,7 @@ def _layout_struct(L: Layout) -> _CLayout:
     """The C struct of a layout, built once per distinct layout (the library only reads it)."""
     return _CLayout(L.batch, L.kv_heads, L.max_seq, L.head_dim, L.bits_k, L.bits_v, L.group_k, L.group_v, L.axis_k, L.axis_v,
                     L.raw_dtype, L.rotate_k, (C.c_uint32 * 4)(*L.signs_k), L.rotate_v, (C.c_uint32 * 4)(*L.signs_v),
-                    L.page_tokens, L.n_pages)
+                    L.page_tokens, L.n_pages, L.resid_len)
 
 
 def _check(status: int, where: str) -> None:

@@ -833,6 +833,90 @@ def test_channelwise_keys_with_key_rotation(kvq, oracle, R, bk, bv, gv, dtype):
     _assert_seq_planes_equal(cache, planes)
 
 
+@pytest.mark.parametrize("R", [1, 4, 8])
+@pytest.mark.parametrize("bk,bv,gk,gv,rot,dtype", [(4, 2, 128, 128, 0, torch.bfloat16), (4, 2, 64, 64, 0, torch.float16),
+                                                   (2, 4, 32, 128, 0, torch.bfloat16), (8, 8, 128, 32, 1, torch.float16),
+                                                   (3, 1, 64, 64, 1, torch.bfloat16)])
+def test_token_wise_keys_behind_a_residual_buffer(kvq, oracle, R, bk, bv, gk, gv, rot, dtype):
+    """Sec. 4 "Downstream Task Accuracy": a 64-token full-precision buffer in front of token-wise groups (128-element
+    groups in the paper's runs).  Six planes byte-identical after ragged chunked appends and after one bulk append,
+    attention at lengths with and without a tail, decode steps across a flush, per-sequence lengths."""
+    B, H, T = 2, 2, 333
+    raw = 1 if dtype == torch.bfloat16 else 0
+    signs = SIGNS if rot else (0, 0, 0, 0)
+    K, V, q = synth.make_kvq(400 + bk + R, B, H, H * R, T, dtype=dtype)
+    Lg = kvq.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw, rotate_k=rot, signs_k=signs, resid_len=64)
+    Lo = oracle.Layout(B, H, T, 128, bk, bv, gk, gv, raw_dtype=raw, rotate_k=rot, signs_k=signs, resid_len=64)
+    assert kvq.cache_bytes(Lg) == oracle.plane_bytes(Lo) and kvq.residual_bytes(Lg) == [B * H * 64 * 256] * 2
+    T0 = 300
+    chunks = [(0, 1), (1, 63), (63, 70), (70, 257), (257, T0)]
+    cache, planes = _seq_fill_both(kvq, oracle, Lg, Lo, K[:, :, :T0], V[:, :, :T0], chunks)
+    _assert_seq_planes_equal(cache, planes)
+    cache2, planes2 = _seq_fill_both(kvq, oracle, Lg, Lo, K[:, :, :T0], V[:, :, :T0], [(0, T0)])
+    _assert_seq_planes_equal(cache2, planes2)
+    qn = synth.to_numpy_bits(q) if raw else q.numpy()
+    bf = bool(raw)
+    for seq_len in (T0,):
+        out = _decode(kvq, Lg, cache, q, seq_len)
+        ref = oracle.seq_decode_attention(Lo, planes, qn, seq_len, 1 / math.sqrt(128), bf16=bf)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, seq_len
+    for n in (256, 64, 63, 1):                                 # whole blocks only, one block, buffer only
+        c3, p3 = _seq_fill_both(kvq, oracle, Lg, Lo, K[:, :, :n], V[:, :, :n], [(0, n)])
+        out = _decode(kvq, Lg, c3, q, n)
+        ref = oracle.seq_decode_attention(Lo, p3, qn, n, 1 / math.sqrt(128), bf16=bf)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, n
+    Kd, Vd = K.cuda(), V.cuda()
+    o2 = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    for pos in range(T0, T):                                   # the step at position 319 flushes a block
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), 1 / math.sqrt(128), o2, ws)
+        torch.cuda.synchronize()
+        oracle.seq_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, pos:pos + 1])),
+                          np.ascontiguousarray(synth.to_numpy_bits(V[:, :, pos:pos + 1])), pos, bf16=bf)
+        if pos in (T0, 318, 319, 320, T - 1):
+            ref = oracle.seq_decode_attention(Lo, planes, qn, pos + 1, 1 / math.sqrt(128), bf16=bf)
+            assert _rel_err(o2.cpu().numpy(), ref) < TOL, pos
+    _assert_seq_planes_equal(cache, planes)
+
+
+def test_token_wise_residual_ragged_batch(kvq, oracle):
+    """Per-sequence lengths with a residual buffer in front of token-wise keys: every sequence has its own flushed
+    blocks and its own tail; a step appends every sequence's token at its own position (some flush, some do not)."""
+    B, H, R, cap = 4, 2, 4, 400
+    lens = [383, 64, 5, 200]
+    K, V, q = synth.make_kvq(77, B, H, H * R, cap, dtype=torch.bfloat16)
+    Lg = kvq.Layout(B, H, cap, 128, 4, 2, 128, 64, raw_dtype=1, resid_len=64)
+    Lo = oracle.Layout(B, H, cap, 128, 4, 2, 128, 64, raw_dtype=1, resid_len=64)
+    cache = kvq.Cache(Lg, fill=0x3C)
+    planes = oracle.new_seq_planes(Lo, fill=0x3C)
+    Kd, Vd = K.cuda(), V.cuda()
+    Kb, Vb = synth.to_numpy_bits(K), synth.to_numpy_bits(V)
+    for b in range(B):
+        L1g = replace(Lg, batch=1)
+        kvq.quantize_append(L1g, cache.batch_element(b, L1g), Kd[b:b + 1, :, :lens[b]], Vd[b:b + 1, :, :lens[b]], 0)
+        L1o, p1 = replace(Lo, batch=1), [p.reshape(B, -1)[b] for p in planes]
+        oracle.seq_append(L1o, p1, np.ascontiguousarray(Kb[b:b + 1, :, :lens[b]]), np.ascontiguousarray(Vb[b:b + 1, :, :lens[b]]), 0, bf16=True)
+    torch.cuda.synchronize()
+    _assert_seq_planes_equal(cache, planes)
+    qn = synth.to_numpy_bits(q)
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, max(lens) + 1)), dtype=torch.uint8, device="cuda")
+    kvq.decode_attention_varlen(Lg, cache, q.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"), max(lens), 1 / math.sqrt(128), out, ws)
+    torch.cuda.synchronize()
+    ref = oracle.seq_decode_attention_varlen(Lo, planes, qn, lens, 1 / math.sqrt(128), bf16=True)
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+    pos = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    kn = torch.stack([Kd[b, :, lens[b]] for b in range(B)]).contiguous()
+    vn = torch.stack([Vd[b, :, lens[b]] for b in range(B)]).contiguous()
+    kvq.decode_step_varlen(Lg, cache, kn, vn, pos, max(lens), q.cuda(), 1 / math.sqrt(128), out, ws)
+    torch.cuda.synchronize()
+    oracle.seq_append_at(Lo, planes, np.stack([Kb[b, :, lens[b]:lens[b] + 1] for b in range(B)]),
+                         np.stack([Vb[b, :, lens[b]:lens[b] + 1] for b in range(B)]), lens, bf16=True)
+    _assert_seq_planes_equal(cache, planes)
+    ref = oracle.seq_decode_attention_varlen(Lo, planes, qn, [n + 1 for n in lens], 1 / math.sqrt(128), bf16=True)
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+
+
 # --------------------------------------------------------------------------- per-sequence lengths
 
 @pytest.mark.parametrize("R,bk,bv,gk,gv", [(4, 4, 2, 64, 64), (8, 4, 2, 32, 64), (1, 2, 4, 64, 128), (8, 8, 8, 64, 64)])
