@@ -644,7 +644,7 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
   // complete anyway; left free, the scheduler pulls the unpacking of the value codes up into the softmax arithmetic,
   // which costs the kernel a dozen registers it does not have: with the fence no instance of the token-wise kernels
   // spills, without it most do.)
-  __builtin_amdgcn_sched_barrier(0);
+  if constexpr (!KSEQ) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) {
     constexpr int kDtPerSet = 8 / NCV;           // value groups of set 0 own the first d-tiles, of set 1 the rest
