@@ -38,12 +38,14 @@
  * apply R_v^T to the normalized output (binary32 butterflies) before it is stored.
  *
  * Channel-wise keys (axis_k = KVQ_AXIS_SEQ; Sec. 4 "Downstream Task Accuracy": the per-column back-end with its
- * 64-token full-precision residual buffer): a key group is 64 consecutive tokens of one channel (group_k must be
- * 64).  The newest tokens are kept as their 16-bit input patterns in a residual buffer of 64 token slots, keys and
- * values both (k_resid, v_resid in kvq_cache, sizes from kvq_residual_bytes); the token that completes a block of 64
- * triggers the flush of that block: its key rows are quantized channel by channel (one scale/zero per channel and
- * block, same arithmetic as above with the group running over tokens), its value rows token-wise as always.
- * Attention reads tokens below floor(seq_len / 64) * 64 from the codes and the rest from the buffer.  Contract:
+ * full-precision residual buffer): a key group is G = group_k (32, 64 or 128) consecutive tokens of one channel.  The
+ * newest tokens are kept as their 16-bit input patterns in a residual buffer of RL token slots, keys and values both
+ * (k_resid, v_resid in kvq_cache, sizes from kvq_residual_bytes); RL = resid_len, or G when that field is 0; RL is 64
+ * or 128 and a multiple of G (G = 32 therefore needs resid_len = 64 or 128; other lengths: KVQ_ERR_UNSUPPORTED, a buffer
+ * that whole groups do not fill: KVQ_ERR_INVALID_ARG).  The token that completes a block of RL tokens triggers the
+ * flush of that block: its key rows are quantized channel by channel (one scale/zero per channel and group of G tokens,
+ * RL / G groups per block, same arithmetic as above with the group running over tokens), its value rows token-wise as
+ * always.  Attention reads tokens below floor(seq_len / RL) * RL from the codes and the rest from the buffer.  Contract:
  * tokens are appended in order starting at 0 (pos = number of tokens appended so far), in_dtype = raw_dtype, and
  * seq_len of a decode call is that number.  Every quantized width for keys and values; bits 16 and rotate_v are not
  * combined with it; axis_v stays KVQ_AXIS_HEAD_DIM.  With rotate_k (Sec. 5.3's key-only rotation on this back-end) the
@@ -54,16 +56,17 @@
  * flushed blocks and its own tail in its residual buffer; kvq_decode_step_varlen appends sequence b's token at pos[b]
  * (= its count so far; in_dtype = raw_dtype).  kvq_dequantize and
  * kvq_reconstruction_error read the codes only: the caller keeps t1 at or below the number of flushed tokens.
- * Format: T_cap is a multiple of 64; k_meta is [B][H_kv][T_cap/64][D] entries {scale, zero},
- * entry (t/64, d); k_resid is [B][H_kv][64][D] 16-bit patterns, token t in slot t%64; v_resid is [B][H_kv][2] blocks
- * in the v_codes order with b_V = 16, token t in block (t%64)/32; the other planes are as below.
+ * Format: T_cap is a multiple of RL; k_meta is [B][H_kv][T_cap/G][D] entries {scale, zero},
+ * entry (t/G, d); k_resid is [B][H_kv][RL][D] 16-bit patterns, token t in slot t%RL; v_resid is [B][H_kv][RL/32] blocks
+ * in the v_codes order with b_V = 16, token t in block (t%RL)/32; the other planes are as below.
  *
  * Paged planes (page_tokens = P != 0; what a serving stack with a block table does): each plane is a pool
  * [n_pages][H_kv][...one head's share of a contiguous cache of capacity P...], and token t of sequence b lives in pool
  * page page_table[b][t / P] at local position t % P.  kvq_cache_bytes reports the pool sizes.  Every call takes the
  * table as it is at launch time; pages of different sequences must not alias unless they are only read.  With
- * channel-wise keys the four code and scale/zero planes are paged the same way (a 64-token block never straddles a page;
- * k_meta holds P/64 blocks per page and head) and the residual buffers stay per sequence.
+ * channel-wise keys the four code and scale/zero planes are paged the same way (group_k = 64 with a 64-slot buffer only,
+ * other lengths: KVQ_ERR_UNSUPPORTED; a 64-token block never straddles a page; k_meta holds P/64 blocks per page and
+ * head) and the residual buffers stay per sequence.
  *
  * Storage format of one layer (sizes from kvq_cache_bytes; T_cap = max_seq rounded up to 32):
  *   k_codes  [B][H_kv][T_cap][D*b_K/8]      b_K in {1,2,4,8,16}: element d of a row at bits [d*b_K, (d+1)*b_K),
@@ -135,8 +138,11 @@ typedef struct {
   int32_t page_tokens;  /* 0: every (b, h) stream is contiguous.  Otherwise (a power of two, 64..65536) the planes are
                            pools of n_pages pages found through kvq_cache.page_table; see "Paged planes" above */
   int32_t n_pages;      /* pages in the pool (page_tokens != 0) */
-  int32_t resid_len;    /* slots of the full-precision residual buffer: 0 (none; with axis_k = KVQ_AXIS_SEQ: 64, the
-                           group length) or 64.  With axis_k = KVQ_AXIS_HEAD_DIM and 64 the keys stay token-wise and the
+  int32_t resid_len;    /* slots of the full-precision residual buffer: 0 (none; with axis_k = KVQ_AXIS_SEQ: group_k of
+                           them), 64, or with channel-wise keys 128 (see "Channel-wise keys" above; the group sizes
+                           are the grid {32, 64, 128} of the group-size study, Sec. 4 "Integration with Rotation-Based
+                           Methods", the 64-token buffer is that of the downstream runs).
+                           With axis_k = KVQ_AXIS_HEAD_DIM and 64 the keys stay token-wise and the
                            cache differs from the plain one only in that the newest seq_len mod 64 tokens are still in
                            the buffer (Sec. 4 "Downstream Task Accuracy": a 64-token buffer in front of 128-element
                            groups); everything said under "Channel-wise keys" about the buffer, the flush, the

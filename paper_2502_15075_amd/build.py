@@ -24,20 +24,10 @@ DECODE_PAIRS = [(4, 2), (2, 4), (4, 4), (8, 8), (2, 2), (8, 4), (8, 2), (4, 8), 
                 (3, 2), (3, 4), (3, 8), (6, 2), (6, 4), (6, 8), (1, 2), (1, 4), (1, 8),
                 (1, 1), (2, 1), (3, 1), (4, 1), (6, 1), (8, 1),
                 (1, 3), (2, 3), (3, 3), (4, 3), (6, 3), (8, 3), (1, 6), (2, 6), (3, 6), (4, 6), (6, 6), (8, 6)]
-# Bytes of scratch memory per lane a decode kernel may use: none, except the channel-wise kernels of 3- and 6-bit keys
-# (two runs, a query operand each) in two value column sets (8 heads per KV head, 32-channel value groups).  Those sit
-# at the 256-register limit with a ring of one step already and keep up to 25 registers in scratch; they are bound by
-# their vector instructions, not by their loads.
-SCRATCH_ALLOWED_TWO_RUN_TWO_SETS = 112
-
-
+# No decode kernel may use scratch memory (a register spill in the streaming loop costs more than any ring depth gains):
+# the build fails on an instance that does.
 def _scratch_allowed(kernel_name: str) -> int:
-    """kernel_name: the mangled decode_kernel<BK, BV, R, NW, BF, NCK, NCV, KSEQ, PAGED, ROTV> instance."""
-    m = re.search(r"decode_kernelILi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)ELb(\d)ELi(\d)ELi(\d)ELb(\d)ELb(\d)ELb(\d)", kernel_name)
-    if not m:
-        return 0
-    bk, _bv, _r, _nw, _bf, _nck, ncv, kseq, _paged, _rotv = (int(x) for x in m.groups())
-    return SCRATCH_ALLOWED_TWO_RUN_TWO_SETS if (bk in (3, 6) and kseq == 1 and ncv == 2) else 0
+    return 0
 
 
 # (source, object name, extra flags).  The quantizer must round every operation once: no contraction.

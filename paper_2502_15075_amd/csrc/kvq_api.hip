@@ -32,12 +32,19 @@ kvq_status check_layout(const kvq_layout* L) {
   if (L->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;
   if (L->axis_v != KVQ_AXIS_HEAD_DIM) return KVQ_ERR_UNSUPPORTED;
   if (L->resid_len < 0) return KVQ_ERR_INVALID_ARG;
-  if (L->resid_len != 0 && L->resid_len != kvq::kSeqGroup) return KVQ_ERR_UNSUPPORTED;
   if (kvq::has_residual(*L)) {
-    // a 64-slot residual buffer: quantized keys and values; keys may be rotated
+    // a residual buffer: quantized keys and values; keys may be rotated
     if (L->bits_k == 16 || L->bits_v == 16 || L->rotate_v) return KVQ_ERR_INVALID_ARG;
-    // channel-wise keys: groups of 64 tokens, the buffer's length
-    if (L->axis_k == KVQ_AXIS_SEQ && L->group_k != kvq::kSeqGroup) return KVQ_ERR_UNSUPPORTED;
+    const int32_t slots = kvq::residual_slots(*L);
+    if (L->axis_k == KVQ_AXIS_SEQ) {
+      // channel-wise keys: groups of 32, 64 or 128 tokens; a buffer of 64 or 128 slots that a whole number of groups fills
+      if (slots % L->group_k != 0) return KVQ_ERR_INVALID_ARG;
+      if (slots != 64 && slots != 128) return KVQ_ERR_UNSUPPORTED;
+      // (paged planes: a 64-token page takes blocks of 64 tokens with one group each)
+      if (L->page_tokens && (slots != 64 || L->group_k != 64)) return KVQ_ERR_UNSUPPORTED;
+    } else if (slots != kvq::kSeqGroup) {
+      return KVQ_ERR_UNSUPPORTED;                  // token-wise keys: a buffer of 64 slots
+    }
   }
   if ((int64_t)L->batch * L->kv_heads > 65535) return KVQ_ERR_UNSUPPORTED;
   if (L->max_seq > (1 << 24)) return KVQ_ERR_UNSUPPORTED;   // a (b,h) stream of any plane stays below 4 GiB
@@ -79,7 +86,7 @@ kvq_status kvq_residual_bytes(const kvq_layout* layout, size_t bytes_out[2]) {
   if (st != KVQ_OK) return st;
   if (!bytes_out) return KVQ_ERR_INVALID_ARG;
   const size_t n = kvq::has_residual(*layout)
-                       ? (size_t)layout->batch * layout->kv_heads * kvq::kSeqGroup * kvq::kHeadDim * 2 : 0;
+                       ? (size_t)layout->batch * layout->kv_heads * kvq::residual_slots(*layout) * kvq::kHeadDim * 2 : 0;
   bytes_out[0] = n;
   bytes_out[1] = n;
   return KVQ_OK;

@@ -485,7 +485,8 @@ template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool MASKED, bool NE
 __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u32x4 (&qb)[NCK][4],
                                              const u32x4 (&qbh)[NCK][4], const float (&qsum_u)[NCK],
                                              float kappa, WaveState<NCV>& st, const LC& L, int step, int seq_len,
-                                             KS& ks, const float* qrow = nullptr, float kseq_low = 0.f) {
+                                             KS& ks, const float* qrow = nullptr, float kseq_low = 0.f,
+                                             bool rebuild = true) {
   constexpr bool RAW = BK == 16;
   constexpr int KLO = k_lo<BK>(), KHI = k_hi<BK>();   // qbh: the query operand of the high run (3- and 6-bit keys)
   constexpr bool KSEQ = !__is_same(KS, NoKSeq);
@@ -495,8 +496,10 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
     // scale/zero bytes: plane order -> LDS -> the entries this lane needs (tokens 4j..4j+3 of both tiles, own groups)
     *reinterpret_cast<u32x4*>(L.meta_lds + L.lane * 16) = r.meta;     // (lanes beyond the bytes fill slots nobody reads)
     if constexpr (KSEQ && NEWBLK) {
-      if constexpr (kseq_prescaled<BK>()) kseq_rebuild<BK>(ks, L, qrow, kseq_low);
-      else kseq_rebuild_runs<BK>(ks, L, qrow, kseq_low);
+      if (rebuild) {                             // (uniform; false only in the second step of a group of 64 or 128 tokens)
+        if constexpr (kseq_prescaled<BK>()) kseq_rebuild<BK>(ks, L, qrow, kseq_low);
+        else kseq_rebuild_runs<BK>(ks, L, qrow, kseq_low);
+      }
     }
 #pragma unroll
     for (int x4 = 0; x4 < 2; ++x4) {
@@ -819,8 +822,8 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   int seq_len = a.seq_len;
   if (a.seq_lens) {
     int n = min(max(a.seq_lens[b] + a.lens_offset, 1), a.lens_bound);
-    if (a.lens_mode == 1) n &= ~(kSeqGroup - 1);            // channel-wise keys: the flushed blocks ...
-    else if (a.lens_mode == 2) n &= kSeqGroup - 1;          // ... or the tail in the residual buffer (either may be empty)
+    if (a.lens_mode == 1) n &= ~(a.lens_block - 1);         // a residual buffer of lens_block slots: the flushed blocks ...
+    else if (a.lens_mode == 2) n &= a.lens_block - 1;       // ... or the tail in the buffer (either may be empty)
     seq_len = min(n, a.seq_len);
   }
 
@@ -836,15 +839,16 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   L.kc_off = L.c * (16 * BK) + L.j * (4 * BK);
   L.vc_off = lane * (BV == 1 ? 8 : 16);
   {
-    // channel-wise keys: 512 bytes of scale/zero per 64-token block (32 lanes), fetched with both steps of the block
+    // channel-wise keys: 512 bytes of scale/zero per group of seq_g = 32, 64 or 128 tokens (32 lanes), fetched with
+    // every step of the group (1, 2 or 4 of them)
     const int nk = KSEQ ? 32 : 8 * g.ng_k, nv = 8 * g.ng_v;
     const int ml = min(lane, nk + nv - 1);       // lanes beyond the scale/zero bytes of a step repeat the last 16
     const bool is_k = ml < nk;
     L.meta_base = is_k ? (const uint8_t*)cache.k_meta + bh_base * g.km_stream
                        : (const uint8_t*)cache.v_meta + bh_base * g.vm_stream;
-    L.meta_mul = is_k ? (KSEQ ? 256 : 128 * g.ng_k) : 128 * g.ng_v;
+    L.meta_mul = is_k ? (KSEQ ? 16384 / g.seq_g : 128 * g.ng_k) : 128 * g.ng_v;
     L.meta_off = 16 * (is_k ? ml : ml - nk);
-    L.meta_step_mask = (KSEQ && is_k) ? ~1u : ~0u;
+    L.meta_step_mask = (KSEQ && is_k) ? ~(uint32_t)((g.seq_g >> 5) - 1) : ~0u;
     L.km_rd = (L.gk * 16 + 4 * L.j) * 4;                       // key bytes come first in the LDS copy
     L.vm_rd = 16 * nk + (L.gv * 16 + 4 * L.j) * 4;
     L.meta_lds = &sm_meta[wave][0];
@@ -1093,12 +1097,15 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   // ahead, so that kStages-1 steps of loads are always in flight behind the one being computed.
   typename std::conditional<KSEQ, typename std::conditional<k_hi<BK>() != 0, KSeqState2, KSeqState>::type, NoKSeq>::type ks;
   const float* qrow = &sm_qf[KSEQ ? (grp < 2 ? h : R) : 0][0];   // (column groups 0 and 1 carry the key side)
-  // one complete step out of ring slot k (for channel-wise keys an even slot starts a block)
+  // one complete step out of ring slot k (for channel-wise keys an even slot starts a 64-token block, and the query
+  // operands are rebuilt there: once per group of 64 tokens, twice per group of 128 -- the second time from the same
+  // entries -- and in the odd steps too when a group is one step long)
+  const bool rebuild_every_step = KSEQ && g.seq_g == 32;       // (uniform)
   auto full_step = [&](int k, int i) {
     if constexpr (KSEQ) {                        // an even step of this wavefront's sequence starts a block (uniform;
       const int odd = kStages % 2 == 0 ? (k & 1) : (i & 1);      // with an even ring it is the ring slot's parity)
-      if (odd) compute_step<BK, BV, R, BF, NCK, NCV, false, false>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), n_att, ks);
-      else compute_step<BK, BV, R, BF, NCK, NCV, false, true>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), n_att, ks, qrow, grp == 1 ? 1.0f : 0.0f);
+      compute_step<BK, BV, R, BF, NCK, NCV, false, true>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), n_att, ks, qrow,
+                                                         grp == 1 ? 1.0f : 0.0f, !odd || rebuild_every_step);
     } else {
       compute_step<BK, BV, R, BF, NCK, NCV, false>(buf[k], qb, qbh, qsum_u, kappa, st, L, step_of(i), n_att, ks);
     }
@@ -1460,7 +1467,7 @@ WaveBudget wave_budget(const Geom& g, int n_steps) {
   return WaveBudget{waves_per_stream, nw, splits};
 }
 int plan_steps(const Geom& g, int32_t seq_len) {
-  return g.resid ? seq_len / kSeqGroup * 2 : (seq_len + 31) / 32;      // (a residual buffer: the flushed tokens only)
+  return g.resid ? seq_len / g.resid * (g.resid / 32) : (seq_len + 31) / 32;      // (a residual buffer: the flushed tokens only)
 }
 }  // namespace
 
@@ -1531,10 +1538,11 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
     // (per-sequence lengths: seq_len is their bound; every sequence's own flushed part and tail are cut out on the
     // device, the tail launch always runs, and a sequence without one of the parts gets empty records for it)
     const bool varlen = seq_lens != nullptr;
-    const int32_t n_flushed = seq_len / kSeqGroup * kSeqGroup;
-    const int32_t tail = varlen ? (n_flushed ? kSeqGroup - 1 : seq_len) : seq_len - n_flushed;
+    const int32_t RL = g.resid;
+    const int32_t n_flushed = seq_len / RL * RL;
+    const int32_t tail = varlen ? (n_flushed ? RL - 1 : seq_len) : seq_len - n_flushed;
     const int32_t records = plan.n_splits + (tail ? 1 : 0);
-    a.lens_bound = seq_len;
+    a.lens_bound = seq_len; a.lens_block = RL;
     hipError_t e = hipSuccess;
     if (n_flushed) {
       a.seq_len = n_flushed; a.rec_splits = records; a.rec_base = 0; a.lens_mode = 1;
@@ -1550,9 +1558,9 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
       t.merge_tag = 0;
       t.g.axis_k = KVQ_AXIS_HEAD_DIM; t.g.bits_k = t.g.bits_v = 16; t.g.g_k = t.g.g_v = kHeadDim; t.g.ng_k = t.g.ng_v = 1;
       t.g.rotate_k = 0;                                    // (the buffer holds the input rows: their scores take q itself)
-      t.g.resid = 0;
-      t.g.t_cap = kSeqGroup; t.g.page_shift = 0; t.cache.page_table = nullptr;     // (the buffers are per sequence, never paged)
-      t.g.kc_stream = t.g.vc_stream = (int64_t)kSeqGroup * kHeadDim * 2; t.g.km_stream = t.g.vm_stream = 0;
+      t.g.resid = 0; t.g.seq_g = 0;
+      t.g.t_cap = RL; t.g.page_shift = 0; t.cache.page_table = nullptr;     // (the buffers are per sequence, never paged)
+      t.g.kc_stream = t.g.vc_stream = (int64_t)RL * kHeadDim * 2; t.g.km_stream = t.g.vm_stream = 0;
       t.cache.k_codes = c.k_resid; t.cache.v_codes = c.v_resid; t.cache.k_meta = t.cache.v_meta = nullptr;
       t.seq_len = tail; t.n_splits = 1; t.steps_per_split = 4; t.lens_mode = 2;
       t.rec_splits = records; t.rec_base = records - 1;
@@ -1566,7 +1574,7 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
     }
     return e;
   }
-  a.lens_mode = 0; a.lens_bound = seq_len;
+  a.lens_mode = 0; a.lens_bound = seq_len; a.lens_block = 1;
   a.merge_tag = merge_tag_for(a.rec_splits);
   if (app) {
     a.k_new = (const uint16_t*)app->k_new; a.v_new = (const uint16_t*)app->v_new;

@@ -9,20 +9,26 @@ namespace kvq {
 
 constexpr int kHeadDim = 128;     // the only head_dim the kernels are written for
 constexpr int kBlockTokens = 32;  // value codes are stored in blocks of this many tokens
-constexpr int kSeqGroup = 64;     // slots of the residual buffer = tokens per group of channel-wise keys
+constexpr int kSeqGroup = 64;     // tokens of the block the attention kernel walks channel-wise keys in (two steps), and the
+                                  // residual buffer's usual length
 
 // A layout with a residual buffer: channel-wise keys always, token-wise keys when resid_len says so.
 inline bool has_residual(const kvq_layout& L) { return L.axis_k == KVQ_AXIS_SEQ || L.resid_len != 0; }
+// Its slots: resid_len, or the group length of channel-wise keys when that field is 0.
+inline int32_t residual_slots(const kvq_layout& L) {
+  return L.resid_len ? L.resid_len : (L.axis_k == KVQ_AXIS_SEQ ? L.group_k : 0);
+}
 
 // Geometry derived once on the host and passed by value to every kernel.
 struct Geom {
   int32_t batch, kv_heads, t_cap;   // t_cap = max_seq rounded up to kBlockTokens
   int32_t bits_k, bits_v, ng_k, ng_v, g_k, g_v;   // bits: 1, 2, 3, 4, 6, 8 (2^b - 1 steps, b bits per code in the plane), 16 = unquantized
   int32_t raw_dtype;
-  int32_t axis_k;                   // KVQ_AXIS_SEQ: channel-wise key groups of kSeqGroup tokens + residual buffer;
+  int32_t axis_k;                   // KVQ_AXIS_SEQ: channel-wise key groups of seq_g tokens + residual buffer;
                                     // then g_k = 128 and ng_k = 1 (one matrix column per head on the key side)
-  int32_t resid;                    // slots of the residual buffer (kSeqGroup), 0 without one: the planes then hold the
-                                    // tokens below seq_len rounded down to it, the buffer the rest
+  int32_t seq_g;                    // tokens per group of channel-wise keys (32, 64 or 128), 0 with token-wise keys
+  int32_t resid;                    // slots of the residual buffer (64 or 128, a multiple of seq_g), 0 without one: the
+                                    // planes then hold the tokens below seq_len rounded down to it, the buffer the rest
   int32_t rotate_k;                 // key rows are stored as codes of R k (randomized Hadamard rotation)
   uint32_t signs_k[4];              // bit d set: s_d = -1
   int32_t rotate_v;                 // value rows are stored as codes of R_v v; outputs are taken back with R_v^T
@@ -40,8 +46,9 @@ inline Geom make_geom(const kvq_layout& L) {
   Geom g{};
   g.batch = L.batch; g.kv_heads = L.kv_heads;
   g.axis_k = L.axis_k;
-  g.resid = has_residual(L) ? kSeqGroup : 0;
-  g.t_cap = (int32_t)round_up(L.max_seq, g.resid ? kSeqGroup : kBlockTokens);
+  g.resid = residual_slots(L);
+  g.seq_g = L.axis_k == KVQ_AXIS_SEQ ? L.group_k : 0;
+  g.t_cap = (int32_t)round_up(L.max_seq, g.resid ? g.resid : kBlockTokens);
   g.page_shift = 0; g.pages_per_seq = 0;
   if (L.page_tokens) {
     while ((1 << g.page_shift) < L.page_tokens) ++g.page_shift;
@@ -59,7 +66,7 @@ inline Geom make_geom(const kvq_layout& L) {
   for (int i = 0; i < 4; ++i) g.signs_v[i] = L.rotate_v ? L.signs_v[i] : 0u;
   g.kc_stream = (int64_t)g.t_cap * (kHeadDim * g.bits_k / 8);
   g.vc_stream = (int64_t)g.t_cap * (kHeadDim * g.bits_v / 8);
-  g.km_stream = L.bits_k == 16 ? 0 : L.axis_k == KVQ_AXIS_SEQ ? (int64_t)(g.t_cap / kSeqGroup) * kHeadDim * 4
+  g.km_stream = L.bits_k == 16 ? 0 : L.axis_k == KVQ_AXIS_SEQ ? (int64_t)(g.t_cap / g.seq_g) * kHeadDim * 4
                                                                 : (int64_t)g.t_cap * g.ng_k * 4;
   g.vm_stream = L.bits_v == 16 ? 0 : (int64_t)g.t_cap * g.ng_v * 4;
   return g;
@@ -92,9 +99,9 @@ struct DecodeArgs {
   // is then the upper bound the launch was planned for); nullptr: every sequence has seq_len tokens
   const int32_t* seq_lens; int32_t lens_offset;
   // channel-wise keys with per-sequence lengths: the length n = clamp(seq_lens[b] + lens_offset, 1, lens_bound) is cut
-  // into its flushed blocks (lens_mode 1: n rounded down to kSeqGroup, possibly 0) or its residual tail (lens_mode 2:
-  // n mod kSeqGroup, possibly 0); a workgroup with nothing to read writes an empty record.  lens_mode 0: n as it is.
-  int32_t lens_mode, lens_bound;
+  // into its flushed blocks (lens_mode 1: n rounded down to the buffer's length, possibly 0) or its residual tail (lens_mode 2:
+  // n modulo that length, possibly 0); a workgroup with nothing to read writes an empty record.  lens_mode 0: n as it is.
+  int32_t lens_mode, lens_bound, lens_block;   // lens_block: the buffer's slots (a power of two)
   float* ws; void* out; int out_dtype;
   int32_t n_splits, steps_per_split;
   // partial records: a workgroup writes record rec_base + split of rec_splits per (batch, query head); rec_splits == 1
@@ -115,7 +122,7 @@ struct DecodeArgs {
 hipError_t launch_quantize_append(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new,
                                   int in_dtype, int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new,
                                   hipStream_t stream);
-// Channel-wise keys: tokens go to the residual buffer; completed blocks of kSeqGroup tokens are flushed.
+// Channel-wise keys: tokens go to the residual buffer; completed blocks of g.resid tokens are flushed.
 hipError_t launch_seq_append(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype,
                              int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream);
 // ... one new token per sequence at that sequence's own position pos_arr[b] (device; clamped to [0, max_pos])

@@ -238,44 +238,47 @@ template <int B> __device__ __forceinline__ void value_codes8(const uint8_t* cs,
 }
 
 // Channel-wise keys (Sec. 4 "Downstream Task Accuracy": the per-column back-end with its residual buffer).
-// One workgroup = one block of kSeqGroup = 64 tokens of one (b,h) stream, restricted to the new tokens [lo, hi) in it.
-// New tokens that no later token of this call overwrites go to their residual slot as 16-bit patterns.  A block that
-// this call completes is flushed: rows below lo come back from the residual buffer (the launcher makes sure that no
-// other workgroup of the same launch writes there), keys are quantized channel by
-// channel (the group is the 64 tokens of one channel), values token-wise exactly as in quantize_append_kernel.
+// One workgroup = one block of RLT tokens (the residual buffer's length: 64 or 128) of one (b,h) stream, restricted to
+// the new tokens [lo, hi) in it.  New tokens that no later token of this call overwrites go to their residual slot as
+// 16-bit patterns.  A block that this call completes is flushed: rows below lo come back from the residual buffer (the
+// launcher makes sure that no other workgroup of the same launch writes there), keys are quantized channel by channel
+// (a group is g.seq_g = 32, 64 or 128 consecutive tokens of one channel, RLT / g.seq_g groups per channel and block),
+// values token-wise exactly as in quantize_append_kernel.
 // KTOK: the keys of a flushed block are quantized row by row like the values (a residual buffer in front of token-wise
 // keys); otherwise channel by channel.
-template <int BK, int BV, bool BF, bool KTOK>
+template <int BK, int BV, bool BF, bool KTOK, int RLT>
 __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_new,
                                                          const uint16_t* __restrict__ v_new, int64_t sb, int64_t sh,
                                                          int64_t st, int32_t pos, int32_t n_new,
                                                          const int32_t* __restrict__ pos_arr, int32_t max_pos) {
-  static_assert(kSeqGroup == kSpan, "a flushed block is one value span");
+  static_assert(RLT % kSpan == 0, "a flushed block is a whole number of value spans");
+  constexpr int NIT = RLT / 16;                            // rows per thread: rg, rg + 16, ...
+  constexpr int NGR = RLT / 32;                            // the most key groups a block can hold
   __shared__ __attribute__((aligned(16))) uint8_t vstage[stage_total<BV>()];
-  __shared__ float s_mn[4][kHeadDim], s_mx[4][kHeadDim];
+  __shared__ float s_mn[KTOK ? 1 : NGR][4][kHeadDim], s_mx[KTOK ? 1 : NGR][4][kHeadDim];
   const int tid = threadIdx.x;
   const int bh = blockIdx.y;
   const int b = bh / g.kv_heads, h = bh % g.kv_heads;
   if (pos_arr) pos = min(max(pos_arr[b], 0), max_pos);     // one token per sequence at its own position (n_new == 1)
-  const int blk = pos / kSpan + blockIdx.x;
-  const int lo = max(pos, blk * kSpan) - blk * kSpan;
-  const int hi = min(pos + n_new, (blk + 1) * kSpan) - blk * kSpan;
-  const bool complete = hi == kSpan;                       // this call brings the block's last token
+  const int blk = pos / RLT + blockIdx.x;
+  const int lo = max(pos, blk * RLT) - blk * RLT;
+  const int hi = min(pos + n_new, (blk + 1) * RLT) - blk * RLT;
+  const bool complete = hi == RLT;                         // this call brings the block's last token
   const int lane16 = tid & 15, rg = tid >> 4;
   const int d0 = lane16 * 8;
-  uint8_t* kr = (uint8_t*)c.k_resid + (int64_t)bh * (kSeqGroup * kHeadDim * 2);
-  uint8_t* vr = (uint8_t*)c.v_resid + (int64_t)bh * (kSeqGroup * kHeadDim * 2);
+  uint8_t* kr = (uint8_t*)c.k_resid + (int64_t)bh * (RLT * kHeadDim * 2);
+  uint8_t* vr = (uint8_t*)c.v_resid + (int64_t)bh * (RLT * kHeadDim * 2);
 
-  uint4 kraw[4], vraw[4];
+  uint4 kraw[NIT], vraw[NIT];
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
+  for (int it = 0; it < NIT; ++it) {
     const int row = rg + 16 * it;
-    const int64_t t = (int64_t)blk * kSpan + row;
+    const int64_t t = (int64_t)blk * RLT + row;
     if (row >= lo && row < hi) {
       const int64_t src = (int64_t)b * sb + (int64_t)h * sh + (t - pos) * st + d0;
       kraw[it] = *reinterpret_cast<const uint4*>(k_new + src);
       vraw[it] = *reinterpret_cast<const uint4*>(v_new + src);
-      if (t + kSeqGroup >= (int64_t)pos + n_new) {         // the last token of this call that lands in slot `row`
+      if (t + RLT >= (int64_t)pos + n_new) {               // the last token of this call that lands in slot `row`
         *reinterpret_cast<uint4*>(kr + row * (kHeadDim * 2) + d0 * 2) = kraw[it];
         const uint32_t rw[4] = {vraw[it].x, vraw[it].y, vraw[it].z, vraw[it].w};
         int dw, bit;
@@ -295,17 +298,15 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
   if (!complete) return;                                   // uniform over the workgroup
 
   // rows of all four planes are addressed by the block's first token in plane order (a block never straddles a page)
-  const int64_t tv0 = virtual_token(g, c.page_table, b, h, (int64_t)blk * kSpan);
+  const int64_t tv0 = virtual_token(g, c.page_table, b, h, (int64_t)blk * RLT);
   uint8_t* kc = (uint8_t*)c.k_codes;
-  uint32_t* km = (uint32_t*)c.k_meta + (tv0 / kSeqGroup) * kHeadDim;      // channel-wise keys: the block's 128 entries
   uint32_t* km_tok = (uint32_t*)c.k_meta;                                  // token-wise keys: entries by token and group
   uint32_t* vm = (uint32_t*)c.v_meta;
-  uint32_t* vc = (uint32_t*)c.v_codes + (tv0 >> 5) * (128 * BV);
 
   if constexpr (KTOK) {
     // ---- keys token-wise: every row on its own, exactly as quantize_append_kernel does it
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
+    for (int it = 0; it < NIT; ++it) {
       const int64_t t = tv0 + rg + 16 * it;
       const uint32_t rw[4] = {kraw[it].x, kraw[it].y, kraw[it].z, kraw[it].w};
       float xk[8];
@@ -320,76 +321,89 @@ __global__ __launch_bounds__(256) void seq_append_kernel(Geom g, kvq_cache c, co
       store_key_codes<BK>(kc + t * (16 * BK), lane16, kcodes);
     }
   } else {
-  // ---- keys: minimum and maximum of every channel over the 64 rows (4 rows here, 4 row groups per wavefront,
-  // 4 wavefronts through LDS)
-  float x[4][8];
-  float mn[8], mx[8];
+    // ---- keys: minimum and maximum of every channel over the rows of each group.  A thread's rows rg + 16 it fall
+    // into group it / gi (gi = seq_g / 16 of its rows in a row per group); within a group: this thread's rows, the 4 row
+    // groups of its wavefront by two shuffles, the 4 wavefronts through LDS.
+    const int gi = g.seq_g >> 4;                           // 2, 4 or 8 (uniform)
+    uint32_t* km = (uint32_t*)c.k_meta + (tv0 / g.seq_g) * kHeadDim;       // the block's first group: 128 entries each
+    float x[NIT][8];
+    float mn[8], mx[8];
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const uint32_t rw[4] = {kraw[it].x, kraw[it].y, kraw[it].z, kraw[it].w};
+    for (int it = 0; it < NIT; ++it) {
+      const uint32_t rw[4] = {kraw[it].x, kraw[it].y, kraw[it].z, kraw[it].w};
 #pragma unroll
-    for (int e = 0; e < 8; ++e) x[it][e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
-    // rotated keys: the block's rows are quantized as R k (the buffer keeps the input rows; the 16 lanes of a row are
-    // neighbours in one wavefront, and the whole workgroup is here)
-    if (g.rotate_k) rotate8(x[it], lane16, rot_sign_bits(g.signs_k, lane16));
+      for (int e = 0; e < 8; ++e) x[it][e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
+      // rotated keys: the block's rows are quantized as R k (the buffer keeps the input rows; the 16 lanes of a row are
+      // neighbours in one wavefront, and the whole workgroup is here)
+      if (g.rotate_k) rotate8(x[it], lane16, rot_sign_bits(g.signs_k, lane16));
+      const bool first = (it & (gi - 1)) == 0, last = ((it + 1) & (gi - 1)) == 0;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      mn[e] = it == 0 ? x[it][e] : fminf(mn[e], x[it][e]);
-      mx[e] = it == 0 ? x[it][e] : fmaxf(mx[e], x[it][e]);
+      for (int e = 0; e < 8; ++e) {
+        mn[e] = first ? x[it][e] : fminf(mn[e], x[it][e]);
+        mx[e] = first ? x[it][e] : fmaxf(mx[e], x[it][e]);
+      }
+      if (last) {                                          // (uniform)
+        const int grp = it / gi;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float lo_e = fminf(mn[e], __shfl_xor(mn[e], 16)); lo_e = fminf(lo_e, __shfl_xor(lo_e, 32));
+          float hi_e = fmaxf(mx[e], __shfl_xor(mx[e], 16)); hi_e = fmaxf(hi_e, __shfl_xor(hi_e, 32));
+          if ((rg & 3) == 0) { s_mn[grp][tid >> 6][d0 + e] = lo_e; s_mx[grp][tid >> 6][d0 + e] = hi_e; }
+        }
+      }
     }
-  }
+    __syncthreads();
+    const float levels = (float)((1 << BK) - 1);
+    const int n_grp = RLT / g.seq_g;
+    for (int grp = 0; grp < n_grp; ++grp) {
+      float sc[8], z[8], rcp[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    mn[e] = fminf(mn[e], __shfl_xor(mn[e], 16)); mn[e] = fminf(mn[e], __shfl_xor(mn[e], 32));
-    mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 16)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 32));
-  }
-  if ((rg & 3) == 0) {
+      for (int e = 0; e < 8; ++e) {
+        const float lo_v = fminf(fminf(s_mn[grp][0][d0 + e], s_mn[grp][1][d0 + e]), fminf(s_mn[grp][2][d0 + e], s_mn[grp][3][d0 + e]));
+        const float hi_v = fmaxf(fmaxf(s_mx[grp][0][d0 + e], s_mx[grp][1][d0 + e]), fmaxf(s_mx[grp][2][d0 + e], s_mx[grp][3][d0 + e]));
+        uint16_t S, Z;
+        group_scale_zero(lo_v, hi_v, BK, &S, &Z);
+        if (rg == 0) km[grp * kHeadDim + d0 + e] = (uint32_t)S | ((uint32_t)Z << 16);
+        sc[e] = widen16(S, false); z[e] = widen16(Z, false);
+        rcp[e] = sc[e] == 0.0f ? 0.0f : rcp_scale(sc[e]);    // (unused when the scale is 0)
+      }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { s_mn[tid >> 6][d0 + e] = mn[e]; s_mx[tid >> 6][d0 + e] = mx[e]; }
-  }
-  __syncthreads();
-  const float levels = (float)((1 << BK) - 1);
-  uint32_t codes[4][8];
+      for (int it = 0; it < NIT; ++it) {
+        if (it / gi != grp) continue;                      // (uniform)
+        uint32_t codes[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const float lo_v = fminf(fminf(s_mn[0][d0 + e], s_mn[1][d0 + e]), fminf(s_mn[2][d0 + e], s_mn[3][d0 + e]));
-    const float hi_v = fmaxf(fmaxf(s_mx[0][d0 + e], s_mx[1][d0 + e]), fmaxf(s_mx[2][d0 + e], s_mx[3][d0 + e]));
-    uint16_t S, Z;
-    group_scale_zero(lo_v, hi_v, BK, &S, &Z);
-    if (rg == 0) km[d0 + e] = (uint32_t)S | ((uint32_t)Z << 16);
-    const float sc = widen16(S, false), z = widen16(Z, false);
-    const float rcp = sc == 0.0f ? 0.0f : rcp_scale(sc);      // (unused when the scale is 0)
-#pragma unroll
-    for (int it = 0; it < 4; ++it) codes[it][e] = group_code(x[it][e], sc, z, rcp, levels);
-  }
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int64_t t = tv0 + rg + 16 * it;
-    store_key_codes<BK>(kc + t * (16 * BK), lane16, codes[it]);
-  }
+        for (int e = 0; e < 8; ++e) codes[e] = group_code(x[it][e], sc[e], z[e], rcp[e], levels);
+        store_key_codes<BK>(kc + (tv0 + rg + 16 * it) * (16 * BK), lane16, codes);
+      }
+    }
   }
 
-  // ---- values: token-wise, as in quantize_append_kernel for a full span
+  // ---- values: token-wise, as in quantize_append_kernel for a full span, one span of kSpan tokens after the other
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int row = rg + 16 * it;
-    const int64_t t = tv0 + row;
-    const uint32_t rw[4] = {vraw[it].x, vraw[it].y, vraw[it].z, vraw[it].w};
-    float xv[8];
+  for (int sp = 0; sp < RLT / kSpan; ++sp) {
+    if (sp) __syncthreads();                               // (the staging area is reused)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) xv[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
-    uint32_t vcodes[8];
-    uint16_t S, Z;
-    const int lpg = g.g_v >> 3;
-    quantize8(xv, BV, lpg, vcodes, &S, &Z);
-    if ((lane16 & (lpg - 1)) == 0) {
-      vm[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
-      note_value_scale(c.v_scale_exp + bh, S);
+    for (int k = 0; k < kSpan / 16; ++k) {
+      const int it = sp * (kSpan / 16) + k;
+      const int row = rg + 16 * k;                         // row inside the span
+      const int64_t t = tv0 + sp * kSpan + row;
+      const uint32_t rw[4] = {vraw[it].x, vraw[it].y, vraw[it].z, vraw[it].w};
+      float xv[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xv[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
+      uint32_t vcodes[8];
+      uint16_t S, Z;
+      const int lpg = g.g_v >> 3;
+      quantize8(xv, BV, lpg, vcodes, &S, &Z);
+      if ((lane16 & (lpg - 1)) == 0) {
+        vm[meta_index(t, lane16 >> lpg_shift(lpg), g.ng_v)] = (uint32_t)S | ((uint32_t)Z << 16);
+        note_value_scale(c.v_scale_exp + bh, S);
+      }
+      stage_value_row<BV>(vstage, row, d0, vcodes);
     }
-    stage_value_row<BV>(vstage, row, d0, vcodes);
+    __syncthreads();
+    store_value_span<BV>((uint32_t*)c.v_codes + ((tv0 + sp * kSpan) >> 5) * (128 * BV), vstage, tid, 0, kSpan);
   }
-  __syncthreads();
-  store_value_span<BV>(vc, vstage, tid, 0, kSpan);
 }
 
 // Reconstruction x^ = code * scale + zero of 8 consecutive channels d0..d0+7 (d0 a multiple of 8) of the token with
@@ -406,8 +420,8 @@ __device__ __forceinline__ void reconstruct8_t(const Geom& g, const kvq_cache& c
     for (int e = 0; e < 8; ++e) val[e] = widen16((uint16_t)code[e], raw_bf16);
   } else {
     const uint32_t* ms = (const uint32_t*)(IS_V ? c.v_meta : c.k_meta);
-    if (!IS_V && g.axis_k == KVQ_AXIS_SEQ) {       // channel-wise keys: one scale/zero per channel and 64-token block
-      const uint4* mp = reinterpret_cast<const uint4*>(ms + (t / kSeqGroup) * kHeadDim + d0);
+    if (!IS_V && g.axis_k == KVQ_AXIS_SEQ) {       // channel-wise keys: one scale/zero per channel and group of seq_g tokens
+      const uint4* mp = reinterpret_cast<const uint4*>(ms + (t / g.seq_g) * kHeadDim + d0);
       const uint4 m0 = mp[0], m1 = mp[1];
       const uint32_t mm[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
 #pragma unroll
@@ -631,14 +645,15 @@ template <int BK, int BV>
 hipError_t launch_sa(const Geom& g, const kvq_cache& c, const void* k_new, const void* v_new, int in_dtype, int64_t sb,
                      int64_t sh, int64_t st, int32_t pos, int32_t n_new, const int32_t* pos_arr, int32_t max_pos,
                      hipStream_t stream) {
-  const int first = pos / kSeqGroup, last = (pos + n_new - 1) / kSeqGroup;
+  const int first = pos / g.resid, last = (pos + n_new - 1) / g.resid;
   dim3 grid(last - first + 1, g.batch * g.kv_heads);
   const bool bf = in_dtype == KVQ_BF16, ktok = g.axis_k != KVQ_AXIS_SEQ;
-#define KVQ_SA_LAUNCH(BF_, KTOK_)                                                                                        \
-  hipLaunchKernelGGL((seq_append_kernel<BK, BV, BF_, KTOK_>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new, \
+#define KVQ_SA_LAUNCH(BF_, KTOK_, RL_)                                                                                     \
+  hipLaunchKernelGGL((seq_append_kernel<BK, BV, BF_, KTOK_, RL_>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new, \
                      (const uint16_t*)v_new, sb, sh, st, pos, n_new, pos_arr, max_pos)
-  if (bf) { if (ktok) KVQ_SA_LAUNCH(true, true); else KVQ_SA_LAUNCH(true, false); }
-  else { if (ktok) KVQ_SA_LAUNCH(false, true); else KVQ_SA_LAUNCH(false, false); }
+  if (ktok) { if (bf) KVQ_SA_LAUNCH(true, true, 64); else KVQ_SA_LAUNCH(false, true, 64); }
+  else if (g.resid == 128) { if (bf) KVQ_SA_LAUNCH(true, false, 128); else KVQ_SA_LAUNCH(false, false, 128); }
+  else { if (bf) KVQ_SA_LAUNCH(true, false, 64); else KVQ_SA_LAUNCH(false, false, 64); }
 #undef KVQ_SA_LAUNCH
   return hipGetLastError();
 }
@@ -680,10 +695,10 @@ hipError_t launch_seq_append(const Geom& g, const kvq_cache& c, const void* k_ne
                              int64_t sb, int64_t sh, int64_t st, int32_t pos, int32_t n_new, hipStream_t stream) {
   if (n_new == 0) return hipSuccess;
   // A first block that starts inside the residual buffer reads its older rows from there, while the workgroups of the
-  // call's last 64 tokens overwrite those slots: when the call goes on beyond that block, the block gets a launch of
+  // call's last tokens (as many as the buffer has slots) overwrite those slots: when the call goes on beyond that block, the block gets a launch of
   // its own and the rest follows in stream order.
-  const int32_t first_end = (pos / kSeqGroup + 1) * kSeqGroup;
-  if (pos % kSeqGroup != 0 && pos + n_new > first_end) {
+  const int32_t first_end = (pos / g.resid + 1) * g.resid;
+  if (pos % g.resid != 0 && pos + n_new > first_end) {
     const int32_t n1 = first_end - pos;
     hipError_t e = launch_seq_append(g, c, k_new, v_new, in_dtype, sb, sh, st, pos, n1, stream);
     if (e != hipSuccess) return e;

@@ -5,6 +5,7 @@ import os
 import re
 
 import pytest
+from dataclasses import replace
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -72,13 +73,22 @@ def test_cache_bytes_closed_forms(kvq):
     assert kvq.decode_workspace_bytes(Ls, 12, 63) == 0
     assert kvq.decode_workspace_bytes(Ls, 12, 64) == kvq.decode_workspace_bytes(Ls, 12, 100) > 0
     assert kvq.residual_bytes(kvq.Layout(2, 3, 100)) == [0, 0]
+    # key groups of 32 tokens behind a 64-slot buffer, of 128 tokens behind a 128-slot one (the capacity is rounded up to
+    # the buffer's length; 4 bytes per channel and group)
+    L32 = kvq.Layout(2, 3, 100, 128, 4, 2, 32, 32, axis_k=kvq.AXIS_SEQ, resid_len=64)
+    assert kvq.cache_bytes(L32) == [6 * 128 * 64, 6 * 4 * 512, 6 * 128 * 32, 6 * 128 * 16] and kvq.residual_bytes(L32) == [6 * 64 * 256] * 2
+    L128 = kvq.Layout(2, 3, 130, 128, 4, 2, 128, 32, axis_k=kvq.AXIS_SEQ)
+    assert kvq.cache_bytes(L128) == [6 * 256 * 64, 6 * 2 * 512, 6 * 256 * 32, 6 * 256 * 16] and kvq.residual_bytes(L128) == [6 * 128 * 256] * 2
+    assert kvq.cache_bytes(replace(L128, resid_len=128)) == kvq.cache_bytes(L128)
 
 
 def test_sizes_agree_with_the_oracle(kvq, oracle):
     for args in ((1, 8, 1024, 128, 4, 2, 32, 32), (3, 2, 77, 128, 2, 8, 128, 64), (2, 2, 33, 128, 16, 4, 64, 32)):
         assert kvq.cache_bytes(kvq.Layout(*args)) == oracle.plane_bytes(oracle.Layout(*args))
-    Lg, Lo = kvq.Layout(3, 2, 77, 128, 4, 2, 64, 32, axis_k=kvq.AXIS_SEQ), oracle.Layout(3, 2, 77, 128, 4, 2, 64, 32, axis_k=1)
-    assert kvq.cache_bytes(Lg) + kvq.residual_bytes(Lg) == [p.size for p in oracle.new_seq_planes(Lo)]
+    for gk, rl in ((64, 0), (32, 64), (128, 128), (128, 0), (64, 128), (32, 128)):
+        Lg = kvq.Layout(3, 2, 77, 128, 4, 2, gk, 32, axis_k=kvq.AXIS_SEQ, resid_len=rl)
+        Lo = oracle.Layout(3, 2, 77, 128, 4, 2, gk, 32, axis_k=1, resid_len=rl)
+        assert kvq.cache_bytes(Lg) + kvq.residual_bytes(Lg) == [p.size for p in oracle.new_seq_planes(Lo)], (gk, rl)
 
 
 def test_workspace_plan(kvq):
@@ -113,6 +123,14 @@ def test_layout_errors(kvq):
         (kvq.Layout(1, 8, 64, 128, 4, 16, rotate_v=1), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 4, 2, 64, 64, axis_k=1, rotate_v=1), kvq.ERR_INVALID_ARG),
         (kvq.Layout(1, 8, 64, 128, 16, 16, rotate_k=1), kvq.ERR_INVALID_ARG),        # rotation needs quantized keys
+        # residual buffers: 64 or 128 slots that whole key groups fill; 64 in front of token-wise keys; paged with 64/64 only
+        (kvq.Layout(1, 8, 256, 128, 4, 2, 128, 64, axis_k=1, resid_len=64), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 256, 128, 4, 2, 32, 64, axis_k=1, resid_len=32), kvq.ERR_UNSUPPORTED),
+        (kvq.Layout(1, 8, 256, 128, 4, 2, 64, 64, axis_k=1, resid_len=256), kvq.ERR_UNSUPPORTED),
+        (kvq.Layout(1, 8, 256, 128, 4, 2, 64, 64, resid_len=128), kvq.ERR_UNSUPPORTED),
+        (kvq.Layout(1, 8, 256, 128, 4, 2, 64, 64, resid_len=-64), kvq.ERR_INVALID_ARG),
+        (kvq.Layout(1, 8, 256, 128, 4, 2, 32, 64, axis_k=1, resid_len=64, page_tokens=64, n_pages=8), kvq.ERR_UNSUPPORTED),
+        (kvq.Layout(1, 8, 256, 128, 4, 2, 128, 64, axis_k=1, page_tokens=128, n_pages=8), kvq.ERR_UNSUPPORTED),
     ]
     for layout, want in bad:
         assert _status(kvq.cache_bytes, layout) == want, layout

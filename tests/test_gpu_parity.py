@@ -879,6 +879,103 @@ def test_token_wise_keys_behind_a_residual_buffer(kvq, oracle, R, bk, bv, gk, gv
     _assert_seq_planes_equal(cache, planes)
 
 
+@pytest.mark.parametrize("R", [4, 8])
+@pytest.mark.parametrize("gk,rl,bk,bv,gv,rot,dtype", [(32, 64, 4, 2, 64, 0, torch.bfloat16), (128, 128, 4, 2, 128, 0, torch.bfloat16),
+                                                      (128, 0, 2, 4, 64, 1, torch.float16), (32, 64, 3, 6, 32, 1, torch.float16),
+                                                      (64, 128, 8, 1, 64, 0, torch.bfloat16), (32, 128, 6, 2, 64, 0, torch.float16)])
+def test_channelwise_group_and_buffer_lengths(kvq, oracle, R, gk, rl, bk, bv, gv, rot, dtype):
+    """Sec. 4 "Downstream Task Accuracy", the per-column back-end with key groups of 32 and 128 tokens and a buffer of 64
+    or 128 slots (resid_len; 0 = the group's length): six planes byte-identical after ragged chunked appends and after
+    one bulk append, attention with and without a tail and with the buffer only, decode steps across a flush."""
+    B, H, T = 2, 2, 420
+    RL = rl or gk
+    raw = 1 if dtype == torch.bfloat16 else 0
+    signs = SIGNS if rot else (0, 0, 0, 0)
+    K, V, q = synth.make_kvq(500 + gk + bk + R, B, H, H * R, T, dtype=dtype)
+    Lg = kvq.Layout(B, H, T, 128, bk, bv, gk, gv, axis_k=kvq.AXIS_SEQ, raw_dtype=raw, rotate_k=rot, signs_k=signs, resid_len=rl)
+    Lo = oracle.Layout(B, H, T, 128, bk, bv, gk, gv, axis_k=1, raw_dtype=raw, rotate_k=rot, signs_k=signs, resid_len=rl)
+    assert kvq.cache_bytes(Lg) == oracle.plane_bytes(Lo) and kvq.residual_bytes(Lg) == [B * H * RL * 256] * 2
+    T0 = 300
+    chunks = [(0, 1), (1, 63), (63, 70), (70, 129), (129, 257), (257, T0)]
+    cache, planes = _seq_fill_both(kvq, oracle, Lg, Lo, K[:, :, :T0], V[:, :, :T0], chunks)
+    _assert_seq_planes_equal(cache, planes)
+    cache2, planes2 = _seq_fill_both(kvq, oracle, Lg, Lo, K[:, :, :T0], V[:, :, :T0], [(0, T0)])
+    _assert_seq_planes_equal(cache2, planes2)
+    qn = synth.to_numpy_bits(q) if raw else q.numpy()
+    bf = bool(raw)
+    out = _decode(kvq, Lg, cache, q, T0)
+    ref = oracle.seq_decode_attention(Lo, planes, qn, T0, 1 / math.sqrt(128), bf16=bf)
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+    for n in (384, 256, 128, 127, 64, 63, 1):                 # whole blocks only, one block, buffer only
+        c3, p3 = _seq_fill_both(kvq, oracle, Lg, Lo, K[:, :, :n], V[:, :, :n], [(0, n)])
+        out = _decode(kvq, Lg, c3, q, n)
+        ref = oracle.seq_decode_attention(Lo, p3, qn, n, 1 / math.sqrt(128), bf16=bf)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, n
+    Kd, Vd = K.cuda(), V.cuda()
+    o2 = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    for pos in range(T0, 390):                                 # the steps at 319 (64 slots) and 383 (both) flush a block
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), 1 / math.sqrt(128), o2, ws)
+        torch.cuda.synchronize()
+        oracle.seq_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, pos:pos + 1])),
+                          np.ascontiguousarray(synth.to_numpy_bits(V[:, :, pos:pos + 1])), pos, bf16=bf)
+        if pos in (T0, 318, 319, 320, 382, 383, 384, 389):
+            ref = oracle.seq_decode_attention(Lo, planes, qn, pos + 1, 1 / math.sqrt(128), bf16=bf)
+            assert _rel_err(o2.cpu().numpy(), ref) < TOL, pos
+    _assert_seq_planes_equal(cache, planes)
+    # the keys as the library reconstructs them (one scale/zero per channel and group of gk tokens), and their error sums
+    n_fl = 384
+    kd = torch.empty(B, H, n_fl, 128, dtype=torch.float32, device="cuda")
+    vd = torch.empty_like(kd)
+    kvq.dequantize(Lg, cache, 0, n_fl, kd, vd)
+    kr, vr = oracle.seq_dequantize(Lo, planes, 390, 0, n_fl)
+    if rot:
+        assert np.abs(kd.cpu().numpy() - kr).max() <= 1e-5 * np.abs(kr).max()    # (R^T in binary32 on both sides)
+    else:
+        assert np.array_equal(kd.cpu().numpy().view(np.uint32), kr.view(np.uint32))
+    assert np.array_equal(vd.cpu().numpy().view(np.uint32), vr.view(np.uint32))
+
+
+def test_channelwise_group_lengths_ragged_batch(kvq, oracle):
+    """Per-sequence lengths with 32-token key groups behind a 64-slot buffer and 128-token groups behind a 128-slot one."""
+    for gk, rl in ((32, 64), (128, 128)):
+        B, H, R, cap = 4, 2, 4, 400
+        lens = [383, 128, 5, 200]
+        K, V, q = synth.make_kvq(78 + gk, B, H, H * R, cap, dtype=torch.bfloat16)
+        Lg = kvq.Layout(B, H, cap, 128, 4, 2, gk, 64, axis_k=kvq.AXIS_SEQ, raw_dtype=1, resid_len=rl)
+        Lo = oracle.Layout(B, H, cap, 128, 4, 2, gk, 64, axis_k=1, raw_dtype=1, resid_len=rl)
+        cache = kvq.Cache(Lg, fill=0x3C)
+        planes = oracle.new_seq_planes(Lo, fill=0x3C)
+        Kd, Vd = K.cuda(), V.cuda()
+        Kb, Vb = synth.to_numpy_bits(K), synth.to_numpy_bits(V)
+        for b in range(B):
+            L1g = replace(Lg, batch=1)
+            kvq.quantize_append(L1g, cache.batch_element(b, L1g), Kd[b:b + 1, :, :lens[b]], Vd[b:b + 1, :, :lens[b]], 0)
+            L1o, p1 = replace(Lo, batch=1), [p.reshape(B, -1)[b] for p in planes]
+            oracle.seq_append(L1o, p1, np.ascontiguousarray(Kb[b:b + 1, :, :lens[b]]), np.ascontiguousarray(Vb[b:b + 1, :, :lens[b]]), 0, bf16=True)
+        torch.cuda.synchronize()
+        _assert_seq_planes_equal(cache, planes)
+        qn = synth.to_numpy_bits(q)
+        lens_d = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, max(lens))), dtype=torch.uint8, device="cuda")
+        kvq.decode_attention_varlen(Lg, cache, q.cuda(), lens_d, max(lens), 1 / math.sqrt(128), out, ws)
+        torch.cuda.synchronize()
+        ref = oracle.seq_decode_attention_varlen(Lo, planes, qn, lens, 1 / math.sqrt(128), bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, (gk, rl)
+        # one step: every sequence appends at its own position (383 flushes with both buffer lengths, the others do not)
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, max(lens) + 1)), dtype=torch.uint8, device="cuda")
+        kn = torch.stack([Kd[b, :, lens[b]] for b in range(B)]).contiguous()
+        vn = torch.stack([Vd[b, :, lens[b]] for b in range(B)]).contiguous()
+        kvq.decode_step_varlen(Lg, cache, kn, vn, lens_d, max(lens), q.cuda(), 1 / math.sqrt(128), out, ws)
+        torch.cuda.synchronize()
+        oracle.seq_append_at(Lo, planes, np.stack([Kb[b, :, lens[b]:lens[b] + 1] for b in range(B)]),
+                             np.stack([Vb[b, :, lens[b]:lens[b] + 1] for b in range(B)]), lens, bf16=True)
+        _assert_seq_planes_equal(cache, planes)
+        ref = oracle.seq_decode_attention_varlen(Lo, planes, qn, [n + 1 for n in lens], 1 / math.sqrt(128), bf16=True)
+        assert _rel_err(out.cpu().numpy(), ref) < TOL, (gk, rl)
+
+
 def test_token_wise_residual_ragged_batch(kvq, oracle):
     """Per-sequence lengths with a residual buffer in front of token-wise keys: every sequence has its own flushed
     blocks and its own tail; a step appends every sequence's token at its own position (some flush, some do not)."""
