@@ -1182,6 +1182,17 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
     }
     if (hh >= r_act) continue;
     const int64_t hq = (int64_t)b * q_heads + hk * r_act + hh;
+    if (a.extra_splits != 0) {
+      // one more record per head lies in the workspace, written by an earlier launch on the same stream (the flushed
+      // part of a cache with a residual buffer, when this launch is the buffer's): it joins here, and no merge launch
+      // follows
+      const float* er = ws + hq * a.extra_splits * kRec;
+      const float me = er[kHeadDim], le = er[kHeadDim + 1], oe = er[d];
+      const float Mn = fmaxf(M, me);
+      const float f0 = exp2f(M - Mn), fe = exp2f(me - Mn);
+      o = fmaf(fe, oe, o * f0);
+      ll = fmaf(fe, le, ll * f0);
+    }
     if (a.rec_splits == 1) {
       const float val = o / ll;
       if (g.rotate_v) { sm_o[0][hh][d] = val; continue; }      // (only this thread touches element (hh, d))
@@ -1542,6 +1553,9 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
     const int32_t n_flushed = seq_len / RL * RL;
     const int32_t tail = varlen ? (n_flushed ? RL - 1 : seq_len) : seq_len - n_flushed;
     const int32_t records = plan.n_splits + (tail ? 1 : 0);
+    // one split of flushed blocks and a tail: the tail's launch, which comes second, takes the first one's record in and
+    // writes the result (one launch less than with the merge kernel)
+    const bool tail_merges = n_flushed && tail && plan.n_splits == 1;
     a.lens_bound = seq_len; a.lens_block = RL;
     hipError_t e = hipSuccess;
     if (n_flushed) {
@@ -1564,10 +1578,11 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
       t.cache.k_codes = c.k_resid; t.cache.v_codes = c.v_resid; t.cache.k_meta = t.cache.v_meta = nullptr;
       t.seq_len = tail; t.n_splits = 1; t.steps_per_split = 4; t.lens_mode = 2;
       t.rec_splits = records; t.rec_base = records - 1;
+      if (tail_merges) { t.rec_splits = 1; t.rec_base = 0; t.extra_splits = records; }
       e = launch_decode_inst_16_16(R, t, DecodePlan{1, 4, 4}, stream);
       if (e != hipSuccess) return e;
     }
-    if (records > 1 && !(n_flushed && !tail)) {     // (a launch that wrote all the records has merged them itself)
+    if (records > 1 && !(n_flushed && !tail) && !tail_merges) {     // (a launch that wrote all the records has merged them itself)
       hipLaunchKernelGGL(merge_kernel, dim3(g.batch * q_heads), dim3(128 * kMergeGroups), 0, stream, workspace, out, out_dtype, records,
                          rot_v_of(g));
       e = hipGetLastError();

@@ -107,6 +107,9 @@ struct DecodeArgs {
   // partial records: a workgroup writes record rec_base + split of rec_splits per (batch, query head); rec_splits == 1
   // means there is nothing to merge and the result goes straight to `out`
   int32_t rec_splits, rec_base;
+  // != 0 (only with rec_splits == 1): record 0 of extra_splits per (batch, query head) in the workspace, complete
+  // before this launch starts, is merged into this launch's result
+  int32_t extra_splits;
   // != 0: this launch writes all rec_splits records of every stream and merges them itself (the workgroup that finishes
   // a stream last does it; the streams' counters, one 64-bit word per (batch, kv head), follow the records in the
   // workspace); the number tells this launch's counts from what the words held before.  0: records are merged by
