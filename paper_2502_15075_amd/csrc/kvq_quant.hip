@@ -20,6 +20,18 @@ constexpr int kSpan = 64;                // tokens one workgroup covers (two 32-
 
 // Pack the codes held one per byte in w (first code in the lowest byte) into adjacent b-bit fields.
 // (Bytes of tokens that were not staged hold garbage: they are masked to b bits so that they stay inside their field.)
+// 16 bytes read once / written once: streaming accesses (see store_bytes)
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+  const u32x4v v = __builtin_nontemporal_load(reinterpret_cast<const u32x4v*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream16(void* p, uint4 w) {
+  typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+  u32x4v v; v.x = w.x; v.y = w.y; v.z = w.z; v.w = w.w;
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4v*>(p));
+}
+
 template <int B> __device__ __forceinline__ uint32_t pack_bytes(uint32_t w) {
   if (B == 1) { w &= 0x01010101u; return (w | (w >> 7) | (w >> 14) | (w >> 21)) & 0xFu; }
   if (B == 2) { w &= 0x03030303u; return (w | (w >> 6) | (w >> 12) | (w >> 18)) & 0xFFu; }
@@ -51,7 +63,7 @@ __device__ __forceinline__ void stage_value_codes(uint8_t* vstage, int row, int 
 // One thread per 32-bit word of the span (two blocks of 128*BV words, BW words apart in the plane: a block of 3- or
 // 6-bit codes is a block of low parts followed by a block of high parts): assemble the word from the staged codes and
 // store it; when the span is only partly covered by the new tokens [lo, hi), keep the fields of the other tokens.
-template <int BV, int BW = 128 * BV, int SPAN = kSpan>
+template <int BV, int BW = 128 * BV, int SPAN = kSpan, bool NT = false>
 __device__ __forceinline__ void store_value_words(uint32_t* vcp, const uint8_t* vstage, int tid, int lo, int hi) {
   constexpr int F = 32 / BV, P = 16 / BV, ES = BV == 16 ? 2 : 1;
   const bool full = lo == 0 && hi == SPAN;
@@ -72,7 +84,10 @@ __device__ __forceinline__ void store_value_words(uint32_t* vcp, const uint8_t* 
     } else {
       bits = *reinterpret_cast<const uint32_t*>(sp);            // 8-bit: four codes; 16-bit: two patterns
     }
-    if (full) { vc[w] = bits; continue; }
+    if (full) {
+      if (NT) __builtin_nontemporal_store(bits, vc + w); else vc[w] = bits;
+      continue;
+    }
     // partially covered span: keep the fields of tokens outside [lo, hi)
     const int sub = w / (128 * BV), wi = w % (128 * BV);
     const int piece = wi >> 8, rem = wi & 255;
@@ -114,104 +129,123 @@ __device__ __forceinline__ void stage_value_row(uint8_t* vstage, int row, int d0
 }
 
 // vc: the span's first block in the plane
-template <int BV, int SPAN = kSpan>
+template <int BV, int SPAN = kSpan, bool NT = false>
 __device__ __forceinline__ void store_value_span(uint32_t* vc, const uint8_t* vstage, int tid, int lo, int hi) {
   constexpr int VLO = code_lo_bits<BV>(), VHI = code_hi_bits<BV>();
   if constexpr (VHI == 0) {
-    store_value_words<BV, 128 * BV, SPAN>(vc, vstage, tid, lo, hi);
+    store_value_words<BV, 128 * BV, SPAN, NT>(vc, vstage, tid, lo, hi);
   } else {
-    store_value_words<VLO, 128 * BV, SPAN>(vc, vstage, tid, lo, hi);
-    store_value_words<VHI, 128 * BV, SPAN>(vc + 128 * VLO, vstage + stage_area<BV, SPAN>(), tid, lo, hi);
+    store_value_words<VLO, 128 * BV, SPAN, NT>(vc, vstage, tid, lo, hi);
+    store_value_words<VHI, 128 * BV, SPAN, NT>(vc + 128 * VLO, vstage + stage_area<BV, SPAN>(), tid, lo, hi);
   }
 }
 
-// One workgroup = one span of SPAN tokens (a multiple of 32: whole blocks of value codes) of one (b,h) stream, restricted
-// to the new tokens in it.
+// One workgroup = `chain` consecutive spans of SPAN tokens (a multiple of 32: whole blocks of value codes) of one (b,h)
+// stream, restricted to the new tokens in them.  The rows of the next span are loaded before the current one is
+// quantized, so that a workgroup has loads in flight while it computes (with one span per workgroup the kernel waits on
+// memory latency: 8 workgroups per compute unit do not keep enough bytes in flight on their own).  No load is
+// conditional -- rows outside the new tokens re-read a row inside them, and the load "after the last span" is
+// collapsed onto 16 bytes -- so that the compiler can count the loads in flight behind the ones it waits for (the last
+// span peeled out of the loop instead, with nothing loaded behind it, costs 20 registers and 7 % of the rate).
 template <int BK, int BV, bool BF, int SPAN>
 __global__ __launch_bounds__(256) void quantize_append_kernel(Geom g, kvq_cache c, const uint16_t* __restrict__ k_new,
                                                               const uint16_t* __restrict__ v_new, int64_t sb, int64_t sh,
-                                                              int64_t st, int32_t pos, int32_t n_new) {
+                                                              int64_t st, int32_t pos, int32_t n_new, int32_t chain) {
   constexpr int kSpan = SPAN;                      // (shadows the 64-token span of the other kernels in this file)
+  constexpr int NR = SPAN / 16;                    // rows per thread and span
   __shared__ __attribute__((aligned(16))) uint8_t vstage[stage_total<BV, SPAN>()];
   const int tid = threadIdx.x;
   const int bh = blockIdx.y;
   const int b = bh / g.kv_heads, h = bh % g.kv_heads;
-  const int blk = pos / kSpan + blockIdx.x;
-  const int lo = max(pos, blk * kSpan) - blk * kSpan;
-  const int hi = min(pos + n_new, (blk + 1) * kSpan) - blk * kSpan;
   const int lane16 = tid & 15;
   const int d0 = lane16 * 8;
-
-  // rows of all four planes are addressed by the span's first token in plane order (a span never straddles a page)
-  const int64_t tv0 = virtual_token(g, c.page_table, b, h, (int64_t)blk * kSpan);
-  uint32_t* vc = (uint32_t*)c.v_codes + (tv0 >> 5) * (128 * BV);
-  // tv0 is a multiple of 32 (of the page size when paged), so row (tid/16) + 16*it sits at position tid/16 of the
-  // span's it-th slab of 16 tokens in the scale/zero planes: one address per thread, a uniform stride per it
   const int lpg_k = g.g_k >> 3, lpg_v = g.g_v >> 3;                  // lanes per group
-  uint8_t* kc = (uint8_t*)c.k_codes + (tv0 + (tid >> 4)) * (BK == 16 ? 256 : 16 * BK);
-  uint32_t* km = (uint32_t*)c.k_meta + meta_index(tv0 + (tid >> 4), lane16 >> lpg_shift(lpg_k), g.ng_k);
-  uint32_t* vm = (uint32_t*)c.v_meta + meta_index(tv0 + (tid >> 4), lane16 >> lpg_shift(lpg_v), g.ng_v);
   const int km_step = 16 * g.ng_k, vm_step = 16 * g.ng_v;
+  const int blk_first = pos / kSpan + blockIdx.x * chain;
+  const int blk_end = min(blk_first + chain, (pos + n_new - 1) / kSpan + 1);     // (the grid leaves no workgroup empty)
+  const int64_t in_base = (int64_t)b * sb + (int64_t)h * sh;
 
-  // each thread owns 8 channels of rows (tid/16) + 16*it, it < SPAN/16: issue all its 16-byte loads, then quantize
-  uint4 kraw[SPAN / 16], vraw[SPAN / 16];
+  // the rows (tid/16) + 16*it of span blk; `live` = 0 collapses all loads onto the first 16 bytes of the span's first
+  // new row
+  auto load_span = [&](int blk, uint32_t live, uint4 (&kraw)[NR], uint4 (&vraw)[NR]) {
+    const int lo = max(pos, blk * kSpan) - blk * kSpan;
+    const int hi = min(pos + n_new, (blk + 1) * kSpan) - blk * kSpan;
 #pragma unroll
-  for (int it = 0; it < SPAN / 16; ++it) {
-    const int row = (tid >> 4) + 16 * it;
-    if (row >= lo && row < hi) {
-      const int64_t src = (int64_t)b * sb + (int64_t)h * sh + ((int64_t)blk * kSpan + row - pos) * st + d0;
-      kraw[it] = *reinterpret_cast<const uint4*>(k_new + src);
-      vraw[it] = *reinterpret_cast<const uint4*>(v_new + src);
+    for (int it = 0; it < NR; ++it) {
+      const int row = min(max((tid >> 4) + 16 * it, lo), hi - 1);
+      const int64_t first_row = (int64_t)blk * kSpan + lo - pos;
+      const int64_t src = in_base + first_row * st + (((int64_t)(row - lo) * st + d0) & (int64_t)(int32_t)live);
+      kraw[it] = load_stream16(k_new + src);       // (streaming: the input rows are read once)
+      vraw[it] = load_stream16(v_new + src);
     }
-  }
+  };
+
+  uint4 kraw[NR], vraw[NR], knext[NR], vnext[NR];
+  load_span(blk_first, ~0u, kraw, vraw);
+  for (int blk = blk_first; blk < blk_end; ++blk) {
+    const bool more = blk + 1 < blk_end;           // uniform
+    load_span(more ? blk + 1 : blk, more ? ~0u : 0u, knext, vnext);
+    const int lo = max(pos, blk * kSpan) - blk * kSpan;
+    const int hi = min(pos + n_new, (blk + 1) * kSpan) - blk * kSpan;
+    // rows of all four planes are addressed by the span's first token in plane order (a span never straddles a page)
+    const int64_t tv0 = virtual_token(g, c.page_table, b, h, (int64_t)blk * kSpan);
+    uint32_t* vc = (uint32_t*)c.v_codes + (tv0 >> 5) * (128 * BV);
+    // tv0 is a multiple of 32 (of the page size when paged), so row (tid/16) + 16*it sits at position tid/16 of the
+    // span's it-th slab of 16 tokens in the scale/zero planes: one address per thread, a uniform stride per it
+    uint8_t* kc = (uint8_t*)c.k_codes + (tv0 + (tid >> 4)) * (BK == 16 ? 256 : 16 * BK);
+    uint32_t* km = (uint32_t*)c.k_meta + meta_index(tv0 + (tid >> 4), lane16 >> lpg_shift(lpg_k), g.ng_k);
+    uint32_t* vm = (uint32_t*)c.v_meta + meta_index(tv0 + (tid >> 4), lane16 >> lpg_shift(lpg_v), g.ng_v);
 #pragma unroll
-  for (int it = 0; it < SPAN / 16; ++it) {
-    const int row = (tid >> 4) + 16 * it;
-    if (row < lo || row >= hi) continue;           // whole 16-lane rows take the same branch
-    // ---- keys: row-major codes
-    {
-      const uint4 raw = kraw[it];
-      const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
-      if (BK == 16) {
-        *reinterpret_cast<uint4*>(kc + it * (16 * 256) + d0 * 2) = raw;
-      } else {
-        float x[8];
+    for (int it = 0; it < NR; ++it) {
+      const int row = (tid >> 4) + 16 * it;
+      if (row < lo || row >= hi) continue;         // whole 16-lane rows take the same branch
+      // ---- keys: row-major codes
+      {
+        const uint4 raw = kraw[it];
+        const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+        if (BK == 16) {
+          store_stream16(kc + it * (16 * 256) + d0 * 2, raw);
+        } else {
+          float x[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
-        if (g.rotate_k) rotate8(x, lane16, rot_sign_bits(g.signs_k, lane16));   // whole 16-lane rows are here together
-        uint32_t codes[8];
-        uint16_t S, Z;
-        quantize8(x, BK, lpg_k, codes, &S, &Z);
-        if ((lane16 & (lpg_k - 1)) == 0) km[it * km_step] = (uint32_t)S | ((uint32_t)Z << 16);
-        store_key_codes<BK>(kc + it * (16 * 16 * BK), lane16, codes);
-      }
-    }
-    // ---- values: scale/zero straight to memory, codes to their place in the staged words
-    {
-      const uint4 raw = vraw[it];
-      const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
-      uint32_t codes[8];
-      if (BV == 16) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) codes[e] = (rw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-      } else {
-        float x[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
-        if (g.rotate_v) rotate8(x, lane16, rot_sign_bits(g.signs_v, lane16));
-        uint16_t S, Z;
-        quantize8(x, BV, lpg_v, codes, &S, &Z);
-        if ((lane16 & (lpg_v - 1)) == 0) {
-          vm[it * vm_step] = (uint32_t)S | ((uint32_t)Z << 16);
-          note_value_scale(c.v_scale_exp + bh, S);
+          for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
+          if (g.rotate_k) rotate8(x, lane16, rot_sign_bits(g.signs_k, lane16));   // whole 16-lane rows are here together
+          uint32_t codes[8];
+          uint16_t S, Z;
+          quantize8(x, BK, lpg_k, codes, &S, &Z);
+          if ((lane16 & (lpg_k - 1)) == 0) __builtin_nontemporal_store((uint32_t)S | ((uint32_t)Z << 16), km + it * km_step);
+          store_key_codes<BK, true>(kc + it * (16 * 16 * BK), lane16, codes);
         }
       }
-      stage_value_row<BV, SPAN>(vstage, row, d0, codes);
+      // ---- values: scale/zero straight to memory, codes to their place in the staged words
+      {
+        const uint4 raw = vraw[it];
+        const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+        uint32_t codes[8];
+        if (BV == 16) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) codes[e] = (rw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+        } else {
+          float x[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) x[e] = widen16((uint16_t)(rw[e >> 1] >> (16 * (e & 1))), BF);
+          if (g.rotate_v) rotate8(x, lane16, rot_sign_bits(g.signs_v, lane16));
+          uint16_t S, Z;
+          quantize8(x, BV, lpg_v, codes, &S, &Z);
+          if ((lane16 & (lpg_v - 1)) == 0) {
+            __builtin_nontemporal_store((uint32_t)S | ((uint32_t)Z << 16), vm + it * vm_step);
+            note_value_scale(c.v_scale_exp + bh, S);
+          }
+        }
+        stage_value_row<BV, SPAN>(vstage, row, d0, codes);
+      }
     }
+    __syncthreads();
+    store_value_span<BV, SPAN, true>(vc, vstage, tid, lo, hi);
+    if (more) __syncthreads();                     // (the staging area is reused by the next span)
+#pragma unroll
+    for (int it = 0; it < NR; ++it) { kraw[it] = knext[it]; vraw[it] = vnext[it]; }
   }
-  __syncthreads();
-
-  store_value_span<BV, SPAN>(vc, vstage, tid, lo, hi);
 }
 
 // The 8 fields of channels d0 .. d0+7 (d0 a multiple of 8) of token u in a 32-token block of B-bit fields: the same
@@ -599,13 +633,18 @@ hipError_t launch_q(const Geom& g, const kvq_cache& c, const void* k_new, const 
   // small call (a 2048-token chunk of one sequence: 6.5 instead of 7.9 us) and costs a large one nothing
   constexpr int kQSpan = 32;
   const int first = pos / kQSpan, last = (pos + n_new - 1) / kQSpan;
-  dim3 grid(last - first + 1, g.batch * g.kv_heads);
+  // spans per workgroup: 4 in a row (each loaded while the one before is quantized) when that still leaves every
+  // compute unit many rounds of workgroups (the 70B layer's bulk fill: 5.6 against 5.15 TB/s; 2 or 8 in a row
+  // measure 5.4), one for smaller calls, which need their workgroups side by side
+  const int64_t spans = (int64_t)(last - first + 1) * g.batch * g.kv_heads;
+  const int chain = spans >= 65536 ? 4 : 1;
+  dim3 grid((last - first + chain) / chain, g.batch * g.kv_heads);
   if (in_dtype == KVQ_BF16)
     hipLaunchKernelGGL((quantize_append_kernel<BK, BV, true, kQSpan>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
-                       (const uint16_t*)v_new, sb, sh, st, pos, n_new);
+                       (const uint16_t*)v_new, sb, sh, st, pos, n_new, chain);
   else
     hipLaunchKernelGGL((quantize_append_kernel<BK, BV, false, kQSpan>), grid, dim3(256), 0, stream, g, c, (const uint16_t*)k_new,
-                       (const uint16_t*)v_new, sb, sh, st, pos, n_new);
+                       (const uint16_t*)v_new, sb, sh, st, pos, n_new, chain);
   return hipGetLastError();
 }
 template <int BK>

@@ -50,7 +50,15 @@ template <int N, bool MASK> __device__ __forceinline__ uint32_t pack8(const uint
   }
   return w;
 }
-template <int NBYTES> __device__ __forceinline__ void store_bytes(uint8_t* p, uint32_t w) {
+// NT: a streaming store (the bulk append writes planes that nothing reads back soon; marked so, its stores and loads
+// leave the caches to data that is reused, and the memory system takes the mixed read/write stream about a tenth faster)
+template <int NBYTES, bool NT = false> __device__ __forceinline__ void store_bytes(uint8_t* p, uint32_t w) {
+  if (NT) {
+    if (NBYTES == 1) __builtin_nontemporal_store((uint8_t)w, p);
+    else if (NBYTES == 2) __builtin_nontemporal_store((uint16_t)w, reinterpret_cast<uint16_t*>(p));
+    else __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(p));
+    return;
+  }
   if (NBYTES == 1) *p = (uint8_t)w;
   else if (NBYTES == 2) *reinterpret_cast<uint16_t*>(p) = (uint16_t)w;
   else *reinterpret_cast<uint32_t*>(p) = w;
@@ -62,19 +70,25 @@ template <int NBYTES> __device__ __forceinline__ uint32_t load_bytes(const uint8
 }
 
 // Store the 8 codes of channels 8*lane16 .. 8*lane16+7 of one key row (rowp: first byte of the row).
-template <int BK>
+template <int BK, bool NT = false>
 __device__ __forceinline__ void store_key_codes(uint8_t* rowp, int lane16, const uint32_t codes[8]) {
   constexpr int LO = code_lo_bits<BK>(), HI = code_hi_bits<BK>();
   if constexpr (BK == 8) {
     const uint32_t w0 = codes[0] | (codes[1] << 8) | (codes[2] << 16) | (codes[3] << 24);
     const uint32_t w1 = codes[4] | (codes[5] << 8) | (codes[6] << 16) | (codes[7] << 24);
-    reinterpret_cast<uint2*>(rowp)[lane16] = make_uint2(w0, w1);
+    if constexpr (NT) {
+      typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+      u32x2 w; w.x = w0; w.y = w1;
+      __builtin_nontemporal_store(w, reinterpret_cast<u32x2*>(rowp) + lane16);
+    } else {
+      reinterpret_cast<uint2*>(rowp)[lane16] = make_uint2(w0, w1);
+    }
   } else if constexpr (HI == 0) {
-    store_bytes<BK>(rowp + lane16 * BK, pack8<BK, false>(codes, 0));              // 8 codes of b bits = b bytes
+    store_bytes<BK, NT>(rowp + lane16 * BK, pack8<BK, false>(codes, 0));          // 8 codes of b bits = b bytes
   } else {
     uint8_t* chunk = rowp + (lane16 >> 2) * (4 * BK);                      // 4 lanes = 32 channels = one chunk
-    store_bytes<LO>(chunk + (lane16 & 3) * LO, pack8<LO, true>(codes, 0));
-    store_bytes<HI>(chunk + 4 * LO + (lane16 & 3) * HI, pack8<HI, false>(codes, LO));
+    store_bytes<LO, NT>(chunk + (lane16 & 3) * LO, pack8<LO, true>(codes, 0));
+    store_bytes<HI, NT>(chunk + 4 * LO + (lane16 & 3) * HI, pack8<HI, false>(codes, LO));
   }
 }
 
@@ -220,10 +234,28 @@ __device__ __forceinline__ void quantize8(const float x[8], int bits, int lanes_
   float mx = max3f(max3f(x[0], x[1], x[2]), max3f(x[3], x[4], x[5]), max2f(x[6], x[7]));
   // the group's lanes are an aligned run of 4, 8 or 16 inside a 16-lane row: two quad exchanges, then the mirror
   // images of the 8- and 16-lane runs (after the quad steps every quad is uniform, so a mirror is as good as an xor)
-  mn = min2f(mn, lane_dpp<0xB1>(mn)); mx = max2f(mx, lane_dpp<0xB1>(mx));       // quad_perm [1,0,3,2]
-  mn = min2f(mn, lane_dpp<0x4E>(mn)); mx = max2f(mx, lane_dpp<0x4E>(mx));       // quad_perm [2,3,0,1]
-  if (lanes_per_group >= 8) { mn = min2f(mn, lane_dpp<0x141>(mn)); mx = max2f(mx, lane_dpp<0x141>(mx)); }   // row_half_mirror
-  if (lanes_per_group >= 16) { mn = min2f(mn, lane_dpp<0x140>(mn)); mx = max2f(mx, lane_dpp<0x140>(mx)); }  // row_mirror
+  // Each step is one instruction per bound: the minimum (maximum) of a register and its own lane-permuted copy.  A
+  // permuted read needs two wait states after the write of its source, which the compiler counts for its own
+  // instructions only; here they are written out: a pause in front of each block (five states in front of the first,
+  // which also covers an execution mask written by a vector compare just before; two in front of the others), and
+  // inside the first block the other bound's instruction plus a one-state pause between a write and its permuted read.
+  asm("s_nop 4\n\t"
+      "v_min_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+      "v_max_f32_dpp %1, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 0\n\t"
+      "v_min_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+      "v_max_f32_dpp %1, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf"
+      : "+v"(mn), "+v"(mx));
+  if (lanes_per_group >= 8)
+    asm("s_nop 1\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xf"
+        : "+v"(mn), "+v"(mx));
+  if (lanes_per_group >= 16)
+    asm("s_nop 1\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 row_mirror row_mask:0xf bank_mask:0xf"
+        : "+v"(mn), "+v"(mx));
   if (mn == 0.0f) mn = 0.0f;  // -0 -> +0
   const float levels = (float)((1 << bits) - 1);
   float s32 = div_levels(mx - mn, levels, inv_levels(bits));
@@ -232,12 +264,10 @@ __device__ __forceinline__ void quantize8(const float x[8], int bits, int lanes_
   uint16_t zb = f32_to_f16_bits(mn);
   float s = widen16(sb, false), z = widen16(zb, false);
   *S = sb; *Z = zb;
-  if (s == 0.0f) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) codes[e] = 0;
-    return;
-  }
+  // a scale of 0 (constant group, or a range that underflows binary16): every code is 0, which a factor of 0 in place
+  // of the reciprocal gives without a branch ((x - z) is finite, its product with 0 is +-0)
   float rcp = rcp_scale(s);
+  if (s == 0.0f) rcp = 0.0f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     float t = (x[e] - z) * rcp;

@@ -622,6 +622,34 @@ def test_decode_step_replayed_from_a_hip_graph(kvq, oracle):
     _assert_planes_equal(cache, planes)
 
 
+@pytest.mark.parametrize("bk,bv,gk,gv,dtype,strided", [(4, 2, 64, 64, torch.bfloat16, False), (3, 6, 32, 128, torch.float16, True)])
+def test_large_ragged_append_walks_several_spans_per_workgroup(kvq, oracle, bk, bv, gk, gv, dtype, strided):
+    """A call of 65536 spans and more gives every workgroup four 32-token spans in a row, each loaded while the one
+    before is quantized: a first span that starts inside a block, a last span that ends inside one, a last workgroup
+    with a single span, and (second case) token-major inputs whose rows are 2048 elements apart.  All planes byte for
+    byte, the bytes no call wrote included."""
+    B, H, T = 32, 8, 8200
+    g = torch.Generator().manual_seed(91 + bk)
+    if strided:                                          # [B, T, H, D] storage viewed as [B, H, T, D]
+        K = (torch.randn(B, T, H, 128, generator=g) * 3).to(dtype).permute(0, 2, 1, 3)
+        V = torch.randn(B, T, H, 128, generator=g).to(dtype).permute(0, 2, 1, 3)
+    else:
+        K = (torch.randn(B, H, T, 128, generator=g) * 3).to(dtype)
+        V = torch.randn(B, H, T, 128, generator=g).to(dtype)
+    raw = 1 if dtype == torch.bfloat16 else 0
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, raw=raw)
+    cache = kvq.Cache(Lg, fill=0xA5)
+    planes = oracle.new_planes(Lo, fill=0xA5)
+    Kd, Vd = K.cuda(), V.cuda()
+    assert Kd.stride(2) == (H * 128 if strided else 128)
+    for a, b in ((0, 5), (5, 8197)):                     # the second call: 257 spans x 256 streams
+        kvq.quantize_append(Lg, cache, Kd[:, :, a:b], Vd[:, :, a:b], a)
+        oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, a:b])),
+                               np.ascontiguousarray(synth.to_numpy_bits(V[:, :, a:b])), a, bf16=bool(raw))
+    torch.cuda.synchronize()
+    _assert_planes_equal(cache, planes)
+
+
 # --------------------------------------------------------------------------- channel-wise keys + residual buffer
 
 def _seq_layouts(kvq, oracle, B, H, T, bk, bv, gv, raw=0):
