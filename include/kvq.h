@@ -198,7 +198,12 @@ kvq_status kvq_quantize_append(const kvq_layout* layout, const kvq_cache* cache,
  *        are not supported); q_heads / kv_heads in 1..8 (with 32-element groups on both tensors: up to 8, and the
  *        head count times the groups per row at most 32 after rounding the heads up to a power of two).
  *   out  [B][q_heads][D] contiguous, KVQ_F32 (the graded type), KVQ_F16 or KVQ_BF16 (rounded once).
- *   workspace  at least kvq_decode_workspace_bytes(layout, q_heads, seq_len) bytes, 16-byte aligned. */
+ *   workspace  at least kvq_decode_workspace_bytes(layout, q_heads, seq_len) bytes, 16-byte aligned.
+ * Unquantized tensors (bits == 16; both: the full-precision baseline; one: the ablation that quantizes only keys or
+ * only values, Table 1's discussion): a 16-bit key plane is multiplied by the query as it is, so q_dtype must be
+ * raw_dtype (KVQ_ERR_UNSUPPORTED otherwise).  With exactly one tensor unquantized the keys are token-wise, values are
+ * not rotated, and the head count times the groups per row of the quantized tensor is at most 16
+ * (KVQ_ERR_UNSUPPORTED otherwise). */
 kvq_status kvq_decode_attention(const kvq_layout* layout, const kvq_cache* cache, const void* q,
                                 kvq_dtype q_dtype, int32_t q_heads, int32_t seq_len, float softmax_scale,
                                 void* out, kvq_dtype out_dtype, void* workspace, size_t workspace_bytes,
@@ -224,6 +229,8 @@ kvq_status kvq_decode_attention_static(const kvq_layout* layout, const kvq_cache
  * token's K/V row of every (b, h_kv) into position pos -- same bytes as kvq_quantize_append with n_new = 1 -- then
  * attend over tokens [0, pos].  Token-wise keys: the append is fused into the attention kernel (one launch, plus the
  * merge launch when the sequence is split).  Channel-wise keys: the append kernel, then the attention launches.
+ * A cache with an unquantized tensor (bits == 16 for keys, values or both) has no fused step (KVQ_ERR_UNSUPPORTED):
+ * call kvq_quantize_append with n_new = 1, then kvq_decode_attention.
  *   k_new, v_new   [B][H_kv][D] of in_dtype (KVQ_F16 / KVQ_BF16), element strides given, D contiguous.
  *   everything else as in kvq_decode_attention with seq_len = pos + 1. */
 kvq_status kvq_decode_step(const kvq_layout* layout, const kvq_cache* cache, const void* k_new, const void* v_new,

@@ -23,7 +23,9 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.j
 DECODE_PAIRS = [(4, 2), (2, 4), (4, 4), (8, 8), (2, 2), (8, 4), (8, 2), (4, 8), (2, 8), (16, 16),
                 (3, 2), (3, 4), (3, 8), (6, 2), (6, 4), (6, 8), (1, 2), (1, 4), (1, 8),
                 (1, 1), (2, 1), (3, 1), (4, 1), (6, 1), (8, 1),
-                (1, 3), (2, 3), (3, 3), (4, 3), (6, 3), (8, 3), (1, 6), (2, 6), (3, 6), (4, 6), (6, 6), (8, 6)]
+                (1, 3), (2, 3), (3, 3), (4, 3), (6, 3), (8, 3), (1, 6), (2, 6), (3, 6), (4, 6), (6, 6), (8, 6),
+                # one tensor unquantized (the ablations that quantize only keys or only values)
+                (16, 1), (16, 2), (16, 3), (16, 4), (16, 6), (16, 8), (1, 16), (2, 16), (3, 16), (4, 16), (6, 16), (8, 16)]
 # No decode kernel may use scratch memory (a register spill in the streaming loop costs more than any ring depth gains):
 # the build fails on an instance that does.
 def _scratch_allowed(kernel_name: str) -> int:

@@ -154,7 +154,7 @@ kvq_status decode_check(const kvq_layout* layout, const kvq_cache* cache, const 
   if (!kvq::decode_supported(g, q_heads)) return KVQ_ERR_UNSUPPORTED;
   if (kvq::has_residual(*layout) && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // residual tail: as unquantized
   if (layout->bits_k == 16 && (int)q_dtype != layout->raw_dtype) return KVQ_ERR_UNSUPPORTED;   // matrix operands share a type
-  if (layout->bits_k == 16 && fused_append) return KVQ_ERR_UNSUPPORTED; // fused append exists for quantized caches only
+  if ((layout->bits_k == 16 || layout->bits_v == 16) && fused_append) return KVQ_ERR_UNSUPPORTED; // fused append: both tensors quantized
   size_t need = 0;
   st = kvq_decode_workspace_bytes(layout, q_heads, seq_len, &need);
   if (st != KVQ_OK) return st;

@@ -288,7 +288,7 @@ __device__ __forceinline__ void load_step(StepRegs<BK, BV>& r, const LaneCtx& L,
 #pragma unroll
   for (int x4 = 0; x4 < 2; ++x4) load_dwords<BK>(r.kc[x4], kbase + (ko + x4 * (256 * BK)));
   // (every lane loads, for the same reason: lanes beyond the scale/zero bytes repeat the last 16 of them)
-  if constexpr (BK != 16)
+  if constexpr (BK != 16 || BV != 16)
     r.meta = ld16(mbase + ((WIDE ? 0u : ((uint32_t)step & L.meta_step_mask) * L.meta_mul) + (L.meta_off & lane_mask)));
   constexpr int VLO = v_lo<BV>(), VHI = v_hi<BV>();
   const uint32_t vstep = WIDE ? 0u : (uint32_t)step * (512 * BV);
@@ -487,12 +487,14 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
                                              float kappa, WaveState<NCV>& st, const LC& L, int step, int seq_len,
                                              KS& ks, const float* qrow = nullptr, float kseq_low = 0.f,
                                              bool rebuild = true) {
-  constexpr bool RAW = BK == 16;
+  // a tensor of bits = 16 is stored as its 16-bit patterns (BF: bfloat16) and multiplied as it is, no scale/zero
+  constexpr bool RAWK = BK == 16, RAWV = BV == 16;
+  constexpr bool BFK = RAWK && BF, BFV = RAWV && BF;
   constexpr int KLO = k_lo<BK>(), KHI = k_hi<BK>();   // qbh: the query operand of the high run (3- and 6-bit keys)
   constexpr bool KSEQ = !__is_same(KS, NoKSeq);
   constexpr int kSetStride = (16 / R) * 64;      // bytes between the scale/zero entries of a lane's groups in two sets
   uint32_t kmeta[NCK][8], vmeta[NCV][8];
-  if constexpr (!RAW) {
+  if constexpr (!RAWK || !RAWV) {
     // scale/zero bytes: plane order -> LDS -> the entries this lane needs (tokens 4j..4j+3 of both tiles, own groups)
     *reinterpret_cast<u32x4*>(L.meta_lds + L.lane * 16) = r.meta;     // (lanes beyond the bytes fill slots nobody reads)
     if constexpr (KSEQ && NEWBLK) {
@@ -505,12 +507,13 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
     for (int x4 = 0; x4 < 2; ++x4) {
 #pragma unroll
       for (int cs = 0; cs < NCK; ++cs) {
-        if constexpr (KSEQ) continue;
+        if constexpr (KSEQ || RAWK) continue;
         const u32x4 a = *reinterpret_cast<const u32x4*>(L.meta_lds + L.km_rd + cs * kSetStride + x4 * (64 * L.ngk));
         kmeta[cs][4 * x4 + 0] = a.x; kmeta[cs][4 * x4 + 1] = a.y; kmeta[cs][4 * x4 + 2] = a.z; kmeta[cs][4 * x4 + 3] = a.w;
       }
 #pragma unroll
       for (int cs = 0; cs < NCV; ++cs) {
+        if constexpr (RAWV) continue;
         const u32x4 b = *reinterpret_cast<const u32x4*>(L.meta_lds + L.vm_rd + cs * kSetStride + x4 * (64 * L.ngv));
         vmeta[cs][4 * x4 + 0] = b.x; vmeta[cs][4 * x4 + 1] = b.y; vmeta[cs][4 * x4 + 2] = b.z; vmeta[cs][4 * x4 + 3] = b.w;
       }
@@ -541,18 +544,18 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
       float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int m = 0; m < 4; ++m) {                // two independent accumulation chains
-        d0 = mma<BF>(unpack_k<KLO>(r.kc[0], m), qb[cs][m], d0);
-        d1 = mma<BF>(unpack_k<KLO>(r.kc[1], m), qb[cs][m], d1);
+        d0 = mma<BFK>(unpack_k<KLO>(r.kc[0], m), qb[cs][m], d0);
+        d1 = mma<BFK>(unpack_k<KLO>(r.kc[1], m), qb[cs][m], d1);
         if constexpr (KHI != 0) {
-          d0 = mma<BF>(unpack_k<KHI, k_hi_base<BK>()>(r.kc[0] + KLO, m), qbh[cs][m], d0);
-          d1 = mma<BF>(unpack_k<KHI, k_hi_base<BK>()>(r.kc[1] + KLO, m), qbh[cs][m], d1);
+          d0 = mma<BFK>(unpack_k<KHI, k_hi_base<BK>()>(r.kc[0] + KLO, m), qbh[cs][m], d0);
+          d1 = mma<BFK>(unpack_k<KHI, k_hi_base<BK>()>(r.kc[1] + KLO, m), qbh[cs][m], d1);
         }
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const float d = i < 4 ? d0[i & 3] : d1[i & 3];
         float pt = d;
-        if constexpr (!RAW) pt = fmaf(d, meta_scale(kmeta[cs][i]), fmaf(meta_zero(kmeta[cs][i]), qsum_u[cs], 0.0f));
+        if constexpr (!RAWK) pt = fmaf(d, meta_scale(kmeta[cs][i]), fmaf(meta_zero(kmeta[cs][i]), qsum_u[cs], 0.0f));
         part[i] = cs == 0 ? pt : part[i] + pt;
       }
     }
@@ -588,7 +591,7 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
   constexpr int VLO = v_lo<BV>(), VHI = v_hi<BV>();
   uint32_t pw[NCV][4], pl[4];                    // pl: low-order bfloat16 part of the weights (bfloat16 cache only)
   uint32_t pwh[NCV][4];                          // weights of the high parts of 3- and 6-bit value codes
-  constexpr bool ROTV = !RAW && !KSEQ && LC::kRotV;   // (rotation is not combined with channel-wise keys)
+  constexpr bool ROTV = !RAWK && !RAWV && !KSEQ && LC::kRotV;   // (rotation is not combined with channel-wise keys)
   float pv[ROTV ? 8 : 1];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -597,7 +600,7 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
     if (MASKED && !valid[i]) p = 0.f;
     if constexpr (ROTV) pv[i] = p;
     st.l[v] += p;
-    if constexpr (!RAW) {
+    if constexpr (!RAWV) {
 #pragma unroll
       for (int cs = 0; cs < NCV; ++cs) {
         uint32_t vm = vmeta[cs][i];
@@ -655,14 +658,14 @@ __device__ __forceinline__ void compute_step(const StepRegs<BK, BV>& r, const u3
     const u32x4 pb = u32x4{pw[cs][0], pw[cs][1], pw[cs][2], pw[cs][3]};
     u32x4 a = unpack_v<VLO>(r.vc, dt);
     if constexpr (VHI != 0)
-      st.acc[dt] = mma<BF>(unpack_v<VHI>(r.vc + 2 * VLO, dt), u32x4{pwh[cs][0], pwh[cs][1], pwh[cs][2], pwh[cs][3]}, st.acc[dt]);
-    if constexpr (RAW && MASKED) {               // unquantized garbage may be Inf/NaN: clear the slots beyond seq_len
+      st.acc[dt] = mma<BFV>(unpack_v<VHI>(r.vc + 2 * VLO, dt), u32x4{pwh[cs][0], pwh[cs][1], pwh[cs][2], pwh[cs][3]}, st.acc[dt]);
+    if constexpr (RAWV && MASKED) {               // unquantized garbage may be Inf/NaN: clear the slots beyond seq_len
       uint32_t* aw = reinterpret_cast<uint32_t*>(&a);
 #pragma unroll
       for (int v = 0; v < 4; ++v) aw[v] &= (valid[2 * v] ? 0x0000FFFFu : 0u) | (valid[2 * v + 1] ? 0xFFFF0000u : 0u);
     }
-    st.acc[dt] = mma<BF>(a, pb, st.acc[dt]);
-    if constexpr (RAW && BF) st.acc[dt] = mma<BF>(a, u32x4{pl[0], pl[1], pl[2], pl[3]}, st.acc[dt]);
+    st.acc[dt] = mma<BFV>(a, pb, st.acc[dt]);
+    if constexpr (BFV) st.acc[dt] = mma<BFV>(a, u32x4{pl[0], pl[1], pl[2], pl[3]}, st.acc[dt]);
   }
 }
 
@@ -784,8 +787,10 @@ __device__ __forceinline__ void store_unrotated_row(const float* row, int lane16
 template <int BK, int BV, int R, int NW, bool BF, int NCK, int NCV, bool KSEQ = false, bool PAGED = false, bool ROTV = false>
 __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(const DecodeArgs a) {
   constexpr int kSetGroups = 16 / R;             // groups per column set
-  constexpr bool RAW = BK == 16;
-  static_assert(!KSEQ || (!RAW && NCK == 1), "channel-wise keys: quantized, one key column per head");
+  constexpr bool RAWK = BK == 16, RAWV = BV == 16;     // a tensor kept as its 16-bit patterns (either one, or both)
+  constexpr bool RAW = RAWK;                          // (what the key side and the query staging ask)
+  static_assert(!KSEQ || (!RAWK && !RAWV && NCK == 1), "channel-wise keys: quantized, one key column per head");
+  static_assert(!ROTV || (!RAWK && !RAWV), "rotated values: both tensors quantized");
   constexpr int kRing = ring_stages<BK, BV, NCK, NCV, ROTV>();
 #ifndef KVQ_KSEQ_STAGES
 #define KVQ_KSEQ_STAGES 2
@@ -794,7 +799,10 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   // measures no faster with a deeper ring)
   constexpr int kStages = KSEQ ? (kRing < KVQ_KSEQ_STAGES ? kRing : KVQ_KSEQ_STAGES) : kRing;
   constexpr int SPB = KSEQ ? 2 : 1;              // steps a wavefront takes in a row
-  constexpr float kUnit = RAW ? 1.0f : kCodeUnit, kInvUnit = RAW ? 1.0f : kInvCodeUnit;
+  // codes enter the matrix unit as binary16 subnormals (code x 2^-24): the key side's factor goes into the logits'
+  // scale, the value side's into the final accumulator
+  constexpr float kUnit = RAWK ? 1.0f : kCodeUnit, kInvUnit = RAWK ? 1.0f : kInvCodeUnit;
+  constexpr float kInvUnitV = RAWV ? 1.0f : kInvCodeUnit;
   __shared__ float sm_o[NW][R][kHeadDim];
   __shared__ float sm_m[NW][R], sm_l[NW][R];
   __shared__ __attribute__((aligned(16))) uint16_t sm_q[R][kHeadDim];
@@ -841,7 +849,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   {
     // channel-wise keys: 512 bytes of scale/zero per group of seq_g = 32, 64 or 128 tokens (32 lanes), fetched with
     // every step of the group (1, 2 or 4 of them)
-    const int nk = KSEQ ? 32 : 8 * g.ng_k, nv = 8 * g.ng_v;
+    const int nk = RAWK ? 0 : KSEQ ? 32 : 8 * g.ng_k, nv = RAWV ? 0 : 8 * g.ng_v;   // (an unquantized tensor has none)
     const int ml = min(lane, nk + nv - 1);       // lanes beyond the scale/zero bytes of a step repeat the last 16
     const bool is_k = ml < nk;
     L.meta_base = is_k ? (const uint8_t*)cache.k_meta + bh_base * g.km_stream
@@ -857,7 +865,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   // ---- what this launch reads.  A fused decode step does not read its new token (position seq_len - 1) back from the
   // cache: the workgroup that owns that position quantizes and stores it, and adds it to the attention as one more
   // partial record, computed from the reconstruction it holds in registers (no store -> load round trip, no fence).
-  constexpr bool kCanAppend = !RAW && !KSEQ;
+  constexpr bool kCanAppend = !RAWK && !RAWV && !KSEQ;
   const bool fused = kCanAppend && a.k_new != nullptr;
   const int n_att = fused ? seq_len - 1 : seq_len;        // tokens attended through the cache planes
   const int n_steps = (n_att + 31) >> 5;
@@ -906,7 +914,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   // threads beyond the rows re-read the first 16 bytes), and in a fused step the new token's rows and the words of the
   // value block that take its codes (threads that have none of these re-read the query).
   int stream_scale_exp = 0;                        // largest exponent field of the stream's value scales (weight_headroom)
-  if constexpr (!RAW) stream_scale_exp = cache.v_scale_exp[bh];
+  if constexpr (!RAWV) stream_scale_exp = cache.v_scale_exp[bh];
   const int r_act = a.heads_per_kv;                // heads that exist (R is the next power of two)
   const bool q_lane = tid < R * 16 && (tid >> 4) < r_act;
   const uint16_t* qsrc = q + ((int64_t)b * q_heads + hk * r_act) * kHeadDim + (q_lane ? tid * 8 : 0);
@@ -1085,7 +1093,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
   for (int dt = 0; dt < 8; ++dt) st.acc[dt] = float4v{0.f, 0.f, 0.f, 0.f};
   st.m = kNegBig;
   st.headroom = 0.f;
-  if constexpr (!RAW) st.headroom = weight_headroom<BV>(stream_scale_exp);
+  if constexpr (!RAWV) st.headroom = weight_headroom<BV>(stream_scale_exp);
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
     st.l[v] = 0.f; st.noff[v] = 0.f;
@@ -1152,7 +1160,7 @@ __global__ __launch_bounds__(64 * NW, KVQ_WAVES_PER_SIMD) void decode_kernel(con
         if (dt / dtg == gcs) {                                 // time; the stores of the other groups' tiles are skipped)
           float* dst = &sm_o[wave][h][16 * dt + 4 * L.j];
 #pragma unroll
-          for (int rr = 0; rr < 4; ++rr) dst[rr] = fmaf(st.acc[dt][rr], kInvUnit, z);
+          for (int rr = 0; rr < 4; ++rr) dst[rr] = fmaf(st.acc[dt][rr], kInvUnitV, z);
         }
     }
   }
@@ -1340,7 +1348,7 @@ inline RotV rot_v_of(const Geom& g) {
 
 template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool KSEQ, bool PAGED>
 void launch_nw(const DecodeArgs& a, const DecodePlan& plan, dim3 grid, hipStream_t stream) {
-  if constexpr (BK != 16 && !KSEQ) {
+  if constexpr (BK != 16 && BV != 16 && !KSEQ) {
     if (a.g.rotate_v) {
       if (plan.waves_per_wg == 8)
         hipLaunchKernelGGL((decode_kernel<BK, BV, R, 8, BF, NCK, NCV, KSEQ, PAGED, true>), grid, dim3(512), 0, stream, a);
@@ -1359,7 +1367,7 @@ void launch_nw(const DecodeArgs& a, const DecodePlan& plan, dim3 grid, hipStream
 template <int BK, int BV, int R, bool BF, bool KSEQ, bool PAGED>
 hipError_t launch_sets(const DecodeArgs& a, const DecodePlan& plan, dim3 grid, hipStream_t stream) {
   const bool k2 = R * a.g.ng_k > 16, v2 = R * a.g.ng_v > 16;
-  if constexpr (R == 8 && BK != 16) {
+  if constexpr (R == 8 && BK != 16 && BV != 16) {
     if constexpr (KSEQ) {
       if (k2) return hipErrorInvalidValue;
       if (v2) launch_nw<BK, BV, R, BF, 1, 2, true, PAGED>(a, plan, grid, stream);
@@ -1411,8 +1419,10 @@ hipError_t launch_r(int R, const DecodeArgs& a, const DecodePlan& plan, hipStrea
 // ---- instance translation unit: the kernels of one (b_K, b_V) pair behind one launcher -------------------------------
 hipError_t KVQ_CAT(launch_decode_inst_, KVQ_INST_BK, KVQ_INST_BV)(int R, const DecodeArgs& a, const DecodePlan& plan,
                                                                   hipStream_t stream) {
-#if KVQ_INST_BK == 16
-  return a.g.raw_dtype == KVQ_BF16 ? launch_r<16, 16, true>(R, a, plan, stream) : launch_r<16, 16, false>(R, a, plan, stream);
+#if KVQ_INST_BK == 16 || KVQ_INST_BV == 16
+  // one tensor or both unquantized: token-wise kernels only, typed by the 16-bit patterns' type
+  return a.g.raw_dtype == KVQ_BF16 ? launch_r<KVQ_INST_BK, KVQ_INST_BV, true>(R, a, plan, stream)
+                                   : launch_r<KVQ_INST_BK, KVQ_INST_BV, false>(R, a, plan, stream);
 #else
   if (a.g.axis_k == KVQ_AXIS_SEQ) return launch_r<KVQ_INST_BK, KVQ_INST_BV, false, true>(R, a, plan, stream);
   return launch_r<KVQ_INST_BK, KVQ_INST_BV>(R, a, plan, stream);
@@ -1425,7 +1435,8 @@ hipError_t KVQ_CAT(launch_decode_inst_, KVQ_INST_BK, KVQ_INST_BV)(int R, const D
 #define KVQ_FOR_EACH_PAIR(X) X(4, 2) X(2, 4) X(4, 4) X(8, 8) X(2, 2) X(8, 4) X(8, 2) X(4, 8) X(2, 8) X(16, 16) \
   X(3, 2) X(3, 4) X(3, 8) X(6, 2) X(6, 4) X(6, 8) X(1, 2) X(1, 4) X(1, 8) \
   X(1, 1) X(2, 1) X(3, 1) X(4, 1) X(6, 1) X(8, 1) \
-  X(1, 3) X(2, 3) X(3, 3) X(4, 3) X(6, 3) X(8, 3) X(1, 6) X(2, 6) X(3, 6) X(4, 6) X(6, 6) X(8, 6)
+  X(1, 3) X(2, 3) X(3, 3) X(4, 3) X(6, 3) X(8, 3) X(1, 6) X(2, 6) X(3, 6) X(4, 6) X(6, 6) X(8, 6) \
+  X(16, 1) X(16, 2) X(16, 3) X(16, 4) X(16, 6) X(16, 8) X(1, 16) X(2, 16) X(3, 16) X(4, 16) X(6, 16) X(8, 16)
 #endif
 #define KVQ_DECL(BK_, BV_) \
   hipError_t KVQ_CAT(launch_decode_inst_, BK_, BV_)(int R, const DecodeArgs& a, const DecodePlan& plan, hipStream_t stream);
@@ -1439,8 +1450,11 @@ bool decode_supported(const Geom& g, int32_t q_heads) {
   const int r = q_heads / g.kv_heads;
   if (r < 1 || r > 8) return false;
   const int R = padded_heads(r);
-  if ((g.bits_k == 16) != (g.bits_v == 16)) return false;      // one tensor unquantized, the other not: no kernel
   if (R * g.ng_k > 32 || R * g.ng_v > 32) return false;        // head x group columns: at most two 16-wide tiles
+  if ((g.bits_k == 16) != (g.bits_v == 16)) {                  // one tensor unquantized, the other not:
+    if (R * g.ng_k > 16 || R * g.ng_v > 16) return false;      // one column set, token-wise keys, values not rotated
+    if (g.axis_k == KVQ_AXIS_SEQ || g.resid || g.rotate_v) return false;
+  }
   return true;
 }
 

@@ -173,9 +173,16 @@ def test_call_errors_are_caught_before_any_launch(kvq):
         assert da(0x50000, 8, 100, 0.1, 0x60000, 2, 0x70000, need - 1) == kvq.ERR_WORKSPACE
         assert da(0x50000, 8, 100, 0.1, 0x60000, 2, 0, need) == kvq.ERR_WORKSPACE
     assert da(0x50000, 32, 50, 0.1, 0x60000, 2, 0x70000, 1 << 20) == kvq.ERR_UNSUPPORTED         # 16 query heads per kv head
-    Lmix = kvq.Layout(2, 2, 100, 128, 16, 2, 64, 64).c()                                          # raw keys, quantized values
-    assert lib.kvq_decode_attention(C.byref(Lmix), C.byref(kvq._CCache(0x10000, 0, 0x30000, 0x40000, v_scale_exp=0x48000)), p(0x50000), 0, 8, 50,
-                                    C.c_float(0.1), p(0x60000), 2, p(0x70000), 1 << 20, None) == kvq.ERR_UNSUPPORTED
+    # one tensor unquantized: attention exists with one column set and token-wise keys; the query of a 16-bit key plane has
+    # the plane's type; the fused step is for caches with both tensors quantized
+    mixc = kvq._CCache(0x10000, 0, 0x30000, 0x40000, v_scale_exp=0x48000)
+    def dmix(layout, q_dtype, heads, fn=lib.kvq_decode_attention):
+        return fn(C.byref(layout.c()), C.byref(mixc), p(0x50000), q_dtype, heads, 50, C.c_float(0.1), p(0x60000), 2, p(0x70000), 1 << 20, None)
+    assert dmix(kvq.Layout(2, 2, 100, 128, 16, 2, 64, 64), 1, 8) == kvq.ERR_UNSUPPORTED            # bfloat16 query, binary16 keys
+    assert dmix(kvq.Layout(2, 2, 100, 128, 16, 2, 64, 32), 0, 16) == kvq.ERR_UNSUPPORTED           # 8 heads x 4 value groups
+    Lm = kvq.Layout(2, 2, 100, 128, 16, 2, 64, 64).c()
+    assert lib.kvq_decode_step(C.byref(Lm), C.byref(mixc), p(0x50000), p(0x51000), 0, 256, 128, 5, p(0x52000), 0, 8,
+                               C.c_float(0.1), p(0x60000), 2, p(0x70000), 1 << 20, None) == kvq.ERR_UNSUPPORTED
 
     def ds(pos, k=0x50000):
         return lib.kvq_decode_step(C.byref(cl), C.byref(good), p(k), p(0x51000), 1, 256, 128, pos, p(0x52000), 1, 8,
@@ -223,20 +230,43 @@ def test_product_path_never_touches_the_oracle():
 
 
 def test_inline_assembly_stays_away_from_transcendental_results():
-    """The compiler keeps the wait state between a transcendental instruction and a reader of its result only for
+    """The compiler keeps the wait states between an instruction and a hazardous reader of its result (a transcendental
+    result read by the next instruction, a register read through a lane permute right after it was written) only for
     instructions it emits itself.  The decode kernels, whose softmax weights come straight from v_exp_f32, therefore
-    carry no instruction in inline assembly at all, and the assembly of the quantizer is limited to the minimum /
-    maximum instructions (their operands are converted inputs and lane permutes, never a reciprocal or exponential)."""
+    carry no instruction in inline assembly at all, and the assembly of the quantizer is limited to minimum / maximum
+    instructions (their operands are converted inputs, never a reciprocal or exponential); the lane-permuted forms come
+    in blocks that open with their own pause and never read a register written by the instruction just before."""
     csrc = os.path.join(ROOT, "paper_2502_15075_amd", "csrc")
     texts = {}
     for name in sorted(os.listdir(csrc)):
         src = open(os.path.join(csrc, name)).read()
-        texts[name] = [m for m in re.findall(r'\basm\s*(?:volatile)?\s*\(\s*"([^"]*)"', src) if m.strip()]
+        blocks = []
+        for m in re.finditer(r'\basm\s*(?:volatile)?\s*\(((?:\s*"(?:[^"\\]|\\.)*")+)', src):
+            text = "".join(re.findall(r'"((?:[^"\\]|\\.)*)"', m.group(1))).replace("\\n", "\n").replace("\\t", " ")
+            if text.strip():
+                blocks.append([l.strip() for l in text.split("\n") if l.strip()])
+        texts[name] = blocks
     assert texts["kvq_decode.hip"] == [] and texts["kvq_api.hip"] == []
-    allowed = ("v_min3_f32", "v_max3_f32", "v_min_f32", "v_max_f32")
-    for name, found in texts.items():
-        for text in found:
-            assert text.split()[0] in allowed, (name, text)
+    allowed = ("v_min3_f32", "v_max3_f32", "v_min_f32", "v_max_f32", "v_min_f32_dpp", "v_max_f32_dpp", "s_nop")
+    n_dpp = 0
+    for name, blocks in texts.items():
+        for lines in blocks:
+            ops = [l.split()[0] for l in lines]
+            assert all(op in allowed for op in ops), (name, lines)
+            if any(op.endswith("_dpp") for op in ops):
+                n_dpp += 1
+                assert ops[0] == "s_nop", (name, lines)
+                # a permuted read of %k needs two wait states after the write of %k: between two instructions on the
+                # same operand lie the other operand's instruction and a pause, or the block's opening pause
+                last_write = {}
+                for i, l in enumerate(lines):
+                    if not l.split()[0].endswith("_dpp"):
+                        continue
+                    dst = l.split()[1].rstrip(",")
+                    if dst in last_write:
+                        assert i - last_write[dst] >= 3, (name, lines)
+                    last_write[dst] = i
+    assert n_dpp >= 1
 
 
 def test_workspace_never_shrinks_as_the_sequence_grows(kvq):

@@ -251,6 +251,51 @@ def test_unquantized_cache_attention(kvq, oracle, dtype, R):
     assert _rel_err(_decode(kvq, Lg, cache, q, T).cpu().numpy(), want) < TOL
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("R", [1, 4, 8])
+@pytest.mark.parametrize("bk,bv,gk,gv,rot", [(16, 2, 64, 64, 0), (16, 4, 64, 128, 0), (16, 8, 64, 32, 0), (16, 1, 64, 64, 0), (16, 3, 64, 64, 0),
+                                             (16, 6, 64, 64, 0), (4, 16, 64, 64, 0), (2, 16, 32, 64, 1), (8, 16, 128, 64, 0), (1, 16, 64, 64, 0),
+                                             (3, 16, 64, 64, 1), (6, 16, 64, 64, 0)])
+def test_one_tensor_unquantized_attention(kvq, oracle, dtype, R, bk, bv, gk, gv, rot):
+    """Only keys or only values quantized (the ablation behind Table 1's discussion): planes byte for byte (the 16-bit
+    tensor's plane holds the input patterns; unwritten bytes are NaN patterns that must not leak in), attention at
+    lengths with and without a ragged tail, per-sequence lengths, and the step as append + attention."""
+    if R * (128 // gk if bk != 16 else 1) > 16 or R * (128 // gv if bv != 16 else 1) > 16:
+        pytest.skip("one column set only when a tensor is unquantized")
+    B, H, T = 2, 2, 333
+    K, V, q = synth.make_kvq(640 + bk + bv + R, B, H, H * R, T, dtype=dtype)
+    raw = 1 if dtype == torch.bfloat16 else 0
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, raw=raw, rot=rot)
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K[:, :, :300], V[:, :, :300], [(0, 100), (100, 300)], fill=0xFF)
+    _assert_planes_equal(cache, planes)
+    qd = q                                                   # (the query has the cache's 16-bit type: a 16-bit key plane needs that)
+    qn = synth.to_numpy_bits(q) if raw else q.numpy()
+    for seq_len in (300, 256, 33, 1):
+        out = _decode(kvq, Lg, cache, qd, seq_len).cpu().numpy()
+        ref = oracle.decode_attention(Lo, planes, qn, seq_len, 1 / math.sqrt(128), bf16=bool(raw))
+        assert np.isfinite(out).all()
+        assert _rel_err(out, ref) < TOL, seq_len
+    lens = [300, 77]
+    out = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * R, 300)), dtype=torch.uint8, device="cuda")
+    kvq.decode_attention_varlen(Lg, cache, q.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"), 300, 1 / math.sqrt(128), out, ws)
+    torch.cuda.synchronize()
+    ref = oracle.decode_attention_varlen(Lo, planes, qn, lens, 1 / math.sqrt(128), bf16=bool(raw))
+    assert _rel_err(out.cpu().numpy(), ref) < TOL
+    # the fused step exists for caches with both tensors quantized: here it is the append, then the attention
+    Kd, Vd = K.cuda(), V.cuda()
+    with pytest.raises(kvq.KvqError) as e:
+        kvq.decode_step(Lg, cache, Kd[:, :, 300], Vd[:, :, 300], 300, q.cuda(), 1 / math.sqrt(128), out, ws)
+    assert e.value.status == kvq.ERR_UNSUPPORTED
+    kvq.quantize_append(Lg, cache, Kd[:, :, 300:301], Vd[:, :, 300:301], 300)
+    oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, 300:301])),
+                           np.ascontiguousarray(synth.to_numpy_bits(V[:, :, 300:301])), 300, bf16=bool(raw))
+    out = _decode(kvq, Lg, cache, q, 301).cpu().numpy()
+    ref = oracle.decode_attention(Lo, planes, qn, 301, 1 / math.sqrt(128), bf16=bool(raw))
+    assert _rel_err(out, ref) < TOL
+    _assert_planes_equal(cache, planes)
+
+
 def test_half_precision_outputs_round_once(kvq, oracle):
     B, H, R, T = 1, 2, 4, 128
     K, V, q = synth.make_kvq(9, B, H, H * R, T, dtype=torch.bfloat16)

@@ -121,6 +121,33 @@ def test_unquantized_cache_equals_plain_attention(oracle):
     assert np.allclose(got, want, rtol=1e-5, atol=1e-6)
 
 
+@pytest.mark.parametrize("bk,bv,dtype", [(16, 2, torch.float16), (16, 4, torch.bfloat16), (4, 16, torch.float16), (2, 16, torch.bfloat16)])
+def test_one_tensor_unquantized(oracle, bk, bv, dtype):
+    """The ablation that quantizes only keys or only values (Table 1's discussion): the 16-bit tensor is kept exactly
+    (its plane holds the input patterns, its scale/zero plane is empty), and attention is the library routine on the
+    exact tensor and the other one's reconstruction."""
+    K, V, q = synth.make_kvq(6 + bk, 1, 2, 4, 70, 128, dtype=dtype)
+    bf = dtype == torch.bfloat16
+    L = oracle.Layout(1, 2, 70, 128, bk, bv, 64, 64, raw_dtype=1 if bf else 0)
+    planes = oracle.new_planes(L)
+    assert planes[1 if bk == 16 else 3].size == 0 and planes[0 if bk == 16 else 2].size == 2 * 96 * 256
+    oracle.quantize_append(L, planes, synth.to_numpy_bits(K), synth.to_numpy_bits(V), 0, bf16=bf)
+    kd, vd = oracle.dequantize(L, planes, 0, 70)
+    exact, other = (kd, K) if bk == 16 else (vd, V)
+    assert np.array_equal(exact, other.float().numpy())
+    Lq = oracle.Layout(1, 2, 70, 128, 4 if bk == 16 else bk, 4 if bv == 16 else bv, 64, 64)     # the quantized tensor alone
+    pq = oracle.new_planes(Lq)
+    oracle.quantize_append(Lq, pq, synth.to_numpy_bits(K), synth.to_numpy_bits(V), 0, bf16=bf)
+    kq, vq = oracle.dequantize(Lq, pq, 0, 70)
+    assert np.array_equal(vd, vq) if bk == 16 else np.array_equal(kd, kq)
+    scale = 1 / math.sqrt(128)
+    got = oracle.decode_attention(L, planes, synth.to_numpy_bits(q), 70, scale, bf16=bf)
+    want = torch.nn.functional.scaled_dot_product_attention(
+        q.double()[:, :, None, :], torch.from_numpy(kd).double().repeat_interleave(2, dim=1),
+        torch.from_numpy(vd).double().repeat_interleave(2, dim=1), scale=scale)[:, :, 0].numpy()
+    assert np.allclose(got, want, rtol=1e-5, atol=1e-6)
+
+
 # --------------------------------------------------------------------------- bit allocation (Theorem 2)
 
 def _alloc_error(oracle, K, V, q, bk, bv, G, bf16):
