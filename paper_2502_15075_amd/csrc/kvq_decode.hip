@@ -1346,6 +1346,51 @@ inline RotV rot_v_of(const Geom& g) {
   return r;
 }
 
+// The same merge for up to 8 records (the plans of the short shapes: 2 to 8 splits): one wavefront pair per head, every
+// record's maximum, sum and element loaded at once -- 24 independent loads, one memory latency -- and no step through
+// LDS (the kernel above spends two latencies and two barriers, which is most of its 3.9 us at 4 records).
+constexpr int kMergeFew = 8;
+__global__ __launch_bounds__(kHeadDim) void merge_few_kernel(const float* __restrict__ ws, void* __restrict__ out,
+                                                             int out_dtype, int32_t n_splits, RotV rot) {
+  __shared__ float row[kHeadDim];
+  const int64_t hq = blockIdx.x;
+  const int d = threadIdx.x;
+  const float* rec = ws + hq * n_splits * kRec;
+  float m[kMergeFew], l[kMergeFew], o[kMergeFew];
+#pragma unroll
+  for (int j = 0; j < kMergeFew; ++j) {
+    const float* r = rec + min(j, n_splits - 1) * kRec;       // (records past the last repeat it: same cache lines)
+    m[j] = r[kHeadDim]; l[j] = r[kHeadDim + 1]; o[j] = r[d];
+  }
+  float M = m[0];
+#pragma unroll
+  for (int j = 1; j < kMergeFew; ++j) M = fmaxf(M, m[j]);
+  float os = 0.f, ls = 0.f;
+#pragma unroll
+  for (int j = 0; j < kMergeFew; ++j) {
+    const float f = j < n_splits ? exp2f(m[j] - M) : 0.f;
+    os = fmaf(f, o[j], os);
+    ls = fmaf(f, l[j], ls);
+  }
+  const float val = os / ls;
+  if (rot.on) {                                      // uniform
+    row[d] = val;
+    __syncthreads();
+    if (d < 16) store_unrotated_row(row, d, rot.signs, out, out_dtype, hq);
+    return;
+  }
+  store_out(out, out_dtype, hq * kHeadDim + d, val);
+}
+
+// Merge `records` partial records per (batch, query head) into the output.
+inline void launch_merge(const float* ws, void* out, int out_dtype, int32_t heads, int32_t records, RotV rot, hipStream_t stream) {
+  if (records <= kMergeFew)
+    hipLaunchKernelGGL(merge_few_kernel, dim3(heads), dim3(kHeadDim), 0, stream, ws, out, out_dtype, records, rot);
+  else
+    hipLaunchKernelGGL(merge_kernel, dim3(heads), dim3(128 * kMergeGroups), 0, stream, ws, out, out_dtype, records, rot);
+}
+
+
 template <int BK, int BV, int R, bool BF, int NCK, int NCV, bool KSEQ, bool PAGED>
 void launch_nw(const DecodeArgs& a, const DecodePlan& plan, dim3 grid, hipStream_t stream) {
   if constexpr (BK != 16 && BV != 16 && !KSEQ) {
@@ -1394,8 +1439,7 @@ hipError_t launch_one(const DecodeArgs& a, const DecodePlan& plan, hipStream_t s
   // the records of this launch are all there is: merge them, in the launch itself where that pays (merge_tag), else
   // here (otherwise the caller adds launches and merges)
   if (e != hipSuccess || a.rec_splits == 1 || a.rec_splits != plan.n_splits || a.merge_tag != 0) return e;
-  hipLaunchKernelGGL(merge_kernel, dim3(a.g.batch * a.q_heads), dim3(128 * kMergeGroups), 0, stream, a.ws, a.out, a.out_dtype, a.rec_splits,
-                     rot_v_of(a.g));
+  launch_merge(a.ws, a.out, a.out_dtype, a.g.batch * a.q_heads, a.rec_splits, rot_v_of(a.g), stream);
   return hipGetLastError();
 }
 
@@ -1483,7 +1527,9 @@ WaveBudget wave_budget(const Geom& g, int n_steps) {
   const int streams = g.batch * g.kv_heads;
   const int total_waves = device_compute_units() * 4 * KVQ_WAVES_PER_SIMD;
   int waves_per_stream = (total_waves + streams - 1) / streams;
-  const int max_waves = (n_steps + 1) / 2;                     // at least two steps per wavefront
+  // at least two steps per wavefront (four or eight, i.e. fewer splits and at B=8, T=2048 the two-record merge inside
+  // the launch instead of the merge launch, measure 13.7 and 14.6 us there against 11.9)
+  const int max_waves = (n_steps + 1) / 2;
   if (waves_per_stream > max_waves) waves_per_stream = max_waves;
   if (waves_per_stream < 4) waves_per_stream = 4;
   const int nw = waves_per_stream >= 8 ? 8 : 4;
@@ -1597,8 +1643,7 @@ hipError_t launch_decode_attention(const Geom& g, const kvq_cache& c, const void
       if (e != hipSuccess) return e;
     }
     if (records > 1 && !(n_flushed && !tail) && !tail_merges) {     // (a launch that wrote all the records has merged them itself)
-      hipLaunchKernelGGL(merge_kernel, dim3(g.batch * q_heads), dim3(128 * kMergeGroups), 0, stream, workspace, out, out_dtype, records,
-                         rot_v_of(g));
+      launch_merge(workspace, out, out_dtype, g.batch * q_heads, records, rot_v_of(g), stream);
       e = hipGetLastError();
     }
     return e;
