@@ -296,7 +296,8 @@ def test_one_tensor_unquantized_attention(kvq, oracle, dtype, R, bk, bv, gk, gv,
     _assert_planes_equal(cache, planes)
 
 
-def test_longest_streams_byte_offsets_beyond_two_gib(kvq, oracle):
+@pytest.mark.parametrize("bk,bv,T", [(16, 16, 9_000_000), (8, 8, (1 << 24) - 7), (4, 2, (1 << 24) - 7)])
+def test_longest_streams_byte_offsets_beyond_two_gib(kvq, oracle, bk, bv, T):
     """Maximum sizes: one (b, h) stream of an unquantized bfloat16 cache with 9 million tokens, so that the 32-bit byte
     offsets inside a stream pass 2^31 (the planes' limit is 4 GiB per stream: max_seq <= 2^24), the sequence is cut
     into the most splits a launch makes (one stream over the whole chip) and the merge runs over hundreds of records.
@@ -304,8 +305,10 @@ def test_longest_streams_byte_offsets_beyond_two_gib(kvq, oracle):
     (the first tokens, the tokens around byte 2^31 of the key plane, the last tokens) point away from every query, their
     softmax weights are below 1e-150, and the attention over the whole stream equals the attention over the windows'
     tokens alone, which the oracle computes on a cache of its own; the planes of the windows are compared byte for byte
-    with that cache's (a token's bytes do not depend on its position), the whole key plane with the input rows."""
-    B, H, R, T = 1, 1, 4, 9_000_000
+    with that cache's (a token's bytes do not depend on its position), the whole key plane with the input rows.
+    The same for 8-bit and K4V2 caches at the longest sequence the planes take (2^24 tokens less a ragged tail: an 8-bit
+    plane then ends at byte 2^31)."""
+    B, H, R = 1, 1, 4
     g = torch.Generator().manual_seed(2024)
     u = torch.randn(128, generator=g)
     q = (u[None, None, :] + 0.1 * torch.randn(B, H * R, 128, generator=g)).to(torch.bfloat16)
@@ -315,32 +318,37 @@ def test_longest_streams_byte_offsets_beyond_two_gib(kvq, oracle):
     piece = torch.randn(B, H, 1 << 20, 128, generator=g).to(torch.bfloat16)
     for a in range(0, T, 1 << 20):                           # (what the dead tokens hold must not matter)
         V[:, :, a:a + (1 << 20)] = piece[:, :, :min(1 << 20, T - a)]
-    mid = 1 << 23                                            # token whose key row starts at byte 2^31
+    mid = 1 << 23                                            # token whose 16-bit key row starts at byte 2^31
     windows = [(0, 64), (mid - 32, mid + 64), (T - 64 - T % 32, T)]
     for a, b in windows:
         K[:, :, a:b] = (torch.randn(B, H, b - a, 128, generator=g) * 2).to(torch.bfloat16)
         V[:, :, a:b] = torch.randn(B, H, b - a, 128, generator=g).to(torch.bfloat16)
     Kb, Vb, qn = synth.to_numpy_bits(K), synth.to_numpy_bits(V), synth.to_numpy_bits(q)
-    Lg = kvq.Layout(B, H, T, 128, 16, 16, 64, 64, raw_dtype=1)
-    assert kvq.cache_bytes(Lg)[0] == (T + 31) // 32 * 32 * 256 > 1 << 31
+    Lg = kvq.Layout(B, H, T, 128, bk, bv, 64, 64, raw_dtype=1)
+    assert kvq.cache_bytes(Lg)[0] == (T + 31) // 32 * 32 * 16 * bk >= (1 << 31 if bk >= 8 else 1 << 30)
     cache = kvq.Cache(Lg, fill=0xFF)
     Kd, Vd = K.cuda(), V.cuda()
     for a, b in ((0, 5_000_001), (5_000_001, T)):
         kvq.quantize_append(Lg, cache, Kd[:, :, a:b], Vd[:, :, a:b], a)
     torch.cuda.synchronize()
     del Kd, Vd
-    kc, vc = cache.planes[0].cpu().numpy(), cache.planes[2].cpu().numpy()
-    assert np.array_equal(kc[:T * 256].view(np.uint16), Kb.reshape(-1))       # a 16-bit key plane is the rows themselves
+    got = [None if p is None else p.cpu().numpy() for p in cache.planes[:4]]
+    if bk == 16:
+        assert np.array_equal(got[0][:T * 256].view(np.uint16), Kb.reshape(-1))   # a 16-bit key plane is the rows themselves
     for a, b in windows:                                                        # (window starts are multiples of 32)
-        Lw = oracle.Layout(B, H, b - a, 128, 16, 16, 64, 64, raw_dtype=1)
+        Lw = oracle.Layout(B, H, b - a, 128, bk, bv, 64, 64, raw_dtype=1)
         pw = oracle.new_planes(Lw, fill=0xFF)
         oracle.quantize_append(Lw, pw, np.ascontiguousarray(Kb[:, :, a:b]), np.ascontiguousarray(Vb[:, :, a:b]), 0, bf16=True)
-        assert np.array_equal(kc[a * 256:a * 256 + pw[0].size], pw[0]), (a, b)
-        assert np.array_equal(vc[a * 256:a * 256 + pw[2].size], pw[2]), (a, b)
+        rows = -(-(b - a) // 32) * 32                                           # (the window's planes, padded to a block)
+        for name, gp, op_ in zip(("k_codes", "k_meta", "v_codes", "v_meta"), got, pw):
+            if op_.size == 0:
+                continue
+            per_token = op_.size // rows                                        # (bytes past the last token: the fill on both sides)
+            assert np.array_equal(gp[a * per_token:a * per_token + op_.size], op_), (name, a, b)
     assert kvq.decode_workspace_bytes(Lg, H * R, T) > 100 * 132 * 4 * H * R
     for seq_len in (T, T - 31):
         live = np.concatenate([np.arange(a, min(b, seq_len)) for a, b in windows])
-        Lw = oracle.Layout(B, H, live.size, 128, 16, 16, 64, 64, raw_dtype=1)
+        Lw = oracle.Layout(B, H, live.size, 128, bk, bv, 64, 64, raw_dtype=1)
         pw = oracle.new_planes(Lw)
         oracle.quantize_append(Lw, pw, np.ascontiguousarray(Kb[:, :, live]), np.ascontiguousarray(Vb[:, :, live]), 0, bf16=True)
         ref = oracle.decode_attention(Lw, pw, qn, live.size, 1 / math.sqrt(128), bf16=True)
