@@ -360,6 +360,32 @@ def test_longest_streams_byte_offsets_beyond_two_gib(kvq, oracle, bk, bv, T):
     assert ((logits - live_max[:, None]) < -350).all()
 
 
+def test_most_streams_one_launch_takes(kvq, oracle):
+    """Maximum sizes: 65535 (batch, kv head) streams, the most a layout may have (one workgroup row each); short
+    sequences with a ragged tail; append, attention and the fused step against the oracle on every stream."""
+    B, H, R, T = 13107, 5, 2, 41
+    K, V, q = synth.make_kvq(321, B, H, H * R, T, dtype=torch.bfloat16)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, 4, 2, 64, 64)
+    assert B * H == 65535 and kvq.decode_workspace_bytes(Lg, H * R, T) == 0
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K[:, :, :T - 1], V[:, :, :T - 1], [(0, T - 1)])
+    _assert_planes_equal(cache, planes)
+    qn = synth.to_numpy_bits(q)
+    out = _decode(kvq, Lg, cache, q, T - 1).cpu().numpy()
+    ref = oracle.decode_attention(Lo, planes, qn, T - 1, 1 / math.sqrt(128), bf16=True)
+    assert _rel_err(out, ref) < TOL
+    o2 = torch.empty(B, H * R, 128, dtype=torch.float32, device="cuda")
+    kvq.decode_step(Lg, cache, K[:, :, T - 1].cuda(), V[:, :, T - 1].cuda(), T - 1, q.cuda(), 1 / math.sqrt(128), o2, None)
+    torch.cuda.synchronize()
+    oracle.quantize_append(Lo, planes, np.ascontiguousarray(synth.to_numpy_bits(K[:, :, T - 1:T])),
+                           np.ascontiguousarray(synth.to_numpy_bits(V[:, :, T - 1:T])), T - 1, bf16=True)
+    _assert_planes_equal(cache, planes)
+    ref = oracle.decode_attention(Lo, planes, qn, T, 1 / math.sqrt(128), bf16=True)
+    assert _rel_err(o2.cpu().numpy(), ref) < TOL
+    with pytest.raises(kvq.KvqError) as e:
+        kvq.cache_bytes(kvq.Layout(B + 1, H, T))
+    assert e.value.status == kvq.ERR_UNSUPPORTED
+
+
 def test_half_precision_outputs_round_once(kvq, oracle):
     B, H, R, T = 1, 2, 4, 128
     K, V, q = synth.make_kvq(9, B, H, H * R, T, dtype=torch.bfloat16)
