@@ -242,6 +242,69 @@ def run_channelwise(args, kvq, synth) -> int:
     return 0
 
 
+def run_variants(args, kvq, synth) -> int:
+    """The 70B layer shape (configs[3]: B=32, H_q=64, H_kv=8, T=32768, bf16, 64-element groups) under the layouts beside
+    the plain K4V2 cache: channel-wise keys (Sec. 4 "Downstream Task Accuracy") with everything flushed, with 40 tokens
+    in the residual buffer, with key rotation (Sec. 5.3), with 32- and 128-token key groups; the buffer in front of
+    token-wise keys; paged planes; caches with only keys or only values quantized and the unquantized one.  One line per
+    variant: time per call over 3 rotating caches filled by kvq_quantize_append from seeded tensors, effective packed
+    bytes per second.  Parity for every one of these layouts is a test (tests/test_gpu_parity.py); this only times them."""
+    B, Hq, Hkv, D, T = 32, 64, 8, 128, 32768
+    scale = 1.0 / math.sqrt(D)
+    K, V, q = synth.make_kvq(11, B, Hkv, Hq, T + 64, D, dtype=torch.bfloat16, device="cuda")
+    k1, v1 = K[:, :, T - 1].contiguous(), V[:, :, T - 1].contiguous()
+    out = torch.empty(B, Hq, D, dtype=torch.float32, device="cuda")
+    SEQ, BF = kvq.AXIS_SEQ, kvq.KVQ_BF16
+    signs = (0x9E3779B9, 0x7F4A7C15, 0xF39CC060, 0x5CEDC834)
+    def pages(P):
+        return dict(page_tokens=P, n_pages=B * (T // P))
+    variants = [
+        ("K4V2 token-wise keys, fused step", dict(), T, True),
+        ("K4V2 channel-wise keys (64-token groups), everything flushed", dict(axis_k=SEQ), T, False),
+        ("K4V2 channel-wise keys, 40 tokens in the residual buffer", dict(axis_k=SEQ), T + 40, False),
+        ("K4V2 channel-wise keys + key rotation, everything flushed", dict(axis_k=SEQ, rotate_k=1, signs_k=signs), T, False),
+        ("K4V2 channel-wise keys, 32-token groups behind a 64-token buffer, flushed", dict(axis_k=SEQ, group_k=32, resid_len=64), T, False),
+        ("K4V2 channel-wise keys, 128-token groups behind a 128-token buffer, flushed", dict(axis_k=SEQ, group_k=128), T, False),
+        ("K4V2 token-wise keys behind a 64-token buffer, 40 tokens in it", dict(resid_len=64), T + 40, False),
+        ("K4V2 paged planes, shuffled 64-token pages, fused step", pages(64), T, True),
+        ("K4V2 paged planes, shuffled 1024-token pages, fused step", pages(1024), T, True),
+        ("K16V2 (values only quantized)", dict(bits_k=16), T, False),
+        ("K4V16 (keys only quantized)", dict(bits_v=16), T, False),
+        ("K16V16 (unquantized bfloat16)", dict(bits_k=16, bits_v=16), T, False),
+    ]
+    for name, kw, seq_len, fused in variants:
+        kw = dict(dict(bits_k=4, bits_v=2, group_k=64, group_v=64), **kw)
+        L = kvq.Layout(B, Hkv, T + 64 if seq_len > T else T, D, raw_dtype=BF, **kw)
+        copies = 2 if kw["bits_k"] == 16 and kw["bits_v"] == 16 else 3
+        caches = []
+        for c in range(copies):
+            cache = kvq.Cache(L, device="cuda")
+            if L.page_tokens:
+                per = T // L.page_tokens
+                g = torch.Generator().manual_seed(5 + c)
+                cache.page_table = torch.randperm(L.n_pages, generator=g)[: B * per].to(torch.int32).view(B, per).contiguous().cuda()
+            n_fill = seq_len - 1 if fused else seq_len
+            kvq.quantize_append(L, cache, K[:, :, :n_fill], V[:, :, :n_fill], 0)
+            caches.append(cache)
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(L, Hq, seq_len)), dtype=torch.uint8, device="cuda")
+        if fused:
+            fn = lambda i: kvq.decode_step(L, caches[i % copies], k1, v1, seq_len - 1, q, scale, out, ws)
+        else:
+            fn = lambda i: kvq.decode_attention(L, caches[i % copies], q, seq_len, scale, out, ws)
+        steps = 400 if kw["bits_k"] == 16 or kw["bits_v"] == 16 else 1200
+        ms = min(_time_events(fn, steps, steps // 4) for _ in range(2))
+        n_res = seq_len % 64 if (kw.get("axis_k") == SEQ or kw.get("resid_len")) else 0
+        kmeta = 0 if kw["bits_k"] == 16 else (512 // kw["group_k"] if kw.get("axis_k") == SEQ else 4 * (D // kw["group_k"]))
+        vmeta = 0 if kw["bits_v"] == 16 else 4 * (D // kw["group_v"])
+        row_bytes = 16 * kw["bits_k"] + 16 * kw["bits_v"] + kmeta + vmeta
+        kv_bytes = B * Hkv * ((seq_len - n_res) * row_bytes + n_res * 512)
+        print(json.dumps({"workload": f"configs[3] shape, B={B}, T={seq_len}: {name}", "bytes_per_cached_row": row_bytes,
+                          "kv_bytes": kv_bytes, "us": round(ms * 1e3, 2), "GB_s": round(kv_bytes / ms / 1e6, 1),
+                          "pct_of_hbm_peak": round(100 * kv_bytes / ms / 1e6 / HBM_PEAK_GBS, 1)}), flush=True)
+        del caches
+    return 0
+
+
 def _time_events(fn, steps, warmup, every=8):
     """Mean device time per call in ms: HIP events on the current stream around consecutive groups of `every` calls."""
     for i in range(warmup):
@@ -499,7 +562,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=4000)
     ap.add_argument("--warmup", type=int, default=400)
     ap.add_argument("--layers", type=int, default=80, help="resident layer caches taken in turn")
-    ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS) + ["sweep", "widths", "groups", "rotation", "channelwise", "stream131k"],
+    ap.add_argument("--workload", default="llama70b", choices=sorted(WORKLOADS) + ["sweep", "widths", "groups", "rotation", "channelwise", "stream131k", "variants"],
                     help="llama70b (default, the headline line) / llama8b: one JSON line; sweep: bit-allocation sweep on the 8B "
                          "layer (one line per allocation and context); stream131k: chunked fill + growing-cache decode at 131072")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -528,6 +591,8 @@ def main() -> int:
         return run_groups(args, kvq, synth)
     if args.workload == "rotation":
         return run_rotation(args, kvq, synth)
+    if args.workload == "variants":
+        return run_variants(args, kvq, synth)
     if args.workload == "channelwise":
         return run_channelwise(args, kvq, synth)
     if args.workload == "stream131k":
