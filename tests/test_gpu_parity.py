@@ -1838,8 +1838,8 @@ def _run_token_wise_case(kvq, oracle, c):
 @pytest.mark.parametrize("bk,bv", [(3, 8), (6, 8), (3, 6), (6, 6)])
 def test_channelwise_two_run_keys_with_wide_values_in_two_column_sets(kvq, oracle, bk, bv):
     """8 heads per KV head and 32-channel value groups (two value column sets) over channel-wise keys of 3 and 6 bits
-    beside 6- and 8-bit values: the kernel instances with the highest register pressure (the only ones allowed to keep
-    registers in scratch memory).  Flushed blocks plus tail, then fused steps across a flush."""
+    beside 6- and 8-bit values: the kernel instances with the highest register pressure (the last ones to stop
+    spilling).  Flushed blocks plus tail, then fused steps across a flush."""
     B, H, r, T = 2, 2, 8, 250
     cap = T + 8
     K, V, q = synth.make_kvq(7100 + 10 * bk + bv, B, H, H * r, cap, dtype=torch.float16)
