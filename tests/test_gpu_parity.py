@@ -1929,3 +1929,62 @@ def test_random_channelwise_configurations(kvq, oracle, case):
         check_planes()
         ref = oracle.seq_decode_attention(Lo, planes, qn, pos + 1, scale, bf16=bf16)
         assert _rel_err(outs.cpu().numpy(), ref) < TOL, pos
+
+
+@pytest.mark.parametrize("case", range(32))
+def test_random_residual_buffer_layouts(kvq, oracle, case):
+    """Seeded random caches with a residual buffer: channel-wise keys in groups of 32, 64 or 128 tokens behind a buffer of
+    64 or 128 slots, or token-wise keys behind 64 slots; with and without key rotation; every width, head ratios, both
+    input types.  Ragged chunked appends, attention over flushed blocks plus tail, fused steps across whatever boundary
+    the lengths happen to produce; all six planes byte-identical, outputs within tolerance."""
+    rng = np.random.default_rng(12000 + case)
+    bk, bv = (int(rng.choice([1, 2, 3, 4, 6, 8])) for _ in range(2))
+    gv = int(rng.choice([32, 64, 128]))
+    r = int(rng.integers(1, 9))
+    R = 1 if r <= 1 else 2 if r <= 2 else 4 if r <= 4 else 8
+    if R * (128 // gv) > 32:
+        gv = 64
+    if rng.integers(0, 3) == 0:                              # token-wise keys behind the buffer
+        axis, rl = 0, 64
+        gk = int(rng.choice([32, 64, 128]))
+        if R * (128 // gk) > 32:
+            gk = 64
+    else:
+        axis = 1
+        gk, rl = [(32, 64), (64, 0), (64, 64), (128, 0), (128, 128), (32, 128), (64, 128)][int(rng.integers(0, 7))]
+    rot = int(rng.integers(0, 3) == 0)
+    B, H, T = int(rng.integers(1, 4)), int(rng.integers(1, 3)), int(rng.integers(1, 700))
+    bf16 = bool(rng.integers(0, 2))
+    cap = T + 3
+    dtype = torch.bfloat16 if bf16 else torch.float16
+    K, V, q = synth.make_kvq(int(rng.integers(0, 1 << 30)), B, H, H * r, cap, dtype=dtype)
+    signs = SIGNS if rot else (0, 0, 0, 0)
+    Lg = kvq.Layout(B, H, cap, 128, bk, bv, gk, gv, axis_k=axis, raw_dtype=int(bf16), rotate_k=rot, signs_k=signs, resid_len=rl)
+    Lo = oracle.Layout(B, H, cap, 128, bk, bv, gk, gv, axis_k=axis, raw_dtype=int(bf16), rotate_k=rot, signs_k=signs, resid_len=rl)
+    cache = kvq.Cache(Lg, fill=0x5A)
+    planes = oracle.new_seq_planes(Lo, fill=0x5A)
+    Kd, Vd = K.cuda(), V.cuda()
+    Kb = synth.to_numpy_bits(K) if bf16 else K.numpy()
+    Vb = synth.to_numpy_bits(V) if bf16 else V.numpy()
+    tag = (bk, bv, gk, gv, axis, rl, rot, r, B, H, T, bf16)
+    cuts = sorted(set([0, T] + [int(x) for x in rng.integers(0, T + 1, size=3)]))
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        kvq.quantize_append(Lg, cache, Kd[:, :, a:b], Vd[:, :, a:b], a)
+        oracle.seq_append(Lo, planes, np.ascontiguousarray(Kb[:, :, a:b]), np.ascontiguousarray(Vb[:, :, a:b]), a, bf16=bf16)
+    torch.cuda.synchronize()
+    _assert_seq_planes_equal(cache, planes)
+    qn = synth.to_numpy_bits(q) if bf16 else q.numpy()
+    scale = 1 / math.sqrt(128)
+    out = _decode(kvq, Lg, cache, q, T)
+    ref = oracle.seq_decode_attention(Lo, planes, qn, T, scale, bf16=bf16)
+    assert _rel_err(out.cpu().numpy(), ref) < TOL, tag
+    outs = torch.empty(B, H * r, 128, dtype=torch.float32, device="cuda")
+    for pos in range(T, T + 3):
+        ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * r, pos + 1)), dtype=torch.uint8, device="cuda")
+        kvq.decode_step(Lg, cache, Kd[:, :, pos], Vd[:, :, pos], pos, q.cuda(), scale, outs, ws)
+        torch.cuda.synchronize()
+        oracle.seq_append(Lo, planes, np.ascontiguousarray(Kb[:, :, pos:pos + 1]), np.ascontiguousarray(Vb[:, :, pos:pos + 1]), pos, bf16=bf16)
+        _assert_seq_planes_equal(cache, planes)
+        ref = oracle.seq_decode_attention(Lo, planes, qn, pos + 1, scale, bf16=bf16)
+        assert _rel_err(outs.cpu().numpy(), ref) < TOL, (tag, pos)
+
