@@ -1781,6 +1781,45 @@ def test_random_token_wise_configurations(kvq, oracle, case):
     _run_token_wise_case(kvq, oracle, _random_case(np.random.default_rng(4242 + case)))
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_random_one_tensor_unquantized_configurations(kvq, oracle, case):
+    """Seeded random caches with only keys or only values quantized (all widths, group sizes, head ratios that fit one
+    column set, key rotation where the keys are quantized, both 16-bit types): ragged chunked appends, attention at the
+    full and at a shorter length, per-sequence lengths; planes byte-identical, outputs within tolerance."""
+    rng = np.random.default_rng(7700 + case)
+    raw_k = bool(rng.integers(0, 2))
+    b = int(rng.choice([1, 2, 3, 4, 6, 8]))
+    g_ = int(rng.choice([32, 64, 128]))
+    r = int(rng.integers(1, 9))
+    R = 1 if r <= 1 else 2 if r <= 2 else 4 if r <= 4 else 8
+    if R * (128 // g_) > 16:
+        g_ = 128 if R == 8 else 64
+    bk, bv, gk, gv = (16, b, 64, g_) if raw_k else (b, 16, g_, 64)
+    rot = int(not raw_k and rng.integers(0, 2) == 0)
+    B, H, T = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.integers(1, 700))
+    bf16 = bool(rng.integers(0, 2))
+    dtype = torch.bfloat16 if bf16 else torch.float16
+    K, V, q = synth.make_kvq(int(rng.integers(0, 1 << 30)), B, H, H * r, T, dtype=dtype)
+    Lg, Lo = _layouts(kvq, oracle, B, H, T, bk, bv, gk, gv, raw=int(bf16), rot=rot)
+    cuts = sorted(set([0, T] + [int(x) for x in rng.integers(0, T + 1, size=3)]))
+    cache, planes = _fill_both(kvq, oracle, Lg, Lo, K, V, list(zip(cuts[:-1], cuts[1:])), fill=0xFF)
+    _assert_planes_equal(cache, planes)
+    qn = synth.to_numpy_bits(q) if bf16 else q.numpy()
+    scale = 1 / math.sqrt(128)
+    tag = (bk, bv, gk, gv, r, B, H, T, bf16, rot)
+    for seq_len in {T, max(1, T // 3)}:
+        out = _decode(kvq, Lg, cache, q, seq_len).cpu().numpy()
+        ref = oracle.decode_attention(Lo, planes, qn, seq_len, scale, bf16=bf16)
+        assert np.isfinite(out).all() and _rel_err(out, ref) < TOL, (tag, seq_len)
+    lens = [int(x) for x in rng.integers(1, T + 1, size=B)]
+    ws = torch.empty(max(16, kvq.decode_workspace_bytes(Lg, H * r, T)), dtype=torch.uint8, device="cuda")
+    out = torch.empty(B, H * r, 128, dtype=torch.float32, device="cuda")
+    kvq.decode_attention_varlen(Lg, cache, q.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"), T, scale, out, ws)
+    torch.cuda.synchronize()
+    ref = oracle.decode_attention_varlen(Lo, planes, qn, lens, scale, bf16=bf16)
+    assert _rel_err(out.cpu().numpy(), ref) < TOL, (tag, lens)
+
+
 # Rotated values with one group per row and few tokens: the rounding of a token's binary16 weight is common to all 128
 # codes of its row, and taking the output back with R_v^T gathers a common part into one channel, sqrt(128) times larger.
 # (Configurations that a wider random search found beyond the tolerance before the kernel gave the rounded-off part of
