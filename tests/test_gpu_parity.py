@@ -492,14 +492,17 @@ def _elementwise_err(out, ref, floor=1e-3):
 
 
 def _check_sampled_streams(kvq, oracle, B, Hq, Hkv, T, seed, sigma_k, samples, fused=True, bk=4, bv=2, axis_seq=False,
-                           page_tokens=0):
+                           page_tokens=0, gk=64, resid_len=0, rot_k=0):
     """Fill a full-size G=64 cache on the GPU exactly as bench.py does (chunks of 2048, last token through the fused
     step, or a plain append and kvq_decode_attention with fused=False), then compare a few (batch, kv head) streams
     with the oracle: every plane's bytes identical, output within TOL.  bk = bv = 16: the unquantized bfloat16 cache.
-    axis_seq: channel-wise keys with their residual buffers.  page_tokens: planes as a pool of shuffled pages."""
+    axis_seq: channel-wise keys with their residual buffers (gk: tokens per key group; resid_len: the buffer's slots, also
+    in front of token-wise keys; rot_k: key rotation).  page_tokens: planes as a pool of shuffled pages."""
     D, G, R = 128, 64, Hq // Hkv
+    resid = axis_seq or resid_len != 0
+    signs = SIGNS if rot_k else (0, 0, 0, 0)
     K, V, q = synth.make_kvq(seed, B, Hkv, Hq, T, D, dtype=torch.bfloat16, sigma_k=sigma_k, device="cuda")
-    kw = dict(raw_dtype=kvq.KVQ_BF16)
+    kw = dict(raw_dtype=kvq.KVQ_BF16, resid_len=resid_len, rotate_k=rot_k, signs_k=signs)
     table = None
     if axis_seq:
         kw["axis_k"] = kvq.AXIS_SEQ
@@ -508,7 +511,7 @@ def _check_sampled_streams(kvq, oracle, B, Hq, Hkv, T, seed, sigma_k, samples, f
         n_pages = B * pps + 3
         table = torch.from_numpy(np.random.default_rng(seed).permutation(n_pages)[:B * pps].reshape(B, pps).astype(np.int32)).cuda()
         kw.update(page_tokens=page_tokens, n_pages=n_pages)
-    Lg = kvq.Layout(B, Hkv, T, D, bk, bv, G, G, **kw)
+    Lg = kvq.Layout(B, Hkv, T, D, bk, bv, gk, G, **kw)
     cache = kvq.Cache(Lg, fill=0)                      # unwritten capacity beyond T compares equal to the oracle's zeros
     if table is not None:
         cache.page_table = table
@@ -524,13 +527,14 @@ def _check_sampled_streams(kvq, oracle, B, Hq, Hkv, T, seed, sigma_k, samples, f
         kvq.decode_attention(Lg, cache, q, T, 1 / math.sqrt(D), out, ws)
     torch.cuda.synchronize()
     cap = -(-T // page_tokens) * page_tokens if page_tokens else T
-    Lo = oracle.Layout(1, 1, cap, D, bk, bv, G, G, raw_dtype=oracle.BF16, axis_k=1 if axis_seq else 0)
+    Lo = oracle.Layout(1, 1, cap, D, bk, bv, gk, G, raw_dtype=oracle.BF16, axis_k=1 if axis_seq else 0, resid_len=resid_len,
+                       rotate_k=rot_k, signs_k=signs)
     names = ("k_codes", "k_meta", "v_codes", "v_meta", "k_resid", "v_resid")
     worst, worst_elem = 0.0, 0.0
     for b, h in samples:
         kb, vb = synth.to_numpy_bits(K[b:b + 1, h:h + 1]), synth.to_numpy_bits(V[b:b + 1, h:h + 1])
         qb = synth.to_numpy_bits(q[b:b + 1, h * R:(h + 1) * R])
-        if axis_seq:
+        if resid:
             planes = oracle.new_seq_planes(Lo)
             oracle.seq_append(Lo, planes, kb, vb, 0, bf16=True)
             ref = oracle.seq_decode_attention(Lo, planes, qb, T, 1 / math.sqrt(D), bf16=True)
@@ -583,6 +587,18 @@ def test_full_size_70b_layer_channelwise_keys_sampled_streams(kvq, oracle):
     """Channel-wise K4V2 at the 70B-layer shape with 40 tokens left in the residual buffers (Sec. 4 "Downstream Task
     Accuracy"): flushed blocks from the codes, the tail through the unquantized kernel, one merge."""
     _check_sampled_streams(kvq, oracle, 32, 64, 8, 32768 + 40, 1001, 3.3, [(0, 0), (21, 6)], fused=False, axis_seq=True)
+
+
+@pytest.mark.parametrize("kw", [dict(axis_seq=True, rot_k=1), dict(axis_seq=True, gk=32, resid_len=64), dict(axis_seq=True, gk=128),
+                                dict(resid_len=64), dict(bk=16), dict(bv=16), dict(page_tokens=1024, fused=True)],
+                         ids=["channelwise-rotated", "channelwise-g32", "channelwise-g128", "tokenwise-buffer", "K16V2", "K4V16", "pages1024"])
+def test_full_size_70b_layer_variants_sampled_streams(kvq, oracle, kw):
+    """The other layouts timed at the 70B-layer shape (bench.py --workload variants), each as it is launched there, 40
+    tokens in the residual buffer where there is one: channel-wise keys with key rotation, with 32- and with 128-token
+    groups, the buffer in front of token-wise keys, only values / only keys quantized, 1024-token pages."""
+    kw = dict(dict(fused=False), **kw)
+    T = 32768 + 40 if (kw.get("axis_seq") or kw.get("resid_len")) else 32768
+    _check_sampled_streams(kvq, oracle, 32, 64, 8, T, 1003, 3.3, [(17, 4)], **kw)
 
 
 def test_full_size_70b_layer_paged_sampled_streams(kvq, oracle):
