@@ -461,7 +461,7 @@ def measure_config4(kvq, synth, copies=3):
             "quantize_GB_s_back_to_back": round(T0 * 4992 / fill_ms / 1e6, 1),
             "quantize_tok_s_graph_replay": round(T0 / fill_graph_ms * 1e3, 1),
             "quantize_us_per_chunk_graph_replay": round(fill_graph_ms * 1e3 / (T0 // chunk), 2),
-            "quantize_note": "64 calls of 10 MB each: back to back the Python binding's per-call cost (about 13 us) paces them; replayed "
+            "quantize_note": "64 calls of 10 MB each: back to back the caller's per-call cost (slicing the chunk and the Python binding: about 8.5 us) paces them; replayed "
                              "from a HIP graph the calls run at the kernel's own rate",
             "quantize_us_per_chunk_call_plus_synchronize": round(percall_s * 1e6, 2),
             "decode_step_us": round(step_ms * 1e3, 2), "decode_GB_s": round(kv_bytes / step_ms / 1e6, 1),

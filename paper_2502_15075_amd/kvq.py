@@ -112,7 +112,11 @@ class Layout:
     resid_len: int = 0
 
     def c(self) -> _CLayout:
-        return _layout_struct(self)
+        st = self.__dict__.get("_c")                         # (kept on the object: hashing 18 fields per call costs 1.5 us)
+        if st is None:
+            st = _layout_struct(self)
+            object.__setattr__(self, "_c", st)
+        return st
 
 
 @functools.lru_cache(maxsize=256)
@@ -129,7 +133,9 @@ def _check(status: int, where: str) -> None:
 
 
 def _stream_ptr():
-    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    # (the raw handle of torch's current stream: the same value as torch.cuda.current_stream().cuda_stream, without
+    # building a Stream object per call)
+    return C.c_void_p(torch._C._cuda_getCurrentRawStream(torch.cuda.current_device()))
 
 
 def _p(t):
@@ -170,14 +176,23 @@ class Cache:
         # per (batch, kv head): largest exponent field of the value scales of 64 and more stored so far; starts at zero
         self.v_scale_exp = torch.zeros(layout.batch * layout.kv_heads, dtype=torch.int32, device=device)
 
+    # int32 device tensor [B, pages per sequence] of a paged cache (None otherwise); setting it rebuilds the C struct
+    @property
+    def page_table(self):
+        return self.__dict__.get("_page_table")
+
+    @page_table.setter
+    def page_table(self, table):
+        self.__dict__["_page_table"] = table
+        self.__dict__["_struct"] = None
+
     def c(self) -> _CCache:
-        table = getattr(self, "page_table", None)          # int32 device tensor [B, pages per sequence] of a paged cache
-        key = (None if table is None else table.data_ptr(), tuple(self.planes[i] is None for i in range(len(self.planes))))
-        if getattr(self, "_struct_key", None) != key:       # the planes never move: the struct is built once per table
-            self._struct = _CCache(*[(0 if p is None else p.data_ptr()) for p in self.planes],
-                                   0 if table is None else table.data_ptr(), self.v_scale_exp.data_ptr())
-            self._struct_key = key
-        return self._struct
+        st = self.__dict__.get("_struct")
+        if st is None:                                      # the planes never move: the struct is built once per table
+            table = self.page_table
+            st = self._struct = _CCache(*[(0 if p is None else p.data_ptr()) for p in self.planes],
+                                        0 if table is None else table.data_ptr(), self.v_scale_exp.data_ptr())
+        return st
 
     def batch_element(self, b: int, layout: "Layout") -> "Cache":
         """A view of batch element b's share of every plane as a cache of batch 1 (`layout`: this cache's layout with
